@@ -1,0 +1,164 @@
+/*
+ * libvector: VECTOR three-way KV-cache routing on one MI355X (gfx950).
+ *
+ * The compression pass at prefill -- importance score, reconstruction residual,
+ * retain / approximate / evict routing, compaction into a packed cache -- and
+ * the decode attention that rebuilds approximated values from their kept keys.
+ *
+ * Conventions shared by every entry point
+ *   - Plain C ABI.  Every pointer marked "device" is device memory owned by the
+ *     caller; "host" pointers are ordinary host memory.  The library never
+ *     allocates, frees or synchronises: work is enqueued on `stream` (a
+ *     hipStream_t passed as void*, NULL = the default stream) and the call
+ *     returns at once.  Inputs are never modified.
+ *   - Return value: VECTOR_OK or a negative VECTOR_ERR_* code.  Arguments are
+ *     validated on the host before anything is launched, so a failing call
+ *     writes nothing.
+ *   - Row convention: v_hat = k . W with W [d, d]; this W is the transpose of
+ *     the column-convention W_OLS of the paper (Section 3.1, footnote).
+ *   - The innermost dimension (head_dim) is contiguous; device tensors must be
+ *     16-byte aligned.  head_dim is 64 or 128.
+ *   - `ws` is caller-owned device scratch of at least vector_workspace_bytes()
+ *     bytes (256-byte aligned); calls sharing one workspace must be ordered on
+ *     one stream.
+ */
+#ifndef VECTOR_H_
+#define VECTOR_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VECTOR_API __attribute__((visibility("default")))
+
+#define VECTOR_OK              0
+#define VECTOR_ERR_ARG        (-1)  /* null pointer, bad count or flag            */
+#define VECTOR_ERR_SHAPE      (-2)  /* shape outside what the kernels support     */
+#define VECTOR_ERR_WORKSPACE  (-3)  /* ws too small or misaligned                 */
+#define VECTOR_ERR_DTYPE      (-4)  /* unknown element type                       */
+#define VECTOR_ERR_HIP        (-5)  /* a HIP call or launch failed                */
+
+typedef enum { VECTOR_F32 = 0, VECTOR_BF16 = 1 } vector_dtype;
+
+/* tiers written by vector_route */
+#define VECTOR_TIER_EVICT   0
+#define VECTOR_TIER_APPROX  1
+#define VECTOR_TIER_RETAIN  2
+
+/* One layer of one sequence. */
+typedef struct {
+  int32_t n_q_heads;      /* Hq, a multiple of n_kv_heads                              */
+  int32_t n_kv_heads;     /* Hkv                                                       */
+  int32_t head_dim;       /* d: 64 or 128                                              */
+  int32_t seq_len;        /* n                                                         */
+  int32_t window;         /* w: the observation window is the last w positions, 1<=w<=n */
+  int32_t pool_kernel;    /* odd k >= 1: average pooling, stride 1, zero pad, divisor k */
+  int32_t dtype;          /* vector_dtype of q, k, v, W; score and eps are always fp32 */
+  int32_t reserved;
+  int64_t k_stride_head, k_stride_tok;   /* element strides of k [Hkv, n, d]; 0,0 = packed */
+  int64_t v_stride_head, v_stride_tok;   /* element strides of v [Hkv, n, d]; 0,0 = packed */
+  int64_t w_stride_head;                 /* element stride between per-head W; 0 with
+                                            w_shared != 0 means one W for all heads      */
+  int32_t w_shared;
+  int32_t reserved2;
+} vector_shape;
+
+/* ---- host-only helpers ------------------------------------------------- */
+
+/* Section 3.2: with compression ratio p_c and approximation ratio p_a the
+ * retained fraction is 1-p_c-p_a and the approximated fraction 2 p_a.
+ * Counts are floors (in double); n_pool = n_retain + n_approx. */
+VECTOR_API int vector_budget_counts(int32_t n, double p_c, double p_a, int32_t* n_pool, int32_t* n_approx);
+/* Same, from token fractions directly. */
+VECTOR_API int vector_budget_counts_frac(int32_t n, double f_retain, double f_approx, int32_t* n_pool, int32_t* n_approx);
+/* Section 4, deployment formula: min(p_c/2, (1-p_c-eps)/2). */
+VECTOR_API double vector_pa_deploy(double p_c, double eps);
+/* Scratch bytes sufficient for any entry point on this shape (batch applies to
+ * vector_decode_attn; pass 1 for the compression pass). */
+VECTOR_API size_t vector_workspace_bytes(const vector_shape* shape, int32_t n_pool, int32_t n_approx, int32_t batch);
+VECTOR_API const char* vector_strerror(int code);
+
+/* ---- the compression pass ---------------------------------------------- */
+
+/* Base importance scorer (Section 3.2 Step 1 needs one; the paper plugs into
+ * SnapKV-style scorers).  Per KV head h and token t < n-w:
+ *   mass[h,t]  = mean over the G = Hq/Hkv query heads of h and the w window rows
+ *                of softmax_t( q . k_t / sqrt(d) ), causal (window row r sees
+ *                keys <= n-w+r);
+ *   score[h,t] = (1/k) sum_{|j|<=k/2, 0<=t+j<n-w} mass[h,t+j];
+ * tokens t >= n-w get +inf.
+ * q_win: device [Hq, w, d] packed.  k: device, strides from shape.
+ * score: device fp32 [Hkv, n] packed (output). */
+VECTOR_API int vector_score(const vector_shape* shape, const void* q_win, const void* k,
+                 float* score, void* ws, size_t ws_bytes, void* stream);
+
+/* Reconstruction residual (Section 3.2 Step 2), for every token:
+ *   eps[h,t] = || v[h,t] - k[h,t] . W[h] ||_2^2, fp32 accumulation.
+ * W: device [Hkv, d, d] (or one [d, d] when w_shared).  eps: device fp32 [Hkv, n]. */
+VECTOR_API int vector_residual(const vector_shape* shape, const void* k, const void* v, const void* W,
+                    float* eps, void* ws, size_t ws_bytes, void* stream);
+
+/* Score and residual in one pass over k (same outputs as the two calls above,
+ * within floating-point tolerance; k is streamed once less). */
+VECTOR_API int vector_score_residual(const vector_shape* shape, const void* q_win, const void* k, const void* v,
+                          const void* W, float* score, float* eps, void* ws, size_t ws_bytes, void* stream);
+
+/* Three-way routing (Section 3.2 Steps 1 and 3), independently per KV head:
+ *   pool    = the n_pool tokens of highest score,
+ *   approx  = the n_approx pool tokens of lowest eps,
+ *   retain  = pool minus approx;  everything else is evicted.
+ * Ties go to the lower token index in both selections.  NaN inputs are not
+ * supported; -0 and +0 compare equal.
+ * score, eps: device fp32 [Hkv, n].  tier: device u8 [Hkv, n] (VECTOR_TIER_*).
+ * idx_retain: device i32 [Hkv, n_pool-n_approx], idx_approx: device i32
+ * [Hkv, n_approx], both ascending token indices.
+ * Requires 0 <= n_approx <= n_pool <= n. */
+VECTOR_API int vector_route(int32_t n_kv_heads, int32_t seq_len, const float* score, const float* eps,
+                 int32_t n_pool, int32_t n_approx,
+                 uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx,
+                 void* ws, size_t ws_bytes, void* stream);
+
+/* Packed cache (Section 3.2: keys of the whole pool, values of retained tokens
+ * only).  Row gather by the index lists:
+ *   k_ret[h,s,:] = k[h, idx_retain[h,s], :],  v_ret likewise,
+ *   k_apx[h,s,:] = k[h, idx_approx[h,s], :].
+ * k_ret, v_ret: device [Hkv, cap_retain, d] with cap_retain >= n_retain (rows
+ * beyond n_retain are left untouched for decode-time appends);
+ * k_apx: device [Hkv, n_approx, d]. */
+VECTOR_API int vector_compact(const vector_shape* shape, const void* k, const void* v,
+                   const int32_t* idx_retain, const int32_t* idx_approx,
+                   int32_t n_retain, int32_t n_approx,
+                   void* k_ret, void* v_ret, void* k_apx, int32_t cap_retain, void* stream);
+
+/* ---- decode attention over packed caches -------------------------------- */
+
+typedef struct {
+  int32_t batch, n_q_heads, n_kv_heads, head_dim;
+  int32_t dtype;                  /* vector_dtype of the cache, q, W and out            */
+  int32_t cap_retain, n_approx;   /* uniform capacities                                 */
+  int32_t w_shared;               /* non-zero: W is one [d, d] for all heads            */
+  const int32_t* len_retain;      /* device [batch]: live rows of the retained segment
+                                     (compressed + appended), 0 <= len <= cap_retain    */
+  const void* k_ret;              /* device [batch, Hkv, cap_retain, d]                 */
+  const void* v_ret;              /* device [batch, Hkv, cap_retain, d]                 */
+  const void* k_apx;              /* device [batch, Hkv, n_approx, d]                   */
+  const void* W;                  /* device [Hkv, d, d]                                 */
+} vector_cache;
+
+/* One query token per sequence (Section 3.2 Step 3: discarded values are
+ * rebuilt from their keys during generation).  Per sequence b and query head
+ * qh (KV head h = qh / G): one softmax over the live retained rows and the
+ * approximated rows together, logits q . k_t * scale, and
+ *   out = sum_ret p_t v_t + sum_apx p_t (k_t . W[h]).
+ * q: device [batch, Hq, d]; out: device [batch, Hq, d], same dtype as the cache.
+ * flags: reserved, pass 0.  A sequence with no live token yields zeros. */
+VECTOR_API int vector_decode_attn(const vector_cache* cache, const void* q, float scale, void* out,
+                       int32_t flags, void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VECTOR_H_ */

@@ -1,0 +1,163 @@
+"""ctypes binding of libvector.so: the same entry points as include/vector.h.
+
+Argument marshalling only -- every step of the path runs in the HIP kernels.
+Tensors are torch tensors used as device memory; the stream defaults to torch's
+current stream.  A missing library is an error: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(PKG_DIR, "libvector.so")
+
+VECTOR_F32, VECTOR_BF16 = 0, 1
+TIER_EVICT, TIER_APPROX, TIER_RETAIN = 0, 1, 2
+
+EXPORTS = (
+    "vector_budget_counts", "vector_budget_counts_frac", "vector_pa_deploy", "vector_workspace_bytes",
+    "vector_strerror", "vector_score", "vector_residual", "vector_score_residual", "vector_route",
+    "vector_compact", "vector_decode_attn",
+)
+
+
+class VectorError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+class Shape(C.Structure):
+    _fields_ = [
+        ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("seq_len", C.c_int32),
+        ("window", C.c_int32), ("pool_kernel", C.c_int32), ("dtype", C.c_int32), ("reserved", C.c_int32),
+        ("k_stride_head", C.c_int64), ("k_stride_tok", C.c_int64),
+        ("v_stride_head", C.c_int64), ("v_stride_tok", C.c_int64),
+        ("w_stride_head", C.c_int64), ("w_shared", C.c_int32), ("reserved2", C.c_int32),
+    ]
+
+
+class Cache(C.Structure):
+    _fields_ = [
+        ("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+        ("dtype", C.c_int32), ("cap_retain", C.c_int32), ("n_approx", C.c_int32), ("w_shared", C.c_int32),
+        ("len_retain", C.c_void_p), ("k_ret", C.c_void_p), ("v_ret", C.c_void_p), ("k_apx", C.c_void_p),
+        ("W", C.c_void_p),
+    ]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libvector.so (built by paper_2605_23258_amd.build); fails loudly if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} not found: build it with `python -m paper_2605_23258_amd.build` "
+                "(there is no CPU fallback for the hot path)")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+        L.vector_budget_counts.argtypes = [i32, C.c_double, C.c_double, C.POINTER(i32), C.POINTER(i32)]
+        L.vector_budget_counts_frac.argtypes = [i32, C.c_double, C.c_double, C.POINTER(i32), C.POINTER(i32)]
+        L.vector_pa_deploy.argtypes = [C.c_double, C.c_double]
+        L.vector_pa_deploy.restype = C.c_double
+        L.vector_workspace_bytes.argtypes = [C.POINTER(Shape), i32, i32, i32]
+        L.vector_workspace_bytes.restype = sz
+        L.vector_strerror.argtypes = [C.c_int]
+        L.vector_strerror.restype = C.c_char_p
+        L.vector_score.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, sz, vp]
+        L.vector_residual.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, sz, vp]
+        L.vector_score_residual.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.vector_route.argtypes = [i32, i32, vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
+        L.vector_compact.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, i32, i32, vp, vp, vp, i32, vp]
+        L.vector_decode_attn.argtypes = [C.POINTER(Cache), vp, C.c_float, vp, i32, vp, sz, vp]
+        for name in EXPORTS:
+            if getattr(L, name).restype is C.c_int:
+                pass
+        _lib = L
+    return _lib
+
+
+def _ptr(t) -> Optional[int]:
+    """Device (or host) address of a tensor, None for None."""
+    if t is None:
+        return None
+    return int(t.data_ptr())
+
+
+def _nbytes(t) -> int:
+    return 0 if t is None else int(t.numel() * t.element_size())
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream) or None
+    return int(getattr(stream, "cuda_stream", stream)) or None
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != 0:
+        raise VectorError(rc, where)
+
+
+def strerror(code: int) -> str:
+    return lib().vector_strerror(code).decode()
+
+
+def vector_budget_counts(n: int, p_c: float, p_a: float):
+    a, b = C.c_int32(), C.c_int32()
+    _check(lib().vector_budget_counts(n, p_c, p_a, C.byref(a), C.byref(b)), "vector_budget_counts")
+    return a.value, b.value
+
+
+def vector_budget_counts_frac(n: int, f_retain: float, f_approx: float):
+    a, b = C.c_int32(), C.c_int32()
+    _check(lib().vector_budget_counts_frac(n, f_retain, f_approx, C.byref(a), C.byref(b)), "vector_budget_counts_frac")
+    return a.value, b.value
+
+
+def vector_pa_deploy(p_c: float, eps: float = 0.0) -> float:
+    return lib().vector_pa_deploy(p_c, eps)
+
+
+def vector_workspace_bytes(shape: Shape, n_pool: int, n_approx: int, batch: int = 1) -> int:
+    return int(lib().vector_workspace_bytes(C.byref(shape), n_pool, n_approx, batch))
+
+
+def vector_score(shape: Shape, q_win, k, score, ws, stream=None) -> None:
+    _check(lib().vector_score(C.byref(shape), _ptr(q_win), _ptr(k), _ptr(score), _ptr(ws), _nbytes(ws),
+                              _stream(stream)), "vector_score")
+
+
+def vector_residual(shape: Shape, k, v, W, eps, ws=None, stream=None) -> None:
+    _check(lib().vector_residual(C.byref(shape), _ptr(k), _ptr(v), _ptr(W), _ptr(eps), _ptr(ws), _nbytes(ws),
+                                 _stream(stream)), "vector_residual")
+
+
+def vector_score_residual(shape: Shape, q_win, k, v, W, score, eps, ws, stream=None) -> None:
+    _check(lib().vector_score_residual(C.byref(shape), _ptr(q_win), _ptr(k), _ptr(v), _ptr(W), _ptr(score),
+                                       _ptr(eps), _ptr(ws), _nbytes(ws), _stream(stream)), "vector_score_residual")
+
+
+def vector_route(n_kv_heads: int, seq_len: int, score, eps, n_pool: int, n_approx: int, tier, idx_retain,
+                 idx_approx, ws, stream=None) -> None:
+    _check(lib().vector_route(n_kv_heads, seq_len, _ptr(score), _ptr(eps), n_pool, n_approx, _ptr(tier),
+                              _ptr(idx_retain), _ptr(idx_approx), _ptr(ws), _nbytes(ws), _stream(stream)),
+           "vector_route")
+
+
+def vector_compact(shape: Shape, k, v, idx_retain, idx_approx, n_retain: int, n_approx: int, k_ret, v_ret, k_apx,
+                   cap_retain: int, stream=None) -> None:
+    _check(lib().vector_compact(C.byref(shape), _ptr(k), _ptr(v), _ptr(idx_retain), _ptr(idx_approx), n_retain,
+                                n_approx, _ptr(k_ret), _ptr(v_ret), _ptr(k_apx), cap_retain, _stream(stream)),
+           "vector_compact")
+
+
+def vector_decode_attn(cache: Cache, q, scale: float, out, ws, flags: int = 0, stream=None) -> None:
+    _check(lib().vector_decode_attn(C.byref(cache), _ptr(q), float(scale), _ptr(out), flags, _ptr(ws), _nbytes(ws),
+                                    _stream(stream)), "vector_decode_attn")

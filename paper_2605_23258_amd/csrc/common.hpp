@@ -1,0 +1,107 @@
+// Shared device helpers for the gfx950 kernels: element types, 16-byte operand
+// chunks for the 32x32 MFMA tiles, and wave-level reductions (wave = 64 lanes).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/vector.h"
+
+namespace vec {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int kWave = 64;
+
+struct bf16_t { uint16_t bits; };   // storage type of VECTOR_BF16 tensors
+
+template <typename T> struct Elem;
+template <> struct Elem<float>  { static constexpr int kPerChunk = 4; static constexpr int kDtype = VECTOR_F32; };
+template <> struct Elem<bf16_t> { static constexpr int kPerChunk = 8; static constexpr int kDtype = VECTOR_BF16; };
+
+__device__ __forceinline__ float to_float(float x) { return x; }
+__device__ __forceinline__ float to_float(bf16_t x) { return __uint_as_float(((uint32_t)x.bits) << 16); }
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
+
+// round-to-nearest-even fp32 -> bf16 bits (finite inputs)
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ void store_elem(float* p, float x) { *p = x; }
+__device__ __forceinline__ void store_elem(bf16_t* p, float x) { p->bits = f32_to_bf16_bits(x); }
+
+// ---------------------------------------------------------------------------
+// Operand chunks.  One 32x32 MFMA tile contracts over head_dim in "chunks": a
+// chunk is what the two lane halves of a wave hold for one row in 16 bytes each
+// (2 x 8 bf16 or 2 x 4 fp32 elements).  Lane l carries row (l & 31); lane half
+// (l >> 5) carries elements [c*2E + half*E, +E) of that row, E = elements per
+// 16 bytes.  Both MFMA operands use the same mapping, so the contraction pairs
+// equal element indices whatever order the hardware walks them in.
+// ---------------------------------------------------------------------------
+typedef uint4 chunk_t;
+
+template <typename T> __device__ __forceinline__ constexpr int chunks_per_row(int d) {
+  return d / (2 * Elem<T>::kPerChunk);
+}
+
+// element offset (within a row) of the 16 bytes lane half `half` holds for chunk c
+template <typename T> __device__ __forceinline__ int chunk_elem_offset(int c, int half) {
+  return (c * 2 + half) * Elem<T>::kPerChunk;
+}
+
+__device__ __forceinline__ chunk_t load_chunk(const void* p) { return *reinterpret_cast<const chunk_t*>(p); }
+
+// acc += A(32 x chunk) * B(chunk x 32): a holds rows of the M side, b rows of the N side.
+template <typename T> __device__ __forceinline__ void mma_chunk(f32x16& acc, const chunk_t& a, const chunk_t& b);
+
+template <> __device__ __forceinline__ void mma_chunk<bf16_t>(f32x16& acc, const chunk_t& a, const chunk_t& b) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+}
+template <> __device__ __forceinline__ void mma_chunk<float>(f32x16& acc, const chunk_t& a, const chunk_t& b) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+}
+
+// Row of the 32x32 accumulator tile that register v of this lane holds
+// (column = lane & 31).
+__device__ __forceinline__ int acc_row(int v, int lane_half) { return (v >> 2) * 8 + lane_half * 4 + (v & 3); }
+
+// ---------------------------------------------------------------------------
+// wave reductions
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, kWave);
+  return x;
+}
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, kWave));
+  return x;
+}
+__device__ __forceinline__ int wave_sum_i(int x) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, kWave);
+  return x;
+}
+// inclusive prefix sum across the 64 lanes
+__device__ __forceinline__ int wave_incl_scan_i(int x, int lane) {
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    int y = __shfl_up(x, o, kWave);
+    if (lane >= o) x += y;
+  }
+  return x;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+}  // namespace vec

@@ -1,0 +1,42 @@
+// Host-side launch helpers shared by the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "../../include/vector.h"
+
+namespace vec {
+
+constexpr size_t kMaxLdsBytes = 160 * 1024;   // LDS per workgroup on gfx950
+
+#define VEC_HIP(expr)                                   \
+  do {                                                  \
+    hipError_t e_ = (expr);                             \
+    if (e_ != hipSuccess) return VECTOR_ERR_HIP;        \
+  } while (0)
+
+// Dynamic LDS above the default limit has to be opted into per kernel.
+inline hipError_t set_max_lds(const void* func, size_t bytes) {
+  if (bytes <= 48 * 1024) return hipSuccess;
+  return hipFuncSetAttribute(func, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// kernel-file entry points used by the C ABI layer
+size_t score_workspace_bytes(const vector_shape& s);
+int launch_score_residual(const vector_shape& s, const void* q, const void* k, const void* v, const void* W,
+                          float* score, float* eps, void* ws, hipStream_t stream);
+
+size_t route_workspace_bytes(int n_kv_heads, int seq_len, int n_pool);
+int launch_route(int n_kv_heads, int seq_len, const float* score, const float* eps, int n_pool, int n_approx,
+                 uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx, void* ws, hipStream_t stream);
+
+int launch_compact(const vector_shape& s, const void* k, const void* v, const int32_t* idx_retain,
+                   const int32_t* idx_approx, int n_retain, int n_approx, void* k_ret, void* v_ret, void* k_apx,
+                   int cap_retain, hipStream_t stream);
+
+size_t decode_workspace_bytes(int batch, int n_q_heads, int n_kv_heads, int head_dim, int cap_retain, int n_approx);
+int launch_decode_attn(const vector_cache& c, const void* q, float scale, void* out, int flags, void* ws,
+                       hipStream_t stream);
+
+}  // namespace vec

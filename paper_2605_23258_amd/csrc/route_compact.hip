@@ -1,0 +1,252 @@
+// Three-way routing (Section 3.2, Steps 1 and 3) and compaction into the packed cache.
+//
+// route_kernel: one workgroup per KV head.
+//   1. radix select (4 x 8-bit digits, LDS histograms) of the n_pool-th largest
+//      score key -> threshold key and the number of threshold ties to take;
+//   2. ordered prefix-sum pass over the tokens: pool membership with ties taken in
+//      ascending token index, pool list (token index, residual key) in token order;
+//   3. radix select of the n_approx-th smallest residual inside the pool;
+//   4. ordered pass over the pool list: ascending idx_approx / idx_retain, tiers.
+// Slot assignment comes from ordered scans only; atomics are used for histograms
+// alone, so the result does not depend on scheduling.
+//
+// gather_rows_kernel: row gather k_ret / v_ret / k_apx by the index lists.
+#include "common.hpp"
+#include "launch.hpp"
+
+namespace vec {
+
+namespace {
+
+constexpr int RT = 1024;          // threads per routing workgroup
+constexpr int RW = RT / kWave;    // waves
+constexpr int EPT = 4;            // consecutive elements per thread in the ordered passes
+
+// Order-preserving map float -> u32 (larger float, larger key); -0 and +0 share a key.
+__device__ __forceinline__ uint32_t float_key(float x) {
+  uint32_t b = __float_as_uint(x + 0.0f);
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+struct RouteShared {
+  int hist[256];
+  int2 wave_tot[2][RW];
+  int digit, above;
+};
+
+// k-th largest key among keyf(0..m-1), 1 <= k <= m.  Returns the key value and how many
+// elements equal to it belong to the k largest.
+template <typename KeyFn>
+__device__ void radix_select_desc(KeyFn keyf, int m, int k, RouteShared& sh, uint32_t& thr, int& quota) {
+  uint32_t prefix = 0, mask = 0;
+  int remaining = k;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    if (threadIdx.x < 256) sh.hist[threadIdx.x] = 0;
+    __syncthreads();
+    for (int i = threadIdx.x; i < m; i += RT) {
+      uint32_t key = keyf(i);
+      if ((key & mask) == prefix) atomicAdd(&sh.hist[(key >> shift) & 255u], 1);
+    }
+    __syncthreads();
+    if (wave == 0) {
+      // lane l owns digits 255-4l .. 252-4l, i.e. lanes walk the digits downwards
+      const int base = 255 - 4 * lane;
+      const int c0 = sh.hist[base], c1 = sh.hist[base - 1], c2 = sh.hist[base - 2], c3 = sh.hist[base - 3];
+      const int tot = c0 + c1 + c2 + c3;
+      const int incl = wave_incl_scan_i(tot, lane);
+      int above = incl - tot;               // candidates with a larger digit than `base`
+      if (above < remaining && remaining <= incl) {
+        int d = base;
+        if (remaining > above + c0) { above += c0; d = base - 1;
+          if (remaining > above + c1) { above += c1; d = base - 2;
+            if (remaining > above + c2) { above += c2; d = base - 3; } } }
+        sh.digit = d;
+        sh.above = above;
+      }
+    }
+    __syncthreads();
+    prefix |= ((uint32_t)sh.digit) << shift;
+    mask |= 255u << shift;
+    remaining -= sh.above;
+  }
+  thr = prefix;
+  quota = remaining;
+  __syncthreads();      // sh.digit / sh.above may be rewritten by the next select
+}
+
+// Ordered pass over m elements in index order.  classify(i) returns 2 for "strictly
+// selected", 1 for "threshold tie", 0 otherwise; emit(i, selected, rank_selected) is
+// called for every element with its rank among the selected ones.  Ties are selected
+// while fewer than `quota` earlier ties exist.
+template <typename ClassFn, typename EmitFn>
+__device__ void ordered_select(ClassFn classify, EmitFn emit, int m, int quota, RouteShared& sh) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int carry_gt = 0, carry_eq = 0, buf = 0;
+  for (int base = 0; base < m; base += RT * EPT) {
+    const int i0 = base + threadIdx.x * EPT;
+    int cls[EPT], gt = 0, eq = 0;
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+      cls[j] = (i0 + j < m) ? classify(i0 + j) : 0;
+      gt += cls[j] == 2;
+      eq += cls[j] == 1;
+    }
+    const int incl_gt = wave_incl_scan_i(gt, lane), incl_eq = wave_incl_scan_i(eq, lane);
+    if (lane == 63) sh.wave_tot[buf][wave] = make_int2(incl_gt, incl_eq);
+    __syncthreads();
+    int pre_gt = carry_gt + incl_gt - gt, pre_eq = carry_eq + incl_eq - eq;
+    for (int wv = 0; wv < RW; ++wv) {
+      int2 t = sh.wave_tot[buf][wv];
+      if (wv < wave) { pre_gt += t.x; pre_eq += t.y; }
+      carry_gt += t.x;
+      carry_eq += t.y;
+    }
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+      if (i0 + j < m) {
+        const bool sel = cls[j] == 2 || (cls[j] == 1 && pre_eq < quota);
+        emit(i0 + j, sel, pre_gt + min(pre_eq, quota));
+        pre_gt += cls[j] == 2;
+        pre_eq += cls[j] == 1;
+      }
+    }
+    buf ^= 1;
+  }
+}
+
+__global__ __launch_bounds__(RT) void route_kernel(const float* __restrict__ score, const float* __restrict__ eps,
+                                                   int n, int n_pool, int n_approx, uint8_t* __restrict__ tier,
+                                                   int32_t* __restrict__ idx_retain, int32_t* __restrict__ idx_approx,
+                                                   int32_t* __restrict__ pool_idx, uint32_t* __restrict__ pool_key) {
+  __shared__ RouteShared sh;
+  const int h = blockIdx.x;
+  const float* sc = score + (size_t)h * n;
+  const float* ep = eps + (size_t)h * n;
+  uint8_t* tr = tier + (size_t)h * n;
+  int32_t* pidx = pool_idx + (size_t)h * n_pool;
+  uint32_t* pkey = pool_key + (size_t)h * n_pool;
+  int32_t* ir = idx_retain + (size_t)h * (n_pool - n_approx);
+  int32_t* ia = idx_approx + (size_t)h * n_approx;
+
+  if (n_pool == 0) {
+    for (int i = threadIdx.x; i < n; i += RT) tr[i] = VECTOR_TIER_EVICT;
+    return;
+  }
+
+  // Step 1: the pool is the n_pool tokens of highest score
+  uint32_t thr;
+  int quota;
+  radix_select_desc([&](int i) { return float_key(sc[i]); }, n, n_pool, sh, thr, quota);
+
+  ordered_select(
+      [&](int i) { uint32_t key = float_key(sc[i]); return key > thr ? 2 : (key == thr ? 1 : 0); },
+      [&](int i, bool sel, int rank) {
+        tr[i] = sel ? VECTOR_TIER_RETAIN : VECTOR_TIER_EVICT;
+        if (sel && rank < n_pool) {          // rank < n_pool by construction; never write past the list
+          pidx[rank] = i;
+          pkey[rank] = ~float_key(ep[i]);      // smaller residual, larger key
+        }
+      },
+      n, quota, sh);
+  __threadfence();
+  __syncthreads();
+
+  // Step 3: inside the pool, the n_approx tokens of lowest residual lose their value
+  if (n_approx == 0) {
+    for (int i = threadIdx.x; i < n_pool; i += RT) ir[i] = pidx[i];
+    return;
+  }
+  radix_select_desc([&](int i) { return pkey[i]; }, n_pool, n_approx, sh, thr, quota);
+  ordered_select(
+      [&](int i) { uint32_t key = pkey[i]; return key > thr ? 2 : (key == thr ? 1 : 0); },
+      [&](int i, bool sel, int rank) {
+        const int tok = pidx[i];
+        if (sel) {
+          if (rank < n_approx) {
+            ia[rank] = tok;
+            tr[tok] = VECTOR_TIER_APPROX;
+          }
+        } else if (i - rank < n_pool - n_approx) {
+          ir[i - rank] = tok;
+        }
+      },
+      n_pool, quota, sh);
+}
+
+// ---------------------------------------------------------------------------
+// compaction: one 16-byte piece per thread, P pieces per row
+// ---------------------------------------------------------------------------
+struct GatherParams {
+  const unsigned char* k; const unsigned char* v;
+  int64_t k_sh, k_st, v_sh, v_st;          // byte strides
+  const int32_t* idx_retain; const int32_t* idx_approx;
+  int n_retain, n_approx, cap_retain, row_bytes, n;
+  unsigned char* k_ret; unsigned char* v_ret; unsigned char* k_apx;
+};
+
+__global__ __launch_bounds__(256) void gather_rows_kernel(GatherParams p) {
+  const int h = blockIdx.y, seg = blockIdx.z;       // seg 0: k_ret, 1: v_ret, 2: k_apx
+  const int pieces = p.row_bytes / 16;
+  const int rows = (seg == 2) ? p.n_approx : p.n_retain;
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int row = (int)(gid / pieces), piece = (int)(gid - (int64_t)row * pieces);
+  if (row >= rows) return;
+  const int32_t* idx = (seg == 2) ? p.idx_approx + (size_t)h * p.n_approx : p.idx_retain + (size_t)h * p.n_retain;
+  int tok = idx[row];
+  tok = min(max(tok, 0), p.n - 1);                  // an index list is trusted, but never walk out of the tensor
+  const unsigned char* src = (seg == 1) ? p.v + h * p.v_sh + (int64_t)tok * p.v_st : p.k + h * p.k_sh + (int64_t)tok * p.k_st;
+  unsigned char* dst = (seg == 0) ? p.k_ret + ((size_t)h * p.cap_retain + row) * p.row_bytes
+                     : (seg == 1) ? p.v_ret + ((size_t)h * p.cap_retain + row) * p.row_bytes
+                                  : p.k_apx + ((size_t)h * p.n_approx + row) * p.row_bytes;
+  *reinterpret_cast<uint4*>(dst + piece * 16) = *reinterpret_cast<const uint4*>(src + piece * 16);
+}
+
+}  // namespace
+
+size_t route_workspace_bytes(int n_kv_heads, int seq_len, int n_pool) {
+  (void)seq_len;
+  return align_up((size_t)n_kv_heads * n_pool * sizeof(int32_t), 256) + align_up((size_t)n_kv_heads * n_pool * sizeof(uint32_t), 256);
+}
+
+int launch_route(int n_kv_heads, int seq_len, const float* score, const float* eps, int n_pool, int n_approx,
+                 uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx, void* ws, hipStream_t stream) {
+  int32_t* pool_idx = reinterpret_cast<int32_t*>(ws);
+  uint32_t* pool_key = reinterpret_cast<uint32_t*>(reinterpret_cast<unsigned char*>(ws) +
+                                                   align_up((size_t)n_kv_heads * n_pool * sizeof(int32_t), 256));
+  hipLaunchKernelGGL(route_kernel, dim3(n_kv_heads), dim3(RT), 0, stream, score, eps, seq_len, n_pool, n_approx, tier,
+                     idx_retain, idx_approx, pool_idx, pool_key);
+  VEC_HIP(hipGetLastError());
+  return VECTOR_OK;
+}
+
+int launch_compact(const vector_shape& s, const void* k, const void* v, const int32_t* idx_retain,
+                   const int32_t* idx_approx, int n_retain, int n_approx, void* k_ret, void* v_ret, void* k_apx,
+                   int cap_retain, hipStream_t stream) {
+  const int esz = (s.dtype == VECTOR_BF16) ? 2 : 4;
+  GatherParams p;
+  p.k = reinterpret_cast<const unsigned char*>(k);
+  p.v = reinterpret_cast<const unsigned char*>(v);
+  const int64_t k_st = s.k_stride_tok ? s.k_stride_tok : s.head_dim;
+  const int64_t v_st = s.v_stride_tok ? s.v_stride_tok : s.head_dim;
+  p.k_st = k_st * esz;
+  p.v_st = v_st * esz;
+  p.k_sh = (s.k_stride_head ? s.k_stride_head : (int64_t)s.seq_len * k_st) * esz;
+  p.v_sh = (s.v_stride_head ? s.v_stride_head : (int64_t)s.seq_len * v_st) * esz;
+  p.idx_retain = idx_retain; p.idx_approx = idx_approx;
+  p.n_retain = n_retain; p.n_approx = n_approx; p.cap_retain = cap_retain;
+  p.row_bytes = s.head_dim * esz; p.n = s.seq_len;
+  p.k_ret = reinterpret_cast<unsigned char*>(k_ret);
+  p.v_ret = reinterpret_cast<unsigned char*>(v_ret);
+  p.k_apx = reinterpret_cast<unsigned char*>(k_apx);
+  const int pieces = p.row_bytes / 16;
+  const int max_rows = n_retain > n_approx ? n_retain : n_approx;
+  if (max_rows == 0) return VECTOR_OK;
+  const int64_t threads = (int64_t)max_rows * pieces;
+  dim3 grid((unsigned)((threads + 255) / 256), s.n_kv_heads, 3);
+  hipLaunchKernelGGL(gather_rows_kernel, grid, dim3(256), 0, stream, p);
+  VEC_HIP(hipGetLastError());
+  return VECTOR_OK;
+}
+
+}  // namespace vec

@@ -1,0 +1,163 @@
+// C ABI of libvector: argument validation and dispatch to the kernel launchers.
+// Everything is checked on the host before the first launch, so a failing call
+// leaves the outputs untouched.
+#include <math.h>
+#include <string.h>
+
+#include "../../include/vector.h"
+#include "launch.hpp"
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_shape(const vector_shape* s, bool need_window) {
+  if (!s) return VECTOR_ERR_ARG;
+  if (s->dtype != VECTOR_F32 && s->dtype != VECTOR_BF16) return VECTOR_ERR_DTYPE;
+  if (s->head_dim != 64 && s->head_dim != 128) return VECTOR_ERR_SHAPE;
+  if (s->n_kv_heads < 1 || s->n_kv_heads > 65535 || s->n_q_heads < s->n_kv_heads || s->n_q_heads % s->n_kv_heads) return VECTOR_ERR_SHAPE;
+  if (s->seq_len < 1) return VECTOR_ERR_SHAPE;
+  const int align = s->dtype == VECTOR_BF16 ? 8 : 4;      // elements per 16 bytes
+  const int64_t strides[5] = {s->k_stride_head, s->k_stride_tok, s->v_stride_head, s->v_stride_tok, s->w_stride_head};
+  for (int64_t st : strides)
+    if (st < 0 || st % align) return VECTOR_ERR_SHAPE;
+  if ((s->k_stride_tok && s->k_stride_tok < s->head_dim) || (s->v_stride_tok && s->v_stride_tok < s->head_dim)) return VECTOR_ERR_SHAPE;
+  if (need_window) {
+    if (s->window < 1 || s->window > s->seq_len) return VECTOR_ERR_SHAPE;
+    if (s->pool_kernel < 1 || !(s->pool_kernel & 1)) return VECTOR_ERR_SHAPE;
+  }
+  return VECTOR_OK;
+}
+
+int check_ws(const void* ws, size_t have, size_t need) {
+  if (need == 0) return VECTOR_OK;
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || have < need) return VECTOR_ERR_WORKSPACE;
+  return VECTOR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int vector_budget_counts_frac(int32_t n, double f_retain, double f_approx, int32_t* n_pool, int32_t* n_approx) {
+  if (!n_pool || !n_approx || n < 0) return VECTOR_ERR_ARG;
+  if (!(f_retain >= 0.0) || !(f_approx >= 0.0) || f_retain + f_approx > 1.0 + 1e-12) return VECTOR_ERR_ARG;
+  const int32_t n_r = (int32_t)floor(f_retain * (double)n);
+  const int32_t n_a = (int32_t)floor(f_approx * (double)n);
+  *n_pool = n_r + n_a;
+  *n_approx = n_a;
+  return VECTOR_OK;
+}
+
+int vector_budget_counts(int32_t n, double p_c, double p_a, int32_t* n_pool, int32_t* n_approx) {
+  if (!(p_c >= 0.0 && p_c <= 1.0) || !(p_a >= 0.0) || p_a > p_c + 1e-12 || 1.0 - p_c - p_a < -1e-12) return VECTOR_ERR_ARG;
+  double f_retain = 1.0 - p_c - p_a;
+  if (f_retain < 0.0) f_retain = 0.0;
+  return vector_budget_counts_frac(n, f_retain, 2.0 * p_a, n_pool, n_approx);
+}
+
+double vector_pa_deploy(double p_c, double eps) {
+  const double a = p_c / 2.0, b = (1.0 - p_c - eps) / 2.0;
+  return a < b ? a : b;
+}
+
+size_t vector_workspace_bytes(const vector_shape* s, int32_t n_pool, int32_t n_approx, int32_t batch) {
+  if (check_shape(s, true) != VECTOR_OK || n_pool < 0 || n_approx < 0 || n_approx > n_pool || batch < 1) return 0;
+  size_t need = vec::score_workspace_bytes(*s);
+  const size_t r = vec::route_workspace_bytes(s->n_kv_heads, s->seq_len, n_pool);
+  if (r > need) need = r;
+  // decode: the retained segment may grow by appended tokens up to seq_len rows
+  const size_t d = vec::decode_workspace_bytes(batch, s->n_q_heads, s->n_kv_heads, s->head_dim, s->seq_len, n_approx);
+  if (d > need) need = d;
+  return need + 256;
+}
+
+const char* vector_strerror(int code) {
+  switch (code) {
+    case VECTOR_OK: return "ok";
+    case VECTOR_ERR_ARG: return "invalid argument";
+    case VECTOR_ERR_SHAPE: return "unsupported shape";
+    case VECTOR_ERR_WORKSPACE: return "workspace too small or misaligned";
+    case VECTOR_ERR_DTYPE: return "unknown element type";
+    case VECTOR_ERR_HIP: return "HIP runtime error";
+    default: return "unknown error";
+  }
+}
+
+int vector_score(const vector_shape* s, const void* q_win, const void* k, float* score, void* ws, size_t ws_bytes,
+                 void* stream) {
+  int rc = check_shape(s, true);
+  if (rc) return rc;
+  if (!q_win || !k || !score || !aligned16(q_win) || !aligned16(k)) return VECTOR_ERR_ARG;
+  if ((rc = check_ws(ws, ws_bytes, vec::score_workspace_bytes(*s)))) return rc;
+  return vec::launch_score_residual(*s, q_win, k, nullptr, nullptr, score, nullptr, ws, (hipStream_t)stream);
+}
+
+int vector_residual(const vector_shape* s, const void* k, const void* v, const void* W, float* eps, void* ws,
+                    size_t ws_bytes, void* stream) {
+  (void)ws; (void)ws_bytes;
+  int rc = check_shape(s, false);
+  if (rc) return rc;
+  if (!k || !v || !W || !eps || !aligned16(k) || !aligned16(v) || !aligned16(W)) return VECTOR_ERR_ARG;
+  vector_shape t = *s;
+  if (t.window < 1 || t.window > t.seq_len) t.window = 1;     // unused by the residual
+  return vec::launch_score_residual(t, nullptr, k, v, W, nullptr, eps, nullptr, (hipStream_t)stream);
+}
+
+int vector_score_residual(const vector_shape* s, const void* q_win, const void* k, const void* v, const void* W,
+                          float* score, float* eps, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_shape(s, true);
+  if (rc) return rc;
+  if (!q_win || !k || !v || !W || !score || !eps) return VECTOR_ERR_ARG;
+  if (!aligned16(q_win) || !aligned16(k) || !aligned16(v) || !aligned16(W)) return VECTOR_ERR_ARG;
+  if ((rc = check_ws(ws, ws_bytes, vec::score_workspace_bytes(*s)))) return rc;
+  return vec::launch_score_residual(*s, q_win, k, v, W, score, eps, ws, (hipStream_t)stream);
+}
+
+int vector_route(int32_t n_kv_heads, int32_t seq_len, const float* score, const float* eps, int32_t n_pool,
+                 int32_t n_approx, uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx, void* ws, size_t ws_bytes,
+                 void* stream) {
+  if (n_kv_heads < 1 || seq_len < 1) return VECTOR_ERR_SHAPE;
+  if (n_approx < 0 || n_pool < n_approx || n_pool > seq_len) return VECTOR_ERR_ARG;
+  if (!score || !eps || !tier) return VECTOR_ERR_ARG;
+  if ((n_pool - n_approx > 0 && !idx_retain) || (n_approx > 0 && !idx_approx)) return VECTOR_ERR_ARG;
+  int rc = check_ws(ws, ws_bytes, vec::route_workspace_bytes(n_kv_heads, seq_len, n_pool));
+  if (rc) return rc;
+  return vec::launch_route(n_kv_heads, seq_len, score, eps, n_pool, n_approx, tier, idx_retain, idx_approx, ws,
+                           (hipStream_t)stream);
+}
+
+int vector_compact(const vector_shape* s, const void* k, const void* v, const int32_t* idx_retain,
+                   const int32_t* idx_approx, int32_t n_retain, int32_t n_approx, void* k_ret, void* v_ret,
+                   void* k_apx, int32_t cap_retain, void* stream) {
+  int rc = check_shape(s, false);
+  if (rc) return rc;
+  if (n_retain < 0 || n_approx < 0 || cap_retain < n_retain || (int64_t)n_retain + n_approx > s->seq_len) return VECTOR_ERR_ARG;
+  if (!k || !v || !aligned16(k) || !aligned16(v)) return VECTOR_ERR_ARG;
+  if (n_retain > 0 && (!idx_retain || !k_ret || !v_ret || !aligned16(k_ret) || !aligned16(v_ret))) return VECTOR_ERR_ARG;
+  if (n_approx > 0 && (!idx_approx || !k_apx || !aligned16(k_apx))) return VECTOR_ERR_ARG;
+  return vec::launch_compact(*s, k, v, idx_retain, idx_approx, n_retain, n_approx, k_ret, v_ret, k_apx, cap_retain,
+                             (hipStream_t)stream);
+}
+
+int vector_decode_attn(const vector_cache* c, const void* q, float scale, void* out, int32_t flags, void* ws,
+                       size_t ws_bytes, void* stream) {
+  if (!c || !q || !out) return VECTOR_ERR_ARG;
+  if (c->dtype != VECTOR_F32 && c->dtype != VECTOR_BF16) return VECTOR_ERR_DTYPE;
+  if (c->head_dim != 64 && c->head_dim != 128) return VECTOR_ERR_SHAPE;
+  if (c->batch < 1 || c->batch > 65535 || c->n_kv_heads < 1 || c->n_kv_heads > 65535) return VECTOR_ERR_SHAPE;
+  if (c->n_q_heads < c->n_kv_heads || c->n_q_heads % c->n_kv_heads) return VECTOR_ERR_SHAPE;
+  const int G = c->n_q_heads / c->n_kv_heads;
+  if (G != 1 && G != 2 && G != 4 && G != 8) return VECTOR_ERR_SHAPE;
+  if (c->cap_retain < 0 || c->n_approx < 0 || flags != 0 || !(scale == scale)) return VECTOR_ERR_ARG;
+  if (!c->len_retain) return VECTOR_ERR_ARG;
+  if (c->cap_retain > 0 && (!c->k_ret || !c->v_ret || !aligned16(c->k_ret) || !aligned16(c->v_ret))) return VECTOR_ERR_ARG;
+  if (c->n_approx > 0 && (!c->k_apx || !c->W || !aligned16(c->k_apx) || !aligned16(c->W))) return VECTOR_ERR_ARG;
+  if (!aligned16(q) || !aligned16(out)) return VECTOR_ERR_ARG;
+  int rc = check_ws(ws, ws_bytes,
+                    vec::decode_workspace_bytes(c->batch, c->n_q_heads, c->n_kv_heads, c->head_dim, c->cap_retain, c->n_approx));
+  if (rc) return rc;
+  return vec::launch_decode_attn(*c, q, scale, out, flags, ws, (hipStream_t)stream);
+}
+
+}  // extern "C"
