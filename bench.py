@@ -1,0 +1,259 @@
+#!/usr/bin/env python3
+"""Benchmark of the VECTOR hot path on one MI355X.
+
+One step = one full prefill compression pass of the 32-layer, 32k-token workload
+(score + residual, routing, compaction, layer by layer), inputs resident in HBM.
+The decode-attention leg (batch 16 over compressed 32k caches, 256 steps) is timed
+in the same run and reported in the same JSON line, as is the CPU oracle on a
+bounded sample of the compression workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
+
+
+def log(msg: str) -> None:
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def compress_bytes_per_token_head(cfg) -> dict:
+    """Algorithmic HBM bytes per token-head of each kernel of the compression pass
+    (bf16, d=128): what a kernel has to read and write once, not what it re-reads."""
+    esz = 2 if cfg.dtype == "bf16" else 4
+    row = cfg.head_dim * esz
+    n_r, n_a, n_p = cfg.counts()
+    f_p, f_r = n_p / cfg.seq_len, n_r / cfg.seq_len
+    return {
+        "score_stats": row,                       # read K
+        "mass_residual": 2 * row + 8,             # read K (again) and V, write mass and eps
+        "pool_scores": 8,                         # read mass, write score
+        "route": 8 + 1 + 8 * f_p,                 # read score, eps; write tier and index lists
+        "gather_rows": 2 * row * (f_p + f_r),     # read and write pool K rows and retained V rows
+        # the whole pass, counting K and V once: the second streaming read of K that the
+        # two-pass softmax makes is not algorithmic
+        "pass": 2 * row + 8 + 8 + 1 + 8 * f_p + 2 * row * (f_p + f_r),
+    }
+
+
+def main() -> None:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging only)")
+    ap.add_argument("--decode-steps", type=int, default=256)
+    ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-layers", type=int, default=6)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2605_23258_amd import binding as vb
+    from paper_2605_23258_amd import datagen as dg
+    from paper_2605_23258_amd import pipeline as pl
+
+    vb.lib()                                   # fail loudly if the HIP library is not built
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = dg.CONFIGS["cfg3"]
+    if args.layers:
+        cfg = dg.scaled(cfg, layers=args.layers)
+    n_r, n_a, n_p = cfg.counts()
+    shape = pl.shape_of(cfg)
+    H, n, d = cfg.n_kv_heads, cfg.seq_len, cfg.head_dim
+    workers = min(16, os.cpu_count() or 1)
+
+    # ---- inputs: every layer has its own draws; all of them resident in HBM ----
+    t0 = time.time()
+    def gen(layer):
+        li = dg.make_layer(cfg, layer)
+        return {k: getattr(li, k) for k in ("q_win", "k", "v", "w_cal")}
+    with ThreadPoolExecutor(workers) as ex:
+        host_layers = list(ex.map(gen, range(cfg.layers)))
+    layers = [{k: pl.to_device(v, dev) for k, v in hl.items()} for hl in host_layers]
+    log(f"generated {cfg.layers} layers of K/V [{H},{n},{d}] {cfg.dtype} in {time.time() - t0:.1f}s")
+    ws = pl.alloc_workspace(vb.vector_workspace_bytes(shape, n_p, n_a, 1), dev)
+    outs = [pl.alloc_outputs(shape, n_p, n_a, n_r, torch.bfloat16, dev) for _ in range(cfg.layers)]
+
+    def step():
+        for L, o in zip(layers, outs):
+            pl.compress_layer(shape, L["q_win"], L["k"], L["v"], L["w_cal"], n_p, n_a, o, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    tokens_per_s = cfg.layers * n * args.steps / elapsed
+    log(f"compression pass: {ms_per_step:.3f} ms/step, {tokens_per_s / 1e6:.2f} M KV tokens/s")
+
+    # ---- per-kernel durations over the same steps, HIP events on the launch stream ----
+    vb.vector_timing_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    timing = vb.vector_timing_read()
+    vb.vector_timing_enable(False)
+    bpt = compress_bytes_per_token_head(cfg)
+    kernels = {}
+    for name, (ms, cnt) in timing.items():
+        if cnt:
+            avg_us = ms / cnt * 1e3
+            kernels[name] = {"avg_us": round(avg_us, 2), "launches": cnt}
+            if name in bpt:
+                kernels[name]["alg_GBs"] = round(bpt[name] * H * n / (avg_us * 1e-6) / 1e9, 1)
+    dominant = max((k for k in kernels if k in bpt), key=lambda k: kernels[k]["avg_us"])
+    dom_bytes = bpt[dominant] * H * n
+    dom_gbs = dom_bytes / (kernels[dominant]["avg_us"] * 1e-6) / 1e9
+    sum_us = sum(v["avg_us"] for v in kernels.values())
+    pass_bytes = bpt["pass"] * H * n
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(dom_gbs, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(dom_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                "bytes_per_launch": int(dom_bytes), "avg_us": kernels[dominant]["avg_us"],
+                "pass_alg_bytes_per_layer": int(pass_bytes),
+                "pass_frac_of_hbm_peak": round(pass_bytes * cfg.layers / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    # MFMA work of the pass (both softmax passes and the residual contraction)
+    G = cfg.group
+    flops_layer = H * n * (2 * 2 * G * cfg.window * d + 2 * d * d)
+    mfma_tflops = flops_layer * cfg.layers / (ms_per_step * 1e-3) / 1e12
+    log(f"kernels: {json.dumps(kernels)} (sum {sum_us:.1f} us per layer)")
+
+    # ---- decode attention over compressed caches ----
+    decode = None
+    if not args.no_decode:
+        decode = run_decode(args, vb, dg, pl, torch, np, dev, workers)
+
+    # ---- CPU oracle on a bounded sample of the same workload ----
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import vector_oracle as vo
+        try:
+            from threadpoolctl import threadpool_info
+            blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            blas_threads = 1
+        ns = min(args.cpu_sample_layers, cfg.layers)
+        t0 = time.perf_counter()
+        for hl in host_layers[:ns]:
+            wide = {k: dg.widen(v) for k, v in hl.items()}
+            s = vo.score(wide["q_win"], wide["k"], cfg.window, cfg.pool_kernel)
+            e = vo.residual(wide["k"], wide["v"], wide["w_cal"])
+            _, ir, ia = vo.route(s, e, n_p, n_a)
+            vo.compact(hl["k"], hl["v"], ir, ia)
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(ns * n / dt, 1), "unit": "KV tokens/s", "cores": int(blas_threads), "kind": "oracle",
+               "sample": f"{ns} of {cfg.layers} layers of the same workload, {dt:.1f}s (numpy fp64; BLAS threads as listed, Python loops single-threaded)"}
+        log(f"cpu oracle: {cpu}")
+
+    line = {
+        "metric": "KV tokens compressed/sec (prefill pass)", "value": round(tokens_per_s, 1), "unit": "KV tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"cfg3: {cfg.layers}-layer compression pass, n={n}, Hq/Hkv={cfg.n_q_heads}/{H}, d={d}, "
+                               f"window={cfg.window}, pool={cfg.pool_kernel}, retain/approx={n_r}/{n_a} per head",
+                   "seed": dg.MASTER_SEED},
+        "roofline": roofline,
+        "kernels": kernels,
+        "mfma": {"achieved_TFLOPs": round(mfma_tflops, 1), "peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS,
+                 "frac": round(mfma_tflops / MFMA_BF16_PEAK_TFLOPS, 4)},
+        "decode": decode,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+
+
+def run_decode(args, vb, dg, pl, torch, np, dev, workers):
+    """Batch-16 decode over caches produced by the compression pass (routing fixed at prefill)."""
+    cfg = dg.CONFIGS["cfg5"]
+    n_r, n_a, n_p = cfg.counts()
+    B, H, Hq, d, n = cfg.batch, cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim, cfg.seq_len
+    steps = args.decode_steps
+    cap = n_r + steps
+    shape = pl.shape_of(cfg)
+    ws = pl.alloc_workspace(vb.vector_workspace_bytes(shape, n_p, n_a, B), dev)
+    k_ret = torch.zeros((B, H, cap, d), dtype=torch.bfloat16, device=dev)
+    v_ret = torch.zeros((B, H, cap, d), dtype=torch.bfloat16, device=dev)
+    k_apx = torch.zeros((B, H, n_a, d), dtype=torch.bfloat16, device=dev)
+    t0 = time.time()
+    with ThreadPoolExecutor(workers) as ex:
+        seqs = list(ex.map(lambda b: dg.make_layer(cfg, 0, sub=b), range(B)))
+    # the first sequence's map is used for every sequence: W belongs to the layer, not the sequence
+    W = pl.to_device(seqs[0].w_cal, dev)
+    scratch = pl.alloc_outputs(shape, n_p, n_a, 1, torch.bfloat16, dev)
+    for b, li in enumerate(seqs):
+        q_win, k, v = (pl.to_device(getattr(li, x), dev) for x in ("q_win", "k", "v"))
+        vb.vector_score_residual(shape, q_win, k, v, W, scratch.score, scratch.eps, ws)
+        vb.vector_route(H, n, scratch.score, scratch.eps, n_p, n_a, scratch.tier, scratch.idx_retain, scratch.idx_approx, ws)
+        vb.vector_compact(shape, k, v, scratch.idx_retain, scratch.idx_approx, n_r, n_a, k_ret[b], v_ret[b], k_apx[b], cap)
+    torch.cuda.synchronize()
+    log(f"decode: built {B} compressed caches ({n_r} retained + {n_a} approximated of {n}) in {time.time() - t0:.1f}s")
+    qs, ks, vs = [], [], []
+    for s in range(steps):
+        q, k, v = dg.make_decode_step(cfg, s)
+        qs.append(q); ks.append(k); vs.append(v)
+    qs = pl.to_device(np.stack(qs), dev)            # [steps, B, Hq, d]
+    ks = pl.to_device(np.stack(ks), dev)            # [steps, B, H, d]
+    vs = pl.to_device(np.stack(vs), dev)
+    length = torch.full((B,), n_r, dtype=torch.int32, device=dev)
+    out = torch.empty((steps, B, Hq, d), dtype=torch.bfloat16, device=dev)
+    cache = vb.Cache(batch=B, n_q_heads=Hq, n_kv_heads=H, head_dim=d, dtype=vb.VECTOR_BF16, cap_retain=cap, n_approx=n_a)
+    cache.len_retain, cache.k_ret, cache.v_ret = length.data_ptr(), k_ret.data_ptr(), v_ret.data_ptr()
+    cache.k_apx, cache.W = k_apx.data_ptr(), W.data_ptr()
+    scale = 1.0 / float(np.sqrt(d))
+
+    def loop(timed: bool):
+        length.fill_(n_r)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(steps):
+            # the new token's exact key and value join the retained segment, then it attends
+            k_ret[:, :, n_r + s] = ks[s]
+            v_ret[:, :, n_r + s] = vs[s]
+            length.add_(1)
+            vb.vector_decode_attn(cache, qs[s], scale, out[s], ws)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    loop(False)                                     # warm-up
+    wall = loop(True)
+    vb.vector_timing_enable(True)
+    loop(True)
+    timing = vb.vector_timing_read()
+    vb.vector_timing_enable(False)
+    attn_us = sum(timing[k][0] for k in ("decode_split", "decode_combine")) / steps * 1e3
+    row = d * 2
+    mean_appended = (steps + 1) / 2.0
+    bytes_step = B * H * (n_p + n_r + 2 * mean_appended) * row + 2 * B * Hq * row
+    gbs = bytes_step / (attn_us * 1e-6) / 1e9
+    res = {"workload": f"cfg5: batch {B}, {Hq}/{H} heads, d={d}, {n_r} retained + {n_a} approximated per head of {n}, {steps} steps",
+           "attn_us_per_step": round(attn_us, 2), "alg_bytes_per_step": int(bytes_step), "achieved_GBs": round(gbs, 1),
+           "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+           "step_us_with_append": round(wall / steps * 1e6, 2),
+           "kernels": {k: round(timing[k][0] / max(timing[k][1], 1) * 1e3, 2) for k in ("decode_split", "decode_combine")}}
+    log(f"decode: {res}")
+    return res
+
+
+if __name__ == "__main__":
+    main()

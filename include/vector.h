@@ -158,6 +158,20 @@ typedef struct {
 VECTOR_API int vector_decode_attn(const vector_cache* cache, const void* q, float scale, void* out,
                        int32_t flags, void* ws, size_t ws_bytes, void* stream);
 
+/* ---- measurement ---------------------------------------------------------- */
+
+/* Optional per-kernel timing for benchmarks.  While enabled, every kernel launch
+ * of the library is bracketed by HIP events recorded on the launch stream
+ * (events are created on demand on the host; no device memory is involved).
+ * vector_timing_read waits for the recorded launches of one kernel, returns
+ * their summed duration in milliseconds and their count, and resets that
+ * kernel's record.  kernel_id runs from 0 to vector_timing_kernels()-1;
+ * vector_timing_name gives the kernel's name.  Single host thread only. */
+VECTOR_API int vector_timing_enable(int on);
+VECTOR_API int vector_timing_kernels(void);
+VECTOR_API const char* vector_timing_name(int kernel_id);
+VECTOR_API int vector_timing_read(int kernel_id, double* total_ms, int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

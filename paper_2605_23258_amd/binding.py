@@ -20,6 +20,7 @@ EXPORTS = (
     "vector_budget_counts", "vector_budget_counts_frac", "vector_pa_deploy", "vector_workspace_bytes",
     "vector_strerror", "vector_score", "vector_residual", "vector_score_residual", "vector_route",
     "vector_compact", "vector_decode_attn",
+    "vector_timing_enable", "vector_timing_kernels", "vector_timing_name", "vector_timing_read",
 )
 
 
@@ -75,6 +76,10 @@ def lib() -> C.CDLL:
         L.vector_route.argtypes = [i32, i32, vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
         L.vector_compact.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, i32, i32, vp, vp, vp, i32, vp]
         L.vector_decode_attn.argtypes = [C.POINTER(Cache), vp, C.c_float, vp, i32, vp, sz, vp]
+        L.vector_timing_enable.argtypes = [C.c_int]
+        L.vector_timing_name.argtypes = [C.c_int]
+        L.vector_timing_name.restype = C.c_char_p
+        L.vector_timing_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         for name in EXPORTS:
             if getattr(L, name).restype is C.c_int:
                 pass
@@ -161,3 +166,18 @@ def vector_compact(shape: Shape, k, v, idx_retain, idx_approx, n_retain: int, n_
 def vector_decode_attn(cache: Cache, q, scale: float, out, ws, flags: int = 0, stream=None) -> None:
     _check(lib().vector_decode_attn(C.byref(cache), _ptr(q), float(scale), _ptr(out), flags, _ptr(ws), _nbytes(ws),
                                     _stream(stream)), "vector_decode_attn")
+
+
+def vector_timing_enable(on: bool) -> None:
+    _check(lib().vector_timing_enable(1 if on else 0), "vector_timing_enable")
+
+
+def vector_timing_read() -> dict:
+    """{kernel name: (total milliseconds, launches)} since the last read; waits for the launches."""
+    L = lib()
+    out = {}
+    for i in range(L.vector_timing_kernels()):
+        ms, cnt = C.c_double(), C.c_int64()
+        _check(L.vector_timing_read(i, C.byref(ms), C.byref(cnt)), "vector_timing_read")
+        out[L.vector_timing_name(i).decode()] = (ms.value, cnt.value)
+    return out

@@ -297,8 +297,8 @@ int pick_splits(int batch, int n_kv_heads, int cap_retain, int n_approx) {
 
 template <typename T, int D, int G>
 int run_decode(const vector_cache& c, DecodeParams& p, hipStream_t stream) {
-  hipLaunchKernelGGL((decode_split_kernel<T, D, G>), dim3(p.n_splits, c.n_kv_heads, c.batch), dim3(DT_), 0, stream, p);
-  hipLaunchKernelGGL((decode_combine_kernel<T, D, G>), dim3(c.n_kv_heads, c.batch), dim3(256), 0, stream, p);
+  VEC_LAUNCH(K_DECODE_SPLIT, (decode_split_kernel<T, D, G>), dim3(p.n_splits, c.n_kv_heads, c.batch), dim3(DT_), 0, stream, p);
+  VEC_LAUNCH(K_DECODE_COMBINE, (decode_combine_kernel<T, D, G>), dim3(c.n_kv_heads, c.batch), dim3(256), 0, stream, p);
   VEC_HIP(hipGetLastError());
   return VECTOR_OK;
 }

@@ -22,6 +22,21 @@ inline hipError_t set_max_lds(const void* func, size_t bytes) {
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// optional per-kernel event timing (timing.hip)
+enum KernelId { K_SCORE_STATS = 0, K_STATS_COMBINE, K_MASS_RESIDUAL, K_POOL, K_ROUTE, K_GATHER, K_DECODE_SPLIT,
+                K_DECODE_COMBINE, K_COUNT };
+bool timing_enabled();
+void timing_begin(int id, hipStream_t stream);
+void timing_end(int id, hipStream_t stream);
+
+#define VEC_LAUNCH(id, kernel, grid, block, lds, stream, ...)                    \
+  do {                                                                           \
+    const bool t_ = ::vec::timing_enabled();                                     \
+    if (t_) ::vec::timing_begin(id, stream);                                     \
+    hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);           \
+    if (t_) ::vec::timing_end(id, stream);                                       \
+  } while (0)
+
 // kernel-file entry points used by the C ABI layer
 size_t score_workspace_bytes(const vector_shape& s);
 int launch_score_residual(const vector_shape& s, const void* q, const void* k, const void* v, const void* W,

@@ -214,7 +214,7 @@ int launch_route(int n_kv_heads, int seq_len, const float* score, const float* e
   int32_t* pool_idx = reinterpret_cast<int32_t*>(ws);
   uint32_t* pool_key = reinterpret_cast<uint32_t*>(reinterpret_cast<unsigned char*>(ws) +
                                                    align_up((size_t)n_kv_heads * n_pool * sizeof(int32_t), 256));
-  hipLaunchKernelGGL(route_kernel, dim3(n_kv_heads), dim3(RT), 0, stream, score, eps, seq_len, n_pool, n_approx, tier,
+  VEC_LAUNCH(K_ROUTE, route_kernel, dim3(n_kv_heads), dim3(RT), 0, stream, score, eps, seq_len, n_pool, n_approx, tier,
                      idx_retain, idx_approx, pool_idx, pool_key);
   VEC_HIP(hipGetLastError());
   return VECTOR_OK;
@@ -244,7 +244,7 @@ int launch_compact(const vector_shape& s, const void* k, const void* v, const in
   if (max_rows == 0) return VECTOR_OK;
   const int64_t threads = (int64_t)max_rows * pieces;
   dim3 grid((unsigned)((threads + 255) / 256), s.n_kv_heads, 3);
-  hipLaunchKernelGGL(gather_rows_kernel, grid, dim3(256), 0, stream, p);
+  VEC_LAUNCH(K_GATHER, gather_rows_kernel, grid, dim3(256), 0, stream, p);
   VEC_HIP(hipGetLastError());
   return VECTOR_OK;
 }

@@ -410,24 +410,24 @@ static int run_score_residual(const vector_shape& s, const void* q, const void* 
   if (do_mass) {
     auto k1 = score_stats_kernel<T, D, kThreads>;
     VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k1), plan.lds_stats));
-    hipLaunchKernelGGL(k1, grid, dim3(kThreads), plan.lds_stats, stream, p);
-    hipLaunchKernelGGL(stats_combine_kernel, dim3((p.R_pad + 127) / 128, s.n_kv_heads), dim3(128), 0, stream, p);
+    VEC_LAUNCH(K_SCORE_STATS, k1, grid, dim3(kThreads), plan.lds_stats, stream, p);
+    VEC_LAUNCH(K_STATS_COMBINE, stats_combine_kernel, dim3((p.R_pad + 127) / 128, s.n_kv_heads), dim3(128), 0, stream, p);
   }
   if (do_mass && do_res) {
     auto k2 = mass_residual_kernel<T, D, kThreads, true, true>;
     VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k2), plan.lds_pass2));
-    hipLaunchKernelGGL(k2, grid, dim3(kThreads), plan.lds_pass2, stream, p);
+    VEC_LAUNCH(K_MASS_RESIDUAL, k2, grid, dim3(kThreads), plan.lds_pass2, stream, p);
   } else if (do_mass) {
     auto k2 = mass_residual_kernel<T, D, kThreads, true, false>;
     VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k2), plan.lds_pass2));
-    hipLaunchKernelGGL(k2, grid, dim3(kThreads), plan.lds_pass2, stream, p);
+    VEC_LAUNCH(K_MASS_RESIDUAL, k2, grid, dim3(kThreads), plan.lds_pass2, stream, p);
   } else {
     auto k2 = mass_residual_kernel<T, D, kThreads, false, true>;
     VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k2), plan.lds_pass2));
-    hipLaunchKernelGGL(k2, grid, dim3(kThreads), plan.lds_pass2, stream, p);
+    VEC_LAUNCH(K_MASS_RESIDUAL, k2, grid, dim3(kThreads), plan.lds_pass2, stream, p);
   }
   if (do_mass)
-    hipLaunchKernelGGL(pool_scores_kernel, dim3((s.seq_len + 255) / 256, s.n_kv_heads), dim3(256), 0, stream,
+    VEC_LAUNCH(K_POOL, pool_scores_kernel, dim3((s.seq_len + 255) / 256, s.n_kv_heads), dim3(256), 0, stream,
                        p.mass, score, s.seq_len, p.n_prefix, s.pool_kernel);
   VEC_HIP(hipGetLastError());
   return VECTOR_OK;
