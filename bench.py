@@ -28,6 +28,16 @@ def log(msg: str) -> None:
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
+def blas_single_thread():
+    """Input generation runs one layer per worker thread: keep BLAS from oversubscribing the cores."""
+    try:
+        from threadpoolctl import threadpool_limits
+        return threadpool_limits(limits=1)
+    except Exception:
+        import contextlib
+        return contextlib.nullcontext()
+
+
 def compress_bytes_per_token_head(cfg) -> dict:
     """Algorithmic HBM bytes per token-head of each kernel of the compression pass
     (bf16, d=128): what a kernel has to read and write once, not what it re-reads."""
@@ -85,7 +95,7 @@ def main() -> None:
     def gen(layer):
         li = dg.make_layer(cfg, layer)
         return {k: getattr(li, k) for k in ("q_win", "k", "v", "w_cal")}
-    with ThreadPoolExecutor(workers) as ex:
+    with blas_single_thread(), ThreadPoolExecutor(workers) as ex:
         host_layers = list(ex.map(gen, range(cfg.layers)))
     layers = [{k: pl.to_device(v, dev) for k, v in hl.items()} for hl in host_layers]
     log(f"generated {cfg.layers} layers of K/V [{H},{n},{d}] {cfg.dtype} in {time.time() - t0:.1f}s")
@@ -196,7 +206,7 @@ def run_decode(args, vb, dg, pl, torch, np, dev, workers):
     v_ret = torch.zeros((B, H, cap, d), dtype=torch.bfloat16, device=dev)
     k_apx = torch.zeros((B, H, n_a, d), dtype=torch.bfloat16, device=dev)
     t0 = time.time()
-    with ThreadPoolExecutor(workers) as ex:
+    with blas_single_thread(), ThreadPoolExecutor(workers) as ex:
         seqs = list(ex.map(lambda b: dg.make_layer(cfg, 0, sub=b), range(B)))
     # the first sequence's map is used for every sequence: W belongs to the layer, not the sequence
     W = pl.to_device(seqs[0].w_cal, dev)

@@ -68,6 +68,21 @@ template <> __device__ __forceinline__ void mma_chunk<float>(f32x16& acc, const 
   acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
 }
 
+// acc = A * B for the first chunk of a contraction: the zero goes in as the MFMA's
+// constant C operand instead of sixteen register moves.
+template <typename T> __device__ __forceinline__ void mma_chunk_first(f32x16& acc, const chunk_t& a, const chunk_t& b);
+template <> __device__ __forceinline__ void mma_chunk_first<bf16_t>(f32x16& acc, const chunk_t& a, const chunk_t& b) {
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), zero, 0, 0, 0);
+}
+template <> __device__ __forceinline__ void mma_chunk_first<float>(f32x16& acc, const chunk_t& a, const chunk_t& b) {
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), zero, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+}
+
 // Row of the 32x32 accumulator tile that register v of this lane holds
 // (column = lane & 31).
 __device__ __forceinline__ int acc_row(int v, int lane_half) { return (v >> 2) * 8 + lane_half * 4 + (v & 3); }

@@ -7,10 +7,17 @@
 // per (sequence, KV head) in the combine step, so every cache row is read exactly once
 // and no value row is ever materialised.
 //
-//   decode_split_kernel   : grid (split, kv head, sequence); each wave walks 32-token
-//                           tiles: logits by MFMA (K tile x the G query rows of the
-//                           head), online softmax, then p . V (or p . K) on the vector
-//                           ALU with rows streamed as 16-byte pieces per lane.
+// The path is bound by HBM (about 5 flop per byte), so it is laid out for streaming, not
+// for the matrix cores: a row of the cache is read by LPR = row_bytes/16 adjacent lanes,
+// 16 bytes each, i.e. every load instruction of a wave covers 1 KiB of consecutive memory.
+//
+//   decode_split_kernel   : grid (split, kv head, sequence).  A workgroup owns a range of
+//                           rows of one segment (retained or approximated).  Each lane
+//                           group scores its row against the G query rows of the head
+//                           (partial dot product per lane, rotate-add across the group),
+//                           runs an online softmax, and accumulates p * row (the value
+//                           row for retained tokens, the key row itself for approximated
+//                           ones).  Several rows per lane group are in flight at once.
 //   decode_combine_kernel : merges the splits, applies W to z, normalises, stores.
 #include "common.hpp"
 #include "launch.hpp"
@@ -23,8 +30,9 @@ struct DecodeParams {
   const void* q; const void* k_ret; const void* v_ret; const void* k_apx; const void* W;
   const int32_t* len_retain;
   void* out;
-  float* part;            // [B, Hkv, S, 2*G + 2*G*D] floats: m[G], l[G], accV[G][D], accZ[G][D]
-  int B, Hq, Hkv, cap_retain, n_approx, n_splits;
+  float* part;            // [B, Hkv, S, 2*G + G*D] floats: m[G], l[G], acc[G][D]
+  int B, Hq, Hkv, cap_retain, n_approx;
+  int splits_ret, splits_apx;   // workgroups per (sequence, head) on each segment
   int64_t w_sh;           // element stride between per-head W
   float c2;               // scale * log2(e)
 };
@@ -32,186 +40,197 @@ struct DecodeParams {
 constexpr int DT_ = 256;          // threads per workgroup
 constexpr int DW = DT_ / kWave;   // waves
 constexpr int kMaxSplits = 64;
+constexpr int kUnroll = 4;        // rows per lane group in flight
+constexpr int kTargetWorkgroups = 768;
+
+template <typename T> struct Unpack16;
+template <> struct Unpack16<bf16_t> {
+  static __device__ __forceinline__ void run(const uint4& r, float* f) {
+    f[0] = bf16_lo(r.x); f[1] = bf16_hi(r.x); f[2] = bf16_lo(r.y); f[3] = bf16_hi(r.y);
+    f[4] = bf16_lo(r.z); f[5] = bf16_hi(r.z); f[6] = bf16_lo(r.w); f[7] = bf16_hi(r.w);
+  }
+};
+template <> struct Unpack16<float> {
+  static __device__ __forceinline__ void run(const uint4& r, float* f) {
+    f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y); f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+  }
+};
+
+// sum over the LPR adjacent lanes that share a row; every lane of the group gets the total
+template <int LPR> __device__ __forceinline__ float group_sum(float x) {
+  if constexpr (LPR == 16) {
+    // rotate-add inside a DPP row of 16 lanes: no LDS traffic
+#define VEC_ROR_ADD(n) x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x120 + (n), 0xf, 0xf, false))
+    VEC_ROR_ADD(8); VEC_ROR_ADD(4); VEC_ROR_ADD(2); VEC_ROR_ADD(1);
+#undef VEC_ROR_ADD
+    return x;
+  } else {
+#pragma unroll
+    for (int o = LPR / 2; o >= 1; o >>= 1) x += __shfl_xor(x, o, kWave);
+    return x;
+  }
+}
 
 template <typename T, int D, int G>
 __global__ __launch_bounds__(DT_) void decode_split_kernel(DecodeParams p) {
   constexpr int E = Elem<T>::kPerChunk;          // elements per 16-byte piece
-  constexpr int NC = D / (2 * E);
-  constexpr int P = D / E;                       // 16-byte pieces per row
-  constexpr int RPL = kWave / P;                 // rows covered by one wave-wide load
-  constexpr int NIT = 32 / RPL;
-  constexpr int PSZ = 2 * G + 2 * G * D;
+  constexpr int LPR = D / E;                     // lanes per row
+  constexpr int RPI = kWave / LPR;               // rows per wave-wide load instruction
+  constexpr int PSZ = 2 * G + G * D;
 
-  __shared__ float p_lds[DW][32][G];
-  __shared__ float alpha_lds[DW][G];
   __shared__ float ml_lds[DW][2][G];
-  __shared__ float red_lds[DW][2][G][D];
+  __shared__ float red_lds[DW][G][D];
 
   const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l31 = lane & 31;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int grp = lane / LPR, piece = lane % LPR;
   const int len_r = min(max(p.len_retain[b], 0), p.cap_retain);
-  const int nt_r = (len_r + 31) / 32, nt_a = (p.n_approx + 31) / 32, nt = nt_r + nt_a;
-  const int tile_begin = (int)((int64_t)nt * split / p.n_splits);
-  const int tile_end = (int)((int64_t)nt * (split + 1) / p.n_splits);
+  const bool is_apx = split >= p.splits_ret;
+  const int seg_len = is_apx ? p.n_approx : len_r;
+  const int n_sp = is_apx ? p.splits_apx : p.splits_ret;
+  const int sp = is_apx ? split - p.splits_ret : split;
+  // ranges are multiples of the workgroup's row step so that loads stay aligned to it
+  constexpr int kStepRows = DW * RPI * kUnroll;
+  const int steps = (seg_len + kStepRows - 1) / kStepRows;
+  const int row_begin = (int)((int64_t)steps * sp / n_sp) * kStepRows;
+  const int row_end = min(seg_len, (int)((int64_t)steps * (sp + 1) / n_sp) * kStepRows);
 
   const size_t bh = (size_t)b * p.Hkv + h;
-  const T* kr = reinterpret_cast<const T*>(p.k_ret) + bh * p.cap_retain * D;
-  const T* vr = reinterpret_cast<const T*>(p.v_ret) + bh * p.cap_retain * D;
-  const T* ka = reinterpret_cast<const T*>(p.k_apx) + bh * p.n_approx * D;
+  const T* kseg = is_apx ? reinterpret_cast<const T*>(p.k_apx) + bh * p.n_approx * D
+                         : reinterpret_cast<const T*>(p.k_ret) + bh * p.cap_retain * D;
+  const T* vseg = reinterpret_cast<const T*>(p.v_ret) + bh * p.cap_retain * D;
 
-  // query rows of this KV head as the N-side MFMA operand: lane (l & 31) = g < G
-  chunk_t qf[NC];
-  {
-    const T* qrow = reinterpret_cast<const T*>(p.q) + ((size_t)b * p.Hq + (size_t)h * G + min(l31, G - 1)) * D;
+  // this lane's slice of the G query rows, pre-scaled into the log2 domain
+  float qf[G][E];
 #pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      qf[c] = load_chunk(qrow + chunk_elem_offset<T>(c, half));
-      if (l31 >= G) qf[c] = make_uint4(0, 0, 0, 0);
-    }
+  for (int g = 0; g < G; ++g) {
+    const uint4 raw = load_chunk(reinterpret_cast<const T*>(p.q) + ((size_t)b * p.Hq + (size_t)h * G + g) * D + piece * E);
+    Unpack16<T>::run(raw, qf[g]);
+#pragma unroll
+    for (int e = 0; e < E; ++e) qf[g][e] *= p.c2;
   }
 
-  float m_run = -INFINITY, l_run = 0.f;         // meaningful in lanes with (l & 31) < G
-  float accV[G][E], accZ[G][E];
+  float m_run[G], l_run[G], acc[G][E];
 #pragma unroll
-  for (int g = 0; g < G; ++g)
+  for (int g = 0; g < G; ++g) {
+    m_run[g] = -INFINITY; l_run[g] = 0.f;
 #pragma unroll
-    for (int e = 0; e < E; ++e) accV[g][e] = accZ[g][e] = 0.f;
-
-  const int prow = lane / P, piece = lane % P;   // row group and 16-byte piece this lane streams
-
-  for (int tile = tile_begin + wave; tile < tile_end; tile += DW) {
-    const bool is_apx = tile >= nt_r;
-    const T* kseg = is_apx ? ka : kr;
-    const int seg_len = is_apx ? p.n_approx : len_r;
-    const int t0 = (is_apx ? tile - nt_r : tile) * 32;
-
-    // logits: rows = tokens, columns = query rows
-    f32x16 s = {0};
-    {
-      const T* krow = kseg + (size_t)min(t0 + l31, seg_len - 1) * D;
-#pragma unroll
-      for (int c = 0; c < NC; ++c) mma_chunk<T>(s, load_chunk(krow + chunk_elem_offset<T>(c, half)), qf[c]);
-    }
-    float x[16];
-    float tmax = -INFINITY;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      x[v] = (t0 + acc_row(v, half) < seg_len) ? s[v] * p.c2 : -INFINITY;
-      tmax = fmaxf(tmax, x[v]);
-    }
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
-    const float m_new = fmaxf(m_run, tmax);      // finite: every tile holds a live token
-    const float alpha = fast_exp2(m_run - m_new);
-    float psum = 0.f;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      x[v] = fast_exp2(x[v] - m_new);
-      psum += x[v];
-    }
-    psum += __shfl_xor(psum, 32, kWave);
-    l_run = l_run * alpha + psum;
-    m_run = m_new;
-    if (l31 < G) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) p_lds[wave][acc_row(v, half)][l31] = x[v];
-      if (half == 0) alpha_lds[wave][l31] = alpha;
-    }
-    // LDS operations of one wave complete in issue order: the reads below see these writes
-    __builtin_amdgcn_wave_barrier();
-
-    float al[G];
-    bool rescale = false;
-#pragma unroll
-    for (int g = 0; g < G; ++g) { al[g] = alpha_lds[wave][g]; rescale |= al[g] != 1.f; }
-    if (rescale) {
-#pragma unroll
-      for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int e = 0; e < E; ++e) { accV[g][e] *= al[g]; accZ[g][e] *= al[g]; }
-    }
-
-    // p . rows: value rows for retained tokens, key rows for approximated ones
-    const T* rseg = is_apx ? ka : vr;
-    if (is_apx) {
-#pragma unroll
-      for (int it = 0; it < NIT; ++it) {
-        const int r = it * RPL + prow;
-        const chunk_t raw = load_chunk(rseg + (size_t)min(t0 + r, seg_len - 1) * D + piece * E);
-        float pg[G];
-#pragma unroll
-        for (int g = 0; g < G; ++g) pg[g] = p_lds[wave][r][g];
-        float f[E];
-        if constexpr (E == 8) {
-          f[0] = bf16_lo(raw.x); f[1] = bf16_hi(raw.x); f[2] = bf16_lo(raw.y); f[3] = bf16_hi(raw.y);
-          f[4] = bf16_lo(raw.z); f[5] = bf16_hi(raw.z); f[6] = bf16_lo(raw.w); f[7] = bf16_hi(raw.w);
-        } else {
-          f[0] = __uint_as_float(raw.x); f[1] = __uint_as_float(raw.y); f[2] = __uint_as_float(raw.z); f[3] = __uint_as_float(raw.w);
-        }
-#pragma unroll
-        for (int g = 0; g < G; ++g)
-#pragma unroll
-          for (int e = 0; e < E; ++e) accZ[g][e] += pg[g] * f[e];
-      }
-    } else {
-#pragma unroll
-      for (int it = 0; it < NIT; ++it) {
-        const int r = it * RPL + prow;
-        const chunk_t raw = load_chunk(rseg + (size_t)min(t0 + r, seg_len - 1) * D + piece * E);
-        float pg[G];
-#pragma unroll
-        for (int g = 0; g < G; ++g) pg[g] = p_lds[wave][r][g];
-        float f[E];
-        if constexpr (E == 8) {
-          f[0] = bf16_lo(raw.x); f[1] = bf16_hi(raw.x); f[2] = bf16_lo(raw.y); f[3] = bf16_hi(raw.y);
-          f[4] = bf16_lo(raw.z); f[5] = bf16_hi(raw.z); f[6] = bf16_lo(raw.w); f[7] = bf16_hi(raw.w);
-        } else {
-          f[0] = __uint_as_float(raw.x); f[1] = __uint_as_float(raw.y); f[2] = __uint_as_float(raw.z); f[3] = __uint_as_float(raw.w);
-        }
-#pragma unroll
-        for (int g = 0; g < G; ++g)
-#pragma unroll
-          for (int e = 0; e < E; ++e) accV[g][e] += pg[g] * f[e];
-      }
-    }
-    __builtin_amdgcn_wave_barrier();             // keep the next tile's LDS writes behind these reads
+    for (int e = 0; e < E; ++e) acc[g][e] = 0.f;
   }
 
-  // ---- merge the row groups of a wave, then the waves of the workgroup ----
+  // The loop bound is the same for every lane of a wave; rows past the range are masked.
+  // The rows of the next step are requested before the current ones are consumed.
+  auto fetch = [&](uint4* kraw, uint4* vraw, int base) {
+    const int r0 = base + grp * kUnroll;
 #pragma unroll
-  for (int g = 0; g < G; ++g)
+    for (int u = 0; u < kUnroll; ++u) {
+      const int r = min(r0 + u, seg_len - 1);      // clamped: never reads past the live rows
+      kraw[u] = load_chunk(kseg + (size_t)r * D + piece * E);
+      if (!is_apx) vraw[u] = load_chunk(vseg + (size_t)r * D + piece * E);
+    }
+  };
+  auto consume = [&](const uint4* kraw, const uint4* vraw, int base) {
+    const int r0 = base + grp * kUnroll;
 #pragma unroll
-    for (int e = 0; e < E; ++e) {
+    for (int u = 0; u < kUnroll; ++u) {
+      float kf[E];
+      Unpack16<T>::run(kraw[u], kf);
+      float s[G];
 #pragma unroll
-      for (int o = P; o < kWave; o <<= 1) {
-        accV[g][e] += __shfl_xor(accV[g][e], o, kWave);
-        accZ[g][e] += __shfl_xor(accZ[g][e], o, kWave);
+      for (int g = 0; g < G; ++g) {
+        float d = 0.f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) d = fmaf(qf[g][e], kf[e], d);
+        s[g] = group_sum<LPR>(d);
+      }
+      const bool live = r0 + u < row_end;
+      bool grew = false;
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        if (!live) s[g] = -INFINITY;
+        grew |= s[g] > m_run[g];
+      }
+      if (__any(grew)) {                             // rare once the running maxima have settled
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          const float m_new = fmaxf(m_run[g], s[g]);
+          const float alpha = (m_new == -INFINITY) ? 1.f : fast_exp2(m_run[g] - m_new);
+          l_run[g] *= alpha;
+#pragma unroll
+          for (int e = 0; e < E; ++e) acc[g][e] *= alpha;
+          m_run[g] = m_new;
+        }
+      }
+      float rowf[E];
+      if (is_apx) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) rowf[e] = kf[e];
+      } else {
+        Unpack16<T>::run(vraw[u], rowf);
+      }
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float pg = (m_run[g] == -INFINITY) ? 0.f : fast_exp2(s[g] - m_run[g]);
+        l_run[g] += pg;
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc[g][e] = fmaf(pg, rowf[e], acc[g][e]);
       }
     }
-  if (lane < P) {
+  };
+  uint4 ka[kUnroll], va[kUnroll], kb[kUnroll], vb[kUnroll];
+  int base = row_begin + wave * RPI * kUnroll;
+  if (base < row_end) fetch(ka, va, base);
+  while (base < row_end) {
+    const int b1 = base + kStepRows;
+    if (b1 < row_end) fetch(kb, vb, b1);
+    consume(ka, va, base);
+    if (b1 >= row_end) break;
+    const int b2 = b1 + kStepRows;
+    if (b2 < row_end) fetch(ka, va, b2);
+    consume(kb, vb, b1);
+    base = b2;
+  }
+
+  // ---- merge the lane groups of a wave (each ran its own softmax), then the waves ----
+#pragma unroll
+  for (int o = LPR; o < kWave; o <<= 1) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const float m2 = __shfl_xor(m_run[g], o, kWave), l2 = __shfl_xor(l_run[g], o, kWave);
+      const float mn = fmaxf(m_run[g], m2);
+      const float a = (m_run[g] == -INFINITY) ? 0.f : fast_exp2(m_run[g] - mn);
+      const float c = (m2 == -INFINITY) ? 0.f : fast_exp2(m2 - mn);
+      l_run[g] = l_run[g] * a + l2 * c;
+#pragma unroll
+      for (int e = 0; e < E; ++e) acc[g][e] = acc[g][e] * a + __shfl_xor(acc[g][e], o, kWave) * c;
+      m_run[g] = mn;
+    }
+  }
+  if (lane < LPR) {
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
-      for (int e = 0; e < E; ++e) {
-        red_lds[wave][0][g][piece * E + e] = accV[g][e];
-        red_lds[wave][1][g][piece * E + e] = accZ[g][e];
-      }
+      for (int e = 0; e < E; ++e) red_lds[wave][g][piece * E + e] = acc[g][e];
   }
-  if (lane < G) { ml_lds[wave][0][lane] = m_run; ml_lds[wave][1][lane] = l_run; }
+  if (lane == 0) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) { ml_lds[wave][0][g] = m_run[g]; ml_lds[wave][1][g] = l_run[g]; }
+  }
   __syncthreads();
 
-  float* out = p.part + (bh * p.n_splits + split) * PSZ;
-  for (int i = threadIdx.x; i < 2 * G * D; i += DT_) {
-    const int set = i / (G * D), g = (i / D) % G, j = i % D;
+  float* out = p.part + (bh * (p.splits_ret + p.splits_apx) + split) * PSZ;
+  for (int i = threadIdx.x; i < G * D; i += DT_) {
+    const int g = i / D, j = i % D;
     float m = -INFINITY;
 #pragma unroll
     for (int wv = 0; wv < DW; ++wv) m = fmaxf(m, ml_lds[wv][0][g]);
-    float acc = 0.f;
+    float a = 0.f;
 #pragma unroll
     for (int wv = 0; wv < DW; ++wv) {
       const float mw = ml_lds[wv][0][g];
-      if (mw != -INFINITY) acc += red_lds[wv][set][g][j] * fast_exp2(mw - m);
+      if (mw != -INFINITY) a += red_lds[wv][g][j] * fast_exp2(mw - m);
     }
-    out[2 * G + i] = acc;
+    out[2 * G + i] = a;
   }
   if (threadIdx.x < G) {
     const int g = threadIdx.x;
@@ -230,21 +249,24 @@ __global__ __launch_bounds__(DT_) void decode_split_kernel(DecodeParams p) {
 
 template <typename T, int D, int G>
 __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeParams p) {
-  constexpr int PSZ = 2 * G + 2 * G * D;
+  constexpr int PSZ = 2 * G + G * D;
+  constexpr int kParts = 256 / D;          // thread groups sharing the contraction with W
   __shared__ float z_lds[G][D];
   __shared__ float v_lds[G][D];
-  __shared__ float scale_lds[kMaxSplits][G];   // per split: exp2(m_s - M)
+  __shared__ float zw_lds[kParts][G][D];
+  __shared__ float scale_lds[2 * kMaxSplits][G];   // per split: exp2(m_s - M)
   __shared__ float linv_lds[G];
   const int h = blockIdx.x, b = blockIdx.y;
   const size_t bh = (size_t)b * p.Hkv + h;
-  const float* part = p.part + bh * p.n_splits * PSZ;
+  const int n_splits = p.splits_ret + p.splits_apx;
+  const float* part = p.part + bh * n_splits * PSZ;
 
   if (threadIdx.x < G) {
     const int g = threadIdx.x;
     float m = -INFINITY;
-    for (int s = 0; s < p.n_splits; ++s) m = fmaxf(m, part[(size_t)s * PSZ + g]);
+    for (int s = 0; s < n_splits; ++s) m = fmaxf(m, part[(size_t)s * PSZ + g]);
     float l = 0.f;
-    for (int s = 0; s < p.n_splits; ++s) {
+    for (int s = 0; s < n_splits; ++s) {
       const float ms = part[(size_t)s * PSZ + g];
       const float sc = (ms == -INFINITY) ? 0.f : fast_exp2(ms - m);
       scale_lds[s][g] = sc;
@@ -256,48 +278,67 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeParams p) {
   for (int i = threadIdx.x; i < G * D; i += 256) {
     const int g = i / D;
     float av = 0.f, az = 0.f;
-    for (int s = 0; s < p.n_splits; ++s) {
-      const float sc = scale_lds[s][g];
-      av += part[(size_t)s * PSZ + 2 * G + i] * sc;
-      az += part[(size_t)s * PSZ + 2 * G + G * D + i] * sc;
-    }
+    for (int s = 0; s < p.splits_ret; ++s) av += part[(size_t)s * PSZ + 2 * G + i] * scale_lds[s][g];
+    for (int s = p.splits_ret; s < n_splits; ++s) az += part[(size_t)s * PSZ + 2 * G + i] * scale_lds[s][g];
     (&v_lds[0][0])[i] = av;
     (&z_lds[0][0])[i] = az;
   }
   __syncthreads();
-  // out[g][j] = (sum_ret p v  +  z[g][:] . W[:, j]) / l
+  // out[g][j] = (sum_ret p v  +  z[g][:] . W[:, j]) / l ; kParts thread groups split the
+  // contraction index between them
   const T* Wh = reinterpret_cast<const T*>(p.W) + (int64_t)h * p.w_sh;
-  T* out = reinterpret_cast<T*>(p.out) + ((size_t)b * p.Hq + (size_t)h * G) * D;
-  for (int j = threadIdx.x; j < D; j += 256 / 1) {
-    float acc[G];
+  {
+    const int j = threadIdx.x % D, part_i = threadIdx.x / D;
+    float a[G];
 #pragma unroll
-    for (int g = 0; g < G; ++g) acc[g] = v_lds[g][j];
+    for (int g = 0; g < G; ++g) a[g] = 0.f;
     if (p.n_approx > 0) {
-      for (int i = 0; i < D; ++i) {
+      const int i0 = part_i * (D / kParts);
+#pragma unroll 8
+      for (int i = i0; i < i0 + D / kParts; ++i) {
         const float wij = to_float(Wh[(size_t)i * D + j]);
 #pragma unroll
-        for (int g = 0; g < G; ++g) acc[g] += z_lds[g][i] * wij;
+        for (int g = 0; g < G; ++g) a[g] = fmaf(z_lds[g][i], wij, a[g]);
       }
     }
 #pragma unroll
-    for (int g = 0; g < G; ++g) store_elem(out + (size_t)g * D + j, acc[g] * linv_lds[g]);
+    for (int g = 0; g < G; ++g) zw_lds[part_i][g][j] = a[g];
+  }
+  __syncthreads();
+  T* out = reinterpret_cast<T*>(p.out) + ((size_t)b * p.Hq + (size_t)h * G) * D;
+  for (int i = threadIdx.x; i < G * D; i += 256) {
+    const int g = i / D, j = i % D;
+    float zw = 0.f;
+#pragma unroll
+    for (int q = 0; q < kParts; ++q) zw += zw_lds[q][g][j];
+    store_elem(out + i, (v_lds[g][j] + zw) * linv_lds[g]);
   }
 }
 
-int pick_splits(int batch, int n_kv_heads, int cap_retain, int n_approx) {
-  // enough workgroups for ~4 per CU, each with at least 4 tiles per wave; at most 64
-  const int tiles = (cap_retain + 31) / 32 + (n_approx + 31) / 32;
-  int s = (1024 + batch * n_kv_heads - 1) / (batch * n_kv_heads);
-  const int max_by_work = tiles / (4 * DW) > 1 ? tiles / (4 * DW) : 1;
-  if (s > max_by_work) s = max_by_work;
-  if (s > kMaxSplits) s = kMaxSplits;
-  if (s < 1) s = 1;
-  return s;
+void pick_splits(int batch, int n_kv_heads, int cap_retain, int n_approx, int& s_ret, int& s_apx) {
+  // One round of workgroups: 256 CUs hold three of these workgroups each, and a second,
+  // partly filled round would stream with too few loads in flight.  The splits are divided
+  // between the segments by their bytes (a retained row is a key and a value); a workgroup
+  // gets a few hundred rows at least.
+  const int pairs = batch * n_kv_heads;
+  int total = kTargetWorkgroups / pairs;
+  if (total > kMaxSplits) total = kMaxSplits;
+  if (total < 2) total = 2;
+  const double w_ret = 2.0 * cap_retain, w_apx = (double)n_approx;
+  s_ret = cap_retain > 0 ? (int)(total * w_ret / (w_ret + w_apx) + 0.5) : 0;
+  if (cap_retain > 0 && s_ret < 1) s_ret = 1;
+  s_apx = n_approx > 0 ? total - s_ret : 0;
+  if (n_approx > 0 && s_apx < 1) s_apx = 1;
+  const int max_ret = cap_retain / 256 + 1, max_apx = n_approx / 256 + 1;
+  if (s_ret > max_ret) s_ret = max_ret;
+  if (s_apx > max_apx) s_apx = max_apx;
+  if (s_ret + s_apx == 0) s_ret = 1;             // nothing cached: one workgroup writes the empty partial
 }
 
 template <typename T, int D, int G>
 int run_decode(const vector_cache& c, DecodeParams& p, hipStream_t stream) {
-  VEC_LAUNCH(K_DECODE_SPLIT, (decode_split_kernel<T, D, G>), dim3(p.n_splits, c.n_kv_heads, c.batch), dim3(DT_), 0, stream, p);
+  VEC_LAUNCH(K_DECODE_SPLIT, (decode_split_kernel<T, D, G>), dim3(p.splits_ret + p.splits_apx, c.n_kv_heads, c.batch),
+             dim3(DT_), 0, stream, p);
   VEC_LAUNCH(K_DECODE_COMBINE, (decode_combine_kernel<T, D, G>), dim3(c.n_kv_heads, c.batch), dim3(256), 0, stream, p);
   VEC_HIP(hipGetLastError());
   return VECTOR_OK;
@@ -320,7 +361,7 @@ size_t decode_workspace_bytes(int batch, int n_q_heads, int n_kv_heads, int head
   // sized for the largest split count so that the bound holds for any live length
   (void)cap_retain; (void)n_approx;
   const int G = n_q_heads / n_kv_heads;
-  return align_up((size_t)batch * n_kv_heads * kMaxSplits * (2 * G + 2 * G * head_dim) * sizeof(float), 256);
+  return align_up((size_t)batch * n_kv_heads * 2 * kMaxSplits * (2 * G + G * head_dim) * sizeof(float), 256);
 }
 
 int launch_decode_attn(const vector_cache& c, const void* q, float scale, void* out, int flags, void* ws,
@@ -330,7 +371,7 @@ int launch_decode_attn(const vector_cache& c, const void* q, float scale, void* 
   p.q = q; p.k_ret = c.k_ret; p.v_ret = c.v_ret; p.k_apx = c.k_apx; p.W = c.W; p.len_retain = c.len_retain;
   p.out = out; p.part = reinterpret_cast<float*>(ws);
   p.B = c.batch; p.Hq = c.n_q_heads; p.Hkv = c.n_kv_heads; p.cap_retain = c.cap_retain; p.n_approx = c.n_approx;
-  p.n_splits = pick_splits(c.batch, c.n_kv_heads, c.cap_retain, c.n_approx);
+  pick_splits(c.batch, c.n_kv_heads, c.cap_retain, c.n_approx, p.splits_ret, p.splits_apx);
   p.w_sh = c.w_shared ? 0 : (int64_t)c.head_dim * c.head_dim;
   p.c2 = scale * kLog2e;
   if (c.dtype == VECTOR_BF16) {

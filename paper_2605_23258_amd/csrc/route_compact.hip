@@ -1,7 +1,7 @@
 // Three-way routing (Section 3.2, Steps 1 and 3) and compaction into the packed cache.
 //
 // route_kernel: one workgroup per KV head.
-//   1. radix select (4 x 8-bit digits, LDS histograms) of the n_pool-th largest
+//   1. radix select (11+11+10-bit digits, LDS histograms) of the n_pool-th largest
 //      score key -> threshold key and the number of threshold ties to take;
 //   2. ordered prefix-sum pass over the tokens: pool membership with ties taken in
 //      ascending token index, pool list (token index, residual key) in token order;
@@ -21,6 +21,8 @@ namespace {
 constexpr int RT = 1024;          // threads per routing workgroup
 constexpr int RW = RT / kWave;    // waves
 constexpr int EPT = 4;            // consecutive elements per thread in the ordered passes
+constexpr int KC = 32;            // keys a thread can keep in registers across the radix passes
+constexpr int KB = 8;             // otherwise: keys loaded together so that their latencies overlap
 
 // Order-preserving map float -> u32 (larger float, larger key); -0 and +0 share a key.
 __device__ __forceinline__ uint32_t float_key(float x) {
@@ -28,46 +30,101 @@ __device__ __forceinline__ uint32_t float_key(float x) {
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
+constexpr int kBins = 2048;
+
 struct RouteShared {
-  int hist[256];
-  int2 wave_tot[2][RW];
+  int hist[kBins];
+  int wave_sum[RW];
+  int wave_tot[2][RW];
   int digit, above;
 };
 
+// hist[digit] += 1 for every active lane, for the leading digit.  Importance scores of
+// neighbouring tokens share their leading bits, so a plain LDS atomic would serialise up to
+// 64 lanes on one bin: lanes that agree with a leader are counted with one ballot and added
+// by the leader alone; after two rounds the stragglers (few, spread over bins) add themselves.
+__device__ __forceinline__ void hist_add_aggregated(int* hist, uint32_t digit, bool active, int lane) {
+  unsigned long long todo = __ballot(active);
+#pragma unroll
+  for (int round = 0; round < 2; ++round) {
+    if (todo == 0) return;
+    const int leader = __ffsll((long long)todo) - 1;
+    const uint32_t d = __builtin_amdgcn_readlane(digit, leader);
+    const bool match = active && digit == d;
+    const unsigned long long m = __ballot(match);
+    if (lane == leader) atomicAdd(&hist[d], __popcll(m));
+    active = active && !match;
+    todo &= ~m;
+  }
+  if (active) atomicAdd(&hist[digit], 1);
+}
+
 // k-th largest key among keyf(0..m-1), 1 <= k <= m.  Returns the key value and how many
-// elements equal to it belong to the k largest.
+// elements equal to it belong to the k largest.  Three passes of LDS histograms.
 template <typename KeyFn>
 __device__ void radix_select_desc(KeyFn keyf, int m, int k, RouteShared& sh, uint32_t& thr, int& quota) {
   uint32_t prefix = 0, mask = 0;
   int remaining = k;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  for (int shift = 24; shift >= 0; shift -= 8) {
-    if (threadIdx.x < 256) sh.hist[threadIdx.x] = 0;
-    __syncthreads();
-    for (int i = threadIdx.x; i < m; i += RT) {
-      uint32_t key = keyf(i);
-      if ((key & mask) == prefix) atomicAdd(&sh.hist[(key >> shift) & 255u], 1);
+  const bool cached = m <= RT * KC;                 // keys stay in registers across the passes
+  uint32_t kreg[KC];
+  if (cached) {
+#pragma unroll
+    for (int j = 0; j < KC; ++j) {
+      const int i = j * RT + threadIdx.x;
+      kreg[j] = (i < m) ? keyf(i) : 0u;
     }
+  }
+  int shift = 32;
+#pragma unroll 1
+  for (int pass = 0; pass < 3; ++pass) {
+    const int bits = pass == 2 ? 10 : 11;           // digits of 11, 11 and 10 bits, most significant first
+    const uint32_t dmask = (1u << bits) - 1u;
+    shift -= bits;
+    for (int i = threadIdx.x; i < kBins; i += RT) sh.hist[i] = 0;
     __syncthreads();
-    if (wave == 0) {
-      // lane l owns digits 255-4l .. 252-4l, i.e. lanes walk the digits downwards
-      const int base = 255 - 4 * lane;
-      const int c0 = sh.hist[base], c1 = sh.hist[base - 1], c2 = sh.hist[base - 2], c3 = sh.hist[base - 3];
-      const int tot = c0 + c1 + c2 + c3;
-      const int incl = wave_incl_scan_i(tot, lane);
-      int above = incl - tot;               // candidates with a larger digit than `base`
-      if (above < remaining && remaining <= incl) {
-        int d = base;
-        if (remaining > above + c0) { above += c0; d = base - 1;
-          if (remaining > above + c1) { above += c1; d = base - 2;
-            if (remaining > above + c2) { above += c2; d = base - 3; } } }
-        sh.digit = d;
-        sh.above = above;
+    auto add = [&](uint32_t key, bool in) {
+      const uint32_t digit = (key >> shift) & dmask;
+      const bool active = in && (key & mask) == prefix;
+      if (pass == 0) hist_add_aggregated(sh.hist, digit, active, lane);
+      else if (active) atomicAdd(&sh.hist[digit], 1);      // later digits are spread: few conflicts
+    };
+    if (cached) {
+#pragma unroll
+      for (int j = 0; j < KC; ++j)
+        if (j * RT < m) add(kreg[j], j * RT + threadIdx.x < m);        // uniform guard: whole waves take part
+    } else {
+      for (int base = 0; base < m; base += RT * KB) {
+        uint32_t key[KB];
+#pragma unroll
+        for (int j = 0; j < KB; ++j) {
+          const int i = base + j * RT + threadIdx.x;
+          key[j] = (i < m) ? keyf(i) : 0u;
+        }
+#pragma unroll
+        for (int j = 0; j < KB; ++j) add(key[j], base + j * RT + threadIdx.x < m);
       }
     }
     __syncthreads();
+    // Thread t owns bins 2047-2t and 2046-2t, so thread order walks the digits downwards.
+    // Find the digit d with  #(digit > d) < remaining <= #(digit >= d).
+    const int b_hi = kBins - 1 - 2 * threadIdx.x;
+    const int c0 = sh.hist[b_hi], c1 = sh.hist[b_hi - 1];
+    const int tot = c0 + c1;
+    const int incl_w = wave_incl_scan_i(tot, lane);
+    if (lane == 63) sh.wave_sum[wave] = incl_w;
+    __syncthreads();
+    int above = incl_w - tot;
+    for (int wv = 0; wv < wave; ++wv) above += sh.wave_sum[wv];
+    if (above < remaining && remaining <= above + tot) {
+      int d = b_hi;
+      if (remaining > above + c0) { above += c0; d = b_hi - 1; }
+      sh.digit = d;
+      sh.above = above;
+    }
+    __syncthreads();
     prefix |= ((uint32_t)sh.digit) << shift;
-    mask |= 255u << shift;
+    mask |= dmask << shift;
     remaining -= sh.above;
   }
   thr = prefix;
@@ -78,30 +135,41 @@ __device__ void radix_select_desc(KeyFn keyf, int m, int k, RouteShared& sh, uin
 // Ordered pass over m elements in index order.  classify(i) returns 2 for "strictly
 // selected", 1 for "threshold tie", 0 otherwise; emit(i, selected, rank_selected) is
 // called for every element with its rank among the selected ones.  Ties are selected
-// while fewer than `quota` earlier ties exist.
+// while fewer than `quota` earlier ties exist.  One tile is RT*EPT elements; the two
+// counts of a thread (each <= EPT) travel through one scan packed as (gt << 16) | eq.
 template <typename ClassFn, typename EmitFn>
 __device__ void ordered_select(ClassFn classify, EmitFn emit, int m, int quota, RouteShared& sh) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int carry_gt = 0, carry_eq = 0, buf = 0;
+  int cls[EPT], next_cls[EPT];
+#pragma unroll
+  for (int j = 0; j < EPT; ++j) {
+    const int i = threadIdx.x * EPT + j;
+    cls[j] = (i < m) ? classify(i) : 0;
+  }
   for (int base = 0; base < m; base += RT * EPT) {
     const int i0 = base + threadIdx.x * EPT;
-    int cls[EPT], gt = 0, eq = 0;
+    // the next tile's keys are requested before this tile's scan and barrier
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
-      cls[j] = (i0 + j < m) ? classify(i0 + j) : 0;
-      gt += cls[j] == 2;
-      eq += cls[j] == 1;
+      const int i = i0 + RT * EPT + j;
+      next_cls[j] = (i < m) ? classify(i) : 0;
     }
-    const int incl_gt = wave_incl_scan_i(gt, lane), incl_eq = wave_incl_scan_i(eq, lane);
-    if (lane == 63) sh.wave_tot[buf][wave] = make_int2(incl_gt, incl_eq);
+    int packed = 0;
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) packed += (cls[j] == 2 ? 0x10000 : 0) + (cls[j] == 1 ? 1 : 0);
+    const int incl = wave_incl_scan_i(packed, lane);
+    if (lane == 63) sh.wave_tot[buf][wave] = incl;
     __syncthreads();
-    int pre_gt = carry_gt + incl_gt - gt, pre_eq = carry_eq + incl_eq - eq;
+    int pre = incl - packed, tile_tot = 0;
     for (int wv = 0; wv < RW; ++wv) {
-      int2 t = sh.wave_tot[buf][wv];
-      if (wv < wave) { pre_gt += t.x; pre_eq += t.y; }
-      carry_gt += t.x;
-      carry_eq += t.y;
+      const int t = sh.wave_tot[buf][wv];
+      if (wv < wave) pre += t;
+      tile_tot += t;
     }
+    int pre_gt = carry_gt + (pre >> 16), pre_eq = carry_eq + (pre & 0xffff);
+    carry_gt += tile_tot >> 16;
+    carry_eq += tile_tot & 0xffff;
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
       if (i0 + j < m) {
@@ -111,6 +179,8 @@ __device__ void ordered_select(ClassFn classify, EmitFn emit, int m, int quota, 
         pre_eq += cls[j] == 1;
       }
     }
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) cls[j] = next_cls[j];
     buf ^= 1;
   }
 }
@@ -143,10 +213,7 @@ __global__ __launch_bounds__(RT) void route_kernel(const float* __restrict__ sco
       [&](int i) { uint32_t key = float_key(sc[i]); return key > thr ? 2 : (key == thr ? 1 : 0); },
       [&](int i, bool sel, int rank) {
         tr[i] = sel ? VECTOR_TIER_RETAIN : VECTOR_TIER_EVICT;
-        if (sel && rank < n_pool) {          // rank < n_pool by construction; never write past the list
-          pidx[rank] = i;
-          pkey[rank] = ~float_key(ep[i]);      // smaller residual, larger key
-        }
+        if (sel && rank < n_pool) pidx[rank] = i;     // rank < n_pool by construction; never write past the list
       },
       n, quota, sh);
   __threadfence();
@@ -157,6 +224,25 @@ __global__ __launch_bounds__(RT) void route_kernel(const float* __restrict__ sco
     for (int i = threadIdx.x; i < n_pool; i += RT) ir[i] = pidx[i];
     return;
   }
+  // residual keys of the pool members, gathered in batches; smaller residual, larger key
+  for (int base = 0; base < n_pool; base += RT * KB) {
+    int tok[KB];
+#pragma unroll
+    for (int j = 0; j < KB; ++j) {
+      const int i = base + j * RT + threadIdx.x;
+      tok[j] = (i < n_pool) ? pidx[i] : 0;
+    }
+    float e[KB];
+#pragma unroll
+    for (int j = 0; j < KB; ++j) e[j] = ep[min(max(tok[j], 0), n - 1)];
+#pragma unroll
+    for (int j = 0; j < KB; ++j) {
+      const int i = base + j * RT + threadIdx.x;
+      if (i < n_pool) pkey[i] = ~float_key(e[j]);
+    }
+  }
+  __threadfence();
+  __syncthreads();
   radix_select_desc([&](int i) { return pkey[i]; }, n_pool, n_approx, sh, thr, quota);
   ordered_select(
       [&](int i) { uint32_t key = pkey[i]; return key > thr ? 2 : (key == thr ? 1 : 0); },

@@ -4,19 +4,27 @@
 //
 // Data flow per KV head h (R = G*w query rows share the head's keys):
 //   pass 1  score_stats   : S = Q_h K_h^T (MFMA), per-row running max / sum-exp
-//                           over a chunk of tokens -> partial (m, l) per chunk
-//   combine stats_combine : merge the chunks -> one bias per row,
-//                           bias_r = log2-domain max + log2(sum-exp)
-//   pass 2  mass_residual : S again, p = exp2(S*c - bias_r), column mean -> mass;
-//                           fused on the same K registers: v_hat = K W (MFMA),
+//                           over a chunk of tokens -> partial (m, l) per (row, chunk)
+//   pass 2  mass_residual : prologue merges the chunk partials into one bias per row,
+//                           bias_r = log2-domain max + log2(sum-exp); then S again,
+//                           p = exp2(S*c - bias_r), column mean -> mass; fused on the
+//                           same K registers: v_hat^T = W^T K^T (MFMA),
 //                           eps = sum_j (v - v_hat)^2
 //   pool    pool_scores   : average pooling of mass over prefix columns, +inf on
 //                           the window columns
 //
-// K rows go straight from HBM into MFMA operand registers (16 bytes per lane);
-// Q_h, W_h^T and the row biases live in LDS for the life of a workgroup.
+// K rows go straight from HBM into MFMA operand registers (16 bytes per lane); the next
+// tile's rows are requested as soon as the last MFMA of the current tile has been issued.
+// Q_h, W_h^T and the row biases live in LDS for the life of a workgroup.  Inside a tile the
+// MFMAs of row block i+1 are issued before the exponentials of row block i, interleaved
+// instruction by instruction, so that the matrix pipe and the vector ALU run together.
 #include "common.hpp"
 #include "launch.hpp"
+
+#ifndef VEC_P1_THREADS
+#define VEC_P1_THREADS 1024
+#define VEC_P1_SUBTILES 1
+#endif
 
 namespace vec {
 
@@ -30,10 +38,10 @@ struct PassParams {
   int64_t k_sh, k_st, v_sh, v_st, w_sh;   // element strides
   int n, w, R, R_pad, n_prefix;
   int tokens_per_chunk, n_chunks;
+  int threads_per_row;  // pass-2 prologue: lanes that share the merge of one row's partials
   float c2;             // log2(e) / sqrt(d)
   float inv_R;
-  float2* part;         // [Hkv, n_chunks, R_pad]  (max, sum-exp), log2 domain
-  float* bias;          // [Hkv, R_pad]
+  float2* part;         // [Hkv, R_pad, n_chunks]  (max, sum-exp), log2 domain
   float* mass;          // [Hkv, n]
   float* eps;           // [Hkv, n]
 };
@@ -43,19 +51,40 @@ template <typename T, int D> struct Tile {
   static constexpr int NC = D / (2 * E);            // chunks per row
   static constexpr int kRowBytes = D * (int)sizeof(T);
   static constexpr int kLdsStride = kRowBytes + 16;  // pad: conflict-free 16-byte reads down a column of rows
-  static constexpr int JB = D / 32;                  // 32-column blocks of the K W product
+  static constexpr int JB = D / 32;                  // 32-row blocks of the W^T K^T product
+  static constexpr int VP = (D / 2) / E;             // 16-byte pieces of half a value row
+  static constexpr int kMfmaPerChunk = (sizeof(T) == 2) ? 1 : 4;   // MFMA instructions per operand chunk
 };
 
 // Copy `rows` rows of D elements from global to LDS with the padded stride;
-// rows in [rows, rows_pad) are zero-filled.
+// rows in [rows, rows_pad) are zero-filled.  Loads go out eight at a time per thread so
+// that their latencies overlap, and each workgroup starts at a different row (`rot`) so
+// that the workgroups of one head, which all read the same rows at the same moment, do
+// not queue up on the same cache lines.
 template <typename T, int D, int NT>
-__device__ __forceinline__ void fill_rows_lds(unsigned char* lds, const T* src, int rows, int rows_pad) {
+__device__ __forceinline__ void fill_rows_lds(unsigned char* lds, const T* src, int rows, int rows_pad, int rot) {
   constexpr int P = Tile<T, D>::kRowBytes / 16;
-  for (int i = threadIdx.x; i < rows_pad * P; i += NT) {
-    int row = i / P, piece = i - row * P;
-    uint4 x = make_uint4(0, 0, 0, 0);
-    if (row < rows) x = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(src) + (size_t)row * Tile<T, D>::kRowBytes + piece * 16);
-    *reinterpret_cast<uint4*>(lds + row * Tile<T, D>::kLdsStride + piece * 16) = x;
+  constexpr int U = 8;
+  const int total = rows_pad * P;
+  const int shift = (rot % rows_pad) * P;
+  for (int base = threadIdx.x; base < total; base += NT * U) {
+    uint4 x[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int i = base + u * NT + shift;
+      if (i >= total) i -= total;
+      const int row = i / P, piece = i - row * P;
+      x[u] = make_uint4(0, 0, 0, 0);
+      if (base + u * NT < total && row < rows)
+        x[u] = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(src) + (size_t)row * Tile<T, D>::kRowBytes + piece * 16);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int i = base + u * NT + shift;
+      if (i >= total) i -= total;
+      const int row = i / P, piece = i - row * P;
+      if (base + u * NT < total) *reinterpret_cast<uint4*>(lds + row * Tile<T, D>::kLdsStride + piece * 16) = x[u];
+    }
   }
 }
 
@@ -73,13 +102,23 @@ __device__ __forceinline__ void load_k_subtile(chunk_t* kf, const T* k_head, int
   for (int c = 0; c < Tile<T, D>::NC; ++c) kf[c] = load_chunk(row + chunk_elem_offset<T>(c, lane >> 5));
 }
 
+__device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+
+// Pure arithmetic has no position of its own in the instruction stream: the compiler
+// would issue a block's MFMAs back to back and its exponentials after them.  An empty
+// volatile asm that "uses" an accumulator and the running sum ties both chains to this
+// point, so what is written between two pins is also issued between them.
+#define VEC_PIN(acc, x) asm volatile("" : "+v"(acc), "+v"(x))
+#define VEC_PIN3(acc, x, y) asm volatile("" : "+v"(acc), "+v"(x), "+v"(y))
+
 // ---------------------------------------------------------------------------
 // pass 1: per-row softmax statistics over a chunk of tokens
 // ---------------------------------------------------------------------------
-template <typename T, int D, int NT>
+template <typename T, int D, int NT, int NS>     // NS subtiles of 32 tokens per wave tile
 __global__ __launch_bounds__(NT) void score_stats_kernel(PassParams p) {
   using TL = Tile<T, D>;
   constexpr int NW = NT / kWave;
+  constexpr int TW = 32 * NS;                    // tokens per wave tile
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* q_lds = smem;
   float2* st_lds = reinterpret_cast<float2*>(smem + (size_t)p.R_pad * TL::kLdsStride);   // [NW][NRB][64]
@@ -88,60 +127,137 @@ __global__ __launch_bounds__(NT) void score_stats_kernel(PassParams p) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l31 = lane & 31;
   const int nrb = p.R_pad / 32;
 
-  fill_rows_lds<T, D, NT>(q_lds, reinterpret_cast<const T*>(p.q) + (size_t)h * p.R * D, p.R, p.R_pad);
-  for (int i = threadIdx.x; i < NW * nrb * 64; i += NT) st_lds[i] = make_float2(-INFINITY, 0.f);
-  __syncthreads();
-
   const T* k_head = reinterpret_cast<const T*>(p.k) + (int64_t)h * p.k_sh;
   const int c_begin = chunk * p.tokens_per_chunk;
   const int c_end = min(p.n, c_begin + p.tokens_per_chunk);
+  constexpr int kStep = NW * TW;
+
+  chunk_t kf[NS][TL::NC];
+  auto load_keys = [&](int t) {
+#pragma unroll
+    for (int sI = 0; sI < NS; ++sI) load_k_subtile<T, D>(kf[sI], k_head, p.k_st, t + 32 * sI, p.n, lane);
+  };
+  int t0 = c_begin + wave * TW;
+  if (t0 < c_end) load_keys(t0);          // first tile's keys fly while Q is staged
+  fill_rows_lds<T, D, NT>(q_lds, reinterpret_cast<const T*>(p.q) + (size_t)h * p.R * D, p.R, p.R_pad, chunk * 8);
+  for (int i = threadIdx.x; i < NW * nrb * 64; i += NT) st_lds[i] = make_float2(-INFINITY, 0.f);
+  __syncthreads();
+
   float2* my_st = st_lds + (size_t)wave * nrb * 64 + lane;
 
-  for (int t0 = c_begin + wave * 64; t0 < c_end; t0 += NW * 64) {
-    chunk_t kf0[TL::NC], kf1[TL::NC];
-    load_k_subtile<T, D>(kf0, k_head, p.k_st, t0, p.n, lane);
-    load_k_subtile<T, D>(kf1, k_head, p.k_st, t0 + 32, p.n, lane);
-    // a tile needs masking if it reaches past the first window position or past the chunk
-    const bool tail = (t0 + 64 > p.n_prefix + 1) || (t0 + 64 > c_end);
-    for (int rb = 0; rb < nrb; ++rb) {
-      f32x16 a0 = {0}, a1 = {0};
+  // logits of one row block against the wave's subtiles: rows = tokens, columns = query rows
+  auto mma_rb = [&](f32x16 (&x)[NS], int rb) {
 #pragma unroll
-      for (int c = 0; c < TL::NC; ++c) {
-        chunk_t qf = lds_chunk<T, D>(q_lds, rb * 32 + l31, c, half);
-        mma_chunk<T>(a0, kf0[c], qf);     // rows = tokens, columns = query rows
-        mma_chunk<T>(a1, kf1[c], qf);
+    for (int c = 0; c < TL::NC; ++c) {
+      chunk_t qf = lds_chunk<T, D>(q_lds, rb * 32 + l31, c, half);
+#pragma unroll
+      for (int sI = 0; sI < NS; ++sI) {
+        if (c == 0) mma_chunk_first<T>(x[sI], kf[sI][c], qf);
+        else mma_chunk<T>(x[sI], kf[sI][c], qf);
       }
-      float x0[16], x1[16];
+    }
+  };
+  auto tile_max = [&](const f32x16 (&x)[NS]) {     // short independent chains, not one long one
+    float m = -INFINITY;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) { x0[v] = a0[v] * p.c2; x1[v] = a1[v] * p.c2; }
-      if (tail) {
+    for (int sI = 0; sI < NS; ++sI) {
+      float m0 = max3(x[sI][0], x[sI][1], x[sI][2]), m1 = max3(x[sI][8], x[sI][9], x[sI][10]);
+      m0 = max3(m0, x[sI][3], x[sI][4]); m1 = max3(m1, x[sI][11], x[sI][12]);
+      m0 = max3(m0, x[sI][5], x[sI][6]); m1 = max3(m1, x[sI][13], x[sI][14]);
+      m = max3(m, fmaxf(m0, x[sI][7]), fmaxf(m1, x[sI][15]));
+    }
+    return m * p.c2;                              // c2 > 0: scaling commutes with max
+  };
+  // fold the lane's logits of one row block into the running (max, sum-exp) of its query row
+  auto stats_rb = [&](const f32x16 (&x)[NS], int rb) {
+    const float tmax = tile_max(x);
+    float2 st = my_st[rb * 64];
+    const float m_new = fmaxf(st.x, tmax);
+    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+    float sum[2] = {0.f, 0.f};
+#pragma unroll
+    for (int sI = 0; sI < NS; ++sI)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sum[(sI + v) & 1] += fast_exp2(fmaf(x[sI][v], p.c2, -m_safe));
+    st.y = st.y * fast_exp2(st.x - m_safe) + (sum[0] + sum[1]);
+    st.x = m_new;
+    my_st[rb * 64] = st;
+  };
+  // One pipelined step: the MFMAs of row block rb_n go out one at a time, each followed by
+  // the exponentials of a few logits of row block rb_c, so that the matrix pipe works while
+  // the vector ALU does.
+  auto step = [&](f32x16 (&nx)[NS], int rb_n, const f32x16 (&cu)[NS], int rb_c) {
+    const float tmax = tile_max(cu);
+    float2 st = my_st[rb_c * 64];
+    const float m_new = fmaxf(st.x, tmax);
+    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+    float sum0 = 0.f, sum1 = 0.f;
+    chunk_t qf = lds_chunk<T, D>(q_lds, rb_n * 32 + l31, 0, half);
+#pragma unroll
+    for (int c = 0; c < TL::NC; ++c) {
+      const chunk_t q_now = qf;
+      if (c + 1 < TL::NC) qf = lds_chunk<T, D>(q_lds, rb_n * 32 + l31, c + 1, half);
+#pragma unroll
+      for (int sI = 0; sI < NS; ++sI) {
+        constexpr int kSlots = TL::NC * NS;
+        const int slot = c * NS + sI;
+        if (c == 0) mma_chunk_first<T>(nx[sI], kf[sI][c], q_now);
+        else mma_chunk<T>(nx[sI], kf[sI][c], q_now);
+#pragma unroll
+        for (int v = slot * 16 / kSlots; v < (slot + 1) * 16 / kSlots; ++v)
+#pragma unroll
+          for (int s2 = 0; s2 < NS; ++s2) {
+            const float e = fast_exp2(fmaf(cu[s2][v], p.c2, -m_safe));
+            if ((s2 + v) & 1) sum1 += e; else sum0 += e;
+          }
+        VEC_PIN3(nx[sI], sum0, sum1);
+      }
+    }
+    st.y = st.y * fast_exp2(st.x - m_safe) + (sum0 + sum1);
+    st.x = m_new;
+    my_st[rb_c * 64] = st;
+  };
+
+  while (t0 < c_end) {
+    const int tn = t0 + kStep;
+    // a tile needs masking if it reaches past the first window position or past the chunk
+    const bool tail = (t0 + TW > p.n_prefix + 1) || (t0 + TW > c_end);
+    f32x16 A[NS], B[NS];
+    if (!tail) {
+      mma_rb(A, 0);
+      int rb = 0;
+      for (; rb + 2 < nrb; rb += 2) {
+        step(B, rb + 1, A, rb);
+        step(A, rb + 2, B, rb + 1);
+      }
+      if (rb + 1 < nrb) {
+        step(B, rb + 1, A, rb);
+        if (tn < c_end) load_keys(tn);     // every MFMA of the tile is issued: fetch the next keys
+        stats_rb(B, rb + 1);
+      } else {
+        if (tn < c_end) load_keys(tn);
+        stats_rb(A, rb);
+      }
+    } else {
+      for (int rb = 0; rb < nrb; ++rb) {
+        mma_rb(A, rb);
         // query row (g, r) sits at position n - w + r and sees tokens <= that
         const int qrow = rb * 32 + l31;
         const int last = (qrow < p.R) ? min(p.n_prefix + (qrow % p.w), c_end - 1) : c_end - 1;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          int t = t0 + acc_row(v, half);
-          if (t > last) x0[v] = -INFINITY;
-          if (t + 32 > last) x1[v] = -INFINITY;
-        }
+        for (int sI = 0; sI < NS; ++sI)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            if (t0 + 32 * sI + acc_row(v, half) > last) A[sI][v] = -INFINITY;
+        stats_rb(A, rb);
       }
-      float tmax = fmaxf(x0[0], x1[0]);
-#pragma unroll
-      for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, fmaxf(x0[v], x1[v]));
-      float2 st = my_st[rb * 64];
-      const float m_new = fmaxf(st.x, tmax);
-      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-      float sum = 0.f;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) sum += fast_exp2(x0[v] - m_safe) + fast_exp2(x1[v] - m_safe);
-      st.y = st.y * fast_exp2(st.x - m_safe) + sum;
-      st.x = m_new;
-      my_st[rb * 64] = st;
+      if (tn < c_end) load_keys(tn);
     }
+    t0 = tn;
   }
   __syncthreads();
   // merge the NW waves x 2 lane halves that saw different tokens of the same query row
-  float2* out = p.part + ((size_t)h * p.n_chunks + chunk) * p.R_pad;
+  float2* out = p.part + (size_t)h * p.R_pad * p.n_chunks + chunk;
   for (int row = threadIdx.x; row < p.R_pad; row += NT) {
     const int rb = row >> 5, c = row & 31;
     float m = -INFINITY;
@@ -154,57 +270,42 @@ __global__ __launch_bounds__(NT) void score_stats_kernel(PassParams p) {
         float2 s = st_lds[((size_t)wv * nrb + rb) * 64 + hf * 32 + c];
         l += s.y * fast_exp2(s.x - m_safe);
       }
-    out[row] = make_float2(m, l);
+    out[(size_t)row * p.n_chunks] = make_float2(m, l);
   }
-}
-
-// merge chunk partials into one bias per query row
-__global__ void stats_combine_kernel(PassParams p) {
-  const int h = blockIdx.y;
-  const int row = blockIdx.x * blockDim.x + threadIdx.x;
-  if (row >= p.R_pad) return;
-  const float2* part = p.part + (size_t)h * p.n_chunks * p.R_pad + row;
-  float m = -INFINITY;
-  for (int c = 0; c < p.n_chunks; ++c) m = fmaxf(m, part[(size_t)c * p.R_pad].x);
-  float l = 0.f;
-  for (int c = 0; c < p.n_chunks; ++c) {
-    float2 s = part[(size_t)c * p.R_pad];
-    l += s.y * fast_exp2(s.x - m);
-  }
-  // padded rows get +inf so that they add exp2(-inf) = 0 to every column
-  p.bias[(size_t)h * p.R_pad + row] = (row < p.R) ? m + __builtin_amdgcn_logf(l) : INFINITY;
 }
 
 // ---------------------------------------------------------------------------
 // pass 2: column mass of the normalised probabilities, and/or the residual
 // ---------------------------------------------------------------------------
-// Raw bits of the JB consecutive value elements a lane compares against its accumulator
-// column block; element i is extracted by shifting so that i may be a run-time value.
-template <int BYTES> struct RawVec;
-template <> struct RawVec<4>  { uint32_t x; };
-template <> struct RawVec<8>  { uint64_t x; };
-template <> struct RawVec<16> { uint64_t lo, hi; };
-template <int BYTES> __device__ __forceinline__ RawVec<BYTES> load_raw(const void* p);
-template <> __device__ __forceinline__ RawVec<4> load_raw<4>(const void* p) { return RawVec<4>{*reinterpret_cast<const uint32_t*>(p)}; }
-template <> __device__ __forceinline__ RawVec<8> load_raw<8>(const void* p) { return RawVec<8>{*reinterpret_cast<const uint64_t*>(p)}; }
-template <> __device__ __forceinline__ RawVec<16> load_raw<16>(const void* p) {
-  uint4 x = *reinterpret_cast<const uint4*>(p);
-  return RawVec<16>{((uint64_t)x.y << 32) | x.x, ((uint64_t)x.w << 32) | x.z};
+template <typename T> struct Unpack;
+template <> struct Unpack<bf16_t> {   // 16 bytes -> 8 floats
+  static __device__ __forceinline__ void run(const uint4& r, float* f) {
+    f[0] = bf16_lo(r.x); f[1] = bf16_hi(r.x); f[2] = bf16_lo(r.y); f[3] = bf16_hi(r.y);
+    f[4] = bf16_lo(r.z); f[5] = bf16_hi(r.z); f[6] = bf16_lo(r.w); f[7] = bf16_hi(r.w);
+  }
+};
+template <> struct Unpack<float> {    // 16 bytes -> 4 floats
+  static __device__ __forceinline__ void run(const uint4& r, float* f) {
+    f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y); f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+  }
+};
+
+// Value registers of a 32-token subtile: lane (token l & 31, half l >> 5) holds the
+// contiguous half row v[token][half*D/2, +D/2) as VP pieces of 16 bytes.
+template <typename T, int D>
+__device__ __forceinline__ void load_v_subtile(chunk_t* vf, const T* v_head, int64_t v_st, int t0, int n, int lane) {
+  int t = min(t0 + (lane & 31), n - 1);
+  const T* row = v_head + (int64_t)t * v_st + (lane >> 5) * (D / 2);
+#pragma unroll
+  for (int i = 0; i < Tile<T, D>::VP; ++i) vf[i] = load_chunk(row + i * Tile<T, D>::E);
 }
-template <typename T, int BYTES> __device__ __forceinline__ float raw_elem(const RawVec<BYTES>& r, int i);
-template <> __device__ __forceinline__ float raw_elem<float, 8>(const RawVec<8>& r, int i) { return __uint_as_float((uint32_t)(r.x >> (32 * i))); }
-template <> __device__ __forceinline__ float raw_elem<float, 16>(const RawVec<16>& r, int i) {
-  uint64_t y = (i & 2) ? r.hi : r.lo;
-  return __uint_as_float((uint32_t)(y >> (32 * (i & 1))));
-}
-template <> __device__ __forceinline__ float raw_elem<bf16_t, 4>(const RawVec<4>& r, int i) { return __uint_as_float((r.x >> (16 * i)) << 16); }
-template <> __device__ __forceinline__ float raw_elem<bf16_t, 8>(const RawVec<8>& r, int i) { return __uint_as_float(((uint32_t)(r.x >> (16 * i))) << 16); }
 
 template <typename T, int D, int NT, bool DO_MASS, bool DO_RES>
 __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p) {
   using TL = Tile<T, D>;
   constexpr int NW = NT / kWave;
   constexpr int JB = TL::JB;
+  constexpr int E = TL::E;
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* q_lds = smem;                                               // DO_MASS: [R_pad] rows
   size_t off = DO_MASS ? (size_t)p.R_pad * TL::kLdsStride : 0;
@@ -216,104 +317,250 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l31 = lane & 31;
   const int nrb = p.R_pad / 32;
 
-  if (DO_MASS) {
-    fill_rows_lds<T, D, NT>(q_lds, reinterpret_cast<const T*>(p.q) + (size_t)h * p.R * D, p.R, p.R_pad);
-    for (int i = threadIdx.x; i < p.R_pad; i += NT) bias_lds[i] = p.bias[(size_t)h * p.R_pad + i];
-  }
-  if (DO_RES) {
-    // W^T into LDS: output column j = nn*JB + jb is stored as physical row jb*32 + nn, so
-    // that the 32 lanes of an MFMA operand read 32 consecutive padded rows.
-    const T* Wh = reinterpret_cast<const T*>(p.W) + (int64_t)h * p.w_sh;
-    for (int i = threadIdx.x; i < D * D; i += NT) {
-      int din = i / D, j = i - din * D;
-      int prow = (j % JB) * 32 + j / JB;
-      *reinterpret_cast<T*>(wt_lds + prow * TL::kLdsStride + din * (int)sizeof(T)) = Wh[i];
-    }
-  }
-  __syncthreads();
-
   const T* k_head = reinterpret_cast<const T*>(p.k) + (int64_t)h * p.k_sh;
   const T* v_head = DO_RES ? reinterpret_cast<const T*>(p.v) + (int64_t)h * p.v_sh : nullptr;
   const int c_begin = chunk * p.tokens_per_chunk;
   const int c_end = min(p.n, c_begin + p.tokens_per_chunk);
   // the mass of window columns is never used: stop the score part at the prefix
   const int mass_end = min(c_end, p.n_prefix);
+  constexpr int kStep = NW * 64;
 
-  for (int t0 = c_begin + wave * 64; t0 < c_end; t0 += NW * 64) {
-    chunk_t kf0[TL::NC], kf1[TL::NC];
+  chunk_t kf0[TL::NC], kf1[TL::NC];
+  int t0 = c_begin + wave * 64;
+  if (t0 < c_end) {                       // first tile's keys fly during the prologue
     load_k_subtile<T, D>(kf0, k_head, p.k_st, t0, p.n, lane);
     load_k_subtile<T, D>(kf1, k_head, p.k_st, t0 + 32, p.n, lane);
+  }
 
+  // Prologue: every global load of the staging below is issued before the first result is
+  // used, so the workgroup pays one memory round trip, not one per stage.
+  constexpr int WU = (D * D / E + NT - 1) / NT;          // 16-byte pieces of W per thread
+  union WPiece { uint4 raw; T el[E]; };
+  WPiece wpiece[WU];
+  if (DO_RES) {
+    const T* Wh = reinterpret_cast<const T*>(p.W) + (int64_t)h * p.w_sh;
+#pragma unroll
+    for (int u = 0; u < WU; ++u) {
+      const int i = threadIdx.x + u * NT;
+      if (i < D * D / E) wpiece[u].raw = load_chunk(Wh + (size_t)(i / (D / E)) * D + (i % (D / E)) * E);
+    }
+  }
+  // pass 1's chunk partials of this thread's row: `tpr` adjacent lanes share one row and
+  // each takes every tpr-th chunk; the first kPre of them are requested here
+  constexpr int kPre = 16;
+  const int tpr = p.threads_per_row, sub = threadIdx.x % tpr;
+  const int rows_per_sweep = NT / tpr;
+  float2 pre[kPre];
+  if (DO_MASS) {
+    const int row = threadIdx.x / tpr;
+    if (row < p.R_pad) {
+      const float2* part = p.part + ((size_t)h * p.R_pad + row) * p.n_chunks;
+#pragma unroll
+      for (int u = 0; u < kPre; ++u) {
+        const int c = sub + u * tpr;
+        pre[u] = (c < p.n_chunks) ? part[c] : make_float2(-INFINITY, 0.f);
+      }
+    }
+    fill_rows_lds<T, D, NT>(q_lds, reinterpret_cast<const T*>(p.q) + (size_t)h * p.R * D, p.R, p.R_pad, chunk * 8);
+  }
+  if (DO_RES) {
+    // W^T into LDS as the M-side operand.  MFMA row m of block jb stands for value dim
+    //   j = hf*(D/2) + jb*16 + (m >> 3)*4 + (m & 3),  hf = (m >> 2) & 1,
+    // which makes accumulator register v of a lane in half hf hold dim hf*(D/2) + jb*16 + v:
+    // exactly the contiguous half row of v that the lane loads.
+#pragma unroll
+    for (int u = 0; u < WU; ++u) {
+      const int i = threadIdx.x + u * NT, din = i / (D / E), j0 = (i % (D / E)) * E;
+      if (i < D * D / E) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+          const int j = j0 + e;
+          const int hf = j / (D / 2), r = j % (D / 2), jb = r >> 4, q16 = r & 15;
+          const int m = (q16 >> 2) * 8 + hf * 4 + (q16 & 3);
+          *reinterpret_cast<T*>(wt_lds + (jb * 32 + m) * TL::kLdsStride + din * (int)sizeof(T)) = wpiece[u].el[e];
+        }
+      }
+    }
+  }
+  if (DO_MASS) {
+    // Merge the partials: bias = max + log2(sum-exp); padded rows get +inf so that they add
+    // exp2(-inf) = 0 to every column.
+    auto fold = [](float& m, float& l, float m2, float l2) {
+      const float mn = fmaxf(m, m2);
+      const float ms = (mn == -INFINITY) ? 0.f : mn;
+      l = l * fast_exp2(m - ms) + l2 * fast_exp2(m2 - ms);
+      m = mn;
+    };
+    for (int row0 = 0; row0 < p.R_pad; row0 += rows_per_sweep) {
+      const int row = row0 + threadIdx.x / tpr;
+      float m = -INFINITY, l = 0.f;
+      if (row < p.R_pad) {
+        const float2* part = p.part + ((size_t)h * p.R_pad + row) * p.n_chunks;
+        int c_from = sub;
+        if (row0 == 0) {                       // the preloaded ones
+#pragma unroll
+          for (int u = 0; u < kPre; ++u) fold(m, l, pre[u].x, pre[u].y);
+          c_from = sub + kPre * tpr;
+        }
+        for (int c = c_from; c < p.n_chunks; c += tpr) {
+          const float2 sv = part[c];
+          fold(m, l, sv.x, sv.y);
+        }
+      }
+      for (int o = 1; o < tpr; o <<= 1) {
+        const float m2 = __shfl_xor(m, o, kWave), l2 = __shfl_xor(l, o, kWave);
+        fold(m, l, m2, l2);
+      }
+      if (sub == 0 && row < p.R_pad) bias_lds[row] = (row < p.R) ? m + __builtin_amdgcn_logf(l) : INFINITY;
+    }
+  }
+  __syncthreads();
+
+  // ---- score part: rows = query rows, columns = tokens ----
+  auto mass_mma = [&](f32x16& x0, f32x16& x1, int rb) {
+#pragma unroll
+    for (int c = 0; c < TL::NC; ++c) {
+      chunk_t qf = lds_chunk<T, D>(q_lds, rb * 32 + l31, c, half);
+      if (c == 0) { mma_chunk_first<T>(x0, qf, kf0[c]); mma_chunk_first<T>(x1, qf, kf1[c]); }
+      else { mma_chunk<T>(x0, qf, kf0[c]); mma_chunk<T>(x1, qf, kf1[c]); }
+    }
+  };
+  auto mass_valu = [&](const f32x16& x0, const f32x16& x1, int rb, float& col0, float& col1) {
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {
+      f32x4 b = *reinterpret_cast<const f32x4*>(bias_lds + rb * 32 + g4 * 8 + half * 4);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        col0 += fast_exp2(fmaf(x0[g4 * 4 + i], p.c2, -b[i]));
+        col1 += fast_exp2(fmaf(x1[g4 * 4 + i], p.c2, -b[i]));
+      }
+    }
+  };
+  // MFMAs of row block rb_n one at a time, each followed by exponentials of row block rb_c
+  auto mass_step = [&](f32x16& n0, f32x16& n1, int rb_n, const f32x16& c0, const f32x16& c1, int rb_c,
+                       float& col0, float& col1) {
+    float b[16];
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {
+      f32x4 bb = *reinterpret_cast<const f32x4*>(bias_lds + rb_c * 32 + g4 * 8 + half * 4);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) b[g4 * 4 + i] = bb[i];
+    }
+    chunk_t qf = lds_chunk<T, D>(q_lds, rb_n * 32 + l31, 0, half);
+#pragma unroll
+    for (int c = 0; c < TL::NC; ++c) {
+      const chunk_t q_now = qf;
+      if (c + 1 < TL::NC) qf = lds_chunk<T, D>(q_lds, rb_n * 32 + l31, c + 1, half);
+      const int lo = c * 16 / TL::NC, hi = (c + 1) * 16 / TL::NC, mid = lo + (hi - lo + 1) / 2;
+      if (c == 0) mma_chunk_first<T>(n0, q_now, kf0[c]);
+      else mma_chunk<T>(n0, q_now, kf0[c]);
+#pragma unroll
+      for (int v = lo; v < mid; ++v) {
+        col0 += fast_exp2(fmaf(c0[v], p.c2, -b[v]));
+        col1 += fast_exp2(fmaf(c1[v], p.c2, -b[v]));
+      }
+      VEC_PIN3(n0, col0, col1);
+      if (c == 0) mma_chunk_first<T>(n1, q_now, kf1[c]);
+      else mma_chunk<T>(n1, q_now, kf1[c]);
+#pragma unroll
+      for (int v = mid; v < hi; ++v) {
+        col0 += fast_exp2(fmaf(c0[v], p.c2, -b[v]));
+        col1 += fast_exp2(fmaf(c1[v], p.c2, -b[v]));
+      }
+      VEC_PIN3(n1, col0, col1);
+    }
+  };
+
+  // ---- residual part: rows = value dims, columns = tokens; block bi = subtile * JB + jb ----
+  chunk_t vf0[TL::VP], vf1[TL::VP];
+  auto res_mma = [&](f32x16& a, int bi) {
+    const chunk_t* kf = (bi / JB) ? kf1 : kf0;
+#pragma unroll
+    for (int c = 0; c < TL::NC; ++c) {
+      const chunk_t wf = lds_chunk<T, D>(wt_lds, (bi % JB) * 32 + l31, c, half);
+      if (c == 0) mma_chunk_first<T>(a, wf, kf[c]);
+      else mma_chunk<T>(a, wf, kf[c]);
+    }
+  };
+  // register v of block (sub, jb) pairs with element jb*16 + v of the lane's half row of v
+  auto res_diff = [&](const f32x16& a, int bi, int v, float& e) {
+    const chunk_t* vf = (bi / JB) ? vf1 : vf0;
+    const int el = (bi % JB) * 16 + v;
+    float f[E];
+    Unpack<T>::run(vf[el / E], f);
+    const float df = f[el % E] - a[v];
+    e = fmaf(df, df, e);
+  };
+  auto res_step = [&](f32x16& nx, int bi_n, const f32x16& cu, int bi_c, float& e) {
+    const chunk_t* kf = (bi_n / JB) ? kf1 : kf0;
+    chunk_t wf = lds_chunk<T, D>(wt_lds, (bi_n % JB) * 32 + l31, 0, half);
+#pragma unroll
+    for (int c = 0; c < TL::NC; ++c) {
+      const chunk_t w_now = wf;
+      if (c + 1 < TL::NC) wf = lds_chunk<T, D>(wt_lds, (bi_n % JB) * 32 + l31, c + 1, half);
+      if (c == 0) mma_chunk_first<T>(nx, w_now, kf[c]);
+      else mma_chunk<T>(nx, w_now, kf[c]);
+#pragma unroll
+      for (int v = c * 16 / TL::NC; v < (c + 1) * 16 / TL::NC; ++v) res_diff(cu, bi_c, v, e);
+      VEC_PIN(nx, e);
+    }
+  };
+  auto load_next = [&](int tn) {
+    if (tn < c_end) {                    // every MFMA of the tile is issued: fetch the next keys
+      load_k_subtile<T, D>(kf0, k_head, p.k_st, tn, p.n, lane);
+      load_k_subtile<T, D>(kf1, k_head, p.k_st, tn + 32, p.n, lane);
+    }
+  };
+
+  while (t0 < c_end) {
+    const int tn = t0 + kStep;
+    if (DO_RES) {                        // values arrive while the score part computes
+      load_v_subtile<T, D>(vf0, v_head, p.v_st, t0, p.n, lane);
+      load_v_subtile<T, D>(vf1, v_head, p.v_st, t0 + 32, p.n, lane);
+    }
     if (DO_MASS && t0 < mass_end) {
       float col0 = 0.f, col1 = 0.f;
-      for (int rb = 0; rb < nrb; ++rb) {
-        f32x16 a0 = {0}, a1 = {0};
-#pragma unroll
-        for (int c = 0; c < TL::NC; ++c) {
-          chunk_t qf = lds_chunk<T, D>(q_lds, rb * 32 + l31, c, half);
-          mma_chunk<T>(a0, qf, kf0[c]);   // rows = query rows, columns = tokens
-          mma_chunk<T>(a1, qf, kf1[c]);
-        }
-#pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-          f32x4 b = *reinterpret_cast<const f32x4*>(bias_lds + rb * 32 + g4 * 8 + half * 4);
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            col0 += fast_exp2(a0[g4 * 4 + i] * p.c2 - b[i]);
-            col1 += fast_exp2(a1[g4 * 4 + i] * p.c2 - b[i]);
-          }
-        }
+      f32x16 A0, A1, B0, B1;
+      mass_mma(A0, A1, 0);
+      int rb = 0;
+      for (; rb + 2 < nrb; rb += 2) {
+        mass_step(B0, B1, rb + 1, A0, A1, rb, col0, col1);
+        mass_step(A0, A1, rb + 2, B0, B1, rb + 1, col0, col1);
+      }
+      if (rb + 1 < nrb) {
+        mass_step(B0, B1, rb + 1, A0, A1, rb, col0, col1);
+        if (!DO_RES) load_next(tn);
+        mass_valu(B0, B1, rb + 1, col0, col1);
+      } else {
+        if (!DO_RES) load_next(tn);
+        mass_valu(A0, A1, rb, col0, col1);
       }
       col0 += __shfl_xor(col0, 32, kWave);
       col1 += __shfl_xor(col1, 32, kWave);
       const int t = t0 + lane;             // lanes 0..31 -> subtile 0, 32..63 -> subtile 1
       if (t < mass_end) p.mass[(size_t)h * p.n + t] = (half ? col1 : col0) * p.inv_R;
+    } else if (DO_MASS && !DO_RES) {
+      load_next(tn);
     }
-
     if (DO_RES) {
+      float e0 = 0.f, e1 = 0.f;
+      f32x16 RA, RB;
+      res_mma(RA, 0);
 #pragma unroll
-      for (int sub = 0; sub < 2; ++sub) {
-        const chunk_t* kf = sub ? kf1 : kf0;
-        const int ts = t0 + sub * 32;
-        // value elements in accumulator layout: register v <-> token row acc_row(v), lane <-> JB consecutive columns
-        constexpr int VB = JB * (int)sizeof(T);
-        RawVec<VB> vv[16];
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          int t = min(ts + acc_row(v, half), p.n - 1);
-          vv[v] = load_raw<VB>(v_head + (int64_t)t * p.v_st + l31 * JB);
-        }
-        float e[16];
-#pragma unroll
-        for (int v = 0; v < 16; ++v) e[v] = 0.f;
-#pragma unroll 1
-        for (int jb = 0; jb < JB; ++jb) {
-          f32x16 a = {0};
-#pragma unroll
-          for (int c = 0; c < TL::NC; ++c) {
-            chunk_t wf = lds_chunk<T, D>(wt_lds, jb * 32 + l31, c, half);
-            mma_chunk<T>(a, kf[c], wf);     // rows = tokens, columns = value dims
-          }
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            float df = raw_elem<T, VB>(vv[v], jb) - a[v];
-            e[v] += df * df;
-          }
-        }
-        // sum over the 32 lanes (value columns) of each half
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-#pragma unroll
-          for (int o = 16; o >= 1; o >>= 1) e[v] += __shfl_xor(e[v], o, kWave);
-        }
-        // lane (l & 31) == v of half hf writes token row acc_row(v, hf)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          int t = ts + acc_row(v, half);
-          if (l31 == v && t < c_end) p.eps[(size_t)h * p.n + t] = e[v];
-        }
+      for (int bi = 0; bi + 1 < 2 * JB; ++bi) {
+        float& e = (bi / JB) ? e1 : e0;
+        if (bi & 1) res_step(RA, bi + 1, RB, bi, e);
+        else res_step(RB, bi + 1, RA, bi, e);
       }
+      load_next(tn);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) res_diff(((2 * JB - 1) & 1) ? RB : RA, 2 * JB - 1, v, e1);
+      e0 += __shfl_xor(e0, 32, kWave);       // the two halves of the value row
+      e1 += __shfl_xor(e1, 32, kWave);
+      const int t = t0 + lane;               // lanes 0..31 -> subtile 0, 32..63 -> subtile 1
+      if (t < c_end) p.eps[(size_t)h * p.n + t] = half ? e1 : e0;
     }
+    t0 = tn;
   }
 }
 
@@ -338,18 +585,20 @@ __global__ void pool_scores_kernel(const float* __restrict__ mass, float* __rest
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
-constexpr int kThreads = 512;
+constexpr int kThreads = 512;        // pass 2
+constexpr int kThreads1 = VEC_P1_THREADS;   // pass 1
+constexpr int kSub1 = VEC_P1_SUBTILES;
 
 struct Plan {
   PassParams pp;
-  size_t ws_need;
   size_t lds_stats, lds_pass2;
 };
 
 int pick_tokens_per_chunk(int n, int n_kv_heads) {
-  // aim for at least ~2 workgroups per CU, chunks of at least 64 tokens per wave
+  // at least one workgroup per CU where the sequence allows it, and then as many
+  // 64-token tiles per wave as possible so that the key prefetch has something to hide
   int tpc = 2048;
-  while (tpc > 512 && (int64_t)((n + tpc - 1) / tpc) * n_kv_heads < 512) tpc >>= 1;
+  while (tpc > 512 && (int64_t)((n + tpc - 1) / tpc) * n_kv_heads < 256) tpc >>= 1;
   return tpc;
 }
 
@@ -362,6 +611,9 @@ int make_plan(const vector_shape& s, bool do_mass, bool do_res, Plan& plan) {
   p.n_prefix = s.seq_len - s.window;
   p.tokens_per_chunk = pick_tokens_per_chunk(s.seq_len, s.n_kv_heads);
   p.n_chunks = (s.seq_len + p.tokens_per_chunk - 1) / p.tokens_per_chunk;
+  int tpr = 1;
+  while (tpr * 2 <= 64 && tpr * 2 * p.R_pad <= kThreads && tpr * 2 <= p.n_chunks) tpr *= 2;
+  p.threads_per_row = tpr;
   p.c2 = kLog2e / sqrtf((float)D);
   p.inv_R = 1.0f / (float)p.R;
   p.k_st = s.k_stride_tok ? s.k_stride_tok : D;
@@ -369,7 +621,7 @@ int make_plan(const vector_shape& s, bool do_mass, bool do_res, Plan& plan) {
   p.v_st = s.v_stride_tok ? s.v_stride_tok : D;
   p.v_sh = s.v_stride_head ? s.v_stride_head : (int64_t)s.seq_len * p.v_st;
   p.w_sh = s.w_shared ? 0 : (s.w_stride_head ? s.w_stride_head : (int64_t)D * D);
-  constexpr int NW = kThreads / kWave;
+  constexpr int NW = kThreads1 / kWave;
   plan.lds_stats = (size_t)p.R_pad * TL::kLdsStride + (size_t)NW * (p.R_pad / 32) * 64 * sizeof(float2);
   plan.lds_pass2 = (do_mass ? (size_t)p.R_pad * (TL::kLdsStride + sizeof(float)) : 0) + (do_res ? (size_t)D * TL::kLdsStride : 0);
   if (plan.lds_stats > kMaxLdsBytes || plan.lds_pass2 > kMaxLdsBytes) return VECTOR_ERR_SHAPE;
@@ -385,7 +637,6 @@ size_t score_workspace_bytes(const vector_shape& s) {
   const int n_chunks = (s.seq_len + tpc - 1) / tpc;
   size_t b = 0;
   b += align_up((size_t)s.n_kv_heads * n_chunks * R_pad * sizeof(float2), 256);
-  b += align_up((size_t)s.n_kv_heads * R_pad * sizeof(float), 256);
   b += align_up((size_t)s.n_kv_heads * s.seq_len * sizeof(float), 256);
   return b;
 }
@@ -402,16 +653,13 @@ static int run_score_residual(const vector_shape& s, const void* q, const void* 
   unsigned char* w8 = reinterpret_cast<unsigned char*>(ws);
   p.part = reinterpret_cast<float2*>(w8);
   w8 += align_up((size_t)s.n_kv_heads * p.n_chunks * p.R_pad * sizeof(float2), 256);
-  p.bias = reinterpret_cast<float*>(w8);
-  w8 += align_up((size_t)s.n_kv_heads * p.R_pad * sizeof(float), 256);
   p.mass = reinterpret_cast<float*>(w8);
 
   dim3 grid(p.n_chunks, s.n_kv_heads);
   if (do_mass) {
-    auto k1 = score_stats_kernel<T, D, kThreads>;
+    auto k1 = score_stats_kernel<T, D, kThreads1, kSub1>;
     VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k1), plan.lds_stats));
-    VEC_LAUNCH(K_SCORE_STATS, k1, grid, dim3(kThreads), plan.lds_stats, stream, p);
-    VEC_LAUNCH(K_STATS_COMBINE, stats_combine_kernel, dim3((p.R_pad + 127) / 128, s.n_kv_heads), dim3(128), 0, stream, p);
+    VEC_LAUNCH(K_SCORE_STATS, k1, grid, dim3(kThreads1), plan.lds_stats, stream, p);
   }
   if (do_mass && do_res) {
     auto k2 = mass_residual_kernel<T, D, kThreads, true, true>;
