@@ -261,6 +261,218 @@ __global__ __launch_bounds__(RT) void route_kernel(const float* __restrict__ sco
 }
 
 // ---------------------------------------------------------------------------
+// Routing with every key held in registers (seq_len <= RT * KC).  A thread owns EPT
+// consecutive tokens in each tile of RT*EPT tokens; scores and residuals are read from
+// memory once, all loads in flight together, and the radix passes and the ordered pass run
+// out of registers.  The only other memory round trip is the pool list between the steps.
+// ---------------------------------------------------------------------------
+// hist[digit] += cnt (cnt in 0..EPT) for every lane, lanes that agree with a leader merged
+// through ballots of the three bits of cnt; see hist_add_aggregated.
+__device__ __forceinline__ void hist_add_weighted(int* hist, uint32_t digit, int cnt, int lane) {
+  unsigned long long todo = __ballot(cnt > 0);
+#pragma unroll
+  for (int round = 0; round < 2; ++round) {
+    if (todo == 0) return;
+    const int leader = __ffsll((long long)todo) - 1;
+    const uint32_t d = __builtin_amdgcn_readlane(digit, leader);
+    const bool match = cnt > 0 && digit == d;
+    const unsigned long long b0 = __ballot(match && (cnt & 1)), b1 = __ballot(match && (cnt & 2)),
+                             b2 = __ballot(match && (cnt & 4));
+    if (lane == leader) atomicAdd(&hist[d], __popcll(b0) + 2 * __popcll(b1) + 4 * __popcll(b2));
+    if (match) cnt = 0;
+    todo &= ~(b0 | b1 | b2);
+  }
+  if (cnt > 0) atomicAdd(&hist[digit], cnt);
+}
+
+// k-th largest of the keys in key[0..KC) (slot s is valid iff valid(s)); see radix_select_desc.
+template <typename ValidFn>
+__device__ void radix_select_regs(const uint32_t (&key)[KC], ValidFn valid, int n_tiles, int k, RouteShared& sh,
+                                  uint32_t& thr, int& quota) {
+  static_assert(EPT == 4, "the weighted histogram add packs counts of up to 4 into three ballots");
+  uint32_t prefix = 0, mask = 0;
+  int remaining = k;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int shift = 32;
+#pragma unroll 1
+  for (int pass = 0; pass < 3; ++pass) {
+    const int bits = pass == 2 ? 10 : 11;
+    const uint32_t dmask = (1u << bits) - 1u;
+    shift -= bits;
+    for (int i = threadIdx.x; i < kBins; i += RT) sh.hist[i] = 0;
+    __syncthreads();
+    if (pass == 0) {
+      // neighbouring tokens mostly share the leading digit: count the thread's tokens that
+      // agree with its first valid one and add them in one go; the others go one by one
+#pragma unroll
+      for (int t = 0; t < KC / EPT; ++t) {
+        if (t < n_tiles) {                    // uniform: whole waves take part
+          uint32_t dg[EPT];
+          bool ok[EPT];
+#pragma unroll
+          for (int j = 0; j < EPT; ++j) { dg[j] = (key[t * EPT + j] >> shift) & dmask; ok[j] = valid(t * EPT + j); }
+          int cnt = 0;
+#pragma unroll
+          for (int j = 0; j < EPT; ++j) cnt += ok[j] && dg[j] == dg[0];
+          if (!ok[0]) cnt = 0;
+          hist_add_weighted(sh.hist, dg[0], cnt, lane);
+#pragma unroll
+          for (int j = 1; j < EPT; ++j)
+            if (ok[j] && !(ok[0] && dg[j] == dg[0])) atomicAdd(&sh.hist[dg[j]], 1);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int s = 0; s < KC; ++s)
+        if (s / EPT < n_tiles && valid(s) && (key[s] & mask) == prefix) atomicAdd(&sh.hist[(key[s] >> shift) & dmask], 1);
+    }
+    __syncthreads();
+    const int b_hi = kBins - 1 - 2 * threadIdx.x;
+    const int c0 = sh.hist[b_hi], c1 = sh.hist[b_hi - 1];
+    const int tot = c0 + c1;
+    const int incl_w = wave_incl_scan_i(tot, lane);
+    if (lane == 63) sh.wave_sum[wave] = incl_w;
+    __syncthreads();
+    int above = incl_w - tot;
+    for (int wv = 0; wv < wave; ++wv) above += sh.wave_sum[wv];
+    if (above < remaining && remaining <= above + tot) {
+      int d = b_hi;
+      if (remaining > above + c0) { above += c0; d = b_hi - 1; }
+      sh.digit = d;
+      sh.above = above;
+    }
+    __syncthreads();
+    prefix |= ((uint32_t)sh.digit) << shift;
+    mask |= dmask << shift;
+    remaining -= sh.above;
+  }
+  thr = prefix;
+  quota = remaining;
+  __syncthreads();
+}
+
+// Ordered pass over keys held in registers; see ordered_select.  emit(slot, i, selected, rank).
+template <typename ValidFn, typename EmitFn>
+__device__ void ordered_select_regs(const uint32_t (&key)[KC], ValidFn valid, int n_tiles, uint32_t thr, int quota,
+                                    EmitFn emit, RouteShared& sh) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int carry_gt = 0, carry_eq = 0;
+#pragma unroll
+  for (int t = 0; t < KC / EPT; ++t) {
+    if (t < n_tiles) {
+      int cls[EPT], packed = 0;
+#pragma unroll
+      for (int j = 0; j < EPT; ++j) {
+        const uint32_t kk = key[t * EPT + j];
+        cls[j] = valid(t * EPT + j) ? (kk > thr ? 2 : (kk == thr ? 1 : 0)) : 0;
+        packed += (cls[j] == 2 ? 0x10000 : 0) + (cls[j] == 1 ? 1 : 0);
+      }
+      const int incl = wave_incl_scan_i(packed, lane);
+      if (lane == 63) sh.wave_tot[t & 1][wave] = incl;
+      __syncthreads();
+      int pre = incl - packed, tile_tot = 0;
+      for (int wv = 0; wv < RW; ++wv) {
+        const int x = sh.wave_tot[t & 1][wv];
+        if (wv < wave) pre += x;
+        tile_tot += x;
+      }
+      int pre_gt = carry_gt + (pre >> 16), pre_eq = carry_eq + (pre & 0xffff);
+      carry_gt += tile_tot >> 16;
+      carry_eq += tile_tot & 0xffff;
+#pragma unroll
+      for (int j = 0; j < EPT; ++j) {
+        if (valid(t * EPT + j)) {
+          const bool sel = cls[j] == 2 || (cls[j] == 1 && pre_eq < quota);
+          emit(t * EPT + j, sel, pre_gt + min(pre_eq, quota));
+          pre_gt += cls[j] == 2;
+          pre_eq += cls[j] == 1;
+        }
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(RT) void route_cached_kernel(const float* __restrict__ score, const float* __restrict__ eps,
+                                                          int n, int n_pool, int n_approx, uint8_t* __restrict__ tier,
+                                                          int32_t* __restrict__ idx_retain,
+                                                          int32_t* __restrict__ idx_approx, int32_t* __restrict__ pool_idx,
+                                                          uint32_t* __restrict__ pool_key) {
+  __shared__ RouteShared sh;
+  // second word of every slot (residual bits, then pool token index): [slot][thread], kept in
+  // LDS as an extension of the register file (each thread only ever touches its own column)
+  extern __shared__ uint32_t side_lds[];
+  const int h = blockIdx.x;
+  const float* sc = score + (size_t)h * n;
+  const float* ep = eps + (size_t)h * n;
+  uint8_t* tr = tier + (size_t)h * n;
+  int32_t* pidx = pool_idx + (size_t)h * n_pool;
+  uint32_t* pkey = pool_key + (size_t)h * n_pool;
+  int32_t* ir = idx_retain + (size_t)h * (n_pool - n_approx);
+  int32_t* ia = idx_approx + (size_t)h * n_approx;
+
+  if (n_pool == 0) {
+    for (int i = threadIdx.x; i < n; i += RT) tr[i] = VECTOR_TIER_EVICT;
+    return;
+  }
+  // slot s of a thread = token (s / EPT) * RT * EPT + tid * EPT + s % EPT
+  auto token_of = [&](int s) { return (s / EPT) * RT * EPT + (int)threadIdx.x * EPT + (s % EPT); };
+  const int n_tiles = (n + RT * EPT - 1) / (RT * EPT);
+
+  // Step 1: the pool is the n_pool tokens of highest score.  One round trip brings in every
+  // score and residual this thread will need.
+  uint32_t key[KC];
+#pragma unroll
+  for (int s = 0; s < KC; ++s) {
+    const int i = token_of(s);
+    const bool in = s / EPT < n_tiles && i < n;
+    key[s] = in ? float_key(sc[i]) : 0u;
+    if (s / EPT < n_tiles) side_lds[s * RT + threadIdx.x] = in ? ~float_key(ep[i]) : 0u;   // smaller residual, larger key
+  }
+  uint32_t thr;
+  int quota;
+  radix_select_regs(key, [&](int s) { return token_of(s) < n; }, n_tiles, n_pool, sh, thr, quota);
+  ordered_select_regs(key, [&](int s) { return token_of(s) < n; }, n_tiles, thr, quota,
+      [&](int s, bool sel, int rank) {
+        const int i = token_of(s);
+        tr[i] = sel ? VECTOR_TIER_RETAIN : VECTOR_TIER_EVICT;
+        if (sel && rank < n_pool) {            // rank < n_pool by construction; never write past the list
+          pidx[rank] = i;
+          pkey[rank] = side_lds[s * RT + threadIdx.x];
+        }
+      }, sh);
+  __threadfence();
+  __syncthreads();
+
+  // Step 3: inside the pool, the n_approx tokens of lowest residual lose their value
+  if (n_approx == 0) {
+    for (int i = threadIdx.x; i < n_pool; i += RT) ir[i] = pidx[i];
+    return;
+  }
+  const int p_tiles = (n_pool + RT * EPT - 1) / (RT * EPT);
+#pragma unroll
+  for (int s = 0; s < KC; ++s) {
+    const int i = token_of(s);
+    const bool in = s / EPT < p_tiles && i < n_pool;
+    key[s] = in ? pkey[i] : 0u;
+    if (s / EPT < p_tiles) side_lds[s * RT + threadIdx.x] = in ? (uint32_t)pidx[i] : 0u;
+  }
+  radix_select_regs(key, [&](int s) { return token_of(s) < n_pool; }, p_tiles, n_approx, sh, thr, quota);
+  ordered_select_regs(key, [&](int s) { return token_of(s) < n_pool; }, p_tiles, thr, quota,
+      [&](int s, bool sel, int rank) {
+        const int i = token_of(s);
+        const int tok = (int)side_lds[s * RT + threadIdx.x];
+        if (sel) {
+          if (rank < n_approx) {
+            ia[rank] = tok;
+            tr[tok] = VECTOR_TIER_APPROX;
+          }
+        } else if (i - rank < n_pool - n_approx) {
+          ir[i - rank] = tok;
+        }
+      }, sh);
+}
+
+// ---------------------------------------------------------------------------
 // compaction: one 16-byte piece per thread, P pieces per row
 // ---------------------------------------------------------------------------
 struct GatherParams {
@@ -300,8 +512,15 @@ int launch_route(int n_kv_heads, int seq_len, const float* score, const float* e
   int32_t* pool_idx = reinterpret_cast<int32_t*>(ws);
   uint32_t* pool_key = reinterpret_cast<uint32_t*>(reinterpret_cast<unsigned char*>(ws) +
                                                    align_up((size_t)n_kv_heads * n_pool * sizeof(int32_t), 256));
-  VEC_LAUNCH(K_ROUTE, route_kernel, dim3(n_kv_heads), dim3(RT), 0, stream, score, eps, seq_len, n_pool, n_approx, tier,
-                     idx_retain, idx_approx, pool_idx, pool_key);
+  if (seq_len <= RT * KC) {
+    const int n_tiles = (seq_len + RT * EPT - 1) / (RT * EPT);
+    const size_t lds = (size_t)n_tiles * EPT * RT * sizeof(uint32_t);
+    VEC_HIP(set_max_lds(reinterpret_cast<const void*>(route_cached_kernel), lds));
+    VEC_LAUNCH(K_ROUTE, route_cached_kernel, dim3(n_kv_heads), dim3(RT), lds, stream, score, eps, seq_len, n_pool,
+               n_approx, tier, idx_retain, idx_approx, pool_idx, pool_key);
+  } else
+    VEC_LAUNCH(K_ROUTE, route_kernel, dim3(n_kv_heads), dim3(RT), 0, stream, score, eps, seq_len, n_pool, n_approx, tier,
+               idx_retain, idx_approx, pool_idx, pool_key);
   VEC_HIP(hipGetLastError());
   return VECTOR_OK;
 }
