@@ -67,6 +67,8 @@ def main() -> None:
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-layers", type=int, default=6)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy (reference kernel for scaling HBM counters)")
     ap.add_argument("--streams", type=int, default=3,
                     help="HIP streams the layers are spread over (layers are independent)")
     args = ap.parse_args()
@@ -115,6 +117,13 @@ def main() -> None:
             pl.compress_layer(shape, L["q_win"], L["k"], L["v"], L["w_cal"], n_p, n_a, o, wss[i % n_streams],
                               stream=streams[i % n_streams])
 
+    if args.copy_calibration:                  # known traffic: 256 MiB read, 256 MiB written per copy
+        src = torch.empty(128 * 1024 * 1024, dtype=torch.bfloat16, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -127,10 +136,15 @@ def main() -> None:
     tokens_per_s = cfg.layers * n * args.steps / elapsed
     log(f"compression pass: {ms_per_step:.3f} ms/step, {tokens_per_s / 1e6:.2f} M KV tokens/s")
 
-    # ---- per-kernel durations over the same steps, HIP events on the launch stream ----
+    # ---- per-kernel durations over the same steps, HIP events on the launch stream.  The
+    # layers run on one stream here: a duration measured while another layer's kernels share
+    # the chip says little about the kernel itself ----
+    def step_one_stream():
+        for L, o in zip(layers, outs):
+            pl.compress_layer(shape, L["q_win"], L["k"], L["v"], L["w_cal"], n_p, n_a, o, wss[0], stream=streams[0])
     vb.vector_timing_enable(True)
     for _ in range(args.steps):
-        step()
+        step_one_stream()
     torch.cuda.synchronize()
     timing = vb.vector_timing_read()
     vb.vector_timing_enable(False)
@@ -152,15 +166,17 @@ def main() -> None:
     sum_us = sum(v["avg_us"] for v in kernels.values())
     pass_bytes = bpt["pass"] * H * n
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
     if os.path.exists(tpath):                  # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain copy
-        try:
-            traffic = json.load(open(tpath)).get(dominant, {}).get("bytes_per_launch")
-        except Exception:
-            traffic = None
+        for line in open(tpath):
+            parts = line.split()
+            if len(parts) == 2 and parts[0] == dominant:
+                traffic = int(parts[1])
+    event_overhead_us = vb.vector_timing_event_overhead(50, streams[0]) * 1e3
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(dom_gbs, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(dom_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "bytes_per_launch": int(dom_bytes), "avg_us": kernels[dominant]["avg_us"],
+                "event_overhead_us": round(event_overhead_us, 2),
                 "pass_alg_bytes_per_layer": int(pass_bytes),
                 "pass_frac_of_hbm_peak": round(pass_bytes * cfg.layers / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
     # MFMA work of the pass (both softmax passes and the residual contraction)

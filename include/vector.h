@@ -171,6 +171,9 @@ VECTOR_API int vector_timing_enable(int on);
 VECTOR_API int vector_timing_kernels(void);
 VECTOR_API const char* vector_timing_name(int kernel_id);
 VECTOR_API int vector_timing_read(int kernel_id, double* total_ms, int64_t* launches);
+/* What the event pair itself measures: the average HIP-event duration around an empty
+ * one-wave kernel on `stream`, over `launches` launches (waits for each). */
+VECTOR_API int vector_timing_event_overhead(void* stream, int launches, double* avg_ms);
 
 #ifdef __cplusplus
 }
