@@ -42,6 +42,10 @@ constexpr int DW = DT_ / kWave;   // waves
 constexpr int kMaxSplits = 64;
 constexpr int kUnroll = 4;        // rows per lane group in flight
 constexpr int kTargetWorkgroups = 768;
+#ifndef VEC_DEC_TARGET
+#define VEC_DEC_TARGET 1024
+#endif
+constexpr int kTargetWorkgroupsMfma = VEC_DEC_TARGET;   // bf16 kernel: two workgroups fit a CU
 
 template <typename T> struct Unpack16;
 template <> struct Unpack16<bf16_t> {
@@ -247,6 +251,225 @@ __global__ __launch_bounds__(DT_) void decode_split_kernel(DecodeParams p) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// bf16 caches: the same split, on the matrix cores.  Rows still arrive as 1 KiB
+// wave-wide loads (16 bytes per lane, adjacent lanes on one row); a wave parks a tile of
+// 32 rows in its own slice of LDS and reads it back in operand order:
+//   scores   S[t][g] = sum_e K[t][e] q[g][e]     A = key tile (16-byte reads along a row),
+//                                                 B = the G query rows (columns >= G zero)
+//   output   O[j][g] += sum_t R[t][j] P[t][g]    A = tile of R read down its columns
+//                                                 (R = values, or the keys themselves for
+//                                                 approximated rows), B = P
+// The accumulator layout of S (column g on lane g, sixteen tokens in the registers of a
+// lane) is already the B-operand layout of the second product once the contraction index
+// is numbered the way those registers number the tokens, so P never leaves its lane.  P is
+// fed to the matrix core as bf16 twice: its rounded value and the remainder of that
+// rounding, which keeps the weights to about 2^-16 relative.
+// ---------------------------------------------------------------------------
+constexpr int kTileRows = 32;
+
+typedef __attribute__((ext_vector_type(8))) unsigned short u16x8;
+
+template <int D> struct MfmaDecodeTile {
+  static constexpr int kRowBytes = D * 2;
+  static constexpr int kStride = kRowBytes + 16;            // LDS row stride: 16-byte reads of 32 rows hit distinct banks
+  static constexpr int kPieces = kRowBytes / 16;            // 16-byte pieces per row
+  static constexpr int kRowsPerLoad = kWave / kPieces;
+  static constexpr int kLoads = kTileRows / kRowsPerLoad;   // wave-wide loads per tile and tensor
+  static constexpr int kTileBytes = kTileRows * kStride;
+  static constexpr int kLdsBytes = DW * 2 * kTileBytes;
+};
+
+template <int D, int G>
+__global__ __launch_bounds__(DT_, 2) void decode_split_mfma_kernel(DecodeParams p) {
+  using T = bf16_t;
+  using TL = MfmaDecodeTile<D>;
+  constexpr int NC = D / 16;               // 16-element steps of the score contraction
+  constexpr int JB = D / 32;               // 32-wide blocks of the output dimension
+  constexpr int PSZ = 2 * G + G * D;
+  constexpr float kNegBig = -1.0e30f;      // running maximum before any row: finite, so differences stay finite
+  static_assert(DW * (G * D + 2 * G) * 4 <= TL::kLdsBytes, "merge area must fit in the tile area");
+
+  extern __shared__ __align__(16) unsigned char dec_lds[];
+
+  const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int l31 = lane & 31, half = lane >> 5;
+  const int len_r = min(max(p.len_retain[b], 0), p.cap_retain);
+  const bool is_apx = split >= p.splits_ret;
+  const int seg_len = is_apx ? p.n_approx : len_r;
+  const int n_sp = is_apx ? p.splits_apx : p.splits_ret;
+  const int sp = is_apx ? split - p.splits_ret : split;
+  constexpr int kStepRows = DW * kTileRows;
+  const int steps = (seg_len + kStepRows - 1) / kStepRows;
+  const int row_begin = (int)((int64_t)steps * sp / n_sp) * kStepRows;
+  const int row_end = min(seg_len, (int)((int64_t)steps * (sp + 1) / n_sp) * kStepRows);
+
+  const size_t bh = (size_t)b * p.Hkv + h;
+  const T* kseg = is_apx ? reinterpret_cast<const T*>(p.k_apx) + bh * p.n_approx * D
+                         : reinterpret_cast<const T*>(p.k_ret) + bh * p.cap_retain * D;
+  const T* vseg = reinterpret_cast<const T*>(p.v_ret) + bh * p.cap_retain * D;
+
+  unsigned char* k_tile = dec_lds + wave * 2 * TL::kTileBytes;
+  unsigned char* v_tile = k_tile + TL::kTileBytes;
+  const unsigned char* r_tile = is_apx ? k_tile : v_tile;
+
+  // B operand of the score product: query row g on lane g, zero beyond G
+  chunk_t qf[NC];
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    qf[c] = make_uint4(0, 0, 0, 0);
+    if (l31 < G)
+      qf[c] = load_chunk(reinterpret_cast<const T*>(p.q) + ((size_t)b * p.Hq + (size_t)h * G + l31) * D + (2 * c + half) * 8);
+  }
+
+  f32x16 o[JB];
+#pragma unroll
+  for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) o[jb][v] = 0.f;
+  float m_run = kNegBig, l_run = 0.f;
+
+  const int ld_row = lane / TL::kPieces, ld_piece = lane % TL::kPieces;
+  auto fetch = [&](uint4* kraw, uint4* vraw, int base) {
+#pragma unroll
+    for (int i = 0; i < TL::kLoads; ++i) {
+      const int r = min(base + i * TL::kRowsPerLoad + ld_row, seg_len - 1);   // clamped: never past the live rows
+      kraw[i] = load_chunk(kseg + (size_t)r * D + ld_piece * 8);
+      if (!is_apx) vraw[i] = load_chunk(vseg + (size_t)r * D + ld_piece * 8);
+    }
+  };
+  auto stage = [&](const uint4* kraw, const uint4* vraw) {
+#pragma unroll
+    for (int i = 0; i < TL::kLoads; ++i) {
+      const int off = (i * TL::kRowsPerLoad + ld_row) * TL::kStride + ld_piece * 16;
+      *reinterpret_cast<uint4*>(k_tile + off) = kraw[i];
+      if (!is_apx) *reinterpret_cast<uint4*>(v_tile + off) = vraw[i];
+    }
+  };
+  // the tile belongs to this wave alone; these keep the compiler from moving LDS accesses of
+  // different lanes across the hand-over (the hardware runs a wave's LDS operations in order)
+  auto wave_fence = [&]() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  };
+
+  auto consume = [&](int base) {
+    // ---- scores ----
+    f32x16 s;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const chunk_t a = *reinterpret_cast<const chunk_t*>(k_tile + l31 * TL::kStride + (2 * c + half) * 16);
+      if (c == 0) mma_chunk_first<T>(s, a, qf[c]); else mma_chunk<T>(s, a, qf[c]);
+    }
+    float tmax = kNegBig;
+    if (base + kTileRows > row_end) {               // ragged last tile: rows past the range score -inf
+#pragma unroll
+      for (int v = 0; v < 16; ++v) s[v] = (base + acc_row(v, half) < row_end) ? s[v] * p.c2 : -INFINITY;
+    } else {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) s[v] *= p.c2;
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, s[v]);
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
+    if (__any(tmax > m_run)) {                       // rare once the running maxima have settled
+      const float m_new = fmaxf(m_run, tmax);
+      const float alpha = fast_exp2(m_run - m_new);
+      l_run *= alpha;
+#pragma unroll
+      for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[jb][v] *= alpha;
+      m_run = m_new;
+    }
+    // ---- weights, split into a bf16 value and the bf16 remainder ----
+    bf16x8 p_hi[2], p_lo[2];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const float pv = fast_exp2(s[v] - m_run);
+      l_run += pv;
+      const __bf16 hi = (__bf16)pv;
+      p_hi[v >> 3][v & 7] = hi;
+      p_lo[v >> 3][v & 7] = (__bf16)(pv - (float)hi);
+    }
+    // ---- output: contraction index e of step ks on lane half `half` is tile row
+    //      16 ks + 4 half + 8 (e / 4) + e % 4, the row accumulator register 8 ks + e holds ----
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb) {
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        u16x8 a;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int row = 16 * ks + 4 * half + 8 * (e >> 2) + (e & 3);
+          a[e] = *reinterpret_cast<const unsigned short*>(r_tile + row * TL::kStride + (jb * 32 + l31) * 2);
+        }
+        o[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), p_hi[ks], o[jb], 0, 0, 0);
+        o[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), p_lo[ks], o[jb], 0, 0, 0);
+      }
+    }
+  };
+
+  uint4 kraw[TL::kLoads], vraw[TL::kLoads];
+  int base = row_begin + wave * kTileRows;
+  if (base < row_end) fetch(kraw, vraw, base);
+  while (base < row_end) {
+    wave_fence();                                    // last tile's reads are done before it is overwritten
+    stage(kraw, vraw);
+    const int next = base + kStepRows;
+    if (next < row_end) fetch(kraw, vraw, next);     // in flight while this tile is consumed
+    wave_fence();
+    consume(base);
+    base = next;
+  }
+
+  // ---- merge the waves ----
+  const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
+  __syncthreads();                                   // every wave is done with its tiles: reuse the area
+  float* red = reinterpret_cast<float*>(dec_lds);                    // [DW][G][D]
+  float* ml = red + DW * G * D;                                       // [DW][2][G]
+  if (l31 < G) {
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) red[(wave * G + l31) * D + jb * 32 + acc_row(v, half)] = o[jb][v];
+    if (half == 0) {
+      ml[(wave * 2 + 0) * G + l31] = (l_tot > 0.f) ? m_run : -INFINITY;
+      ml[(wave * 2 + 1) * G + l31] = l_tot;
+    }
+  }
+  __syncthreads();
+  float* out = p.part + (bh * (p.splits_ret + p.splits_apx) + split) * PSZ;
+  for (int i = threadIdx.x; i < G * D; i += DT_) {
+    const int g = i / D, j = i % D;
+    float m = -INFINITY;
+#pragma unroll
+    for (int wv = 0; wv < DW; ++wv) m = fmaxf(m, ml[(wv * 2) * G + g]);
+    float a = 0.f;
+#pragma unroll
+    for (int wv = 0; wv < DW; ++wv) {
+      const float mw = ml[(wv * 2) * G + g];
+      if (mw != -INFINITY) a += red[(wv * G + g) * D + j] * fast_exp2(mw - m);
+    }
+    out[2 * G + i] = a;
+  }
+  if (threadIdx.x < G) {
+    const int g = threadIdx.x;
+    float m = -INFINITY, l = 0.f;
+#pragma unroll
+    for (int wv = 0; wv < DW; ++wv) m = fmaxf(m, ml[(wv * 2) * G + g]);
+#pragma unroll
+    for (int wv = 0; wv < DW; ++wv) {
+      const float mw = ml[(wv * 2) * G + g];
+      if (mw != -INFINITY) l += ml[(wv * 2 + 1) * G + g] * fast_exp2(mw - m);
+    }
+    out[g] = m;
+    out[G + g] = l;
+  }
+}
+
 template <typename T, int D, int G>
 __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeParams p) {
   constexpr int PSZ = 2 * G + G * D;
@@ -255,22 +478,30 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeParams p) {
   __shared__ float v_lds[G][D];
   __shared__ float zw_lds[kParts][G][D];
   __shared__ float scale_lds[2 * kMaxSplits][G];   // per split: exp2(m_s - M)
+  __shared__ float m_lds[2 * kMaxSplits][G];
   __shared__ float linv_lds[G];
   const int h = blockIdx.x, b = blockIdx.y;
   const size_t bh = (size_t)b * p.Hkv + h;
   const int n_splits = p.splits_ret + p.splits_apx;
   const float* part = p.part + bh * n_splits * PSZ;
 
+  // every split's (m, l) in one round of loads, then the global maximum per query row
+  for (int t = threadIdx.x; t < n_splits * G; t += 256) {
+    const int s = t / G, g = t % G;
+    m_lds[s][g] = part[(size_t)s * PSZ + g];
+    scale_lds[s][g] = part[(size_t)s * PSZ + G + g];          // l for now
+  }
+  __syncthreads();
   if (threadIdx.x < G) {
     const int g = threadIdx.x;
     float m = -INFINITY;
-    for (int s = 0; s < n_splits; ++s) m = fmaxf(m, part[(size_t)s * PSZ + g]);
+    for (int s = 0; s < n_splits; ++s) m = fmaxf(m, m_lds[s][g]);
     float l = 0.f;
     for (int s = 0; s < n_splits; ++s) {
-      const float ms = part[(size_t)s * PSZ + g];
+      const float ms = m_lds[s][g];
       const float sc = (ms == -INFINITY) ? 0.f : fast_exp2(ms - m);
+      l += scale_lds[s][g] * sc;
       scale_lds[s][g] = sc;
-      l += part[(size_t)s * PSZ + G + g] * sc;
     }
     linv_lds[g] = (l > 0.f) ? 1.f / l : 0.f;
   }
@@ -278,7 +509,9 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeParams p) {
   for (int i = threadIdx.x; i < G * D; i += 256) {
     const int g = i / D;
     float av = 0.f, az = 0.f;
+#pragma unroll 8
     for (int s = 0; s < p.splits_ret; ++s) av += part[(size_t)s * PSZ + 2 * G + i] * scale_lds[s][g];
+#pragma unroll 4
     for (int s = p.splits_ret; s < n_splits; ++s) az += part[(size_t)s * PSZ + 2 * G + i] * scale_lds[s][g];
     (&v_lds[0][0])[i] = av;
     (&z_lds[0][0])[i] = az;
@@ -315,13 +548,13 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeParams p) {
   }
 }
 
-void pick_splits(int batch, int n_kv_heads, int cap_retain, int n_approx, int& s_ret, int& s_apx) {
+void pick_splits(int target, int batch, int n_kv_heads, int cap_retain, int n_approx, int& s_ret, int& s_apx) {
   // One round of workgroups: 256 CUs hold three of these workgroups each, and a second,
   // partly filled round would stream with too few loads in flight.  The splits are divided
   // between the segments by their bytes (a retained row is a key and a value); a workgroup
   // gets a few hundred rows at least.
   const int pairs = batch * n_kv_heads;
-  int total = kTargetWorkgroups / pairs;
+  int total = target / pairs;
   if (total > kMaxSplits) total = kMaxSplits;
   if (total < 2) total = 2;
   const double w_ret = 2.0 * cap_retain, w_apx = (double)n_approx;
@@ -337,8 +570,14 @@ void pick_splits(int batch, int n_kv_heads, int cap_retain, int n_approx, int& s
 
 template <typename T, int D, int G>
 int run_decode(const vector_cache& c, DecodeParams& p, hipStream_t stream) {
-  VEC_LAUNCH(K_DECODE_SPLIT, (decode_split_kernel<T, D, G>), dim3(p.splits_ret + p.splits_apx, c.n_kv_heads, c.batch),
-             dim3(DT_), 0, stream, p);
+  const dim3 grid(p.splits_ret + p.splits_apx, c.n_kv_heads, c.batch);
+  if constexpr (Elem<T>::kDtype == VECTOR_BF16) {
+    constexpr int lds = MfmaDecodeTile<D>::kLdsBytes;
+    VEC_HIP(set_max_lds(reinterpret_cast<const void*>(decode_split_mfma_kernel<D, G>), lds));
+    VEC_LAUNCH(K_DECODE_SPLIT, (decode_split_mfma_kernel<D, G>), grid, dim3(DT_), lds, stream, p);
+  } else {
+    VEC_LAUNCH(K_DECODE_SPLIT, (decode_split_kernel<T, D, G>), grid, dim3(DT_), 0, stream, p);
+  }
   VEC_LAUNCH(K_DECODE_COMBINE, (decode_combine_kernel<T, D, G>), dim3(c.n_kv_heads, c.batch), dim3(256), 0, stream, p);
   VEC_HIP(hipGetLastError());
   return VECTOR_OK;
@@ -371,7 +610,8 @@ int launch_decode_attn(const vector_cache& c, const void* q, float scale, void* 
   p.q = q; p.k_ret = c.k_ret; p.v_ret = c.v_ret; p.k_apx = c.k_apx; p.W = c.W; p.len_retain = c.len_retain;
   p.out = out; p.part = reinterpret_cast<float*>(ws);
   p.B = c.batch; p.Hq = c.n_q_heads; p.Hkv = c.n_kv_heads; p.cap_retain = c.cap_retain; p.n_approx = c.n_approx;
-  pick_splits(c.batch, c.n_kv_heads, c.cap_retain, c.n_approx, p.splits_ret, p.splits_apx);
+  pick_splits(c.dtype == VECTOR_BF16 ? kTargetWorkgroupsMfma : kTargetWorkgroups, c.batch, c.n_kv_heads, c.cap_retain, c.n_approx,
+              p.splits_ret, p.splits_apx);
   p.w_sh = c.w_shared ? 0 : (int64_t)c.head_dim * c.head_dim;
   p.c2 = scale * kLog2e;
   if (c.dtype == VECTOR_BF16) {
