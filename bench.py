@@ -172,11 +172,9 @@ def main() -> None:
             parts = line.split()
             if len(parts) == 2 and parts[0] == dominant:
                 traffic = int(parts[1])
-    event_overhead_us = vb.vector_timing_event_overhead(50, streams[0]) * 1e3
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(dom_gbs, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(dom_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "bytes_per_launch": int(dom_bytes), "avg_us": kernels[dominant]["avg_us"],
-                "event_overhead_us": round(event_overhead_us, 2),
                 "pass_alg_bytes_per_layer": int(pass_bytes),
                 "pass_frac_of_hbm_peak": round(pass_bytes * cfg.layers / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
     # MFMA work of the pass (both softmax passes and the residual contraction)
@@ -184,6 +182,25 @@ def main() -> None:
     flops_layer = H * n * (2 * 2 * G * cfg.window * d + 2 * d * d)
     mfma_tflops = flops_layer * cfg.layers / (ms_per_step * 1e-3) / 1e12
     log(f"kernels: {json.dumps(kernels)} (sum {sum_us:.1f} us per layer)")
+
+    # The reconstruction contraction with memory out of the picture: the residual kernel re-runs
+    # each tile's arithmetic `repeat` times on operands it already holds; the time added per
+    # extra repeat is one pass of the contraction code at the rate the matrix cores sustain.
+    def probe_ms(repeat, launches=10):
+        x = layers[0]
+        o = outs[0]
+        vb.vector_probe_residual_mfma(shape, x["k"], x["v"], x["w_cal"], o.eps, repeat)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(launches):
+            vb.vector_probe_residual_mfma(shape, x["k"], x["v"], x["w_cal"], o.eps, repeat)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / launches * 1e3
+    r_hi = 17
+    t_lo, t_hi = probe_ms(1), probe_ms(r_hi)
+    res_flops = H * n * 2 * d * d
+    iso_tflops = res_flops / ((t_hi - t_lo) / (r_hi - 1) * 1e-3) / 1e12
+    log(f"residual contraction probe: repeat 1 {t_lo * 1e3:.1f} us, repeat {r_hi} {t_hi * 1e3:.1f} us -> {iso_tflops:.0f} TFLOP/s isolated")
 
     # ---- decode attention over compressed caches ----
     decode = None
@@ -222,7 +239,9 @@ def main() -> None:
         "roofline": roofline,
         "kernels": kernels,
         "mfma": {"achieved_TFLOPs": round(mfma_tflops, 1), "peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS,
-                 "frac": round(mfma_tflops / MFMA_BF16_PEAK_TFLOPS, 4)},
+                 "frac": round(mfma_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+                 "residual_contraction_isolated_TFLOPs": round(iso_tflops, 1),
+                 "residual_contraction_isolated_frac": round(iso_tflops / MFMA_BF16_PEAK_TFLOPS, 4)},
         "decode": decode,
         "cpu_baseline": cpu,
     }

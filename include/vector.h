@@ -171,9 +171,16 @@ VECTOR_API int vector_timing_enable(int on);
 VECTOR_API int vector_timing_kernels(void);
 VECTOR_API const char* vector_timing_name(int kernel_id);
 VECTOR_API int vector_timing_read(int kernel_id, double* total_ms, int64_t* launches);
-/* What the event pair itself measures: the average HIP-event duration around an empty
- * one-wave kernel on `stream`, over `launches` launches (waits for each). */
-VECTOR_API int vector_timing_event_overhead(void* stream, int launches, double* avg_ms);
+
+/* Diagnostic: the reconstruction contraction of Section 3.2 Step 2 (v_hat = k W, then the
+ * squared distance to v) with memory out of the picture.  Same arguments, layout and
+ * arithmetic as vector_residual for bf16 inputs, but every workgroup runs the arithmetic
+ * of each tile `repeat` times on the operands it already holds in registers and LDS, so
+ * (time(repeat = r) - time(repeat = 1)) / (r - 1) is one pass of the contraction code at
+ * the rate the matrix cores sustain when they are not waiting for HBM.  eps receives the
+ * same values as vector_residual.  VECTOR_ERR_DTYPE for fp32 inputs. */
+VECTOR_API int vector_probe_residual_mfma(const vector_shape* shape, const void* k, const void* v, const void* W,
+                               float* eps, int32_t repeat, void* stream);
 
 #ifdef __cplusplus
 }

@@ -21,7 +21,7 @@ EXPORTS = (
     "vector_strerror", "vector_score", "vector_residual", "vector_score_residual", "vector_route",
     "vector_compact", "vector_decode_attn",
     "vector_timing_enable", "vector_timing_kernels", "vector_timing_name", "vector_timing_read",
-    "vector_timing_event_overhead",
+    "vector_probe_residual_mfma",
 )
 
 
@@ -81,7 +81,7 @@ def lib() -> C.CDLL:
         L.vector_timing_name.argtypes = [C.c_int]
         L.vector_timing_name.restype = C.c_char_p
         L.vector_timing_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
-        L.vector_timing_event_overhead.argtypes = [vp, C.c_int, C.POINTER(C.c_double)]
+        L.vector_probe_residual_mfma.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, i32, vp]
         for name in EXPORTS:
             if getattr(L, name).restype is C.c_int:
                 pass
@@ -185,8 +185,6 @@ def vector_timing_read() -> dict:
     return out
 
 
-def vector_timing_event_overhead(launches: int = 50, stream=None) -> float:
-    """Average HIP-event duration (ms) around an empty kernel: what the event pair itself costs."""
-    ms = C.c_double()
-    _check(lib().vector_timing_event_overhead(_stream(stream), launches, C.byref(ms)), "vector_timing_event_overhead")
-    return ms.value
+def vector_probe_residual_mfma(shape: Shape, k, v, W, eps, repeat: int, stream=None) -> None:
+    _check(lib().vector_probe_residual_mfma(C.byref(shape), _ptr(k), _ptr(v), _ptr(W), _ptr(eps), repeat,
+                                            _stream(stream)), "vector_probe_residual_mfma")

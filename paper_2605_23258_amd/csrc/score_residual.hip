@@ -44,6 +44,7 @@ struct PassParams {
   float2* part;         // [Hkv, R_pad, n_chunks]  (max, sum-exp), log2 domain
   float* mass;          // [Hkv, n]
   float* eps;           // [Hkv, n]
+  int repeat;           // probe kernels only: times each tile's arithmetic is run on the same registers
 };
 
 template <typename T, int D> struct Tile {
@@ -300,7 +301,9 @@ __device__ __forceinline__ void load_v_subtile(chunk_t* vf, const T* v_head, int
   for (int i = 0; i < Tile<T, D>::VP; ++i) vf[i] = load_chunk(row + i * Tile<T, D>::E);
 }
 
-template <typename T, int D, int NT, bool DO_MASS, bool DO_RES>
+// PROBE: the tile loop re-runs each tile's arithmetic p.repeat times on the operands it already
+// holds (no further loads), to time the contraction code with memory out of the picture.
+template <typename T, int D, int NT, bool DO_MASS, bool DO_RES, bool PROBE = false>
 __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p) {
   using TL = Tile<T, D>;
   constexpr int NW = NT / kWave;
@@ -505,7 +508,9 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p) {
       VEC_PIN(nx, e);
     }
   };
+  int rep = 0;
   auto load_next = [&](int tn) {
+    if (PROBE && rep + 1 < p.repeat) return;
     if (tn < c_end) {                    // every MFMA of the tile is issued: fetch the next keys
       load_k_subtile<T, D>(kf0, k_head, p.k_st, tn, p.n, lane);
       load_k_subtile<T, D>(kf1, k_head, p.k_st, tn + 32, p.n, lane);
@@ -514,7 +519,7 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p) {
 
   while (t0 < c_end) {
     const int tn = t0 + kStep;
-    if (DO_RES) {                        // values arrive while the score part computes
+    if (DO_RES && (!PROBE || rep == 0)) {   // values arrive while the score part computes
       load_v_subtile<T, D>(vf0, v_head, p.v_st, t0, p.n, lane);
       load_v_subtile<T, D>(vf1, v_head, p.v_st, t0 + 32, p.n, lane);
     }
@@ -560,6 +565,8 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p) {
       const int t = t0 + lane;               // lanes 0..31 -> subtile 0, 32..63 -> subtile 1
       if (t < c_end) p.eps[(size_t)h * p.n + t] = half ? e1 : e0;
     }
+    if (PROBE && ++rep < p.repeat) continue;
+    rep = 0;
     t0 = tn;
   }
 }
@@ -649,7 +656,7 @@ static int run_score_residual(const vector_shape& s, const void* q, const void* 
   int rc = make_plan<T, D>(s, do_mass, do_res, plan);
   if (rc != VECTOR_OK) return rc;
   PassParams& p = plan.pp;
-  p.q = q; p.k = k; p.v = v; p.W = W; p.eps = eps;
+  p.q = q; p.k = k; p.v = v; p.W = W; p.eps = eps; p.repeat = 1;
   unsigned char* w8 = reinterpret_cast<unsigned char*>(ws);
   p.part = reinterpret_cast<float2*>(w8);
   w8 += align_up((size_t)s.n_kv_heads * p.n_chunks * p.R_pad * sizeof(float2), 256);
@@ -679,6 +686,29 @@ static int run_score_residual(const vector_shape& s, const void* q, const void* 
                        p.mass, score, s.seq_len, p.n_prefix, s.pool_kernel);
   VEC_HIP(hipGetLastError());
   return VECTOR_OK;
+}
+
+template <typename T, int D>
+static int run_residual_probe(const vector_shape& s, const void* k, const void* v, const void* W, float* eps, int repeat,
+                              hipStream_t stream) {
+  Plan plan;
+  int rc = make_plan<T, D>(s, false, true, plan);
+  if (rc != VECTOR_OK) return rc;
+  PassParams& p = plan.pp;
+  p.q = nullptr; p.k = k; p.v = v; p.W = W; p.eps = eps; p.part = nullptr; p.mass = nullptr; p.repeat = repeat;
+  auto k2 = mass_residual_kernel<T, D, kThreads, false, true, true>;
+  VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k2), plan.lds_pass2));
+  VEC_LAUNCH(K_MASS_RESIDUAL, k2, dim3(p.n_chunks, s.n_kv_heads), dim3(kThreads), plan.lds_pass2, stream, p);
+  VEC_HIP(hipGetLastError());
+  return VECTOR_OK;
+}
+
+int launch_residual_probe(const vector_shape& s, const void* k, const void* v, const void* W, float* eps, int repeat,
+                          hipStream_t stream) {
+  if (s.dtype != VECTOR_BF16) return VECTOR_ERR_DTYPE;
+  if (s.head_dim == 128) return run_residual_probe<bf16_t, 128>(s, k, v, W, eps, repeat, stream);
+  if (s.head_dim == 64) return run_residual_probe<bf16_t, 64>(s, k, v, W, eps, repeat, stream);
+  return VECTOR_ERR_SHAPE;
 }
 
 int launch_score_residual(const vector_shape& s, const void* q, const void* k, const void* v, const void* W,

@@ -9,7 +9,6 @@
 namespace vec {
 
 namespace {
-__global__ void empty_kernel() {}
 struct Span { hipEvent_t start, stop; };
 struct Slot {
   std::vector<Span> spans;     // recorded since the last read
@@ -54,30 +53,6 @@ int vector_timing_kernels(void) { return vec::K_COUNT; }
 
 const char* vector_timing_name(int kernel_id) {
   return (kernel_id >= 0 && kernel_id < vec::K_COUNT) ? vec::kNames[kernel_id] : "";
-}
-
-int vector_timing_event_overhead(void* stream, int launches, double* avg_ms) {
-  if (launches < 1 || launches > 4096 || !avg_ms) return VECTOR_ERR_ARG;
-  hipStream_t st = (hipStream_t)stream;
-  // back to back, as in a timed run: the queue stays busy and no launch pays a cold start
-  std::vector<hipEvent_t> ev(2 * (size_t)launches);
-  for (hipEvent_t& e : ev)
-    if (hipEventCreate(&e) != hipSuccess) return VECTOR_ERR_HIP;
-  for (int i = 0; i < launches; ++i) {
-    hipEventRecord(ev[2 * i], st);
-    hipLaunchKernelGGL(vec::empty_kernel, dim3(1), dim3(64), 0, st);
-    hipEventRecord(ev[2 * i + 1], st);
-  }
-  if (hipEventSynchronize(ev.back()) != hipSuccess) return VECTOR_ERR_HIP;
-  double sum = 0.0;
-  for (int i = 0; i < launches; ++i) {
-    float ms = 0.f;
-    hipEventElapsedTime(&ms, ev[2 * i], ev[2 * i + 1]);
-    sum += ms;
-  }
-  for (hipEvent_t& e : ev) hipEventDestroy(e);
-  *avg_ms = sum / launches;
-  return VECTOR_OK;
 }
 
 int vector_timing_read(int kernel_id, double* total_ms, int64_t* launches) {

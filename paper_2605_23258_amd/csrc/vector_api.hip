@@ -104,6 +104,16 @@ int vector_residual(const vector_shape* s, const void* k, const void* v, const v
   return vec::launch_score_residual(t, nullptr, k, v, W, nullptr, eps, nullptr, (hipStream_t)stream);
 }
 
+int vector_probe_residual_mfma(const vector_shape* s, const void* k, const void* v, const void* W, float* eps,
+                               int32_t repeat, void* stream) {
+  int rc = check_shape(s, false);
+  if (rc) return rc;
+  if (!k || !v || !W || !eps || !aligned16(k) || !aligned16(v) || !aligned16(W) || repeat < 1) return VECTOR_ERR_ARG;
+  vector_shape t = *s;
+  if (t.window < 1 || t.window > t.seq_len) t.window = 1;
+  return vec::launch_residual_probe(t, k, v, W, eps, repeat, (hipStream_t)stream);
+}
+
 int vector_score_residual(const vector_shape* s, const void* q_win, const void* k, const void* v, const void* W,
                           float* score, float* eps, void* ws, size_t ws_bytes, void* stream) {
   int rc = check_shape(s, true);

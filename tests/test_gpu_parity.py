@@ -80,6 +80,20 @@ def test_score_and_residual(name):
     close(eps2.cpu().numpy(), ref_eps, "eps (fused)")
 
 
+@pytest.mark.parametrize("name", ["bf16_d128_ragged", "bf16_d64"])
+def test_residual_probe_matches_oracle(name):
+    """The contraction probe repeats each tile's arithmetic on resident operands; its eps output
+    is still the residual, whatever the repeat count."""
+    cfg, li, dev, wide = _inputs(name)
+    shape = pl.shape_of(cfg)
+    ref_eps = vo.residual(wide["k"], wide["v"], wide["w_cal"])
+    for repeat in (1, 3):
+        eps = torch.full((cfg.n_kv_heads, cfg.seq_len), -1.0, device="cuda:0")
+        vb.vector_probe_residual_mfma(shape, dev["k"], dev["v"], dev["w_cal"], eps, repeat)
+        torch.cuda.synchronize()
+        close(eps.cpu().numpy(), ref_eps, f"eps (probe, repeat {repeat})")
+
+
 def _route_gpu(score, eps, n_pool, n_approx):
     H, n = score.shape
     shape = vb.Shape(n_q_heads=H, n_kv_heads=H, head_dim=64, seq_len=n, window=1, pool_kernel=1, dtype=0)
