@@ -1,0 +1,152 @@
+"""GPU tests of what the C header promises beyond the packed default layout: strided
+K/V views, one W shared by all heads, and error returns that leave outputs untouched."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import vector_oracle as vo
+from paper_2605_23258_amd import binding as vb
+from paper_2605_23258_amd import datagen as dg
+from paper_2605_23258_amd import pipeline as pl
+
+pytestmark = pytest.mark.gpu
+ATOL, RTOL = 1e-3, 2e-3
+
+
+def close(got, ref, what):
+    err = np.abs(np.asarray(got, np.float64) - np.asarray(ref, np.float64))
+    bad = err > ATOL + RTOL * np.abs(ref)
+    assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} outside tolerance, max err {err.max():.3e}"
+
+
+def _layer(**over):
+    cfg = dg.scaled(dg.CONFIGS["cfg2"], **over)
+    return cfg, dg.make_layer(cfg, 0)
+
+
+def test_token_major_interleaved_kv_layout():
+    """K and V live in one [n, Hkv, 2, d] buffer (token-major, K and V of a head adjacent):
+    every entry point that takes strides reads the same logical tensors as the packed layout."""
+    cfg, li = _layer(seq_len=1500, n_kv_heads=2, n_q_heads=8, window=16)
+    H, n, d = cfg.n_kv_heads, cfg.seq_len, cfg.head_dim
+    n_r, n_a, n_p = cfg.counts()
+    fused = np.zeros((n, H, 2, d), np.uint16)
+    fused[:, :, 0] = np.transpose(li.k, (1, 0, 2))
+    fused[:, :, 1] = np.transpose(li.v, (1, 0, 2))
+    buf = pl.to_device(fused)
+    k_view, v_view = buf[:, :, 0], buf[:, :, 1]                 # views only: pointers into buf
+    shape = pl.shape_of(cfg)
+    shape.k_stride_head = shape.v_stride_head = 2 * d
+    shape.k_stride_tok = shape.v_stride_tok = H * 2 * d
+    q, W = pl.to_device(li.q_win), pl.to_device(li.w_cal)
+    ws = pl.alloc_workspace(vb.vector_workspace_bytes(shape, n_p, n_a, 1))
+    score = torch.empty((H, n), device="cuda:0")
+    eps = torch.empty((H, n), device="cuda:0")
+    vb.vector_score_residual(shape, q, k_view, v_view, W, score, eps, ws)
+    torch.cuda.synchronize()
+    wide = {x: dg.widen(getattr(li, x)) for x in ("q_win", "k", "v", "w_cal")}
+    ref_s = vo.score(wide["q_win"], wide["k"], cfg.window, cfg.pool_kernel)
+    ref_e = vo.residual(wide["k"], wide["v"], wide["w_cal"])
+    w = cfg.window
+    close(score.cpu().numpy()[:, : n - w].astype(np.float64) * n, ref_s[:, : n - w].astype(np.float64) * n, "n*score (strided)")
+    close(eps.cpu().numpy(), ref_e, "eps (strided)")
+    # separate entry points on the same views
+    score1 = torch.empty((H, n), device="cuda:0")
+    eps1 = torch.empty((H, n), device="cuda:0")
+    vb.vector_score(shape, q, k_view, score1, ws)
+    vb.vector_residual(shape, k_view, v_view, W, eps1, ws)
+    torch.cuda.synchronize()
+    close(score1.cpu().numpy()[:, : n - w].astype(np.float64) * n, ref_s[:, : n - w].astype(np.float64) * n, "n*score (strided, own call)")
+    close(eps1.cpu().numpy(), ref_e, "eps (strided, own call)")
+    # compaction gathers from the strided source, bit for bit
+    tier, idx_r, idx_a = vo.route(score.cpu().numpy(), eps.cpu().numpy(), n_p, n_a)
+    cap = n_r + 3
+    k_ret = torch.zeros((H, cap, d), dtype=torch.bfloat16, device="cuda:0")
+    v_ret = torch.zeros_like(k_ret)
+    k_apx = torch.zeros((H, n_a, d), dtype=torch.bfloat16, device="cuda:0")
+    vb.vector_compact(shape, k_view, v_view, pl.to_device(idx_r.astype(np.int32)), pl.to_device(idx_a.astype(np.int32)),
+                      n_r, n_a, k_ret, v_ret, k_apx, cap)
+    torch.cuda.synchronize()
+    rk, rv, ra = vo.compact(li.k, li.v, idx_r, idx_a)
+    assert np.array_equal(pl.to_host(k_ret)[:, :n_r], rk) and np.array_equal(pl.to_host(v_ret)[:, :n_r], rv)
+    assert np.array_equal(pl.to_host(k_apx), ra)
+    assert not pl.to_host(k_ret)[:, n_r:].any() and not pl.to_host(v_ret)[:, n_r:].any(), "rows past n_retain are the caller's"
+
+
+def test_one_map_shared_by_all_heads():
+    cfg, li = _layer(seq_len=640, n_kv_heads=4, n_q_heads=8, window=8)
+    H, n, d = cfg.n_kv_heads, cfg.seq_len, cfg.head_dim
+    W1 = li.w_cal[2:3]                                           # one [d, d] map
+    shape = pl.shape_of(cfg)
+    shape.w_shared = 1
+    eps = torch.empty((H, n), device="cuda:0")
+    vb.vector_residual(shape, pl.to_device(li.k), pl.to_device(li.v), pl.to_device(W1), eps)
+    torch.cuda.synchronize()
+    Wb = np.broadcast_to(dg.widen(W1), (H, d, d))
+    close(eps.cpu().numpy(), vo.residual(dg.widen(li.k), dg.widen(li.v), Wb), "eps (shared W)")
+    # decode with the shared map
+    B, Hq, n_r, n_a = 2, cfg.n_q_heads, 40, 50
+    rng = np.random.default_rng(3)
+    k_ret = dg.f32_to_bf16_bits(rng.standard_normal((B, H, n_r, d)).astype(np.float32))
+    v_ret = dg.f32_to_bf16_bits(rng.standard_normal((B, H, n_r, d)).astype(np.float32))
+    k_apx = dg.f32_to_bf16_bits(rng.standard_normal((B, H, n_a, d)).astype(np.float32))
+    q = dg.f32_to_bf16_bits(rng.standard_normal((B, Hq, d)).astype(np.float32))
+    t = [pl.to_device(x) for x in (k_ret, v_ret, k_apx, W1, q)]
+    length = torch.full((B,), n_r, dtype=torch.int32, device="cuda:0")
+    cache = vb.Cache(batch=B, n_q_heads=Hq, n_kv_heads=H, head_dim=d, dtype=vb.VECTOR_BF16, cap_retain=n_r, n_approx=n_a,
+                     w_shared=1)
+    cache.len_retain, cache.k_ret, cache.v_ret, cache.k_apx, cache.W = (length.data_ptr(), t[0].data_ptr(), t[1].data_ptr(),
+                                                                      t[2].data_ptr(), t[3].data_ptr())
+    ws = pl.alloc_workspace(vb.vector_workspace_bytes(pl.shape_of(cfg), n_r + n_a, n_a, B))
+    out = torch.empty((B, Hq, d), dtype=torch.bfloat16, device="cuda:0")
+    scale = 1.0 / np.sqrt(d)
+    vb.vector_decode_attn(cache, t[4], scale, out, ws)
+    torch.cuda.synchronize()
+    ref = vo.decode_attn(dg.widen(q), dg.widen(k_ret), dg.widen(v_ret), np.full(B, n_r), dg.widen(k_apx), Wb, scale)
+    err = np.abs(dg.widen(pl.to_host(out)) - ref)
+    assert (err <= ATOL + (RTOL + 2.0 ** -8) * np.abs(ref)).all(), f"max err {err.max():.3e}"
+
+
+def test_errors_are_reported_before_any_launch():
+    cfg, li = _layer(seq_len=256, n_kv_heads=1, n_q_heads=4, window=8)
+    H, n = cfg.n_kv_heads, cfg.seq_len
+    n_r, n_a, n_p = cfg.counts()
+    dev = {x: pl.to_device(getattr(li, x)) for x in ("q_win", "k", "v", "w_cal")}
+    shape = pl.shape_of(cfg)
+    ws = pl.alloc_workspace(vb.vector_workspace_bytes(shape, n_p, n_a, 1))
+    sentinel = 123.0
+    score = torch.full((H, n), sentinel, device="cuda:0")
+    eps = torch.full((H, n), sentinel, device="cuda:0")
+
+    def code_of(fn):
+        with pytest.raises(vb.VectorError) as ei:
+            fn()
+        return ei.value.code
+
+    def with_shape(**kw):
+        s = pl.shape_of(cfg)
+        for k, v in kw.items():
+            setattr(s, k, v)
+        return s
+
+    run = lambda s, w=ws: vb.vector_score_residual(s, dev["q_win"], dev["k"], dev["v"], dev["w_cal"], score, eps, w)
+    assert code_of(lambda: run(with_shape(head_dim=96))) == vb.VECTOR_ERR_SHAPE
+    assert code_of(lambda: run(with_shape(dtype=7))) == vb.VECTOR_ERR_DTYPE
+    assert code_of(lambda: run(with_shape(window=n + 1))) == vb.VECTOR_ERR_SHAPE
+    assert code_of(lambda: run(with_shape(pool_kernel=4))) == vb.VECTOR_ERR_SHAPE
+    assert code_of(lambda: run(with_shape(n_q_heads=3, n_kv_heads=2))) == vb.VECTOR_ERR_SHAPE
+    assert code_of(lambda: run(with_shape(k_stride_tok=cfg.head_dim - 8))) == vb.VECTOR_ERR_SHAPE
+    assert code_of(lambda: run(shape, ws[:256])) == vb.VECTOR_ERR_WORKSPACE        # too small
+    assert code_of(lambda: run(shape, ws[8:])) == vb.VECTOR_ERR_WORKSPACE          # misaligned
+    assert code_of(lambda: vb.vector_score_residual(shape, dev["q_win"], None, dev["v"], dev["w_cal"], score, eps, ws)) == vb.VECTOR_ERR_ARG
+    assert code_of(lambda: vb.vector_score_residual(shape, dev["q_win"], dev["k"].view(torch.int16).flatten()[1:], dev["v"],
+                                                    dev["w_cal"], score, eps, ws)) == vb.VECTOR_ERR_ARG   # 2-byte offset
+    tier = torch.full((H, n), 77, dtype=torch.uint8, device="cuda:0")
+    idx_r = torch.full((H, n), -5, dtype=torch.int32, device="cuda:0")
+    idx_a = torch.full((H, n), -5, dtype=torch.int32, device="cuda:0")
+    assert code_of(lambda: vb.vector_route(H, n, score, eps, n + 1, 0, tier, idx_r, idx_a, ws)) == vb.VECTOR_ERR_ARG
+    assert code_of(lambda: vb.vector_route(H, n, score, eps, 10, 11, tier, idx_r, idx_a, ws)) == vb.VECTOR_ERR_ARG
+    torch.cuda.synchronize()
+    assert (score == sentinel).all() and (eps == sentinel).all(), "a failing call must not write"
+    assert (tier == 77).all() and (idx_r == -5).all() and (idx_a == -5).all()
