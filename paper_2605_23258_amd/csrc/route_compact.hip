@@ -36,6 +36,7 @@ struct RouteShared {
   int hist[kBins];
   int wave_sum[RW];
   int wave_tot[2][RW];
+  uint32_t tile_wave[(KC / EPT) * RW];   // register-cached ordered pass: totals, then exclusive prefixes, by (tile, wave)
   int digit, above;
 };
 
@@ -351,45 +352,60 @@ __device__ void radix_select_regs(const uint32_t (&key)[KC], ValidFn valid, int 
   __syncthreads();
 }
 
-// Ordered pass over keys held in registers; see ordered_select.  emit(slot, i, selected, rank).
+// Ordered pass over keys held in registers; see ordered_select.  emit(slot, selected, rank).
+// All tiles are scanned together: every wave scans each of its tiles, one wave turns the
+// (tile, wave) totals into exclusive prefixes, and the ranks follow with two barriers in all.
+// Counts travel packed, "greater" in the high half-word and "equal" in the low one (each at
+// most RT * KC = 32768, so neither half overflows).
 template <typename ValidFn, typename EmitFn>
 __device__ void ordered_select_regs(const uint32_t (&key)[KC], ValidFn valid, int n_tiles, uint32_t thr, int quota,
                                     EmitFn emit, RouteShared& sh) {
+  constexpr int NTL = KC / EPT;
+  static_assert(NTL * RW == 2 * kWave, "one wave, two entries per lane, covers the (tile, wave) table");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  int carry_gt = 0, carry_eq = 0;
+  auto cls_of = [&](int s) { return valid(s) ? (key[s] > thr ? 2 : (key[s] == thr ? 1 : 0)) : 0; };
+  uint32_t before[NTL];                         // packed counts of this wave's earlier lanes, per tile
 #pragma unroll
-  for (int t = 0; t < KC / EPT; ++t) {
+  for (int t = 0; t < NTL; ++t) {
+    uint32_t packed = 0;
     if (t < n_tiles) {
-      int cls[EPT], packed = 0;
 #pragma unroll
       for (int j = 0; j < EPT; ++j) {
-        const uint32_t kk = key[t * EPT + j];
-        cls[j] = valid(t * EPT + j) ? (kk > thr ? 2 : (kk == thr ? 1 : 0)) : 0;
-        packed += (cls[j] == 2 ? 0x10000 : 0) + (cls[j] == 1 ? 1 : 0);
+        const int c = cls_of(t * EPT + j);
+        packed += (c == 2 ? 0x10000u : 0u) + (c == 1 ? 1u : 0u);
       }
-      const int incl = wave_incl_scan_i(packed, lane);
-      if (lane == 63) sh.wave_tot[t & 1][wave] = incl;
-      __syncthreads();
-      int pre = incl - packed, tile_tot = 0;
-      for (int wv = 0; wv < RW; ++wv) {
-        const int x = sh.wave_tot[t & 1][wv];
-        if (wv < wave) pre += x;
-        tile_tot += x;
-      }
-      int pre_gt = carry_gt + (pre >> 16), pre_eq = carry_eq + (pre & 0xffff);
-      carry_gt += tile_tot >> 16;
-      carry_eq += tile_tot & 0xffff;
+    }
+    const uint32_t incl = (uint32_t)wave_incl_scan_i((int)packed, lane);
+    before[t] = incl - packed;
+    if (lane == 63) sh.tile_wave[t * RW + wave] = incl;
+  }
+  __syncthreads();
+  if (wave == 0) {
+    const uint32_t x0 = sh.tile_wave[2 * lane], x1 = sh.tile_wave[2 * lane + 1];
+    const uint32_t incl = (uint32_t)wave_incl_scan_i((int)(x0 + x1), lane);
+    sh.tile_wave[2 * lane] = incl - x0 - x1;
+    sh.tile_wave[2 * lane + 1] = incl - x1;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int t = 0; t < NTL; ++t) {
+    if (t < n_tiles) {
+      const uint32_t pre = sh.tile_wave[t * RW + wave] + before[t];
+      int pre_gt = (int)(pre >> 16), pre_eq = (int)(pre & 0xffffu);
 #pragma unroll
       for (int j = 0; j < EPT; ++j) {
-        if (valid(t * EPT + j)) {
-          const bool sel = cls[j] == 2 || (cls[j] == 1 && pre_eq < quota);
-          emit(t * EPT + j, sel, pre_gt + min(pre_eq, quota));
-          pre_gt += cls[j] == 2;
-          pre_eq += cls[j] == 1;
+        const int s = t * EPT + j;
+        if (valid(s)) {
+          const int c = cls_of(s);
+          const bool sel = c == 2 || (c == 1 && pre_eq < quota);
+          emit(s, sel, pre_gt + min(pre_eq, quota));
+          pre_gt += c == 2;
+          pre_eq += c == 1;
         }
       }
     }
   }
+  __syncthreads();                              // the table is free for the next call
 }
 
 __global__ __launch_bounds__(RT) void route_cached_kernel(const float* __restrict__ score, const float* __restrict__ eps,
@@ -421,12 +437,35 @@ __global__ __launch_bounds__(RT) void route_cached_kernel(const float* __restric
   // Step 1: the pool is the n_pool tokens of highest score.  One round trip brings in every
   // score and residual this thread will need.
   uint32_t key[KC];
+  static_assert(EPT == 4, "a thread's tokens of one tile are one 16-byte load");
+  if ((n & 3) == 0 && ((reinterpret_cast<uintptr_t>(sc) | reinterpret_cast<uintptr_t>(ep)) & 15u) == 0) {
+    float4 s4[KC / EPT], e4[KC / EPT];
 #pragma unroll
-  for (int s = 0; s < KC; ++s) {
-    const int i = token_of(s);
-    const bool in = s / EPT < n_tiles && i < n;
-    key[s] = in ? float_key(sc[i]) : 0u;
-    if (s / EPT < n_tiles) side_lds[s * RT + threadIdx.x] = in ? ~float_key(ep[i]) : 0u;   // smaller residual, larger key
+    for (int t = 0; t < KC / EPT; ++t) {
+      const int i = token_of(t * EPT);
+      if (t < n_tiles && i < n) {               // n is a multiple of 4: all four tokens are inside
+        s4[t] = *reinterpret_cast<const float4*>(sc + i);
+        e4[t] = *reinterpret_cast<const float4*>(ep + i);
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < KC / EPT; ++t) {
+      const bool in = t < n_tiles && token_of(t * EPT) < n;
+      const float sv[EPT] = {s4[t].x, s4[t].y, s4[t].z, s4[t].w}, ev[EPT] = {e4[t].x, e4[t].y, e4[t].z, e4[t].w};
+#pragma unroll
+      for (int j = 0; j < EPT; ++j) {
+        key[t * EPT + j] = in ? float_key(sv[j]) : 0u;
+        if (t < n_tiles) side_lds[(t * EPT + j) * RT + threadIdx.x] = in ? ~float_key(ev[j]) : 0u;
+      }
+    }
+  } else {
+#pragma unroll
+    for (int s = 0; s < KC; ++s) {
+      const int i = token_of(s);
+      const bool in = s / EPT < n_tiles && i < n;
+      key[s] = in ? float_key(sc[i]) : 0u;
+      if (s / EPT < n_tiles) side_lds[s * RT + threadIdx.x] = in ? ~float_key(ep[i]) : 0u;   // smaller residual, larger key
+    }
   }
   uint32_t thr;
   int quota;
