@@ -15,10 +15,16 @@ then average-pooled along the sequence.
 Row convention throughout: v_hat = k @ W, i.e. W here is the transpose of the
 paper's column-convention W_OLS (footnote in Section 3.1).
 
+Keys cached after rotary position embedding (Section 3.1, "RoPE Decoupling") are
+turned back by the inverse rotation of their position before the value map is
+applied; attention logits always use the cached (rotated) keys.
+
 Pins (tests/test_oracle_*.py): softmax-row mass conservation, the q = 0 closed
 form, reduction to a textbook softmax, brute-force routing on tiny inputs, the
 truncated-Gaussian closed form of Example 1, planted-map recovery by the
-least-squares fit, the printed p_a table, and identities of decode attention.
+least-squares fit, the printed p_a table, identities of decode attention, and for
+the rotary un-rotation its dense block-rotation matrix, R^-1 R = I, the relative-
+position property of rotated dot products and a hand-computed quarter turn.
 Not pinned against the authors' own code (none is published with the paper):
 the scorer reading (mean vs sum, pooling pad, window handling) is this build's.
 """
@@ -123,12 +129,45 @@ def score(q_win: np.ndarray, k: np.ndarray, window: int, pool_kernel: int) -> np
 # ----------------------------------------------------------------------------
 # Step 2: reconstruction residual
 # ----------------------------------------------------------------------------
-def residual(k: np.ndarray, v: np.ndarray, w: np.ndarray) -> np.ndarray:
+def rope_unrotate(k_post: np.ndarray, pos: np.ndarray, inv_freq: np.ndarray, interleaved: bool = False) -> np.ndarray:
+    """Section 3.1, RoPE decoupling: R_m^{-1} applied to each cached key row.
+
+    R_m turns pair i of a row, (a_i, b_i), by the angle m * inv_freq[i]:
+    (a, b) -> (a cos - b sin, a sin + b cos); its inverse turns it back by the
+    same angle.  Pair i is (x[i], x[i + d/2]), or (x[2i], x[2i+1]) when
+    `interleaved`.  k_post [..., n, d], pos [..., n] (integers), inv_freq [d/2].
+    Returns float64."""
+    x = np.asarray(k_post, dtype=np.float64)
+    d = x.shape[-1]
+    ang = np.asarray(pos, dtype=np.float64)[..., None] * np.asarray(inv_freq, dtype=np.float64)
+    c, s_ = np.cos(ang), np.sin(ang)
+    if interleaved:
+        a, b = x[..., 0::2], x[..., 1::2]
+    else:
+        a, b = x[..., : d // 2], x[..., d // 2:]
+    a_pre = a * c + b * s_
+    b_pre = -a * s_ + b * c
+    out = np.empty_like(x)
+    if interleaved:
+        out[..., 0::2], out[..., 1::2] = a_pre, b_pre
+    else:
+        out[..., : d // 2], out[..., d // 2:] = a_pre, b_pre
+    return out
+
+
+def residual(k: np.ndarray, v: np.ndarray, w: np.ndarray, pos: np.ndarray = None, inv_freq: np.ndarray = None,
+             interleaved: bool = False) -> np.ndarray:
     """eps[h, t] = || v[h,t] - k[h,t] @ W[h] ||_2^2 (squared, un-normalised),
-    for every token; float32 as the routing consumes it."""
+    for every token; float32 as the routing consumes it.  With `inv_freq` the
+    keys are post-RoPE and are un-rotated by their positions first (pos [n] or
+    [H, n]; None = the row index)."""
     k = np.asarray(k, dtype=np.float64)
     v = np.asarray(v, dtype=np.float64)
     w = np.asarray(w, dtype=np.float64)
+    if inv_freq is not None:
+        if pos is None:
+            pos = np.arange(k.shape[1])
+        k = rope_unrotate(k, np.broadcast_to(pos, k.shape[:2]), inv_freq, interleaved)
     eps = np.empty(k.shape[:2])
     for h in range(k.shape[0]):
         diff = v[h] - k[h] @ w[h]
@@ -182,11 +221,15 @@ def compact(k: np.ndarray, v: np.ndarray, idx_retain: np.ndarray, idx_approx: np
 # decode attention over the packed cache, approximated values rebuilt as k @ W
 # ----------------------------------------------------------------------------
 def decode_attn(q: np.ndarray, k_ret: np.ndarray, v_ret: np.ndarray, len_retain: np.ndarray,
-                k_apx: np.ndarray, w: np.ndarray, scale: float) -> np.ndarray:
+                k_apx: np.ndarray, w: np.ndarray, scale: float, pos_apx: np.ndarray = None,
+                inv_freq: np.ndarray = None, interleaved: bool = False) -> np.ndarray:
     """q [B, Hq, d]; k_ret, v_ret [B, Hkv, cap, d] of which the first
     len_retain[b] rows are live; k_apx [B, Hkv, n_a, d]; W [Hkv, d, d].
     One softmax over retained and approximated tokens together;
-    out = sum_ret p_t v_t + sum_apx p_t (k_t @ W).  Returns float64 [B, Hq, d]."""
+    out = sum_ret p_t v_t + sum_apx p_t (k_t @ W).  With `inv_freq` the cached keys
+    are post-RoPE: logits use them as they are, and the rebuilt value of an
+    approximated token comes from its key un-rotated by its original position
+    pos_apx [B, Hkv, n_a].  Returns float64 [B, Hq, d]."""
     q = np.asarray(q, dtype=np.float64)
     k_ret = np.asarray(k_ret, dtype=np.float64)
     v_ret = np.asarray(v_ret, dtype=np.float64)
@@ -200,7 +243,10 @@ def decode_attn(q: np.ndarray, k_ret: np.ndarray, v_ret: np.ndarray, len_retain:
         length = int(len_retain[b])
         for h in range(n_kv):
             keys = np.concatenate([k_ret[b, h, :length], k_apx[b, h]], axis=0)
-            v_hat = k_apx[b, h] @ w[h]                    # rebuilt values
+            k_lin = k_apx[b, h]
+            if inv_freq is not None:
+                k_lin = rope_unrotate(k_lin, np.asarray(pos_apx)[b, h], inv_freq, interleaved)
+            v_hat = k_lin @ w[h]                          # rebuilt values
             vals = np.concatenate([v_ret[b, h, :length], v_hat], axis=0)
             for g in range(group):
                 qh = h * group + g

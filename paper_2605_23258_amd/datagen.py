@@ -162,16 +162,49 @@ def fit_w(k_cal: np.ndarray, v_cal: np.ndarray) -> np.ndarray:
     return out
 
 
-def make_layer(cfg: Config, layer: int = 0, sub: int = 0) -> LayerInputs:
-    """Inputs of one compression pass: one layer of one sequence (`sub` = sequence id)."""
+def rotary_inv_freq(head_dim: int, theta: float) -> np.ndarray:
+    """Angular frequency of pair i: theta^(-2i/d), float64 [d/2]."""
+    return np.asarray(theta, dtype=np.float64) ** (-np.arange(head_dim // 2, dtype=np.float64) * 2.0 / head_dim)
+
+
+def apply_rotary(x: np.ndarray, pos: np.ndarray, inv_freq: np.ndarray, interleaved: bool = False) -> np.ndarray:
+    """Rows of x [..., n, d] as a model with rotary position embedding would cache them:
+    pair i of row t turned forward by pos[t] * inv_freq[i].  float64 in, float64 out."""
+    x = np.asarray(x, dtype=np.float64)
+    d = x.shape[-1]
+    ang = np.asarray(pos, dtype=np.float64)[..., None] * inv_freq
+    c, s = np.cos(ang), np.sin(ang)
+    out = np.empty_like(x)
+    if interleaved:
+        a, b = x[..., 0::2], x[..., 1::2]
+        out[..., 0::2], out[..., 1::2] = a * c - b * s, a * s + b * c
+    else:
+        a, b = x[..., : d // 2], x[..., d // 2:]
+        out[..., : d // 2], out[..., d // 2:] = a * c - b * s, a * s + b * c
+    return out
+
+
+def make_layer(cfg: Config, layer: int = 0, sub: int = 0, rope_theta: Optional[float] = None,
+               rope_interleaved: bool = False, pos_offset: int = 0) -> LayerInputs:
+    """Inputs of one compression pass: one layer of one sequence (`sub` = sequence id).
+
+    With `rope_theta` the stored keys are post-RoPE: the values (and the calibrated map) belong
+    to the keys as drawn, and row t of the stored keys is that key turned by position
+    pos_offset + t.  `extra` then holds inv_freq (float64 [d/2]), the positions, and the flag."""
     H, d, n, w = cfg.n_kv_heads, cfg.head_dim, cfg.seq_len, cfg.window
     w_true = _rng(cfg.cfg_id, layer, _TAG_WTRUE, sub).standard_normal((H, d, d)) / np.sqrt(d)
     k, v, sigma, heavy = _draw_kv(cfg, layer, n, w_true, 0, sub)
     k_cal, v_cal, _, _ = _draw_kv(cfg, layer, cfg.cal_tokens, w_true, _TAG_CAL, sub)
     w_cal = fit_w(k_cal, v_cal)
     q = _rng(cfg.cfg_id, layer, _TAG_Q, sub).standard_normal((cfg.n_q_heads, w, d), dtype=np.float32)
+    extra = {}
+    if rope_theta is not None:
+        inv_freq = rotary_inv_freq(d, rope_theta)
+        pos = np.arange(n, dtype=np.int64) + pos_offset
+        k = apply_rotary(k, pos, inv_freq, rope_interleaved)
+        extra = {"inv_freq": inv_freq, "pos": pos.astype(np.int32), "interleaved": rope_interleaved}
     return LayerInputs(cfg, layer, _store(cfg, q), _store(cfg, k), _store(cfg, v), _store(cfg, w_cal),
-                       w_true, sigma, heavy)
+                       w_true, sigma, heavy, extra)
 
 
 def make_decode_step(cfg: Config, step: int, w_true_per_seq: Optional[np.ndarray] = None):
