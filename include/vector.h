@@ -172,6 +172,40 @@ VECTOR_API int vector_timing_kernels(void);
 VECTOR_API const char* vector_timing_name(int kernel_id);
 VECTOR_API int vector_timing_read(int kernel_id, double* total_ms, int64_t* launches);
 
+/* ---- keys cached after rotary position embedding -------------------------- */
+
+/* Section 3.1, "RoPE Decoupling": the value map is fitted on keys as projected, while a
+ * cache holds them after the rotary embedding of their position.  Wherever a value is
+ * rebuilt from a cached key (the residual of Step 2, the approximated rows of decode
+ * attention), the key is first turned back by its position; attention logits and
+ * importance scores use the cached keys unchanged.
+ * The rotation of a row at position m turns pair i by the angle m * inv_freq[i]:
+ * (a, b) -> (a cos - b sin, a sin + b cos). */
+typedef struct {
+  const double* inv_freq;    /* HOST memory, head_dim/2 values, radians per position;
+                                read during the call, not kept                          */
+  int32_t interleaved;       /* 0: pair i = (x[i], x[i + d/2]); 1: pair i = (x[2i], x[2i+1]) */
+  int32_t pos_offset;        /* added to every position                                */
+  const int32_t* positions;  /* device memory or NULL.  vector_*residual_rope: [n], the
+                                position of each row of k (NULL: the row index).
+                                vector_decode_attn_rope: [batch, Hkv, n_approx], the
+                                original position of each approximated row (NULL: the
+                                row index).                                             */
+} vector_rope;
+
+/* vector_residual / vector_score_residual on post-RoPE keys: same arguments, layouts,
+ * workspace and errors; eps[h,t] = || v[h,t] - (R^-1 k[h,t]) . W[h] ||^2, the score is
+ * that of vector_score on the same k.  VECTOR_ERR_ARG for a NULL rope or inv_freq. */
+VECTOR_API int vector_residual_rope(const vector_shape* shape, const void* k, const void* v, const void* W,
+                         const vector_rope* rope, float* eps, void* ws, size_t ws_bytes, void* stream);
+VECTOR_API int vector_score_residual_rope(const vector_shape* shape, const void* q_win, const void* k, const void* v,
+                               const void* W, const vector_rope* rope, float* score, float* eps, void* ws,
+                               size_t ws_bytes, void* stream);
+/* vector_decode_attn on a post-RoPE cache: out = sum_ret p_t v_t + sum_apx p_t ((R^-1 k_t) . W[h]),
+ * logits from the cached keys.  bf16 caches only (VECTOR_ERR_DTYPE otherwise). */
+VECTOR_API int vector_decode_attn_rope(const vector_cache* cache, const vector_rope* rope, const void* q, float scale,
+                            void* out, int32_t flags, void* ws, size_t ws_bytes, void* stream);
+
 /* Diagnostic: the reconstruction contraction of Section 3.2 Step 2 (v_hat = k W, then the
  * squared distance to v) with memory out of the picture.  Same arguments, layout and
  * arithmetic as vector_residual for bf16 inputs, but every workgroup runs the arithmetic

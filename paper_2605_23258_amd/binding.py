@@ -23,6 +23,7 @@ EXPORTS = (
     "vector_compact", "vector_decode_attn",
     "vector_timing_enable", "vector_timing_kernels", "vector_timing_name", "vector_timing_read",
     "vector_probe_residual_mfma",
+    "vector_residual_rope", "vector_score_residual_rope", "vector_decode_attn_rope",
 )
 
 
@@ -40,6 +41,22 @@ class Shape(C.Structure):
         ("v_stride_head", C.c_int64), ("v_stride_tok", C.c_int64),
         ("w_stride_head", C.c_int64), ("w_shared", C.c_int32), ("reserved2", C.c_int32),
     ]
+
+
+class Rope(C.Structure):
+    """vector_rope: inv_freq is HOST memory (keep the array it points into alive during the call)."""
+    _fields_ = [("inv_freq", C.POINTER(C.c_double)), ("interleaved", C.c_int32), ("pos_offset", C.c_int32),
+                ("positions", C.c_void_p)]
+
+
+def make_rope(inv_freq, positions=None, interleaved: bool = False, pos_offset: int = 0):
+    """(Rope, keep-alive) from a float64 host array of head_dim/2 frequencies and an optional
+    device int32 tensor of positions."""
+    import numpy as np
+    arr = np.ascontiguousarray(inv_freq, dtype=np.float64)
+    r = Rope(inv_freq=arr.ctypes.data_as(C.POINTER(C.c_double)), interleaved=int(bool(interleaved)),
+             pos_offset=int(pos_offset), positions=_ptr(positions))
+    return r, (arr, positions)
 
 
 class Cache(C.Structure):
@@ -83,6 +100,9 @@ def lib() -> C.CDLL:
         L.vector_timing_name.restype = C.c_char_p
         L.vector_timing_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         L.vector_probe_residual_mfma.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, i32, vp]
+        L.vector_residual_rope.argtypes = [C.POINTER(Shape), vp, vp, vp, C.POINTER(Rope), vp, vp, sz, vp]
+        L.vector_score_residual_rope.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, C.POINTER(Rope), vp, vp, vp, sz, vp]
+        L.vector_decode_attn_rope.argtypes = [C.POINTER(Cache), C.POINTER(Rope), vp, C.c_float, vp, i32, vp, sz, vp]
         for name in EXPORTS:
             if getattr(L, name).restype is C.c_int:
                 pass
@@ -189,3 +209,19 @@ def vector_timing_read() -> dict:
 def vector_probe_residual_mfma(shape: Shape, k, v, W, eps, repeat: int, stream=None) -> None:
     _check(lib().vector_probe_residual_mfma(C.byref(shape), _ptr(k), _ptr(v), _ptr(W), _ptr(eps), repeat,
                                             _stream(stream)), "vector_probe_residual_mfma")
+
+
+def vector_residual_rope(shape: Shape, k, v, W, rope: Rope, eps, ws=None, stream=None) -> None:
+    _check(lib().vector_residual_rope(C.byref(shape), _ptr(k), _ptr(v), _ptr(W), C.byref(rope), _ptr(eps), _ptr(ws),
+                                      _nbytes(ws), _stream(stream)), "vector_residual_rope")
+
+
+def vector_score_residual_rope(shape: Shape, q_win, k, v, W, rope: Rope, score, eps, ws, stream=None) -> None:
+    _check(lib().vector_score_residual_rope(C.byref(shape), _ptr(q_win), _ptr(k), _ptr(v), _ptr(W), C.byref(rope),
+                                            _ptr(score), _ptr(eps), _ptr(ws), _nbytes(ws), _stream(stream)),
+           "vector_score_residual_rope")
+
+
+def vector_decode_attn_rope(cache: Cache, rope: Rope, q, scale: float, out, ws, stream=None) -> None:
+    _check(lib().vector_decode_attn_rope(C.byref(cache), C.byref(rope), _ptr(q), scale, _ptr(out), 0, _ptr(ws),
+                                         _nbytes(ws), _stream(stream)), "vector_decode_attn_rope")

@@ -31,6 +31,14 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
   u += 0x7fffu + ((u >> 16) & 1u);
   return (uint16_t)(u >> 16);
 }
+// two floats -> two bf16 in one word (low half first), round to nearest even, in hardware
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  bf16x2 v;
+  v[0] = (__bf16)lo;
+  v[1] = (__bf16)hi;
+  return __builtin_bit_cast(uint32_t, v);
+}
 __device__ __forceinline__ void store_elem(float* p, float x) { *p = x; }
 __device__ __forceinline__ void store_elem(bf16_t* p, float x) { p->bits = f32_to_bf16_bits(x); }
 
@@ -116,6 +124,38 @@ __device__ __forceinline__ int wave_incl_scan_i(int x, int lane) {
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// ---------------------------------------------------------------------------
+// Rotary position embedding of cached keys (Section 3.1, RoPE decoupling): the value map
+// was fitted on keys as projected, so a cached key is turned back by its position before
+// the map is applied.  Frequencies travel as turns (cycles) per position, split into two
+// floats (48 bits together); position * frequency is reduced to its fractional turn with an
+// exact product (fma) so that the angle is good to about 2^-24 of a turn for any position
+// below 2^24.  The hardware sine and cosine take their argument in turns.
+// ---------------------------------------------------------------------------
+constexpr int kMaxRotaryPairs = 64;      // head_dim / 2 at head_dim = 128
+
+struct RopeParams {
+  float turns_hi[kMaxRotaryPairs];       // inv_freq[i] / (2 pi), leading 24 bits
+  float turns_lo[kMaxRotaryPairs];       // the next 24 bits
+  const int32_t* positions;              // device, or null: the row index
+  int32_t pos_offset;
+  int32_t interleaved;                   // 0: pair i = (x[i], x[i + d/2]); 1: pair i = (x[2i], x[2i + 1])
+};
+
+// (cos, sin) of position * frequency; pos_f = the position as a float (exact below 2^24)
+__device__ __forceinline__ void rotary_cos_sin(float pos_f, float t_hi, float t_lo, float& c, float& s) {
+  const float p = pos_f * t_hi;
+  const float err = fmaf(pos_f, t_hi, -p);                 // exact: the bits the product dropped
+  const float u = __builtin_amdgcn_fractf(p) + fmaf(pos_f, t_lo, err);
+  c = __builtin_amdgcn_cosf(u);
+  s = __builtin_amdgcn_sinf(u);
+}
+// the inverse rotation of one pair
+__device__ __forceinline__ void rotary_back(float a, float b, float c, float s, float& a_pre, float& b_pre) {
+  a_pre = fmaf(a, c, b * s);
+  b_pre = fmaf(b, c, -(a * s));
+}
 
 constexpr float kLog2e = 1.4426950408889634f;
 

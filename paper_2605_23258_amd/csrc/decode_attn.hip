@@ -46,6 +46,10 @@ constexpr int kTargetWorkgroups = 768;
 #define VEC_DEC_TARGET 1024
 #endif
 constexpr int kTargetWorkgroupsMfma = VEC_DEC_TARGET;   // bf16 kernel: two workgroups fit a CU
+#ifndef VEC_ROPE_APX_COST
+#define VEC_ROPE_APX_COST 3.0
+#endif
+constexpr double kRopeApxCost = VEC_ROPE_APX_COST;
 
 template <typename T> struct Unpack16;
 template <> struct Unpack16<bf16_t> {
@@ -280,8 +284,11 @@ template <int D> struct MfmaDecodeTile {
   static constexpr int kLdsBytes = DW * 2 * kTileBytes;
 };
 
-template <int D, int G>
-__global__ __launch_bounds__(DT_, 2) void decode_split_mfma_kernel(DecodeParams p) {
+// ROPE: the cached keys carry rotary position embedding.  Logits use them as cached; the
+// rows that stand in for values of approximated tokens are the keys turned back by their
+// original positions (rp.positions [B, Hkv, n_approx]), written to the second tile as bf16.
+template <int D, int G, bool ROPE>
+__global__ __launch_bounds__(DT_, 2) void decode_split_mfma_kernel(DecodeParams p, RopeParams rp) {
   using T = bf16_t;
   using TL = MfmaDecodeTile<D>;
   constexpr int NC = D / 16;               // 16-element steps of the score contraction
@@ -312,7 +319,7 @@ __global__ __launch_bounds__(DT_, 2) void decode_split_mfma_kernel(DecodeParams 
 
   unsigned char* k_tile = dec_lds + wave * 2 * TL::kTileBytes;
   unsigned char* v_tile = k_tile + TL::kTileBytes;
-  const unsigned char* r_tile = is_apx ? k_tile : v_tile;
+  const unsigned char* r_tile = (is_apx && !ROPE) ? k_tile : v_tile;
 
   // B operand of the score product: query row g on lane g, zero beyond G
   chunk_t qf[NC];
@@ -331,13 +338,56 @@ __global__ __launch_bounds__(DT_, 2) void decode_split_mfma_kernel(DecodeParams 
   float m_run = kNegBig, l_run = 0.f;
 
   const int ld_row = lane / TL::kPieces, ld_piece = lane % TL::kPieces;
+  const int32_t* pos_seg = (ROPE && is_apx && rp.positions) ? rp.positions + bh * p.n_approx : nullptr;
+  // For an approximated row under ROPE the second register set carries the row's position
+  // (in .x) instead of a value row.
   auto fetch = [&](uint4* kraw, uint4* vraw, int base) {
 #pragma unroll
     for (int i = 0; i < TL::kLoads; ++i) {
       const int r = min(base + i * TL::kRowsPerLoad + ld_row, seg_len - 1);   // clamped: never past the live rows
       kraw[i] = load_chunk(kseg + (size_t)r * D + ld_piece * 8);
       if (!is_apx) vraw[i] = load_chunk(vseg + (size_t)r * D + ld_piece * 8);
+      else if (ROPE) vraw[i].x = (uint32_t)((pos_seg ? pos_seg[r] : r) + rp.pos_offset);
     }
+  };
+  // the 16-byte piece of a cached key row, turned back by the row's position.  Pairs
+  // (i, i + d/2) sit kPieces/2 lanes apart in the same row; pairs (2i, 2i+1) in the same lane.
+  // this lane's piece always covers the same rotary pairs: their frequencies stay in registers
+  float t_hi[8], t_lo[8];
+  if (ROPE && is_apx) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int i = rp.interleaved ? (ld_piece * 8 + e) / 2 : (ld_piece % (TL::kPieces / 2)) * 8 + e;
+      t_hi[e] = rp.turns_hi[i];
+      t_lo[e] = rp.turns_lo[i];
+    }
+  }
+  auto unrotate_piece = [&](const uint4& raw, int pos) {
+    float f[8], g[8];
+    const float pf = (float)pos;
+    Unpack16<T>::run(raw, f);
+    if (!rp.interleaved) {
+      uint4 other;
+      other.x = __shfl_xor(raw.x, TL::kPieces / 2, kWave); other.y = __shfl_xor(raw.y, TL::kPieces / 2, kWave);
+      other.z = __shfl_xor(raw.z, TL::kPieces / 2, kWave); other.w = __shfl_xor(raw.w, TL::kPieces / 2, kWave);
+      Unpack16<T>::run(other, g);
+      const bool first = ld_piece < TL::kPieces / 2;          // holds the first member of its pairs
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float cs, sn;
+        rotary_cos_sin(pf, t_hi[e], t_lo[e], cs, sn);
+        // first member: a cos + b sin; second member: b cos - a sin
+        f[e] = first ? fmaf(f[e], cs, g[e] * sn) : fmaf(f[e], cs, -(g[e] * sn));
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; e += 2) {
+        float cs, sn;
+        rotary_cos_sin(pf, t_hi[e], t_lo[e], cs, sn);
+        rotary_back(f[e], f[e + 1], cs, sn, f[e], f[e + 1]);
+      }
+    }
+    return make_uint4(pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3]), pack_bf16(f[4], f[5]), pack_bf16(f[6], f[7]));
   };
   auto stage = [&](const uint4* kraw, const uint4* vraw) {
 #pragma unroll
@@ -345,6 +395,7 @@ __global__ __launch_bounds__(DT_, 2) void decode_split_mfma_kernel(DecodeParams 
       const int off = (i * TL::kRowsPerLoad + ld_row) * TL::kStride + ld_piece * 16;
       *reinterpret_cast<uint4*>(k_tile + off) = kraw[i];
       if (!is_apx) *reinterpret_cast<uint4*>(v_tile + off) = vraw[i];
+      else if (ROPE) *reinterpret_cast<uint4*>(v_tile + off) = unrotate_piece(kraw[i], (int)vraw[i].x);
     }
   };
   // the tile belongs to this wave alone; these keep the compiler from moving LDS accesses of
@@ -548,7 +599,7 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeParams p) {
   }
 }
 
-void pick_splits(int target, int batch, int n_kv_heads, int cap_retain, int n_approx, int& s_ret, int& s_apx) {
+void pick_splits(int target, int batch, int n_kv_heads, int cap_retain, int n_approx, double apx_cost, int& s_ret, int& s_apx) {
   // One round of workgroups: 256 CUs hold three of these workgroups each, and a second,
   // partly filled round would stream with too few loads in flight.  The splits are divided
   // between the segments by their bytes (a retained row is a key and a value); a workgroup
@@ -557,7 +608,7 @@ void pick_splits(int target, int batch, int n_kv_heads, int cap_retain, int n_ap
   int total = target / pairs;
   if (total > kMaxSplits) total = kMaxSplits;
   if (total < 2) total = 2;
-  const double w_ret = 2.0 * cap_retain, w_apx = (double)n_approx;
+  const double w_ret = 2.0 * cap_retain, w_apx = apx_cost * n_approx;
   s_ret = cap_retain > 0 ? (int)(total * w_ret / (w_ret + w_apx) + 0.5) : 0;
   if (cap_retain > 0 && s_ret < 1) s_ret = 1;
   s_apx = n_approx > 0 ? total - s_ret : 0;
@@ -569,13 +620,19 @@ void pick_splits(int target, int batch, int n_kv_heads, int cap_retain, int n_ap
 }
 
 template <typename T, int D, int G>
-int run_decode(const vector_cache& c, DecodeParams& p, hipStream_t stream) {
+int run_decode(const vector_cache& c, DecodeParams& p, hipStream_t stream, const RopeParams* rope) {
   const dim3 grid(p.splits_ret + p.splits_apx, c.n_kv_heads, c.batch);
   if constexpr (Elem<T>::kDtype == VECTOR_BF16) {
     constexpr int lds = MfmaDecodeTile<D>::kLdsBytes;
-    VEC_HIP(set_max_lds(reinterpret_cast<const void*>(decode_split_mfma_kernel<D, G>), lds));
-    VEC_LAUNCH(K_DECODE_SPLIT, (decode_split_mfma_kernel<D, G>), grid, dim3(DT_), lds, stream, p);
+    if (rope) {
+      VEC_HIP(set_max_lds(reinterpret_cast<const void*>(decode_split_mfma_kernel<D, G, true>), lds));
+      VEC_LAUNCH(K_DECODE_SPLIT, (decode_split_mfma_kernel<D, G, true>), grid, dim3(DT_), lds, stream, p, *rope);
+    } else {
+      VEC_HIP(set_max_lds(reinterpret_cast<const void*>(decode_split_mfma_kernel<D, G, false>), lds));
+      VEC_LAUNCH(K_DECODE_SPLIT, (decode_split_mfma_kernel<D, G, false>), grid, dim3(DT_), lds, stream, p, RopeParams{});
+    }
   } else {
+    if (rope) return VECTOR_ERR_DTYPE;             // rotary caches: bf16 only
     VEC_LAUNCH(K_DECODE_SPLIT, (decode_split_kernel<T, D, G>), grid, dim3(DT_), 0, stream, p);
   }
   VEC_LAUNCH(K_DECODE_COMBINE, (decode_combine_kernel<T, D, G>), dim3(c.n_kv_heads, c.batch), dim3(256), 0, stream, p);
@@ -584,12 +641,12 @@ int run_decode(const vector_cache& c, DecodeParams& p, hipStream_t stream) {
 }
 
 template <typename T, int D>
-int run_decode_g(const vector_cache& c, DecodeParams& p, hipStream_t stream) {
+int run_decode_g(const vector_cache& c, DecodeParams& p, hipStream_t stream, const RopeParams* rope) {
   switch (c.n_q_heads / c.n_kv_heads) {
-    case 1: return run_decode<T, D, 1>(c, p, stream);
-    case 2: return run_decode<T, D, 2>(c, p, stream);
-    case 4: return run_decode<T, D, 4>(c, p, stream);
-    case 8: return run_decode<T, D, 8>(c, p, stream);
+    case 1: return run_decode<T, D, 1>(c, p, stream, rope);
+    case 2: return run_decode<T, D, 2>(c, p, stream, rope);
+    case 4: return run_decode<T, D, 4>(c, p, stream, rope);
+    case 8: return run_decode<T, D, 8>(c, p, stream, rope);
     default: return VECTOR_ERR_SHAPE;
   }
 }
@@ -604,22 +661,26 @@ size_t decode_workspace_bytes(int batch, int n_q_heads, int n_kv_heads, int head
 }
 
 int launch_decode_attn(const vector_cache& c, const void* q, float scale, void* out, int flags, void* ws,
-                       hipStream_t stream) {
+                       hipStream_t stream, const RopeParams* rope) {
   (void)flags;
   DecodeParams p;
   p.q = q; p.k_ret = c.k_ret; p.v_ret = c.v_ret; p.k_apx = c.k_apx; p.W = c.W; p.len_retain = c.len_retain;
   p.out = out; p.part = reinterpret_cast<float*>(ws);
   p.B = c.batch; p.Hq = c.n_q_heads; p.Hkv = c.n_kv_heads; p.cap_retain = c.cap_retain; p.n_approx = c.n_approx;
+  // an approximated row costs its bytes; with the rotary un-rotation, its 64 sine/cosine pairs
+  // make it about as expensive as six rows' worth of streaming
+  // an approximated row costs its bytes; with the rotary un-rotation its sines and cosines make
+  // it cost about as much as three rows' worth of streaming
   pick_splits(c.dtype == VECTOR_BF16 ? kTargetWorkgroupsMfma : kTargetWorkgroups, c.batch, c.n_kv_heads, c.cap_retain, c.n_approx,
-              p.splits_ret, p.splits_apx);
+              rope ? kRopeApxCost : 1.0, p.splits_ret, p.splits_apx);
   p.w_sh = c.w_shared ? 0 : (int64_t)c.head_dim * c.head_dim;
   p.c2 = scale * kLog2e;
   if (c.dtype == VECTOR_BF16) {
-    if (c.head_dim == 128) return run_decode_g<bf16_t, 128>(c, p, stream);
-    if (c.head_dim == 64) return run_decode_g<bf16_t, 64>(c, p, stream);
+    if (c.head_dim == 128) return run_decode_g<bf16_t, 128>(c, p, stream, rope);
+    if (c.head_dim == 64) return run_decode_g<bf16_t, 64>(c, p, stream, rope);
   } else if (c.dtype == VECTOR_F32) {
-    if (c.head_dim == 128) return run_decode_g<float, 128>(c, p, stream);
-    if (c.head_dim == 64) return run_decode_g<float, 64>(c, p, stream);
+    if (c.head_dim == 128) return run_decode_g<float, 128>(c, p, stream, rope);
+    if (c.head_dim == 64) return run_decode_g<float, 64>(c, p, stream, rope);
   } else {
     return VECTOR_ERR_DTYPE;
   }

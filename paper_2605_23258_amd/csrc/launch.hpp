@@ -39,8 +39,9 @@ void timing_end(int id, hipStream_t stream);
 
 // kernel-file entry points used by the C ABI layer
 size_t score_workspace_bytes(const vector_shape& s);
+struct RopeParams;
 int launch_score_residual(const vector_shape& s, const void* q, const void* k, const void* v, const void* W,
-                          float* score, float* eps, void* ws, hipStream_t stream);
+                          float* score, float* eps, void* ws, hipStream_t stream, const RopeParams* rope = nullptr);
 
 int launch_residual_probe(const vector_shape& s, const void* k, const void* v, const void* W, float* eps, int repeat,
                           hipStream_t stream);
@@ -55,6 +56,6 @@ int launch_compact(const vector_shape& s, const void* k, const void* v, const in
 
 size_t decode_workspace_bytes(int batch, int n_q_heads, int n_kv_heads, int head_dim, int cap_retain, int n_approx);
 int launch_decode_attn(const vector_cache& c, const void* q, float scale, void* out, int flags, void* ws,
-                       hipStream_t stream);
+                       hipStream_t stream, const RopeParams* rope = nullptr);
 
 }  // namespace vec

@@ -291,6 +291,74 @@ template <> struct Unpack<float> {    // 16 bytes -> 4 floats
   }
 };
 
+// 16 bytes of un-rotated key elements back into operand form.  bf16 operands cannot hold
+// the turned-back values exactly, so they go to the matrix core twice: the rounded value and
+// the remainder of that rounding (about 2^-17 relative together).
+template <typename T> struct SplitPack;
+template <> struct SplitPack<bf16_t> {
+  static constexpr bool kTwoParts = true;
+  static __device__ __forceinline__ void run(const float* f, chunk_t& hi, chunk_t& lo) {
+    uint32_t h[4], l[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      h[e] = pack_bf16(f[2 * e], f[2 * e + 1]);
+      l[e] = pack_bf16(f[2 * e] - bf16_lo(h[e]), f[2 * e + 1] - bf16_hi(h[e]));
+    }
+    hi = make_uint4(h[0], h[1], h[2], h[3]);
+    lo = make_uint4(l[0], l[1], l[2], l[3]);
+  }
+};
+template <> struct SplitPack<float> {
+  static constexpr bool kTwoParts = false;
+  static __device__ __forceinline__ void run(const float* f, chunk_t& hi, chunk_t& lo) {
+    hi = make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+    lo = make_uint4(0, 0, 0, 0);
+  }
+};
+
+// Operand registers of a 32-token subtile with the rotary embedding of the lane's token
+// (at position pos) taken back out.  A lane holds elements c*2E + half*E + e of its row
+// (chunk c, element e), so both partners of a rotary pair sit in the same lane: chunks c and
+// c + NC/2 for pairs (i, i + d/2), neighbours inside a chunk for pairs (2i, 2i + 1).
+template <typename T, int D>
+__device__ __forceinline__ void unrotate_subtile(const chunk_t* kf, float pos, const float2* turns, int interleaved, int half,
+                                                 chunk_t* kh, chunk_t* kl) {
+  constexpr int E = Tile<T, D>::E, NC = Tile<T, D>::NC;
+  if (!interleaved) {
+#pragma unroll
+    for (int c = 0; c < NC / 2; ++c) {
+      float a[E], b[E];
+      Unpack<T>::run(kf[c], a);
+      Unpack<T>::run(kf[c + NC / 2], b);
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        float cs, sn;
+        const float2 t = turns[c * 2 * E + half * E + e];
+        rotary_cos_sin(pos, t.x, t.y, cs, sn);
+        rotary_back(a[e], b[e], cs, sn, a[e], b[e]);
+      }
+      SplitPack<T>::run(a, kh[c], kl[c]);
+      SplitPack<T>::run(b, kh[c + NC / 2], kl[c + NC / 2]);
+      __builtin_amdgcn_sched_barrier(0);        // one chunk pair at a time: keeps the live set small
+    }
+  } else {
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      float f[E];
+      Unpack<T>::run(kf[c], f);
+#pragma unroll
+      for (int e = 0; e < E; e += 2) {
+        float cs, sn;
+        const float2 t = turns[(c * 2 * E + half * E + e) / 2];
+        rotary_cos_sin(pos, t.x, t.y, cs, sn);
+        rotary_back(f[e], f[e + 1], cs, sn, f[e], f[e + 1]);
+      }
+      SplitPack<T>::run(f, kh[c], kl[c]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+}
+
 // Value registers of a 32-token subtile: lane (token l & 31, half l >> 5) holds the
 // contiguous half row v[token][half*D/2, +D/2) as VP pieces of 16 bytes.
 template <typename T, int D>
@@ -303,8 +371,10 @@ __device__ __forceinline__ void load_v_subtile(chunk_t* vf, const T* v_head, int
 
 // PROBE: the tile loop re-runs each tile's arithmetic p.repeat times on the operands it already
 // holds (no further loads), to time the contraction code with memory out of the picture.
-template <typename T, int D, int NT, bool DO_MASS, bool DO_RES, bool PROBE = false>
-__global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p) {
+// ROPE: the keys are cached after rotary position embedding; the residual un-rotates them
+// (the scores use them as cached).
+template <typename T, int D, int NT, bool DO_MASS, bool DO_RES, bool PROBE = false, bool ROPE = false>
+__global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopeParams rp) {
   using TL = Tile<T, D>;
   constexpr int NW = NT / kWave;
   constexpr int JB = TL::JB;
@@ -315,6 +385,8 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p) {
   float* bias_lds = reinterpret_cast<float*>(smem + off);                    // DO_MASS: [R_pad]
   off += DO_MASS ? (size_t)p.R_pad * sizeof(float) : 0;
   unsigned char* wt_lds = smem + off;                                        // DO_RES: [D] rows of W^T, permuted
+  off += DO_RES ? (size_t)D * TL::kLdsStride : 0;
+  float2* turns_lds = reinterpret_cast<float2*>(smem + off);                 // ROPE: [D/2] rotary frequencies (hi, lo)
 
   const int h = blockIdx.y, chunk = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l31 = lane & 31;
@@ -417,6 +489,7 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p) {
       if (sub == 0 && row < p.R_pad) bias_lds[row] = (row < p.R) ? m + __builtin_amdgcn_logf(l) : INFINITY;
     }
   }
+  if (ROPE && threadIdx.x < D / 2) turns_lds[threadIdx.x] = make_float2(rp.turns_hi[threadIdx.x], rp.turns_lo[threadIdx.x]);
   __syncthreads();
 
   // ---- score part: rows = query rows, columns = tokens ----
@@ -519,7 +592,7 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p) {
 
   while (t0 < c_end) {
     const int tn = t0 + kStep;
-    if (DO_RES && (!PROBE || rep == 0)) {   // values arrive while the score part computes
+    if (DO_RES && !ROPE && (!PROBE || rep == 0)) {   // values arrive while the score part computes
       load_v_subtile<T, D>(vf0, v_head, p.v_st, t0, p.n, lane);
       load_v_subtile<T, D>(vf1, v_head, p.v_st, t0 + 32, p.n, lane);
     }
@@ -547,7 +620,53 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p) {
     } else if (DO_MASS && !DO_RES) {
       load_next(tn);
     }
-    if (DO_RES) {
+    if constexpr (DO_RES && ROPE) {
+      // un-rotate one subtile at a time, then its W^T k products: the MFMAs of block jb + 1
+      // are issued before the differences of block jb are taken
+      float e01[2] = {0.f, 0.f};
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub) {
+        const int tok = min(t0 + 32 * sub + l31, p.n - 1);
+        const float pos = (float)((rp.positions ? rp.positions[tok] : tok) + rp.pos_offset);
+        chunk_t vsub[TL::VP];                       // this subtile's values arrive during the un-rotation
+        load_v_subtile<T, D>(vsub, v_head, p.v_st, t0 + 32 * sub, p.n, lane);
+        chunk_t kh[TL::NC], kl[TL::NC];
+        const float2* turns = turns_lds;            // re-read per subtile: hoisting the table out of the
+        asm volatile("" : "+v"(turns));             // tile loop would pin 64 registers for the whole kernel
+        unrotate_subtile<T, D>(sub ? kf1 : kf0, pos, turns, rp.interleaved, half, kh, kl);
+        auto mma_block = [&](f32x16& a, int jb) {
+#pragma unroll
+          for (int c = 0; c < TL::NC; ++c) {
+            const chunk_t wf = lds_chunk<T, D>(wt_lds, jb * 32 + l31, c, half);
+            if (c == 0) mma_chunk_first<T>(a, wf, kh[c]);
+            else mma_chunk<T>(a, wf, kh[c]);
+            if (SplitPack<T>::kTwoParts) mma_chunk<T>(a, wf, kl[c]);
+          }
+        };
+        f32x16 RA, RB;
+        mma_block(RA, 0);
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb) {
+          f32x16& cur = (jb & 1) ? RB : RA;
+          f32x16& nxt = (jb & 1) ? RA : RB;
+          if (jb + 1 < JB) mma_block(nxt, jb + 1);
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int el = jb * 16 + v;             // element of the lane's half row of v
+            float f[E];
+            Unpack<T>::run(vsub[el / E], f);
+            const float df = f[el % E] - cur[v];
+            e01[sub] = fmaf(df, df, e01[sub]);
+          }
+        }
+      }
+      load_next(tn);
+      float e0 = e01[0], e1 = e01[1];
+      e0 += __shfl_xor(e0, 32, kWave);
+      e1 += __shfl_xor(e1, 32, kWave);
+      const int t = t0 + lane;
+      if (t < c_end) p.eps[(size_t)h * p.n + t] = half ? e1 : e0;
+    } else if (DO_RES) {
       float e0 = 0.f, e1 = 0.f;
       f32x16 RA, RB;
       res_mma(RA, 0);
@@ -650,7 +769,7 @@ size_t score_workspace_bytes(const vector_shape& s) {
 
 template <typename T, int D>
 static int run_score_residual(const vector_shape& s, const void* q, const void* k, const void* v, const void* W,
-                              float* score, float* eps, void* ws, hipStream_t stream) {
+                              float* score, float* eps, void* ws, hipStream_t stream, const RopeParams* rope) {
   const bool do_mass = score != nullptr, do_res = eps != nullptr;
   Plan plan;
   int rc = make_plan<T, D>(s, do_mass, do_res, plan);
@@ -661,6 +780,11 @@ static int run_score_residual(const vector_shape& s, const void* q, const void* 
   p.part = reinterpret_cast<float2*>(w8);
   w8 += align_up((size_t)s.n_kv_heads * p.n_chunks * p.R_pad * sizeof(float2), 256);
   p.mass = reinterpret_cast<float*>(w8);
+  RopeParams rp = {};
+  const bool use_rope = rope != nullptr && do_res;         // the scores use the keys as cached
+  if (use_rope) rp = *rope;
+  const size_t lds2 = plan.lds_pass2 + (use_rope ? (D / 2) * sizeof(float2) : 0);
+  if (lds2 > kMaxLdsBytes) return VECTOR_ERR_SHAPE;
 
   dim3 grid(p.n_chunks, s.n_kv_heads);
   if (do_mass) {
@@ -668,19 +792,12 @@ static int run_score_residual(const vector_shape& s, const void* q, const void* 
     VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k1), plan.lds_stats));
     VEC_LAUNCH(K_SCORE_STATS, k1, grid, dim3(kThreads1), plan.lds_stats, stream, p);
   }
-  if (do_mass && do_res) {
-    auto k2 = mass_residual_kernel<T, D, kThreads, true, true>;
-    VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k2), plan.lds_pass2));
-    VEC_LAUNCH(K_MASS_RESIDUAL, k2, grid, dim3(kThreads), plan.lds_pass2, stream, p);
-  } else if (do_mass) {
-    auto k2 = mass_residual_kernel<T, D, kThreads, true, false>;
-    VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k2), plan.lds_pass2));
-    VEC_LAUNCH(K_MASS_RESIDUAL, k2, grid, dim3(kThreads), plan.lds_pass2, stream, p);
-  } else {
-    auto k2 = mass_residual_kernel<T, D, kThreads, false, true>;
-    VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k2), plan.lds_pass2));
-    VEC_LAUNCH(K_MASS_RESIDUAL, k2, grid, dim3(kThreads), plan.lds_pass2, stream, p);
-  }
+  void (*k2)(PassParams, RopeParams);
+  if (do_mass && do_res) k2 = use_rope ? mass_residual_kernel<T, D, kThreads, true, true, false, true> : mass_residual_kernel<T, D, kThreads, true, true>;
+  else if (do_mass) k2 = mass_residual_kernel<T, D, kThreads, true, false>;
+  else k2 = use_rope ? mass_residual_kernel<T, D, kThreads, false, true, false, true> : mass_residual_kernel<T, D, kThreads, false, true>;
+  VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k2), lds2));
+  VEC_LAUNCH(K_MASS_RESIDUAL, k2, grid, dim3(kThreads), lds2, stream, p, rp);
   if (do_mass)
     VEC_LAUNCH(K_POOL, pool_scores_kernel, dim3((s.seq_len + 255) / 256, s.n_kv_heads), dim3(256), 0, stream,
                        p.mass, score, s.seq_len, p.n_prefix, s.pool_kernel);
@@ -698,7 +815,7 @@ static int run_residual_probe(const vector_shape& s, const void* k, const void* 
   p.q = nullptr; p.k = k; p.v = v; p.W = W; p.eps = eps; p.part = nullptr; p.mass = nullptr; p.repeat = repeat;
   auto k2 = mass_residual_kernel<T, D, kThreads, false, true, true>;
   VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k2), plan.lds_pass2));
-  VEC_LAUNCH(K_MASS_RESIDUAL, k2, dim3(p.n_chunks, s.n_kv_heads), dim3(kThreads), plan.lds_pass2, stream, p);
+  VEC_LAUNCH(K_MASS_RESIDUAL, k2, dim3(p.n_chunks, s.n_kv_heads), dim3(kThreads), plan.lds_pass2, stream, p, RopeParams{});
   VEC_HIP(hipGetLastError());
   return VECTOR_OK;
 }
@@ -712,13 +829,13 @@ int launch_residual_probe(const vector_shape& s, const void* k, const void* v, c
 }
 
 int launch_score_residual(const vector_shape& s, const void* q, const void* k, const void* v, const void* W,
-                          float* score, float* eps, void* ws, hipStream_t stream) {
+                          float* score, float* eps, void* ws, hipStream_t stream, const RopeParams* rope) {
   if (s.dtype == VECTOR_BF16) {
-    if (s.head_dim == 128) return run_score_residual<bf16_t, 128>(s, q, k, v, W, score, eps, ws, stream);
-    if (s.head_dim == 64) return run_score_residual<bf16_t, 64>(s, q, k, v, W, score, eps, ws, stream);
+    if (s.head_dim == 128) return run_score_residual<bf16_t, 128>(s, q, k, v, W, score, eps, ws, stream, rope);
+    if (s.head_dim == 64) return run_score_residual<bf16_t, 64>(s, q, k, v, W, score, eps, ws, stream, rope);
   } else if (s.dtype == VECTOR_F32) {
-    if (s.head_dim == 128) return run_score_residual<float, 128>(s, q, k, v, W, score, eps, ws, stream);
-    if (s.head_dim == 64) return run_score_residual<float, 64>(s, q, k, v, W, score, eps, ws, stream);
+    if (s.head_dim == 128) return run_score_residual<float, 128>(s, q, k, v, W, score, eps, ws, stream, rope);
+    if (s.head_dim == 64) return run_score_residual<float, 64>(s, q, k, v, W, score, eps, ws, stream, rope);
   } else {
     return VECTOR_ERR_DTYPE;
   }

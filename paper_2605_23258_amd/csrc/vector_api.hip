@@ -5,6 +5,7 @@
 #include <string.h>
 
 #include "../../include/vector.h"
+#include "common.hpp"
 #include "launch.hpp"
 
 namespace {
@@ -26,6 +27,23 @@ int check_shape(const vector_shape* s, bool need_window) {
     if (s->window < 1 || s->window > s->seq_len) return VECTOR_ERR_SHAPE;
     if (s->pool_kernel < 1 || !(s->pool_kernel & 1)) return VECTOR_ERR_SHAPE;
   }
+  return VECTOR_OK;
+}
+
+// frequencies in radians per position (host) -> turns per position, by value for the kernels
+int make_rope(const vector_rope* r, int head_dim, vec::RopeParams& out) {
+  if (!r || !r->inv_freq || head_dim / 2 > vec::kMaxRotaryPairs) return VECTOR_ERR_ARG;
+  const double two_pi = 6.283185307179586476925286766559;
+  for (int i = 0; i < vec::kMaxRotaryPairs; ++i) out.turns_hi[i] = out.turns_lo[i] = 0.f;
+  for (int i = 0; i < head_dim / 2; ++i) {
+    if (!(r->inv_freq[i] == r->inv_freq[i])) return VECTOR_ERR_ARG;
+    const double t = r->inv_freq[i] / two_pi;
+    out.turns_hi[i] = (float)t;
+    out.turns_lo[i] = (float)(t - (double)out.turns_hi[i]);
+  }
+  out.positions = r->positions;
+  out.pos_offset = r->pos_offset;
+  out.interleaved = r->interleaved != 0;
   return VECTOR_OK;
 }
 
@@ -150,10 +168,11 @@ int vector_compact(const vector_shape* s, const void* k, const void* v, const in
                              (hipStream_t)stream);
 }
 
-int vector_decode_attn(const vector_cache* c, const void* q, float scale, void* out, int32_t flags, void* ws,
-                       size_t ws_bytes, void* stream) {
+static int decode_checked(const vector_cache* c, const void* q, float scale, void* out, int32_t flags, void* ws,
+                          size_t ws_bytes, void* stream, const vec::RopeParams* rope) {
   if (!c || !q || !out) return VECTOR_ERR_ARG;
   if (c->dtype != VECTOR_F32 && c->dtype != VECTOR_BF16) return VECTOR_ERR_DTYPE;
+  if (rope && c->dtype != VECTOR_BF16) return VECTOR_ERR_DTYPE;
   if (c->head_dim != 64 && c->head_dim != 128) return VECTOR_ERR_SHAPE;
   if (c->batch < 1 || c->batch > 65535 || c->n_kv_heads < 1 || c->n_kv_heads > 65535) return VECTOR_ERR_SHAPE;
   if (c->n_q_heads < c->n_kv_heads || c->n_q_heads % c->n_kv_heads) return VECTOR_ERR_SHAPE;
@@ -167,7 +186,47 @@ int vector_decode_attn(const vector_cache* c, const void* q, float scale, void* 
   int rc = check_ws(ws, ws_bytes,
                     vec::decode_workspace_bytes(c->batch, c->n_q_heads, c->n_kv_heads, c->head_dim, c->cap_retain, c->n_approx));
   if (rc) return rc;
-  return vec::launch_decode_attn(*c, q, scale, out, flags, ws, (hipStream_t)stream);
+  return vec::launch_decode_attn(*c, q, scale, out, flags, ws, (hipStream_t)stream, rope);
+}
+
+int vector_decode_attn(const vector_cache* c, const void* q, float scale, void* out, int32_t flags, void* ws,
+                       size_t ws_bytes, void* stream) {
+  return decode_checked(c, q, scale, out, flags, ws, ws_bytes, stream, nullptr);
+}
+
+int vector_decode_attn_rope(const vector_cache* c, const vector_rope* rope, const void* q, float scale, void* out,
+                            int32_t flags, void* ws, size_t ws_bytes, void* stream) {
+  if (!c) return VECTOR_ERR_ARG;
+  vec::RopeParams rp;
+  int rc = make_rope(rope, c->head_dim, rp);
+  if (rc) return rc;
+  return decode_checked(c, q, scale, out, flags, ws, ws_bytes, stream, &rp);
+}
+
+int vector_residual_rope(const vector_shape* s, const void* k, const void* v, const void* W, const vector_rope* rope,
+                         float* eps, void* ws, size_t ws_bytes, void* stream) {
+  (void)ws; (void)ws_bytes;
+  int rc = check_shape(s, false);
+  if (rc) return rc;
+  if (!k || !v || !W || !eps || !aligned16(k) || !aligned16(v) || !aligned16(W)) return VECTOR_ERR_ARG;
+  vec::RopeParams rp;
+  if ((rc = make_rope(rope, s->head_dim, rp))) return rc;
+  vector_shape t = *s;
+  if (t.window < 1 || t.window > t.seq_len) t.window = 1;     // unused by the residual
+  return vec::launch_score_residual(t, nullptr, k, v, W, nullptr, eps, nullptr, (hipStream_t)stream, &rp);
+}
+
+int vector_score_residual_rope(const vector_shape* s, const void* q_win, const void* k, const void* v, const void* W,
+                               const vector_rope* rope, float* score, float* eps, void* ws, size_t ws_bytes,
+                               void* stream) {
+  int rc = check_shape(s, true);
+  if (rc) return rc;
+  if (!q_win || !k || !v || !W || !score || !eps) return VECTOR_ERR_ARG;
+  if (!aligned16(q_win) || !aligned16(k) || !aligned16(v) || !aligned16(W)) return VECTOR_ERR_ARG;
+  vec::RopeParams rp;
+  if ((rc = make_rope(rope, s->head_dim, rp))) return rc;
+  if ((rc = check_ws(ws, ws_bytes, vec::score_workspace_bytes(*s)))) return rc;
+  return vec::launch_score_residual(*s, q_win, k, v, W, score, eps, ws, (hipStream_t)stream, &rp);
 }
 
 }  // extern "C"

@@ -1,0 +1,110 @@
+"""GPU parity of the post-RoPE entry points (Section 3.1, RoPE decoupling) against the oracle."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import vector_oracle as vo
+from paper_2605_23258_amd import binding as vb
+from paper_2605_23258_amd import datagen as dg
+from paper_2605_23258_amd import pipeline as pl
+
+pytestmark = pytest.mark.gpu
+ATOL, RTOL = 1e-3, 2e-3
+THETA = 500000.0
+
+
+def close(got, ref, what):
+    err = np.abs(np.asarray(got, np.float64) - np.asarray(ref, np.float64))
+    bad = err > ATOL + RTOL * np.abs(ref)
+    assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} outside tolerance, max err {err.max():.3e}"
+
+
+CASES = {
+    "bf16_d128": ("cfg2", dict(seq_len=2048, n_kv_heads=2, n_q_heads=8), False, 0),
+    "bf16_d128_ragged_offset": ("cfg2", dict(seq_len=1777, n_kv_heads=2, n_q_heads=8, window=24), False, 31000),
+    "bf16_d128_interleaved": ("cfg2", dict(seq_len=1100, n_kv_heads=1, n_q_heads=4), True, 7),
+    "bf16_d64": ("cfg2", dict(seq_len=900, head_dim=64, n_kv_heads=2, n_q_heads=4, window=16), False, 0),
+    "f32_d64": ("cfg1", dict(seq_len=1000, window=20, n_q_heads=6, n_kv_heads=2), False, 100),
+    "f32_d64_interleaved": ("cfg1", dict(seq_len=640), True, 0),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_residual_and_score_on_rotated_keys(name):
+    base, over, interleaved, offset = CASES[name]
+    cfg = dg.scaled(dg.CONFIGS[base], **over)
+    li = dg.make_layer(cfg, 0, rope_theta=THETA, rope_interleaved=interleaved, pos_offset=offset)
+    inv_freq = li.extra["inv_freq"]
+    H, n, w = cfg.n_kv_heads, cfg.seq_len, cfg.window
+    n_r, n_a, n_p = cfg.counts()
+    shape = pl.shape_of(cfg)
+    dev = {x: pl.to_device(getattr(li, x)) for x in ("q_win", "k", "v", "w_cal")}
+    wide = {x: dg.widen(getattr(li, x)) for x in ("q_win", "k", "v", "w_cal")}
+    ws = pl.alloc_workspace(vb.vector_workspace_bytes(shape, n_p, n_a, 1))
+    ref_eps = vo.residual(wide["k"], wide["v"], wide["w_cal"], pos=li.extra["pos"], inv_freq=inv_freq, interleaved=interleaved)
+    ref_score = vo.score(wide["q_win"], wide["k"], w, cfg.pool_kernel)
+
+    # positions implied by the row index plus an offset
+    rope, keep = vb.make_rope(inv_freq, None, interleaved, offset)
+    eps = torch.full((H, n), -1.0, device="cuda:0")
+    vb.vector_residual_rope(shape, dev["k"], dev["v"], dev["w_cal"], rope, eps, ws)
+    torch.cuda.synchronize()
+    close(eps.cpu().numpy(), ref_eps, "eps (rope)")
+    # without the un-rotation the residual is far off: the test would notice a path that skips it
+    plain = torch.empty((H, n), device="cuda:0")
+    vb.vector_residual(shape, dev["k"], dev["v"], dev["w_cal"], plain, ws)
+    torch.cuda.synchronize()
+    assert np.median(plain.cpu().numpy()) > 10 * np.median(ref_eps)
+
+    # explicit positions, fused with the score
+    pos_dev = pl.to_device(li.extra["pos"])
+    rope2, keep2 = vb.make_rope(inv_freq, pos_dev, interleaved, 0)
+    score = torch.full((H, n), -1.0, device="cuda:0")
+    eps2 = torch.full((H, n), -1.0, device="cuda:0")
+    vb.vector_score_residual_rope(shape, dev["q_win"], dev["k"], dev["v"], dev["w_cal"], rope2, score, eps2, ws)
+    torch.cuda.synchronize()
+    close(eps2.cpu().numpy(), ref_eps, "eps (rope, fused, explicit positions)")
+    got = score.cpu().numpy()
+    assert np.isposinf(got[:, n - w:]).all()
+    close(got[:, : n - w].astype(np.float64) * n, ref_score[:, : n - w].astype(np.float64) * n, "n*score (rope call)")
+
+
+@pytest.mark.parametrize("d,B,Hq,Hkv,n_r,n_a,interleaved", [
+    (128, 2, 8, 2, 300, 200, False),
+    (128, 1, 4, 4, 0, 65, True),
+    (128, 3, 32, 8, 700, 900, False),
+    (64, 2, 4, 2, 100, 77, False),
+    (64, 1, 8, 1, 33, 40, True),
+])
+def test_decode_on_rotated_cache(d, B, Hq, Hkv, n_r, n_a, interleaved):
+    rng = np.random.default_rng(d + n_a)
+    inv_freq = dg.rotary_inv_freq(d, THETA)
+    bf = lambda x: dg.f32_to_bf16_bits(np.asarray(x, np.float32))
+    k_ret, v_ret = bf(rng.standard_normal((B, Hkv, max(n_r, 1), d))), bf(rng.standard_normal((B, Hkv, max(n_r, 1), d)))
+    k_pre = rng.standard_normal((B, Hkv, n_a, d))
+    pos = np.sort(rng.choice(32768, size=(B, Hkv, n_a)), axis=-1).astype(np.int32)
+    k_apx = bf(dg.apply_rotary(k_pre, pos, inv_freq, interleaved))
+    W = bf(rng.standard_normal((Hkv, d, d)) / np.sqrt(d))
+    q = bf(rng.standard_normal((B, Hq, d)))
+    t = [pl.to_device(x) for x in (k_ret, v_ret, k_apx, W, q, pos)]
+    length = torch.full((B,), n_r, dtype=torch.int32, device="cuda:0")
+    cache = vb.Cache(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, dtype=vb.VECTOR_BF16, cap_retain=max(n_r, 1), n_approx=n_a)
+    cache.len_retain, cache.k_ret, cache.v_ret, cache.k_apx, cache.W = (length.data_ptr(), t[0].data_ptr(), t[1].data_ptr(),
+                                                                      t[2].data_ptr(), t[3].data_ptr())
+    shape = vb.Shape(n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, seq_len=max(n_r + n_a, 64), window=1, pool_kernel=1, dtype=1)
+    ws = pl.alloc_workspace(vb.vector_workspace_bytes(shape, n_r + n_a, n_a, B))
+    out = torch.empty((B, Hq, d), dtype=torch.bfloat16, device="cuda:0")
+    scale = 1.0 / np.sqrt(d)
+    rope, keep = vb.make_rope(inv_freq, t[5], interleaved, 0)
+    vb.vector_decode_attn_rope(cache, rope, t[4], scale, out, ws)
+    torch.cuda.synchronize()
+    ref = vo.decode_attn(dg.widen(q), dg.widen(k_ret), dg.widen(v_ret), np.full(B, n_r), dg.widen(k_apx), dg.widen(W), scale,
+                         pos_apx=pos, inv_freq=inv_freq, interleaved=interleaved)
+    err = np.abs(dg.widen(pl.to_host(out)) - ref)
+    assert (err <= ATOL + (RTOL + 2.0 ** -8) * np.abs(ref)).all(), f"max err {err.max():.3e}"
+    # the plain entry point on the same cache gives something else: the rotation matters here
+    out2 = torch.empty_like(out)
+    vb.vector_decode_attn(cache, t[4], scale, out2, ws)
+    torch.cuda.synchronize()
+    assert np.abs(dg.widen(pl.to_host(out2)) - ref).max() > 10 * ATOL
