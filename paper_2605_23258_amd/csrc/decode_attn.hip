@@ -524,69 +524,103 @@ __global__ __launch_bounds__(DT_, 2) void decode_split_mfma_kernel(DecodeParams 
 template <typename T, int D, int G>
 __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeParams p) {
   constexpr int PSZ = 2 * G + G * D;
-  constexpr int kParts = 256 / D;          // thread groups sharing the contraction with W
+  constexpr int E = Elem<T>::kPerChunk;    // elements of W per 16-byte load
+  constexpr int CG = D / E;                // thread groups along a row of W
+  constexpr int RG = 256 / CG;             // thread groups along its rows (the contraction index)
+  constexpr int RP = D / RG;               // rows of W per thread
+  constexpr int kWavesC = 256 / kWave;
+  static_assert(CG <= kWave && D % RG == 0, "a wave holds whole row groups");
   __shared__ float z_lds[G][D];
   __shared__ float v_lds[G][D];
-  __shared__ float zw_lds[kParts][G][D];
-  __shared__ float scale_lds[2 * kMaxSplits][G];   // per split: exp2(m_s - M)
-  __shared__ float m_lds[2 * kMaxSplits][G];
+  __shared__ float zw_lds[kWavesC][G][D];
   __shared__ float linv_lds[G];
   const int h = blockIdx.x, b = blockIdx.y;
   const size_t bh = (size_t)b * p.Hkv + h;
   const int n_splits = p.splits_ret + p.splits_apx;
   const float* part = p.part + bh * n_splits * PSZ;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
-  // every split's (m, l) in one round of loads, then the global maximum per query row
-  for (int t = threadIdx.x; t < n_splits * G; t += 256) {
-    const int s = t / G, g = t % G;
-    m_lds[s][g] = part[(size_t)s * PSZ + g];
-    scale_lds[s][g] = part[(size_t)s * PSZ + G + g];          // l for now
+  // this thread's block of W (rows rg*RP.., 16 bytes of each) is requested first: it depends on
+  // nothing and arrives while the splits are merged
+  const int cg = threadIdx.x % CG, rg = threadIdx.x / CG;
+  const T* Wh = reinterpret_cast<const T*>(p.W) + (int64_t)h * p.w_sh;
+  uint4 wraw[RP];
+  if (p.n_approx > 0) {
+#pragma unroll
+    for (int r = 0; r < RP; ++r) wraw[r] = load_chunk(Wh + (size_t)(rg * RP + r) * D + cg * E);
   }
-  __syncthreads();
-  if (threadIdx.x < G) {
-    const int g = threadIdx.x;
-    float m = -INFINITY;
-    for (int s = 0; s < n_splits; ++s) m = fmaxf(m, m_lds[s][g]);
-    float l = 0.f;
-    for (int s = 0; s < n_splits; ++s) {
-      const float ms = m_lds[s][g];
-      const float sc = (ms == -INFINITY) ? 0.f : fast_exp2(ms - m);
-      l += scale_lds[s][g] * sc;
-      scale_lds[s][g] = sc;
-    }
-    linv_lds[g] = (l > 0.f) ? 1.f / l : 0.f;
-  }
-  __syncthreads();
+
+  // Merge the splits in one round of loads: a thread owns G*D/256 output elements and, for each,
+  // reads every split's (m, l, partial) itself (the (m, l) reads of a query row are shared by
+  // the lanes that work on that row), folding eight splits at a time into a running maximum.
+  constexpr int kFold = 8;
   for (int i = threadIdx.x; i < G * D; i += 256) {
     const int g = i / D;
-    float av = 0.f, az = 0.f;
-#pragma unroll 8
-    for (int s = 0; s < p.splits_ret; ++s) av += part[(size_t)s * PSZ + 2 * G + i] * scale_lds[s][g];
-#pragma unroll 4
-    for (int s = p.splits_ret; s < n_splits; ++s) az += part[(size_t)s * PSZ + 2 * G + i] * scale_lds[s][g];
+    float M = -INFINITY, L = 0.f, av = 0.f, az = 0.f;
+    for (int s0 = 0; s0 < n_splits; s0 += kFold) {
+      float ms[kFold], ls[kFold], xs[kFold];
+#pragma unroll
+      for (int u = 0; u < kFold; ++u) {
+        const int sI = min(s0 + u, n_splits - 1);
+        ms[u] = part[(size_t)sI * PSZ + g];
+        ls[u] = part[(size_t)sI * PSZ + G + g];
+        xs[u] = part[(size_t)sI * PSZ + 2 * G + i];
+      }
+      float mx = M;
+#pragma unroll
+      for (int u = 0; u < kFold; ++u)
+        if (s0 + u < n_splits) mx = fmaxf(mx, ms[u]);
+      const float keep = (M == -INFINITY) ? 0.f : fast_exp2(M - mx);     // mx = -inf only if M is
+      L *= keep; av *= keep; az *= keep;
+#pragma unroll
+      for (int u = 0; u < kFold; ++u) {
+        if (s0 + u < n_splits && ms[u] != -INFINITY) {
+          const float sc = fast_exp2(ms[u] - mx);
+          L = fmaf(ls[u], sc, L);
+          if (s0 + u < p.splits_ret) av = fmaf(xs[u], sc, av);
+          else az = fmaf(xs[u], sc, az);
+        }
+      }
+      M = mx;
+    }
     (&v_lds[0][0])[i] = av;
     (&z_lds[0][0])[i] = az;
+    if (i % D == 0) linv_lds[g] = (L > 0.f) ? 1.f / L : 0.f;
   }
   __syncthreads();
-  // out[g][j] = (sum_ret p v  +  z[g][:] . W[:, j]) / l ; kParts thread groups split the
-  // contraction index between them
-  const T* Wh = reinterpret_cast<const T*>(p.W) + (int64_t)h * p.w_sh;
+  // out[g][j] = (sum_ret p v  +  z[g][:] . W[:, j]) / l : partial products over the thread's rows
+  // of W, summed over the row groups of a wave by lane exchange, over the waves through LDS
   {
-    const int j = threadIdx.x % D, part_i = threadIdx.x / D;
-    float a[G];
+    float a[G][E];
 #pragma unroll
-    for (int g = 0; g < G; ++g) a[g] = 0.f;
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int e = 0; e < E; ++e) a[g][e] = 0.f;
     if (p.n_approx > 0) {
-      const int i0 = part_i * (D / kParts);
-#pragma unroll 8
-      for (int i = i0; i < i0 + D / kParts; ++i) {
-        const float wij = to_float(Wh[(size_t)i * D + j]);
 #pragma unroll
-        for (int g = 0; g < G; ++g) a[g] = fmaf(z_lds[g][i], wij, a[g]);
+      for (int r = 0; r < RP; ++r) {
+        float wf[E];
+        Unpack16<T>::run(wraw[r], wf);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          const float zg = z_lds[g][rg * RP + r];
+#pragma unroll
+          for (int e = 0; e < E; ++e) a[g][e] = fmaf(zg, wf[e], a[g][e]);
+        }
       }
     }
 #pragma unroll
-    for (int g = 0; g < G; ++g) zw_lds[part_i][g][j] = a[g];
+    for (int o = CG; o < kWave; o <<= 1)
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int e = 0; e < E; ++e) a[g][e] += __shfl_xor(a[g][e], o, kWave);
+    if (lane < CG) {
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int e = 0; e < E; ++e) zw_lds[wave][g][cg * E + e] = a[g][e];
+    }
   }
   __syncthreads();
   T* out = reinterpret_cast<T*>(p.out) + ((size_t)b * p.Hq + (size_t)h * G) * D;
@@ -594,7 +628,7 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeParams p) {
     const int g = i / D, j = i % D;
     float zw = 0.f;
 #pragma unroll
-    for (int q = 0; q < kParts; ++q) zw += zw_lds[q][g][j];
+    for (int q = 0; q < kWavesC; ++q) zw += zw_lds[q][g][j];
     store_elem(out + i, (v_lds[g][j] + zw) * linv_lds[g]);
   }
 }
