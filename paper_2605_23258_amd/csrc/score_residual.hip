@@ -18,6 +18,8 @@
 // Q_h, W_h^T and the row biases live in LDS for the life of a workgroup.  Inside a tile the
 // MFMAs of row block i+1 are issued before the exponentials of row block i, interleaved
 // instruction by instruction, so that the matrix pipe and the vector ALU run together.
+#include <stdlib.h>
+
 #include "common.hpp"
 #include "launch.hpp"
 
@@ -37,7 +39,8 @@ struct PassParams {
   const void* W;
   int64_t k_sh, k_st, v_sh, v_st, w_sh;   // element strides
   int n, w, R, R_pad, n_prefix;
-  int tokens_per_chunk, n_chunks;
+  int tokens_per_chunk;  // pass 2: tokens per workgroup
+  int tpc1, n_chunks;    // pass 1: tokens per workgroup, and the number of such chunks (= partials per row)
   int threads_per_row;  // pass-2 prologue: lanes that share the merge of one row's partials
   float c2;             // log2(e) / sqrt(d)
   float inv_R;
@@ -129,8 +132,8 @@ __global__ __launch_bounds__(NT) void score_stats_kernel(PassParams p) {
   const int nrb = p.R_pad / 32;
 
   const T* k_head = reinterpret_cast<const T*>(p.k) + (int64_t)h * p.k_sh;
-  const int c_begin = chunk * p.tokens_per_chunk;
-  const int c_end = min(p.n, c_begin + p.tokens_per_chunk);
+  const int c_begin = chunk * p.tpc1;
+  const int c_end = min(p.n, c_begin + p.tpc1);
   constexpr int kStep = NW * TW;
 
   chunk_t kf[NS][TL::NC];
@@ -271,6 +274,196 @@ __global__ __launch_bounds__(NT) void score_stats_kernel(PassParams p) {
         float2 s = st_lds[((size_t)wv * nrb + rb) * 64 + hf * 32 + c];
         l += s.y * fast_exp2(s.x - m_safe);
       }
+    out[(size_t)row * p.n_chunks] = make_float2(m, l);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// pass 1, key tiles through LDS: for R_pad = 128 or 256 (4 or 8 row blocks)
+// ---------------------------------------------------------------------------
+// Eight waves; a wave owns one 32-row block of Q_h for the whole launch and keeps it in
+// registers as the B operand, so its lanes carry the running (max, sum-exp) of their own
+// query rows in registers too.  The keys of the chunk stream through LDS in 64-token
+// tiles per token group (NW / NRB groups work on different tiles): all 512 threads load
+// a tile with 16-byte loads, 16 adjacent lanes per row, one tile ahead of the one being
+// consumed (double buffered, one barrier per step), and every wave of a token group reads
+// the tile back in operand order.  Compared with score_stats_kernel the key loads are
+// fully coalesced, overlap with the arithmetic, and no statistics pass through LDS.
+constexpr int kV2Threads = 512;
+constexpr int kV2TileTokens = 64;
+
+template <typename T, int D, int NRB>
+__global__ __launch_bounds__(kV2Threads) void score_stats_tiles_kernel(PassParams p) {
+  using TL = Tile<T, D>;
+  constexpr int NT = kV2Threads;
+  constexpr int NW = NT / kWave;
+  constexpr int TG = NW / NRB;                       // token groups
+  constexpr int NC = TL::NC;
+  constexpr int kStepTokens = TG * kV2TileTokens;
+  constexpr int kPieces = TL::kRowBytes / 16;        // 16-byte pieces per key row
+  constexpr int kLoads = kStepTokens * kPieces / NT; // pieces per thread and step
+  static_assert(NW % NRB == 0 && (kStepTokens * kPieces) % NT == 0, "tile shape");
+  constexpr int kBufBytes = kStepTokens * TL::kLdsStride;
+  extern __shared__ __align__(16) unsigned char smem[];
+
+  const int h = blockIdx.y, chunk = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l31 = lane & 31;
+  const int rb = wave % NRB, tg = wave / NRB;
+  const T* k_head = reinterpret_cast<const T*>(p.k) + (int64_t)h * p.k_sh;
+  const int c_begin = chunk * p.tpc1;
+  const int c_end = min(p.n, c_begin + p.tpc1);
+  const int n_steps = (c_end - c_begin + kStepTokens - 1) / kStepTokens;
+
+  // this wave's query rows: B operand, zero beyond R
+  chunk_t qf[NC];
+  {
+    const int qrow = rb * 32 + l31;
+    const T* qrow_p = reinterpret_cast<const T*>(p.q) + ((size_t)h * p.R + min(qrow, p.R - 1)) * D;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      qf[c] = load_chunk(qrow_p + chunk_elem_offset<T>(c, half));
+      if (qrow >= p.R) qf[c] = make_uint4(0, 0, 0, 0);
+    }
+  }
+  // piece i of a step: token i / kPieces of the step, 16 bytes at piece i % kPieces
+  auto fetch = [&](uint4* raw, int step) {
+#pragma unroll
+    for (int u = 0; u < kLoads; ++u) {
+      const int i = threadIdx.x + u * NT;
+      const int t = min(c_begin + step * kStepTokens + i / kPieces, p.n - 1);    // clamped: masked below
+      raw[u] = load_chunk(reinterpret_cast<const unsigned char*>(k_head + (int64_t)t * p.k_st) + (i % kPieces) * 16);
+    }
+  };
+  auto stash = [&](const uint4* raw, int buf) {
+#pragma unroll
+    for (int u = 0; u < kLoads; ++u) {
+      const int i = threadIdx.x + u * NT;
+      *reinterpret_cast<uint4*>(smem + buf * kBufBytes + (i / kPieces) * TL::kLdsStride + (i % kPieces) * 16) = raw[u];
+    }
+  };
+
+  float m_run = -INFINITY, l_run = 0.f;              // of query row rb*32 + l31, over this lane half's tokens
+  // rows = tokens, columns = query rows
+  auto mma_sub = [&](f32x16& x, const unsigned char* tile, int sub) {
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const chunk_t kf = lds_chunk<T, D>(tile, sub * 32 + l31, c, half);
+      if (c == 0) mma_chunk_first<T>(x, kf, qf[c]);
+      else mma_chunk<T>(x, kf, qf[c]);
+    }
+  };
+  auto tile_max1 = [&](const f32x16& x) {
+    float m0 = max3(x[0], x[1], x[2]), m1 = max3(x[8], x[9], x[10]);
+    m0 = max3(m0, x[3], x[4]); m1 = max3(m1, x[11], x[12]);
+    m0 = max3(m0, x[5], x[6]); m1 = max3(m1, x[13], x[14]);
+    return fmaxf(fmaxf(m0, x[7]), fmaxf(m1, x[15])) * p.c2;
+  };
+  auto fold = [&](const f32x16& x) {
+    const float m_new = fmaxf(m_run, tile_max1(x));
+    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+    float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; v += 2) {
+      s0 += fast_exp2(fmaf(x[v], p.c2, -m_safe));
+      s1 += fast_exp2(fmaf(x[v + 1], p.c2, -m_safe));
+    }
+    l_run = l_run * fast_exp2(m_run - m_safe) + (s0 + s1);
+    m_run = m_new;
+  };
+  // second subtile's MFMAs one at a time, each followed by exponentials of the first subtile
+  auto mma_fold = [&](f32x16& nx, const unsigned char* tile, const f32x16& cu) {
+    const float m_new = fmaxf(m_run, tile_max1(cu));
+    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+    float s0 = 0.f, s1 = 0.f;
+    chunk_t kf = lds_chunk<T, D>(tile, 32 + l31, 0, half);
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const chunk_t k_now = kf;
+      if (c + 1 < NC) kf = lds_chunk<T, D>(tile, 32 + l31, c + 1, half);
+      if (c == 0) mma_chunk_first<T>(nx, k_now, qf[c]);
+      else mma_chunk<T>(nx, k_now, qf[c]);
+#pragma unroll
+      for (int v = c * 16 / NC; v < (c + 1) * 16 / NC; ++v) {
+        const float e = fast_exp2(fmaf(cu[v], p.c2, -m_safe));
+        if (v & 1) s1 += e; else s0 += e;
+      }
+      VEC_PIN3(nx, s0, s1);
+    }
+    l_run = l_run * fast_exp2(m_run - m_safe) + (s0 + s1);
+    m_run = m_new;
+  };
+
+  // Key tiles are requested kAhead steps before they are consumed (a step's arithmetic is
+  // shorter than a trip to HBM); they wait in registers and enter LDS one step ahead.
+  constexpr int kAhead = 3;
+  uint4 raw[kAhead][kLoads];
+  const int qrow = rb * 32 + l31;
+  auto compute = [&](int step) {
+    const unsigned char* tile = smem + (step & 1) * kBufBytes + tg * kV2TileTokens * TL::kLdsStride;
+    const int t0 = c_begin + step * kStepTokens + tg * kV2TileTokens;
+    if (t0 < c_end) {
+      f32x16 A, B;
+      // a tile needs masking if it reaches past the first window position or past the chunk
+      const bool tail = (t0 + kV2TileTokens > p.n_prefix + 1) || (t0 + kV2TileTokens > c_end);
+      if (!tail) {
+        mma_sub(A, tile, 0);
+        mma_fold(B, tile, A);
+        fold(B);
+      } else {
+        // query row (g, r) sits at position n - w + r and sees tokens <= that
+        const int last = (qrow < p.R) ? min(p.n_prefix + (qrow % p.w), c_end - 1) : c_end - 1;
+        mma_sub(A, tile, 0);
+        mma_sub(B, tile, 1);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          if (t0 + acc_row(v, half) > last) A[v] = -INFINITY;
+          if (t0 + 32 + acc_row(v, half) > last) B[v] = -INFINITY;
+        }
+        fold(A);
+        fold(B);
+      }
+    }
+  };
+#pragma unroll
+  for (int a = 0; a < kAhead; ++a)
+    if (a < n_steps) fetch(raw[a], a);
+  stash(raw[0], 0);
+  for (int step0 = 0; step0 < n_steps; step0 += kAhead) {
+#pragma unroll
+    for (int a = 0; a < kAhead; ++a) {               // ring slot a holds tile step0 + a
+      const int step = step0 + a;
+      if (step < n_steps) {
+        __syncthreads();                   // tile `step` is in its buffer; the other buffer is free
+        if (step + kAhead < n_steps) fetch(raw[a], step + kAhead);      // slot a was stashed a step ago
+        compute(step);
+        if (step + 1 < n_steps) stash(raw[(a + 1) % kAhead], (step + 1) & 1);
+      }
+    }
+  }
+  // merge the two lane halves, then the token groups; one (max, sum) per (row, chunk)
+  {
+    const float m2 = __shfl_xor(m_run, 32, kWave), l2 = __shfl_xor(l_run, 32, kWave);
+    const float mn = fmaxf(m_run, m2);
+    const float ms = (mn == -INFINITY) ? 0.f : mn;
+    l_run = l_run * fast_exp2(m_run - ms) + l2 * fast_exp2(m2 - ms);
+    m_run = mn;
+  }
+  __syncthreads();                         // tiles are dead: reuse LDS for the group merge
+  float2* grp = reinterpret_cast<float2*>(smem);     // [TG][NRB * 32]
+  if (half == 0) grp[tg * (NRB * 32) + qrow] = make_float2(m_run, l_run);
+  __syncthreads();
+  float2* out = p.part + (size_t)h * p.R_pad * p.n_chunks + chunk;
+  for (int row = threadIdx.x; row < NRB * 32; row += NT) {
+    float m = -INFINITY;
+#pragma unroll
+    for (int g = 0; g < TG; ++g) m = fmaxf(m, grp[g * (NRB * 32) + row].x);
+    const float ms = (m == -INFINITY) ? 0.f : m;
+    float l = 0.f;
+#pragma unroll
+    for (int g = 0; g < TG; ++g) {
+      const float2 sv = grp[g * (NRB * 32) + row];
+      l += sv.y * fast_exp2(sv.x - ms);
+    }
     out[(size_t)row * p.n_chunks] = make_float2(m, l);
   }
 }
@@ -422,7 +615,7 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
   }
   // pass 1's chunk partials of this thread's row: `tpr` adjacent lanes share one row and
   // each takes every tpr-th chunk; the first kPre of them are requested here
-  constexpr int kPre = 16;
+  constexpr int kPre = 32;
   const int tpr = p.threads_per_row, sub = threadIdx.x % tpr;
   const int rows_per_sweep = NT / tpr;
   float2 pre[kPre];
@@ -712,13 +905,38 @@ __global__ void pool_scores_kernel(const float* __restrict__ mass, float* __rest
 // host side
 // ---------------------------------------------------------------------------
 constexpr int kThreads = 512;        // pass 2
+
+// VECTOR_STATS_DIRECT=1 in the environment keeps pass 1 on the kernel that loads keys straight
+// into operand registers (for comparison runs)
+bool stats_tiles_disabled() {
+  static const bool off = [] { const char* e = getenv("VECTOR_STATS_DIRECT"); return e && e[0] == '1'; }();
+  return off;
+}
 constexpr int kThreads1 = VEC_P1_THREADS;   // pass 1
 constexpr int kSub1 = VEC_P1_SUBTILES;
 
 struct Plan {
   PassParams pp;
-  size_t lds_stats, lds_pass2;
+  size_t lds_stats, lds_pass2, lds_tiles;
+  bool tiles;           // pass 1 on the kernel that streams key tiles through LDS
 };
+
+#ifndef VEC_TILES_MIN_WGS
+#define VEC_TILES_MIN_WGS 512
+#endif
+// pass 1 through LDS tiles: two workgroups per CU hide each other's barriers and LDS round trips
+int pick_tokens_per_chunk_tiles(int n, int n_kv_heads) {
+  int tpc = 2048;
+  while (tpc > 256 && (int64_t)((n + tpc - 1) / tpc) * n_kv_heads < VEC_TILES_MIN_WGS) tpc >>= 1;
+  return tpc;
+}
+
+size_t stats_tiles_lds(int nrb, size_t lds_stride) {
+  return (size_t)2 * (kV2Threads / kWave / (nrb ? nrb : 1)) * kV2TileTokens * lds_stride;
+}
+bool stats_by_tiles(int nrb, size_t lds_stride) {
+  return (nrb == 8 || nrb == 4) && stats_tiles_lds(nrb, lds_stride) <= kMaxLdsBytes && !stats_tiles_disabled();
+}
 
 int pick_tokens_per_chunk(int n, int n_kv_heads) {
   // at least one workgroup per CU where the sequence allows it, and then as many
@@ -736,7 +954,9 @@ int make_plan(const vector_shape& s, bool do_mass, bool do_res, Plan& plan) {
   p.n = s.seq_len; p.w = s.window; p.R = G * s.window; p.R_pad = (p.R + 31) / 32 * 32;
   p.n_prefix = s.seq_len - s.window;
   p.tokens_per_chunk = pick_tokens_per_chunk(s.seq_len, s.n_kv_heads);
-  p.n_chunks = (s.seq_len + p.tokens_per_chunk - 1) / p.tokens_per_chunk;
+  plan.tiles = stats_by_tiles(p.R_pad / 32, (size_t)Tile<T, D>::kLdsStride);
+  p.tpc1 = plan.tiles ? pick_tokens_per_chunk_tiles(s.seq_len, s.n_kv_heads) : p.tokens_per_chunk;
+  p.n_chunks = (s.seq_len + p.tpc1 - 1) / p.tpc1;
   int tpr = 1;
   while (tpr * 2 <= 64 && tpr * 2 * p.R_pad <= kThreads && tpr * 2 <= p.n_chunks) tpr *= 2;
   p.threads_per_row = tpr;
@@ -759,8 +979,7 @@ int make_plan(const vector_shape& s, bool do_mass, bool do_res, Plan& plan) {
 size_t score_workspace_bytes(const vector_shape& s) {
   const int G = s.n_q_heads / s.n_kv_heads;
   const int R_pad = (G * s.window + 31) / 32 * 32;
-  const int tpc = pick_tokens_per_chunk(s.seq_len, s.n_kv_heads);
-  const int n_chunks = (s.seq_len + tpc - 1) / tpc;
+  const int n_chunks = (s.seq_len + 255) / 256;      // upper bound over both pass-1 kernels' chunkings
   size_t b = 0;
   b += align_up((size_t)s.n_kv_heads * n_chunks * R_pad * sizeof(float2), 256);
   b += align_up((size_t)s.n_kv_heads * s.seq_len * sizeof(float), 256);
@@ -778,7 +997,7 @@ static int run_score_residual(const vector_shape& s, const void* q, const void* 
   p.q = q; p.k = k; p.v = v; p.W = W; p.eps = eps; p.repeat = 1;
   unsigned char* w8 = reinterpret_cast<unsigned char*>(ws);
   p.part = reinterpret_cast<float2*>(w8);
-  w8 += align_up((size_t)s.n_kv_heads * p.n_chunks * p.R_pad * sizeof(float2), 256);
+  w8 += align_up((size_t)s.n_kv_heads * ((s.seq_len + 255) / 256) * p.R_pad * sizeof(float2), 256);
   p.mass = reinterpret_cast<float*>(w8);
   RopeParams rp = {};
   const bool use_rope = rope != nullptr && do_res;         // the scores use the keys as cached
@@ -786,11 +1005,20 @@ static int run_score_residual(const vector_shape& s, const void* q, const void* 
   const size_t lds2 = plan.lds_pass2 + (use_rope ? (D / 2) * sizeof(float2) : 0);
   if (lds2 > kMaxLdsBytes) return VECTOR_ERR_SHAPE;
 
-  dim3 grid(p.n_chunks, s.n_kv_heads);
+  const dim3 grid1(p.n_chunks, s.n_kv_heads);
+  const dim3 grid((s.seq_len + p.tokens_per_chunk - 1) / p.tokens_per_chunk, s.n_kv_heads);
   if (do_mass) {
-    auto k1 = score_stats_kernel<T, D, kThreads1, kSub1>;
-    VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k1), plan.lds_stats));
-    VEC_LAUNCH(K_SCORE_STATS, k1, grid, dim3(kThreads1), plan.lds_stats, stream, p);
+    const int nrb = p.R_pad / 32;
+    if (plan.tiles) {
+      const size_t lds_tiles = stats_tiles_lds(nrb, Tile<T, D>::kLdsStride);
+      void (*k1)(PassParams) = nrb == 8 ? score_stats_tiles_kernel<T, D, 8> : score_stats_tiles_kernel<T, D, 4>;
+      VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k1), lds_tiles));
+      VEC_LAUNCH(K_SCORE_STATS, k1, grid1, dim3(kV2Threads), lds_tiles, stream, p);
+    } else {
+      auto k1 = score_stats_kernel<T, D, kThreads1, kSub1>;
+      VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k1), plan.lds_stats));
+      VEC_LAUNCH(K_SCORE_STATS, k1, grid1, dim3(kThreads1), plan.lds_stats, stream, p);
+    }
   }
   void (*k2)(PassParams, RopeParams);
   if (do_mass && do_res) k2 = use_rope ? mass_residual_kernel<T, D, kThreads, true, true, false, true> : mass_residual_kernel<T, D, kThreads, true, true>;
@@ -815,7 +1043,8 @@ static int run_residual_probe(const vector_shape& s, const void* k, const void* 
   p.q = nullptr; p.k = k; p.v = v; p.W = W; p.eps = eps; p.part = nullptr; p.mass = nullptr; p.repeat = repeat;
   auto k2 = mass_residual_kernel<T, D, kThreads, false, true, true>;
   VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k2), plan.lds_pass2));
-  VEC_LAUNCH(K_MASS_RESIDUAL, k2, dim3(p.n_chunks, s.n_kv_heads), dim3(kThreads), plan.lds_pass2, stream, p, RopeParams{});
+  VEC_LAUNCH(K_MASS_RESIDUAL, k2, dim3((s.seq_len + p.tokens_per_chunk - 1) / p.tokens_per_chunk, s.n_kv_heads), dim3(kThreads), plan.lds_pass2,
+             stream, p, RopeParams{});
   VEC_HIP(hipGetLastError());
   return VECTOR_OK;
 }
