@@ -206,6 +206,21 @@ VECTOR_API int vector_score_residual_rope(const vector_shape* shape, const void*
 VECTOR_API int vector_decode_attn_rope(const vector_cache* cache, const vector_rope* rope, const void* q, float scale,
                             void* out, int32_t flags, void* ws, size_t ws_bytes, void* stream);
 
+/* ---- calibration of the value map ---------------------------------------- */
+
+/* Section 3.1: the least-squares map from keys to values, per KV head and without intercept,
+ *   W[h] = argmin_W || k[h] W - v[h] ||_F^2      (v_hat = k . W; the transpose of the paper's W_OLS),
+ * from shape->seq_len calibration tokens (k, v: device [Hkv, seq_len, d] with the shape's
+ * strides and dtype; keys as projected, i.e. before any rotary embedding).  Solved through
+ * the normal equations: the two d x d products are accumulated on the matrix cores in
+ * fp32 per chunk of tokens and summed in fp64; Cholesky and the triangular solves run in fp64.
+ * W: device [Hkv, d, d] (output, shape dtype).  ws: vector_calibrate_workspace_bytes(shape)
+ * bytes of device scratch, 256-byte aligned.  VECTOR_ERR_ARG if seq_len < head_dim.  A head
+ * whose K^T K is not positive definite gets NaN in its W. */
+VECTOR_API size_t vector_calibrate_workspace_bytes(const vector_shape* shape);
+VECTOR_API int vector_calibrate(const vector_shape* shape, const void* k, const void* v, void* W, void* ws,
+                     size_t ws_bytes, void* stream);
+
 /* Diagnostic: the reconstruction contraction of Section 3.2 Step 2 (v_hat = k W, then the
  * squared distance to v) with memory out of the picture.  Same arguments, layout and
  * arithmetic as vector_residual for bf16 inputs, but every workgroup runs the arithmetic

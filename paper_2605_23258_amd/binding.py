@@ -24,6 +24,7 @@ EXPORTS = (
     "vector_timing_enable", "vector_timing_kernels", "vector_timing_name", "vector_timing_read",
     "vector_probe_residual_mfma",
     "vector_residual_rope", "vector_score_residual_rope", "vector_decode_attn_rope",
+    "vector_calibrate_workspace_bytes", "vector_calibrate",
 )
 
 
@@ -100,6 +101,9 @@ def lib() -> C.CDLL:
         L.vector_timing_name.restype = C.c_char_p
         L.vector_timing_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         L.vector_probe_residual_mfma.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, i32, vp]
+        L.vector_calibrate_workspace_bytes.argtypes = [C.POINTER(Shape)]
+        L.vector_calibrate_workspace_bytes.restype = sz
+        L.vector_calibrate.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, sz, vp]
         L.vector_residual_rope.argtypes = [C.POINTER(Shape), vp, vp, vp, C.POINTER(Rope), vp, vp, sz, vp]
         L.vector_score_residual_rope.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, C.POINTER(Rope), vp, vp, vp, sz, vp]
         L.vector_decode_attn_rope.argtypes = [C.POINTER(Cache), C.POINTER(Rope), vp, C.c_float, vp, i32, vp, sz, vp]
@@ -225,3 +229,12 @@ def vector_score_residual_rope(shape: Shape, q_win, k, v, W, rope: Rope, score, 
 def vector_decode_attn_rope(cache: Cache, rope: Rope, q, scale: float, out, ws, stream=None) -> None:
     _check(lib().vector_decode_attn_rope(C.byref(cache), C.byref(rope), _ptr(q), scale, _ptr(out), 0, _ptr(ws),
                                          _nbytes(ws), _stream(stream)), "vector_decode_attn_rope")
+
+
+def vector_calibrate_workspace_bytes(shape: Shape) -> int:
+    return int(lib().vector_calibrate_workspace_bytes(C.byref(shape)))
+
+
+def vector_calibrate(shape: Shape, k, v, W, ws, stream=None) -> None:
+    _check(lib().vector_calibrate(C.byref(shape), _ptr(k), _ptr(v), _ptr(W), _ptr(ws), _nbytes(ws), _stream(stream)),
+           "vector_calibrate")

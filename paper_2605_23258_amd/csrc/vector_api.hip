@@ -122,6 +122,20 @@ int vector_residual(const vector_shape* s, const void* k, const void* v, const v
   return vec::launch_score_residual(t, nullptr, k, v, W, nullptr, eps, nullptr, (hipStream_t)stream);
 }
 
+size_t vector_calibrate_workspace_bytes(const vector_shape* s) {
+  if (check_shape(s, false) != VECTOR_OK) return 0;
+  return vec::calibrate_workspace_bytes(*s);
+}
+
+int vector_calibrate(const vector_shape* s, const void* k, const void* v, void* W, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_shape(s, false);
+  if (rc) return rc;
+  if (!k || !v || !W || !aligned16(k) || !aligned16(v) || !aligned16(W)) return VECTOR_ERR_ARG;
+  if (s->seq_len < s->head_dim) return VECTOR_ERR_ARG;          // fewer tokens than unknowns per column: singular
+  if ((rc = check_ws(ws, ws_bytes, vec::calibrate_workspace_bytes(*s)))) return rc;
+  return vec::launch_calibrate(*s, k, v, W, ws, (hipStream_t)stream);
+}
+
 int vector_probe_residual_mfma(const vector_shape* s, const void* k, const void* v, const void* W, float* eps,
                                int32_t repeat, void* stream) {
   int rc = check_shape(s, false);

@@ -1,0 +1,84 @@
+"""GPU parity of the least-squares value map (Section 3.1) against the oracle's normal-equation fit."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import vector_oracle as vo
+from paper_2605_23258_amd import binding as vb
+from paper_2605_23258_amd import datagen as dg
+from paper_2605_23258_amd import pipeline as pl
+
+pytestmark = pytest.mark.gpu
+
+CASES = {
+    "bf16_d128_4096": ("cfg2", dict(seq_len=4096, n_kv_heads=2, n_q_heads=8)),
+    "bf16_d128_ragged": ("cfg2", dict(seq_len=3001, n_kv_heads=3, n_q_heads=6)),
+    "bf16_d64": ("cfg2", dict(seq_len=1500, head_dim=64, n_kv_heads=2, n_q_heads=4)),
+    "f32_d64": ("cfg1", dict(seq_len=1000, n_kv_heads=2, n_q_heads=4)),
+    "f32_d128_short": ("cfg1", dict(seq_len=300, head_dim=128, n_kv_heads=1, n_q_heads=2)),
+}
+
+
+def _fit_gpu(cfg, k_dev, v_dev, shape=None):
+    shape = shape or pl.shape_of(cfg)
+    H, d = cfg.n_kv_heads, cfg.head_dim
+    W = torch.zeros((H, d, d), dtype=torch.bfloat16 if cfg.dtype == "bf16" else torch.float32, device="cuda:0")
+    ws = pl.alloc_workspace(vb.vector_calibrate_workspace_bytes(shape))
+    vb.vector_calibrate(shape, k_dev, v_dev, W, ws)
+    torch.cuda.synchronize()
+    return dg.widen(pl.to_host(W))
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_value_map_matches_oracle_fit(name):
+    base, over = CASES[name]
+    cfg = dg.scaled(dg.CONFIGS[base], **over)
+    li = dg.make_layer(cfg, 0)
+    got = _fit_gpu(cfg, pl.to_device(li.k), pl.to_device(li.v))
+    ref = vo.ols_fit(dg.widen(li.k), dg.widen(li.v))
+    # the output is stored in the tensors' dtype: bf16 adds its own rounding (2^-9 relative)
+    rel = 2.0 ** -8 if cfg.dtype == "bf16" else 1e-4
+    err = np.abs(got - ref)
+    assert (err <= 1e-4 + rel * np.abs(ref)).all(), f"max err {err.max():.3e} at |ref| {np.abs(ref).flat[err.argmax()]:.3e}"
+    # and it is the map the data was drawn from, up to the noise of the draw
+    assert np.abs(got - li.w_true).max() < 0.1
+
+
+def test_planted_map_without_noise_is_recovered():
+    cfg = dg.scaled(dg.CONFIGS["cfg1"], seq_len=512, n_kv_heads=2, n_q_heads=2)
+    rng = np.random.default_rng(0)
+    k = rng.standard_normal((2, 512, 64)).astype(np.float32)
+    w = (rng.standard_normal((2, 64, 64)) / 8).astype(np.float32)
+    v = np.einsum("hti,hij->htj", k.astype(np.float64), w.astype(np.float64)).astype(np.float32)
+    got = _fit_gpu(cfg, pl.to_device(k), pl.to_device(v))
+    assert np.abs(got - w).max() < 1e-4
+
+
+def test_strided_views_and_errors():
+    cfg = dg.scaled(dg.CONFIGS["cfg2"], seq_len=2000, n_kv_heads=2, n_q_heads=8)
+    li = dg.make_layer(cfg, 0)
+    H, n, d = cfg.n_kv_heads, cfg.seq_len, cfg.head_dim
+    fused = np.zeros((n, H, 2, d), np.uint16)
+    fused[:, :, 0] = np.transpose(li.k, (1, 0, 2))
+    fused[:, :, 1] = np.transpose(li.v, (1, 0, 2))
+    buf = pl.to_device(fused)
+    shape = pl.shape_of(cfg)
+    shape.k_stride_head = shape.v_stride_head = 2 * d
+    shape.k_stride_tok = shape.v_stride_tok = H * 2 * d
+    got = _fit_gpu(cfg, buf[:, :, 0], buf[:, :, 1], shape)
+    ref = vo.ols_fit(dg.widen(li.k), dg.widen(li.v))
+    err = np.abs(got - ref)
+    assert (err <= 1e-4 + 2.0 ** -8 * np.abs(ref)).all()
+    # fewer tokens than dimensions: refused before any launch
+    short = pl.shape_of(dg.scaled(cfg, seq_len=100))
+    W = torch.full((H, d, d), 7.0, dtype=torch.bfloat16, device="cuda:0")
+    ws = pl.alloc_workspace(1 << 20)
+    with pytest.raises(vb.VectorError) as ei:
+        vb.vector_calibrate(short, pl.to_device(li.k), pl.to_device(li.v), W, ws)
+    assert ei.value.code == vb.VECTOR_ERR_ARG
+    with pytest.raises(vb.VectorError) as ei:
+        vb.vector_calibrate(pl.shape_of(cfg), pl.to_device(li.k), pl.to_device(li.v), W, ws[:512])
+    assert ei.value.code == vb.VECTOR_ERR_WORKSPACE
+    torch.cuda.synchronize()
+    assert (W == 7.0).all()
