@@ -266,3 +266,32 @@ def distortion(weights: np.ndarray, tier: np.ndarray, eps: np.ndarray, v_sqnorm:
     weights = np.asarray(weights, dtype=np.float64)
     rel = np.asarray(eps, dtype=np.float64) / np.asarray(v_sqnorm, dtype=np.float64)
     return (weights * (tier == EVICT)).sum(axis=1) + (weights * rel * (tier == APPROX)).sum(axis=1)
+
+
+def distortion_report(weights: np.ndarray, tier: np.ndarray, eps: np.ndarray, v: np.ndarray) -> dict:
+    """The quantities of Section 4 per head, from importance weights w [H, n] (summing to one
+    per head), the routing, the residuals and the values v [H, n, d]:
+
+      E          the distortion above
+      w_evict    sum of w over evicted tokens;  w_approx  the same over approximated tokens
+      mu_approx  mean over approximated tokens of eps_i / ||v_i||^2;  r2_approx = 1 - mu_approx
+      w_bar      (1 - w_evict) / (pool fraction): mean pool weight relative to the uniform 1/n
+      w_star     n * (largest weight among evicted tokens): the token at the truncation boundary
+                 of the eviction set, on the same scale (0 when nothing is evicted)
+      threshold  w_bar / (w_star + w_bar): Proposition 1 says that growing the approximation
+                 tier lowers E when r2_approx exceeds it."""
+    w = np.asarray(weights, dtype=np.float64)
+    e = np.asarray(eps, dtype=np.float64)
+    vsq = (np.asarray(v, dtype=np.float64) ** 2).sum(axis=-1)
+    n = w.shape[1]
+    ev, ap = tier == EVICT, tier == APPROX
+    rel = e / vsq
+    n_ap = ap.sum(axis=1)
+    w_evict = (w * ev).sum(axis=1)
+    mu = np.where(n_ap > 0, (rel * ap).sum(axis=1) / np.maximum(n_ap, 1), 0.0)
+    pool_frac = (~ev).sum(axis=1) / n
+    w_bar = (1.0 - w_evict) / pool_frac
+    w_star = n * np.where(ev, w, 0.0).max(axis=1)
+    return {"E": w_evict + (w * rel * ap).sum(axis=1), "w_evict": w_evict, "w_approx": (w * ap).sum(axis=1),
+            "mu_approx": mu, "r2_approx": 1.0 - mu, "w_bar": w_bar, "w_star": w_star,
+            "threshold": w_bar / (w_star + w_bar), "n_approx": n_ap, "n_evict": ev.sum(axis=1)}
