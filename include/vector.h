@@ -221,6 +221,25 @@ VECTOR_API size_t vector_calibrate_workspace_bytes(const vector_shape* shape);
 VECTOR_API int vector_calibrate(const vector_shape* shape, const void* k, const void* v, void* W, void* ws,
                      size_t ws_bytes, void* stream);
 
+/* ---- distortion diagnostics ------------------------------------------------ */
+
+/* Section 4: with importance weights w (device fp32 [Hkv, n], summing to one per head), the
+ * routing (tier), the residuals (eps) and the values v [Hkv, n, d] (shape strides, dtype):
+ *   out[h][0] E          sum_evicted w_i + sum_approx w_i eps_i / ||v_i||^2
+ *   out[h][1] w_evict    sum of w over evicted tokens        out[h][2] w_approx  same, approximated
+ *   out[h][3] mu_approx  mean of eps_i / ||v_i||^2 over approximated tokens
+ *   out[h][4] r2_approx  1 - mu_approx
+ *   out[h][5] w_bar      (1 - w_evict) / (fraction of tokens in the pool)
+ *   out[h][6] w_star     n * largest weight among evicted tokens (0 if none)
+ *   out[h][7] threshold  w_bar / (w_star + w_bar): Proposition 1's bound on r2_approx
+ *   out[h][8] n_approx   out[h][9] n_evict
+ * out: device fp64 [Hkv, VECTOR_DISTORTION_FIELDS].  Sums run in fp64 in a fixed order.
+ * ws: vector_distortion_workspace_bytes(shape) bytes, 256-byte aligned. */
+#define VECTOR_DISTORTION_FIELDS 10
+VECTOR_API size_t vector_distortion_workspace_bytes(const vector_shape* shape);
+VECTOR_API int vector_distortion(const vector_shape* shape, const float* weights, const uint8_t* tier, const float* eps,
+                      const void* v, double* out, void* ws, size_t ws_bytes, void* stream);
+
 /* Diagnostic: the reconstruction contraction of Section 3.2 Step 2 (v_hat = k W, then the
  * squared distance to v) with memory out of the picture.  Same arguments, layout and
  * arithmetic as vector_residual for bf16 inputs, but every workgroup runs the arithmetic

@@ -25,6 +25,7 @@ EXPORTS = (
     "vector_probe_residual_mfma",
     "vector_residual_rope", "vector_score_residual_rope", "vector_decode_attn_rope",
     "vector_calibrate_workspace_bytes", "vector_calibrate",
+    "vector_distortion_workspace_bytes", "vector_distortion",
 )
 
 
@@ -104,6 +105,9 @@ def lib() -> C.CDLL:
         L.vector_calibrate_workspace_bytes.argtypes = [C.POINTER(Shape)]
         L.vector_calibrate_workspace_bytes.restype = sz
         L.vector_calibrate.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, sz, vp]
+        L.vector_distortion_workspace_bytes.argtypes = [C.POINTER(Shape)]
+        L.vector_distortion_workspace_bytes.restype = sz
+        L.vector_distortion.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, vp, sz, vp]
         L.vector_residual_rope.argtypes = [C.POINTER(Shape), vp, vp, vp, C.POINTER(Rope), vp, vp, sz, vp]
         L.vector_score_residual_rope.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, C.POINTER(Rope), vp, vp, vp, sz, vp]
         L.vector_decode_attn_rope.argtypes = [C.POINTER(Cache), C.POINTER(Rope), vp, C.c_float, vp, i32, vp, sz, vp]
@@ -238,3 +242,15 @@ def vector_calibrate_workspace_bytes(shape: Shape) -> int:
 def vector_calibrate(shape: Shape, k, v, W, ws, stream=None) -> None:
     _check(lib().vector_calibrate(C.byref(shape), _ptr(k), _ptr(v), _ptr(W), _ptr(ws), _nbytes(ws), _stream(stream)),
            "vector_calibrate")
+
+
+DISTORTION_FIELDS = ("E", "w_evict", "w_approx", "mu_approx", "r2_approx", "w_bar", "w_star", "threshold", "n_approx", "n_evict")
+
+
+def vector_distortion_workspace_bytes(shape: Shape) -> int:
+    return int(lib().vector_distortion_workspace_bytes(C.byref(shape)))
+
+
+def vector_distortion(shape: Shape, weights, tier, eps, v, out, ws, stream=None) -> None:
+    _check(lib().vector_distortion(C.byref(shape), _ptr(weights), _ptr(tier), _ptr(eps), _ptr(v), _ptr(out), _ptr(ws),
+                                   _nbytes(ws), _stream(stream)), "vector_distortion")

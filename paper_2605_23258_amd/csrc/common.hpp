@@ -95,6 +95,20 @@ template <> __device__ __forceinline__ void mma_chunk_first<float>(f32x16& acc, 
 // (column = lane & 31).
 __device__ __forceinline__ int acc_row(int v, int lane_half) { return (v >> 2) * 8 + lane_half * 4 + (v & 3); }
 
+// 16 bytes of a row -> floats (8 for bf16, 4 for fp32)
+template <typename T> struct Unpack16;
+template <> struct Unpack16<bf16_t> {
+  static __device__ __forceinline__ void run(const uint4& r, float* f) {
+    f[0] = bf16_lo(r.x); f[1] = bf16_hi(r.x); f[2] = bf16_lo(r.y); f[3] = bf16_hi(r.y);
+    f[4] = bf16_lo(r.z); f[5] = bf16_hi(r.z); f[6] = bf16_lo(r.w); f[7] = bf16_hi(r.w);
+  }
+};
+template <> struct Unpack16<float> {
+  static __device__ __forceinline__ void run(const uint4& r, float* f) {
+    f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y); f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+  }
+};
+
 // ---------------------------------------------------------------------------
 // wave reductions
 // ---------------------------------------------------------------------------

@@ -51,19 +51,6 @@ constexpr int kTargetWorkgroupsMfma = VEC_DEC_TARGET;   // bf16 kernel: two work
 #endif
 constexpr double kRopeApxCost = VEC_ROPE_APX_COST;
 
-template <typename T> struct Unpack16;
-template <> struct Unpack16<bf16_t> {
-  static __device__ __forceinline__ void run(const uint4& r, float* f) {
-    f[0] = bf16_lo(r.x); f[1] = bf16_hi(r.x); f[2] = bf16_lo(r.y); f[3] = bf16_hi(r.y);
-    f[4] = bf16_lo(r.z); f[5] = bf16_hi(r.z); f[6] = bf16_lo(r.w); f[7] = bf16_hi(r.w);
-  }
-};
-template <> struct Unpack16<float> {
-  static __device__ __forceinline__ void run(const uint4& r, float* f) {
-    f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y); f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
-  }
-};
-
 // sum over the LPR adjacent lanes that share a row; every lane of the group gets the total
 template <int LPR> __device__ __forceinline__ float group_sum(float x) {
   if constexpr (LPR == 16) {

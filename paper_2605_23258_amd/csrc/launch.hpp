@@ -49,6 +49,10 @@ int launch_residual_probe(const vector_shape& s, const void* k, const void* v, c
 size_t calibrate_workspace_bytes(const vector_shape& s);
 int launch_calibrate(const vector_shape& s, const void* k, const void* v, void* W, void* ws, hipStream_t stream);
 
+size_t distortion_workspace_bytes(int n_kv_heads, int seq_len);
+int launch_distortion(const vector_shape& s, const float* w, const uint8_t* tier, const float* eps, const void* v,
+                      double* out, void* ws, hipStream_t stream);
+
 size_t route_workspace_bytes(int n_kv_heads, int seq_len, int n_pool);
 int launch_route(int n_kv_heads, int seq_len, const float* score, const float* eps, int n_pool, int n_approx,
                  uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx, void* ws, hipStream_t stream);

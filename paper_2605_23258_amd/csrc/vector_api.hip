@@ -136,6 +136,20 @@ int vector_calibrate(const vector_shape* s, const void* k, const void* v, void* 
   return vec::launch_calibrate(*s, k, v, W, ws, (hipStream_t)stream);
 }
 
+size_t vector_distortion_workspace_bytes(const vector_shape* s) {
+  if (check_shape(s, false) != VECTOR_OK) return 0;
+  return vec::distortion_workspace_bytes(s->n_kv_heads, s->seq_len);
+}
+
+int vector_distortion(const vector_shape* s, const float* weights, const uint8_t* tier, const float* eps, const void* v,
+                      double* out, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_shape(s, false);
+  if (rc) return rc;
+  if (!weights || !tier || !eps || !v || !out || !aligned16(v)) return VECTOR_ERR_ARG;
+  if ((rc = check_ws(ws, ws_bytes, vec::distortion_workspace_bytes(s->n_kv_heads, s->seq_len)))) return rc;
+  return vec::launch_distortion(*s, weights, tier, eps, v, out, ws, (hipStream_t)stream);
+}
+
 int vector_probe_residual_mfma(const vector_shape* s, const void* k, const void* v, const void* W, float* eps,
                                int32_t repeat, void* stream) {
   int rc = check_shape(s, false);
