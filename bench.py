@@ -69,6 +69,8 @@ def main() -> None:
     ap.add_argument("--cpu-sample-layers", type=int, default=6)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (reference kernel for scaling HBM counters)")
+    ap.add_argument("--extras", action="store_true",
+                    help="also time the entry points beyond the benchmark workload (post-RoPE variants, calibration, diagnostics)")
     ap.add_argument("--streams", type=int, default=3,
                     help="HIP streams the layers are spread over (layers are independent)")
     args = ap.parse_args()
@@ -229,6 +231,10 @@ def main() -> None:
                "sample": f"{ns} of {cfg.layers} layers of the same workload, {dt:.1f}s (numpy fp64; BLAS threads as listed, Python loops single-threaded)"}
         log(f"cpu oracle: {cpu}")
 
+    extras = None
+    if args.extras:
+        extras = run_extras(vb, dg, pl, torch, np, dev, cfg, shape, layers[0], outs[0], wss[0], n_p, n_a)
+
     line = {
         "metric": "KV tokens compressed/sec (prefill pass)", "value": round(tokens_per_s, 1), "unit": "KV tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -245,7 +251,70 @@ def main() -> None:
         "decode": decode,
         "cpu_baseline": cpu,
     }
+    if extras is not None:
+        line["extras"] = extras
     print(json.dumps(line), flush=True)
+
+
+def run_extras(vb, dg, pl, torch, np, dev, cfg, shape, layer, out, ws, n_p, n_a):
+    """Entry points outside the benchmark workload, timed as back-to-back launches on one stream
+    (wall clock per call, synchronised at both ends)."""
+    H, n, d = cfg.n_kv_heads, cfg.seq_len, cfg.head_dim
+
+    def per_call_us(fn, calls=20):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(calls):
+            fn()
+        torch.cuda.synchronize()
+        return round((time.perf_counter() - t0) / calls * 1e6, 1)
+
+    res = {}
+    inv_freq = dg.rotary_inv_freq(d, 500000.0)
+    rope, keep = vb.make_rope(inv_freq, None, False, 0)
+    # the cfg-3 layer read as a post-RoPE cache (same bytes; the un-rotation does the same work on any keys)
+    res["score_residual_rope_us_per_layer"] = per_call_us(
+        lambda: vb.vector_score_residual_rope(shape, layer["q_win"], layer["k"], layer["v"], layer["w_cal"], rope, out.score, out.eps, ws))
+    res["score_residual_us_per_layer"] = per_call_us(
+        lambda: vb.vector_score_residual(shape, layer["q_win"], layer["k"], layer["v"], layer["w_cal"], out.score, out.eps, ws))
+    # decode over a cfg-5 shaped cache of random rows, with and without the un-rotation
+    c5 = dg.CONFIGS["cfg5"]
+    n_r5, n_a5, n_p5 = c5.counts()
+    B = c5.batch
+    g = torch.Generator(device=dev).manual_seed(7)
+    rnd = lambda *sh: torch.randn(*sh, generator=g, device=dev, dtype=torch.float32).bfloat16()
+    k_ret, v_ret, k_apx = rnd(B, H, n_r5, d), rnd(B, H, n_r5, d), rnd(B, H, n_a5, d)
+    q = rnd(B, c5.n_q_heads, d)
+    pos = torch.sort(torch.randint(0, c5.seq_len, (B, H, n_a5), generator=g, device=dev, dtype=torch.int32), dim=-1).values.contiguous()
+    length = torch.full((B,), n_r5, dtype=torch.int32, device=dev)
+    cache = vb.Cache(batch=B, n_q_heads=c5.n_q_heads, n_kv_heads=H, head_dim=d, dtype=vb.VECTOR_BF16, cap_retain=n_r5, n_approx=n_a5)
+    cache.len_retain, cache.k_ret, cache.v_ret = length.data_ptr(), k_ret.data_ptr(), v_ret.data_ptr()
+    cache.k_apx, cache.W = k_apx.data_ptr(), layer["w_cal"].data_ptr()
+    ws5 = pl.alloc_workspace(vb.vector_workspace_bytes(pl.shape_of(c5), n_p5, n_a5, B), dev)
+    o5 = torch.empty((B, c5.n_q_heads, d), dtype=torch.bfloat16, device=dev)
+    rope5, keep5 = vb.make_rope(inv_freq, pos, False, 0)
+    scale = 1.0 / float(np.sqrt(d))
+    res["decode_attn_rope_us_per_step"] = per_call_us(lambda: vb.vector_decode_attn_rope(cache, rope5, q, scale, o5, ws5), 50)
+    res["decode_attn_us_per_step"] = per_call_us(lambda: vb.vector_decode_attn(cache, q, scale, o5, ws5), 50)
+    # calibration on 262144 tokens per head (random keys, values linear in them plus noise)
+    m = 262144
+    kc = rnd(H, m, d)
+    vc = (kc.float() @ (torch.randn(H, d, d, generator=g, device=dev) / d ** 0.5) + 0.1 * torch.randn(H, m, d, generator=g, device=dev)).bfloat16()
+    cshape = vb.Shape(n_q_heads=H, n_kv_heads=H, head_dim=d, seq_len=m, window=1, pool_kernel=1, dtype=vb.VECTOR_BF16)
+    wsc = pl.alloc_workspace(vb.vector_calibrate_workspace_bytes(cshape), dev)
+    Wc = torch.empty((H, d, d), dtype=torch.bfloat16, device=dev)
+    us = per_call_us(lambda: vb.vector_calibrate(cshape, kc, vc, Wc, wsc), 5)
+    res["calibrate_262144_tokens_us"] = us
+    res["calibrate_gram_flops"] = int(H * 2 * 2 * m * d * d)
+    del kc, vc
+    # diagnostics on the layer's own routing
+    dout = torch.empty((H, len(vb.DISTORTION_FIELDS)), dtype=torch.float64, device=dev)
+    wsd = pl.alloc_workspace(vb.vector_distortion_workspace_bytes(shape), dev)
+    wts = torch.softmax(torch.randn(H, n, generator=g, device=dev), dim=-1)
+    res["distortion_us_per_layer"] = per_call_us(lambda: vb.vector_distortion(shape, wts, out.tier, out.eps, layer["v"], dout, wsd))
+    log(f"extras: {res}")
+    return res
 
 
 def run_decode(args, vb, dg, pl, torch, np, dev, workers):

@@ -30,7 +30,7 @@ struct CalParams {
   int m;                                    // calibration tokens per head
   int tokens_per_chunk, n_chunks;
   float* part;                              // [Hkv, n_chunks, 2, d, d] fp32: K^T K, then K^T V
-  double* c64;                              // [Hkv, d, d] fp64 scratch: K^T V, then W
+  double* c64;                              // [Hkv, d, d] fp64 scratch: the Cholesky factor during the solves
   void* W;                                  // [Hkv, d, d] out
   int* status;                              // [Hkv]: 0 ok, 1 not positive definite
 };
@@ -175,36 +175,45 @@ __global__ __launch_bounds__(kCalThreads) void gram_valu_kernel(CalParams p) {
 template <typename T, int D>
 __global__ __launch_bounds__(kCalThreads) void solve_kernel(CalParams p) {
   extern __shared__ __align__(16) unsigned char cal_smem[];
-  double* G = reinterpret_cast<double*>(cal_smem);           // [D][D]: K^T K, then its lower Cholesky factor
+  constexpr int LD = D + 1;                                  // padded row: a column walk hits distinct banks
+  double* G = reinterpret_cast<double*>(cal_smem);           // [D][LD]: K^T K, then its Cholesky factor; later K^T V / W
   __shared__ int bad;
   const int h = blockIdx.x;
   const float* part = p.part + (size_t)h * p.n_chunks * 2 * D * D;
-  double* C = p.c64 + (size_t)h * D * D;
+  double* Lg = p.c64 + (size_t)h * D * D;                    // the factor, parked in global memory for the solves
   if (threadIdx.x == 0) bad = 0;
   for (int o = threadIdx.x; o < D * D; o += kCalThreads) {
-    double g = 0.0, c = 0.0;
-    for (int ch = 0; ch < p.n_chunks; ++ch) {
-      g += (double)part[(size_t)ch * 2 * D * D + o];
-      c += (double)part[(size_t)ch * 2 * D * D + D * D + o];
-    }
-    G[o] = g;
-    C[o] = c;
+    double g = 0.0;
+#pragma unroll 8
+    for (int ch = 0; ch < p.n_chunks; ++ch) g += (double)part[(size_t)ch * 2 * D * D + o];
+    G[(o / D) * LD + o % D] = g;
   }
   __syncthreads();
-  // right-looking Cholesky on the lower triangle
+  // left-looking Cholesky, one thread per row: column kk of the factor is
+  //   L[i][kk] = (G[i][kk] - sum_{q < kk} L[i][q] L[kk][q]) / L[kk][kk],   i >= kk
   for (int kk = 0; kk < D; ++kk) {
-    const double piv = G[kk * D + kk];
-    if (!(piv > 0.0)) { if (threadIdx.x == 0) bad = 1; }
-    __syncthreads();
-    if (bad) break;
-    const double inv = 1.0 / sqrt(piv);
-    for (int i = kk + threadIdx.x; i < D; i += kCalThreads) G[i * D + kk] *= inv;     // includes the diagonal: sqrt(piv)
-    __syncthreads();
-    const int rest = D - kk - 1;
-    for (int o = threadIdx.x; o < rest * rest; o += kCalThreads) {
-      const int i = kk + 1 + o / rest, j = kk + 1 + o % rest;
-      if (j <= i) G[i * D + j] -= G[i * D + kk] * G[j * D + kk];
+    const int i = threadIdx.x;
+    double v = 0.0;
+    if (i >= kk && i < D) {
+      // four running sums and an unrolled body: the loads of several steps are in flight together
+      double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+      int q = 0;
+#pragma unroll 2
+      for (; q + 4 <= kk; q += 4) {
+        a0 += G[i * LD + q] * G[kk * LD + q];
+        a1 += G[i * LD + q + 1] * G[kk * LD + q + 1];
+        a2 += G[i * LD + q + 2] * G[kk * LD + q + 2];
+        a3 += G[i * LD + q + 3] * G[kk * LD + q + 3];
+      }
+      for (; q < kk; ++q) a0 += G[i * LD + q] * G[kk * LD + q];
+      v = G[i * LD + kk] - ((a0 + a1) + (a2 + a3));
     }
+    if (i == kk && !(v > 0.0)) bad = 1;
+    __syncthreads();                            // every row has read what it needs of column kk's old values
+    if (bad) break;
+    if (i == kk) G[kk * LD + kk] = sqrt(v);
+    __syncthreads();
+    if (i > kk && i < D) G[i * LD + kk] = v / G[kk * LD + kk];
     __syncthreads();
   }
   T* Wh = reinterpret_cast<T*>(p.W) + (size_t)h * D * D;
@@ -214,22 +223,75 @@ __global__ __launch_bounds__(kCalThreads) void solve_kernel(CalParams p) {
     return;
   }
   if (threadIdx.x == 0) p.status[h] = 0;
-  __threadfence_block();
-  // one thread per column j of W: L y = c_j, then L^T x = y, in place in C (row i of all
-  // columns is contiguous, so the threads' accesses coalesce)
-  const int j = threadIdx.x;
-  if (j < D) {
-    for (int i = 0; i < D; ++i) {
-      double s = C[i * D + j];
-      for (int q = 0; q < i; ++q) s -= G[i * D + q] * C[q * D + j];
-      C[i * D + j] = s / G[i * D + i];
+  // Solves out of LDS: the factor is repacked as its lower triangle (through global memory,
+  // which avoids an in-place shuffle), and the right-hand sides come in blocks of kCols columns.
+  for (int o = threadIdx.x; o < D * D; o += kCalThreads) Lg[o] = G[(o / D) * LD + o % D];
+  __syncthreads();
+  double* Lp = G;                                             // packed: L[i][q] at i (i + 1) / 2 + q
+  for (int o = threadIdx.x; o < D * D; o += kCalThreads) {
+    const int i = o / D, q = o % D;
+    if (q <= i) Lp[i * (i + 1) / 2 + q] = Lg[o];
+  }
+  constexpr int kSplit = 4;                                   // adjacent lanes that share a column's inner sums
+  constexpr int kCols = kCalThreads / kSplit;                 // columns per block
+  static_assert(D % kCols == 0 || kCols % D == 0, "column blocks");
+  constexpr int kBlockCols = kCols < D ? kCols : D;
+  double* C = Lp + D * (D + 1) / 2;                           // [D][kBlockCols]
+  const int jl = threadIdx.x / kSplit, r = threadIdx.x % kSplit;
+  auto wave_sync = [&]() {                                    // the lanes of a column sit in one wave
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  };
+  for (int j0 = 0; j0 < D; j0 += kBlockCols) {
+    __syncthreads();                                          // packed factor in place / previous block done
+    for (int o = threadIdx.x; o < D * kBlockCols; o += kCalThreads) {
+      const int i = o / kBlockCols, jj = o % kBlockCols;
+      double c = 0.0;
+#pragma unroll 8
+      for (int ch = 0; ch < p.n_chunks; ++ch) c += (double)part[(size_t)ch * 2 * D * D + D * D + i * D + j0 + jj];
+      C[o] = c;
     }
-    for (int i = D - 1; i >= 0; --i) {
-      double s = C[i * D + j];
-      for (int q = i + 1; q < D; ++q) s -= G[q * D + i] * C[q * D + j];
-      s /= G[i * D + i];
-      C[i * D + j] = s;
-      store_elem(Wh + (size_t)i * D + j, (float)s);
+    __syncthreads();
+    if (jl < kBlockCols) {
+      // L y = c_j
+      for (int i = 0; i < D; ++i) {
+        const double* Li = Lp + i * (i + 1) / 2;
+        double s = 0.0, s1 = 0.0;
+        int q = r;
+#pragma unroll 4
+        for (; q + kSplit < i; q += 2 * kSplit) {
+          s += Li[q] * C[q * kBlockCols + jl];
+          s1 += Li[q + kSplit] * C[(q + kSplit) * kBlockCols + jl];
+        }
+        if (q < i) s += Li[q] * C[q * kBlockCols + jl];
+        s += s1;
+#pragma unroll
+        for (int o = 1; o < kSplit; o <<= 1) s += __shfl_xor(s, o, kWave);
+        if (r == 0) C[i * kBlockCols + jl] = (C[i * kBlockCols + jl] - s) / Li[i];
+        wave_sync();
+      }
+      // L^T x = y
+      for (int i = D - 1; i >= 0; --i) {
+        double s = 0.0, s1 = 0.0;
+        int q = i + 1 + r;
+#pragma unroll 4
+        for (; q + kSplit < D; q += 2 * kSplit) {
+          s += Lp[q * (q + 1) / 2 + i] * C[q * kBlockCols + jl];
+          s1 += Lp[(q + kSplit) * (q + kSplit + 1) / 2 + i] * C[(q + kSplit) * kBlockCols + jl];
+        }
+        if (q < D) s += Lp[q * (q + 1) / 2 + i] * C[q * kBlockCols + jl];
+        s += s1;
+#pragma unroll
+        for (int o = 1; o < kSplit; o <<= 1) s += __shfl_xor(s, o, kWave);
+        const double x = (C[i * kBlockCols + jl] - s) / Lp[i * (i + 1) / 2 + i];
+        wave_sync();
+        if (r == 0) {
+          C[i * kBlockCols + jl] = x;
+          store_elem(Wh + (size_t)i * D + j0 + jl, (float)x);
+        }
+        wave_sync();
+      }
     }
   }
 }
@@ -248,7 +310,10 @@ int run_calibrate(const vector_shape& s, CalParams& p, hipStream_t stream) {
   const dim3 grid(p.n_chunks, s.n_kv_heads);
   if constexpr (Elem<T>::kDtype == VECTOR_BF16) hipLaunchKernelGGL(gram_kernel<D>, grid, dim3(kCalThreads), 0, stream, p);
   else hipLaunchKernelGGL(gram_valu_kernel<D>, grid, dim3(kCalThreads), 0, stream, p);
-  const size_t lds = (size_t)D * D * sizeof(double);
+  // padded square for the factorisation; packed triangle plus a block of right-hand sides for the solves
+  constexpr int kBlockCols = (kCalThreads / 4) < D ? (kCalThreads / 4) : D;
+  constexpr size_t kFactor = (size_t)D * (D + 1), kSolve = (size_t)D * (D + 1) / 2 + (size_t)D * kBlockCols;
+  const size_t lds = (kFactor > kSolve ? kFactor : kSolve) * sizeof(double);
   VEC_HIP(set_max_lds(reinterpret_cast<const void*>(solve_kernel<T, D>), lds));
   hipLaunchKernelGGL((solve_kernel<T, D>), dim3(s.n_kv_heads), dim3(kCalThreads), lds, stream, p);
   VEC_HIP(hipGetLastError());
