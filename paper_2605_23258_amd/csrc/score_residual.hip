@@ -922,9 +922,10 @@ struct Plan {
 };
 
 #ifndef VEC_TILES_MIN_WGS
-#define VEC_TILES_MIN_WGS 512
+#define VEC_TILES_MIN_WGS 256
 #endif
-// pass 1 through LDS tiles: two workgroups per CU hide each other's barriers and LDS round trips
+// pass 1 through LDS tiles: one workgroup per CU where the sequence allows it (more, shorter chunks
+// gain a microsecond in pass 1 and lose two in the partial merge of pass 2)
 int pick_tokens_per_chunk_tiles(int n, int n_kv_heads) {
   int tpc = 2048;
   while (tpc > 256 && (int64_t)((n + tpc - 1) / tpc) * n_kv_heads < VEC_TILES_MIN_WGS) tpc >>= 1;
