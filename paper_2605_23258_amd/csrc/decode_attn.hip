@@ -47,7 +47,7 @@ constexpr int kTargetWorkgroups = 768;
 #endif
 constexpr int kTargetWorkgroupsMfma = VEC_DEC_TARGET;   // bf16 kernel: two workgroups fit a CU
 #ifndef VEC_ROPE_APX_COST
-#define VEC_ROPE_APX_COST 3.0
+#define VEC_ROPE_APX_COST 2.2
 #endif
 constexpr double kRopeApxCost = VEC_ROPE_APX_COST;
 
@@ -326,63 +326,100 @@ __global__ __launch_bounds__(DT_, 2) void decode_split_mfma_kernel(DecodeParams 
 
   const int ld_row = lane / TL::kPieces, ld_piece = lane % TL::kPieces;
   const int32_t* pos_seg = (ROPE && is_apx && rp.positions) ? rp.positions + bh * p.n_approx : nullptr;
+  // Which 16 bytes of the tile a lane brings in with its i-th load.  Normally 16 adjacent lanes
+  // share a row.  For approximated rows that are to be un-rotated with pairs (x[i], x[i + d/2])
+  // a lane instead takes both members of its pairs: loads 2u and 2u+1 bring pieces p and
+  // p + kPieces/2 of the same row, kPieces/2 adjacent lanes share a row.
+  constexpr int HP = TL::kPieces / 2;
+  constexpr int kRowsPerPair = kWave / HP;
+  const bool paired = ROPE && is_apx && !rp.interleaved;
+  const int pr_row = lane / HP, pr_piece = lane % HP;
+  auto row_of = [&](int i) { return paired ? (i / 2) * kRowsPerPair + pr_row : i * TL::kRowsPerLoad + ld_row; };
+  auto piece_of = [&](int i) { return paired ? pr_piece + (i & 1) * HP : ld_piece; };
   // For an approximated row under ROPE the second register set carries the row's position
   // (in .x) instead of a value row.
+  // (the segment is the same for the whole workgroup: one straight-line loop per case, so that
+  // all loads of a tile go out together)
   auto fetch = [&](uint4* kraw, uint4* vraw, int base) {
+    if (!ROPE || !is_apx) {
 #pragma unroll
-    for (int i = 0; i < TL::kLoads; ++i) {
-      const int r = min(base + i * TL::kRowsPerLoad + ld_row, seg_len - 1);   // clamped: never past the live rows
-      kraw[i] = load_chunk(kseg + (size_t)r * D + ld_piece * 8);
-      if (!is_apx) vraw[i] = load_chunk(vseg + (size_t)r * D + ld_piece * 8);
-      else if (ROPE) vraw[i].x = (uint32_t)((pos_seg ? pos_seg[r] : r) + rp.pos_offset);
+      for (int i = 0; i < TL::kLoads; ++i) {
+        const int r = min(base + i * TL::kRowsPerLoad + ld_row, seg_len - 1);   // clamped: never past the live rows
+        kraw[i] = load_chunk(kseg + (size_t)r * D + ld_piece * 8);
+        if (!is_apx) vraw[i] = load_chunk(vseg + (size_t)r * D + ld_piece * 8);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < TL::kLoads; ++i) {
+        const int r = min(base + row_of(i), seg_len - 1);
+        kraw[i] = load_chunk(kseg + (size_t)r * D + piece_of(i) * 8);
+        vraw[i].x = (uint32_t)((pos_seg ? pos_seg[r] : r) + rp.pos_offset);
+      }
     }
   };
-  // the 16-byte piece of a cached key row, turned back by the row's position.  Pairs
-  // (i, i + d/2) sit kPieces/2 lanes apart in the same row; pairs (2i, 2i+1) in the same lane.
-  // this lane's piece always covers the same rotary pairs: their frequencies stay in registers
+  // the lane's pieces always cover the same rotary pairs: their frequencies stay in registers
   float t_hi[8], t_lo[8];
   if (ROPE && is_apx) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const int i = rp.interleaved ? (ld_piece * 8 + e) / 2 : (ld_piece % (TL::kPieces / 2)) * 8 + e;
+      const int i = rp.interleaved ? (ld_piece * 8 + e) / 2 : pr_piece * 8 + e;
       t_hi[e] = rp.turns_hi[i];
       t_lo[e] = rp.turns_lo[i];
     }
   }
+  auto pack8 = [](const float* f) {
+    return make_uint4(pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3]), pack_bf16(f[4], f[5]), pack_bf16(f[6], f[7]));
+  };
+  // both members of eight pairs (x[i], x[i + d/2]) of a cached key row, turned back by the row's position
+  auto unrotate_pair = [&](const uint4& ra, const uint4& rb, int pos, uint4& oa, uint4& ob) {
+    float a[8], b[8];
+    const float pf = (float)pos;
+    Unpack16<T>::run(ra, a);
+    Unpack16<T>::run(rb, b);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float cs, sn;
+      rotary_cos_sin(pf, t_hi[e], t_lo[e], cs, sn);
+      rotary_back(a[e], b[e], cs, sn, a[e], b[e]);
+    }
+    oa = pack8(a);
+    ob = pack8(b);
+  };
+  // pairs (x[2i], x[2i+1]): four of them inside one 16-byte piece
   auto unrotate_piece = [&](const uint4& raw, int pos) {
-    float f[8], g[8];
+    float f[8];
     const float pf = (float)pos;
     Unpack16<T>::run(raw, f);
-    if (!rp.interleaved) {
-      uint4 other;
-      other.x = __shfl_xor(raw.x, TL::kPieces / 2, kWave); other.y = __shfl_xor(raw.y, TL::kPieces / 2, kWave);
-      other.z = __shfl_xor(raw.z, TL::kPieces / 2, kWave); other.w = __shfl_xor(raw.w, TL::kPieces / 2, kWave);
-      Unpack16<T>::run(other, g);
-      const bool first = ld_piece < TL::kPieces / 2;          // holds the first member of its pairs
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float cs, sn;
-        rotary_cos_sin(pf, t_hi[e], t_lo[e], cs, sn);
-        // first member: a cos + b sin; second member: b cos - a sin
-        f[e] = first ? fmaf(f[e], cs, g[e] * sn) : fmaf(f[e], cs, -(g[e] * sn));
+    for (int e = 0; e < 8; e += 2) {
+      float cs, sn;
+      rotary_cos_sin(pf, t_hi[e], t_lo[e], cs, sn);
+      rotary_back(f[e], f[e + 1], cs, sn, f[e], f[e + 1]);
+    }
+    return pack8(f);
+  };
+  auto stage = [&](const uint4* kraw, const uint4* vraw) {
+    if (!is_apx || !ROPE) {
+#pragma unroll
+      for (int i = 0; i < TL::kLoads; ++i) {
+        const int off = (i * TL::kRowsPerLoad + ld_row) * TL::kStride + ld_piece * 16;
+        *reinterpret_cast<uint4*>(k_tile + off) = kraw[i];
+        if (!is_apx) *reinterpret_cast<uint4*>(v_tile + off) = vraw[i];
       }
     } else {
 #pragma unroll
-      for (int e = 0; e < 8; e += 2) {
-        float cs, sn;
-        rotary_cos_sin(pf, t_hi[e], t_lo[e], cs, sn);
-        rotary_back(f[e], f[e + 1], cs, sn, f[e], f[e + 1]);
+      for (int i = 0; i < TL::kLoads; ++i) {
+        const int off = row_of(i) * TL::kStride + piece_of(i) * 16;
+        *reinterpret_cast<uint4*>(k_tile + off) = kraw[i];
+        if (!paired) {
+          *reinterpret_cast<uint4*>(v_tile + off) = unrotate_piece(kraw[i], (int)vraw[i].x);
+        } else if (i & 1) {
+          uint4 oa, ob;
+          unrotate_pair(kraw[i - 1], kraw[i], (int)vraw[i].x, oa, ob);
+          *reinterpret_cast<uint4*>(v_tile + row_of(i - 1) * TL::kStride + piece_of(i - 1) * 16) = oa;
+          *reinterpret_cast<uint4*>(v_tile + off) = ob;
+        }
       }
-    }
-    return make_uint4(pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3]), pack_bf16(f[4], f[5]), pack_bf16(f[6], f[7]));
-  };
-  auto stage = [&](const uint4* kraw, const uint4* vraw) {
-#pragma unroll
-    for (int i = 0; i < TL::kLoads; ++i) {
-      const int off = (i * TL::kRowsPerLoad + ld_row) * TL::kStride + ld_piece * 16;
-      *reinterpret_cast<uint4*>(k_tile + off) = kraw[i];
-      if (!is_apx) *reinterpret_cast<uint4*>(v_tile + off) = vraw[i];
-      else if (ROPE) *reinterpret_cast<uint4*>(v_tile + off) = unrotate_piece(kraw[i], (int)vraw[i].x);
     }
   };
   // the tile belongs to this wave alone; these keep the compiler from moving LDS accesses of
@@ -691,7 +728,7 @@ int launch_decode_attn(const vector_cache& c, const void* q, float scale, void* 
   // an approximated row costs its bytes; with the rotary un-rotation, its 64 sine/cosine pairs
   // make it about as expensive as six rows' worth of streaming
   // an approximated row costs its bytes; with the rotary un-rotation its sines and cosines make
-  // it cost about as much as three rows' worth of streaming
+  // it cost about as much as two rows' worth of streaming
   pick_splits(c.dtype == VECTOR_BF16 ? kTargetWorkgroupsMfma : kTargetWorkgroups, c.batch, c.n_kv_heads, c.cap_retain, c.n_approx,
               rope ? kRopeApxCost : 1.0, p.splits_ret, p.splits_apx);
   p.w_sh = c.w_shared ? 0 : (int64_t)c.head_dim * c.head_dim;
