@@ -725,8 +725,6 @@ int launch_decode_attn(const vector_cache& c, const void* q, float scale, void* 
   p.q = q; p.k_ret = c.k_ret; p.v_ret = c.v_ret; p.k_apx = c.k_apx; p.W = c.W; p.len_retain = c.len_retain;
   p.out = out; p.part = reinterpret_cast<float*>(ws);
   p.B = c.batch; p.Hq = c.n_q_heads; p.Hkv = c.n_kv_heads; p.cap_retain = c.cap_retain; p.n_approx = c.n_approx;
-  // an approximated row costs its bytes; with the rotary un-rotation, its 64 sine/cosine pairs
-  // make it about as expensive as six rows' worth of streaming
   // an approximated row costs its bytes; with the rotary un-rotation its sines and cosines make
   // it cost about as much as two rows' worth of streaming
   pick_splits(c.dtype == VECTOR_BF16 ? kTargetWorkgroupsMfma : kTargetWorkgroups, c.batch, c.n_kv_heads, c.cap_retain, c.n_approx,
