@@ -615,7 +615,7 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
   }
   // pass 1's chunk partials of this thread's row: `tpr` adjacent lanes share one row and
   // each takes every tpr-th chunk; the first kPre of them are requested here
-  constexpr int kPre = 32;
+  constexpr int kPre = 16;
   const int tpr = p.threads_per_row, sub = threadIdx.x % tpr;
   const int rows_per_sweep = NT / tpr;
   float2 pre[kPre];
@@ -670,9 +670,15 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
           for (int u = 0; u < kPre; ++u) fold(m, l, pre[u].x, pre[u].y);
           c_from = sub + kPre * tpr;
         }
-        for (int c = c_from; c < p.n_chunks; c += tpr) {
-          const float2 sv = part[c];
-          fold(m, l, sv.x, sv.y);
+        for (int c0 = c_from; c0 < p.n_chunks; c0 += 8 * tpr) {       // the rest, eight loads in flight at a time
+          float2 sv[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const int c = c0 + u * tpr;
+            sv[u] = (c < p.n_chunks) ? part[c] : make_float2(-INFINITY, 0.f);
+          }
+#pragma unroll
+          for (int u = 0; u < 8; ++u) fold(m, l, sv[u].x, sv[u].y);
         }
       }
       for (int o = 1; o < tpr; o <<= 1) {
