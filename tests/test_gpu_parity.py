@@ -116,7 +116,9 @@ def _assert_route_equal(score, eps, n_pool, n_approx):
 
 @pytest.mark.parametrize("n,n_pool,n_approx", [
     (1, 1, 1), (1, 0, 0), (5, 5, 0), (64, 10, 10), (1000, 300, 150), (4096, 1228, 614), (4097, 4097, 2000),
-    (5000, 0, 0), (12345, 2469, 1234), (40000, 8000, 4000)])
+    (5000, 0, 0), (12345, 2469, 1234), (40000, 8000, 4000),
+    # beyond 32768 tokens per head the selection by score runs chip-wide in chunks of 8192
+    (32769, 100, 50), (65536, 65536, 30000), (70000, 40000, 20000), (100000, 1, 1), (49152, 0, 0), (90001, 9000, 0)])
 def test_route_bit_exact_random(n, n_pool, n_approx):
     rng = np.random.default_rng(n * 7 + n_pool)
     score = rng.random((3, n)).astype(np.float32)
@@ -135,6 +137,18 @@ def test_route_bit_exact_heavy_ties_and_signed_zero():
     score[2] = 1.0                      # all equal: lowest indices win
     eps[3] = 0.0
     for n_pool, n_approx in ((1500, 700), (n, n // 2), (1, 1), (2999, 0)):
+        _assert_route_equal(score, eps, n_pool, n_approx)
+
+
+def test_route_long_sequence_with_heavy_ties():
+    """Ties across chunk boundaries of the chip-wide path: the lowest token indices win."""
+    rng = np.random.default_rng(9)
+    n = 50000
+    score = rng.integers(0, 4, size=(3, n)).astype(np.float32) * 0.5
+    eps = rng.integers(0, 3, size=(3, n)).astype(np.float32)
+    score[1] = 2.0                      # all equal
+    score[2, ::3] = -0.0
+    for n_pool, n_approx in ((20000, 9000), (n, 100), (8193, 8193), (1, 0)):
         _assert_route_equal(score, eps, n_pool, n_approx)
 
 
