@@ -78,9 +78,15 @@ __device__ __forceinline__ void fill_rows_lds(unsigned char* lds, const T* src, 
       int i = base + u * NT + shift;
       if (i >= total) i -= total;
       const int row = i / P, piece = i - row * P;
-      x[u] = make_uint4(0, 0, 0, 0);
-      if (base + u * NT < total && row < rows)
-        x[u] = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(src) + (size_t)row * Tile<T, D>::kRowBytes + piece * 16);
+      // always load (from a clamped row) and blank afterwards: a load under a branch makes the
+      // compiler wait for every earlier load as well
+      x[u] = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(src) + (size_t)min(row, rows - 1) * Tile<T, D>::kRowBytes + piece * 16);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int i = base + u * NT + shift;
+      if (i >= total) i -= total;
+      if (!(base + u * NT < total && i / P < rows)) x[u] = make_uint4(0, 0, 0, 0);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -609,8 +615,8 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
     const T* Wh = reinterpret_cast<const T*>(p.W) + (int64_t)h * p.w_sh;
 #pragma unroll
     for (int u = 0; u < WU; ++u) {
-      const int i = threadIdx.x + u * NT;
-      if (i < D * D / E) wpiece[u].raw = load_chunk(Wh + (size_t)(i / (D / E)) * D + (i % (D / E)) * E);
+      const int i = min(threadIdx.x + u * NT, D * D / E - 1);      // clamped: the store below is guarded
+      wpiece[u].raw = load_chunk(Wh + (size_t)(i / (D / E)) * D + (i % (D / E)) * E);
     }
   }
   // pass 1's chunk partials of this thread's row: `tpr` adjacent lanes share one row and
@@ -620,14 +626,11 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
   const int rows_per_sweep = NT / tpr;
   float2 pre[kPre];
   if (DO_MASS) {
-    const int row = threadIdx.x / tpr;
-    if (row < p.R_pad) {
+    {
+      const int row = min((int)threadIdx.x / tpr, p.R_pad - 1);      // threads beyond R_pad rows load a duplicate
       const float2* part = p.part + ((size_t)h * p.R_pad + row) * p.n_chunks;
 #pragma unroll
-      for (int u = 0; u < kPre; ++u) {
-        const int c = sub + u * tpr;
-        pre[u] = (c < p.n_chunks) ? part[c] : make_float2(-INFINITY, 0.f);
-      }
+      for (int u = 0; u < kPre; ++u) pre[u] = part[min(sub + u * tpr, p.n_chunks - 1)];   // blanked when folded
     }
     fill_rows_lds<T, D, NT>(q_lds, reinterpret_cast<const T*>(p.q) + (size_t)h * p.R * D, p.R, p.R_pad, chunk * 8);
   }
@@ -667,18 +670,21 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
         int c_from = sub;
         if (row0 == 0) {                       // the preloaded ones
 #pragma unroll
-          for (int u = 0; u < kPre; ++u) fold(m, l, pre[u].x, pre[u].y);
+          for (int u = 0; u < kPre; ++u) {
+            const bool in = sub + u * tpr < p.n_chunks;
+            fold(m, l, in ? pre[u].x : -INFINITY, in ? pre[u].y : 0.f);
+          }
           c_from = sub + kPre * tpr;
         }
         for (int c0 = c_from; c0 < p.n_chunks; c0 += 8 * tpr) {       // the rest, eight loads in flight at a time
           float2 sv[8];
 #pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            const int c = c0 + u * tpr;
-            sv[u] = (c < p.n_chunks) ? part[c] : make_float2(-INFINITY, 0.f);
-          }
+          for (int u = 0; u < 8; ++u) sv[u] = part[min(c0 + u * tpr, p.n_chunks - 1)];
 #pragma unroll
-          for (int u = 0; u < 8; ++u) fold(m, l, sv[u].x, sv[u].y);
+          for (int u = 0; u < 8; ++u) {
+            const bool in = c0 + u * tpr < p.n_chunks;
+            fold(m, l, in ? sv[u].x : -INFINITY, in ? sv[u].y : 0.f);
+          }
         }
       }
       for (int o = 1; o < tpr; o <<= 1) {
