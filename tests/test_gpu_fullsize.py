@@ -80,6 +80,42 @@ def test_prefill_32k_layer(layer):
     _compress_and_check(dg.CONFIGS["cfg3"], layer)
 
 
+def test_prefill_32k_layers_on_three_streams():
+    """The benchmark's launch configuration: consecutive layers enqueued on three streams, each
+    with its own workspace, before anything is waited for.  Every layer is then checked as above
+    (floats against the oracle, routing and compaction bit for bit on the GPU's floats)."""
+    cfg = dg.CONFIGS["cfg3"]
+    layers = [4, 5, 6, 7, 8, 9]
+    shape = pl.shape_of(cfg)
+    n_r, n_a, n_p = cfg.counts()
+    n, w = cfg.seq_len, cfg.window
+    from threadpoolctl import threadpool_limits
+    with threadpool_limits(limits=1), ThreadPoolExecutor(6) as ex:
+        lis = list(ex.map(lambda l: dg.make_layer(cfg, l), layers))
+    devs = [{k: pl.to_device(getattr(li, k)) for k in ("q_win", "k", "v", "w_cal")} for li in lis]
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    wss = [pl.alloc_workspace(vb.vector_workspace_bytes(shape, n_p, n_a, 1)) for _ in range(3)]
+    outs = [pl.alloc_outputs(shape, n_p, n_a, n_r, torch.bfloat16) for _ in layers]
+    torch.cuda.synchronize()
+    for rep in range(2):                               # the second round reuses the workspaces while the first drains
+        for i, (dev, out) in enumerate(zip(devs, outs)):
+            pl.compress_layer(shape, dev["q_win"], dev["k"], dev["v"], dev["w_cal"], n_p, n_a, out, wss[i % 3], stream=streams[i % 3])
+    torch.cuda.synchronize()
+    for li, out in list(zip(lis, outs))[::2]:          # the oracle takes a few seconds per layer: every other one
+        wide = {k: dg.widen(getattr(li, k)) for k in ("q_win", "k", "v", "w_cal")}
+        g_score, g_eps = out.score.cpu().numpy(), out.eps.cpu().numpy()
+        _close(g_score[:, : n - w].astype(np.float64) * n, vo.score(wide["q_win"], wide["k"], w, cfg.pool_kernel)[:, : n - w].astype(np.float64) * n, "n*score")
+        _close(g_eps, vo.residual(wide["k"], wide["v"], wide["w_cal"]), "eps")
+    for li, out in zip(lis, outs):
+        g_score, g_eps = out.score.cpu().numpy(), out.eps.cpu().numpy()
+        tier, idx_r, idx_a = vo.route(g_score, g_eps, n_p, n_a)
+        assert np.array_equal(out.tier.cpu().numpy(), tier)
+        assert np.array_equal(out.idx_retain.cpu().numpy(), idx_r) and np.array_equal(out.idx_approx.cpu().numpy(), idx_a)
+        rk, rv, ra = vo.compact(li.k, li.v, idx_r, idx_a)
+        assert np.array_equal(pl.to_host(out.k_ret)[:, :n_r], rk) and np.array_equal(pl.to_host(out.v_ret)[:, :n_r], rv)
+        assert np.array_equal(pl.to_host(out.k_apx)[:, :n_a], ra)
+
+
 def test_long_context_128k():
     _compress_and_check(dg.CONFIGS["cfg4"], 0)
 
