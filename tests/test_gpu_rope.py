@@ -108,3 +108,45 @@ def test_decode_on_rotated_cache(d, B, Hq, Hkv, n_r, n_a, interleaved):
     vb.vector_decode_attn(cache, t[4], scale, out2, ws)
     torch.cuda.synchronize()
     assert np.abs(dg.widen(pl.to_host(out2)) - ref).max() > 10 * ATOL
+
+
+def test_full_size_layer_and_decode_step():
+    """The 32k-token layer and the batch-16 decode shape of the benchmark, read as post-RoPE caches."""
+    cfg = dg.CONFIGS["cfg3"]
+    li = dg.make_layer(cfg, 3, rope_theta=THETA)
+    inv_freq = li.extra["inv_freq"]
+    H, n, d = cfg.n_kv_heads, cfg.seq_len, cfg.head_dim
+    n_r, n_a, n_p = cfg.counts()
+    shape = pl.shape_of(cfg)
+    dev = {x: pl.to_device(getattr(li, x)) for x in ("q_win", "k", "v", "w_cal")}
+    ws = pl.alloc_workspace(vb.vector_workspace_bytes(shape, n_p, n_a, 1))
+    rope, keep = vb.make_rope(inv_freq, None, False, 0)
+    score = torch.empty((H, n), device="cuda:0")
+    eps = torch.empty((H, n), device="cuda:0")
+    vb.vector_score_residual_rope(shape, dev["q_win"], dev["k"], dev["v"], dev["w_cal"], rope, score, eps, ws)
+    torch.cuda.synchronize()
+    ref_eps = vo.residual(dg.widen(li.k), dg.widen(li.v), dg.widen(li.w_cal), inv_freq=inv_freq)
+    close(eps.cpu().numpy(), ref_eps, "eps (rope, 32k layer)")
+    # decode: caches cut from this layer by the oracle's routing of the GPU's floats
+    B, Hq = 4, cfg.n_q_heads
+    _, idx_r, idx_a = vo.route(score.cpu().numpy(), eps.cpu().numpy(), n_p, n_a)
+    rk, rv, ra = vo.compact(li.k, li.v, idx_r, idx_a)
+    rng = np.random.default_rng(11)
+    q = dg.f32_to_bf16_bits(rng.standard_normal((B, Hq, d)).astype(np.float32))
+    k_ret, v_ret, k_apx = (np.broadcast_to(x, (B,) + x.shape).copy() for x in (rk, rv, ra))
+    pos = np.broadcast_to(idx_a.astype(np.int32), (B,) + idx_a.shape).copy()
+    t = [pl.to_device(x) for x in (k_ret, v_ret, k_apx, q, pos)]
+    length = torch.full((B,), n_r, dtype=torch.int32, device="cuda:0")
+    cache = vb.Cache(batch=B, n_q_heads=Hq, n_kv_heads=H, head_dim=d, dtype=vb.VECTOR_BF16, cap_retain=n_r, n_approx=n_a)
+    cache.len_retain, cache.k_ret, cache.v_ret, cache.k_apx, cache.W = (length.data_ptr(), t[0].data_ptr(), t[1].data_ptr(),
+                                                                      t[2].data_ptr(), dev["w_cal"].data_ptr())
+    wsd = pl.alloc_workspace(vb.vector_workspace_bytes(shape, n_p, n_a, B))
+    out = torch.empty((B, Hq, d), dtype=torch.bfloat16, device="cuda:0")
+    scale = 1.0 / np.sqrt(d)
+    rope_d, keep_d = vb.make_rope(inv_freq, t[4], False, 0)
+    vb.vector_decode_attn_rope(cache, rope_d, t[3], scale, out, wsd)
+    torch.cuda.synchronize()
+    ref = vo.decode_attn(dg.widen(q), dg.widen(k_ret), dg.widen(v_ret), np.full(B, n_r), dg.widen(k_apx), dg.widen(li.w_cal), scale,
+                         pos_apx=pos, inv_freq=inv_freq)
+    err = np.abs(dg.widen(pl.to_host(out)) - ref)
+    assert (err <= ATOL + (RTOL + 2.0 ** -8) * np.abs(ref)).all(), f"max err {err.max():.3e}"
