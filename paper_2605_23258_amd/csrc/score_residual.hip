@@ -833,12 +833,14 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
       for (int sub = 0; sub < 2; ++sub) {
         const int tok = min(t0 + 32 * sub + l31, p.n - 1);
         const float pos = (float)((rp.positions ? rp.positions[tok] : tok) + rp.pos_offset);
-        chunk_t vsub[TL::VP];                       // this subtile's values arrive during the un-rotation
-        load_v_subtile<T, D>(vsub, v_head, p.v_st, t0 + 32 * sub, p.n, lane);
         chunk_t kh[TL::NC], kl[TL::NC];
         const float2* turns = turns_lds;            // re-read per subtile: hoisting the table out of the
         asm volatile("" : "+v"(turns));             // tile loop would pin 64 registers for the whole kernel
         unrotate_subtile<T, D>(sub ? kf1 : kf0, pos, turns, rp.interleaved, half, kh, kl);
+        // the values are requested only now: earlier they would sit in registers the un-rotation
+        // needs (and be spilled); they arrive while the first block's products run
+        chunk_t vsub[TL::VP];
+        load_v_subtile<T, D>(vsub, v_head, p.v_st, t0 + 32 * sub, p.n, lane);
         auto mma_block = [&](f32x16& a, int jb) {
 #pragma unroll
           for (int c = 0; c < TL::NC; ++c) {
