@@ -185,7 +185,8 @@ typedef struct {
   const double* inv_freq;    /* HOST memory, head_dim/2 values, radians per position;
                                 read during the call, not kept                          */
   int32_t interleaved;       /* 0: pair i = (x[i], x[i + d/2]); 1: pair i = (x[2i], x[2i+1]) */
-  int32_t pos_offset;        /* added to every position                                */
+  int32_t pos_offset;        /* added to every position; positions (offset included)
+                                must lie in [0, 2^24)                                   */
   const int32_t* positions;  /* device memory or NULL.  vector_*residual_rope: [n], the
                                 position of each row of k (NULL: the row index).
                                 vector_decode_attn_rope: [batch, Hkv, n_approx], the
