@@ -33,6 +33,7 @@ int check_shape(const vector_shape* s, bool need_window) {
 // frequencies in radians per position (host) -> turns per position, by value for the kernels
 int make_rope(const vector_rope* r, int head_dim, vec::RopeParams& out) {
   if (!r || !r->inv_freq || head_dim / 2 > vec::kMaxRotaryPairs) return VECTOR_ERR_ARG;
+  if (r->pos_offset < 0 || r->pos_offset >= (1 << 24)) return VECTOR_ERR_ARG;
   const double two_pi = 6.283185307179586476925286766559;
   for (int i = 0; i < vec::kMaxRotaryPairs; ++i) out.turns_hi[i] = out.turns_lo[i] = 0.f;
   for (int i = 0; i < head_dim / 2; ++i) {
