@@ -328,6 +328,8 @@ def run_extras(vb, dg, pl, torch, np, dev, cfg, shape, layer, out, ws, n_p, n_a)
     scale = 1.0 / float(np.sqrt(d))
     res["decode_attn_rope_us_per_step"] = per_call_us(lambda: vb.vector_decode_attn_rope(cache, rope5, q, scale, o5, ws5), 50)
     res["decode_attn_us_per_step"] = per_call_us(lambda: vb.vector_decode_attn(cache, q, scale, o5, ws5), 50)
+    res["decode_attn_literal_us_per_step"] = per_call_us(
+        lambda: vb.vector_decode_attn(cache, q, scale, o5, ws5, flags=vb.VECTOR_DECODE_LITERAL), 50)
     # calibration on 262144 tokens per head (random keys, values linear in them plus noise)
     m = 262144
     kc = rnd(H, m, d)

@@ -154,7 +154,11 @@ typedef struct {
  * approximated rows together, logits q . k_t * scale, and
  *   out = sum_ret p_t v_t + sum_apx p_t (k_t . W[h]).
  * q: device [batch, Hq, d]; out: device [batch, Hq, d], same dtype as the cache.
- * flags: reserved, pass 0.  A sequence with no live token yields zeros. */
+ * flags: 0, or VECTOR_DECODE_LITERAL to rebuild v_hat = k . W for every approximated row on
+ * the matrix cores before weighting it (bf16 caches only); by default the weighted keys are
+ * summed first and W is applied once, (sum p_t k_t) . W, which is the same sum in another
+ * order and far less work.  A sequence with no live token yields zeros. */
+#define VECTOR_DECODE_LITERAL 1
 VECTOR_API int vector_decode_attn(const vector_cache* cache, const void* q, float scale, void* out,
                        int32_t flags, void* ws, size_t ws_bytes, void* stream);
 

@@ -14,6 +14,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(PKG_DIR, "libvector.so")
 
 VECTOR_F32, VECTOR_BF16 = 0, 1
+VECTOR_DECODE_LITERAL = 1
 VECTOR_OK, VECTOR_ERR_ARG, VECTOR_ERR_SHAPE, VECTOR_ERR_WORKSPACE, VECTOR_ERR_DTYPE, VECTOR_ERR_HIP = 0, -1, -2, -3, -4, -5
 TIER_EVICT, TIER_APPROX, TIER_RETAIN = 0, 1, 2
 

@@ -35,6 +35,7 @@ struct DecodeParams {
   int splits_ret, splits_apx;   // workgroups per (sequence, head) on each segment
   int64_t w_sh;           // element stride between per-head W
   float c2;               // scale * log2(e)
+  int literal;            // approximated rows: rebuild v_hat = k W per row instead of (sum p k) W
 };
 
 constexpr int DT_ = 256;          // threads per workgroup
@@ -274,7 +275,8 @@ template <int D> struct MfmaDecodeTile {
 // ROPE: the cached keys carry rotary position embedding.  Logits use them as cached; the
 // rows that stand in for values of approximated tokens are the keys turned back by their
 // original positions (rp.positions [B, Hkv, n_approx]), written to the second tile as bf16.
-template <int D, int G, bool ROPE>
+// LITERAL: approximated rows are rebuilt one by one, v_hat = k W, before they are weighted.
+template <int D, int G, bool ROPE, bool LITERAL = false>
 __global__ __launch_bounds__(DT_, 2) void decode_split_mfma_kernel(DecodeParams p, RopeParams rp) {
   using T = bf16_t;
   using TL = MfmaDecodeTile<D>;
@@ -307,6 +309,7 @@ __global__ __launch_bounds__(DT_, 2) void decode_split_mfma_kernel(DecodeParams 
   unsigned char* k_tile = dec_lds + wave * 2 * TL::kTileBytes;
   unsigned char* v_tile = k_tile + TL::kTileBytes;
   const unsigned char* r_tile = (is_apx && !ROPE) ? k_tile : v_tile;
+  const bool literal = LITERAL && is_apx;                    // rebuild every approximated value row
 
   // B operand of the score product: query row g on lane g, zero beyond G
   chunk_t qf[NC];
@@ -471,6 +474,37 @@ __global__ __launch_bounds__(DT_, 2) void decode_split_mfma_kernel(DecodeParams 
     }
     // ---- output: contraction index e of step ks on lane half `half` is tile row
     //      16 ks + 4 half + 8 (e / 4) + e % 4, the row accumulator register 8 ks + e holds ----
+    if (LITERAL && literal) {
+      // v_hat[t][j] = sum_i K[t][i] W[i][j] per 32-wide block of j: rows = tokens, so that the
+      // accumulator of lane j holds its column in exactly the order the second product wants
+      // for its A operand; fed as bf16 value + remainder like the weights.
+#pragma unroll
+      for (int jb = 0; jb < JB; ++jb) {
+        const unsigned char* wt = dec_lds + jb * 2 * TL::kTileBytes + TL::kTileBytes;
+        f32x16 vh;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+          const chunk_t a = *reinterpret_cast<const chunk_t*>(k_tile + l31 * TL::kStride + (2 * c + half) * 16);
+          const chunk_t b = *reinterpret_cast<const chunk_t*>(wt + l31 * TL::kStride + (2 * c + half) * 16);
+          if (c == 0) mma_chunk_first<T>(vh, a, b); else mma_chunk<T>(vh, a, b);
+        }
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+          bf16x8 v_hi, v_lo;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float x = vh[8 * ks + e];
+            const __bf16 hi = (__bf16)x;
+            v_hi[e] = hi;
+            v_lo[e] = (__bf16)(x - (float)hi);
+          }
+          o[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_hi, p_hi[ks], o[jb], 0, 0, 0);
+          o[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_lo, p_hi[ks], o[jb], 0, 0, 0);
+          o[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_hi, p_lo[ks], o[jb], 0, 0, 0);
+        }
+      }
+      return;
+    }
 #pragma unroll
     for (int jb = 0; jb < JB; ++jb) {
 #pragma unroll
@@ -486,6 +520,23 @@ __global__ __launch_bounds__(DT_, 2) void decode_split_mfma_kernel(DecodeParams 
       }
     }
   };
+
+  // Literal reconstruction: W^T of the head sits in the value-tile slots, which approximated rows
+  // do not use (32 rows of W^T per slot, same row stride as a tile).
+  if (LITERAL && literal) {
+    const T* Wh = reinterpret_cast<const T*>(p.W) + (int64_t)h * p.w_sh;
+    for (int idx = threadIdx.x; idx < D * D / 8; idx += DT_) {
+      const int i = idx / (D / 8), j0 = (idx % (D / 8)) * 8;
+      union { uint4 raw; unsigned short el[8]; } w;
+      w.raw = load_chunk(Wh + (size_t)i * D + j0);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int j = j0 + e;
+        *reinterpret_cast<unsigned short*>(dec_lds + (j / 32) * 2 * TL::kTileBytes + TL::kTileBytes + (j % 32) * TL::kStride + i * 2) = w.el[e];
+      }
+    }
+    __syncthreads();
+  }
 
   uint4 kraw[TL::kLoads], vraw[TL::kLoads];
   int base = row_begin + wave * kTileRows;
@@ -569,7 +620,8 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeParams p) {
   const int cg = threadIdx.x % CG, rg = threadIdx.x / CG;
   const T* Wh = reinterpret_cast<const T*>(p.W) + (int64_t)h * p.w_sh;
   uint4 wraw[RP];
-  if (p.n_approx > 0) {
+  const bool use_w = p.n_approx > 0 && !p.literal;      // literal partials are values already
+  if (use_w) {
 #pragma unroll
     for (int r = 0; r < RP; ++r) wraw[r] = load_chunk(Wh + (size_t)(rg * RP + r) * D + cg * E);
   }
@@ -601,7 +653,7 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeParams p) {
         if (s0 + u < n_splits && ms[u] != -INFINITY) {
           const float sc = fast_exp2(ms[u] - mx);
           L = fmaf(ls[u], sc, L);
-          if (s0 + u < p.splits_ret) av = fmaf(xs[u], sc, av);
+          if (s0 + u < p.splits_ret || p.literal) av = fmaf(xs[u], sc, av);
           else az = fmaf(xs[u], sc, az);
         }
       }
@@ -620,7 +672,7 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeParams p) {
     for (int g = 0; g < G; ++g)
 #pragma unroll
       for (int e = 0; e < E; ++e) a[g][e] = 0.f;
-    if (p.n_approx > 0) {
+    if (use_w) {
 #pragma unroll
       for (int r = 0; r < RP; ++r) {
         float wf[E];
@@ -685,6 +737,9 @@ int run_decode(const vector_cache& c, DecodeParams& p, hipStream_t stream, const
     if (rope) {
       VEC_HIP(set_max_lds(reinterpret_cast<const void*>(decode_split_mfma_kernel<D, G, true>), lds));
       VEC_LAUNCH(K_DECODE_SPLIT, (decode_split_mfma_kernel<D, G, true>), grid, dim3(DT_), lds, stream, p, *rope);
+    } else if (p.literal) {
+      VEC_HIP(set_max_lds(reinterpret_cast<const void*>(decode_split_mfma_kernel<D, G, false, true>), lds));
+      VEC_LAUNCH(K_DECODE_SPLIT, (decode_split_mfma_kernel<D, G, false, true>), grid, dim3(DT_), lds, stream, p, RopeParams{});
     } else {
       VEC_HIP(set_max_lds(reinterpret_cast<const void*>(decode_split_mfma_kernel<D, G, false>), lds));
       VEC_LAUNCH(K_DECODE_SPLIT, (decode_split_mfma_kernel<D, G, false>), grid, dim3(DT_), lds, stream, p, RopeParams{});
@@ -720,8 +775,9 @@ size_t decode_workspace_bytes(int batch, int n_q_heads, int n_kv_heads, int head
 
 int launch_decode_attn(const vector_cache& c, const void* q, float scale, void* out, int flags, void* ws,
                        hipStream_t stream, const RopeParams* rope) {
-  (void)flags;
   DecodeParams p;
+  p.literal = (flags & VECTOR_DECODE_LITERAL) ? 1 : 0;
+  if (p.literal && (rope || c.dtype != VECTOR_BF16)) return VECTOR_ERR_DTYPE;
   p.q = q; p.k_ret = c.k_ret; p.v_ret = c.v_ret; p.k_apx = c.k_apx; p.W = c.W; p.len_retain = c.len_retain;
   p.out = out; p.part = reinterpret_cast<float*>(ws);
   p.B = c.batch; p.Hq = c.n_q_heads; p.Hkv = c.n_kv_heads; p.cap_retain = c.cap_retain; p.n_approx = c.n_approx;

@@ -207,7 +207,8 @@ static int decode_checked(const vector_cache* c, const void* q, float scale, voi
   if (c->n_q_heads < c->n_kv_heads || c->n_q_heads % c->n_kv_heads) return VECTOR_ERR_SHAPE;
   const int G = c->n_q_heads / c->n_kv_heads;
   if (G != 1 && G != 2 && G != 4 && G != 8) return VECTOR_ERR_SHAPE;
-  if (c->cap_retain < 0 || c->n_approx < 0 || flags != 0 || !(scale == scale)) return VECTOR_ERR_ARG;
+  if (c->cap_retain < 0 || c->n_approx < 0 || (flags & ~VECTOR_DECODE_LITERAL) || !(scale == scale)) return VECTOR_ERR_ARG;
+  if ((flags & VECTOR_DECODE_LITERAL) && (rope || c->dtype != VECTOR_BF16)) return VECTOR_ERR_DTYPE;
   if (!c->len_retain) return VECTOR_ERR_ARG;
   if (c->cap_retain > 0 && (!c->k_ret || !c->v_ret || !aligned16(c->k_ret) || !aligned16(c->v_ret))) return VECTOR_ERR_ARG;
   if (c->n_approx > 0 && (!c->k_apx || !c->W || !aligned16(c->k_apx) || !aligned16(c->W))) return VECTOR_ERR_ARG;

@@ -239,6 +239,18 @@ def test_decode_attn(dtype, d, B, Hq, Hkv, n_r, n_a, cap):
         close(got, ref, "decode out")
     if B > 1 and length[1] == 0 and n_a == 0:
         assert not got[1].any()
+    if dtype == "bf16":
+        # the literal variant (every approximated value rebuilt as k W before it is weighted) is
+        # the same sum in another order
+        out_l = torch.full((B, Hq, d), 7.0, dtype=tdt, device="cuda:0")
+        vb.vector_decode_attn(cache, t["q"], scale, out_l, ws, flags=vb.VECTOR_DECODE_LITERAL)
+        torch.cuda.synchronize()
+        err = np.abs(dg.widen(pl.to_host(out_l)) - ref)
+        assert (err <= ATOL + (RTOL + 2.0 ** -8) * np.abs(ref)).all(), f"literal: max err {err.max():.3e}"
+    else:
+        with pytest.raises(vb.VectorError) as ei:
+            vb.vector_decode_attn(cache, t["q"], scale, out, ws, flags=vb.VECTOR_DECODE_LITERAL)
+        assert ei.value.code == vb.VECTOR_ERR_DTYPE
 
 
 def _band_check(score_ref, eps_ref, n_p, n_a, got_tier, ref_tier, n, what):
