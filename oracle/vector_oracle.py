@@ -80,6 +80,25 @@ def ols_fit(k: np.ndarray, v: np.ndarray) -> np.ndarray:
     return out
 
 
+def r2_global(k: np.ndarray, v: np.ndarray, w: np.ndarray) -> dict:
+    """Section 3.1, predictability of values from keys on a set of tokens (the paper reports
+    it on held-out sequences), per head:
+      sse           sum_t || v_t - k_t W ||^2
+      sst_centered  sum_t || v_t - mean_t v ||^2      r2_centered   = 1 - sse / sst_centered
+      sst_raw       sum_t || v_t ||^2                 r2_uncentered = 1 - sse / sst_raw
+    The centred form is the usual coefficient of determination (all value dimensions pooled);
+    the other is one minus the mean relative error that Section 4 uses."""
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    w = np.asarray(w, dtype=np.float64)
+    diff = v - np.einsum("hti,hij->htj", k, w)
+    sse = (diff * diff).sum(axis=(1, 2))
+    sst_c = ((v - v.mean(axis=1, keepdims=True)) ** 2).sum(axis=(1, 2))
+    sst_r = (v * v).sum(axis=(1, 2))
+    return {"r2_centered": 1.0 - sse / sst_c, "r2_uncentered": 1.0 - sse / sst_r, "sse": sse, "sst_centered": sst_c,
+            "sst_raw": sst_r}
+
+
 # ----------------------------------------------------------------------------
 # base scorer (observation-window attention mass, pooled)
 # ----------------------------------------------------------------------------

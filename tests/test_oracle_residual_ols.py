@@ -123,3 +123,19 @@ def test_bf16_round_to_nearest_even():
     # 1 + 3*2^-8 is a tie between 1+2^-7 (odd) and 1+2^-6 (even)
     assert back[0] == 1.0 and back[1] == 1.0 and back[2] == 1.015625 and back[3] == -2.5
     assert np.all(np.abs(back[:4] - x[:4]) <= np.abs(x[:4]) * 2.0 ** -8)
+
+
+def test_r2_global_against_library_and_limits():
+    from sklearn.metrics import r2_score
+    k, w = _rand(20, 2, 200, 12), _rand(21, 2, 12, 12) / 3
+    v = np.einsum("hti,hij->htj", k, w) + 0.5 * _rand(22, 2, 200, 12) + 3.0      # an offset: centring matters
+    r = vo.r2_global(k, v, w)
+    for h in range(2):
+        lib = r2_score(v[h], k[h] @ w[h], multioutput="variance_weighted")
+        assert abs(r["r2_centered"][h] - lib) < 1e-12
+    assert (r["r2_uncentered"] > r["r2_centered"]).all()                        # the offset inflates the raw total
+    exact = vo.r2_global(k, np.einsum("hti,hij->htj", k, w), w)
+    assert np.allclose(exact["r2_centered"], 1.0) and np.allclose(exact["r2_uncentered"], 1.0)
+    none = vo.r2_global(k, v, np.zeros_like(w))
+    assert np.allclose(none["r2_uncentered"], 0.0)
+    np.testing.assert_allclose(r["sse"], vo.residual(k, v, w).astype(np.float64).sum(axis=1), rtol=1e-6)
