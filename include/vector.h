@@ -226,6 +226,20 @@ VECTOR_API size_t vector_calibrate_workspace_bytes(const vector_shape* shape);
 VECTOR_API int vector_calibrate(const vector_shape* shape, const void* k, const void* v, void* W, void* ws,
                      size_t ws_bytes, void* stream);
 
+/* Section 3.1: how well the map predicts the values of a token set (the paper reports it on
+ * held-out sequences), per KV head:
+ *   out[h][0] r2_centered    1 - sse / sst_centered   (coefficient of determination, all value
+ *                                                      dimensions pooled)
+ *   out[h][1] r2_uncentered  1 - sse / sst_raw        (one minus the relative error of Section 4)
+ *   out[h][2] sse            sum_t || v_t - k_t . W[h] ||^2
+ *   out[h][3] sst_centered   sum_t || v_t - mean_t v ||^2        out[h][4] sst_raw  sum_t || v_t ||^2
+ * k, v, W as for vector_residual; out: device fp64 [Hkv, VECTOR_R2_FIELDS]; ws:
+ * vector_r2_workspace_bytes(shape) bytes.  Residuals in fp32 as in vector_residual, sums in fp64. */
+#define VECTOR_R2_FIELDS 5
+VECTOR_API size_t vector_r2_workspace_bytes(const vector_shape* shape);
+VECTOR_API int vector_r2(const vector_shape* shape, const void* k, const void* v, const void* W, double* out, void* ws,
+              size_t ws_bytes, void* stream);
+
 /* ---- distortion diagnostics ------------------------------------------------ */
 
 /* Section 4: with importance weights w (device fp32 [Hkv, n], summing to one per head), the

@@ -27,6 +27,7 @@ EXPORTS = (
     "vector_residual_rope", "vector_score_residual_rope", "vector_decode_attn_rope",
     "vector_calibrate_workspace_bytes", "vector_calibrate",
     "vector_distortion_workspace_bytes", "vector_distortion",
+    "vector_r2_workspace_bytes", "vector_r2",
 )
 
 
@@ -109,6 +110,9 @@ def lib() -> C.CDLL:
         L.vector_distortion_workspace_bytes.argtypes = [C.POINTER(Shape)]
         L.vector_distortion_workspace_bytes.restype = sz
         L.vector_distortion.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, vp, sz, vp]
+        L.vector_r2_workspace_bytes.argtypes = [C.POINTER(Shape)]
+        L.vector_r2_workspace_bytes.restype = sz
+        L.vector_r2.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, sz, vp]
         L.vector_residual_rope.argtypes = [C.POINTER(Shape), vp, vp, vp, C.POINTER(Rope), vp, vp, sz, vp]
         L.vector_score_residual_rope.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, C.POINTER(Rope), vp, vp, vp, sz, vp]
         L.vector_decode_attn_rope.argtypes = [C.POINTER(Cache), C.POINTER(Rope), vp, C.c_float, vp, i32, vp, sz, vp]
@@ -255,3 +259,15 @@ def vector_distortion_workspace_bytes(shape: Shape) -> int:
 def vector_distortion(shape: Shape, weights, tier, eps, v, out, ws, stream=None) -> None:
     _check(lib().vector_distortion(C.byref(shape), _ptr(weights), _ptr(tier), _ptr(eps), _ptr(v), _ptr(out), _ptr(ws),
                                    _nbytes(ws), _stream(stream)), "vector_distortion")
+
+
+R2_FIELDS = ("r2_centered", "r2_uncentered", "sse", "sst_centered", "sst_raw")
+
+
+def vector_r2_workspace_bytes(shape: Shape) -> int:
+    return int(lib().vector_r2_workspace_bytes(C.byref(shape)))
+
+
+def vector_r2(shape: Shape, k, v, W, out, ws, stream=None) -> None:
+    _check(lib().vector_r2(C.byref(shape), _ptr(k), _ptr(v), _ptr(W), _ptr(out), _ptr(ws), _nbytes(ws), _stream(stream)),
+           "vector_r2")

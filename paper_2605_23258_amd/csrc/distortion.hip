@@ -1,4 +1,4 @@
-// Distortion diagnostics of Section 4: E = sum over evicted tokens of w_i plus sum over
+// Diagnostics.  Distortion of Section 4: E = sum over evicted tokens of w_i plus sum over
 // approximated tokens of w_i * eps_i / ||v_i||^2, the mean relative error over the
 // approximated set (1 - R^2_approx), and the quantities of Proposition 1.
 //
@@ -98,7 +98,110 @@ __global__ __launch_bounds__(kWave) void distortion_final_kernel(DistParams p) {
   o[7] = w_bar / (w_star + w_bar); o[8] = n_ap; o[9] = n_ev;
 }
 
+// ---------------------------------------------------------------------------
+// R^2 of the value map on a token set (Section 3.1): residuals come from the residual kernel;
+// here the totals.  r2_partial_kernel: grid (chunks of 1024 tokens, heads); thread j (and its
+// partner j + D) accumulates sum v_j and sum v_j^2 over every other token of the chunk in
+// fp64, the workgroup also sums the chunk's residuals.  r2_final_kernel adds the chunks in order.
+// ---------------------------------------------------------------------------
+struct R2Params {
+  const float* eps; const void* v;
+  int64_t v_sh, v_st;
+  int n, n_chunks;
+  double* part;                            // [Hkv, n_chunks, 2 D + 1]
+  double* out;                             // [Hkv, VECTOR_R2_FIELDS]
+};
+
+template <typename T, int D>
+__global__ __launch_bounds__(kDistThreads) void r2_partial_kernel(R2Params p) {
+  static_assert(kDistThreads % D == 0, "token groups");
+  constexpr int TG = kDistThreads / D;
+  __shared__ double red[TG][2][D];
+  __shared__ double eps_red[kDistThreads / kWave];
+  const int h = blockIdx.y, chunk = blockIdx.x;
+  const int j = threadIdx.x % D, tg = threadIdx.x / D;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const T* v_head = reinterpret_cast<const T*>(p.v) + (int64_t)h * p.v_sh;
+  const int t_end = min(p.n, (chunk + 1) * kDistTokens);
+  double s1 = 0.0, s2 = 0.0, se = 0.0;
+  for (int t = chunk * kDistTokens + tg; t < t_end; t += TG) {
+    const double x = (double)to_float(v_head[(int64_t)t * p.v_st + j]);
+    s1 += x;
+    s2 += x * x;
+  }
+  for (int t = chunk * kDistTokens + threadIdx.x; t < t_end; t += kDistThreads) se += (double)p.eps[(size_t)h * p.n + t];
+  red[tg][0][j] = s1;
+  red[tg][1][j] = s2;
+  se = wave_sum_f64(se);
+  if (lane == 0) eps_red[wave] = se;
+  __syncthreads();
+  double* out = p.part + ((size_t)h * p.n_chunks + chunk) * (2 * D + 1);
+  if (threadIdx.x < 2 * D) {
+    const int which = threadIdx.x / D, jj = threadIdx.x % D;
+    double x = 0.0;
+    for (int g = 0; g < TG; ++g) x += red[g][which][jj];
+    out[which * D + jj] = x;
+  }
+  if (threadIdx.x == 0) {
+    double x = 0.0;
+    for (int wv = 0; wv < kDistThreads / kWave; ++wv) x += eps_red[wv];
+    out[2 * D] = x;
+  }
+}
+
+template <int D>
+__global__ __launch_bounds__(2 * D) void r2_final_kernel(R2Params p) {
+  __shared__ double tot[2][D];
+  __shared__ double sse_lds;
+  const int h = blockIdx.x;
+  const int which = threadIdx.x / D, j = threadIdx.x % D;
+  const double* part = p.part + (size_t)h * p.n_chunks * (2 * D + 1);
+  double x = 0.0;
+  for (int c = 0; c < p.n_chunks; ++c) x += part[(size_t)c * (2 * D + 1) + which * D + j];
+  tot[which][j] = x;
+  if (threadIdx.x == 0) {
+    double e = 0.0;
+    for (int c = 0; c < p.n_chunks; ++c) e += part[(size_t)c * (2 * D + 1) + 2 * D];
+    sse_lds = e;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double raw = 0.0, cen = 0.0;
+    for (int d = 0; d < D; ++d) {
+      raw += tot[1][d];
+      cen += tot[1][d] - tot[0][d] * tot[0][d] / (double)p.n;
+    }
+    double* o = p.out + (size_t)h * VECTOR_R2_FIELDS;
+    o[0] = 1.0 - sse_lds / cen; o[1] = 1.0 - sse_lds / raw; o[2] = sse_lds; o[3] = cen; o[4] = raw;
+  }
+}
+
 }  // namespace
+
+size_t r2_workspace_bytes(int n_kv_heads, int seq_len, int head_dim) {
+  return align_up((size_t)n_kv_heads * seq_len * sizeof(float), 256) +
+         align_up((size_t)n_kv_heads * ((seq_len + kDistTokens - 1) / kDistTokens) * (2 * head_dim + 1) * sizeof(double), 256);
+}
+
+// eps [Hkv, n] (already computed into the head of ws by the residual kernel) -> report
+int launch_r2(const vector_shape& s, const float* eps, const void* v, double* out, void* part_ws, hipStream_t stream) {
+  R2Params p;
+  p.eps = eps; p.v = v; p.n = s.seq_len; p.out = out;
+  p.v_st = s.v_stride_tok ? s.v_stride_tok : s.head_dim;
+  p.v_sh = s.v_stride_head ? s.v_stride_head : (int64_t)s.seq_len * p.v_st;
+  p.n_chunks = (s.seq_len + kDistTokens - 1) / kDistTokens;
+  p.part = reinterpret_cast<double*>(part_ws);
+  const dim3 grid(p.n_chunks, s.n_kv_heads);
+  if (s.dtype == VECTOR_BF16 && s.head_dim == 128) hipLaunchKernelGGL((r2_partial_kernel<bf16_t, 128>), grid, dim3(kDistThreads), 0, stream, p);
+  else if (s.dtype == VECTOR_BF16 && s.head_dim == 64) hipLaunchKernelGGL((r2_partial_kernel<bf16_t, 64>), grid, dim3(kDistThreads), 0, stream, p);
+  else if (s.dtype == VECTOR_F32 && s.head_dim == 128) hipLaunchKernelGGL((r2_partial_kernel<float, 128>), grid, dim3(kDistThreads), 0, stream, p);
+  else if (s.dtype == VECTOR_F32 && s.head_dim == 64) hipLaunchKernelGGL((r2_partial_kernel<float, 64>), grid, dim3(kDistThreads), 0, stream, p);
+  else return s.dtype == VECTOR_BF16 || s.dtype == VECTOR_F32 ? VECTOR_ERR_SHAPE : VECTOR_ERR_DTYPE;
+  if (s.head_dim == 128) hipLaunchKernelGGL(r2_final_kernel<128>, dim3(s.n_kv_heads), dim3(256), 0, stream, p);
+  else hipLaunchKernelGGL(r2_final_kernel<64>, dim3(s.n_kv_heads), dim3(128), 0, stream, p);
+  VEC_HIP(hipGetLastError());
+  return VECTOR_OK;
+}
 
 size_t distortion_workspace_bytes(int n_kv_heads, int seq_len) {
   return align_up((size_t)n_kv_heads * ((seq_len + kDistTokens - 1) / kDistTokens) * kDistPartial * sizeof(double), 256);

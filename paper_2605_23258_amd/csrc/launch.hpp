@@ -53,6 +53,9 @@ size_t distortion_workspace_bytes(int n_kv_heads, int seq_len);
 int launch_distortion(const vector_shape& s, const float* w, const uint8_t* tier, const float* eps, const void* v,
                       double* out, void* ws, hipStream_t stream);
 
+size_t r2_workspace_bytes(int n_kv_heads, int seq_len, int head_dim);
+int launch_r2(const vector_shape& s, const float* eps, const void* v, double* out, void* part_ws, hipStream_t stream);
+
 size_t route_workspace_bytes(int n_kv_heads, int seq_len, int n_pool);
 int launch_route(int n_kv_heads, int seq_len, const float* score, const float* eps, int n_pool, int n_approx,
                  uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx, void* ws, hipStream_t stream);

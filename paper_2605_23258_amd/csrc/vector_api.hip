@@ -151,6 +151,26 @@ int vector_distortion(const vector_shape* s, const float* weights, const uint8_t
   return vec::launch_distortion(*s, weights, tier, eps, v, out, ws, (hipStream_t)stream);
 }
 
+size_t vector_r2_workspace_bytes(const vector_shape* s) {
+  if (check_shape(s, false) != VECTOR_OK) return 0;
+  return vec::r2_workspace_bytes(s->n_kv_heads, s->seq_len, s->head_dim);
+}
+
+int vector_r2(const vector_shape* s, const void* k, const void* v, const void* W, double* out, void* ws, size_t ws_bytes,
+              void* stream) {
+  int rc = check_shape(s, false);
+  if (rc) return rc;
+  if (!k || !v || !W || !out || !aligned16(k) || !aligned16(v) || !aligned16(W)) return VECTOR_ERR_ARG;
+  if ((rc = check_ws(ws, ws_bytes, vec::r2_workspace_bytes(s->n_kv_heads, s->seq_len, s->head_dim)))) return rc;
+  vector_shape t = *s;
+  if (t.window < 1 || t.window > t.seq_len) t.window = 1;
+  float* eps = reinterpret_cast<float*>(ws);
+  rc = vec::launch_score_residual(t, nullptr, k, v, W, nullptr, eps, nullptr, (hipStream_t)stream);
+  if (rc) return rc;
+  unsigned char* part = reinterpret_cast<unsigned char*>(ws) + ((size_t)s->n_kv_heads * s->seq_len * sizeof(float) + 255) / 256 * 256;
+  return vec::launch_r2(*s, eps, v, out, part, (hipStream_t)stream);
+}
+
 int vector_probe_residual_mfma(const vector_shape* s, const void* k, const void* v, const void* W, float* eps,
                                int32_t repeat, void* stream) {
   int rc = check_shape(s, false);

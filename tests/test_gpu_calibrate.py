@@ -82,3 +82,29 @@ def test_strided_views_and_errors():
     assert ei.value.code == vb.VECTOR_ERR_WORKSPACE
     torch.cuda.synchronize()
     assert (W == 7.0).all()
+
+
+@pytest.mark.parametrize("name", ["bf16_d128_ragged", "bf16_d64", "f32_d64"])
+def test_r2_of_the_fitted_map(name):
+    """Fit on the first half of a draw, evaluate on the second half (the paper's held-out R^2);
+    both halves are strided views of the same tensors."""
+    base, over = CASES[name]
+    cfg = dg.scaled(dg.CONFIGS[base], **over)
+    li = dg.make_layer(cfg, 0)
+    H, d, n = cfg.n_kv_heads, cfg.head_dim, cfg.seq_len
+    m = n // 2
+    shape = pl.shape_of(cfg, seq_len=m)
+    shape.k_stride_head = shape.v_stride_head = n * d
+    shape.k_stride_tok = shape.v_stride_tok = d
+    k_dev, v_dev = pl.to_device(li.k), pl.to_device(li.v)
+    W = torch.zeros((H, d, d), dtype=torch.bfloat16 if cfg.dtype == "bf16" else torch.float32, device="cuda:0")
+    ws = pl.alloc_workspace(max(vb.vector_calibrate_workspace_bytes(shape), vb.vector_r2_workspace_bytes(shape)))
+    vb.vector_calibrate(shape, k_dev[:, :m], v_dev[:, :m], W, ws)
+    out = torch.zeros((H, len(vb.R2_FIELDS)), dtype=torch.float64, device="cuda:0")
+    vb.vector_r2(shape, k_dev[:, m:2 * m], v_dev[:, m:2 * m], W, out, ws)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    ref = vo.r2_global(dg.widen(li.k[:, m:2 * m]), dg.widen(li.v[:, m:2 * m]), dg.widen(pl.to_host(W)))
+    for i, f in enumerate(vb.R2_FIELDS):
+        np.testing.assert_allclose(got[:, i], ref[f], rtol=2e-4, atol=1e-6, err_msg=f)
+    assert (got[:, 0] > 0.5).all()                                         # the planted map explains most of the variance
