@@ -7,17 +7,20 @@
 // per (sequence, KV head) in the combine step, so every cache row is read exactly once
 // and no value row is ever materialised.
 //
-// The path is bound by HBM (about 5 flop per byte), so it is laid out for streaming, not
-// for the matrix cores: a row of the cache is read by LPR = row_bytes/16 adjacent lanes,
-// 16 bytes each, i.e. every load instruction of a wave covers 1 KiB of consecutive memory.
+// The path is bound by HBM (about 5 flop per byte): a row of the cache is read by
+// row_bytes/16 adjacent lanes, 16 bytes each, so every load instruction of a wave covers
+// 1 KiB of consecutive memory, and every cache row is read exactly once per step.
 //
-//   decode_split_kernel   : grid (split, kv head, sequence).  A workgroup owns a range of
-//                           rows of one segment (retained or approximated).  Each lane
-//                           group scores its row against the G query rows of the head
-//                           (partial dot product per lane, rotate-add across the group),
-//                           runs an online softmax, and accumulates p * row (the value
-//                           row for retained tokens, the key row itself for approximated
-//                           ones).  Several rows per lane group are in flight at once.
+//   decode_split_mfma_kernel : bf16 caches.  grid (split, kv head, sequence); a workgroup owns
+//                           a range of rows of one segment (retained or approximated).  Waves
+//                           park 32-row tiles in LDS and run both products (scores, then
+//                           weights times rows) on the matrix cores; see the comment above
+//                           the kernel.  Variants: ROPE (approximated rows are un-rotated
+//                           before they stand in for values), LITERAL (v_hat = k W rebuilt per
+//                           row instead of the reassociated sum).
+//   decode_split_kernel   : fp32 caches: the same split with vector-ALU dot products (partial
+//                           dot product per lane, rotate-add across the lanes of a row,
+//                           online softmax per lane group).
 //   decode_combine_kernel : merges the splits, applies W to z, normalises, stores.
 #include "common.hpp"
 #include "launch.hpp"

@@ -13,11 +13,16 @@
 //   pool    pool_scores   : average pooling of mass over prefix columns, +inf on
 //                           the window columns
 //
-// K rows go straight from HBM into MFMA operand registers (16 bytes per lane); the next
-// tile's rows are requested as soon as the last MFMA of the current tile has been issued.
-// Q_h, W_h^T and the row biases live in LDS for the life of a workgroup.  Inside a tile the
-// MFMAs of row block i+1 are issued before the exponentials of row block i, interleaved
-// instruction by instruction, so that the matrix pipe and the vector ALU run together.
+// Pass 1 has two kernels: score_stats_tiles_kernel (R_pad = 128 or 256: key tiles through LDS,
+// a wave keeps its block of Q_h and the rows' running statistics in registers) and
+// score_stats_kernel (any row count: keys straight into operand registers, Q_h in LDS).
+// In pass 2 K rows go straight from HBM into MFMA operand registers (16 bytes per lane); the
+// next tile's rows are requested as soon as the last MFMA of the current tile has been issued;
+// Q_h, W_h^T and the row biases live in LDS for the life of a workgroup.  MFMAs of row block
+// i+1 are written between the exponentials of row block i; on this chip that only pays across
+// the waves of a SIMD (vector-ALU work does not overlap the MFMAs of its own wave).
+// Template flags of pass 2: PROBE (repeat a tile's arithmetic on resident operands, for
+// measuring the contraction alone), ROPE (keys are un-rotated by position for the residual).
 #include <stdlib.h>
 
 #include "common.hpp"
