@@ -19,8 +19,8 @@
 // In pass 2 K rows go straight from HBM into MFMA operand registers (16 bytes per lane); the
 // next tile's rows are requested as soon as the last MFMA of the current tile has been issued;
 // Q_h, W_h^T and the row biases live in LDS for the life of a workgroup.  MFMAs of row block
-// i+1 are written between the exponentials of row block i; on this chip that only pays across
-// the waves of a SIMD (vector-ALU work does not overlap the MFMAs of its own wave).
+// i+1 are written between the exponentials of row block i; on this chip vector-ALU work does not
+// overlap the MFMAs of its own wave and only partly those of the SIMD's other wave.
 // Template flags of pass 2: PROBE (repeat a tile's arithmetic on resident operands, for
 // measuring the contraction alone), ROPE (keys are un-rotated by position for the residual).
 #include <stdlib.h>
