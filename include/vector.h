@@ -133,6 +133,16 @@ VECTOR_API int vector_compact(const vector_shape* shape, const void* k, const vo
                    int32_t n_retain, int32_t n_approx,
                    void* k_ret, void* v_ret, void* k_apx, int32_t cap_retain, void* stream);
 
+/* The whole compression pass of one layer in one call: vector_score_residual, vector_route
+ * and vector_compact with the same arguments and the same outputs, bit for bit; everything is
+ * validated before the first launch.  ws: vector_compress_workspace_bytes(shape, n_pool, n_approx)
+ * bytes. */
+VECTOR_API size_t vector_compress_workspace_bytes(const vector_shape* shape, int32_t n_pool, int32_t n_approx);
+VECTOR_API int vector_compress(const vector_shape* shape, const void* q_win, const void* k, const void* v, const void* W,
+                    int32_t n_pool, int32_t n_approx, float* score, float* eps, uint8_t* tier,
+                    int32_t* idx_retain, int32_t* idx_approx, void* k_ret, void* v_ret, void* k_apx,
+                    int32_t cap_retain, void* ws, size_t ws_bytes, void* stream);
+
 /* ---- decode attention over packed caches -------------------------------- */
 
 typedef struct {

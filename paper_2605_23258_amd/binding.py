@@ -21,7 +21,7 @@ TIER_EVICT, TIER_APPROX, TIER_RETAIN = 0, 1, 2
 EXPORTS = (
     "vector_budget_counts", "vector_budget_counts_frac", "vector_pa_deploy", "vector_workspace_bytes",
     "vector_strerror", "vector_score", "vector_residual", "vector_score_residual", "vector_route",
-    "vector_compact", "vector_decode_attn",
+    "vector_compact", "vector_decode_attn", "vector_compress_workspace_bytes", "vector_compress",
     "vector_timing_enable", "vector_timing_kernels", "vector_timing_name", "vector_timing_read",
     "vector_probe_residual_mfma",
     "vector_residual_rope", "vector_score_residual_rope", "vector_decode_attn_rope",
@@ -113,6 +113,9 @@ def lib() -> C.CDLL:
         L.vector_r2_workspace_bytes.argtypes = [C.POINTER(Shape)]
         L.vector_r2_workspace_bytes.restype = sz
         L.vector_r2.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, sz, vp]
+        L.vector_compress_workspace_bytes.argtypes = [C.POINTER(Shape), i32, i32]
+        L.vector_compress_workspace_bytes.restype = sz
+        L.vector_compress.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
         L.vector_residual_rope.argtypes = [C.POINTER(Shape), vp, vp, vp, C.POINTER(Rope), vp, vp, sz, vp]
         L.vector_score_residual_rope.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, C.POINTER(Rope), vp, vp, vp, sz, vp]
         L.vector_decode_attn_rope.argtypes = [C.POINTER(Cache), C.POINTER(Rope), vp, C.c_float, vp, i32, vp, sz, vp]
@@ -271,3 +274,14 @@ def vector_r2_workspace_bytes(shape: Shape) -> int:
 def vector_r2(shape: Shape, k, v, W, out, ws, stream=None) -> None:
     _check(lib().vector_r2(C.byref(shape), _ptr(k), _ptr(v), _ptr(W), _ptr(out), _ptr(ws), _nbytes(ws), _stream(stream)),
            "vector_r2")
+
+
+def vector_compress_workspace_bytes(shape: Shape, n_pool: int, n_approx: int) -> int:
+    return int(lib().vector_compress_workspace_bytes(C.byref(shape), n_pool, n_approx))
+
+
+def vector_compress(shape: Shape, q_win, k, v, W, n_pool: int, n_approx: int, score, eps, tier, idx_retain, idx_approx,
+                    k_ret, v_ret, k_apx, cap_retain: int, ws, stream=None) -> None:
+    _check(lib().vector_compress(C.byref(shape), _ptr(q_win), _ptr(k), _ptr(v), _ptr(W), n_pool, n_approx, _ptr(score),
+                                 _ptr(eps), _ptr(tier), _ptr(idx_retain), _ptr(idx_approx), _ptr(k_ret), _ptr(v_ret),
+                                 _ptr(k_apx), cap_retain, _ptr(ws), _nbytes(ws), _stream(stream)), "vector_compress")

@@ -123,6 +123,32 @@ int vector_residual(const vector_shape* s, const void* k, const void* v, const v
   return vec::launch_score_residual(t, nullptr, k, v, W, nullptr, eps, nullptr, (hipStream_t)stream);
 }
 
+size_t vector_compress_workspace_bytes(const vector_shape* s, int32_t n_pool, int32_t n_approx) {
+  if (check_shape(s, true) != VECTOR_OK || n_pool < 0 || n_approx < 0 || n_approx > n_pool) return 0;
+  return vec::score_workspace_bytes(*s) + vec::route_workspace_bytes(s->n_kv_heads, s->seq_len, n_pool) + 256;
+}
+
+int vector_compress(const vector_shape* s, const void* q_win, const void* k, const void* v, const void* W, int32_t n_pool,
+                    int32_t n_approx, float* score, float* eps, uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx,
+                    void* k_ret, void* v_ret, void* k_apx, int32_t cap_retain, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_shape(s, true);
+  if (rc) return rc;
+  const int n_retain = n_pool - n_approx;
+  if (n_approx < 0 || n_pool < n_approx || n_pool > s->seq_len || cap_retain < n_retain) return VECTOR_ERR_ARG;
+  if (!q_win || !k || !v || !W || !score || !eps || !tier) return VECTOR_ERR_ARG;
+  if (!aligned16(q_win) || !aligned16(k) || !aligned16(v) || !aligned16(W)) return VECTOR_ERR_ARG;
+  if (n_retain > 0 && (!idx_retain || !k_ret || !v_ret || !aligned16(k_ret) || !aligned16(v_ret))) return VECTOR_ERR_ARG;
+  if (n_approx > 0 && (!idx_approx || !k_apx || !aligned16(k_apx))) return VECTOR_ERR_ARG;
+  const size_t score_ws = vec::score_workspace_bytes(*s);
+  if ((rc = check_ws(ws, ws_bytes, vector_compress_workspace_bytes(s, n_pool, n_approx)))) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  void* route_ws = reinterpret_cast<unsigned char*>(ws) + (score_ws + 255) / 256 * 256;
+  if ((rc = vec::launch_score_residual(*s, q_win, k, v, W, score, eps, ws, st))) return rc;
+  if ((rc = vec::launch_route(s->n_kv_heads, s->seq_len, score, eps, n_pool, n_approx, tier, idx_retain, idx_approx, route_ws, st)))
+    return rc;
+  return vec::launch_compact(*s, k, v, idx_retain, idx_approx, n_retain, n_approx, k_ret, v_ret, k_apx, cap_retain, st);
+}
+
 size_t vector_calibrate_workspace_bytes(const vector_shape* s) {
   if (check_shape(s, false) != VECTOR_OK) return 0;
   return vec::calibrate_workspace_bytes(*s);

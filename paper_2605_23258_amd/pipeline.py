@@ -65,10 +65,16 @@ def alloc_outputs(shape: vb.Shape, n_pool: int, n_approx: int, cap_retain: int, 
 
 
 def compress_layer(shape: vb.Shape, q_win, k, v, W, n_pool: int, n_approx: int, out: Compressed, ws,
-                   cap_retain: Optional[int] = None, fused: bool = True, stream=None) -> Compressed:
-    """One compression pass: score + residual -> route -> compact, all enqueued on one stream."""
+                   cap_retain: Optional[int] = None, fused: bool = True, stream=None, one_call: bool = False) -> Compressed:
+    """One compression pass: score + residual -> route -> compact, all enqueued on one stream.
+    `one_call` uses vector_compress (ws of vector_compress_workspace_bytes) instead of the three calls."""
     n_r = n_pool - n_approx
     cap = cap_retain if cap_retain is not None else out.k_ret.shape[1]
+    if one_call:
+        vb.vector_compress(shape, q_win, k, v, W, n_pool, n_approx, out.score, out.eps, out.tier,
+                           out.idx_retain if n_r else None, out.idx_approx if n_approx else None,
+                           out.k_ret, out.v_ret, out.k_apx, cap, ws, stream)
+        return out
     if fused:
         vb.vector_score_residual(shape, q_win, k, v, W, out.score, out.eps, ws, stream)
     else:

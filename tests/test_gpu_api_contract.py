@@ -150,3 +150,32 @@ def test_errors_are_reported_before_any_launch():
     torch.cuda.synchronize()
     assert (score == sentinel).all() and (eps == sentinel).all(), "a failing call must not write"
     assert (tier == 77).all() and (idx_r == -5).all() and (idx_a == -5).all()
+
+
+@pytest.mark.parametrize("base,over", [
+    ("cfg2", dict(seq_len=2048, n_kv_heads=2, n_q_heads=8)),
+    ("cfg2", dict(seq_len=1777, n_kv_heads=2, n_q_heads=8, window=24, pool_kernel=5)),
+    ("cfg2", dict(seq_len=4096, n_kv_heads=1, n_q_heads=4, pool_kernel=1)),
+    ("cfg2", dict(seq_len=3000, n_kv_heads=1, n_q_heads=4, pool_kernel=13)),
+    ("cfg1", dict(seq_len=1000, window=20, n_q_heads=6, n_kv_heads=2)),
+    ("cfg2", dict(seq_len=40000, n_kv_heads=1, n_q_heads=2, window=16)),           # chip-wide routing
+])
+def test_one_call_pass_equals_the_three_calls(base, over):
+    cfg = dg.scaled(dg.CONFIGS[base], **over)
+    li = dg.make_layer(cfg, 0)
+    shape = pl.shape_of(cfg)
+    n_r, n_a, n_p = cfg.counts()
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    dev = {x: pl.to_device(getattr(li, x)) for x in ("q_win", "k", "v", "w_cal")}
+    a = pl.alloc_outputs(shape, n_p, n_a, n_r + 1, tdt)
+    b = pl.alloc_outputs(shape, n_p, n_a, n_r + 1, tdt)
+    ws_a = pl.alloc_workspace(vb.vector_workspace_bytes(shape, n_p, n_a, 1))
+    ws_b = pl.alloc_workspace(vb.vector_compress_workspace_bytes(shape, n_p, n_a))
+    pl.compress_layer(shape, dev["q_win"], dev["k"], dev["v"], dev["w_cal"], n_p, n_a, a, ws_a)
+    pl.compress_layer(shape, dev["q_win"], dev["k"], dev["v"], dev["w_cal"], n_p, n_a, b, ws_b, one_call=True)
+    torch.cuda.synchronize()
+    for name in ("score", "eps", "tier", "idx_retain", "idx_approx", "k_ret", "v_ret", "k_apx"):
+        x, y = getattr(a, name), getattr(b, name)
+        if x.dtype == torch.bfloat16:
+            x, y = x.view(torch.int16), y.view(torch.int16)
+        assert torch.equal(x, y), name
