@@ -57,3 +57,14 @@ def test_bad_arguments_are_rejected_on_the_host():
     s.pool_kernel = 4
     assert L.vector_score(C.byref(s), None, None, None, None, 0, None) == -2
     assert vb.strerror(-3).startswith("workspace")
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one GPU; asking for more ends with a message and a non-zero status
+    before anything touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)
