@@ -92,8 +92,8 @@ VECTOR_API const char* vector_strerror(int code);
  * tokens t >= n-w get +inf.
  * q_win: device [Hq, w, d] packed.  k: device, strides from shape.
  * score: device fp32 [Hkv, n] packed (output).
- * The G*w query rows of a KV head are held in LDS: VECTOR_ERR_SHAPE beyond about 448 rows
- * (bf16) or 160 rows (fp32) at d = 128, twice that at d = 64. */
+ * The G*w query rows of a KV head are held in LDS: VECTOR_ERR_SHAPE beyond 288 rows (bf16) or
+ * 160 rows (fp32) at d = 128, 384 or 288 rows at d = 64. */
 VECTOR_API int vector_score(const vector_shape* shape, const void* q_win, const void* k,
                  float* score, void* ws, size_t ws_bytes, void* stream);
 

@@ -179,3 +179,25 @@ def test_one_call_pass_equals_the_three_calls(base, over):
         if x.dtype == torch.bfloat16:
             x, y = x.view(torch.int16), y.view(torch.int16)
         assert torch.equal(x, y), name
+
+
+def test_query_row_limit():
+    """G*w rows per KV head live in LDS: the largest supported count works, the next one is refused."""
+    ok = dg.scaled(dg.CONFIGS["cfg2"], seq_len=600, n_kv_heads=1, n_q_heads=4, window=72)       # 288 rows
+    li = dg.make_layer(ok, 0)
+    shape = pl.shape_of(ok)
+    n_r, n_a, n_p = ok.counts()
+    dev = {x: pl.to_device(getattr(li, x)) for x in ("q_win", "k", "v", "w_cal")}
+    ws = pl.alloc_workspace(vb.vector_workspace_bytes(shape, n_p, n_a, 1))
+    score = torch.empty((1, 600), device="cuda:0")
+    eps = torch.empty((1, 600), device="cuda:0")
+    vb.vector_score_residual(shape, dev["q_win"], dev["k"], dev["v"], dev["w_cal"], score, eps, ws)
+    torch.cuda.synchronize()
+    wide = {x: dg.widen(getattr(li, x)) for x in ("q_win", "k", "v", "w_cal")}
+    ref = vo.score(wide["q_win"], wide["k"], 72, ok.pool_kernel)
+    close(score.cpu().numpy()[:, :528].astype(np.float64) * 600, ref[:, :528].astype(np.float64) * 600, "n*score (288 rows)")
+    too_many = dg.scaled(ok, window=80)                                                          # 320 rows
+    q_big = torch.zeros((4, 80, 128), dtype=torch.bfloat16, device="cuda:0")
+    with pytest.raises(vb.VectorError) as ei:
+        vb.vector_score_residual(pl.shape_of(too_many), q_big, dev["k"], dev["v"], dev["w_cal"], score, eps, ws)
+    assert ei.value.code == vb.VECTOR_ERR_SHAPE
