@@ -119,3 +119,54 @@ def test_decode_on_random_shape(case):
     err = np.abs(got - ref)
     tol = ATOL + (RTOL + (2.0 ** -8 if is_bf else 0.0)) * np.abs(ref)
     assert (err <= tol).all(), f"max err {err.max():.3e}"
+
+
+def _route_cases():
+    rng = np.random.default_rng(909)
+    out = []
+    for i in range(36):
+        n = int(rng.choice([7, 63, 64, 65, 1000, 4095, 4096, 4100, 9000, 32767, 32768, 33000, 50000, 70001]))
+        n_pool = int(rng.integers(0, n + 1))
+        n_approx = int(rng.integers(0, n_pool + 1))
+        kind = int(rng.integers(0, 5))
+        out.append((i, n, n_pool, n_approx, kind))
+    return out
+
+
+@pytest.mark.parametrize("case", _route_cases(), ids=lambda c: f"{c[0]}-n{c[1]}-p{c[2]}-a{c[3]}-k{c[4]}")
+def test_route_on_random_distributions(case):
+    """Bit-exact routing on value distributions that stress the radix digits: few distinct values,
+    values that differ only in the low mantissa bits, negative and infinite entries, denormals."""
+    i, n, n_pool, n_approx, kind = case
+    rng = np.random.default_rng(5000 + i)
+    H = int(rng.integers(1, 4))
+    if kind == 0:
+        score, eps = rng.random((H, n)), rng.random((H, n))
+    elif kind == 1:                                  # a handful of distinct values: ties everywhere
+        score, eps = rng.integers(0, 3, (H, n)) * 0.5, rng.integers(0, 4, (H, n)) * 1.0
+    elif kind == 2:                                  # differences in the last mantissa bits only
+        score = 1.0 + rng.integers(0, 50, (H, n)) * 2.0 ** -23
+        eps = 3.0 + rng.integers(0, 50, (H, n)) * 2.0 ** -22
+    elif kind == 3:                                  # signs, infinities, zeros of both signs
+        score = rng.standard_normal((H, n)) * 10.0 ** rng.integers(-30, 30, (H, n))
+        score[:, :: 11] = np.inf
+        score[:, 5:: 13] = -0.0
+        eps = np.abs(rng.standard_normal((H, n))) * 10.0 ** rng.integers(-20, 20, (H, n))
+        eps[:, 3:: 17] = np.inf
+        eps[:, 1:: 19] = 0.0
+    else:                                            # denormals and tiny values
+        score = rng.random((H, n)) * 1e-41
+        eps = rng.random((H, n)) * 1e-40
+    score, eps = score.astype(np.float32), eps.astype(np.float32)
+    shape = vb.Shape(n_q_heads=H, n_kv_heads=H, head_dim=64, seq_len=n, window=1, pool_kernel=1, dtype=0)
+    ws = pl.alloc_workspace(vb.vector_workspace_bytes(shape, n_pool, n_approx, 1))
+    tier = torch.full((H, n), 77, dtype=torch.uint8, device="cuda:0")
+    idx_r = torch.full((H, max(n_pool - n_approx, 1)), -1, dtype=torch.int32, device="cuda:0")
+    idx_a = torch.full((H, max(n_approx, 1)), -1, dtype=torch.int32, device="cuda:0")
+    vb.vector_route(H, n, pl.to_device(score), pl.to_device(eps), n_pool, n_approx, tier,
+                    idx_r if n_pool - n_approx else None, idx_a if n_approx else None, ws)
+    torch.cuda.synchronize()
+    r_tier, r_ir, r_ia = vo.route(score, eps, n_pool, n_approx)
+    assert np.array_equal(tier.cpu().numpy(), r_tier)
+    assert np.array_equal(idx_r.cpu().numpy()[:, : n_pool - n_approx], r_ir)
+    assert np.array_equal(idx_a.cpu().numpy()[:, :n_approx], r_ia)
