@@ -170,3 +170,31 @@ def test_route_on_random_distributions(case):
     assert np.array_equal(tier.cpu().numpy(), r_tier)
     assert np.array_equal(idx_r.cpu().numpy()[:, : n_pool - n_approx], r_ir)
     assert np.array_equal(idx_a.cpu().numpy()[:, :n_approx], r_ia)
+
+
+@pytest.mark.parametrize("q_scale", [0.0, 30.0, 300.0])
+def test_decode_with_flat_and_peaked_softmax(q_scale):
+    """q = 0 gives the plain mean over live and approximated rows; a large q makes the softmax
+    one-hot (running maxima jump, almost every weight underflows)."""
+    rng = np.random.default_rng(int(q_scale) + 1)
+    B, hkv, g, d, cap, n_a = 2, 2, 4, 128, 900, 700
+    bf = lambda x: dg.f32_to_bf16_bits(np.asarray(x, np.float32))
+    k_ret, v_ret = bf(rng.standard_normal((B, hkv, cap, d))), bf(rng.standard_normal((B, hkv, cap, d)))
+    k_apx = bf(rng.standard_normal((B, hkv, n_a, d)))
+    W = bf(rng.standard_normal((hkv, d, d)) / np.sqrt(d))
+    q = bf(rng.standard_normal((B, hkv * g, d)) * q_scale)
+    lens = np.array([cap, cap - 123], np.int32)
+    t = [pl.to_device(x) for x in (k_ret, v_ret, k_apx, W, q, lens)]
+    cache = vb.Cache(batch=B, n_q_heads=hkv * g, n_kv_heads=hkv, head_dim=d, dtype=vb.VECTOR_BF16, cap_retain=cap, n_approx=n_a)
+    cache.len_retain, cache.k_ret, cache.v_ret, cache.k_apx, cache.W = (t[5].data_ptr(), t[0].data_ptr(), t[1].data_ptr(),
+                                                                      t[2].data_ptr(), t[3].data_ptr())
+    shape = vb.Shape(n_q_heads=hkv * g, n_kv_heads=hkv, head_dim=d, seq_len=cap + n_a, window=1, pool_kernel=1, dtype=1)
+    ws = pl.alloc_workspace(vb.vector_workspace_bytes(shape, cap + n_a, n_a, B))
+    out = torch.empty((B, hkv * g, d), dtype=torch.bfloat16, device="cuda:0")
+    scale = 1.0 / np.sqrt(d)
+    ref = vo.decode_attn(dg.widen(q), dg.widen(k_ret), dg.widen(v_ret), lens, dg.widen(k_apx), dg.widen(W), scale)
+    for flags in (0, vb.VECTOR_DECODE_LITERAL):
+        vb.vector_decode_attn(cache, t[4], scale, out, ws, flags=flags)
+        torch.cuda.synchronize()
+        err = np.abs(dg.widen(pl.to_host(out)) - ref)
+        assert (err <= ATOL + (RTOL + 2.0 ** -8) * np.abs(ref)).all(), f"flags {flags}: max err {err.max():.3e}"
