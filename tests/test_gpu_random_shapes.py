@@ -198,3 +198,24 @@ def test_decode_with_flat_and_peaked_softmax(q_scale):
         torch.cuda.synchronize()
         err = np.abs(dg.widen(pl.to_host(out)) - ref)
         assert (err <= ATOL + (RTOL + 2.0 ** -8) * np.abs(ref)).all(), f"flags {flags}: max err {err.max():.3e}"
+
+
+@pytest.mark.parametrize("q_scale", [0.0, 6.0, 40.0])
+def test_score_with_flat_and_peaked_attention(q_scale):
+    """q = 0: every window row spreads its mass evenly over what it sees; large q: almost all of a
+    row's mass sits on one key, row maxima are far apart and jump between tiles."""
+    cfg = dg.scaled(dg.CONFIGS["cfg2"], seq_len=3000, n_kv_heads=2, n_q_heads=8, window=32)
+    li = dg.make_layer(cfg, 1)
+    q = dg.f32_to_bf16_bits((dg.widen(li.q_win) * q_scale).astype(np.float32))
+    shape = pl.shape_of(cfg)
+    n_r, n_a, n_p = cfg.counts()
+    n, w = cfg.seq_len, cfg.window
+    ws = pl.alloc_workspace(vb.vector_workspace_bytes(shape, n_p, n_a, 1))
+    score = torch.empty((cfg.n_kv_heads, n), device="cuda:0")
+    eps = torch.empty((cfg.n_kv_heads, n), device="cuda:0")
+    vb.vector_score_residual(shape, pl.to_device(q), pl.to_device(li.k), pl.to_device(li.v), pl.to_device(li.w_cal), score, eps, ws)
+    torch.cuda.synchronize()
+    ref = vo.score(dg.widen(q), dg.widen(li.k), w, cfg.pool_kernel)
+    got = score.cpu().numpy()
+    assert np.isfinite(got[:, : n - w]).all()
+    _close(got[:, : n - w].astype(np.float64) * n, ref[:, : n - w].astype(np.float64) * n, f"n*score (q x {q_scale})")
