@@ -125,6 +125,19 @@ def attention_mass(q_win: np.ndarray, k: np.ndarray) -> np.ndarray:
     return mass
 
 
+def score_key_diversity(k: np.ndarray) -> np.ndarray:
+    """A query-agnostic importance score (Section 5 names scorers that rank tokens by the
+    geometric diversity of their keys, without giving a formula; this is this build's reading):
+    with a_h the direction of the mean of the head's unit-normalised keys,
+        score[h, t] = - cos(k[h, t], a_h),
+    so keys that point away from the common direction rank highest.  k [H, n, d] -> float32 [H, n]."""
+    k = np.asarray(k, dtype=np.float64)
+    unit = k / np.linalg.norm(k, axis=-1, keepdims=True)
+    anchor = unit.sum(axis=1)
+    anchor /= np.linalg.norm(anchor, axis=-1, keepdims=True)
+    return (-(unit * anchor[:, None, :]).sum(axis=-1)).astype(np.float32)
+
+
 def pool_scores(mass: np.ndarray, window: int, pool_kernel: int) -> np.ndarray:
     """Average pooling (stride 1, zero padding, divisor always the kernel size)
     over the prefix columns [0, n - w); window columns get +inf."""

@@ -152,3 +152,35 @@ def test_pooling_matches_library_convolution():
         ref = np.convolve(mass[h, : 41 - w], np.ones(kern) / kern, mode="same")
         np.testing.assert_allclose(sc[h, : 41 - w], ref, rtol=1e-13)
     assert np.isposinf(sc[:, 41 - w:]).all()
+
+
+# ---- the query-agnostic key-diversity score ----
+def test_key_diversity_brute_force_and_invariances():
+    rng = np.random.default_rng(31)
+    k = rng.standard_normal((2, 50, 8)) + 1.5                       # a common direction plus spread
+    got = vo.score_key_diversity(k)
+    for h in range(2):
+        unit = [row / np.sqrt((row * row).sum()) for row in k[h]]
+        a = np.sum(unit, axis=0)
+        a = a / np.sqrt((a * a).sum())
+        for t in range(50):
+            assert abs(got[h, t] + float(unit[t] @ a)) < 1e-6
+    # positive rescaling of single keys changes nothing; a common rotation changes nothing
+    scale = rng.random((2, 50, 1)) * 10 + 0.1
+    np.testing.assert_allclose(vo.score_key_diversity(k * scale), got, atol=1e-6)
+    qmat, _ = np.linalg.qr(rng.standard_normal((8, 8)))
+    np.testing.assert_allclose(vo.score_key_diversity(k @ qmat), got, atol=1e-6)
+
+
+def test_key_diversity_extremes_and_minority_cluster():
+    same = np.tile(np.array([1.0, 2.0, -1.0, 0.5]), (1, 20, 1))
+    np.testing.assert_allclose(vo.score_key_diversity(same), -1.0, atol=1e-6)   # all along the anchor
+    k = np.tile(np.array([1.0, 0.0, 0.0, 0.0]), (1, 20, 1))
+    k[0, 7] = [-3.0, 0.0, 0.0, 0.0]                                           # one key points the other way
+    s = vo.score_key_diversity(k)
+    assert abs(s[0, 7] - 1.0) < 1e-6 and np.allclose(np.delete(s[0], 7), -1.0, atol=1e-6)
+    rng = np.random.default_rng(32)
+    big = rng.standard_normal((1, 90, 6)) * 0.1 + np.array([3.0, 0, 0, 0, 0, 0])
+    small = rng.standard_normal((1, 10, 6)) * 0.1 + np.array([0, 3.0, 0, 0, 0, 0])
+    s = vo.score_key_diversity(np.concatenate([big, small], axis=1))
+    assert s[0, 90:].min() > s[0, :90].max()                                  # the minority direction ranks highest
