@@ -97,6 +97,15 @@ VECTOR_API const char* vector_strerror(int code);
 VECTOR_API int vector_score(const vector_shape* shape, const void* q_win, const void* k,
                  float* score, void* ws, size_t ws_bytes, void* stream);
 
+/* A query-agnostic scorer (Section 5 pairs VECTOR with scorers that rank tokens by the geometric
+ * diversity of their keys and gives no formula; this is one such score): with a_h the direction of
+ * the mean of head h's unit-normalised keys, score[h,t] = - cos(k[h,t], a_h); a zero key scores 0.
+ * No observation window is involved (shape->window and pool_kernel are ignored).  The result feeds
+ * vector_route like any other score.  ws: vector_score_key_diversity_workspace_bytes(shape). */
+VECTOR_API size_t vector_score_key_diversity_workspace_bytes(const vector_shape* shape);
+VECTOR_API int vector_score_key_diversity(const vector_shape* shape, const void* k, float* score, void* ws,
+                               size_t ws_bytes, void* stream);
+
 /* Reconstruction residual (Section 3.2 Step 2), for every token:
  *   eps[h,t] = || v[h,t] - k[h,t] . W[h] ||_2^2, fp32 accumulation.
  * W: device [Hkv, d, d] (or one [d, d] when w_shared).  eps: device fp32 [Hkv, n]. */

@@ -28,6 +28,7 @@ EXPORTS = (
     "vector_calibrate_workspace_bytes", "vector_calibrate",
     "vector_distortion_workspace_bytes", "vector_distortion",
     "vector_r2_workspace_bytes", "vector_r2",
+    "vector_score_key_diversity_workspace_bytes", "vector_score_key_diversity",
 )
 
 
@@ -116,6 +117,9 @@ def lib() -> C.CDLL:
         L.vector_compress_workspace_bytes.argtypes = [C.POINTER(Shape), i32, i32]
         L.vector_compress_workspace_bytes.restype = sz
         L.vector_compress.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
+        L.vector_score_key_diversity_workspace_bytes.argtypes = [C.POINTER(Shape)]
+        L.vector_score_key_diversity_workspace_bytes.restype = sz
+        L.vector_score_key_diversity.argtypes = [C.POINTER(Shape), vp, vp, vp, sz, vp]
         L.vector_residual_rope.argtypes = [C.POINTER(Shape), vp, vp, vp, C.POINTER(Rope), vp, vp, sz, vp]
         L.vector_score_residual_rope.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, C.POINTER(Rope), vp, vp, vp, sz, vp]
         L.vector_decode_attn_rope.argtypes = [C.POINTER(Cache), C.POINTER(Rope), vp, C.c_float, vp, i32, vp, sz, vp]
@@ -285,3 +289,12 @@ def vector_compress(shape: Shape, q_win, k, v, W, n_pool: int, n_approx: int, sc
     _check(lib().vector_compress(C.byref(shape), _ptr(q_win), _ptr(k), _ptr(v), _ptr(W), n_pool, n_approx, _ptr(score),
                                  _ptr(eps), _ptr(tier), _ptr(idx_retain), _ptr(idx_approx), _ptr(k_ret), _ptr(v_ret),
                                  _ptr(k_apx), cap_retain, _ptr(ws), _nbytes(ws), _stream(stream)), "vector_compress")
+
+
+def vector_score_key_diversity_workspace_bytes(shape: Shape) -> int:
+    return int(lib().vector_score_key_diversity_workspace_bytes(C.byref(shape)))
+
+
+def vector_score_key_diversity(shape: Shape, k, score, ws, stream=None) -> None:
+    _check(lib().vector_score_key_diversity(C.byref(shape), _ptr(k), _ptr(score), _ptr(ws), _nbytes(ws), _stream(stream)),
+           "vector_score_key_diversity")

@@ -56,6 +56,9 @@ int launch_distortion(const vector_shape& s, const float* w, const uint8_t* tier
 size_t r2_workspace_bytes(int n_kv_heads, int seq_len, int head_dim);
 int launch_r2(const vector_shape& s, const float* eps, const void* v, double* out, void* part_ws, hipStream_t stream);
 
+size_t diversity_workspace_bytes(const vector_shape& s);
+int launch_key_diversity(const vector_shape& s, const void* k, float* score, void* ws, hipStream_t stream);
+
 size_t route_workspace_bytes(int n_kv_heads, int seq_len, int n_pool);
 int launch_route(int n_kv_heads, int seq_len, const float* score, const float* eps, int n_pool, int n_approx,
                  uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx, void* ws, hipStream_t stream);

@@ -123,6 +123,19 @@ int vector_residual(const vector_shape* s, const void* k, const void* v, const v
   return vec::launch_score_residual(t, nullptr, k, v, W, nullptr, eps, nullptr, (hipStream_t)stream);
 }
 
+size_t vector_score_key_diversity_workspace_bytes(const vector_shape* s) {
+  if (check_shape(s, false) != VECTOR_OK) return 0;
+  return vec::diversity_workspace_bytes(*s);
+}
+
+int vector_score_key_diversity(const vector_shape* s, const void* k, float* score, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_shape(s, false);
+  if (rc) return rc;
+  if (!k || !score || !aligned16(k)) return VECTOR_ERR_ARG;
+  if ((rc = check_ws(ws, ws_bytes, vec::diversity_workspace_bytes(*s)))) return rc;
+  return vec::launch_key_diversity(*s, k, score, ws, (hipStream_t)stream);
+}
+
 size_t vector_compress_workspace_bytes(const vector_shape* s, int32_t n_pool, int32_t n_approx) {
   if (check_shape(s, true) != VECTOR_OK || n_pool < 0 || n_approx < 0 || n_approx > n_pool) return 0;
   return vec::score_workspace_bytes(*s) + vec::route_workspace_bytes(s->n_kv_heads, s->seq_len, n_pool) + 256;
