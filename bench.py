@@ -341,6 +341,10 @@ def run_extras(vb, dg, pl, torch, np, dev, cfg, shape, layer, out, ws, n_p, n_a)
     res["calibrate_262144_tokens_us"] = us
     res["calibrate_gram_flops"] = int(H * 2 * 2 * m * d * d)
     del kc, vc
+    # the query-agnostic scorer on the same keys
+    wsk = pl.alloc_workspace(vb.vector_score_key_diversity_workspace_bytes(shape), dev)
+    sk = torch.empty((H, n), device=dev)
+    res["score_key_diversity_us_per_layer"] = per_call_us(lambda: vb.vector_score_key_diversity(shape, layer["k"], sk, wsk))
     # diagnostics on the layer's own routing
     dout = torch.empty((H, len(vb.DISTORTION_FIELDS)), dtype=torch.float64, device=dev)
     wsd = pl.alloc_workspace(vb.vector_distortion_workspace_bytes(shape), dev)

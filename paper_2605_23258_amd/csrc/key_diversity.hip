@@ -1,7 +1,7 @@
 // A query-agnostic importance score: the negative cosine of a key to the mean direction of
 // its head's unit-normalised keys (a reading of the "key geometric diversity" scorers that
 // Section 5 names without a formula).  Two streaming passes over K, both bound by HBM:
-//   anchor_partial_kernel : grid (chunks of 2048 tokens, kv heads).  A row is read by
+//   anchor_partial_kernel : grid (chunks of 512 tokens, kv heads).  A row is read by
 //                           row_bytes/16 adjacent lanes; the row norm is a rotate-add across
 //                           them; every lane accumulates its 16 bytes of k / ||k|| over the
 //                           rows it sees; lanes, waves -> one partial sum per chunk.
@@ -15,7 +15,8 @@ namespace vec {
 namespace {
 
 constexpr int kDivThreads = 256;
-constexpr int kDivTokens = 2048;          // per workgroup
+constexpr int kDivTokens = 512;           // per workgroup
+constexpr int kDivUnroll = 4;             // rows per lane group in flight
 
 struct DivParams {
   const void* k;
@@ -46,17 +47,24 @@ __global__ __launch_bounds__(kDivThreads) void anchor_partial_kernel(DivParams p
   float acc[E];
 #pragma unroll
   for (int e = 0; e < E; ++e) acc[e] = 0.f;
-  for (int t0 = chunk * kDivTokens + wave * RPW; t0 < t_end; t0 += NW * RPW) {
-    const int t = t0 + grp;
-    float f[8];
-    Unpack16<T>::run(load_chunk(k_head + (int64_t)min(t, p.n - 1) * p.k_st + piece * E), f);
-    float sq = 0.f;
+  for (int t0 = chunk * kDivTokens + wave * RPW; t0 < t_end; t0 += NW * RPW * kDivUnroll) {
+    uint4 raw[kDivUnroll];
 #pragma unroll
-    for (int e = 0; e < E; ++e) sq = fmaf(f[e], f[e], sq);
-    sq = lanes_sum<LPR>(sq);
-    const float inv = (t < t_end && sq > 0.f) ? 1.0f / sqrtf(sq) : 0.f;      // a zero key has no direction
+    for (int u = 0; u < kDivUnroll; ++u)
+      raw[u] = load_chunk(k_head + (int64_t)min(t0 + u * NW * RPW + grp, p.n - 1) * p.k_st + piece * E);
 #pragma unroll
-    for (int e = 0; e < E; ++e) acc[e] = fmaf(f[e], inv, acc[e]);
+    for (int u = 0; u < kDivUnroll; ++u) {
+      const int t = t0 + u * NW * RPW + grp;
+      float f[8];
+      Unpack16<T>::run(raw[u], f);
+      float sq = 0.f;
+#pragma unroll
+      for (int e = 0; e < E; ++e) sq = fmaf(f[e], f[e], sq);
+      sq = lanes_sum<LPR>(sq);
+      const float inv = (t < t_end && sq > 0.f) ? 1.0f / sqrtf(sq) : 0.f;      // a zero key has no direction
+#pragma unroll
+      for (int e = 0; e < E; ++e) acc[e] = fmaf(f[e], inv, acc[e]);
+    }
   }
 #pragma unroll
   for (int e = 0; e < E; ++e) red[wave][grp][piece * E + e] = acc[e];
@@ -100,16 +108,23 @@ __global__ __launch_bounds__(kDivThreads) void diversity_score_kernel(DivParams 
   for (int e = 0; e < E; ++e) a[e] = anchor[piece * E + e] * norm_lds;
   const T* k_head = reinterpret_cast<const T*>(p.k) + (int64_t)h * p.k_sh;
   const int t_end = min(p.n, (chunk + 1) * kDivTokens);
-  for (int t0 = chunk * kDivTokens + wave * RPW; t0 < t_end; t0 += NW * RPW) {
-    const int t = t0 + grp;
-    float f[8];
-    Unpack16<T>::run(load_chunk(k_head + (int64_t)min(t, p.n - 1) * p.k_st + piece * E), f);
-    float sq = 0.f, dot = 0.f;
+  for (int t0 = chunk * kDivTokens + wave * RPW; t0 < t_end; t0 += NW * RPW * kDivUnroll) {
+    uint4 raw[kDivUnroll];
 #pragma unroll
-    for (int e = 0; e < E; ++e) { sq = fmaf(f[e], f[e], sq); dot = fmaf(f[e], a[e], dot); }
-    sq = lanes_sum<LPR>(sq);
-    dot = lanes_sum<LPR>(dot);
-    if (piece == 0 && t < t_end) p.score[(size_t)h * p.n + t] = sq > 0.f ? -dot / sqrtf(sq) : 0.f;
+    for (int u = 0; u < kDivUnroll; ++u)
+      raw[u] = load_chunk(k_head + (int64_t)min(t0 + u * NW * RPW + grp, p.n - 1) * p.k_st + piece * E);
+#pragma unroll
+    for (int u = 0; u < kDivUnroll; ++u) {
+      const int t = t0 + u * NW * RPW + grp;
+      float f[8];
+      Unpack16<T>::run(raw[u], f);
+      float sq = 0.f, dot = 0.f;
+#pragma unroll
+      for (int e = 0; e < E; ++e) { sq = fmaf(f[e], f[e], sq); dot = fmaf(f[e], a[e], dot); }
+      sq = lanes_sum<LPR>(sq);
+      dot = lanes_sum<LPR>(dot);
+      if (piece == 0 && t < t_end) p.score[(size_t)h * p.n + t] = sq > 0.f ? -dot / sqrtf(sq) : 0.f;
+    }
   }
 }
 
