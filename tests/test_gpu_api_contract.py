@@ -201,3 +201,32 @@ def test_query_row_limit():
     with pytest.raises(vb.VectorError) as ei:
         vb.vector_score_residual(pl.shape_of(too_many), q_big, dev["k"], dev["v"], dev["w_cal"], score, eps, ws)
     assert ei.value.code == vb.VECTOR_ERR_SHAPE
+
+
+def test_layers_stacked_along_the_head_axis():
+    """Every step is independent per KV head: four layers stacked as 8 heads give, head for head,
+    exactly what the four separate calls give."""
+    cfg = dg.scaled(dg.CONFIGS["cfg2"], seq_len=2048, n_kv_heads=2, n_q_heads=8)
+    lis = [dg.make_layer(cfg, l) for l in range(4)]
+    n_r, n_a, n_p = cfg.counts()
+    shape1 = pl.shape_of(cfg)
+    singles = []
+    for li in lis:
+        dev = {x: pl.to_device(getattr(li, x)) for x in ("q_win", "k", "v", "w_cal")}
+        out = pl.alloc_outputs(shape1, n_p, n_a, n_r, torch.bfloat16)
+        ws = pl.alloc_workspace(vb.vector_workspace_bytes(shape1, n_p, n_a, 1))
+        pl.compress_layer(shape1, dev["q_win"], dev["k"], dev["v"], dev["w_cal"], n_p, n_a, out, ws)
+        singles.append(out)
+    big = dg.scaled(cfg, n_kv_heads=8, n_q_heads=32)
+    shape4 = pl.shape_of(big)
+    stack = {x: pl.to_device(np.concatenate([getattr(li, x) for li in lis], axis=0)) for x in ("q_win", "k", "v", "w_cal")}
+    out4 = pl.alloc_outputs(shape4, n_p, n_a, n_r, torch.bfloat16)
+    ws4 = pl.alloc_workspace(vb.vector_workspace_bytes(shape4, n_p, n_a, 1))
+    pl.compress_layer(shape4, stack["q_win"], stack["k"], stack["v"], stack["w_cal"], n_p, n_a, out4, ws4)
+    torch.cuda.synchronize()
+    for name in ("score", "eps", "tier", "idx_retain", "idx_approx", "k_ret", "v_ret", "k_apx"):
+        got = getattr(out4, name)
+        want = torch.cat([getattr(o, name) for o in singles], dim=0)
+        if got.dtype == torch.bfloat16:
+            got, want = got.view(torch.int16), want.view(torch.int16)
+        assert torch.equal(got, want), name
