@@ -60,8 +60,14 @@ def budget_counts(n: int, p_c: float, p_a: float) -> Tuple[int, int]:
 
 
 def budget_counts_frac(n: int, f_retain: float, f_approx: float) -> Tuple[int, int]:
-    n_r = int(math.floor(f_retain * n))
-    n_a = int(math.floor(f_approx * n))
+    """Floors of fraction * n.  The paper's ratios are decimals (Section 5 uses p_c = 0.9 with
+    p_a = 0.05) that doubles only approximate, so a product within 1e-9 of an integer is taken
+    as that integer: 5 % of 1000 tokens is 50 tokens."""
+    def count(f: float) -> int:
+        x = f * n
+        r = round(x)
+        return int(r) if abs(x - r) <= 1e-9 else int(math.floor(x))
+    n_r, n_a = count(f_retain), count(f_approx)
     return n_r + n_a, n_a
 
 

@@ -45,3 +45,15 @@ def test_counts_from_paper_ratios():
         n_pool, n_approx = vo.budget_counts(n, p_c, p_a)
         assert abs(n_approx - 2 * p_a * n) <= 1 and abs(n_pool - (1 - p_c + p_a) * n) <= 2
         assert n_pool + (n_pool - n_approx) <= 2 * (1 - p_c) * n + 1e-9
+
+
+def test_exact_counts_at_decimal_ratios():
+    """Hand values.  Section 5 runs p_c = 0.9 with p_a = 0.05: of 1000 tokens 5 % = 50 are retained and
+    10 % = 100 approximated, although 1 - 0.9 - 0.05 is a hair below 0.05 in binary floating point.
+    Products that are not integers are still floored."""
+    assert vo.budget_counts(1000, 0.9, 0.05) == (150, 100)
+    assert vo.budget_counts(30000, 0.9, 0.05) == (4500, 3000)
+    assert vo.budget_counts(1000, 0.8, 0.1) == (300, 200)
+    assert vo.budget_counts(1001, 0.9, 0.05) == (150, 100)          # 50.05 -> 50, 100.1 -> 100
+    assert vo.budget_counts(7, 0.5, 0.25) == (4, 3)                 # 1.75 -> 1, 3.5 -> 3
+    assert vo.budget_counts_frac(10, 0.29, 0.0) == (2, 0)           # 2.9 stays 2
