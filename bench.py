@@ -20,6 +20,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+import workloads as wl   # noqa: E402  (harness: input draws + the offline least-squares calibration)
+
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
 
@@ -99,7 +101,7 @@ def main() -> None:
     # ---- inputs: every layer has its own draws; all of them resident in HBM ----
     t0 = time.time()
     def gen(layer):
-        li = dg.make_layer(cfg, layer)
+        li = wl.make_layer(cfg, layer)
         return {k: getattr(li, k) for k in ("q_win", "k", "v", "w_cal")}
     with blas_single_thread(), ThreadPoolExecutor(workers) as ex:
         host_layers = list(ex.map(gen, range(cfg.layers)))
@@ -368,7 +370,7 @@ def run_decode(args, vb, dg, pl, torch, np, dev, workers):
     k_apx = torch.zeros((B, H, n_a, d), dtype=torch.bfloat16, device=dev)
     t0 = time.time()
     with blas_single_thread(), ThreadPoolExecutor(workers) as ex:
-        seqs = list(ex.map(lambda b: dg.make_layer(cfg, 0, sub=b), range(B)))
+        seqs = list(ex.map(lambda b: wl.make_layer(cfg, 0, sub=b), range(B)))
     # the first sequence's map is used for every sequence: W belongs to the layer, not the sequence
     W = pl.to_device(seqs[0].w_cal, dev)
     scratch = pl.alloc_outputs(shape, n_p, n_a, 1, torch.bfloat16, dev)

@@ -70,7 +70,9 @@ typedef struct {
 
 /* Section 3.2: with compression ratio p_c and approximation ratio p_a the
  * retained fraction is 1-p_c-p_a and the approximated fraction 2 p_a.
- * Counts are floors (in double); n_pool = n_retain + n_approx. */
+ * Counts are floors of fraction * n, where a product within 1e-9 of an integer counts as that
+ * integer (p_c = 0.9, p_a = 0.05, n = 1000 gives 50 retained, not 49);
+ * n_pool = n_retain + n_approx. */
 VECTOR_API int vector_budget_counts(int32_t n, double p_c, double p_a, int32_t* n_pool, int32_t* n_approx);
 /* Same, from token fractions directly. */
 VECTOR_API int vector_budget_counts_frac(int32_t n, double f_retain, double f_approx, int32_t* n_pool, int32_t* n_approx);
@@ -126,7 +128,7 @@ VECTOR_API int vector_score_residual(const vector_shape* shape, const void* q_wi
  * score, eps: device fp32 [Hkv, n].  tier: device u8 [Hkv, n] (VECTOR_TIER_*).
  * idx_retain: device i32 [Hkv, n_pool-n_approx], idx_approx: device i32
  * [Hkv, n_approx], both ascending token indices.
- * Requires 0 <= n_approx <= n_pool <= n. */
+ * Requires 0 <= n_approx <= n_pool <= n, n <= 2^20 and n_kv_heads <= 65535 (VECTOR_ERR_SHAPE beyond). */
 VECTOR_API int vector_route(int32_t n_kv_heads, int32_t seq_len, const float* score, const float* eps,
                  int32_t n_pool, int32_t n_approx,
                  uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx,
@@ -175,11 +177,15 @@ typedef struct {
  * approximated rows together, logits q . k_t * scale, and
  *   out = sum_ret p_t v_t + sum_apx p_t (k_t . W[h]).
  * q: device [batch, Hq, d]; out: device [batch, Hq, d], same dtype as the cache.
+ * Hq / Hkv may be 1 .. 8 (VECTOR_ERR_SHAPE otherwise).
  * flags: 0, or VECTOR_DECODE_LITERAL to rebuild v_hat = k . W for every approximated row on
  * the matrix cores before weighting it (bf16 caches only); by default the weighted keys are
  * summed first and W is applied once, (sum p_t k_t) . W, which is the same sum in another
  * order and far less work.  A sequence with no live token yields zeros. */
 #define VECTOR_DECODE_LITERAL 1
+/* flags: VECTOR_DECODE_OUT_F32 stores out as fp32 [batch, Hq, d] whatever the cache dtype (the
+ * kernels accumulate in fp32; without the flag a bf16 cache rounds the result to bf16 on store). */
+#define VECTOR_DECODE_OUT_F32 2
 VECTOR_API int vector_decode_attn(const vector_cache* cache, const void* q, float scale, void* out,
                        int32_t flags, void* ws, size_t ws_bytes, void* stream);
 

@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(PKG_DIR, "libvector.so")
 
 VECTOR_F32, VECTOR_BF16 = 0, 1
 VECTOR_DECODE_LITERAL = 1
+VECTOR_DECODE_OUT_F32 = 2
 VECTOR_OK, VECTOR_ERR_ARG, VECTOR_ERR_SHAPE, VECTOR_ERR_WORKSPACE, VECTOR_ERR_DTYPE, VECTOR_ERR_HIP = 0, -1, -2, -3, -4, -5
 TIER_EVICT, TIER_APPROX, TIER_RETAIN = 0, 1, 2
 
@@ -123,9 +124,6 @@ def lib() -> C.CDLL:
         L.vector_residual_rope.argtypes = [C.POINTER(Shape), vp, vp, vp, C.POINTER(Rope), vp, vp, sz, vp]
         L.vector_score_residual_rope.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, C.POINTER(Rope), vp, vp, vp, sz, vp]
         L.vector_decode_attn_rope.argtypes = [C.POINTER(Cache), C.POINTER(Rope), vp, C.c_float, vp, i32, vp, sz, vp]
-        for name in EXPORTS:
-            if getattr(L, name).restype is C.c_int:
-                pass
         _lib = L
     return _lib
 
@@ -242,8 +240,8 @@ def vector_score_residual_rope(shape: Shape, q_win, k, v, W, rope: Rope, score, 
            "vector_score_residual_rope")
 
 
-def vector_decode_attn_rope(cache: Cache, rope: Rope, q, scale: float, out, ws, stream=None) -> None:
-    _check(lib().vector_decode_attn_rope(C.byref(cache), C.byref(rope), _ptr(q), scale, _ptr(out), 0, _ptr(ws),
+def vector_decode_attn_rope(cache: Cache, rope: Rope, q, scale: float, out, ws, flags: int = 0, stream=None) -> None:
+    _check(lib().vector_decode_attn_rope(C.byref(cache), C.byref(rope), _ptr(q), scale, _ptr(out), flags, _ptr(ws),
                                          _nbytes(ws), _stream(stream)), "vector_decode_attn_rope")
 
 

@@ -39,6 +39,7 @@ struct DecodeParams {
   int64_t w_sh;           // element stride between per-head W
   float c2;               // scale * log2(e)
   int literal;            // approximated rows: rebuild v_hat = k W per row instead of (sum p k) W
+  int out_f32;            // store the result as fp32 whatever the cache dtype
 };
 
 constexpr int DT_ = 256;          // threads per workgroup
@@ -708,7 +709,9 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeParams p) {
     float zw = 0.f;
 #pragma unroll
     for (int q = 0; q < kWavesC; ++q) zw += zw_lds[q][g][j];
-    store_elem(out + i, (v_lds[g][j] + zw) * linv_lds[g]);
+    const float r = (v_lds[g][j] + zw) * linv_lds[g];
+    if (p.out_f32) reinterpret_cast<float*>(p.out)[((size_t)b * p.Hq + (size_t)h * G) * D + i] = r;
+    else store_elem(out + i, r);
   }
 }
 
@@ -761,7 +764,11 @@ int run_decode_g(const vector_cache& c, DecodeParams& p, hipStream_t stream, con
   switch (c.n_q_heads / c.n_kv_heads) {
     case 1: return run_decode<T, D, 1>(c, p, stream, rope);
     case 2: return run_decode<T, D, 2>(c, p, stream, rope);
+    case 3: return run_decode<T, D, 3>(c, p, stream, rope);
     case 4: return run_decode<T, D, 4>(c, p, stream, rope);
+    case 5: return run_decode<T, D, 5>(c, p, stream, rope);
+    case 6: return run_decode<T, D, 6>(c, p, stream, rope);
+    case 7: return run_decode<T, D, 7>(c, p, stream, rope);
     case 8: return run_decode<T, D, 8>(c, p, stream, rope);
     default: return VECTOR_ERR_SHAPE;
   }
@@ -780,6 +787,7 @@ int launch_decode_attn(const vector_cache& c, const void* q, float scale, void* 
                        hipStream_t stream, const RopeParams* rope) {
   DecodeParams p;
   p.literal = (flags & VECTOR_DECODE_LITERAL) ? 1 : 0;
+  p.out_f32 = (flags & VECTOR_DECODE_OUT_F32) ? 1 : 0;
   if (p.literal && (rope || c.dtype != VECTOR_BF16)) return VECTOR_ERR_DTYPE;
   p.q = q; p.k_ret = c.k_ret; p.v_ret = c.v_ret; p.k_apx = c.k_apx; p.W = c.W; p.len_retain = c.len_retain;
   p.out = out; p.part = reinterpret_cast<float*>(ws);

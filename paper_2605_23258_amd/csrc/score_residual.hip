@@ -10,8 +10,9 @@
 //                           p = exp2(S*c - bias_r), column mean -> mass; fused on the
 //                           same K registers: v_hat^T = W^T K^T (MFMA),
 //                           eps = sum_j (v - v_hat)^2
-//   pool    pool_scores   : average pooling of mass over prefix columns, +inf on
-//                           the window columns
+//   pool                  : average pooling of mass over prefix columns, +inf on the window
+//                           columns (route_hist_kernel in route_compact.hip, which can hand the
+//                           routing its first histogram in the same launch)
 //
 // Pass 1 has two kernels: score_stats_tiles_kernel (R_pad = 128 or 256: key tiles through LDS,
 // a wave keeps its block of Q_h and the rows' running statistics in registers) and
@@ -23,8 +24,6 @@
 // overlap the MFMAs of its own wave and only partly those of the SIMD's other wave.
 // Template flags of pass 2: PROBE (repeat a tile's arithmetic on resident operands, for
 // measuring the contraction alone), ROPE (keys are un-rotated by position for the residual).
-#include <stdlib.h>
-
 #include "common.hpp"
 #include "launch.hpp"
 
@@ -903,34 +902,10 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
 }
 
 // ---------------------------------------------------------------------------
-// pooling
-// ---------------------------------------------------------------------------
-__global__ void pool_scores_kernel(const float* __restrict__ mass, float* __restrict__ score, int n, int n_prefix, int kernel) {
-  const int h = blockIdx.y;
-  const int t = blockIdx.x * blockDim.x + threadIdx.x;
-  if (t >= n) return;
-  float out = INFINITY;
-  if (t < n_prefix) {
-    const int half = kernel / 2;
-    const int lo = max(0, t - half), hi = min(n_prefix - 1, t + half);
-    float s = 0.f;
-    for (int j = lo; j <= hi; ++j) s += mass[(size_t)h * n + j];
-    out = s / (float)kernel;
-  }
-  score[(size_t)h * n + t] = out;
-}
-
-// ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
 constexpr int kThreads = 512;        // pass 2
 
-// VECTOR_STATS_DIRECT=1 in the environment keeps pass 1 on the kernel that loads keys straight
-// into operand registers (for comparison runs)
-bool stats_tiles_disabled() {
-  static const bool off = [] { const char* e = getenv("VECTOR_STATS_DIRECT"); return e && e[0] == '1'; }();
-  return off;
-}
 constexpr int kThreads1 = VEC_P1_THREADS;   // pass 1
 constexpr int kSub1 = VEC_P1_SUBTILES;
 
@@ -955,7 +930,7 @@ size_t stats_tiles_lds(int nrb, size_t lds_stride) {
   return (size_t)2 * (kV2Threads / kWave / (nrb ? nrb : 1)) * kV2TileTokens * lds_stride;
 }
 bool stats_by_tiles(int nrb, size_t lds_stride) {
-  return (nrb == 8 || nrb == 4) && stats_tiles_lds(nrb, lds_stride) <= kMaxLdsBytes && !stats_tiles_disabled();
+  return (nrb == 8 || nrb == 4) && stats_tiles_lds(nrb, lds_stride) <= kMaxLdsBytes;
 }
 
 int pick_tokens_per_chunk(int n, int n_kv_heads) {
@@ -990,7 +965,8 @@ int make_plan(const vector_shape& s, bool do_mass, bool do_res, Plan& plan) {
   constexpr int NW = kThreads1 / kWave;
   plan.lds_stats = (size_t)p.R_pad * TL::kLdsStride + (size_t)NW * (p.R_pad / 32) * 64 * sizeof(float2);
   plan.lds_pass2 = (do_mass ? (size_t)p.R_pad * (TL::kLdsStride + sizeof(float)) : 0) + (do_res ? (size_t)D * TL::kLdsStride : 0);
-  if (plan.lds_stats > kMaxLdsBytes || plan.lds_pass2 > kMaxLdsBytes) return VECTOR_ERR_SHAPE;
+  // the pass-1 footprint only matters when the scores are asked for
+  if ((do_mass && !plan.tiles && plan.lds_stats > kMaxLdsBytes) || plan.lds_pass2 > kMaxLdsBytes) return VECTOR_ERR_SHAPE;
   return VECTOR_OK;
 }
 
@@ -1008,7 +984,8 @@ size_t score_workspace_bytes(const vector_shape& s) {
 
 template <typename T, int D>
 static int run_score_residual(const vector_shape& s, const void* q, const void* k, const void* v, const void* W,
-                              float* score, float* eps, void* ws, hipStream_t stream, const RopeParams* rope) {
+                              float* score, float* eps, void* ws, hipStream_t stream, const RopeParams* rope,
+                              uint16_t* score_hist) {
   const bool do_mass = score != nullptr, do_res = eps != nullptr;
   Plan plan;
   int rc = make_plan<T, D>(s, do_mass, do_res, plan);
@@ -1046,10 +1023,8 @@ static int run_score_residual(const vector_shape& s, const void* q, const void* 
   else k2 = use_rope ? mass_residual_kernel<T, D, kThreads, false, true, false, true> : mass_residual_kernel<T, D, kThreads, false, true>;
   VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k2), lds2));
   VEC_LAUNCH(K_MASS_RESIDUAL, k2, grid, dim3(kThreads), lds2, stream, p, rp);
-  if (do_mass)
-    VEC_LAUNCH(K_POOL, pool_scores_kernel, dim3((s.seq_len + 255) / 256, s.n_kv_heads), dim3(256), 0, stream,
-                       p.mass, score, s.seq_len, p.n_prefix, s.pool_kernel);
   VEC_HIP(hipGetLastError());
+  if (do_mass) return launch_pool_scores(p.mass, score, s.n_kv_heads, s.seq_len, p.n_prefix, s.pool_kernel, score_hist, stream);
   return VECTOR_OK;
 }
 
@@ -1078,13 +1053,14 @@ int launch_residual_probe(const vector_shape& s, const void* k, const void* v, c
 }
 
 int launch_score_residual(const vector_shape& s, const void* q, const void* k, const void* v, const void* W,
-                          float* score, float* eps, void* ws, hipStream_t stream, const RopeParams* rope) {
+                          float* score, float* eps, void* ws, hipStream_t stream, const RopeParams* rope,
+                          uint16_t* score_hist) {
   if (s.dtype == VECTOR_BF16) {
-    if (s.head_dim == 128) return run_score_residual<bf16_t, 128>(s, q, k, v, W, score, eps, ws, stream, rope);
-    if (s.head_dim == 64) return run_score_residual<bf16_t, 64>(s, q, k, v, W, score, eps, ws, stream, rope);
+    if (s.head_dim == 128) return run_score_residual<bf16_t, 128>(s, q, k, v, W, score, eps, ws, stream, rope, score_hist);
+    if (s.head_dim == 64) return run_score_residual<bf16_t, 64>(s, q, k, v, W, score, eps, ws, stream, rope, score_hist);
   } else if (s.dtype == VECTOR_F32) {
-    if (s.head_dim == 128) return run_score_residual<float, 128>(s, q, k, v, W, score, eps, ws, stream, rope);
-    if (s.head_dim == 64) return run_score_residual<float, 64>(s, q, k, v, W, score, eps, ws, stream, rope);
+    if (s.head_dim == 128) return run_score_residual<float, 128>(s, q, k, v, W, score, eps, ws, stream, rope, score_hist);
+    if (s.head_dim == 64) return run_score_residual<float, 64>(s, q, k, v, W, score, eps, ws, stream, rope, score_hist);
   } else {
     return VECTOR_ERR_DTYPE;
   }

@@ -17,7 +17,7 @@ int check_shape(const vector_shape* s, bool need_window) {
   if (s->dtype != VECTOR_F32 && s->dtype != VECTOR_BF16) return VECTOR_ERR_DTYPE;
   if (s->head_dim != 64 && s->head_dim != 128) return VECTOR_ERR_SHAPE;
   if (s->n_kv_heads < 1 || s->n_kv_heads > 65535 || s->n_q_heads < s->n_kv_heads || s->n_q_heads % s->n_kv_heads) return VECTOR_ERR_SHAPE;
-  if (s->seq_len < 1) return VECTOR_ERR_SHAPE;
+  if (s->seq_len < 1 || s->seq_len > vec::kRouteMaxSeqLen) return VECTOR_ERR_SHAPE;
   const int align = s->dtype == VECTOR_BF16 ? 8 : 4;      // elements per 16 bytes
   const int64_t strides[5] = {s->k_stride_head, s->k_stride_tok, s->v_stride_head, s->v_stride_tok, s->w_stride_head};
   for (int64_t st : strides)
@@ -61,8 +61,10 @@ extern "C" {
 int vector_budget_counts_frac(int32_t n, double f_retain, double f_approx, int32_t* n_pool, int32_t* n_approx) {
   if (!n_pool || !n_approx || n < 0) return VECTOR_ERR_ARG;
   if (!(f_retain >= 0.0) || !(f_approx >= 0.0) || f_retain + f_approx > 1.0 + 1e-12) return VECTOR_ERR_ARG;
-  const int32_t n_r = (int32_t)floor(f_retain * (double)n);
-  const int32_t n_a = (int32_t)floor(f_approx * (double)n);
+  // the fractions are decimal ratios that binary doubles only approximate (1 - 0.9 - 0.05 is a hair
+  // under 0.05): a product within 1e-9 of an integer is that integer
+  const int32_t n_r = (int32_t)floor(f_retain * (double)n + 1e-9);
+  const int32_t n_a = (int32_t)floor(f_approx * (double)n + 1e-9);
   *n_pool = n_r + n_a;
   *n_approx = n_a;
   return VECTOR_OK;
@@ -156,8 +158,11 @@ int vector_compress(const vector_shape* s, const void* q_win, const void* k, con
   if ((rc = check_ws(ws, ws_bytes, vector_compress_workspace_bytes(s, n_pool, n_approx)))) return rc;
   hipStream_t st = (hipStream_t)stream;
   void* route_ws = reinterpret_cast<unsigned char*>(ws) + (score_ws + 255) / 256 * 256;
-  if ((rc = vec::launch_score_residual(*s, q_win, k, v, W, score, eps, ws, st))) return rc;
-  if ((rc = vec::launch_route(s->n_kv_heads, s->seq_len, score, eps, n_pool, n_approx, tier, idx_retain, idx_approx, route_ws, st)))
+  // the scorer's pooling launch also builds the routing's first histogram
+  uint16_t* hist = n_pool > 0 ? vec::route_score_hist(route_ws) : nullptr;
+  if ((rc = vec::launch_score_residual(*s, q_win, k, v, W, score, eps, ws, st, nullptr, hist))) return rc;
+  if ((rc = vec::launch_route(s->n_kv_heads, s->seq_len, score, eps, n_pool, n_approx, tier, idx_retain, idx_approx, route_ws,
+                              hist != nullptr, st)))
     return rc;
   return vec::launch_compact(*s, k, v, idx_retain, idx_approx, n_retain, n_approx, k_ret, v_ret, k_apx, cap_retain, st);
 }
@@ -233,13 +238,13 @@ int vector_score_residual(const vector_shape* s, const void* q_win, const void* 
 int vector_route(int32_t n_kv_heads, int32_t seq_len, const float* score, const float* eps, int32_t n_pool,
                  int32_t n_approx, uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx, void* ws, size_t ws_bytes,
                  void* stream) {
-  if (n_kv_heads < 1 || seq_len < 1) return VECTOR_ERR_SHAPE;
+  if (n_kv_heads < 1 || n_kv_heads > 65535 || seq_len < 1 || seq_len > vec::kRouteMaxSeqLen) return VECTOR_ERR_SHAPE;
   if (n_approx < 0 || n_pool < n_approx || n_pool > seq_len) return VECTOR_ERR_ARG;
   if (!score || !eps || !tier) return VECTOR_ERR_ARG;
   if ((n_pool - n_approx > 0 && !idx_retain) || (n_approx > 0 && !idx_approx)) return VECTOR_ERR_ARG;
   int rc = check_ws(ws, ws_bytes, vec::route_workspace_bytes(n_kv_heads, seq_len, n_pool));
   if (rc) return rc;
-  return vec::launch_route(n_kv_heads, seq_len, score, eps, n_pool, n_approx, tier, idx_retain, idx_approx, ws,
+  return vec::launch_route(n_kv_heads, seq_len, score, eps, n_pool, n_approx, tier, idx_retain, idx_approx, ws, false,
                            (hipStream_t)stream);
 }
 
@@ -265,8 +270,9 @@ static int decode_checked(const vector_cache* c, const void* q, float scale, voi
   if (c->batch < 1 || c->batch > 65535 || c->n_kv_heads < 1 || c->n_kv_heads > 65535) return VECTOR_ERR_SHAPE;
   if (c->n_q_heads < c->n_kv_heads || c->n_q_heads % c->n_kv_heads) return VECTOR_ERR_SHAPE;
   const int G = c->n_q_heads / c->n_kv_heads;
-  if (G != 1 && G != 2 && G != 4 && G != 8) return VECTOR_ERR_SHAPE;
-  if (c->cap_retain < 0 || c->n_approx < 0 || (flags & ~VECTOR_DECODE_LITERAL) || !(scale == scale)) return VECTOR_ERR_ARG;
+  if (G > 8) return VECTOR_ERR_SHAPE;
+  if (c->cap_retain < 0 || c->n_approx < 0 || (flags & ~(VECTOR_DECODE_LITERAL | VECTOR_DECODE_OUT_F32)) || !(scale == scale))
+    return VECTOR_ERR_ARG;
   if ((flags & VECTOR_DECODE_LITERAL) && (rope || c->dtype != VECTOR_BF16)) return VECTOR_ERR_DTYPE;
   if (!c->len_retain) return VECTOR_ERR_ARG;
   if (c->cap_retain > 0 && (!c->k_ret || !c->v_ret || !aligned16(c->k_ret) || !aligned16(c->v_ret))) return VECTOR_ERR_ARG;

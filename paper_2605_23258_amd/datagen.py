@@ -1,11 +1,10 @@
 """Seeded synthetic inputs for the VECTOR compression pass and decode attention.
 
 This module only draws numbers. It holds none of the method's arithmetic (no
-scoring, residual, routing or attention): it produces the planted-regression
-K/V tensors, observation-window queries and the calibrated value map that the
-paper's Section 3.1 obtains offline by ordinary least squares, here fitted by a
-library least-squares call on a separate seeded draw so that it can be handed
-to the compression pass as an input.
+scoring, residual, routing, attention or least-squares fit): it produces the
+planted-regression K/V tensors and observation-window queries, and the separate
+seeded calibration draw from which the caller fits the value map that the paper's
+Section 3.1 obtains offline (the fit itself is passed in as a callable).
 
 Every stream is a counter-based Philox generator keyed by
 (master seed, config id, layer, tag), so any tensor can be regenerated on its
@@ -154,14 +153,6 @@ def _draw_kv(cfg: Config, layer: int, n: int, w_true: np.ndarray, tag_off: int, 
     return k, v, sigma, heavy
 
 
-def fit_w(k_cal: np.ndarray, v_cal: np.ndarray) -> np.ndarray:
-    """Least-squares value map per head on a calibration draw (library lstsq, fp64)."""
-    out = np.empty((k_cal.shape[0], k_cal.shape[2], v_cal.shape[2]), dtype=np.float64)
-    for h in range(k_cal.shape[0]):
-        out[h] = np.linalg.lstsq(k_cal[h].astype(np.float64), v_cal[h].astype(np.float64), rcond=None)[0]
-    return out
-
-
 def rotary_inv_freq(head_dim: int, theta: float) -> np.ndarray:
     """Angular frequency of pair i: theta^(-2i/d), float64 [d/2]."""
     return np.asarray(theta, dtype=np.float64) ** (-np.arange(head_dim // 2, dtype=np.float64) * 2.0 / head_dim)
@@ -184,9 +175,13 @@ def apply_rotary(x: np.ndarray, pos: np.ndarray, inv_freq: np.ndarray, interleav
     return out
 
 
-def make_layer(cfg: Config, layer: int = 0, sub: int = 0, rope_theta: Optional[float] = None,
+def make_layer(cfg: Config, fit, layer: int = 0, sub: int = 0, rope_theta: Optional[float] = None,
                rope_interleaved: bool = False, pos_offset: int = 0) -> LayerInputs:
     """Inputs of one compression pass: one layer of one sequence (`sub` = sequence id).
+
+    `fit(k_cal, v_cal) -> W [Hkv, d, d]` is the caller's offline calibration of the value map
+    (Section 3.1), run on a separate draw of `cfg.cal_tokens` tokens of the same law; this module
+    draws numbers and does none of the method's arithmetic itself.
 
     With `rope_theta` the stored keys are post-RoPE: the values (and the calibrated map) belong
     to the keys as drawn, and row t of the stored keys is that key turned by position
@@ -195,7 +190,7 @@ def make_layer(cfg: Config, layer: int = 0, sub: int = 0, rope_theta: Optional[f
     w_true = _rng(cfg.cfg_id, layer, _TAG_WTRUE, sub).standard_normal((H, d, d)) / np.sqrt(d)
     k, v, sigma, heavy = _draw_kv(cfg, layer, n, w_true, 0, sub)
     k_cal, v_cal, _, _ = _draw_kv(cfg, layer, cfg.cal_tokens, w_true, _TAG_CAL, sub)
-    w_cal = fit_w(k_cal, v_cal)
+    w_cal = fit(k_cal, v_cal)
     q = _rng(cfg.cfg_id, layer, _TAG_Q, sub).standard_normal((cfg.n_q_heads, w, d), dtype=np.float32)
     extra = {}
     if rope_theta is not None:

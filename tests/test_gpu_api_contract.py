@@ -8,7 +8,9 @@ torch = pytest.importorskip("torch")
 from oracle import vector_oracle as vo
 from paper_2605_23258_amd import binding as vb
 from paper_2605_23258_amd import datagen as dg
+import workloads as wl
 from paper_2605_23258_amd import pipeline as pl
+from parity_util import decode_check
 
 pytestmark = pytest.mark.gpu
 ATOL, RTOL = 1e-3, 2e-3
@@ -22,7 +24,7 @@ def close(got, ref, what):
 
 def _layer(**over):
     cfg = dg.scaled(dg.CONFIGS["cfg2"], **over)
-    return cfg, dg.make_layer(cfg, 0)
+    return cfg, wl.make_layer(cfg, 0)
 
 
 def test_token_major_interleaved_kv_layout():
@@ -99,13 +101,9 @@ def test_one_map_shared_by_all_heads():
     cache.len_retain, cache.k_ret, cache.v_ret, cache.k_apx, cache.W = (length.data_ptr(), t[0].data_ptr(), t[1].data_ptr(),
                                                                       t[2].data_ptr(), t[3].data_ptr())
     ws = pl.alloc_workspace(vb.vector_workspace_bytes(pl.shape_of(cfg), n_r + n_a, n_a, B))
-    out = torch.empty((B, Hq, d), dtype=torch.bfloat16, device="cuda:0")
     scale = 1.0 / np.sqrt(d)
-    vb.vector_decode_attn(cache, t[4], scale, out, ws)
-    torch.cuda.synchronize()
     ref = vo.decode_attn(dg.widen(q), dg.widen(k_ret), dg.widen(v_ret), np.full(B, n_r), dg.widen(k_apx), Wb, scale)
-    err = np.abs(dg.widen(pl.to_host(out)) - ref)
-    assert (err <= ATOL + (RTOL + 2.0 ** -8) * np.abs(ref)).all(), f"max err {err.max():.3e}"
+    decode_check(cache, t[4], scale, ws, ref, "decode (shared W)")
 
 
 def test_errors_are_reported_before_any_launch():
@@ -162,7 +160,7 @@ def test_errors_are_reported_before_any_launch():
 ])
 def test_one_call_pass_equals_the_three_calls(base, over):
     cfg = dg.scaled(dg.CONFIGS[base], **over)
-    li = dg.make_layer(cfg, 0)
+    li = wl.make_layer(cfg, 0)
     shape = pl.shape_of(cfg)
     n_r, n_a, n_p = cfg.counts()
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
@@ -184,7 +182,7 @@ def test_one_call_pass_equals_the_three_calls(base, over):
 def test_query_row_limit():
     """G*w rows per KV head live in LDS: the largest supported count works, the next one is refused."""
     ok = dg.scaled(dg.CONFIGS["cfg2"], seq_len=600, n_kv_heads=1, n_q_heads=4, window=72)       # 288 rows
-    li = dg.make_layer(ok, 0)
+    li = wl.make_layer(ok, 0)
     shape = pl.shape_of(ok)
     n_r, n_a, n_p = ok.counts()
     dev = {x: pl.to_device(getattr(li, x)) for x in ("q_win", "k", "v", "w_cal")}
@@ -207,7 +205,7 @@ def test_layers_stacked_along_the_head_axis():
     """Every step is independent per KV head: four layers stacked as 8 heads give, head for head,
     exactly what the four separate calls give."""
     cfg = dg.scaled(dg.CONFIGS["cfg2"], seq_len=2048, n_kv_heads=2, n_q_heads=8)
-    lis = [dg.make_layer(cfg, l) for l in range(4)]
+    lis = [wl.make_layer(cfg, l) for l in range(4)]
     n_r, n_a, n_p = cfg.counts()
     shape1 = pl.shape_of(cfg)
     singles = []

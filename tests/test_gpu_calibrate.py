@@ -7,6 +7,7 @@ torch = pytest.importorskip("torch")
 from oracle import vector_oracle as vo
 from paper_2605_23258_amd import binding as vb
 from paper_2605_23258_amd import datagen as dg
+import workloads as wl
 from paper_2605_23258_amd import pipeline as pl
 
 pytestmark = pytest.mark.gpu
@@ -34,7 +35,7 @@ def _fit_gpu(cfg, k_dev, v_dev, shape=None):
 def test_value_map_matches_oracle_fit(name):
     base, over = CASES[name]
     cfg = dg.scaled(dg.CONFIGS[base], **over)
-    li = dg.make_layer(cfg, 0)
+    li = wl.make_layer(cfg, 0)
     got = _fit_gpu(cfg, pl.to_device(li.k), pl.to_device(li.v))
     ref = vo.ols_fit(dg.widen(li.k), dg.widen(li.v))
     # the output is stored in the tensors' dtype: bf16 adds its own rounding (2^-9 relative)
@@ -57,7 +58,7 @@ def test_planted_map_without_noise_is_recovered():
 
 def test_strided_views_and_errors():
     cfg = dg.scaled(dg.CONFIGS["cfg2"], seq_len=2000, n_kv_heads=2, n_q_heads=8)
-    li = dg.make_layer(cfg, 0)
+    li = wl.make_layer(cfg, 0)
     H, n, d = cfg.n_kv_heads, cfg.seq_len, cfg.head_dim
     fused = np.zeros((n, H, 2, d), np.uint16)
     fused[:, :, 0] = np.transpose(li.k, (1, 0, 2))
@@ -90,7 +91,7 @@ def test_r2_of_the_fitted_map(name):
     both halves are strided views of the same tensors."""
     base, over = CASES[name]
     cfg = dg.scaled(dg.CONFIGS[base], **over)
-    li = dg.make_layer(cfg, 0)
+    li = wl.make_layer(cfg, 0)
     H, d, n = cfg.n_kv_heads, cfg.head_dim, cfg.seq_len
     m = n // 2
     shape = pl.shape_of(cfg, seq_len=m)

@@ -7,6 +7,7 @@ torch = pytest.importorskip("torch")
 from oracle import vector_oracle as vo
 from paper_2605_23258_amd import binding as vb
 from paper_2605_23258_amd import datagen as dg
+import workloads as wl
 from paper_2605_23258_amd import pipeline as pl
 
 pytestmark = pytest.mark.gpu
@@ -19,7 +20,7 @@ pytestmark = pytest.mark.gpu
 ])
 def test_report_matches_oracle(base, over):
     cfg = dg.scaled(dg.CONFIGS[base], **over)
-    li = dg.make_layer(cfg, 0)
+    li = wl.make_layer(cfg, 0)
     H, n = cfg.n_kv_heads, cfg.seq_len
     n_r, n_a, n_p = cfg.counts()
     wide = {x: dg.widen(getattr(li, x)) for x in ("q_win", "k", "v", "w_cal")}

@@ -10,7 +10,9 @@ torch = pytest.importorskip("torch")
 from oracle import vector_oracle as vo
 from paper_2605_23258_amd import binding as vb
 from paper_2605_23258_amd import datagen as dg
+import workloads as wl
 from paper_2605_23258_amd import pipeline as pl
+from parity_util import decode_check
 
 pytestmark = pytest.mark.gpu
 
@@ -49,7 +51,7 @@ CASES = {
 def _inputs(name):
     base, over = CASES[name]
     cfg = dg.scaled(dg.CONFIGS[base], **over)
-    li = dg.make_layer(cfg, 0)
+    li = wl.make_layer(cfg, 0)
     dev = {k: pl.to_device(getattr(li, k)) for k in ("q_win", "k", "v", "w_cal")}
     wide = {k: dg.widen(getattr(li, k)) for k in ("q_win", "k", "v", "w_cal")}
     return cfg, li, dev, wide
@@ -228,25 +230,13 @@ def test_decode_attn(dtype, d, B, Hq, Hkv, n_r, n_a, cap):
     shape = vb.Shape(n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, seq_len=max(cap, 1), window=1, pool_kernel=1, dtype=cache.dtype)
     ws = pl.alloc_workspace(vb.vector_workspace_bytes(shape, max(cap, 1), 0, B) + (1 << 20))
     out = torch.full((B, Hq, d), 7.0, dtype=tdt, device="cuda:0")
-    vb.vector_decode_attn(cache, t["q"], scale, out, ws)
-    torch.cuda.synchronize()
-    got = dg.widen(pl.to_host(out))
-    if dtype == "bf16":
-        # the output is rounded to bf16 on store: allow half an ulp on top of the tolerance
-        err = np.abs(got - ref)
-        assert (err <= ATOL + (RTOL + 2.0 ** -8) * np.abs(ref)).all(), f"max err {err.max():.3e}"
-    else:
-        close(got, ref, "decode out")
+    got = decode_check(cache, t["q"], scale, ws, ref, "decode out")
     if B > 1 and length[1] == 0 and n_a == 0:
         assert not got[1].any()
     if dtype == "bf16":
         # the literal variant (every approximated value rebuilt as k W before it is weighted) is
         # the same sum in another order
-        out_l = torch.full((B, Hq, d), 7.0, dtype=tdt, device="cuda:0")
-        vb.vector_decode_attn(cache, t["q"], scale, out_l, ws, flags=vb.VECTOR_DECODE_LITERAL)
-        torch.cuda.synchronize()
-        err = np.abs(dg.widen(pl.to_host(out_l)) - ref)
-        assert (err <= ATOL + (RTOL + 2.0 ** -8) * np.abs(ref)).all(), f"literal: max err {err.max():.3e}"
+        decode_check(cache, t["q"], scale, ws, ref, "decode out (literal)", flags=vb.VECTOR_DECODE_LITERAL)
     else:
         with pytest.raises(vb.VectorError) as ei:
             vb.vector_decode_attn(cache, t["q"], scale, out, ws, flags=vb.VECTOR_DECODE_LITERAL)
@@ -300,4 +290,4 @@ def test_end_to_end_compress(name):
     o_eps = vo.residual(wide["k"], wide["v"], wide["w_cal"])
     o_tier, _, _ = vo.route(o_score, o_eps, n_p, n_a)
     flips = _band_check(o_score, o_eps, n_p, n_a, tier, o_tier, n, name)
-    assert flips <= 0.01 * tier.size
+    assert flips <= 0.002 * tier.size

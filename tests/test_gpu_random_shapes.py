@@ -9,7 +9,9 @@ torch = pytest.importorskip("torch")
 from oracle import vector_oracle as vo
 from paper_2605_23258_amd import binding as vb
 from paper_2605_23258_amd import datagen as dg
+import workloads as wl
 from paper_2605_23258_amd import pipeline as pl
+from parity_util import decode_check
 
 pytestmark = pytest.mark.gpu
 ATOL, RTOL = 1e-3, 2e-3
@@ -43,7 +45,7 @@ def test_compression_pass_on_random_shape(case):
     base = dg.CONFIGS["cfg2" if dtype == "bf16" else "cfg1"]
     cfg = dg.scaled(base, head_dim=d, n_kv_heads=hkv, n_q_heads=hkv * g, seq_len=n, window=w, pool_kernel=pool,
                     f_retain=f_r, f_approx=f_a, cal_tokens=512, heavy_frac=0.05)
-    li = dg.make_layer(cfg, i)
+    li = wl.make_layer(cfg, i)
     n_r, n_a, n_p = cfg.counts()
     if n_p < 1:
         n_r, n_a, n_p = 1, 0, 1
@@ -77,7 +79,7 @@ def _decode_shapes():
         dtype = "bf16" if rng.random() < 0.7 else "f32"
         B = int(rng.integers(1, 4))
         hkv = int(rng.integers(1, 5))
-        g = int(rng.choice([1, 2, 4, 8]))
+        g = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8]))
         cap = int(rng.integers(1, 700))
         n_a = int(rng.integers(0, 700))
         out.append((i, dtype, d, B, hkv, g, cap, n_a))
@@ -109,16 +111,10 @@ def test_decode_on_random_shape(case):
     shape = vb.Shape(n_q_heads=hq, n_kv_heads=hkv, head_dim=d, seq_len=max(cap + n_a, 64), window=1, pool_kernel=1,
                      dtype=cache.dtype)
     ws = pl.alloc_workspace(vb.vector_workspace_bytes(shape, cap + n_a, n_a, B))
-    out = torch.empty((B, hq, d), dtype=torch.bfloat16 if is_bf else torch.float32, device="cuda:0")
     scale = 1.0 / np.sqrt(d)
-    vb.vector_decode_attn(cache, t["q"], scale, out, ws)
-    torch.cuda.synchronize()
     ref = vo.decode_attn(dg.widen(q), dg.widen(k_ret), dg.widen(v_ret), lens, dg.widen(k_apx) if n_a else np.zeros((B, hkv, 0, d)),
                          dg.widen(W), scale)
-    got = dg.widen(pl.to_host(out))
-    err = np.abs(got - ref)
-    tol = ATOL + (RTOL + (2.0 ** -8 if is_bf else 0.0)) * np.abs(ref)
-    assert (err <= tol).all(), f"max err {err.max():.3e}"
+    decode_check(cache, t["q"], scale, ws, ref)
 
 
 def _route_cases():
@@ -190,14 +186,10 @@ def test_decode_with_flat_and_peaked_softmax(q_scale):
                                                                       t[2].data_ptr(), t[3].data_ptr())
     shape = vb.Shape(n_q_heads=hkv * g, n_kv_heads=hkv, head_dim=d, seq_len=cap + n_a, window=1, pool_kernel=1, dtype=1)
     ws = pl.alloc_workspace(vb.vector_workspace_bytes(shape, cap + n_a, n_a, B))
-    out = torch.empty((B, hkv * g, d), dtype=torch.bfloat16, device="cuda:0")
     scale = 1.0 / np.sqrt(d)
     ref = vo.decode_attn(dg.widen(q), dg.widen(k_ret), dg.widen(v_ret), lens, dg.widen(k_apx), dg.widen(W), scale)
     for flags in (0, vb.VECTOR_DECODE_LITERAL):
-        vb.vector_decode_attn(cache, t[4], scale, out, ws, flags=flags)
-        torch.cuda.synchronize()
-        err = np.abs(dg.widen(pl.to_host(out)) - ref)
-        assert (err <= ATOL + (RTOL + 2.0 ** -8) * np.abs(ref)).all(), f"flags {flags}: max err {err.max():.3e}"
+        decode_check(cache, t[4], scale, ws, ref, f"flags {flags}", flags=flags)
 
 
 @pytest.mark.parametrize("q_scale", [0.0, 6.0, 40.0])
@@ -205,7 +197,7 @@ def test_score_with_flat_and_peaked_attention(q_scale):
     """q = 0: every window row spreads its mass evenly over what it sees; large q: almost all of a
     row's mass sits on one key, row maxima are far apart and jump between tiles."""
     cfg = dg.scaled(dg.CONFIGS["cfg2"], seq_len=3000, n_kv_heads=2, n_q_heads=8, window=32)
-    li = dg.make_layer(cfg, 1)
+    li = wl.make_layer(cfg, 1)
     q = dg.f32_to_bf16_bits((dg.widen(li.q_win) * q_scale).astype(np.float32))
     shape = pl.shape_of(cfg)
     n_r, n_a, n_p = cfg.counts()

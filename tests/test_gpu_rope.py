@@ -7,7 +7,9 @@ torch = pytest.importorskip("torch")
 from oracle import vector_oracle as vo
 from paper_2605_23258_amd import binding as vb
 from paper_2605_23258_amd import datagen as dg
+import workloads as wl
 from paper_2605_23258_amd import pipeline as pl
+from parity_util import decode_check
 
 pytestmark = pytest.mark.gpu
 ATOL, RTOL = 1e-3, 2e-3
@@ -34,7 +36,7 @@ CASES = {
 def test_residual_and_score_on_rotated_keys(name):
     base, over, interleaved, offset = CASES[name]
     cfg = dg.scaled(dg.CONFIGS[base], **over)
-    li = dg.make_layer(cfg, 0, rope_theta=THETA, rope_interleaved=interleaved, pos_offset=offset)
+    li = wl.make_layer(cfg, 0, rope_theta=THETA, rope_interleaved=interleaved, pos_offset=offset)
     inv_freq = li.extra["inv_freq"]
     H, n, w = cfg.n_kv_heads, cfg.seq_len, cfg.window
     n_r, n_a, n_p = cfg.counts()
@@ -94,15 +96,11 @@ def test_decode_on_rotated_cache(d, B, Hq, Hkv, n_r, n_a, interleaved):
                                                                       t[2].data_ptr(), t[3].data_ptr())
     shape = vb.Shape(n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, seq_len=max(n_r + n_a, 64), window=1, pool_kernel=1, dtype=1)
     ws = pl.alloc_workspace(vb.vector_workspace_bytes(shape, n_r + n_a, n_a, B))
-    out = torch.empty((B, Hq, d), dtype=torch.bfloat16, device="cuda:0")
     scale = 1.0 / np.sqrt(d)
     rope, keep = vb.make_rope(inv_freq, t[5], interleaved, 0)
-    vb.vector_decode_attn_rope(cache, rope, t[4], scale, out, ws)
-    torch.cuda.synchronize()
     ref = vo.decode_attn(dg.widen(q), dg.widen(k_ret), dg.widen(v_ret), np.full(B, n_r), dg.widen(k_apx), dg.widen(W), scale,
                          pos_apx=pos, inv_freq=inv_freq, interleaved=interleaved)
-    err = np.abs(dg.widen(pl.to_host(out)) - ref)
-    assert (err <= ATOL + (RTOL + 2.0 ** -8) * np.abs(ref)).all(), f"max err {err.max():.3e}"
+    decode_check(cache, t[4], scale, ws, ref, "decode (rotary cache)", rope=rope)
     # the plain entry point on the same cache gives something else: the rotation matters here
     out2 = torch.empty_like(out)
     vb.vector_decode_attn(cache, t[4], scale, out2, ws)
@@ -113,7 +111,7 @@ def test_decode_on_rotated_cache(d, B, Hq, Hkv, n_r, n_a, interleaved):
 def test_full_size_layer_and_decode_step():
     """The 32k-token layer and the batch-16 decode shape of the benchmark, read as post-RoPE caches."""
     cfg = dg.CONFIGS["cfg3"]
-    li = dg.make_layer(cfg, 3, rope_theta=THETA)
+    li = wl.make_layer(cfg, 3, rope_theta=THETA)
     inv_freq = li.extra["inv_freq"]
     H, n, d = cfg.n_kv_heads, cfg.seq_len, cfg.head_dim
     n_r, n_a, n_p = cfg.counts()
@@ -141,12 +139,8 @@ def test_full_size_layer_and_decode_step():
     cache.len_retain, cache.k_ret, cache.v_ret, cache.k_apx, cache.W = (length.data_ptr(), t[0].data_ptr(), t[1].data_ptr(),
                                                                       t[2].data_ptr(), dev["w_cal"].data_ptr())
     wsd = pl.alloc_workspace(vb.vector_workspace_bytes(shape, n_p, n_a, B))
-    out = torch.empty((B, Hq, d), dtype=torch.bfloat16, device="cuda:0")
     scale = 1.0 / np.sqrt(d)
     rope_d, keep_d = vb.make_rope(inv_freq, t[4], False, 0)
-    vb.vector_decode_attn_rope(cache, rope_d, t[3], scale, out, wsd)
-    torch.cuda.synchronize()
     ref = vo.decode_attn(dg.widen(q), dg.widen(k_ret), dg.widen(v_ret), np.full(B, n_r), dg.widen(k_apx), dg.widen(li.w_cal), scale,
                          pos_apx=pos, inv_freq=inv_freq)
-    err = np.abs(dg.widen(pl.to_host(out)) - ref)
-    assert (err <= ATOL + (RTOL + 2.0 ** -8) * np.abs(ref)).all(), f"max err {err.max():.3e}"
+    decode_check(cache, t[3], scale, wsd, ref, "decode (rotary cache, full layer)", rope=rope_d)

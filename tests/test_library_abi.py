@@ -40,6 +40,16 @@ def test_budget_helpers_match_oracle():
             assert vb.vector_budget_counts(n, p_c, p_a) == vo.budget_counts(n, p_c, p_a)
 
 
+def test_budget_counts_hand_values():
+    """The library against hand-computed counts, not against the oracle: Section 5's p_c = 0.9,
+    p_a = 0.05 keeps 5 % of the tokens and approximates 10 %."""
+    assert vb.vector_budget_counts(1000, 0.9, 0.05) == (150, 100)
+    assert vb.vector_budget_counts(30000, 0.9, 0.05) == (4500, 3000)
+    assert vb.vector_budget_counts(1000, 0.8, 0.1) == (300, 200)
+    assert vb.vector_budget_counts(1001, 0.9, 0.05) == (150, 100)
+    assert vb.vector_budget_counts_frac(10, 0.29, 0.0) == (2, 0)
+
+
 def test_bad_arguments_are_rejected_on_the_host():
     with pytest.raises(vb.VectorError):
         vb.vector_budget_counts_frac(100, 0.8, 0.5)

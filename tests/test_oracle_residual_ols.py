@@ -5,6 +5,7 @@ import pytest
 
 from oracle import vector_oracle as vo
 from paper_2605_23258_amd import datagen as dg
+import workloads as wl
 
 
 def _rand(seed, *shape):
@@ -93,12 +94,12 @@ def test_generator_calibration_agrees_with_oracle_fit():
     cfg = dg.scaled(dg.CONFIGS["cfg1"], seq_len=256, cal_tokens=1024)
     w_true = np.random.default_rng(0).standard_normal((1, 64, 64)) / 8
     k_cal, v_cal, _, _ = dg._draw_kv(cfg, 0, cfg.cal_tokens, w_true, dg._TAG_CAL)
-    np.testing.assert_allclose(dg.fit_w(k_cal, v_cal), vo.ols_fit(k_cal, v_cal), rtol=0, atol=1e-9)
+    np.testing.assert_allclose(wl.fit_w(k_cal, v_cal), vo.ols_fit(k_cal, v_cal), rtol=0, atol=1e-9)
 
 
 def test_generator_recipe_shapes_and_planted_structure():
     cfg = dg.scaled(dg.CONFIGS["cfg2"], seq_len=512, n_kv_heads=2, n_q_heads=8)
-    li = dg.make_layer(cfg, 0)
+    li = wl.make_layer(cfg, 0)
     assert li.k.dtype == np.uint16 and li.k.shape == (2, 512, 128)
     assert li.q_win.shape == (8, 32, 128) and li.w_cal.shape == (2, 128, 128)
     k, v = dg.widen(li.k), dg.widen(li.v)
@@ -110,9 +111,9 @@ def test_generator_recipe_shapes_and_planted_structure():
     norms = np.linalg.norm(k, axis=-1)
     assert norms[li.heavy].mean() / norms[~li.heavy].mean() == pytest.approx(4.0, rel=0.05)
     # regenerating gives identical bits
-    li2 = dg.make_layer(cfg, 0)
+    li2 = wl.make_layer(cfg, 0)
     assert np.array_equal(li.k, li2.k) and np.array_equal(li.w_cal, li2.w_cal)
-    assert not np.array_equal(li.k, dg.make_layer(cfg, 1).k)
+    assert not np.array_equal(li.k, wl.make_layer(cfg, 1).k)
 
 
 def test_bf16_round_to_nearest_even():
