@@ -296,6 +296,12 @@ VECTOR_API int vector_distortion(const vector_shape* shape, const float* weights
 VECTOR_API int vector_probe_residual_mfma(const vector_shape* shape, const void* k, const void* v, const void* W,
                                float* eps, int32_t repeat, void* stream);
 
+/* Diagnostic: the matrix-core ceiling as measured on this chip.  Launches 256 workgroups of 16 waves
+ * that each run `iters` rounds of four independent 32x32x16 bf16 MFMAs on register operands, and
+ * writes the flop count of the launch to *flops (host).  out: device fp32 [262144] (a sink that
+ * keeps the loop alive; its contents mean nothing).  Time the launch on `stream` to get FLOP/s. */
+VECTOR_API int vector_probe_mfma_loop(float* out, int32_t iters, int64_t* flops, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,7 @@ EXPORTS = (
     "vector_strerror", "vector_score", "vector_residual", "vector_score_residual", "vector_route",
     "vector_compact", "vector_decode_attn", "vector_compress_workspace_bytes", "vector_compress",
     "vector_timing_enable", "vector_timing_kernels", "vector_timing_name", "vector_timing_read",
-    "vector_probe_residual_mfma",
+    "vector_probe_residual_mfma", "vector_probe_mfma_loop",
     "vector_residual_rope", "vector_score_residual_rope", "vector_decode_attn_rope",
     "vector_calibrate_workspace_bytes", "vector_calibrate",
     "vector_distortion_workspace_bytes", "vector_distortion",
@@ -106,6 +106,7 @@ def lib() -> C.CDLL:
         L.vector_timing_name.restype = C.c_char_p
         L.vector_timing_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         L.vector_probe_residual_mfma.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, i32, vp]
+        L.vector_probe_mfma_loop.argtypes = [vp, i32, C.POINTER(C.c_int64), vp]
         L.vector_calibrate_workspace_bytes.argtypes = [C.POINTER(Shape)]
         L.vector_calibrate_workspace_bytes.restype = sz
         L.vector_calibrate.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, sz, vp]
@@ -227,6 +228,13 @@ def vector_timing_read() -> dict:
 def vector_probe_residual_mfma(shape: Shape, k, v, W, eps, repeat: int, stream=None) -> None:
     _check(lib().vector_probe_residual_mfma(C.byref(shape), _ptr(k), _ptr(v), _ptr(W), _ptr(eps), repeat,
                                             _stream(stream)), "vector_probe_residual_mfma")
+
+
+def vector_probe_mfma_loop(out, iters: int, stream=None) -> int:
+    """Launch the register-only MFMA loop; returns the flops of the launch."""
+    flops = C.c_int64()
+    _check(lib().vector_probe_mfma_loop(_ptr(out), iters, C.byref(flops), _stream(stream)), "vector_probe_mfma_loop")
+    return flops.value
 
 
 def vector_residual_rope(shape: Shape, k, v, W, rope: Rope, eps, ws=None, stream=None) -> None:

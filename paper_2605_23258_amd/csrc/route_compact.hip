@@ -28,6 +28,16 @@
 #include "common.hpp"
 #include "launch.hpp"
 
+#ifdef VEC_ROUTE_TRACE
+__device__ long long g_route_trace[32];
+#define VEC_TRACE(slot) do { if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) g_route_trace[slot] = wall_clock64(); } while (0)
+extern "C" __attribute__((visibility("default"))) int vector_debug_route_trace(long long* host_out) {
+  return hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_route_trace), sizeof(long long) * 32) == hipSuccess ? 0 : -5;
+}
+#else
+#define VEC_TRACE(slot) do { } while (0)
+#endif
+
 namespace vec {
 
 namespace {
@@ -38,7 +48,7 @@ constexpr int EPT = 4;            // consecutive elements per thread and tile (o
 constexpr int kTile = RT * EPT;   // elements per tile of a selecting workgroup
 constexpr int kBatch = 8;         // tiles whose loads are in flight together
 constexpr int kBins = 2048;
-constexpr int kCandCap = 16384;   // candidates (keys sharing the chosen leading digit) kept in LDS
+constexpr int kCandCap = 12288;   // candidates (keys sharing the chosen leading digit) kept in LDS, a 16th per wave
 constexpr int HT = 512;           // threads of the histogram kernel
 constexpr int kHistTile = HT * EPT;
 constexpr int kMinChunk = 2048;   // tokens per chunk: doubled until a head has at most kMaxChunks
@@ -193,40 +203,84 @@ __global__ __launch_bounds__(HT) void route_hist_kernel(HistParams p) {
 }
 
 // ---------------------------------------------------------------------------
+// prefix sums: inside a wave on the DPP network, across the waves through one LDS row that
+// every thread reads whole (no chain of dependent LDS reads)
+// ---------------------------------------------------------------------------
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ int dpp_take(int v) {   // 0 where no lane feeds this one
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xf, false);
+}
+__device__ __forceinline__ int wave_incl_scan_dpp(int v) {
+  v += dpp_take<0x111, 0xf>(v);      // row_shr:1 .. 8: inclusive scan inside each row of 16 lanes
+  v += dpp_take<0x112, 0xf>(v);
+  v += dpp_take<0x114, 0xf>(v);
+  v += dpp_take<0x118, 0xf>(v);
+  v += dpp_take<0x142, 0xa>(v);      // row_bcast:15 into rows 1 and 3
+  v += dpp_take<0x143, 0xc>(v);      // row_bcast:31 into rows 2 and 3
+  return v;
+}
+__device__ __forceinline__ int wave_total_of_scan(int incl) { return __builtin_amdgcn_readlane(incl, 63); }
+
+// RW per-wave values -> their sum over the waves before `wave`, and over all waves
+__device__ __forceinline__ void wave_row_sums(const int* row, int wave, int& before, int& total) {
+  const int4* r4 = reinterpret_cast<const int4*>(row);
+  before = 0;
+  total = 0;
+#pragma unroll
+  for (int q = 0; q < RW / 4; ++q) {
+    const int4 v = r4[q];
+    const int x[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      total += x[u];
+      before += (q * 4 + u < wave) ? x[u] : 0;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // radix select shared by the two selecting kernels
 // ---------------------------------------------------------------------------
+constexpr int kWaveCand = kCandCap / RW;     // each wave keeps its own candidates: no shared counter
+
+enum { ROW_PICK0 = 0, ROW_PICK1, ROW_PICK2, ROW_GT, ROW_EQ, ROW_EMIT0, ROW_EMIT1, ROW_COUNT };
+
 struct SelectShared {
-  int hist[kBins];
-  int wave_sum[RW];
-  int wave_tot[2][RW];
-  int digit, above, bin_count;
-  int n_cand;
-  int red[2];
+  int hist[3][kBins];                    // digits of levels 1 and 2 of a select, and one for the caller; zeroed at the start
+  __align__(16) int row[ROW_COUNT][RW];  // per-wave terms of the workgroup-wide sums, one row per use
+  int pick[3][4];                        // per level: digit, #(digit above it), count of its bin
+  int overflow;                          // a wave found more candidates than it can keep
 };
+
+__device__ __forceinline__ void select_shared_init(SelectShared& sh) {
+  int* h = &sh.hist[0][0];
+  for (int i = threadIdx.x; i < 3 * kBins; i += RT) h[i] = 0;
+  if (threadIdx.x == 0) sh.overflow = 0;
+}
 
 // The digit d with #(digit > d) < remaining <= #(digit >= d), from per-thread counts of bins
 // kBins-1-2t (c0) and kBins-2-2t (c1); every thread gets d, #(digit > d) and the count of bin d.
-__device__ __forceinline__ void pick_digit(int c0, int c1, int remaining, SelectShared& sh, int& digit, int& above_out, int& count) {
+__device__ __forceinline__ void pick_digit(int c0, int c1, int remaining, SelectShared& sh, int level, int& digit, int& above_out,
+                                           int& count) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int b_hi = kBins - 1 - 2 * (int)threadIdx.x;
   const int tot = c0 + c1;
-  const int incl_w = wave_incl_scan_i(tot, lane);
-  if (lane == 63) sh.wave_sum[wave] = incl_w;
+  const int incl_w = wave_incl_scan_dpp(tot);
+  if (lane == 63) sh.row[ROW_PICK0 + level][wave] = incl_w;
   __syncthreads();
-  int above = incl_w - tot;
-  for (int wv = 0; wv < wave; ++wv) above += sh.wave_sum[wv];
+  int before, total;
+  wave_row_sums(sh.row[ROW_PICK0 + level], wave, before, total);
+  int above = incl_w - tot + before;
   if (above < remaining && remaining <= above + tot) {
     int d = b_hi, cnt = c0;
     if (remaining > above + c0) { above += c0; d = b_hi - 1; cnt = c1; }
-    sh.digit = d;
-    sh.above = above;
-    sh.bin_count = cnt;
+    sh.pick[level][0] = d;
+    sh.pick[level][1] = above;
+    sh.pick[level][2] = cnt;
   }
   __syncthreads();
-  digit = sh.digit;
-  above_out = sh.above;
-  count = sh.bin_count;
-  __syncthreads();                              // sh.digit / above / wave_sum are free again
+  digit = sh.pick[level][0];
+  above_out = sh.pick[level][1];
+  count = sh.pick[level][2];
 }
 
 // The k-th largest (1 <= k <= m) of the m keys that load4 delivers four at a time, given the
@@ -234,18 +288,43 @@ __device__ __forceinline__ void pick_digit(int c0, int c1, int remaining, Select
 // the number of keys equal to it that belong to the k largest (`quota`, taken in index order by
 // the caller), and how many keys at positions below `before` are greater than / equal to the
 // threshold.  load4(i0, key, ok): keys of positions i0 .. i0+3 (i0 a multiple of 4), ok = inside.
-// cand_key / cand_pos: LDS, kCandCap entries each.
+// cand_key / cand_pos: LDS, kCandCap entries each.  select_shared_init must have run (no barrier
+// needed in between: the first pick has two).
+// One trip to memory for the histograms and the first kBatch tiles of keys together; after that
+// the select runs out of registers and LDS.
 template <typename Load4>
 __device__ __forceinline__ void select_threshold(Load4 load4, int m, int k, const uint16_t* part, int n_parts, int before,
                                                  SelectShared& sh, uint32_t* cand_key, int32_t* cand_pos, uint32_t& thr,
-                                                 int& quota, int& base_gt, int& base_eq) {
+                                                 int& quota, int& base_gt, int& base_eq, int trace_base = 0) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  (void)trace_base;
+  VEC_TRACE(trace_base + 0);
+  const int n_tiles = (m + kTile - 1) / kTile;
   // ---- leading digit, from the partial histograms: thread t owns bins 2047-2t and 2046-2t ----
   int c0 = 0, c1 = 0;
+  uint32_t cur[kBatch][EPT];
+  bool cur_ok[kBatch][EPT];
+  auto load_batch = [&](int tb, uint32_t (&key)[kBatch][EPT], bool (&ok)[kBatch][EPT]) {
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      if (tb + u < n_tiles) {
+        load4((tb + u) * kTile + (int)threadIdx.x * EPT, key[u], ok[u]);
+      } else {
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) { key[u][j] = 0u; ok[u][j] = false; }
+      }
+    }
+  };
   {
     const uint32_t* p32 = reinterpret_cast<const uint32_t*>(part) + (kBins / 2 - 1 - (int)threadIdx.x);
-    for (int c = 0; c < n_parts; c += 8) {
-      uint32_t v[8];
+    uint32_t v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = p32[(size_t)min(u, n_parts - 1) * (kBins / 2)];
+    load_batch(0, cur, cur_ok);                  // in flight together with the histograms
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (u < n_parts) { c1 += (int)(v[u] & 0xffffu); c0 += (int)(v[u] >> 16); }
+    for (int c = 8; c < n_parts; c += 8) {
 #pragma unroll
       for (int u = 0; u < 8; ++u) v[u] = p32[(size_t)min(c + u, n_parts - 1) * (kBins / 2)];
 #pragma unroll
@@ -253,18 +332,63 @@ __device__ __forceinline__ void select_threshold(Load4 load4, int m, int k, cons
         if (c + u < n_parts) { c1 += (int)(v[u] & 0xffffu); c0 += (int)(v[u] >> 16); }
     }
   }
-  if (threadIdx.x == 0) sh.n_cand = 0;
+  VEC_TRACE(trace_base + 1);
   int d0, above0, m0;
-  pick_digit(c0, c1, k, sh, d0, above0, m0);      // its barriers also publish n_cand = 0
+  pick_digit(c0, c1, k, sh, 0, d0, above0, m0);
   int remaining = k - above0;
-  const bool use_list = m0 <= kCandCap;
-  const int n_tiles = (m + kTile - 1) / kTile;
+  VEC_TRACE(trace_base + 2);
 
-  // visit every key whose leading digit is d0: f(key, position)
+  // ---- all keys once: candidates (leading digit d0) into this wave's list and into the
+  //      histogram of the second digit; earlier keys above the digit counted ----
+  int gt = 0, n_mine = 0;
+  uint32_t* my_key = cand_key + wave * kWaveCand;
+  int32_t* my_pos = cand_pos + wave * kWaveCand;
+  auto scan_batch = [&](int tb, const uint32_t (&key)[kBatch][EPT], const bool (&ok)[kBatch][EPT]) {
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      if (tb + u < n_tiles) {                    // uniform
+        const int i0 = (tb + u) * kTile + (int)threadIdx.x * EPT;
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) {
+          const int dg = (int)(key[u][j] >> 21);
+          gt += ok[u][j] && i0 + j < before && dg > d0;
+          const bool is_c = ok[u][j] && dg == d0;
+          const unsigned long long b = __ballot(is_c);
+          if (b) {
+            if (is_c) {
+              const int pos = n_mine + __popcll(b & ((1ull << lane) - 1ull));
+              if (pos < kWaveCand) { my_key[pos] = key[u][j]; my_pos[pos] = i0 + j; }
+              atomicAdd(&sh.hist[0][(key[u][j] >> 10) & 2047u], 1);
+            }
+            n_mine += __popcll(b);
+          }
+        }
+      }
+    }
+  };
+  for (int tb = 0; tb < n_tiles; tb += kBatch) {
+    uint32_t nxt[kBatch][EPT];
+    bool nxt_ok[kBatch][EPT];
+    const bool more = tb + kBatch < n_tiles;
+    if (more) load_batch(tb + kBatch, nxt, nxt_ok);      // requested before this batch is worked on
+    scan_batch(tb, cur, cur_ok);
+    if (more) {
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u)
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) { cur[u][j] = nxt[u][j]; cur_ok[u][j] = nxt_ok[u][j]; }
+    }
+  }
+  if (n_mine > kWaveCand && lane == 0) sh.overflow = 1;
+  __syncthreads();
+  VEC_TRACE(trace_base + 3);
+  const bool use_list = sh.overflow == 0;
+  const int n_list = min(n_mine, kWaveCand);
+
+  // visit every key whose leading digit is d0 (each wave its own): f(key, position)
   auto for_each_candidate = [&](auto f) {
     if (use_list) {
-      const int nc = sh.n_cand;
-      for (int i = threadIdx.x; i < nc; i += RT) f(cand_key[i], cand_pos[i]);
+      for (int i = lane; i < n_list; i += kWave) f(my_key[i], my_pos[i]);
     } else {
       for (int t = 0; t < n_tiles; ++t) {
         uint32_t key[EPT];
@@ -278,87 +402,38 @@ __device__ __forceinline__ void select_threshold(Load4 load4, int m, int k, cons
     }
   };
 
-  // ---- one pass over all keys: candidates into LDS, earlier keys above the digit counted ----
-  int gt = 0;
-  for (int tb = 0; tb < n_tiles; tb += kBatch) {
-    uint32_t key[kBatch][EPT];
-    bool ok[kBatch][EPT];
-#pragma unroll
-    for (int u = 0; u < kBatch; ++u) {
-      const int i0 = (tb + u) * kTile + (int)threadIdx.x * EPT;
-      if (tb + u < n_tiles) {
-        load4(i0, key[u], ok[u]);
-      } else {
-#pragma unroll
-        for (int j = 0; j < EPT; ++j) { key[u][j] = 0u; ok[u][j] = false; }
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < kBatch; ++u) {
-      if (tb + u < n_tiles) {                    // uniform
-        const int i0 = (tb + u) * kTile + (int)threadIdx.x * EPT;
-#pragma unroll
-        for (int j = 0; j < EPT; ++j) {
-          const int dg = (int)(key[u][j] >> 21);
-          gt += ok[u][j] && i0 + j < before && dg > d0;
-          if (use_list) {
-            const bool is_c = ok[u][j] && dg == d0;
-            const unsigned long long b = __ballot(is_c);
-            if (b) {
-              int base = 0;
-              if (lane == 0) base = atomicAdd(&sh.n_cand, __popcll(b));
-              base = __builtin_amdgcn_readfirstlane(base);
-              const int pos = base + __popcll(b & ((1ull << lane) - 1ull));
-              if (is_c && pos < kCandCap) { cand_key[pos] = key[u][j]; cand_pos[pos] = i0 + j; }
-            }
-          }
-        }
-      }
-    }
-  }
+  // ---- second digit: its histogram was filled during the scan ----
+  const int b_hi = kBins - 1 - 2 * (int)threadIdx.x;
+  int d1, above1, m1;
+  pick_digit(sh.hist[0][b_hi], sh.hist[0][b_hi - 1], remaining, sh, 1, d1, above1, m1);
+  remaining -= above1;
+  const uint32_t prefix22 = (((uint32_t)d0) << 21) | (((uint32_t)d1) << 10);
+  // ---- third digit ----
+  for_each_candidate([&](uint32_t key, int) {
+    if ((key >> 10) == (prefix22 >> 10)) atomicAdd(&sh.hist[1][key & 1023u], 1);
+  });
   __syncthreads();
-
-  // ---- the two lower digits, on the candidates ----
-  uint32_t prefix = ((uint32_t)d0) << 21, mask = 2047u << 21;
-#pragma unroll 1
-  for (int level = 1; level <= 2; ++level) {
-    for (int i = threadIdx.x; i < kBins; i += RT) sh.hist[i] = 0;
-    __syncthreads();
-    const int shift = level_shift(level);
-    const uint32_t dmask = level_mask(level);
-    for_each_candidate([&](uint32_t key, int) {
-      if ((key & mask) == prefix) atomicAdd(&sh.hist[(key >> shift) & dmask], 1);
-    });
-    __syncthreads();
-    const int b_hi = kBins - 1 - 2 * (int)threadIdx.x;
-    int d, above, cnt;
-    pick_digit(sh.hist[b_hi], sh.hist[b_hi - 1], remaining, sh, d, above, cnt);
-    prefix |= ((uint32_t)d) << shift;
-    mask |= dmask << shift;
-    remaining -= above;
-  }
-  thr = prefix;
+  int d2, above2, m2;
+  pick_digit(sh.hist[1][b_hi], sh.hist[1][b_hi - 1], remaining, sh, 2, d2, above2, m2);
+  remaining -= above2;
+  thr = prefix22 | (uint32_t)d2;
   quota = remaining;
+  VEC_TRACE(trace_base + 4);
 
   // ---- keys before `before`: above the threshold, equal to it ----
   int eq = 0;
+  const uint32_t t_key = thr;
   for_each_candidate([&](uint32_t key, int pos) {
-    if (pos < before) { gt += key > prefix; eq += key == prefix; }
+    if (pos < before) { gt += key > t_key; eq += key == t_key; }
   });
-  gt = wave_sum_i(gt);
-  eq = wave_sum_i(eq);
-  if (lane == 0) { sh.wave_tot[0][wave] = gt; sh.wave_tot[1][wave] = eq; }
+  gt = wave_total_of_scan(wave_incl_scan_dpp(gt));
+  eq = wave_total_of_scan(wave_incl_scan_dpp(eq));
+  if (lane == 0) { sh.row[ROW_GT][wave] = gt; sh.row[ROW_EQ][wave] = eq; }
   __syncthreads();
-  if (threadIdx.x == 0) {
-    int a = 0, b = 0;
-    for (int wv = 0; wv < RW; ++wv) { a += sh.wave_tot[0][wv]; b += sh.wave_tot[1][wv]; }
-    sh.red[0] = a;
-    sh.red[1] = b;
-  }
-  __syncthreads();
-  base_gt = sh.red[0];
-  base_eq = sh.red[1];
-  __syncthreads();
+  int unused;
+  wave_row_sums(sh.row[ROW_GT], RW, unused, base_gt);
+  wave_row_sums(sh.row[ROW_EQ], RW, unused, base_eq);
+  VEC_TRACE(trace_base + 5);
 }
 
 // Ordered pass over positions [begin, end) in tiles of kTile: a thread's EPT consecutive
@@ -378,15 +453,12 @@ __device__ __forceinline__ void ordered_emit(ClsFn load_cls, EmitFn emit, int be
     int packed = 0;
 #pragma unroll
     for (int j = 0; j < EPT; ++j) packed += (cls[j] == 2 ? 0x10000 : 0) + (cls[j] == 1 ? 1 : 0);
-    const int incl = wave_incl_scan_i(packed, lane);
-    if (lane == 63) sh.wave_tot[buf][wave] = incl;
+    const int incl = wave_incl_scan_dpp(packed);
+    if (lane == 63) sh.row[ROW_EMIT0 + buf][wave] = incl;
     __syncthreads();
-    int pre = incl - packed, tile_tot = 0;
-    for (int wv = 0; wv < RW; ++wv) {
-      const int t = sh.wave_tot[buf][wv];
-      if (wv < wave) pre += t;
-      tile_tot += t;
-    }
+    int pre, tile_tot;
+    wave_row_sums(sh.row[ROW_EMIT0 + buf], wave, pre, tile_tot);
+    pre += incl - packed;
     int pre_gt = carry_gt + (pre >> 16), pre_eq = carry_eq + (pre & 0xffff);
     carry_gt += tile_tot >> 16;
     carry_eq += tile_tot & 0xffff;
@@ -422,10 +494,10 @@ __global__ __launch_bounds__(RT) void route_pool_kernel(RouteParams p) {
   uint32_t* cand_key = reinterpret_cast<uint32_t*>(dyn_lds);
   int32_t* cand_pos = reinterpret_cast<int32_t*>(dyn_lds) + kCandCap;
   const int h = blockIdx.y, chunk = blockIdx.x;
-  const int lane = threadIdx.x & 63;
   const float* sc = p.score + (size_t)h * p.n;
   const float* ep = p.eps + (size_t)h * p.n;
   const int n = p.n;
+  select_shared_init(sh);
   const bool vec4 = (n & 3) == 0 && ((reinterpret_cast<uintptr_t>(sc) | reinterpret_cast<uintptr_t>(ep)) & 15u) == 0;
   auto load_f4 = [&](const float* a, int i0, float (&x)[EPT]) {
     if (vec4 && i0 + EPT <= n) {
@@ -443,29 +515,35 @@ __global__ __launch_bounds__(RT) void route_pool_kernel(RouteParams p) {
     for (int j = 0; j < EPT; ++j) { ok[j] = i0 + j < n; key[j] = ok[j] ? float_key(x[j]) : 0u; }
   };
   const int begin = chunk * p.chunk_tokens, end = min(n, begin + p.chunk_tokens);
+  // this thread's tokens of the chunk's first tile: requested now, used by the ordered pass
+  const int first_i0 = begin + (int)threadIdx.x * EPT;
+  float sc0[EPT], ep0[EPT];
+  load_f4(sc, first_i0, sc0);
+  load_f4(ep, first_i0, ep0);
   uint32_t thr;
   int quota, base_gt, base_eq;
   select_threshold(load4, n, p.n_pool, p.part0 + (size_t)h * p.n_chunks * kBins, p.n_chunks, begin, sh, cand_key, cand_pos, thr,
-                   quota, base_gt, base_eq);
+                   quota, base_gt, base_eq, 0);
 
   // ordered pass over the chunk: tiers, pool list, leading digits of the residual keys
-  for (int i = threadIdx.x; i < kBins; i += RT) sh.hist[i] = 0;
-  __syncthreads();
   uint8_t* tr = p.tier + (size_t)h * n;
   int32_t* pidx = p.pool_idx + (size_t)h * p.pool_stride;
   uint32_t* pkey = p.pool_key + (size_t)h * p.pool_stride;
   uint32_t ekey[EPT];
   ordered_emit(
       [&](int i0, int (&cls)[EPT]) {
-        uint32_t key[EPT];
-        bool ok[EPT];
-        float e[EPT];
-        load4(i0, key, ok);
-        load_f4(ep, i0, e);
+        float x[EPT], e[EPT];
+        if (i0 == first_i0) {
+#pragma unroll
+          for (int j = 0; j < EPT; ++j) { x[j] = sc0[j]; e[j] = ep0[j]; }
+        } else {
+          load_f4(sc, i0, x);
+          load_f4(ep, i0, e);
+        }
 #pragma unroll
         for (int j = 0; j < EPT; ++j) {
-          ok[j] = ok[j] && i0 + j < end;
-          cls[j] = ok[j] ? (key[j] > thr ? 2 : (key[j] == thr ? 1 : 0)) : 0;
+          const uint32_t key = float_key(x[j]);
+          cls[j] = i0 + j < end ? (key > thr ? 2 : (key == thr ? 1 : 0)) : 0;
           ekey[j] = ~float_key(e[j]);               // smaller residual, larger key
         }
       },
@@ -475,13 +553,14 @@ __global__ __launch_bounds__(RT) void route_pool_kernel(RouteParams p) {
           const uint32_t ek = ekey[i & (EPT - 1)];   // tiles start at multiples of EPT
           pidx[rank] = i;
           pkey[rank] = ek;
-          atomicAdd(&sh.hist[ek >> 21], 1);
+          atomicAdd(&sh.hist[2][ek >> 21], 1);
         }
       },
       begin, end, base_gt, base_eq, quota, sh);
-  (void)lane;
+  VEC_TRACE(6);
   __syncthreads();
-  store_partial<RT>(p.part1 + ((size_t)h * p.n_chunks + chunk) * kBins, sh.hist);
+  store_partial<RT>(p.part1 + ((size_t)h * p.n_chunks + chunk) * kBins, sh.hist[2]);
+  VEC_TRACE(7);
 }
 
 // Step 3: inside the pool, the n_approx tokens of lowest residual lose their value
@@ -502,36 +581,46 @@ __global__ __launch_bounds__(RT) void route_split_kernel(RouteParams p) {
     for (int i = begin + (int)threadIdx.x; i < end; i += RT) ir[i] = pidx[i];
     return;
   }
-  auto load4 = [&](int i0, uint32_t (&key)[EPT], bool (&ok)[EPT]) {
+  select_shared_init(sh);
+  auto load_u4 = [&](const uint32_t* a, int i0, uint32_t (&x)[EPT]) {
     if (i0 + EPT <= m) {                             // lists start at 16-byte boundaries
-      const uint4 v = *reinterpret_cast<const uint4*>(pkey + i0);
-      key[0] = v.x; key[1] = v.y; key[2] = v.z; key[3] = v.w;
-#pragma unroll
-      for (int j = 0; j < EPT; ++j) ok[j] = true;
+      const uint4 v = *reinterpret_cast<const uint4*>(a + i0);
+      x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
     } else {
 #pragma unroll
-      for (int j = 0; j < EPT; ++j) { ok[j] = i0 + j < m; key[j] = ok[j] ? pkey[i0 + j] : 0u; }
+      for (int j = 0; j < EPT; ++j) x[j] = i0 + j < m ? a[i0 + j] : 0u;
     }
   };
+  auto load4 = [&](int i0, uint32_t (&key)[EPT], bool (&ok)[EPT]) {
+    load_u4(pkey, i0, key);
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) ok[j] = i0 + j < m;
+  };
+  // this thread's entries of the slice's first tile: requested now, used by the ordered pass
+  const int first_i0 = begin + (int)threadIdx.x * EPT;
+  uint32_t key0[EPT], tok0[EPT];
+  load_u4(pkey, first_i0, key0);
+  load_u4(reinterpret_cast<const uint32_t*>(pidx), first_i0, tok0);
   uint32_t thr;
   int quota, base_gt, base_eq;
   select_threshold(load4, m, p.n_approx, p.part1 + (size_t)h * p.n_chunks * kBins, p.n_chunks, begin, sh, cand_key, cand_pos, thr,
-                   quota, base_gt, base_eq);
-  int tok[EPT];
+                   quota, base_gt, base_eq, 16);
+  uint32_t tok[EPT];
   ordered_emit(
       [&](int i0, int (&cls)[EPT]) {
         uint32_t key[EPT];
-        bool ok[EPT];
-        load4(i0, key, ok);
+        if (i0 == first_i0) {
 #pragma unroll
-        for (int j = 0; j < EPT; ++j) {
-          ok[j] = ok[j] && i0 + j < end;
-          cls[j] = ok[j] ? (key[j] > thr ? 2 : (key[j] == thr ? 1 : 0)) : 0;
-          tok[j] = ok[j] ? pidx[i0 + j] : 0;
+          for (int j = 0; j < EPT; ++j) { key[j] = key0[j]; tok[j] = tok0[j]; }
+        } else {
+          load_u4(pkey, i0, key);
+          load_u4(reinterpret_cast<const uint32_t*>(pidx), i0, tok);
         }
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) cls[j] = i0 + j < end ? (key[j] > thr ? 2 : (key[j] == thr ? 1 : 0)) : 0;
       },
       [&](int i, bool sel, int rank) {
-        const int t = tok[i & (EPT - 1)];
+        const int t = (int)tok[i & (EPT - 1)];
         if (sel) {
           if (rank < p.n_approx) {
             ia[rank] = t;
@@ -542,6 +631,7 @@ __global__ __launch_bounds__(RT) void route_split_kernel(RouteParams p) {
         }
       },
       begin, end, base_gt, base_eq, quota, sh);
+  VEC_TRACE(16 + 6);
 }
 
 // nothing is kept: every token is evicted

@@ -75,3 +75,45 @@ int vector_timing_read(int kernel_id, double* total_ms, int64_t* launches) {
 }
 
 }  // extern "C"
+
+// ---------------------------------------------------------------------------
+// Measured matrix-core ceiling: every wave runs `iters` rounds of four independent
+// v_mfma_f32_32x32x16_bf16 on operands in registers (no memory traffic in the loop).
+// 256 workgroups of 1024 threads: four waves per SIMD on every CU.
+// ---------------------------------------------------------------------------
+namespace vec {
+namespace {
+typedef __attribute__((ext_vector_type(8))) __bf16 probe_bf16x8;
+typedef __attribute__((ext_vector_type(16))) float probe_f32x16;
+constexpr int kMfmaProbeGrid = 256, kMfmaProbeThreads = 1024;
+
+__global__ __launch_bounds__(kMfmaProbeThreads) void mfma_loop_kernel(float* out, int iters) {
+  probe_f32x16 a0 = {0}, a1 = {0}, a2 = {0}, a3 = {0};
+  probe_bf16x8 a, b;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) { a[i] = (__bf16)(float)(threadIdx.x & 3); b[i] = (__bf16)1.0f; }
+  for (int it = 0; it < iters; ++it) {
+    a0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, a0, 0, 0, 0);
+    a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, a1, 0, 0, 0);
+    a2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, a2, 0, 0, 0);
+    a3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, a3, 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) s += a0[i] + a1[i] + a2[i] + a3[i];
+  out[(size_t)blockIdx.x * kMfmaProbeThreads + threadIdx.x] = s;
+}
+}  // namespace
+}  // namespace vec
+
+extern "C" {
+
+int vector_probe_mfma_loop(float* out, int32_t iters, int64_t* flops, void* stream) {
+  if (!out || iters < 1 || !flops) return VECTOR_ERR_ARG;
+  hipLaunchKernelGGL(vec::mfma_loop_kernel, dim3(vec::kMfmaProbeGrid), dim3(vec::kMfmaProbeThreads), 0, (hipStream_t)stream, out, iters);
+  if (hipGetLastError() != hipSuccess) return VECTOR_ERR_HIP;
+  *flops = (int64_t)vec::kMfmaProbeGrid * (vec::kMfmaProbeThreads / 64) * iters * 4 * (2LL * 32 * 32 * 16);
+  return VECTOR_OK;
+}
+
+}  // extern "C"

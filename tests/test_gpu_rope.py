@@ -102,7 +102,7 @@ def test_decode_on_rotated_cache(d, B, Hq, Hkv, n_r, n_a, interleaved):
                          pos_apx=pos, inv_freq=inv_freq, interleaved=interleaved)
     decode_check(cache, t[4], scale, ws, ref, "decode (rotary cache)", rope=rope)
     # the plain entry point on the same cache gives something else: the rotation matters here
-    out2 = torch.empty_like(out)
+    out2 = torch.empty((B, Hq, d), dtype=torch.bfloat16, device="cuda:0")
     vb.vector_decode_attn(cache, t[4], scale, out2, ws)
     torch.cuda.synchronize()
     assert np.abs(dg.widen(pl.to_host(out2)) - ref).max() > 10 * ATOL
