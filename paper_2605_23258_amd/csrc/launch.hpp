@@ -42,7 +42,7 @@ size_t score_workspace_bytes(const vector_shape& s);
 struct RopeParams;
 int launch_score_residual(const vector_shape& s, const void* q, const void* k, const void* v, const void* W,
                           float* score, float* eps, void* ws, hipStream_t stream, const RopeParams* rope = nullptr,
-                          uint16_t* score_hist = nullptr);
+                          void* route_ws = nullptr);
 
 int launch_residual_probe(const vector_shape& s, const void* k, const void* v, const void* W, float* eps, int repeat,
                           hipStream_t stream);
@@ -60,16 +60,15 @@ int launch_r2(const vector_shape& s, const float* eps, const void* v, double* ou
 size_t diversity_workspace_bytes(const vector_shape& s);
 int launch_key_diversity(const vector_shape& s, const void* k, float* score, void* ws, hipStream_t stream);
 
-constexpr int kRouteMaxSeqLen = 1 << 20;      // chunk histograms carry 16-bit counts: at most 32 chunks of 32768 tokens
+constexpr int kRouteMaxSeqLen = 1 << 20;      // per-chunk digit tables carry 16-bit counts: at most 32 chunks of 32768 tokens
 size_t route_workspace_bytes(int n_kv_heads, int seq_len, int n_pool);
-// where, inside a routing workspace, the leading-digit histograms of the score keys live
-uint16_t* route_score_hist(void* route_ws);
-// average pooling of the attention mass into the score; with score_hist also the routing's first
-// histogram (then launch_route is told so and skips its own histogram launch)
+// average pooling of the attention mass into the score; with a routing workspace (route_ws, sized by
+// route_workspace_bytes) also the routing's buckets of score keys (then launch_route is told so and
+// skips its own bucket launch)
 int launch_pool_scores(const float* mass, float* score, int n_kv_heads, int seq_len, int n_prefix, int pool_kernel,
-                       uint16_t* score_hist, hipStream_t stream);
+                       void* route_ws, hipStream_t stream);
 int launch_route(int n_kv_heads, int seq_len, const float* score, const float* eps, int n_pool, int n_approx,
-                 uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx, void* ws, bool have_score_hist, hipStream_t stream);
+                 uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx, void* ws, bool have_buckets, hipStream_t stream);
 
 int launch_compact(const vector_shape& s, const void* k, const void* v, const int32_t* idx_retain,
                    const int32_t* idx_approx, int n_retain, int n_approx, void* k_ret, void* v_ret, void* k_apx,

@@ -4,31 +4,33 @@
 // residuals) are radix selects on order-preserving 32-bit keys with digits of 11, 11 and 10 bits,
 // spread over the whole chip and synchronised by kernel boundaries only:
 //
-//   route_hist_kernel    grid (chunk, head).  Histogram of the leading digit of a chunk's score
-//                        keys -> one partial histogram per chunk (16-bit counts, plain stores).
-//                        The POOL variant first forms the score itself, the average pooling of the
+//   route_bucket_kernel  grid (chunk, head).  Counts the leading digit of a chunk's score keys and
+//                        writes the chunk's (key, token) pairs grouped by that digit, highest digit
+//                        first, next to the table D[b] = #keys of the chunk with digit >= b.  The
+//                        POOL variant first forms the score itself, the average pooling of the
 //                        attention mass (Step 1's base scorer), so the scorer's last kernel already
-//                        hands the routing its first histogram.
-//   route_pool_kernel    grid (chunk, head).  Every workgroup sums the partial histograms of its
-//                        head, picks the leading digit, reads all score keys of the head once,
-//                        keeps those with that digit in LDS and finishes the select on them (all
-//                        workgroups of a head reach the same threshold).  It then makes the
-//                        ordered pass over its own chunk: tiers, the pool list (token index and
-//                        residual key, in token order) and the leading-digit histogram of the
-//                        chunk's residual keys.
+//                        hands the routing its buckets.
+//   route_pool_kernel    grid (chunk, head).  Every workgroup sums the D tables of its head: the
+//                        leading digit of the threshold is the bin where the sum crosses n_pool,
+//                        and the keys that share it are one contiguous piece of every chunk's
+//                        bucket list.  Those few keys go to LDS and the select finishes on them (all
+//                        workgroups of a head reach the same threshold).  Then the ordered pass
+//                        over the workgroup's own chunk: tiers, the pool list (token index and
+//                        residual key, in token order) and the D table of the chunk's residual keys.
 //   route_split_kernel   grid (slice, head).  The same select on the residual keys of the pool
-//                        list, then the ordered pass over a slice of the list: ascending
-//                        idx_approx / idx_retain, and the approximated tier.
+//                        list (read whole: a pool is a fraction of the sequence), then the ordered
+//                        pass over a slice of the list: ascending idx_approx / idx_retain, and the
+//                        approximated tier.
 //
-// Every slot comes from an ordered prefix sum (ties go to the lower token index); atomics only
-// feed LDS histograms and the unordered candidate list of a select, so the result does not depend
-// on scheduling.  No workgroup waits for another inside a kernel.
+// Every slot of an output comes from an ordered prefix sum (ties go to the lower token index);
+// atomics only feed LDS histograms and the order inside a bucket, which no result depends on.
+// No workgroup waits for another inside a kernel.
 //
 // gather_rows_kernel: row gather k_ret / v_ret / k_apx by the index lists.
 #include "common.hpp"
 #include "launch.hpp"
 
-#ifdef VEC_ROUTE_TRACE
+#ifdef VEC_ROUTE_TRACE      // tuning builds only: time stamps of workgroup (0, 0)
 __device__ long long g_route_trace[32];
 #define VEC_TRACE(slot) do { if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) g_route_trace[slot] = wall_clock64(); } while (0)
 extern "C" __attribute__((visibility("default"))) int vector_debug_route_trace(long long* host_out) {
@@ -42,16 +44,18 @@ namespace vec {
 
 namespace {
 
-constexpr int RT = 1024;          // threads per selecting workgroup
-constexpr int RW = RT / kWave;    // waves
-constexpr int EPT = 4;            // consecutive elements per thread and tile (one 16-byte load)
-constexpr int kTile = RT * EPT;   // elements per tile of a selecting workgroup
-constexpr int kBatch = 8;         // tiles whose loads are in flight together
 constexpr int kBins = 2048;
-constexpr int kCandCap = 12288;   // candidates (keys sharing the chosen leading digit) kept in LDS, a 16th per wave
-constexpr int HT = 512;           // threads of the histogram kernel
-constexpr int kHistTile = HT * EPT;
-constexpr int kMinChunk = 2048;   // tokens per chunk: doubled until a head has at most kMaxChunks
+constexpr int kTableStride = kBins + 8;   // 16-bit entries of a D table: D[0 .. 2048] and padding to 16 bytes
+constexpr int EPT = 4;                    // consecutive elements per thread and tile (one 16-byte load)
+constexpr int BT = 512;                   // threads of the bucket kernel
+constexpr int kBucketTile = BT * EPT;
+constexpr int ST = 256;                   // threads of a selecting workgroup: one wave per SIMD
+constexpr int SW = ST / kWave;
+constexpr int kTile = ST * EPT;           // elements per tile of a selecting workgroup
+constexpr int kBatch = 8;                 // tiles whose loads are in flight together
+constexpr int kCandCap = 12288;           // candidates (keys sharing the threshold's leading digit) kept in LDS
+constexpr int kWaveCand = kCandCap / SW;  // each wave keeps its own: no shared counter
+constexpr int kMinChunk = 2048;           // tokens per chunk: doubled until a head has at most kMaxChunks
 constexpr int kMaxChunks = 32;
 
 // Order-preserving map float -> u32 (larger float, larger key); -0 and +0 share a key.
@@ -60,31 +64,10 @@ __device__ __forceinline__ uint32_t float_key(float x) {
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
-__device__ __forceinline__ int level_shift(int level) { return level == 0 ? 21 : (level == 1 ? 10 : 0); }
-__device__ __forceinline__ uint32_t level_mask(int level) { return level == 2 ? 1023u : 2047u; }
-
-// hist[digit] += 1 for every active lane.  Keys of neighbouring tokens often share their
-// leading bits, so a plain LDS atomic would serialise up to 64 lanes on one bin: lanes that
-// agree with a leader are counted with one ballot and added by the leader alone; after two
-// rounds the stragglers (few, spread over bins) add themselves.
-__device__ __forceinline__ void hist_add_aggregated(int* hist, uint32_t digit, bool active, int lane) {
-  unsigned long long todo = __ballot(active);
-#pragma unroll
-  for (int round = 0; round < 2; ++round) {
-    if (todo == 0) return;
-    const int leader = __ffsll((long long)todo) - 1;
-    const uint32_t d = __builtin_amdgcn_readlane(digit, leader);
-    const bool match = active && digit == d;
-    const unsigned long long m = __ballot(match);
-    if (lane == leader) atomicAdd(&hist[d], __popcll(m));
-    active = active && !match;
-    todo &= ~m;
-  }
-  if (active) atomicAdd(&hist[digit], 1);
-}
-
-// hist[digit] += cnt (cnt in 0..7) for every lane, lanes that agree with a leader merged
-// through ballots of the three bits of cnt.
+// hist[digit] += cnt (cnt in 0..7) for every lane.  Keys of neighbouring tokens often share their
+// leading bits, so a plain LDS atomic would serialise up to 64 lanes on one bin: lanes that agree
+// with a leader are merged through ballots of the three bits of cnt and added by the leader alone;
+// after two rounds the stragglers (few, spread over bins) add themselves.
 __device__ __forceinline__ void hist_add_weighted(int* hist, uint32_t digit, int cnt, int lane) {
   unsigned long long todo = __ballot(cnt > 0);
 #pragma unroll
@@ -122,86 +105,6 @@ __device__ __forceinline__ void hist_add_thread_keys(int* hist, const uint32_t (
     if (ok[j] && dg[j] != d0) atomicAdd(&hist[dg[j]], 1);
 }
 
-// 16-bit partial histogram of a workgroup: two bins per 32-bit store
-template <int NT> __device__ __forceinline__ void store_partial(uint16_t* out, const int* hist) {
-  uint32_t* o32 = reinterpret_cast<uint32_t*>(out);
-  for (int i = threadIdx.x; i < kBins / 2; i += NT) o32[i] = (uint32_t)hist[2 * i] | ((uint32_t)hist[2 * i + 1] << 16);
-}
-
-// ---------------------------------------------------------------------------
-// leading-digit histogram of the score keys (and, POOL, the pooled score itself)
-// ---------------------------------------------------------------------------
-struct HistParams {
-  const float* src;       // POOL: attention mass [H, n]; otherwise the scores [H, n]
-  float* score;           // POOL: output [H, n]
-  uint16_t* part;         // [H, C, kBins] or null (POOL only: pooling without a histogram)
-  int n, n_prefix, kernel, chunk_tokens, n_chunks;
-};
-
-template <bool POOL>
-__global__ __launch_bounds__(HT) void route_hist_kernel(HistParams p) {
-  __shared__ int hist[kBins];
-  const int h = blockIdx.y, chunk = blockIdx.x;
-  const int lane = threadIdx.x & 63;
-  const bool do_hist = p.part != nullptr;
-  if (do_hist) {
-    for (int i = threadIdx.x; i < kBins; i += HT) hist[i] = 0;
-    __syncthreads();
-  }
-  const float* src = p.src + (size_t)h * p.n;
-  const int begin = chunk * p.chunk_tokens, end = min(p.n, begin + p.chunk_tokens);
-  const bool vec4 = (p.n & 3) == 0 && (reinterpret_cast<uintptr_t>(src) & 15u) == 0 &&
-                    (!POOL || (reinterpret_cast<uintptr_t>(p.score) & 15u) == 0);
-  for (int tile = begin; tile < end; tile += kHistTile) {        // uniform trip count: whole waves take part
-    const int t0 = tile + (int)threadIdx.x * EPT;
-    float s[EPT];
-    bool ok[EPT];
-#pragma unroll
-    for (int j = 0; j < EPT; ++j) ok[j] = t0 + j < end;
-    if (POOL) {
-      const int half = p.kernel / 2;
-#pragma unroll
-      for (int j = 0; j < EPT; ++j) {
-        const int t = t0 + j;
-        float out = INFINITY;                                      // window columns
-        if (ok[j] && t < p.n_prefix) {
-          const int lo = max(0, t - half), hi = min(p.n_prefix - 1, t + half);
-          float acc = 0.f;
-          for (int i = lo; i <= hi; ++i) acc += src[i];
-          out = acc / (float)p.kernel;
-        }
-        s[j] = out;
-      }
-      float* dst = p.score + (size_t)h * p.n;
-      if (vec4 && ok[EPT - 1]) {
-        *reinterpret_cast<float4*>(dst + t0) = make_float4(s[0], s[1], s[2], s[3]);
-      } else {
-#pragma unroll
-        for (int j = 0; j < EPT; ++j)
-          if (ok[j]) dst[t0 + j] = s[j];
-      }
-    } else {
-      if (vec4 && ok[EPT - 1]) {
-        const float4 x = *reinterpret_cast<const float4*>(src + t0);
-        s[0] = x.x; s[1] = x.y; s[2] = x.z; s[3] = x.w;
-      } else {
-#pragma unroll
-        for (int j = 0; j < EPT; ++j) s[j] = ok[j] ? src[t0 + j] : 0.f;
-      }
-    }
-    if (do_hist) {
-      uint32_t key[EPT];
-#pragma unroll
-      for (int j = 0; j < EPT; ++j) key[j] = float_key(s[j]);
-      hist_add_thread_keys(hist, key, ok, lane);
-    }
-  }
-  if (do_hist) {
-    __syncthreads();
-    store_partial<HT>(p.part + ((size_t)h * p.n_chunks + chunk) * kBins, hist);
-  }
-}
-
 // ---------------------------------------------------------------------------
 // prefix sums: inside a wave on the DPP network, across the waves through one LDS row that
 // every thread reads whole (no chain of dependent LDS reads)
@@ -220,19 +123,173 @@ __device__ __forceinline__ int wave_incl_scan_dpp(int v) {
 }
 __device__ __forceinline__ int wave_total_of_scan(int incl) { return __builtin_amdgcn_readlane(incl, 63); }
 
-// RW per-wave values -> their sum over the waves before `wave`, and over all waves
-__device__ __forceinline__ void wave_row_sums(const int* row, int wave, int& before, int& total) {
-  const int4* r4 = reinterpret_cast<const int4*>(row);
+// NW per-wave values -> their sum over the waves before `wave`, and over all waves
+template <int NW> __device__ __forceinline__ void wave_row_sums(const int* row, int wave, int& before, int& total) {
   before = 0;
   total = 0;
 #pragma unroll
-  for (int q = 0; q < RW / 4; ++q) {
-    const int4 v = r4[q];
-    const int x[4] = {v.x, v.y, v.z, v.w};
+  for (int q = 0; q < NW; ++q) {
+    const int x = row[q];
+    total += x;
+    before += (q < wave) ? x : 0;
+  }
+}
+
+// Counts of a 2048-bin LDS histogram -> D[b] = #(digit >= b), written as a 16-bit table to
+// global memory (D[2048] = 0 and the padding included); the histogram itself is turned into
+// #(digit > b), the first slot of bin b when the keys are laid out highest digit first.
+// NT threads, thread t owns the kBins / NT bins below and including kBins - 1 - t * kBins / NT.
+// row: LDS, NT / 64 ints.  Ends with a barrier.
+template <int NT>
+__device__ __forceinline__ void counts_to_table(int* hist, uint16_t* table, int* row) {
+  constexpr int BPT = kBins / NT, NW = NT / kWave;
+  static_assert(BPT % 2 == 0, "pairs of bins are stored as one word");
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int hi = kBins - 1 - BPT * (int)threadIdx.x;
+  int c[BPT], s[BPT], run = 0;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      total += x[u];
-      before += (q * 4 + u < wave) ? x[u] : 0;
+  for (int k = 0; k < BPT; ++k) { c[k] = hist[hi - k]; run += c[k]; s[k] = run; }
+  const int incl = wave_incl_scan_dpp(run);
+  if (lane == 63) row[wave] = incl;
+  __syncthreads();
+  int before, total;
+  wave_row_sums<NW>(row, wave, before, total);
+  before += incl - run;
+  uint32_t* t32 = reinterpret_cast<uint32_t*>(table);
+#pragma unroll
+  for (int k = 0; k < BPT; k += 2) {          // bins hi-k (odd) and hi-k-1 (even) share a word
+    const uint32_t d_hi = (uint32_t)(before + s[k]), d_lo = (uint32_t)(before + s[k + 1]);
+    t32[(hi - k - 1) >> 1] = d_lo | (d_hi << 16);
+    hist[hi - k] = before + s[k] - c[k];
+    hist[hi - k - 1] = before + s[k + 1] - c[k + 1];
+  }
+  if (threadIdx.x < (kTableStride - kBins) / 2) t32[kBins / 2 + threadIdx.x] = 0u;
+  __syncthreads();
+}
+
+// ---------------------------------------------------------------------------
+// buckets of the score keys by leading digit (and, POOL, the pooled score itself)
+// ---------------------------------------------------------------------------
+struct BucketParams {
+  const float* src;       // POOL: attention mass [H, n]; otherwise the scores [H, n]
+  float* score;           // POOL: output [H, n]
+  uint16_t* table;        // [H, C, kTableStride] or null (POOL only: pooling alone)
+  uint32_t* bkey;         // [H, n]: chunk c owns [c * chunk_tokens, ...), keys grouped by digit, highest first
+  int32_t* bpos;          // [H, n]: the token each key belongs to
+  int n, n_prefix, kernel, chunk_tokens, n_chunks;
+};
+
+template <bool POOL>
+__global__ __launch_bounds__(BT) void route_bucket_kernel(BucketParams p) {
+  __shared__ int hist[kBins];
+  __shared__ int row[BT / kWave];
+  const int h = blockIdx.y, chunk = blockIdx.x;
+  const int lane = threadIdx.x & 63;
+  const bool do_buckets = p.table != nullptr;
+  if (do_buckets) {
+    for (int i = threadIdx.x; i < kBins; i += BT) hist[i] = 0;
+    __syncthreads();
+  }
+  const float* src = p.src + (size_t)h * p.n;
+  const float* scores = POOL ? p.score + (size_t)h * p.n : src;
+  const int begin = chunk * p.chunk_tokens, end = min(p.n, begin + p.chunk_tokens);
+  const bool vec4 = (p.n & 3) == 0 && ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(scores)) & 15u) == 0;
+  auto load_scores = [&](int t0, float (&s)[EPT]) {
+    if (vec4 && t0 + EPT <= end) {
+      const float4 x = *reinterpret_cast<const float4*>(scores + t0);
+      s[0] = x.x; s[1] = x.y; s[2] = x.z; s[3] = x.w;
+    } else {
+#pragma unroll
+      for (int j = 0; j < EPT; ++j) s[j] = t0 + j < end ? scores[t0 + j] : 0.f;
+    }
+  };
+  uint32_t key0[EPT];                            // the keys of the first tile stay in registers for the scatter
+  for (int tile = begin; tile < end; tile += kBucketTile) {        // uniform trip count: whole waves take part
+    const int t0 = tile + (int)threadIdx.x * EPT;
+    float s[EPT];
+    bool ok[EPT];
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) ok[j] = t0 + j < end;
+    if (POOL) {
+      const int half = p.kernel / 2;
+      if (vec4 && half <= EPT && t0 >= EPT && t0 + 2 * EPT <= p.n) {
+        // the 12 mass values around the thread's four tokens in three loads; each window is
+        // summed in ascending token order, like the general loop below
+        float m[3 * EPT];
+#pragma unroll
+        for (int q = 0; q < 3; ++q) {
+          const float4 x = *reinterpret_cast<const float4*>(src + t0 - EPT + q * EPT);
+          m[q * EPT + 0] = x.x; m[q * EPT + 1] = x.y; m[q * EPT + 2] = x.z; m[q * EPT + 3] = x.w;
+        }
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) {
+          const int t = t0 + j;
+          float acc = 0.f;
+#pragma unroll
+          for (int d = -EPT; d <= EPT; ++d)
+            if (d >= -half && d <= half && t + d < p.n_prefix) acc += m[EPT + j + d];
+          s[j] = (ok[j] && t < p.n_prefix) ? acc / (float)p.kernel : INFINITY;
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) {
+          const int t = t0 + j;
+          float out = INFINITY;                                      // window columns
+          if (ok[j] && t < p.n_prefix) {
+            const int lo = max(0, t - half), hi = min(p.n_prefix - 1, t + half);
+            float acc = 0.f;
+            for (int i = lo; i <= hi; ++i) acc += src[i];
+            out = acc / (float)p.kernel;
+          }
+          s[j] = out;
+        }
+      }
+      float* dst = p.score + (size_t)h * p.n;
+      if (vec4 && ok[EPT - 1]) {
+        *reinterpret_cast<float4*>(dst + t0) = make_float4(s[0], s[1], s[2], s[3]);
+      } else {
+#pragma unroll
+        for (int j = 0; j < EPT; ++j)
+          if (ok[j]) dst[t0 + j] = s[j];
+      }
+    } else {
+      load_scores(t0, s);
+    }
+    if (do_buckets) {
+      uint32_t key[EPT];
+#pragma unroll
+      for (int j = 0; j < EPT; ++j) key[j] = float_key(s[j]);
+      hist_add_thread_keys(hist, key, ok, lane);
+      if (tile == begin) {
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) key0[j] = key[j];
+      }
+    }
+  }
+  if (!do_buckets) return;
+  __syncthreads();
+  counts_to_table<BT>(hist, p.table + ((size_t)h * p.n_chunks + chunk) * kTableStride, row);
+  // scatter: hist[b] is now the next free slot of bin b in the chunk's list
+  uint32_t* bkey = p.bkey + (size_t)h * p.n + begin;
+  int32_t* bpos = p.bpos + (size_t)h * p.n + begin;
+  for (int tile = begin; tile < end; tile += kBucketTile) {
+    const int t0 = tile + (int)threadIdx.x * EPT;
+    uint32_t key[EPT];
+    if (tile == begin) {
+#pragma unroll
+      for (int j = 0; j < EPT; ++j) key[j] = key0[j];
+    } else {                                     // later tiles: the scores this thread stored (or read) above
+      float s[EPT];
+      load_scores(t0, s);
+#pragma unroll
+      for (int j = 0; j < EPT; ++j) key[j] = float_key(s[j]);
+    }
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+      if (t0 + j < end) {
+        const int slot = atomicAdd(&hist[key[j] >> 21], 1);
+        if (slot < end - begin) { bkey[slot] = key[j]; bpos[slot] = t0 + j; }    // always true: counted above
+      }
     }
   }
 }
@@ -240,187 +297,161 @@ __device__ __forceinline__ void wave_row_sums(const int* row, int wave, int& bef
 // ---------------------------------------------------------------------------
 // radix select shared by the two selecting kernels
 // ---------------------------------------------------------------------------
-constexpr int kWaveCand = kCandCap / RW;     // each wave keeps its own candidates: no shared counter
-
-enum { ROW_PICK0 = 0, ROW_PICK1, ROW_PICK2, ROW_GT, ROW_EQ, ROW_EMIT0, ROW_EMIT1, ROW_COUNT };
+enum { ROW_PICK1 = 0, ROW_PICK2, ROW_GT, ROW_EQ, ROW_EMIT0, ROW_EMIT1, ROW_TABLE, ROW_COUNT };
 
 struct SelectShared {
-  int hist[3][kBins];                    // digits of levels 1 and 2 of a select, and one for the caller; zeroed at the start
-  __align__(16) int row[ROW_COUNT][RW];  // per-wave terms of the workgroup-wide sums, one row per use
+  __align__(16) int hist[3][kBins];      // digits of levels 1 and 2 of a select, and one for the caller; zeroed at the start
+  int row[ROW_COUNT][SW];                // per-wave terms of the workgroup-wide sums, one row per use
   int pick[3][4];                        // per level: digit, #(digit above it), count of its bin
+  int seg_first[kMaxChunks], seg_count[kMaxChunks], seg_start[kMaxChunks];   // per chunk: where the keys with the chosen
+                                         // leading digit sit, how many, and how many in earlier chunks
   int overflow;                          // a wave found more candidates than it can keep
 };
 
 __device__ __forceinline__ void select_shared_init(SelectShared& sh) {
   int* h = &sh.hist[0][0];
-  for (int i = threadIdx.x; i < 3 * kBins; i += RT) h[i] = 0;
+  for (int i = threadIdx.x; i < 3 * kBins; i += ST) h[i] = 0;
   if (threadIdx.x == 0) sh.overflow = 0;
 }
 
-// The digit d with #(digit > d) < remaining <= #(digit >= d), from per-thread counts of bins
-// kBins-1-2t (c0) and kBins-2-2t (c1); every thread gets d, #(digit > d) and the count of bin d.
-__device__ __forceinline__ void pick_digit(int c0, int c1, int remaining, SelectShared& sh, int level, int& digit, int& above_out,
-                                           int& count) {
+// Leading digit of the k-th largest key from the D tables of a head's chunks: summed over the
+// chunks, S[b] = #(digit >= b) falls from the key count at b = 0 to 0 at b = 2048, and the digit is
+// the one bin with S[b+1] < k <= S[b].  Thread t looks at bins 2040-8t .. 2047-8t (one 16-byte
+// load per chunk plus the entry above).  Every thread gets the digit, #(digit above it) and the
+// count of its bin.  prefetch() is called once the table loads are out, so that the caller's own
+// first loads travel with them.
+template <typename Prefetch>
+__device__ __forceinline__ void pick_leading_digit(const uint16_t* tables, int n_parts, int k, SelectShared& sh, Prefetch prefetch,
+                                                   int& digit, int& above, int& count) {
+  const int lo = kBins - 8 - 8 * (int)threadIdx.x;
+  int S[9];
+#pragma unroll
+  for (int j = 0; j < 9; ++j) S[j] = 0;
+  bool first = true;
+  constexpr int kInFlight = 16;                 // tables requested together: one trip to memory for up to 16 chunks
+  for (int c = 0; c < n_parts; c += kInFlight) {
+    uint4 v[kInFlight];
+    uint16_t e[kInFlight];
+#pragma unroll
+    for (int u = 0; u < kInFlight; ++u) {
+      const uint16_t* t = tables + (size_t)min(c + u, n_parts - 1) * kTableStride + lo;
+      v[u] = *reinterpret_cast<const uint4*>(t);
+      e[u] = t[8];
+    }
+    if (first) { prefetch(); first = false; }
+#pragma unroll
+    for (int u = 0; u < kInFlight; ++u) {
+      if (c + u < n_parts) {
+        const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { S[2 * q] += (int)(w[q] & 0xffffu); S[2 * q + 1] += (int)(w[q] >> 16); }
+        S[8] += (int)e[u];
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    if (S[j + 1] < k && k <= S[j]) {
+      sh.pick[0][0] = lo + j;
+      sh.pick[0][1] = S[j + 1];
+      sh.pick[0][2] = S[j] - S[j + 1];
+    }
+  }
+  __syncthreads();
+  digit = sh.pick[0][0];
+  above = sh.pick[0][1];
+  count = sh.pick[0][2];
+}
+
+// The digit d with #(digit > d) < remaining <= #(digit >= d) of an LDS histogram of counts
+// (thread t owns bins 2040-8t .. 2047-8t).  level 1 or 2: which row / result slot to use.
+__device__ __forceinline__ void pick_digit(const int* hist, int remaining, SelectShared& sh, int level, int& digit, int& above_out) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int b_hi = kBins - 1 - 2 * (int)threadIdx.x;
-  const int tot = c0 + c1;
-  const int incl_w = wave_incl_scan_dpp(tot);
-  if (lane == 63) sh.row[ROW_PICK0 + level][wave] = incl_w;
+  const int lo = kBins - 8 - 8 * (int)threadIdx.x;
+  const int4 a = *reinterpret_cast<const int4*>(hist + lo), b = *reinterpret_cast<const int4*>(hist + lo + 4);
+  const int c[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};      // bins lo .. lo+7
+  int tot = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) tot += c[j];
+  const int incl = wave_incl_scan_dpp(tot);
+  if (lane == 63) sh.row[ROW_PICK1 + level - 1][wave] = incl;
   __syncthreads();
   int before, total;
-  wave_row_sums(sh.row[ROW_PICK0 + level], wave, before, total);
-  int above = incl_w - tot + before;
+  wave_row_sums<SW>(sh.row[ROW_PICK1 + level - 1], wave, before, total);
+  int above = incl - tot + before;                                  // keys in bins above this thread's
   if (above < remaining && remaining <= above + tot) {
-    int d = b_hi, cnt = c0;
-    if (remaining > above + c0) { above += c0; d = b_hi - 1; cnt = c1; }
-    sh.pick[level][0] = d;
-    sh.pick[level][1] = above;
-    sh.pick[level][2] = cnt;
+#pragma unroll
+    for (int j = 7; j >= 0; --j) {
+      if (above < remaining && remaining <= above + c[j]) { sh.pick[level][0] = lo + j; sh.pick[level][1] = above; }
+      above += c[j];
+    }
   }
   __syncthreads();
   digit = sh.pick[level][0];
   above_out = sh.pick[level][1];
-  count = sh.pick[level][2];
 }
 
-// The k-th largest (1 <= k <= m) of the m keys that load4 delivers four at a time, given the
-// leading-digit histogram of those keys as n_parts partial histograms.  Returns the threshold key,
-// the number of keys equal to it that belong to the k largest (`quota`, taken in index order by
-// the caller), and how many keys at positions below `before` are greater than / equal to the
-// threshold.  load4(i0, key, ok): keys of positions i0 .. i0+3 (i0 a multiple of 4), ok = inside.
-// cand_key / cand_pos: LDS, kCandCap entries each.  select_shared_init must have run (no barrier
-// needed in between: the first pick has two).
-// One trip to memory for the histograms and the first kBatch tiles of keys together; after that
-// the select runs out of registers and LDS.
-template <typename Load4>
-__device__ __forceinline__ void select_threshold(Load4 load4, int m, int k, const uint16_t* part, int n_parts, int before,
-                                                 SelectShared& sh, uint32_t* cand_key, int32_t* cand_pos, uint32_t& thr,
-                                                 int& quota, int& base_gt, int& base_eq, int trace_base = 0) {
+// The candidates of a select (keys that share the threshold's leading digit), each wave its own
+// list in LDS.  Entries are appended either by the lanes that found one (`append_found`, inside
+// uniform control flow) or as a dense run (`append_run`).
+struct CandidateList {
+  uint32_t* key;
+  int32_t* pos;
+  int n;                // appended so far by this wave (uniform); may exceed kWaveCand: then the list is not used
+  bool shared = false;  // one list for the whole workgroup (n entries) instead of one per wave
+  __device__ __forceinline__ void append_found(bool found, uint32_t k, int p, int lane, int* hist1) {
+    const unsigned long long b = __ballot(found);
+    if (b) {
+      if (found) {
+        const int at = n + __popcll(b & ((1ull << lane) - 1ull));
+        if (at < kWaveCand) { key[at] = k; pos[at] = p; }
+        atomicAdd(&hist1[(k >> 10) & 2047u], 1);
+      }
+      n += __popcll(b);
+    }
+  }
+  __device__ __forceinline__ void append_run(bool valid, int n_valid, uint32_t k, int p, int lane, int* hist1) {
+    if (valid) {
+      const int at = n + lane;
+      if (at < kWaveCand) { key[at] = k; pos[at] = p; }
+      atomicAdd(&hist1[(k >> 10) & 2047u], 1);
+    }
+    n += n_valid;
+  }
+};
+
+// Second and third digit of the threshold on the candidates, and how many candidates at positions
+// below `before` are above / equal to the threshold.  each_global(f) visits every candidate from
+// memory (used when a wave's list overflowed).  Called by all threads after the candidates are
+// in (lists written, sh.hist[0] filled); starts with the barrier that publishes them.
+template <typename GlobalEach>
+__device__ __forceinline__ void finish_select(const CandidateList& list, GlobalEach each_global, int d0, int remaining, int before,
+                                              int gt, SelectShared& sh, uint32_t& thr, int& quota, int& base_gt, int& base_eq) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  (void)trace_base;
-  VEC_TRACE(trace_base + 0);
-  const int n_tiles = (m + kTile - 1) / kTile;
-  // ---- leading digit, from the partial histograms: thread t owns bins 2047-2t and 2046-2t ----
-  int c0 = 0, c1 = 0;
-  uint32_t cur[kBatch][EPT];
-  bool cur_ok[kBatch][EPT];
-  auto load_batch = [&](int tb, uint32_t (&key)[kBatch][EPT], bool (&ok)[kBatch][EPT]) {
-#pragma unroll
-    for (int u = 0; u < kBatch; ++u) {
-      if (tb + u < n_tiles) {
-        load4((tb + u) * kTile + (int)threadIdx.x * EPT, key[u], ok[u]);
-      } else {
-#pragma unroll
-        for (int j = 0; j < EPT; ++j) { key[u][j] = 0u; ok[u][j] = false; }
-      }
-    }
-  };
-  {
-    const uint32_t* p32 = reinterpret_cast<const uint32_t*>(part) + (kBins / 2 - 1 - (int)threadIdx.x);
-    uint32_t v[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = p32[(size_t)min(u, n_parts - 1) * (kBins / 2)];
-    load_batch(0, cur, cur_ok);                  // in flight together with the histograms
-#pragma unroll
-    for (int u = 0; u < 8; ++u)
-      if (u < n_parts) { c1 += (int)(v[u] & 0xffffu); c0 += (int)(v[u] >> 16); }
-    for (int c = 8; c < n_parts; c += 8) {
-#pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = p32[(size_t)min(c + u, n_parts - 1) * (kBins / 2)];
-#pragma unroll
-      for (int u = 0; u < 8; ++u)
-        if (c + u < n_parts) { c1 += (int)(v[u] & 0xffffu); c0 += (int)(v[u] >> 16); }
-    }
-  }
-  VEC_TRACE(trace_base + 1);
-  int d0, above0, m0;
-  pick_digit(c0, c1, k, sh, 0, d0, above0, m0);
-  int remaining = k - above0;
-  VEC_TRACE(trace_base + 2);
-
-  // ---- all keys once: candidates (leading digit d0) into this wave's list and into the
-  //      histogram of the second digit; earlier keys above the digit counted ----
-  int gt = 0, n_mine = 0;
-  uint32_t* my_key = cand_key + wave * kWaveCand;
-  int32_t* my_pos = cand_pos + wave * kWaveCand;
-  auto scan_batch = [&](int tb, const uint32_t (&key)[kBatch][EPT], const bool (&ok)[kBatch][EPT]) {
-#pragma unroll
-    for (int u = 0; u < kBatch; ++u) {
-      if (tb + u < n_tiles) {                    // uniform
-        const int i0 = (tb + u) * kTile + (int)threadIdx.x * EPT;
-#pragma unroll
-        for (int j = 0; j < EPT; ++j) {
-          const int dg = (int)(key[u][j] >> 21);
-          gt += ok[u][j] && i0 + j < before && dg > d0;
-          const bool is_c = ok[u][j] && dg == d0;
-          const unsigned long long b = __ballot(is_c);
-          if (b) {
-            if (is_c) {
-              const int pos = n_mine + __popcll(b & ((1ull << lane) - 1ull));
-              if (pos < kWaveCand) { my_key[pos] = key[u][j]; my_pos[pos] = i0 + j; }
-              atomicAdd(&sh.hist[0][(key[u][j] >> 10) & 2047u], 1);
-            }
-            n_mine += __popcll(b);
-          }
-        }
-      }
-    }
-  };
-  for (int tb = 0; tb < n_tiles; tb += kBatch) {
-    uint32_t nxt[kBatch][EPT];
-    bool nxt_ok[kBatch][EPT];
-    const bool more = tb + kBatch < n_tiles;
-    if (more) load_batch(tb + kBatch, nxt, nxt_ok);      // requested before this batch is worked on
-    scan_batch(tb, cur, cur_ok);
-    if (more) {
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u)
-#pragma unroll
-        for (int j = 0; j < EPT; ++j) { cur[u][j] = nxt[u][j]; cur_ok[u][j] = nxt_ok[u][j]; }
-    }
-  }
-  if (n_mine > kWaveCand && lane == 0) sh.overflow = 1;
+  if (!list.shared && list.n > kWaveCand && lane == 0) sh.overflow = 1;
   __syncthreads();
-  VEC_TRACE(trace_base + 3);
   const bool use_list = sh.overflow == 0;
-  const int n_list = min(n_mine, kWaveCand);
-
-  // visit every key whose leading digit is d0 (each wave its own): f(key, position)
   auto for_each_candidate = [&](auto f) {
     if (use_list) {
-      for (int i = lane; i < n_list; i += kWave) f(my_key[i], my_pos[i]);
+      const int first = list.shared ? (int)threadIdx.x : lane, step = list.shared ? ST : kWave;
+      for (int i = first; i < list.n; i += step) f(list.key[i], list.pos[i]);
     } else {
-      for (int t = 0; t < n_tiles; ++t) {
-        uint32_t key[EPT];
-        bool ok[EPT];
-        const int i0 = t * kTile + (int)threadIdx.x * EPT;
-        load4(i0, key, ok);
-#pragma unroll
-        for (int j = 0; j < EPT; ++j)
-          if (ok[j] && (int)(key[j] >> 21) == d0) f(key[j], i0 + j);
-      }
+      each_global(f);
     }
   };
-
-  // ---- second digit: its histogram was filled during the scan ----
-  const int b_hi = kBins - 1 - 2 * (int)threadIdx.x;
-  int d1, above1, m1;
-  pick_digit(sh.hist[0][b_hi], sh.hist[0][b_hi - 1], remaining, sh, 1, d1, above1, m1);
+  int d1, above1;
+  pick_digit(sh.hist[0], remaining, sh, 1, d1, above1);
   remaining -= above1;
   const uint32_t prefix22 = (((uint32_t)d0) << 21) | (((uint32_t)d1) << 10);
-  // ---- third digit ----
   for_each_candidate([&](uint32_t key, int) {
     if ((key >> 10) == (prefix22 >> 10)) atomicAdd(&sh.hist[1][key & 1023u], 1);
   });
   __syncthreads();
-  int d2, above2, m2;
-  pick_digit(sh.hist[1][b_hi], sh.hist[1][b_hi - 1], remaining, sh, 2, d2, above2, m2);
+  int d2, above2;
+  pick_digit(sh.hist[1], remaining, sh, 2, d2, above2);
   remaining -= above2;
   thr = prefix22 | (uint32_t)d2;
   quota = remaining;
-  VEC_TRACE(trace_base + 4);
-
-  // ---- keys before `before`: above the threshold, equal to it ----
   int eq = 0;
   const uint32_t t_key = thr;
   for_each_candidate([&](uint32_t key, int pos) {
@@ -431,16 +462,16 @@ __device__ __forceinline__ void select_threshold(Load4 load4, int m, int k, cons
   if (lane == 0) { sh.row[ROW_GT][wave] = gt; sh.row[ROW_EQ][wave] = eq; }
   __syncthreads();
   int unused;
-  wave_row_sums(sh.row[ROW_GT], RW, unused, base_gt);
-  wave_row_sums(sh.row[ROW_EQ], RW, unused, base_eq);
-  VEC_TRACE(trace_base + 5);
+  wave_row_sums<SW>(sh.row[ROW_GT], SW, unused, base_gt);
+  wave_row_sums<SW>(sh.row[ROW_EQ], SW, unused, base_eq);
 }
 
 // Ordered pass over positions [begin, end) in tiles of kTile: a thread's EPT consecutive
 // elements are classified by load_cls (2: above the threshold, 1: equal, 0: below or outside);
 // emit(position, selected, rank among the selected) is called for every element inside.
 // Equal elements are selected while fewer than `quota` earlier ones exist.  The two running
-// counts of a thread travel through one scan packed as (greater << 16) | equal.
+// counts of a thread travel through one scan packed as (greater << 16) | equal (a tile has
+// 1024 elements, so neither half overflows).
 template <typename ClsFn, typename EmitFn>
 __device__ __forceinline__ void ordered_emit(ClsFn load_cls, EmitFn emit, int begin, int end, int base_gt, int base_eq, int quota,
                                              SelectShared& sh) {
@@ -457,7 +488,7 @@ __device__ __forceinline__ void ordered_emit(ClsFn load_cls, EmitFn emit, int be
     if (lane == 63) sh.row[ROW_EMIT0 + buf][wave] = incl;
     __syncthreads();
     int pre, tile_tot;
-    wave_row_sums(sh.row[ROW_EMIT0 + buf], wave, pre, tile_tot);
+    wave_row_sums<SW>(sh.row[ROW_EMIT0 + buf], wave, pre, tile_tot);
     pre += incl - packed;
     int pre_gt = carry_gt + (pre >> 16), pre_eq = carry_eq + (pre & 0xffff);
     carry_gt += tile_tot >> 16;
@@ -481,22 +512,24 @@ struct RouteParams {
   int chunk_tokens, n_chunks;      // selection by score: tokens per workgroup
   int slice, n_slices;             // selection by residual: pool entries per workgroup
   int pool_stride;                 // entries between the pool lists of two heads (a multiple of 4)
-  const uint16_t* part0;           // [H, C, kBins] leading digits of the score keys
-  uint16_t* part1;                 // [H, C, kBins] leading digits of the residual keys of pool members
+  const uint16_t* table0;          // [H, C, kTableStride] leading digits of the score keys
+  const uint32_t* bkey;            // [H, n] score keys grouped by leading digit, chunk by chunk
+  const int32_t* bpos;
+  uint16_t* table1;                // [H, C, kTableStride] leading digits of the residual keys of pool members
   uint8_t* tier; int32_t* idx_retain; int32_t* idx_approx;
   int32_t* pool_idx; uint32_t* pool_key;
 };
 
 // Step 1: the pool is the n_pool tokens of highest score
-__global__ __launch_bounds__(RT) void route_pool_kernel(RouteParams p) {
+__global__ __launch_bounds__(ST) void route_pool_kernel(RouteParams p) {
   __shared__ SelectShared sh;
   extern __shared__ __align__(16) unsigned char dyn_lds[];
-  uint32_t* cand_key = reinterpret_cast<uint32_t*>(dyn_lds);
-  int32_t* cand_pos = reinterpret_cast<int32_t*>(dyn_lds) + kCandCap;
   const int h = blockIdx.y, chunk = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const float* sc = p.score + (size_t)h * p.n;
   const float* ep = p.eps + (size_t)h * p.n;
   const int n = p.n;
+  VEC_TRACE(0);
   select_shared_init(sh);
   const bool vec4 = (n & 3) == 0 && ((reinterpret_cast<uintptr_t>(sc) | reinterpret_cast<uintptr_t>(ep)) & 15u) == 0;
   auto load_f4 = [&](const float* a, int i0, float (&x)[EPT]) {
@@ -508,22 +541,90 @@ __global__ __launch_bounds__(RT) void route_pool_kernel(RouteParams p) {
       for (int j = 0; j < EPT; ++j) x[j] = i0 + j < n ? a[i0 + j] : 0.f;
     }
   };
-  auto load4 = [&](int i0, uint32_t (&key)[EPT], bool (&ok)[EPT]) {
-    float x[EPT];
-    load_f4(sc, i0, x);
-#pragma unroll
-    for (int j = 0; j < EPT; ++j) { ok[j] = i0 + j < n; key[j] = ok[j] ? float_key(x[j]) : 0u; }
-  };
   const int begin = chunk * p.chunk_tokens, end = min(n, begin + p.chunk_tokens);
-  // this thread's tokens of the chunk's first tile: requested now, used by the ordered pass
+  // this thread's tokens of the chunk's first two tiles: requested with the tables, used by the ordered pass
   const int first_i0 = begin + (int)threadIdx.x * EPT;
-  float sc0[EPT], ep0[EPT];
-  load_f4(sc, first_i0, sc0);
-  load_f4(ep, first_i0, ep0);
+  float sc0[2][EPT], ep0[2][EPT];
+  int d0, above0, m0;
+  const uint16_t* tables = p.table0 + (size_t)h * p.n_chunks * kTableStride;
+  pick_leading_digit(tables, p.n_chunks, p.n_pool, sh,
+                     [&]() {
+#pragma unroll
+                       for (int u = 0; u < 2; ++u) { load_f4(sc, first_i0 + u * kTile, sc0[u]); load_f4(ep, first_i0 + u * kTile, ep0[u]); }
+                     },
+                     d0, above0, m0);
+  VEC_TRACE(1);
+  // where every chunk keeps its keys of digit d0: after the D[d0+1] keys of higher digits
+  if (wave == 0) {                               // n_chunks <= 32: one lane per chunk
+    int hi = 0, cnt = 0;
+    if (lane < p.n_chunks) {
+      const uint16_t* t = tables + (size_t)lane * kTableStride;
+      hi = t[d0 + 1];
+      cnt = (int)t[d0] - hi;
+    }
+    const int incl = wave_incl_scan_dpp(cnt);
+    if (lane < p.n_chunks) { sh.seg_first[lane] = hi; sh.seg_count[lane] = cnt; sh.seg_start[lane] = incl - cnt; }
+  }
+  __syncthreads();
+  VEC_TRACE(2);
+  // Candidates: a group of threads per chunk reads that chunk's piece, kBatch loads in flight per
+  // thread; candidate number = pieces of earlier chunks + place in the piece, which is also its
+  // slot in the one list the waves then share out.  Keys above the digit in earlier chunks are
+  // all selected.
+  uint32_t* cand_key = reinterpret_cast<uint32_t*>(dyn_lds);
+  int32_t* cand_pos = reinterpret_cast<int32_t*>(dyn_lds) + kCandCap;
+  const uint32_t* bkey = p.bkey + (size_t)h * n;
+  const int32_t* bpos = p.bpos + (size_t)h * n;
+  int gt = 0;
+  for (int c = 0; c < p.n_chunks; ++c)
+    if (c < chunk && threadIdx.x == 0) gt += sh.seg_first[c];
+  int groups = 1;
+  while (groups < p.n_chunks) groups *= 2;
+  const int tpc = ST / groups;                   // threads per chunk (at least 8)
+  const int my_c = (int)threadIdx.x / tpc, my_sub = (int)threadIdx.x % tpc;
+  const bool fits = m0 <= kCandCap;
+  {
+    const bool live = my_c < p.n_chunks;
+    const int cnt = live ? sh.seg_count[my_c] : 0;
+    const int src0 = live ? my_c * p.chunk_tokens + sh.seg_first[my_c] : 0;
+    const int dst0 = live ? sh.seg_start[my_c] : 0;
+    for (int i0 = 0; i0 < cnt; i0 += tpc * kBatch) {
+      uint32_t ck[kBatch];
+      int cp[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int i = min(i0 + u * tpc + my_sub, cnt - 1);
+        ck[u] = bkey[src0 + i];
+        cp[u] = bpos[src0 + i];
+      }
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int i = i0 + u * tpc + my_sub;
+        if (i < cnt) {
+          if (fits) { cand_key[dst0 + i] = ck[u]; cand_pos[dst0 + i] = cp[u]; }
+          atomicAdd(&sh.hist[0][(ck[u] >> 10) & 2047u], 1);
+        }
+      }
+    }
+  }
+  if (!fits && threadIdx.x == 0) sh.overflow = 1;
+  CandidateList list;                            // every wave a share of the one list
+  list.key = cand_key;
+  list.pos = cand_pos;
+  list.n = fits ? m0 : kWaveCand + 1;
+  list.shared = true;
+  VEC_TRACE(3);
   uint32_t thr;
   int quota, base_gt, base_eq;
-  select_threshold(load4, n, p.n_pool, p.part0 + (size_t)h * p.n_chunks * kBins, p.n_chunks, begin, sh, cand_key, cand_pos, thr,
-                   quota, base_gt, base_eq, 0);
+  finish_select(
+      list,
+      [&](auto f) {
+        const int cnt = my_c < p.n_chunks ? sh.seg_count[my_c] : 0;
+        const int src0 = my_c < p.n_chunks ? my_c * p.chunk_tokens + sh.seg_first[my_c] : 0;
+        for (int i = my_sub; i < cnt; i += tpc) f(bkey[src0 + i], bpos[src0 + i]);
+      },
+      d0, p.n_pool - above0, begin, gt, sh, thr, quota, base_gt, base_eq);
+  VEC_TRACE(4);
 
   // ordered pass over the chunk: tiers, pool list, leading digits of the residual keys
   uint8_t* tr = p.tier + (size_t)h * n;
@@ -533,9 +634,10 @@ __global__ __launch_bounds__(RT) void route_pool_kernel(RouteParams p) {
   ordered_emit(
       [&](int i0, int (&cls)[EPT]) {
         float x[EPT], e[EPT];
-        if (i0 == first_i0) {
+        if (i0 == first_i0 || i0 == first_i0 + kTile) {
+          const int u = i0 == first_i0 ? 0 : 1;
 #pragma unroll
-          for (int j = 0; j < EPT; ++j) { x[j] = sc0[j]; e[j] = ep0[j]; }
+          for (int j = 0; j < EPT; ++j) { x[j] = sc0[u][j]; e[j] = ep0[u][j]; }
         } else {
           load_f4(sc, i0, x);
           load_f4(ep, i0, e);
@@ -557,19 +659,18 @@ __global__ __launch_bounds__(RT) void route_pool_kernel(RouteParams p) {
         }
       },
       begin, end, base_gt, base_eq, quota, sh);
-  VEC_TRACE(6);
+  VEC_TRACE(5);
   __syncthreads();
-  store_partial<RT>(p.part1 + ((size_t)h * p.n_chunks + chunk) * kBins, sh.hist[2]);
-  VEC_TRACE(7);
+  counts_to_table<ST>(sh.hist[2], p.table1 + ((size_t)h * p.n_chunks + chunk) * kTableStride, sh.row[ROW_TABLE]);
+  VEC_TRACE(6);
 }
 
 // Step 3: inside the pool, the n_approx tokens of lowest residual lose their value
-__global__ __launch_bounds__(RT) void route_split_kernel(RouteParams p) {
+__global__ __launch_bounds__(ST) void route_split_kernel(RouteParams p) {
   __shared__ SelectShared sh;
   extern __shared__ __align__(16) unsigned char dyn_lds[];
-  uint32_t* cand_key = reinterpret_cast<uint32_t*>(dyn_lds);
-  int32_t* cand_pos = reinterpret_cast<int32_t*>(dyn_lds) + kCandCap;
   const int h = blockIdx.y, slice = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int m = p.n_pool;
   const int32_t* pidx = p.pool_idx + (size_t)h * p.pool_stride;
   const uint32_t* pkey = p.pool_key + (size_t)h * p.pool_stride;
@@ -578,9 +679,10 @@ __global__ __launch_bounds__(RT) void route_split_kernel(RouteParams p) {
   int32_t* ia = p.idx_approx + (size_t)h * p.n_approx;
   const int begin = slice * p.slice, end = min(m, begin + p.slice);
   if (p.n_approx == 0) {
-    for (int i = begin + (int)threadIdx.x; i < end; i += RT) ir[i] = pidx[i];
+    for (int i = begin + (int)threadIdx.x; i < end; i += ST) ir[i] = pidx[i];
     return;
   }
+  VEC_TRACE(16);
   select_shared_init(sh);
   auto load_u4 = [&](const uint32_t* a, int i0, uint32_t (&x)[EPT]) {
     if (i0 + EPT <= m) {                             // lists start at 16-byte boundaries
@@ -591,20 +693,79 @@ __global__ __launch_bounds__(RT) void route_split_kernel(RouteParams p) {
       for (int j = 0; j < EPT; ++j) x[j] = i0 + j < m ? a[i0 + j] : 0u;
     }
   };
-  auto load4 = [&](int i0, uint32_t (&key)[EPT], bool (&ok)[EPT]) {
-    load_u4(pkey, i0, key);
+  const int n_tiles = (m + kTile - 1) / kTile;
+  uint32_t cur[kBatch][EPT];
+  auto load_batch = [&](int tb, uint32_t (&key)[kBatch][EPT]) {
 #pragma unroll
-    for (int j = 0; j < EPT; ++j) ok[j] = i0 + j < m;
+    for (int u = 0; u < kBatch; ++u) {
+      if (tb + u < n_tiles) {
+        load_u4(pkey, (tb + u) * kTile + (int)threadIdx.x * EPT, key[u]);
+      } else {
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) key[u][j] = 0u;
+      }
+    }
   };
-  // this thread's entries of the slice's first tile: requested now, used by the ordered pass
+  // this thread's entries of the slice's first tile: requested with the tables, used by the ordered pass
   const int first_i0 = begin + (int)threadIdx.x * EPT;
   uint32_t key0[EPT], tok0[EPT];
-  load_u4(pkey, first_i0, key0);
-  load_u4(reinterpret_cast<const uint32_t*>(pidx), first_i0, tok0);
+  int d0, above0, m0;
+  pick_leading_digit(p.table1 + (size_t)h * p.n_chunks * kTableStride, p.n_chunks, p.n_approx, sh,
+                     [&]() {
+                       load_batch(0, cur);
+                       load_u4(pkey, first_i0, key0);
+                       load_u4(reinterpret_cast<const uint32_t*>(pidx), first_i0, tok0);
+                     },
+                     d0, above0, m0);
+  VEC_TRACE(17);
+  // all keys of the pool once: candidates into this wave's list, earlier keys above the digit counted
+  CandidateList list;
+  list.key = reinterpret_cast<uint32_t*>(dyn_lds) + wave * kWaveCand;
+  list.pos = reinterpret_cast<int32_t*>(dyn_lds) + kCandCap + wave * kWaveCand;
+  list.n = 0;
+  list.shared = false;
+  int gt = 0;
+  for (int tb = 0; tb < n_tiles; tb += kBatch) {
+    uint32_t nxt[kBatch][EPT];
+    const bool more = tb + kBatch < n_tiles;
+    if (more) load_batch(tb + kBatch, nxt);          // requested before this batch is worked on
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      if (tb + u < n_tiles) {                        // uniform
+        const int i0 = (tb + u) * kTile + (int)threadIdx.x * EPT;
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) {
+          const bool ok = i0 + j < m;
+          const int dg = (int)(cur[u][j] >> 21);
+          gt += ok && i0 + j < begin && dg > d0;
+          list.append_found(ok && dg == d0, cur[u][j], i0 + j, lane, sh.hist[0]);
+        }
+      }
+    }
+    if (more) {
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u)
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) cur[u][j] = nxt[u][j];
+    }
+  }
+  VEC_TRACE(18);
   uint32_t thr;
   int quota, base_gt, base_eq;
-  select_threshold(load4, m, p.n_approx, p.part1 + (size_t)h * p.n_chunks * kBins, p.n_chunks, begin, sh, cand_key, cand_pos, thr,
-                   quota, base_gt, base_eq, 16);
+  finish_select(
+      list,
+      [&](auto f) {
+        for (int t = 0; t < n_tiles; ++t) {
+          uint32_t key[EPT];
+          const int i0 = t * kTile + (int)threadIdx.x * EPT;
+          load_u4(pkey, i0, key);
+#pragma unroll
+          for (int j = 0; j < EPT; ++j)
+            if (i0 + j < m && (int)(key[j] >> 21) == d0) f(key[j], i0 + j);
+        }
+      },
+      d0, p.n_approx - above0, begin, gt, sh, thr, quota, base_gt, base_eq);
+  VEC_TRACE(19);
   uint32_t tok[EPT];
   ordered_emit(
       [&](int i0, int (&cls)[EPT]) {
@@ -631,7 +792,7 @@ __global__ __launch_bounds__(RT) void route_split_kernel(RouteParams p) {
         }
       },
       begin, end, base_gt, base_eq, quota, sh);
-  VEC_TRACE(16 + 6);
+  VEC_TRACE(20);
 }
 
 // nothing is kept: every token is evicted
@@ -673,7 +834,7 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(GatherParams p) {
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
-int route_chunk_tokens(int seq_len) {
+static int route_chunk_tokens(int seq_len) {
   int ch = kMinChunk;
   while ((seq_len + ch - 1) / ch > kMaxChunks) ch *= 2;
   return ch;
@@ -682,40 +843,52 @@ int route_chunk_tokens(int seq_len) {
 namespace {
 struct RouteLayout {
   int chunk_tokens, n_chunks, pool_stride;
-  size_t off_idx, off_key, off_part0, off_part1, total;
+  size_t off_table0, off_table1, off_bkey, off_bpos, off_idx, off_key, total;
 };
 RouteLayout route_layout(int n_kv_heads, int seq_len, int n_pool) {
   RouteLayout L;
   L.chunk_tokens = route_chunk_tokens(seq_len);
   L.n_chunks = (seq_len + L.chunk_tokens - 1) / L.chunk_tokens;
   L.pool_stride = (n_pool + 3) / 4 * 4;
+  const size_t tables = align_up((size_t)n_kv_heads * L.n_chunks * kTableStride * sizeof(uint16_t), 256);
+  const size_t per_token = align_up((size_t)n_kv_heads * seq_len * sizeof(uint32_t), 256);
+  const size_t per_pool = align_up((size_t)n_kv_heads * L.pool_stride * sizeof(uint32_t), 256);
   size_t off = 0;
-  L.off_part0 = off; off += align_up((size_t)n_kv_heads * L.n_chunks * kBins * sizeof(uint16_t), 256);
-  L.off_part1 = off; off += align_up((size_t)n_kv_heads * L.n_chunks * kBins * sizeof(uint16_t), 256);
-  L.off_idx = off;   off += align_up((size_t)n_kv_heads * L.pool_stride * sizeof(int32_t), 256);
-  L.off_key = off;   off += align_up((size_t)n_kv_heads * L.pool_stride * sizeof(uint32_t), 256);
+  L.off_table0 = off; off += tables;
+  L.off_table1 = off; off += tables;
+  L.off_bkey = off;   off += per_token;
+  L.off_bpos = off;   off += per_token;
+  L.off_idx = off;    off += per_pool;
+  L.off_key = off;    off += per_pool;
   L.total = off;
   return L;
+}
+
+void fill_bucket_params(BucketParams& bp, const RouteLayout& L, void* route_ws) {
+  unsigned char* w8 = reinterpret_cast<unsigned char*>(route_ws);
+  bp.table = w8 ? reinterpret_cast<uint16_t*>(w8 + L.off_table0) : nullptr;
+  bp.bkey = w8 ? reinterpret_cast<uint32_t*>(w8 + L.off_bkey) : nullptr;
+  bp.bpos = w8 ? reinterpret_cast<int32_t*>(w8 + L.off_bpos) : nullptr;
+  bp.chunk_tokens = L.chunk_tokens;
+  bp.n_chunks = L.n_chunks;
 }
 }  // namespace
 
 size_t route_workspace_bytes(int n_kv_heads, int seq_len, int n_pool) { return route_layout(n_kv_heads, seq_len, n_pool).total; }
 
-uint16_t* route_score_hist(void* route_ws) { return reinterpret_cast<uint16_t*>(route_ws); }   // off_part0 == 0
-
 int launch_pool_scores(const float* mass, float* score, int n_kv_heads, int seq_len, int n_prefix, int pool_kernel,
-                       uint16_t* score_hist, hipStream_t stream) {
-  HistParams hp;
-  hp.src = mass; hp.score = score; hp.part = score_hist; hp.n = seq_len; hp.n_prefix = n_prefix; hp.kernel = pool_kernel;
-  hp.chunk_tokens = route_chunk_tokens(seq_len);
-  hp.n_chunks = (seq_len + hp.chunk_tokens - 1) / hp.chunk_tokens;
-  VEC_LAUNCH(K_POOL, route_hist_kernel<true>, dim3(hp.n_chunks, n_kv_heads), dim3(HT), 0, stream, hp);
+                       void* route_ws, hipStream_t stream) {
+  const RouteLayout L = route_layout(n_kv_heads, seq_len, 0);      // the bucket areas do not depend on the pool size
+  BucketParams bp;
+  bp.src = mass; bp.score = score; bp.n = seq_len; bp.n_prefix = n_prefix; bp.kernel = pool_kernel;
+  fill_bucket_params(bp, L, route_ws);
+  VEC_LAUNCH(K_POOL, route_bucket_kernel<true>, dim3(L.n_chunks, n_kv_heads), dim3(BT), 0, stream, bp);
   VEC_HIP(hipGetLastError());
   return VECTOR_OK;
 }
 
 int launch_route(int n_kv_heads, int seq_len, const float* score, const float* eps, int n_pool, int n_approx,
-                 uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx, void* ws, bool have_score_hist, hipStream_t stream) {
+                 uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx, void* ws, bool have_buckets, hipStream_t stream) {
   if (n_pool == 0) {
     const size_t total = (size_t)n_kv_heads * seq_len;
     VEC_LAUNCH(K_ROUTE, route_evict_all_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, tier, total);
@@ -730,9 +903,10 @@ int launch_route(int n_kv_heads, int seq_len, const float* score, const float* e
   p.slice = kTile;
   while ((n_pool + p.slice - 1) / p.slice > kMaxChunks) p.slice *= 2;
   p.n_slices = (n_pool + p.slice - 1) / p.slice;
-  uint16_t* part0 = reinterpret_cast<uint16_t*>(w8 + L.off_part0);
-  p.part0 = part0;
-  p.part1 = reinterpret_cast<uint16_t*>(w8 + L.off_part1);
+  p.table0 = reinterpret_cast<uint16_t*>(w8 + L.off_table0);
+  p.table1 = reinterpret_cast<uint16_t*>(w8 + L.off_table1);
+  p.bkey = reinterpret_cast<uint32_t*>(w8 + L.off_bkey);
+  p.bpos = reinterpret_cast<int32_t*>(w8 + L.off_bpos);
   p.pool_idx = reinterpret_cast<int32_t*>(w8 + L.off_idx);
   p.pool_key = reinterpret_cast<uint32_t*>(w8 + L.off_key);
   p.tier = tier; p.idx_retain = idx_retain; p.idx_approx = idx_approx;
@@ -741,14 +915,14 @@ int launch_route(int n_kv_heads, int seq_len, const float* score, const float* e
   VEC_HIP(set_max_lds(reinterpret_cast<const void*>(route_split_kernel), lds));
   const bool t_ = timing_enabled();
   if (t_) timing_begin(K_ROUTE, stream);             // the launches count as one routing step
-  if (!have_score_hist) {
-    HistParams hp;
-    hp.src = score; hp.score = nullptr; hp.part = part0; hp.n = seq_len; hp.n_prefix = seq_len; hp.kernel = 1;
-    hp.chunk_tokens = L.chunk_tokens; hp.n_chunks = L.n_chunks;
-    hipLaunchKernelGGL(route_hist_kernel<false>, dim3(L.n_chunks, n_kv_heads), dim3(HT), 0, stream, hp);
+  if (!have_buckets) {
+    BucketParams bp;
+    bp.src = score; bp.score = nullptr; bp.n = seq_len; bp.n_prefix = seq_len; bp.kernel = 1;
+    fill_bucket_params(bp, L, ws);
+    hipLaunchKernelGGL(route_bucket_kernel<false>, dim3(L.n_chunks, n_kv_heads), dim3(BT), 0, stream, bp);
   }
-  hipLaunchKernelGGL(route_pool_kernel, dim3(L.n_chunks, n_kv_heads), dim3(RT), lds, stream, p);
-  hipLaunchKernelGGL(route_split_kernel, dim3(p.n_slices, n_kv_heads), dim3(RT), lds, stream, p);
+  hipLaunchKernelGGL(route_pool_kernel, dim3(L.n_chunks, n_kv_heads), dim3(ST), lds, stream, p);
+  hipLaunchKernelGGL(route_split_kernel, dim3(p.n_slices, n_kv_heads), dim3(ST), lds, stream, p);
   if (t_) timing_end(K_ROUTE, stream);
   VEC_HIP(hipGetLastError());
   return VECTOR_OK;

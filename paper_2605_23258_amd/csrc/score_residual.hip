@@ -985,7 +985,7 @@ size_t score_workspace_bytes(const vector_shape& s) {
 template <typename T, int D>
 static int run_score_residual(const vector_shape& s, const void* q, const void* k, const void* v, const void* W,
                               float* score, float* eps, void* ws, hipStream_t stream, const RopeParams* rope,
-                              uint16_t* score_hist) {
+                              void* route_ws) {
   const bool do_mass = score != nullptr, do_res = eps != nullptr;
   Plan plan;
   int rc = make_plan<T, D>(s, do_mass, do_res, plan);
@@ -1024,7 +1024,7 @@ static int run_score_residual(const vector_shape& s, const void* q, const void* 
   VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k2), lds2));
   VEC_LAUNCH(K_MASS_RESIDUAL, k2, grid, dim3(kThreads), lds2, stream, p, rp);
   VEC_HIP(hipGetLastError());
-  if (do_mass) return launch_pool_scores(p.mass, score, s.n_kv_heads, s.seq_len, p.n_prefix, s.pool_kernel, score_hist, stream);
+  if (do_mass) return launch_pool_scores(p.mass, score, s.n_kv_heads, s.seq_len, p.n_prefix, s.pool_kernel, route_ws, stream);
   return VECTOR_OK;
 }
 
@@ -1054,13 +1054,13 @@ int launch_residual_probe(const vector_shape& s, const void* k, const void* v, c
 
 int launch_score_residual(const vector_shape& s, const void* q, const void* k, const void* v, const void* W,
                           float* score, float* eps, void* ws, hipStream_t stream, const RopeParams* rope,
-                          uint16_t* score_hist) {
+                          void* route_ws) {
   if (s.dtype == VECTOR_BF16) {
-    if (s.head_dim == 128) return run_score_residual<bf16_t, 128>(s, q, k, v, W, score, eps, ws, stream, rope, score_hist);
-    if (s.head_dim == 64) return run_score_residual<bf16_t, 64>(s, q, k, v, W, score, eps, ws, stream, rope, score_hist);
+    if (s.head_dim == 128) return run_score_residual<bf16_t, 128>(s, q, k, v, W, score, eps, ws, stream, rope, route_ws);
+    if (s.head_dim == 64) return run_score_residual<bf16_t, 64>(s, q, k, v, W, score, eps, ws, stream, rope, route_ws);
   } else if (s.dtype == VECTOR_F32) {
-    if (s.head_dim == 128) return run_score_residual<float, 128>(s, q, k, v, W, score, eps, ws, stream, rope, score_hist);
-    if (s.head_dim == 64) return run_score_residual<float, 64>(s, q, k, v, W, score, eps, ws, stream, rope, score_hist);
+    if (s.head_dim == 128) return run_score_residual<float, 128>(s, q, k, v, W, score, eps, ws, stream, rope, route_ws);
+    if (s.head_dim == 64) return run_score_residual<float, 64>(s, q, k, v, W, score, eps, ws, stream, rope, route_ws);
   } else {
     return VECTOR_ERR_DTYPE;
   }

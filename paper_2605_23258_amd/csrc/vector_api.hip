@@ -158,11 +158,11 @@ int vector_compress(const vector_shape* s, const void* q_win, const void* k, con
   if ((rc = check_ws(ws, ws_bytes, vector_compress_workspace_bytes(s, n_pool, n_approx)))) return rc;
   hipStream_t st = (hipStream_t)stream;
   void* route_ws = reinterpret_cast<unsigned char*>(ws) + (score_ws + 255) / 256 * 256;
-  // the scorer's pooling launch also builds the routing's first histogram
-  uint16_t* hist = n_pool > 0 ? vec::route_score_hist(route_ws) : nullptr;
-  if ((rc = vec::launch_score_residual(*s, q_win, k, v, W, score, eps, ws, st, nullptr, hist))) return rc;
+  // the scorer's pooling launch also builds the routing's buckets of score keys
+  void* buckets = n_pool > 0 ? route_ws : nullptr;
+  if ((rc = vec::launch_score_residual(*s, q_win, k, v, W, score, eps, ws, st, nullptr, buckets))) return rc;
   if ((rc = vec::launch_route(s->n_kv_heads, s->seq_len, score, eps, n_pool, n_approx, tier, idx_retain, idx_approx, route_ws,
-                              hist != nullptr, st)))
+                              buckets != nullptr, st)))
     return rc;
   return vec::launch_compact(*s, k, v, idx_retain, idx_approx, n_retain, n_approx, k_ret, v_ret, k_apx, cap_retain, st);
 }
