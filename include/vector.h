@@ -134,6 +134,22 @@ VECTOR_API int vector_route(int32_t n_kv_heads, int32_t seq_len, const float* sc
                  uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx,
                  void* ws, size_t ws_bytes, void* stream);
 
+/* vector_route for callers that cannot allocate device memory or size a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, outputs
+ * and errors as vector_route, without ws: the routing kernels' scratch is a device array of
+ * VECTOR_ROUTE_STATIC_SCRATCH_BYTES that lives inside the library (one copy per GPU, held until the
+ * process ends; its address is looked up on the first call on a device, on the device that is
+ * current then).  The call allocates and frees nothing.  VECTOR_ERR_WORKSPACE when
+ * the shape needs more scratch than the array holds (what vector_route would ask its caller for;
+ * 8 heads of 131072 tokens fit).  Every call on a GPU uses that GPU's one array: calls on different
+ * streams of one GPU must not overlap; calls on one stream are ordered and safe.  Nothing in the
+ * array has to be cleared between calls (every call rewrites what it reads). */
+#define VECTOR_ROUTE_STATIC_SCRATCH_BYTES (16u << 20)
+VECTOR_API size_t vector_route_static_scratch_bytes(void);
+VECTOR_API int vector_route_static(int32_t n_kv_heads, int32_t seq_len, const float* score, const float* eps,
+                        int32_t n_pool, int32_t n_approx,
+                        uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx, void* stream);
+
 /* Packed cache (Section 3.2: keys of the whole pool, values of retained tokens
  * only).  Row gather by the index lists:
  *   k_ret[h,s,:] = k[h, idx_retain[h,s], :],  v_ret likewise,

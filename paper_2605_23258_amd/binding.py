@@ -22,7 +22,7 @@ TIER_EVICT, TIER_APPROX, TIER_RETAIN = 0, 1, 2
 EXPORTS = (
     "vector_budget_counts", "vector_budget_counts_frac", "vector_pa_deploy", "vector_workspace_bytes",
     "vector_strerror", "vector_score", "vector_residual", "vector_score_residual", "vector_route",
-    "vector_compact", "vector_decode_attn", "vector_compress_workspace_bytes", "vector_compress",
+    "vector_route_static", "vector_route_static_scratch_bytes", "vector_compact", "vector_decode_attn", "vector_compress_workspace_bytes", "vector_compress",
     "vector_timing_enable", "vector_timing_kernels", "vector_timing_name", "vector_timing_read",
     "vector_probe_residual_mfma", "vector_probe_mfma_loop",
     "vector_residual_rope", "vector_score_residual_rope", "vector_decode_attn_rope",
@@ -99,6 +99,9 @@ def lib() -> C.CDLL:
         L.vector_residual.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, sz, vp]
         L.vector_score_residual.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.vector_route.argtypes = [i32, i32, vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
+        L.vector_route_static.argtypes = [i32, i32, vp, vp, i32, i32, vp, vp, vp, vp]
+        L.vector_route_static_scratch_bytes.argtypes = []
+        L.vector_route_static_scratch_bytes.restype = sz
         L.vector_compact.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, i32, i32, vp, vp, vp, i32, vp]
         L.vector_decode_attn.argtypes = [C.POINTER(Cache), vp, C.c_float, vp, i32, vp, sz, vp]
         L.vector_timing_enable.argtypes = [C.c_int]
@@ -196,6 +199,13 @@ def vector_route(n_kv_heads: int, seq_len: int, score, eps, n_pool: int, n_appro
     _check(lib().vector_route(n_kv_heads, seq_len, _ptr(score), _ptr(eps), n_pool, n_approx, _ptr(tier),
                               _ptr(idx_retain), _ptr(idx_approx), _ptr(ws), _nbytes(ws), _stream(stream)),
            "vector_route")
+
+
+def vector_route_static(n_kv_heads: int, seq_len: int, score, eps, n_pool: int, n_approx: int, tier, idx_retain,
+                        idx_approx, stream=None) -> None:
+    """vector_route on the library's own scratch array (no workspace, no allocation)."""
+    _check(lib().vector_route_static(n_kv_heads, seq_len, _ptr(score), _ptr(eps), n_pool, n_approx, _ptr(tier),
+                                     _ptr(idx_retain), _ptr(idx_approx), _stream(stream)), "vector_route_static")
 
 
 def vector_compact(shape: Shape, k, v, idx_retain, idx_approx, n_retain: int, n_approx: int, k_ret, v_ret, k_apx,

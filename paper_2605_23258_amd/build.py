@@ -8,7 +8,7 @@ import sys
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libvector.so")
-SOURCES = ["vector_api.hip", "score_residual.hip", "route_compact.hip", "decode_attn.hip", "calibrate.hip", "distortion.hip", "key_diversity.hip", "timing.hip"]
+SOURCES = ["vector_api.hip", "score_residual.hip", "route_compact.hip", "route_static.hip", "decode_attn.hip", "calibrate.hip", "distortion.hip", "key_diversity.hip", "timing.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
