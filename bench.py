@@ -2,16 +2,20 @@
 """Benchmark of the VECTOR hot path on one MI355X.
 
 One step = one full prefill compression pass of the 32-layer, 32k-token workload
-(score + residual, routing, compaction, layer by layer), inputs resident in HBM.
-The decode-attention leg (batch 16 over compressed 32k caches, 256 steps) is timed
-in the same run and reported in the same JSON line, as is the CPU oracle on a
-bounded sample of the compression workload.
+(score + residual, routing, compaction), strictly layer by layer on one stream, inputs
+resident in HBM.  The same JSON line carries: per-kernel durations (HIP events on the launch
+stream), the roofline of the longest kernel and of the two streaming kernels together, the
+matrix-core figures of the contractions as they run, the single-layer 8k and 128k workloads,
+the decode-attention leg (batch 16 over compressed 32k caches, 256 steps), peaks measured
+in the same run (device copy, register-only MFMA loop), and the CPU oracle on a bounded sample
+of the compression workload (single-threaded and on all threads).
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 from concurrent.futures import ThreadPoolExecutor
@@ -30,33 +34,62 @@ def log(msg: str) -> None:
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
-def blas_single_thread():
-    """Input generation runs one layer per worker thread: keep BLAS from oversubscribing the cores."""
+def blas_threads(n):
     try:
         from threadpoolctl import threadpool_limits
-        return threadpool_limits(limits=1)
+        return threadpool_limits(limits=n)
     except Exception:
         import contextlib
         return contextlib.nullcontext()
 
 
 def compress_bytes_per_token_head(cfg) -> dict:
-    """Algorithmic HBM bytes per token-head of each kernel of the compression pass
-    (bf16, d=128): what a kernel has to read and write once, not what it re-reads."""
+    """Algorithmic HBM bytes per token-head of each kernel of the compression pass: what has to be
+    read and written once.  K is counted once across the two softmax passes (in the first); the
+    second streaming read of K that the two-pass softmax makes is not algorithmic and shows up
+    under `executed`."""
     esz = 2 if cfg.dtype == "bf16" else 4
     row = cfg.head_dim * esz
     n_r, n_a, n_p = cfg.counts()
     f_p, f_r = n_p / cfg.seq_len, n_r / cfg.seq_len
-    return {
+    alg = {
         "score_stats": row,                       # read K
-        "mass_residual": 2 * row + 8,             # read K (again) and V, write mass and eps
+        "mass_residual": row + 8,                 # read V, write mass and eps (K again: not algorithmic)
         "pool_scores": 8,                         # read mass, write score
         "route": 8 + 1 + 8 * f_p,                 # read score, eps; write tier and index lists
         "gather_rows": 2 * row * (f_p + f_r),     # read and write pool K rows and retained V rows
-        # the whole pass, counting K and V once: the second streaming read of K that the
-        # two-pass softmax makes is not algorithmic
-        "pass": 2 * row + 8 + 8 + 1 + 8 * f_p + 2 * row * (f_p + f_r),
     }
+    alg["pass"] = sum(alg.values())
+    alg["score_residual_pair"] = alg["score_stats"] + alg["mass_residual"]
+    executed = dict(alg)
+    executed["mass_residual"] = 2 * row + 8
+    executed["pass"] = alg["pass"] + row
+    return {"algorithmic": alg, "executed": executed}
+
+
+def profile_value(fname: str, key: str):
+    """A figure from a committed rocprofv3 summary under profiles/ (two columns: name, value)."""
+    path = os.path.join(ROOT, "profiles", fname)
+    if os.path.exists(path):
+        for line in open(path):
+            parts = line.split()
+            if len(parts) >= 2 and parts[0] == key:
+                try:
+                    return float(parts[1])
+                except ValueError:
+                    return None
+    return None
+
+
+def timed(fn, torch, iters):
+    """Wall-clock seconds per call of fn, device idle before and after."""
+    fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(iters):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / iters
 
 
 def main() -> None:
@@ -68,13 +101,16 @@ def main() -> None:
     ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-layers", type=int, default=6)
+    ap.add_argument("--no-sweep", action="store_true", help="skip the single-layer 8k / 128k workloads and the measured peaks")
+    ap.add_argument("--cpu-sample-layers", type=int, default=24)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (reference kernel for scaling HBM counters)")
     ap.add_argument("--extras", action="store_true",
                     help="also time the entry points beyond the benchmark workload (post-RoPE variants, calibration, diagnostics)")
-    ap.add_argument("--streams", type=int, default=3,
-                    help="HIP streams the layers are spread over (layers are independent)")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="HIP streams the layers of the timed region are spread over (1 = layer by layer, the workload as stated)")
+    ap.add_argument("--overlap-streams", type=int, default=3,
+                    help="also report the pass with the layers spread over this many streams (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -103,23 +139,23 @@ def main() -> None:
     def gen(layer):
         li = wl.make_layer(cfg, layer)
         return {k: getattr(li, k) for k in ("q_win", "k", "v", "w_cal")}
-    with blas_single_thread(), ThreadPoolExecutor(workers) as ex:
+    with blas_threads(1), ThreadPoolExecutor(workers) as ex:
         host_layers = list(ex.map(gen, range(cfg.layers)))
     layers = [{k: pl.to_device(v, dev) for k, v in hl.items()} for hl in host_layers]
     log(f"generated {cfg.layers} layers of K/V [{H},{n},{d}] {cfg.dtype} in {time.time() - t0:.1f}s")
-    # Layers are independent, so consecutive layers go to different streams (each with its own
-    # workspace): the routing kernel of one layer, which occupies 8 CUs, and the launch ramps
-    # of the streaming kernels overlap with the next layer's work.
-    n_streams = max(1, args.streams)
-    streams = [torch.cuda.Stream(device=dev) for _ in range(n_streams)]
-    wss = [pl.alloc_workspace(vb.vector_workspace_bytes(shape, n_p, n_a, 1), dev) for _ in range(n_streams)]
+    max_streams = max(1, args.streams, args.overlap_streams)
+    streams = [torch.cuda.Stream(device=dev) for _ in range(max_streams)]
+    ws_bytes = vb.vector_compress_workspace_bytes(shape, n_p, n_a)
+    wss = [pl.alloc_workspace(ws_bytes, dev) for _ in range(max_streams)]
     outs = [pl.alloc_outputs(shape, n_p, n_a, n_r, torch.bfloat16, dev) for _ in range(cfg.layers)]
     torch.cuda.synchronize()
 
-    def step():
-        for i, (L, o) in enumerate(zip(layers, outs)):
-            pl.compress_layer(shape, L["q_win"], L["k"], L["v"], L["w_cal"], n_p, n_a, o, wss[i % n_streams],
-                              stream=streams[i % n_streams])
+    def make_step(n_streams):
+        def step():
+            for i, (L, o) in enumerate(zip(layers, outs)):
+                pl.compress_layer(shape, L["q_win"], L["k"], L["v"], L["w_cal"], n_p, n_a, o, wss[i % n_streams],
+                                  stream=streams[i % n_streams], one_call=True)
+        return step
 
     if args.copy_calibration:                  # known traffic: 256 MiB read, 256 MiB written per copy
         src = torch.empty(128 * 1024 * 1024, dtype=torch.bfloat16, device=dev).normal_()
@@ -128,6 +164,7 @@ def main() -> None:
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    step = make_step(max(1, args.streams))
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -138,73 +175,101 @@ def main() -> None:
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
     tokens_per_s = cfg.layers * n * args.steps / elapsed
-    log(f"compression pass: {ms_per_step:.3f} ms/step, {tokens_per_s / 1e6:.2f} M KV tokens/s")
+    log(f"compression pass ({max(1, args.streams)} stream): {ms_per_step:.3f} ms/step, {tokens_per_s / 1e6:.2f} M KV tokens/s")
 
-    # ---- per-kernel durations over the same steps, HIP events on the launch stream.  The
-    # layers run on one stream here: a duration measured while another layer's kernels share
-    # the chip says little about the kernel itself ----
-    def step_one_stream():
-        for L, o in zip(layers, outs):
-            pl.compress_layer(shape, L["q_win"], L["k"], L["v"], L["w_cal"], n_p, n_a, o, wss[0], stream=streams[0])
+    overlap = None
+    if args.overlap_streams > 1:               # named extra: consecutive layers' passes allowed to overlap
+        ostep = make_step(args.overlap_streams)
+        dt = timed(ostep, torch, max(3, args.steps // 2))
+        overlap = {"streams": args.overlap_streams, "ms_per_step": round(dt * 1e3, 4),
+                   "KV_tokens_per_s": round(cfg.layers * n / dt, 1),
+                   "note": "layers round-robin over several streams; not the headline: the workload runs layer by layer"}
+        log(f"overlapped: {overlap}")
+
+    # ---- per-kernel durations over the same steps, HIP events on the launch stream ----
     vb.vector_timing_enable(True)
+    one = make_step(1)
     for _ in range(args.steps):
-        step_one_stream()
+        one()
     torch.cuda.synchronize()
     timing = vb.vector_timing_read()
     vb.vector_timing_enable(False)
     bpt = compress_bytes_per_token_head(cfg)
+    alg, executed = bpt["algorithmic"], bpt["executed"]
+    units = H * n
     kernels = {}
     for name, (ms, cnt) in timing.items():
         if cnt:
             avg_us = ms / cnt * 1e3
             kernels[name] = {"avg_us": round(avg_us, 2), "launches": cnt}
-            if name in bpt:
-                kernels[name]["alg_GBs"] = round(bpt[name] * H * n / (avg_us * 1e-6) / 1e9, 1)
-    # The roofline kernel is the longest of the kernels that occupy the whole chip.  The routing
-    # kernel is listed with the others, but it runs on 8 workgroups (one per KV head) next to the
-    # following layer's streaming kernels and moves 13 bytes per token: no bandwidth bound applies.
-    chip_wide = [k for k in ("score_stats", "mass_residual", "gather_rows", "pool_scores") if k in kernels]
-    dominant = max(chip_wide, key=lambda k: kernels[k]["avg_us"])
-    dom_bytes = bpt[dominant] * H * n
-    dom_gbs = dom_bytes / (kernels[dominant]["avg_us"] * 1e-6) / 1e9
+            if name in alg:
+                kernels[name]["alg_GBs"] = round(alg[name] * units / (avg_us * 1e-6) / 1e9, 1)
     sum_us = sum(v["avg_us"] for v in kernels.values())
-    pass_bytes = bpt["pass"] * H * n
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
-    if os.path.exists(tpath):                  # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain copy
-        for line in open(tpath):
-            parts = line.split()
-            if len(parts) == 2 and parts[0] == dominant:
-                traffic = int(parts[1])
+    # The roofline kernel is the longest kernel of the pass, whichever it is.
+    dominant = max(kernels, key=lambda k: kernels[k]["avg_us"])
+    dom_bytes = alg[dominant] * units
+    dom_gbs = dom_bytes / (kernels[dominant]["avg_us"] * 1e-6) / 1e9
+    pass_bytes = alg["pass"] * units
+    pair_us = kernels.get("score_stats", {}).get("avg_us", 0.0) + kernels.get("mass_residual", {}).get("avg_us", 0.0)
+    pair_bytes = alg["score_residual_pair"] * units
+    traffic = profile_value("hbm_traffic.txt", dominant)
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(dom_gbs, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(dom_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
-                "bytes_per_launch": int(dom_bytes), "avg_us": kernels[dominant]["avg_us"],
+                "unit": "GB/s", "frac": round(dom_gbs / HBM_PEAK_GBS, 4),
+                "traffic": int(traffic) if traffic else None,
+                "traffic_source": "profiles/hbm_traffic.txt: rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE of a committed profile run, not measured in this run",
+                "bytes_per_launch": int(dom_bytes), "executed_bytes_per_launch": int(executed[dominant] * units),
+                "avg_us": kernels[dominant]["avg_us"],
+                "accounting": "algorithmic bytes, K counted once across the two softmax passes",
+                "score_residual_pair": {"kernels": ["score_stats", "mass_residual"], "bytes_per_layer": int(pair_bytes),
+                                        "us_per_layer": round(pair_us, 2),
+                                        "achieved": round(pair_bytes / (pair_us * 1e-6) / 1e9, 1) if pair_us else None,
+                                        "frac": round(pair_bytes / (pair_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if pair_us else None},
                 "pass_alg_bytes_per_layer": int(pass_bytes),
                 "pass_frac_of_hbm_peak": round(pass_bytes * cfg.layers / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-    # MFMA work of the pass (both softmax passes and the residual contraction)
-    G = cfg.group
-    flops_layer = H * n * (2 * 2 * G * cfg.window * d + 2 * d * d)
-    mfma_tflops = flops_layer * cfg.layers / (ms_per_step * 1e-3) / 1e12
     log(f"kernels: {json.dumps(kernels)} (sum {sum_us:.1f} us per layer)")
+
+    # ---- matrix cores: the contractions as they run inside the two streaming kernels ----
+    G = cfg.group
+    flops_exec = units * (2 * 2 * G * cfg.window * d + 2 * d * d)      # both softmax passes and the residual
+    flops_alg = units * (2 * G * cfg.window * d + 2 * d * d)           # one Q K^T and K W
+    mfma_run = flops_exec / (pair_us * 1e-6) / 1e12 if pair_us else None
+    intensity = flops_alg / pass_bytes                                  # flop per algorithmic byte of the pass
+    attainable = min(MFMA_BF16_PEAK_TFLOPS, intensity * HBM_PEAK_GBS / 1e3)
 
     # The reconstruction contraction with memory out of the picture: the residual kernel re-runs
     # each tile's arithmetic `repeat` times on operands it already holds; the time added per
     # extra repeat is one pass of the contraction code at the rate the matrix cores sustain.
     def probe_ms(repeat, launches=10):
-        x = layers[0]
-        o = outs[0]
-        vb.vector_probe_residual_mfma(shape, x["k"], x["v"], x["w_cal"], o.eps, repeat)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(launches):
-            vb.vector_probe_residual_mfma(shape, x["k"], x["v"], x["w_cal"], o.eps, repeat)
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / launches * 1e3
+        x, o = layers[0], outs[0]
+        return timed(lambda: vb.vector_probe_residual_mfma(shape, x["k"], x["v"], x["w_cal"], o.eps, repeat), torch, launches) * 1e3
     r_hi = 17
     t_lo, t_hi = probe_ms(1), probe_ms(r_hi)
-    res_flops = H * n * 2 * d * d
-    iso_tflops = res_flops / ((t_hi - t_lo) / (r_hi - 1) * 1e-3) / 1e12
+    iso_tflops = units * 2 * d * d / ((t_hi - t_lo) / (r_hi - 1) * 1e-3) / 1e12
     log(f"residual contraction probe: repeat 1 {t_lo * 1e3:.1f} us, repeat {r_hi} {t_hi * 1e3:.1f} us -> {iso_tflops:.0f} TFLOP/s isolated")
+    mfma = {"contraction_kernels_TFLOPs": round(mfma_run, 1) if mfma_run else None, "peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS,
+            "frac": round(mfma_run / MFMA_BF16_PEAK_TFLOPS, 4) if mfma_run else None,
+            "what": "executed flops of score_stats + mass_residual (both Q K^T passes and K W) over their summed durations",
+            "whole_pass_TFLOPs": round(flops_exec * cfg.layers / (ms_per_step * 1e-3) / 1e12, 1),
+            "intensity_flop_per_alg_byte": round(intensity, 1),
+            "attainable_TFLOPs": round(attainable, 1),
+            "attainable_what": "min(bf16 peak, algorithmic flops per algorithmic byte of the pass x 8 TB/s)",
+            "frac_of_attainable": round(flops_alg / (pair_us * 1e-6) / 1e12 / attainable, 4) if pair_us else None,
+            "matrix_pipe_busy_pct": {"score_stats": profile_value("sq_busy.txt", "score_stats_mfma_busy_pct"),
+                                     "mass_residual": profile_value("sq_busy.txt", "mass_residual_mfma_busy_pct"),
+                                     "source": "profiles/sq_busy.txt: rocprofv3 --pmc SQ counters of a committed profile run"},
+            "residual_contraction_isolated_TFLOPs": round(iso_tflops, 1),
+            "residual_contraction_isolated_frac": round(iso_tflops / MFMA_BF16_PEAK_TFLOPS, 4)}
+
+    sweep = None
+    if not args.no_sweep:
+        sweep = run_sweep(args, vb, dg, pl, torch, np, dev, workers)
+        if sweep.get("measured_peaks", {}).get("mfma_loop_TFLOPs") and mfma_run:
+            mfma["frac_of_measured_mfma_loop"] = round(mfma_run / sweep["measured_peaks"]["mfma_loop_TFLOPs"], 4)
+        cp = sweep.get("measured_peaks", {}).get("device_copy_GBs")
+        if cp:
+            roofline["frac_of_measured_copy"] = round(dom_gbs / cp, 4)
+            roofline["score_residual_pair"]["frac_of_measured_copy"] = round(roofline["score_residual_pair"]["achieved"] / cp, 4)
+            roofline["pass_frac_of_measured_copy"] = round(pass_bytes * cfg.layers / (ms_per_step * 1e-3) / 1e9 / cp, 4)
 
     # ---- decode attention over compressed caches ----
     decode = None
@@ -214,24 +279,7 @@ def main() -> None:
     # ---- CPU oracle on a bounded sample of the same workload ----
     cpu = None
     if not args.no_cpu_baseline:
-        from oracle import vector_oracle as vo
-        try:
-            from threadpoolctl import threadpool_info
-            blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-        except Exception:
-            blas_threads = 1
-        ns = min(args.cpu_sample_layers, cfg.layers)
-        t0 = time.perf_counter()
-        for hl in host_layers[:ns]:
-            wide = {k: dg.widen(v) for k, v in hl.items()}
-            s = vo.score(wide["q_win"], wide["k"], cfg.window, cfg.pool_kernel)
-            e = vo.residual(wide["k"], wide["v"], wide["w_cal"])
-            _, ir, ia = vo.route(s, e, n_p, n_a)
-            vo.compact(hl["k"], hl["v"], ir, ia)
-        dt = time.perf_counter() - t0
-        cpu = {"value": round(ns * n / dt, 1), "unit": "KV tokens/s", "cores": int(blas_threads), "kind": "oracle",
-               "sample": f"{ns} of {cfg.layers} layers of the same workload, {dt:.1f}s (numpy fp64; BLAS threads as listed, Python loops single-threaded)"}
-        log(f"cpu oracle: {cpu}")
+        cpu = run_cpu_baseline(args, cfg, host_layers, dg, n_p, n_a)
 
     extras = None
     if args.extras:
@@ -242,21 +290,110 @@ def main() -> None:
         "metric": "KV tokens compressed/sec (prefill pass)", "value": round(tokens_per_s, 1), "unit": "KV tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"cfg3: {cfg.layers}-layer compression pass, n={n}, Hq/Hkv={cfg.n_q_heads}/{H}, d={d}, "
+        "config": {"workload": f"cfg3: {cfg.layers}-layer compression pass, layer by layer, n={n}, Hq/Hkv={cfg.n_q_heads}/{H}, d={d}, "
                                f"window={cfg.window}, pool={cfg.pool_kernel}, retain/approx={n_r}/{n_a} per head",
-                   "seed": dg.MASTER_SEED, "streams": n_streams},
+                   "seed": dg.MASTER_SEED, "streams": max(1, args.streams)},
         "roofline": roofline,
         "kernels": kernels,
-        "mfma": {"achieved_TFLOPs": round(mfma_tflops, 1), "peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS,
-                 "frac": round(mfma_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
-                 "residual_contraction_isolated_TFLOPs": round(iso_tflops, 1),
-                 "residual_contraction_isolated_frac": round(iso_tflops / MFMA_BF16_PEAK_TFLOPS, 4)},
+        "mfma": mfma,
+        "overlapped": overlap,
+        "workloads": sweep,
         "decode": decode,
         "cpu_baseline": cpu,
     }
     if extras is not None:
         line["extras"] = extras
     print(json.dumps(line), flush=True)
+
+
+def run_cpu_baseline(args, cfg, host_layers, dg, n_p, n_a):
+    """The oracle as it stands on the host cores: all BLAS threads on most layers, one thread on a few."""
+    from oracle import vector_oracle as vo
+    try:
+        from threadpoolctl import threadpool_info
+        n_threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        n_threads = 1
+    n = cfg.seq_len
+
+    def run(layers_):
+        t0 = time.perf_counter()
+        for hl in layers_:
+            wide = {k: dg.widen(v) for k, v in hl.items()}
+            s = vo.score(wide["q_win"], wide["k"], cfg.window, cfg.pool_kernel)
+            e = vo.residual(wide["k"], wide["v"], wide["w_cal"])
+            _, ir, ia = vo.route(s, e, n_p, n_a)
+            vo.compact(hl["k"], hl["v"], ir, ia)
+        return time.perf_counter() - t0
+    ns = min(args.cpu_sample_layers, cfg.layers)
+    dt_all = run(host_layers[:ns])
+    n1 = min(8, cfg.layers)
+    with blas_threads(1):
+        dt_one = run(host_layers[:n1])
+    cpu = {"value": round(ns * n / dt_all, 1), "unit": "KV tokens/s", "cores": int(n_threads), "kind": "oracle",
+           "sample": f"{ns} of {cfg.layers} layers of the same workload, {dt_all:.1f}s (numpy fp64; BLAS on {n_threads} threads, Python loops single-threaded)",
+           "single_thread": {"value": round(n1 * n / dt_one, 1), "unit": "KV tokens/s", "cores": 1,
+                             "sample": f"{n1} layers, {dt_one:.1f}s"},
+           "host_cpus": os.cpu_count()}
+    log(f"cpu oracle: {cpu}")
+    return cpu
+
+
+def run_sweep(args, vb, dg, pl, torch, np, dev, workers):
+    """The single-layer workloads (8k tokens, 128k tokens) and two peaks measured in this run."""
+    res = {}
+    for name, n_sets, iters in (("cfg2", 12, 240), ("cfg4", 1, 20)):
+        cfg = dg.CONFIGS[name]
+        n_r, n_a, n_p = cfg.counts()
+        shape = pl.shape_of(cfg)
+        with blas_threads(1), ThreadPoolExecutor(workers) as ex:
+            sets = list(ex.map(lambda i: wl.make_layer(cfg, i), range(n_sets)))
+        devs = [{k: pl.to_device(getattr(li, k), dev) for k in ("q_win", "k", "v", "w_cal")} for li in sets]
+        ws = pl.alloc_workspace(vb.vector_compress_workspace_bytes(shape, n_p, n_a), dev)
+        out = pl.alloc_outputs(shape, n_p, n_a, n_r, torch.bfloat16, dev)
+        state = {"i": 0}
+
+        def one():                             # rotate over distinct inputs so that nothing stays cached between calls
+            x = devs[state["i"] % n_sets]
+            state["i"] += 1
+            pl.compress_layer(shape, x["q_win"], x["k"], x["v"], x["w_cal"], n_p, n_a, out, ws, one_call=True)
+        for _ in range(n_sets):
+            one()
+        dt = timed(one, torch, iters)
+        vb.vector_timing_enable(True)
+        for _ in range(max(n_sets, 4)):
+            one()
+        torch.cuda.synchronize()
+        t = vb.vector_timing_read()
+        vb.vector_timing_enable(False)
+        alg = compress_bytes_per_token_head(cfg)["algorithmic"]
+        pass_bytes = alg["pass"] * cfg.n_kv_heads * cfg.seq_len
+        input_mb = n_sets * 2 * cfg.n_kv_heads * cfg.seq_len * cfg.head_dim * 2 / 1e6
+        res[name] = {"workload": f"{name}: 1 layer, n={cfg.seq_len}, window={cfg.window}, retain/approx={n_r}/{n_a} per head",
+                     "us_per_layer": round(dt * 1e6, 2), "KV_tokens_per_s": round(cfg.seq_len / dt, 1),
+                     "pass_alg_bytes": int(pass_bytes), "pass_frac_of_hbm_peak": round(pass_bytes / dt / 1e9 / HBM_PEAK_GBS, 4),
+                     "distinct_input_sets": n_sets, "distinct_input_MB": round(input_mb, 1),
+                     "note": "inputs rotate over sets larger than the 256 MB Infinity Cache" if n_sets > 1 else "one input set, larger than the 256 MB Infinity Cache",
+                     "kernels_us": {k: round(ms / c * 1e3, 2) for k, (ms, c) in t.items() if c}}
+        log(f"{name}: {res[name]}")
+        del devs, sets, out, ws
+        torch.cuda.empty_cache()
+    # measured peaks: a plain device-to-device copy (256 MiB read + 256 MiB written), a register-only MFMA loop
+    src = torch.empty(128 * 1024 * 1024, dtype=torch.bfloat16, device=dev).normal_()
+    dst = torch.empty_like(src)
+    dt = timed(lambda: dst.copy_(src), torch, 20)
+    copy_gbs = 2 * src.numel() * 2 / dt / 1e9
+    del src, dst
+    sink = torch.empty(262144, dtype=torch.float32, device=dev)
+    iters = 20000
+    flops = vb.vector_probe_mfma_loop(sink, iters)
+    dt = timed(lambda: vb.vector_probe_mfma_loop(sink, iters), torch, 5)
+    res["measured_peaks"] = {"device_copy_GBs": round(copy_gbs, 1), "device_copy_frac_of_hbm_peak": round(copy_gbs / HBM_PEAK_GBS, 4),
+                             "mfma_loop_TFLOPs": round(flops / dt / 1e12, 1),
+                             "mfma_loop_frac_of_bf16_peak": round(flops / dt / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                             "what": "256 MiB device-to-device copy (bytes read + written); 32x32x16 bf16 MFMA loop on register operands, 16 waves per CU"}
+    log(f"measured peaks: {res['measured_peaks']}")
+    return res
 
 
 def run_stacked(vb, pl, torch, dev, cfg, layers, n_p, n_a, n_r):
@@ -268,16 +405,10 @@ def run_stacked(vb, pl, torch, dev, cfg, layers, n_p, n_a, n_r):
     stack = {k: torch.cat([x[k] for x in layers], dim=0).contiguous() for k in ("q_win", "k", "v", "w_cal")}
     shape = vb.Shape(n_q_heads=Hq * L, n_kv_heads=H * L, head_dim=cfg.head_dim, seq_len=cfg.seq_len, window=cfg.window,
                      pool_kernel=cfg.pool_kernel, dtype=vb.VECTOR_BF16)
-    ws = pl.alloc_workspace(vb.vector_workspace_bytes(shape, n_p, n_a, 1), dev)
+    ws = pl.alloc_workspace(vb.vector_compress_workspace_bytes(shape, n_p, n_a), dev)
     out = pl.alloc_outputs(shape, n_p, n_a, n_r, torch.bfloat16, dev)
-    run = lambda: pl.compress_layer(shape, stack["q_win"], stack["k"], stack["v"], stack["w_cal"], n_p, n_a, out, ws)
-    run()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(5):
-        run()
-    torch.cuda.synchronize()
-    dt = (time.perf_counter() - t0) / 5
+    run = lambda: pl.compress_layer(shape, stack["q_win"], stack["k"], stack["v"], stack["w_cal"], n_p, n_a, out, ws, one_call=True)
+    dt = timed(run, torch, 5)
     vb.vector_timing_enable(True)
     run()
     torch.cuda.synchronize()
@@ -295,13 +426,7 @@ def run_extras(vb, dg, pl, torch, np, dev, cfg, shape, layer, out, ws, n_p, n_a)
     H, n, d = cfg.n_kv_heads, cfg.seq_len, cfg.head_dim
 
     def per_call_us(fn, calls=20):
-        fn()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(calls):
-            fn()
-        torch.cuda.synchronize()
-        return round((time.perf_counter() - t0) / calls * 1e6, 1)
+        return round(timed(fn, torch, calls) * 1e6, 1)
 
     res = {}
     inv_freq = dg.rotary_inv_freq(d, 500000.0)
@@ -364,21 +489,20 @@ def run_decode(args, vb, dg, pl, torch, np, dev, workers):
     steps = args.decode_steps
     cap = n_r + steps
     shape = pl.shape_of(cfg)
-    ws = pl.alloc_workspace(vb.vector_workspace_bytes(shape, n_p, n_a, B), dev)
+    ws = pl.alloc_workspace(max(vb.vector_workspace_bytes(shape, n_p, n_a, B), vb.vector_compress_workspace_bytes(shape, n_p, n_a)), dev)
     k_ret = torch.zeros((B, H, cap, d), dtype=torch.bfloat16, device=dev)
     v_ret = torch.zeros((B, H, cap, d), dtype=torch.bfloat16, device=dev)
     k_apx = torch.zeros((B, H, n_a, d), dtype=torch.bfloat16, device=dev)
     t0 = time.time()
-    with blas_single_thread(), ThreadPoolExecutor(workers) as ex:
+    with blas_threads(1), ThreadPoolExecutor(workers) as ex:
         seqs = list(ex.map(lambda b: wl.make_layer(cfg, 0, sub=b), range(B)))
     # the first sequence's map is used for every sequence: W belongs to the layer, not the sequence
     W = pl.to_device(seqs[0].w_cal, dev)
     scratch = pl.alloc_outputs(shape, n_p, n_a, 1, torch.bfloat16, dev)
     for b, li in enumerate(seqs):
         q_win, k, v = (pl.to_device(getattr(li, x), dev) for x in ("q_win", "k", "v"))
-        vb.vector_score_residual(shape, q_win, k, v, W, scratch.score, scratch.eps, ws)
-        vb.vector_route(H, n, scratch.score, scratch.eps, n_p, n_a, scratch.tier, scratch.idx_retain, scratch.idx_approx, ws)
-        vb.vector_compact(shape, k, v, scratch.idx_retain, scratch.idx_approx, n_r, n_a, k_ret[b], v_ret[b], k_apx[b], cap)
+        vb.vector_compress(shape, q_win, k, v, W, n_p, n_a, scratch.score, scratch.eps, scratch.tier, scratch.idx_retain,
+                           scratch.idx_approx, k_ret[b], v_ret[b], k_apx[b], cap, ws)
     torch.cuda.synchronize()
     log(f"decode: built {B} compressed caches ({n_r} retained + {n_a} approximated of {n}) in {time.time() - t0:.1f}s")
     qs, ks, vs = [], [], []
@@ -395,7 +519,7 @@ def run_decode(args, vb, dg, pl, torch, np, dev, workers):
     cache.k_apx, cache.W = k_apx.data_ptr(), W.data_ptr()
     scale = 1.0 / float(np.sqrt(d))
 
-    def loop(timed: bool):
+    def loop():
         length.fill_(n_r)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -408,24 +532,25 @@ def run_decode(args, vb, dg, pl, torch, np, dev, workers):
         torch.cuda.synchronize()
         return time.perf_counter() - t0
 
-    loop(False)                                     # warm-up
-    wall = loop(True)
+    loop()                                          # warm-up
+    wall = loop()
     # attention alone, back to back: every appended row is in place after the loops above, so
     # step s only needs its own live length (read from a precomputed table, no extra kernel)
     lengths = (torch.arange(steps, dtype=torch.int32, device=dev) + (n_r + 1))[:, None].expand(steps, B).contiguous()
     q_l, out_l, len_l = list(qs.unbind(0)), list(out.unbind(0)), [lengths[s].data_ptr() for s in range(steps)]
 
-    def attn_only():
+    def attn_only(c=cache):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for s in range(steps):
-            cache.len_retain = len_l[s]
-            vb.vector_decode_attn(cache, q_l[s], scale, out_l[s], ws)
+            c.len_retain = len_l[s]
+            vb.vector_decode_attn(c, q_l[s], scale, out_l[s], ws)
         torch.cuda.synchronize()
         return time.perf_counter() - t0
 
     attn_only()
-    attn_us = min(attn_only() for _ in range(3)) / steps * 1e6
+    runs = [attn_only() for _ in range(5)]
+    attn_us = statistics.median(runs) / steps * 1e6
     vb.vector_timing_enable(True)
     attn_only()
     timing = vb.vector_timing_read()
@@ -434,10 +559,28 @@ def run_decode(args, vb, dg, pl, torch, np, dev, workers):
     mean_appended = (steps + 1) / 2.0
     bytes_step = B * H * (n_p + n_r + 2 * mean_appended) * row + 2 * B * Hq * row
     gbs = bytes_step / (attn_us * 1e-6) / 1e9
+    # Reference point at equal footprint: plain binary eviction keeps (n_pool + n_retain) / 2 full
+    # key-value pairs per head in the same bytes; the same kernel with nothing approximated.
+    n_eq = (n_p + n_r) // 2
+    g = torch.Generator(device=dev).manual_seed(11)
+    k_eq = torch.randn((B, H, n_eq, d), generator=g, device=dev, dtype=torch.float32).bfloat16()
+    v_eq = torch.randn((B, H, n_eq, d), generator=g, device=dev, dtype=torch.float32).bfloat16()
+    cache_eq = vb.Cache(batch=B, n_q_heads=Hq, n_kv_heads=H, head_dim=d, dtype=vb.VECTOR_BF16, cap_retain=n_eq, n_approx=0)
+    len_eq = torch.full((B,), n_eq, dtype=torch.int32, device=dev)
+    cache_eq.len_retain, cache_eq.k_ret, cache_eq.v_ret = len_eq.data_ptr(), k_eq.data_ptr(), v_eq.data_ptr()
+    cache_eq.k_apx, cache_eq.W = None, W.data_ptr()
+
+    def eq_loop():
+        for s in range(steps):
+            vb.vector_decode_attn(cache_eq, q_l[s], scale, out_l[s], ws)
+    eq_us = statistics.median([timed(eq_loop, torch, 1) for _ in range(3)]) / steps * 1e6
     res = {"workload": f"cfg5: batch {B}, {Hq}/{H} heads, d={d}, {n_r} retained + {n_a} approximated per head of {n}, {steps} steps",
-           "attn_us_per_step": round(attn_us, 2), "alg_bytes_per_step": int(bytes_step), "achieved_GBs": round(gbs, 1),
+           "attn_us_per_step": round(attn_us, 2), "attn_us_per_step_runs": [round(r / steps * 1e6, 2) for r in runs],
+           "alg_bytes_per_step": int(bytes_step), "achieved_GBs": round(gbs, 1),
            "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
            "step_us_with_append": round(wall / steps * 1e6, 2),
+           "binary_eviction_equal_footprint": {"full_pairs_per_head": n_eq, "attn_us_per_step": round(eq_us, 2) if eq_us else None,
+                                               "note": f"VECTOR attends over {n_p} tokens per head in the bytes of {n_eq} full pairs"},
            "kernels": {k: round(timing[k][0] / max(timing[k][1], 1) * 1e3, 2) for k in ("decode_split", "decode_combine")}}
     log(f"decode: {res}")
     return res
