@@ -156,7 +156,10 @@ def test_errors_are_reported_before_any_launch():
     ("cfg2", dict(seq_len=4096, n_kv_heads=1, n_q_heads=4, pool_kernel=1)),
     ("cfg2", dict(seq_len=3000, n_kv_heads=1, n_q_heads=4, pool_kernel=13)),
     ("cfg1", dict(seq_len=1000, window=20, n_q_heads=6, n_kv_heads=2)),
-    ("cfg2", dict(seq_len=40000, n_kv_heads=1, n_q_heads=2, window=16)),           # chip-wide routing
+    ("cfg2", dict(seq_len=40000, n_kv_heads=1, n_q_heads=2, window=16)),           # several chunks per head
+    ("cfg2", dict(seq_len=2500, n_kv_heads=2, n_q_heads=8, f_approx=0.0)),          # nothing approximated
+    ("cfg2", dict(seq_len=2500, n_kv_heads=2, n_q_heads=8, f_retain=0.0)),          # nothing retained
+    ("cfg1", dict(seq_len=3000, head_dim=128, n_kv_heads=1, n_q_heads=2, window=8)),   # fp32 rows of 512 bytes
 ])
 def test_one_call_pass_equals_the_three_calls(base, over):
     cfg = dg.scaled(dg.CONFIGS[base], **over)
