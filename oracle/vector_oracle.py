@@ -144,9 +144,12 @@ def score_key_diversity(k: np.ndarray) -> np.ndarray:
     return (-(unit * anchor[:, None, :]).sum(axis=-1)).astype(np.float32)
 
 
-def pool_scores(mass: np.ndarray, window: int, pool_kernel: int) -> np.ndarray:
-    """Average pooling (stride 1, zero padding, divisor always the kernel size)
-    over the prefix columns [0, n - w); window columns get +inf."""
+def pool_scores(mass: np.ndarray, window: int, pool_kernel: int, pool_mode: str = "avg") -> np.ndarray:
+    """1-D pooling (stride 1, odd kernel, centred) over the prefix columns [0, n - w); window
+    columns get +inf.  "avg": zero padding, divisor always the kernel size.  "max": the largest
+    mass among the columns of the kernel that lie inside the prefix (mass is never negative, so
+    this equals padding with zeros)."""
+    assert pool_mode in ("avg", "max")
     n_kv, n = mass.shape
     n_prefix = n - window
     half = pool_kernel // 2
@@ -154,14 +157,17 @@ def pool_scores(mass: np.ndarray, window: int, pool_kernel: int) -> np.ndarray:
     for h in range(n_kv):
         for t in range(n_prefix):
             lo, hi = max(0, t - half), min(n_prefix, t + half + 1)
-            score[h, t] = mass[h, lo:hi].sum() / pool_kernel
+            if pool_mode == "avg":
+                score[h, t] = mass[h, lo:hi].sum() / pool_kernel
+            else:
+                score[h, t] = mass[h, lo:hi].max()
     return score
 
 
-def score(q_win: np.ndarray, k: np.ndarray, window: int, pool_kernel: int) -> np.ndarray:
+def score(q_win: np.ndarray, k: np.ndarray, window: int, pool_kernel: int, pool_mode: str = "avg") -> np.ndarray:
     """Importance score per KV head and token, float32 as the routing consumes it."""
     assert q_win.shape[1] == window
-    return pool_scores(attention_mass(q_win, k), window, pool_kernel).astype(np.float32)
+    return pool_scores(attention_mass(q_win, k), window, pool_kernel, pool_mode).astype(np.float32)
 
 
 # ----------------------------------------------------------------------------

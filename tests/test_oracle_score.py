@@ -154,6 +154,52 @@ def test_pooling_matches_library_convolution():
     assert np.isposinf(sc[:, 41 - w:]).all()
 
 
+# ---- the maximum-pooling variant ----
+def test_max_pooling_matches_library_filter_and_hand_values():
+    from scipy.ndimage import maximum_filter1d
+    rng = np.random.default_rng(19)
+    mass = rng.random((3, 41))
+    w = 6
+    for kern in (1, 3, 5, 7, 13):
+        sc = vo.pool_scores(mass, w, kern, "max")
+        for h in range(3):
+            ref = maximum_filter1d(mass[h, : 41 - w], size=kern, mode="constant", cval=0.0)
+            np.testing.assert_array_equal(sc[h, : 41 - w], ref)
+        assert np.isposinf(sc[:, 41 - w:]).all()
+    # by hand: kernel 3 over the prefix (2, 9, 4, 1, 7), one window column that must not leak in
+    hand = vo.pool_scores(np.array([[2.0, 9.0, 4.0, 1.0, 7.0, 100.0]]), 1, 3, "max")
+    assert hand[0, :5].tolist() == [9.0, 9.0, 9.0, 7.0, 7.0] and np.isposinf(hand[0, 5])
+
+
+def test_max_pooling_closed_forms():
+    n, w, kern = 30, 4, 7
+    half = kern // 2
+    # a unit impulse spreads over the kernel's width at full height (average pooling: height 1/k)
+    imp = np.zeros((1, n)); imp[0, 11] = 1.0
+    mx = vo.pool_scores(imp, w, kern, "max")[0, : n - w]
+    av = vo.pool_scores(imp, w, kern, "avg")[0, : n - w]
+    want = np.zeros(n - w); want[11 - half: 11 + half + 1] = 1.0
+    np.testing.assert_array_equal(mx, want)
+    np.testing.assert_allclose(av, want / kern, rtol=1e-15)
+    # an increasing sequence is shifted by half a kernel and clamped at the prefix's end
+    ramp = np.arange(n, dtype=np.float64)[None, :]
+    mx = vo.pool_scores(ramp, w, kern, "max")[0, : n - w]
+    np.testing.assert_array_equal(mx, np.minimum(np.arange(n - w) + half, n - w - 1))
+    # kernel 1 is the identity; the maximum dominates the average everywhere
+    rng = np.random.default_rng(23)
+    mass = rng.random((2, n))
+    np.testing.assert_array_equal(vo.pool_scores(mass, w, 1, "max")[:, : n - w], mass[:, : n - w])
+    assert (vo.pool_scores(mass, w, kern, "max")[:, : n - w] >= vo.pool_scores(mass, w, kern, "avg")[:, : n - w]).all()
+
+
+def test_score_passes_the_pool_mode_through():
+    q = _rand(41, 2, 3, 4)
+    k = _rand(42, 1, 20, 4)
+    mass = vo.attention_mass(q, k)
+    np.testing.assert_array_equal(vo.score(q, k, 3, 5, "max"), vo.pool_scores(mass, 3, 5, "max").astype(np.float32))
+    np.testing.assert_array_equal(vo.score(q, k, 3, 5), vo.pool_scores(mass, 3, 5, "avg").astype(np.float32))
+
+
 # ---- the query-agnostic key-diversity score ----
 def test_key_diversity_brute_force_and_invariances():
     rng = np.random.default_rng(31)
