@@ -48,6 +48,10 @@ typedef enum { VECTOR_F32 = 0, VECTOR_BF16 = 1 } vector_dtype;
 #define VECTOR_TIER_APPROX  1
 #define VECTOR_TIER_RETAIN  2
 
+/* how the base scorer smooths the attention mass along the token axis */
+#define VECTOR_POOL_AVG 0
+#define VECTOR_POOL_MAX 1
+
 /* One layer of one sequence. */
 typedef struct {
   int32_t n_q_heads;      /* Hq, a multiple of n_kv_heads                              */
@@ -55,9 +59,9 @@ typedef struct {
   int32_t head_dim;       /* d: 64 or 128                                              */
   int32_t seq_len;        /* n                                                         */
   int32_t window;         /* w: the observation window is the last w positions, 1<=w<=n */
-  int32_t pool_kernel;    /* odd k >= 1: average pooling, stride 1, zero pad, divisor k */
+  int32_t pool_kernel;    /* odd k >= 1: pooling window, stride 1                      */
   int32_t dtype;          /* vector_dtype of q, k, v, W; score and eps are always fp32 */
-  int32_t reserved;
+  int32_t pool_mode;      /* VECTOR_POOL_AVG (zero pad, divisor k) or VECTOR_POOL_MAX   */
   int64_t k_stride_head, k_stride_tok;   /* element strides of k [Hkv, n, d]; 0,0 = packed */
   int64_t v_stride_head, v_stride_tok;   /* element strides of v [Hkv, n, d]; 0,0 = packed */
   int64_t w_stride_head;                 /* element stride between per-head W; 0 with
@@ -90,7 +94,8 @@ VECTOR_API const char* vector_strerror(int code);
  *   mass[h,t]  = mean over the G = Hq/Hkv query heads of h and the w window rows
  *                of softmax_t( q . k_t / sqrt(d) ), causal (window row r sees
  *                keys <= n-w+r);
- *   score[h,t] = (1/k) sum_{|j|<=k/2, 0<=t+j<n-w} mass[h,t+j];
+ *   score[h,t] = (1/k) sum_{|j|<=k/2, 0<=t+j<n-w} mass[h,t+j]      (VECTOR_POOL_AVG), or
+ *   score[h,t] = max_{|j|<=k/2, 0<=t+j<n-w} mass[h,t+j]            (VECTOR_POOL_MAX);
  * tokens t >= n-w get +inf.
  * q_win: device [Hq, w, d] packed.  k: device, strides from shape.
  * score: device fp32 [Hkv, n] packed (output).
@@ -172,19 +177,61 @@ VECTOR_API int vector_compress(const vector_shape* shape, const void* q_win, con
                     int32_t* idx_retain, int32_t* idx_approx, void* k_ret, void* v_ret, void* k_apx,
                     int32_t cap_retain, void* ws, size_t ws_bytes, void* stream);
 
+/* The compression pass of one layer for a batch of sequences of unequal length (Section 3.2 applies
+ * per sequence: every sequence is scored, routed and packed on its own, with its own counts).
+ * Sizes are host arrays of `batch` entries; shape->seq_len is ignored.  With
+ * T_b = seq_len[0] + .. + seq_len[b-1], R_b and A_b the same running sums of n_pool - n_approx and of
+ * n_approx, and C_b that of cap_retain:
+ *   k, v        device, ragged along tokens: sequence b owns rows T_b .. T_b + seq_len[b] - 1 of every
+ *               head; strides from shape, packed (0, 0) meaning [Hkv, T, d] with T the total;
+ *   q_win       device [batch, Hq, w, d];  W as in vector_compress (shared by the sequences);
+ *   score, eps, tier   sequence after sequence: block b is [Hkv, seq_len[b]] and starts at element Hkv * T_b;
+ *   idx_retain  block b is [Hkv, n_pool[b] - n_approx[b]] at element Hkv * R_b, idx_approx block b is
+ *               [Hkv, n_approx[b]] at element Hkv * A_b; token indices count from the sequence's first row;
+ *   k_ret, v_ret   block b is [Hkv, cap_retain[b], d] at row Hkv * C_b;  k_apx block b is
+ *               [Hkv, n_approx[b], d] at row Hkv * A_b
+ * (the blocks of a vector_cache with per-sequence capacities, below).  Each sequence gives exactly
+ * what vector_compress gives for it alone.  Every sequence must satisfy vector_compress's
+ * conditions (window <= seq_len[b], n_approx[b] <= n_pool[b] <= seq_len[b],
+ * cap_retain[b] >= n_pool[b] - n_approx[b]); everything is validated before the first launch.
+ * The sequences are processed one after the other on `stream` and share ws:
+ * vector_compress_batch_workspace_bytes(shape, batch) bytes. */
+typedef struct {
+  int32_t batch;
+  const int32_t* seq_len;      /* host [batch] */
+  const int32_t* n_pool;       /* host [batch] */
+  const int32_t* n_approx;     /* host [batch] */
+  const int32_t* cap_retain;   /* host [batch] */
+} vector_batch;
+VECTOR_API size_t vector_compress_batch_workspace_bytes(const vector_shape* shape, const vector_batch* batch);
+VECTOR_API int vector_compress_batch(const vector_shape* shape, const vector_batch* batch, const void* q_win, const void* k,
+                          const void* v, const void* W, float* score, float* eps, uint8_t* tier,
+                          int32_t* idx_retain, int32_t* idx_approx, void* k_ret, void* v_ret, void* k_apx,
+                          void* ws, size_t ws_bytes, void* stream);
+
 /* ---- decode attention over packed caches -------------------------------- */
 
 typedef struct {
   int32_t batch, n_q_heads, n_kv_heads, head_dim;
   int32_t dtype;                  /* vector_dtype of the cache, q, W and out            */
-  int32_t cap_retain, n_approx;   /* uniform capacities                                 */
+  int32_t cap_retain, n_approx;   /* capacities: of every sequence, or (per-sequence
+                                     capacities below) the largest of the batch         */
   int32_t w_shared;               /* non-zero: W is one [d, d] for all heads            */
   const int32_t* len_retain;      /* device [batch]: live rows of the retained segment
-                                     (compressed + appended), 0 <= len <= cap_retain    */
+                                     (compressed + appended), 0 <= len <= capacity      */
   const void* k_ret;              /* device [batch, Hkv, cap_retain, d]                 */
   const void* v_ret;              /* device [batch, Hkv, cap_retain, d]                 */
   const void* k_apx;              /* device [batch, Hkv, n_approx, d]                   */
   const void* W;                  /* device [Hkv, d, d]                                 */
+  /* Per-sequence capacities (sequences compressed at their own lengths): all four null, or all
+   * four device arrays of `batch` entries.  Then sequence b's retained block is
+   * [Hkv, cap_retain_seq[b], d] starting at row ret_row_start[b] of k_ret / v_ret, its
+   * approximated block [Hkv, n_approx_seq[b], d] starting at row apx_row_start[b] of k_apx, with
+   * cap_retain and n_approx above then only steer how the work is split: give the largest of the batch. */
+  const int32_t* cap_retain_seq;
+  const int32_t* n_approx_seq;
+  const int64_t* ret_row_start;
+  const int64_t* apx_row_start;
 } vector_cache;
 
 /* One query token per sequence (Section 3.2 Step 3: discarded values are
@@ -236,7 +283,8 @@ typedef struct {
                                 must lie in [0, 2^24)                                   */
   const int32_t* positions;  /* device memory or NULL.  vector_*residual_rope: [n], the
                                 position of each row of k (NULL: the row index).
-                                vector_decode_attn_rope: [batch, Hkv, n_approx], the
+                                vector_decode_attn_rope: [batch, Hkv, n_approx] (one per
+                                row of k_apx, also with per-sequence capacities), the
                                 original position of each approximated row (NULL: the
                                 row index).                                             */
 } vector_rope;

@@ -14,6 +14,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(PKG_DIR, "libvector.so")
 
 VECTOR_F32, VECTOR_BF16 = 0, 1
+VECTOR_POOL_AVG, VECTOR_POOL_MAX = 0, 1
 VECTOR_DECODE_LITERAL = 1
 VECTOR_DECODE_OUT_F32 = 2
 VECTOR_OK, VECTOR_ERR_ARG, VECTOR_ERR_SHAPE, VECTOR_ERR_WORKSPACE, VECTOR_ERR_DTYPE, VECTOR_ERR_HIP = 0, -1, -2, -3, -4, -5
@@ -23,6 +24,7 @@ EXPORTS = (
     "vector_budget_counts", "vector_budget_counts_frac", "vector_pa_deploy", "vector_workspace_bytes",
     "vector_strerror", "vector_score", "vector_residual", "vector_score_residual", "vector_route",
     "vector_route_static", "vector_route_static_scratch_bytes", "vector_compact", "vector_decode_attn", "vector_compress_workspace_bytes", "vector_compress",
+    "vector_compress_batch_workspace_bytes", "vector_compress_batch",
     "vector_timing_enable", "vector_timing_kernels", "vector_timing_name", "vector_timing_read",
     "vector_probe_residual_mfma", "vector_probe_mfma_loop",
     "vector_residual_rope", "vector_score_residual_rope", "vector_decode_attn_rope",
@@ -42,7 +44,7 @@ class VectorError(RuntimeError):
 class Shape(C.Structure):
     _fields_ = [
         ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("seq_len", C.c_int32),
-        ("window", C.c_int32), ("pool_kernel", C.c_int32), ("dtype", C.c_int32), ("reserved", C.c_int32),
+        ("window", C.c_int32), ("pool_kernel", C.c_int32), ("dtype", C.c_int32), ("pool_mode", C.c_int32),
         ("k_stride_head", C.c_int64), ("k_stride_tok", C.c_int64),
         ("v_stride_head", C.c_int64), ("v_stride_tok", C.c_int64),
         ("w_stride_head", C.c_int64), ("w_shared", C.c_int32), ("reserved2", C.c_int32),
@@ -71,7 +73,21 @@ class Cache(C.Structure):
         ("dtype", C.c_int32), ("cap_retain", C.c_int32), ("n_approx", C.c_int32), ("w_shared", C.c_int32),
         ("len_retain", C.c_void_p), ("k_ret", C.c_void_p), ("v_ret", C.c_void_p), ("k_apx", C.c_void_p),
         ("W", C.c_void_p),
+        ("cap_retain_seq", C.c_void_p), ("n_approx_seq", C.c_void_p), ("ret_row_start", C.c_void_p),
+        ("apx_row_start", C.c_void_p),
     ]
+
+
+class Batch(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("seq_len", C.POINTER(C.c_int32)), ("n_pool", C.POINTER(C.c_int32)),
+                ("n_approx", C.POINTER(C.c_int32)), ("cap_retain", C.POINTER(C.c_int32))]
+
+
+def make_batch(seq_len, n_pool, n_approx, cap_retain):
+    """(Batch, keep-alive) from four host sequences of equal length."""
+    arrs = [(C.c_int32 * len(seq_len))(*[int(x) for x in a]) for a in (seq_len, n_pool, n_approx, cap_retain)]
+    assert len({len(a) for a in arrs}) == 1
+    return Batch(len(seq_len), *[C.cast(a, C.POINTER(C.c_int32)) for a in arrs]), arrs
 
 
 _lib = None
@@ -122,6 +138,9 @@ def lib() -> C.CDLL:
         L.vector_compress_workspace_bytes.argtypes = [C.POINTER(Shape), i32, i32]
         L.vector_compress_workspace_bytes.restype = sz
         L.vector_compress.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
+        L.vector_compress_batch_workspace_bytes.argtypes = [C.POINTER(Shape), C.POINTER(Batch)]
+        L.vector_compress_batch_workspace_bytes.restype = sz
+        L.vector_compress_batch.argtypes = [C.POINTER(Shape), C.POINTER(Batch), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.vector_score_key_diversity_workspace_bytes.argtypes = [C.POINTER(Shape)]
         L.vector_score_key_diversity_workspace_bytes.restype = sz
         L.vector_score_key_diversity.argtypes = [C.POINTER(Shape), vp, vp, vp, sz, vp]
@@ -305,6 +324,17 @@ def vector_compress(shape: Shape, q_win, k, v, W, n_pool: int, n_approx: int, sc
     _check(lib().vector_compress(C.byref(shape), _ptr(q_win), _ptr(k), _ptr(v), _ptr(W), n_pool, n_approx, _ptr(score),
                                  _ptr(eps), _ptr(tier), _ptr(idx_retain), _ptr(idx_approx), _ptr(k_ret), _ptr(v_ret),
                                  _ptr(k_apx), cap_retain, _ptr(ws), _nbytes(ws), _stream(stream)), "vector_compress")
+
+
+def vector_compress_batch_workspace_bytes(shape: Shape, batch: Batch) -> int:
+    return int(lib().vector_compress_batch_workspace_bytes(C.byref(shape), C.byref(batch)))
+
+
+def vector_compress_batch(shape: Shape, batch: Batch, q_win, k, v, W, score, eps, tier, idx_retain, idx_approx,
+                          k_ret, v_ret, k_apx, ws, stream=None) -> None:
+    _check(lib().vector_compress_batch(C.byref(shape), C.byref(batch), _ptr(q_win), _ptr(k), _ptr(v), _ptr(W), _ptr(score),
+                                       _ptr(eps), _ptr(tier), _ptr(idx_retain), _ptr(idx_approx), _ptr(k_ret), _ptr(v_ret),
+                                       _ptr(k_apx), _ptr(ws), _nbytes(ws), _stream(stream)), "vector_compress_batch")
 
 
 def vector_score_key_diversity_workspace_bytes(shape: Shape) -> int:

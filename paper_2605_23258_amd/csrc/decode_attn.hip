@@ -32,6 +32,9 @@ namespace {
 struct DecodeParams {
   const void* q; const void* k_ret; const void* v_ret; const void* k_apx; const void* W;
   const int32_t* len_retain;
+  // per-sequence capacities and first rows of the sequences' blocks (all null: uniform blocks)
+  const int32_t* cap_retain_seq; const int32_t* n_approx_seq;
+  const int64_t* ret_row_start; const int64_t* apx_row_start;
   void* out;
   float* part;            // [B, Hkv, S, 2*G + G*D] floats: m[G], l[G], acc[G][D]
   int B, Hq, Hkv, cap_retain, n_approx;
@@ -41,6 +44,27 @@ struct DecodeParams {
   int literal;            // approximated rows: rebuild v_hat = k W per row instead of (sum p k) W
   int out_f32;            // store the result as fp32 whatever the cache dtype
 };
+
+// Where the rows of one (sequence, KV head) lie: row offsets into k_ret / v_ret and into k_apx,
+// the live length of the retained segment and the length of the approximated one.
+struct SegmentRows { size_t ret_row0, apx_row0; int len_retain, n_approx; };
+__device__ __forceinline__ SegmentRows segment_rows(const DecodeParams& p, int b, int h) {
+  SegmentRows s;
+  int cap = p.cap_retain;
+  s.n_approx = p.n_approx;
+  if (p.cap_retain_seq) {
+    cap = max(p.cap_retain_seq[b], 0);
+    s.n_approx = max(p.n_approx_seq[b], 0);
+    s.ret_row0 = (size_t)p.ret_row_start[b] + (size_t)h * cap;
+    s.apx_row0 = (size_t)p.apx_row_start[b] + (size_t)h * s.n_approx;
+  } else {
+    const size_t bh = (size_t)b * p.Hkv + h;
+    s.ret_row0 = bh * cap;
+    s.apx_row0 = bh * s.n_approx;
+  }
+  s.len_retain = min(max(p.len_retain[b], 0), cap);
+  return s;
+}
 
 constexpr int DT_ = 256;          // threads per workgroup
 constexpr int DW = DT_ / kWave;   // waves
@@ -84,9 +108,9 @@ __global__ __launch_bounds__(DT_) void decode_split_kernel(DecodeParams p) {
   const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int grp = lane / LPR, piece = lane % LPR;
-  const int len_r = min(max(p.len_retain[b], 0), p.cap_retain);
+  const SegmentRows seg = segment_rows(p, b, h);
   const bool is_apx = split >= p.splits_ret;
-  const int seg_len = is_apx ? p.n_approx : len_r;
+  const int seg_len = is_apx ? seg.n_approx : seg.len_retain;
   const int n_sp = is_apx ? p.splits_apx : p.splits_ret;
   const int sp = is_apx ? split - p.splits_ret : split;
   // ranges are multiples of the workgroup's row step so that loads stay aligned to it
@@ -96,9 +120,9 @@ __global__ __launch_bounds__(DT_) void decode_split_kernel(DecodeParams p) {
   const int row_end = min(seg_len, (int)((int64_t)steps * (sp + 1) / n_sp) * kStepRows);
 
   const size_t bh = (size_t)b * p.Hkv + h;
-  const T* kseg = is_apx ? reinterpret_cast<const T*>(p.k_apx) + bh * p.n_approx * D
-                         : reinterpret_cast<const T*>(p.k_ret) + bh * p.cap_retain * D;
-  const T* vseg = reinterpret_cast<const T*>(p.v_ret) + bh * p.cap_retain * D;
+  const T* kseg = is_apx ? reinterpret_cast<const T*>(p.k_apx) + seg.apx_row0 * D
+                         : reinterpret_cast<const T*>(p.k_ret) + seg.ret_row0 * D;
+  const T* vseg = reinterpret_cast<const T*>(p.v_ret) + seg.ret_row0 * D;
 
   // this lane's slice of the G query rows, pre-scaled into the log2 domain
   float qf[G][E];
@@ -278,7 +302,7 @@ template <int D> struct MfmaDecodeTile {
 
 // ROPE: the cached keys carry rotary position embedding.  Logits use them as cached; the
 // rows that stand in for values of approximated tokens are the keys turned back by their
-// original positions (rp.positions [B, Hkv, n_approx]), written to the second tile as bf16.
+// original positions (rp.positions, one per row of k_apx), written to the second tile as bf16.
 // LITERAL: approximated rows are rebuilt one by one, v_hat = k W, before they are weighted.
 template <int D, int G, bool ROPE, bool LITERAL = false>
 __global__ __launch_bounds__(DT_, 2) void decode_split_mfma_kernel(DecodeParams p, RopeParams rp) {
@@ -295,9 +319,9 @@ __global__ __launch_bounds__(DT_, 2) void decode_split_mfma_kernel(DecodeParams 
   const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int l31 = lane & 31, half = lane >> 5;
-  const int len_r = min(max(p.len_retain[b], 0), p.cap_retain);
+  const SegmentRows seg = segment_rows(p, b, h);
   const bool is_apx = split >= p.splits_ret;
-  const int seg_len = is_apx ? p.n_approx : len_r;
+  const int seg_len = is_apx ? seg.n_approx : seg.len_retain;
   const int n_sp = is_apx ? p.splits_apx : p.splits_ret;
   const int sp = is_apx ? split - p.splits_ret : split;
   constexpr int kStepRows = DW * kTileRows;
@@ -306,9 +330,9 @@ __global__ __launch_bounds__(DT_, 2) void decode_split_mfma_kernel(DecodeParams 
   const int row_end = min(seg_len, (int)((int64_t)steps * (sp + 1) / n_sp) * kStepRows);
 
   const size_t bh = (size_t)b * p.Hkv + h;
-  const T* kseg = is_apx ? reinterpret_cast<const T*>(p.k_apx) + bh * p.n_approx * D
-                         : reinterpret_cast<const T*>(p.k_ret) + bh * p.cap_retain * D;
-  const T* vseg = reinterpret_cast<const T*>(p.v_ret) + bh * p.cap_retain * D;
+  const T* kseg = is_apx ? reinterpret_cast<const T*>(p.k_apx) + seg.apx_row0 * D
+                         : reinterpret_cast<const T*>(p.k_ret) + seg.ret_row0 * D;
+  const T* vseg = reinterpret_cast<const T*>(p.v_ret) + seg.ret_row0 * D;
 
   unsigned char* k_tile = dec_lds + wave * 2 * TL::kTileBytes;
   unsigned char* v_tile = k_tile + TL::kTileBytes;
@@ -332,7 +356,7 @@ __global__ __launch_bounds__(DT_, 2) void decode_split_mfma_kernel(DecodeParams 
   float m_run = kNegBig, l_run = 0.f;
 
   const int ld_row = lane / TL::kPieces, ld_piece = lane % TL::kPieces;
-  const int32_t* pos_seg = (ROPE && is_apx && rp.positions) ? rp.positions + bh * p.n_approx : nullptr;
+  const int32_t* pos_seg = (ROPE && is_apx && rp.positions) ? rp.positions + seg.apx_row0 : nullptr;
   // Which 16 bytes of the tile a lane brings in with its i-th load.  Normally 16 adjacent lanes
   // share a row.  For approximated rows that are to be un-rotated with pairs (x[i], x[i + d/2])
   // a lane instead takes both members of its pairs: loads 2u and 2u+1 bring pieces p and
@@ -790,6 +814,8 @@ int launch_decode_attn(const vector_cache& c, const void* q, float scale, void* 
   p.out_f32 = (flags & VECTOR_DECODE_OUT_F32) ? 1 : 0;
   if (p.literal && (rope || c.dtype != VECTOR_BF16)) return VECTOR_ERR_DTYPE;
   p.q = q; p.k_ret = c.k_ret; p.v_ret = c.v_ret; p.k_apx = c.k_apx; p.W = c.W; p.len_retain = c.len_retain;
+  p.cap_retain_seq = c.cap_retain_seq; p.n_approx_seq = c.n_approx_seq;
+  p.ret_row_start = c.ret_row_start; p.apx_row_start = c.apx_row_start;
   p.out = out; p.part = reinterpret_cast<float*>(ws);
   p.B = c.batch; p.Hq = c.n_q_heads; p.Hkv = c.n_kv_heads; p.cap_retain = c.cap_retain; p.n_approx = c.n_approx;
   // an approximated row costs its bytes; with the rotary un-rotation its sines and cosines make

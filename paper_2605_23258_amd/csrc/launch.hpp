@@ -65,7 +65,7 @@ size_t route_workspace_bytes(int n_kv_heads, int seq_len, int n_pool);
 // average pooling of the attention mass into the score; with a routing workspace (route_ws, sized by
 // route_workspace_bytes) also the routing's buckets of score keys (then launch_route is told so and
 // skips its own bucket launch)
-int launch_pool_scores(const float* mass, float* score, int n_kv_heads, int seq_len, int n_prefix, int pool_kernel,
+int launch_pool_scores(const float* mass, float* score, int n_kv_heads, int seq_len, int n_prefix, int pool_kernel, int pool_mode,
                        void* route_ws, hipStream_t stream);
 int launch_route(int n_kv_heads, int seq_len, const float* score, const float* eps, int n_pool, int n_approx,
                  uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx, void* ws, bool have_buckets, hipStream_t stream);

@@ -177,6 +177,7 @@ struct BucketParams {
   uint32_t* bkey;         // [H, n]: chunk c owns [c * chunk_tokens, ...), keys grouped by digit, highest first
   int32_t* bpos;          // [H, n]: the token each key belongs to
   int n, n_prefix, kernel, chunk_tokens, n_chunks;
+  int take_max;           // POOL: the window's largest mass instead of its sum over the kernel size
 };
 
 template <bool POOL>
@@ -214,7 +215,8 @@ __global__ __launch_bounds__(BT) void route_bucket_kernel(BucketParams p) {
       const int half = p.kernel / 2;
       if (vec4 && half <= EPT && t0 >= EPT && t0 + 2 * EPT <= p.n) {
         // the 12 mass values around the thread's four tokens in three loads; each window is
-        // summed in ascending token order, like the general loop below
+        // folded in ascending token order, like the general loop below (mass is never negative,
+        // so the maximum may start from zero)
         float m[3 * EPT];
 #pragma unroll
         for (int q = 0; q < 3; ++q) {
@@ -227,8 +229,8 @@ __global__ __launch_bounds__(BT) void route_bucket_kernel(BucketParams p) {
           float acc = 0.f;
 #pragma unroll
           for (int d = -EPT; d <= EPT; ++d)
-            if (d >= -half && d <= half && t + d < p.n_prefix) acc += m[EPT + j + d];
-          s[j] = (ok[j] && t < p.n_prefix) ? acc / (float)p.kernel : INFINITY;
+            if (d >= -half && d <= half && t + d < p.n_prefix) acc = p.take_max ? fmaxf(acc, m[EPT + j + d]) : acc + m[EPT + j + d];
+          s[j] = (ok[j] && t < p.n_prefix) ? (p.take_max ? acc : acc / (float)p.kernel) : INFINITY;
         }
       } else {
 #pragma unroll
@@ -238,8 +240,8 @@ __global__ __launch_bounds__(BT) void route_bucket_kernel(BucketParams p) {
           if (ok[j] && t < p.n_prefix) {
             const int lo = max(0, t - half), hi = min(p.n_prefix - 1, t + half);
             float acc = 0.f;
-            for (int i = lo; i <= hi; ++i) acc += src[i];
-            out = acc / (float)p.kernel;
+            for (int i = lo; i <= hi; ++i) acc = p.take_max ? fmaxf(acc, src[i]) : acc + src[i];
+            out = p.take_max ? acc : acc / (float)p.kernel;
           }
           s[j] = out;
         }
@@ -876,11 +878,11 @@ void fill_bucket_params(BucketParams& bp, const RouteLayout& L, void* route_ws) 
 
 size_t route_workspace_bytes(int n_kv_heads, int seq_len, int n_pool) { return route_layout(n_kv_heads, seq_len, n_pool).total; }
 
-int launch_pool_scores(const float* mass, float* score, int n_kv_heads, int seq_len, int n_prefix, int pool_kernel,
+int launch_pool_scores(const float* mass, float* score, int n_kv_heads, int seq_len, int n_prefix, int pool_kernel, int pool_mode,
                        void* route_ws, hipStream_t stream) {
   const RouteLayout L = route_layout(n_kv_heads, seq_len, 0);      // the bucket areas do not depend on the pool size
   BucketParams bp;
-  bp.src = mass; bp.score = score; bp.n = seq_len; bp.n_prefix = n_prefix; bp.kernel = pool_kernel;
+  bp.src = mass; bp.score = score; bp.n = seq_len; bp.n_prefix = n_prefix; bp.kernel = pool_kernel; bp.take_max = pool_mode == VECTOR_POOL_MAX;
   fill_bucket_params(bp, L, route_ws);
   VEC_LAUNCH(K_POOL, route_bucket_kernel<true>, dim3(L.n_chunks, n_kv_heads), dim3(BT), 0, stream, bp);
   VEC_HIP(hipGetLastError());

@@ -1024,7 +1024,7 @@ static int run_score_residual(const vector_shape& s, const void* q, const void* 
   VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k2), lds2));
   VEC_LAUNCH(K_MASS_RESIDUAL, k2, grid, dim3(kThreads), lds2, stream, p, rp);
   VEC_HIP(hipGetLastError());
-  if (do_mass) return launch_pool_scores(p.mass, score, s.n_kv_heads, s.seq_len, p.n_prefix, s.pool_kernel, route_ws, stream);
+  if (do_mass) return launch_pool_scores(p.mass, score, s.n_kv_heads, s.seq_len, p.n_prefix, s.pool_kernel, s.pool_mode, route_ws, stream);
   return VECTOR_OK;
 }
 

@@ -26,6 +26,7 @@ int check_shape(const vector_shape* s, bool need_window) {
   if (need_window) {
     if (s->window < 1 || s->window > s->seq_len) return VECTOR_ERR_SHAPE;
     if (s->pool_kernel < 1 || !(s->pool_kernel & 1)) return VECTOR_ERR_SHAPE;
+    if (s->pool_mode != VECTOR_POOL_AVG && s->pool_mode != VECTOR_POOL_MAX) return VECTOR_ERR_SHAPE;
   }
   return VECTOR_OK;
 }
@@ -167,6 +168,101 @@ int vector_compress(const vector_shape* s, const void* q_win, const void* k, con
   return vec::launch_compact(*s, k, v, idx_retain, idx_approx, n_retain, n_approx, k_ret, v_ret, k_apx, cap_retain, st);
 }
 
+namespace {
+
+// sequence b of a batch as a one-sequence problem: its shape (explicit strides, so that a packed
+// ragged [Hkv, T, d] keeps its head stride) and where its blocks start
+struct BatchItem {
+  vector_shape shape;
+  int64_t tok0, ret0, apx0, cap0;     // running sums of seq_len, n_retain, n_approx, cap_retain
+};
+
+int check_batch(const vector_shape* s, const vector_batch* bt) {
+  if (!s || !bt) return VECTOR_ERR_ARG;
+  if (bt->batch < 1 || !bt->seq_len || !bt->n_pool || !bt->n_approx || !bt->cap_retain) return VECTOR_ERR_ARG;
+  int64_t total = 0;
+  for (int b = 0; b < bt->batch; ++b) {
+    vector_shape t = *s;
+    t.seq_len = bt->seq_len[b];
+    const int rc = check_shape(&t, true);
+    if (rc) return rc;
+    const int n_pool = bt->n_pool[b], n_approx = bt->n_approx[b];
+    if (n_approx < 0 || n_pool < n_approx || n_pool > t.seq_len || bt->cap_retain[b] < n_pool - n_approx) return VECTOR_ERR_ARG;
+    total += t.seq_len;
+  }
+  if (total > ((int64_t)1 << 40)) return VECTOR_ERR_SHAPE;
+  return VECTOR_OK;
+}
+
+BatchItem batch_item(const vector_shape* s, const vector_batch* bt, int b, int64_t total_tokens, const BatchItem* prev) {
+  BatchItem it;
+  it.shape = *s;
+  it.shape.seq_len = bt->seq_len[b];
+  if (!it.shape.k_stride_tok) it.shape.k_stride_tok = s->head_dim;
+  if (!it.shape.k_stride_head) it.shape.k_stride_head = total_tokens * it.shape.k_stride_tok;
+  if (!it.shape.v_stride_tok) it.shape.v_stride_tok = s->head_dim;
+  if (!it.shape.v_stride_head) it.shape.v_stride_head = total_tokens * it.shape.v_stride_tok;
+  it.tok0 = prev ? prev->tok0 + bt->seq_len[b - 1] : 0;
+  it.ret0 = prev ? prev->ret0 + (bt->n_pool[b - 1] - bt->n_approx[b - 1]) : 0;
+  it.apx0 = prev ? prev->apx0 + bt->n_approx[b - 1] : 0;
+  it.cap0 = prev ? prev->cap0 + bt->cap_retain[b - 1] : 0;
+  return it;
+}
+
+}  // namespace
+
+size_t vector_compress_batch_workspace_bytes(const vector_shape* s, const vector_batch* bt) {
+  if (check_batch(s, bt) != VECTOR_OK) return 0;
+  size_t need = 0;
+  for (int b = 0; b < bt->batch; ++b) {
+    vector_shape t = *s;
+    t.seq_len = bt->seq_len[b];
+    const size_t one = vector_compress_workspace_bytes(&t, bt->n_pool[b], bt->n_approx[b]);
+    if (one > need) need = one;
+  }
+  return need;
+}
+
+int vector_compress_batch(const vector_shape* s, const vector_batch* bt, const void* q_win, const void* k, const void* v,
+                          const void* W, float* score, float* eps, uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx,
+                          void* k_ret, void* v_ret, void* k_apx, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_batch(s, bt);
+  if (rc) return rc;
+  if (!q_win || !k || !v || !W || !score || !eps || !tier) return VECTOR_ERR_ARG;
+  if (!aligned16(q_win) || !aligned16(k) || !aligned16(v) || !aligned16(W)) return VECTOR_ERR_ARG;
+  int64_t total = 0, total_ret = 0, total_apx = 0;
+  for (int b = 0; b < bt->batch; ++b) {
+    total += bt->seq_len[b];
+    total_ret += bt->n_pool[b] - bt->n_approx[b];
+    total_apx += bt->n_approx[b];
+  }
+  if (total_ret > 0 && (!idx_retain || !k_ret || !v_ret || !aligned16(k_ret) || !aligned16(v_ret))) return VECTOR_ERR_ARG;
+  if (total_apx > 0 && (!idx_approx || !k_apx || !aligned16(k_apx))) return VECTOR_ERR_ARG;
+  if ((rc = check_ws(ws, ws_bytes, vector_compress_batch_workspace_bytes(s, bt)))) return rc;
+  // One sequence after the other on the stream, through the one-sequence pass: the launches of
+  // consecutive sequences follow each other without a host wait, and the workspace is reused in
+  // stream order.
+  const size_t esz = s->dtype == VECTOR_BF16 ? 2 : 4;
+  const int64_t H = s->n_kv_heads, d = s->head_dim;
+  BatchItem it{}, prev{};
+  for (int b = 0; b < bt->batch; ++b) {
+    it = batch_item(s, bt, b, total, b ? &prev : nullptr);
+    prev = it;
+    const unsigned char* kb = reinterpret_cast<const unsigned char*>(k) + (size_t)(it.tok0 * it.shape.k_stride_tok) * esz;
+    const unsigned char* vb = reinterpret_cast<const unsigned char*>(v) + (size_t)(it.tok0 * it.shape.v_stride_tok) * esz;
+    const unsigned char* qb = reinterpret_cast<const unsigned char*>(q_win) + (size_t)b * s->n_q_heads * s->window * d * esz;
+    const int n_pool = bt->n_pool[b], n_approx = bt->n_approx[b];
+    rc = vector_compress(&it.shape, qb, kb, vb, W, n_pool, n_approx, score + H * it.tok0, eps + H * it.tok0, tier + H * it.tok0,
+                         idx_retain ? idx_retain + H * it.ret0 : nullptr, idx_approx ? idx_approx + H * it.apx0 : nullptr,
+                         k_ret ? reinterpret_cast<unsigned char*>(k_ret) + (size_t)(H * it.cap0 * d) * esz : nullptr,
+                         v_ret ? reinterpret_cast<unsigned char*>(v_ret) + (size_t)(H * it.cap0 * d) * esz : nullptr,
+                         k_apx ? reinterpret_cast<unsigned char*>(k_apx) + (size_t)(H * it.apx0 * d) * esz : nullptr,
+                         bt->cap_retain[b], ws, ws_bytes, stream);
+    if (rc) return rc;
+  }
+  return VECTOR_OK;
+}
+
 size_t vector_calibrate_workspace_bytes(const vector_shape* s) {
   if (check_shape(s, false) != VECTOR_OK) return 0;
   return vec::calibrate_workspace_bytes(*s);
@@ -275,6 +371,9 @@ static int decode_checked(const vector_cache* c, const void* q, float scale, voi
     return VECTOR_ERR_ARG;
   if ((flags & VECTOR_DECODE_LITERAL) && (rope || c->dtype != VECTOR_BF16)) return VECTOR_ERR_DTYPE;
   if (!c->len_retain) return VECTOR_ERR_ARG;
+  const int n_seq_arrays = (c->cap_retain_seq != nullptr) + (c->n_approx_seq != nullptr) + (c->ret_row_start != nullptr) +
+                           (c->apx_row_start != nullptr);
+  if (n_seq_arrays != 0 && n_seq_arrays != 4) return VECTOR_ERR_ARG;
   if (c->cap_retain > 0 && (!c->k_ret || !c->v_ret || !aligned16(c->k_ret) || !aligned16(c->v_ret))) return VECTOR_ERR_ARG;
   if (c->n_approx > 0 && (!c->k_apx || !c->W || !aligned16(c->k_apx) || !aligned16(c->W))) return VECTOR_ERR_ARG;
   if (!aligned16(q) || !aligned16(out)) return VECTOR_ERR_ARG;

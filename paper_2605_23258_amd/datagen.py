@@ -81,6 +81,7 @@ class Config:
     heavy_scale: float = 4.0
     cal_tokens: int = 4096
     decode_steps: int = 0
+    pool_mode: str = "avg"     # "avg" | "max"
 
     @property
     def group(self) -> int:

@@ -30,6 +30,7 @@ def to_host(t: torch.Tensor) -> np.ndarray:
 def shape_of(cfg: Config, seq_len: Optional[int] = None) -> vb.Shape:
     return vb.Shape(n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim,
                     seq_len=seq_len or cfg.seq_len, window=cfg.window, pool_kernel=cfg.pool_kernel,
+                    pool_mode=vb.VECTOR_POOL_MAX if cfg.pool_mode == "max" else vb.VECTOR_POOL_AVG,
                     dtype=vb.VECTOR_BF16 if cfg.dtype == "bf16" else vb.VECTOR_F32)
 
 

@@ -52,3 +52,24 @@ def decode_check(cache, q_dev, scale, ws, ref, what="decode", flags=0, rope=None
     else:
         assert np.array_equal(native.cpu().numpy(), got32), f"{what}: the flag must not change an fp32 cache's output"
     return got32
+
+
+def band_check(score_ref, eps_ref, n_p, n_a, got_tier, ref_tier, n, what):
+    """Tokens routed differently must sit within float tolerance of the oracle's own
+    selection thresholds (GPU and oracle scores differ in the last bits)."""
+    flips = 0
+    for h in range(score_ref.shape[0]):
+        diff = np.flatnonzero(got_tier[h] != ref_tier[h])
+        if not len(diff):
+            continue
+        flips += len(diff)
+        s = score_ref[h].astype(np.float64) * n
+        thr_s = np.sort(s)[::-1][n_p - 1]
+        pool_ref = ref_tier[h] != 0
+        e = eps_ref[h].astype(np.float64)
+        thr_e = np.sort(e[pool_ref])[n_a - 1] if n_a else 0.0
+        for t in diff:
+            near_s = abs(s[t] - thr_s) <= 2 * (ATOL + RTOL * abs(thr_s))
+            near_e = abs(e[t] - thr_e) <= 2 * (ATOL + RTOL * abs(thr_e))
+            assert near_s or near_e, f"{what}: head {h} token {t} flipped far from both thresholds"
+    return flips

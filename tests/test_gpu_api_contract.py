@@ -133,6 +133,7 @@ def test_errors_are_reported_before_any_launch():
     assert code_of(lambda: run(with_shape(dtype=7))) == vb.VECTOR_ERR_DTYPE
     assert code_of(lambda: run(with_shape(window=n + 1))) == vb.VECTOR_ERR_SHAPE
     assert code_of(lambda: run(with_shape(pool_kernel=4))) == vb.VECTOR_ERR_SHAPE
+    assert code_of(lambda: run(with_shape(pool_mode=2))) == vb.VECTOR_ERR_SHAPE
     assert code_of(lambda: run(with_shape(n_q_heads=3, n_kv_heads=2))) == vb.VECTOR_ERR_SHAPE
     assert code_of(lambda: run(with_shape(k_stride_tok=cfg.head_dim - 8))) == vb.VECTOR_ERR_SHAPE
     assert code_of(lambda: run(shape, ws[:256])) == vb.VECTOR_ERR_WORKSPACE        # too small
@@ -160,6 +161,7 @@ def test_errors_are_reported_before_any_launch():
     ("cfg2", dict(seq_len=2500, n_kv_heads=2, n_q_heads=8, f_approx=0.0)),          # nothing approximated
     ("cfg2", dict(seq_len=2500, n_kv_heads=2, n_q_heads=8, f_retain=0.0)),          # nothing retained
     ("cfg1", dict(seq_len=3000, head_dim=128, n_kv_heads=1, n_q_heads=2, window=8)),   # fp32 rows of 512 bytes
+    ("cfg2", dict(seq_len=4500, n_kv_heads=2, n_q_heads=4, pool_mode="max")),
 ])
 def test_one_call_pass_equals_the_three_calls(base, over):
     cfg = dg.scaled(dg.CONFIGS[base], **over)
