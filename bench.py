@@ -477,6 +477,35 @@ def run_extras(vb, dg, pl, torch, np, dev, cfg, shape, layer, out, ws, n_p, n_a)
     wsd = pl.alloc_workspace(vb.vector_distortion_workspace_bytes(shape), dev)
     wts = torch.softmax(torch.randn(H, n, generator=g, device=dev), dim=-1)
     res["distortion_us_per_layer"] = per_call_us(lambda: vb.vector_distortion(shape, wts, out.tier, out.eps, layer["v"], dout, wsd))
+    # Section 5's approximation-ratio sweep re-expressed on the distortion measure of Section 4: at a
+    # fixed compression ratio (fixed footprint of 2 (1 - p_c) n rows) budget moves from retained
+    # values to pool keys; p_a = 0 is binary eviction with the same memory.  Weights: the layer's
+    # un-pooled attention mass from the scorer itself (window columns, which are always kept, weigh 0).
+    p_c = 1.0 - cfg.f_retain - cfg.f_approx / 2.0
+    mshape = pl.shape_of(cfg)
+    mshape.pool_kernel = 1
+    mass = torch.empty((H, n), device=dev)
+    vb.vector_score(mshape, layer["q_win"], layer["k"], mass, ws)
+    mass = torch.where(torch.isinf(mass), torch.zeros_like(mass), mass)
+    wsr = pl.alloc_workspace(vb.vector_workspace_bytes(shape, n, n, 1), dev)
+    tier = torch.empty((H, n), dtype=torch.uint8, device=dev)
+    idx_r = torch.empty((H, n), dtype=torch.int32, device=dev)
+    idx_a = torch.empty((H, n), dtype=torch.int32, device=dev)
+    sweep = []
+    for i in range(0, 9):
+        p_a = round((1.0 - p_c) * i / 8.0, 6)                  # 0 .. 1 - p_c: nothing retained at the end
+        npool, napx = vb.vector_budget_counts(n, p_c, p_a)
+        vb.vector_route(H, n, out.score, out.eps, npool, napx, tier, idx_r if npool > napx else None,
+                        idx_a if napx else None, wsr)
+        vb.vector_distortion(shape, mass, tier, out.eps, layer["v"], dout, wsd)
+        torch.cuda.synchronize()
+        rep = dout.cpu().numpy()
+        sweep.append({"p_a": p_a, "n_pool": npool, "n_approx": napx, "rows_kept": 2 * npool - napx,
+                      "E_mean_over_heads": float(rep[:, 0].mean()), "w_evict": float(rep[:, 1].mean()),
+                      "r2_approx": float(rep[:, 4].mean()), "prop1_threshold": float(rep[:, 7].mean())})
+    res["pa_sweep"] = {"p_c": round(p_c, 6), "weights": "un-pooled attention mass of the layer (GPU scorer, pool 1)",
+                       "points": sweep, "binary_eviction_E": sweep[0]["E_mean_over_heads"],
+                       "best_p_a": min(sweep, key=lambda r: r["E_mean_over_heads"])["p_a"]}
     log(f"extras: {res}")
     return res
 
