@@ -252,6 +252,19 @@ typedef struct {
 VECTOR_API int vector_decode_attn(const vector_cache* cache, const void* q, float scale, void* out,
                        int32_t flags, void* ws, size_t ws_bytes, void* stream);
 
+/* One decode step with its append (Section 3.2 keeps what generation adds exactly): the new
+ * token's key and value (k_new, v_new: device [batch, Hkv, d], cache dtype) join the retained
+ * segment of their sequence as row len_retain[b], the query attends over the cache with that row
+ * included, and len_retain[b] grows by one, all inside the two launches of vector_decode_attn
+ * (the workgroup whose rows include the new one stores it; the step itself reads it from k_new /
+ * v_new).  Same arguments, flags, outputs and errors as vector_decode_attn otherwise.  The call
+ * writes cache->k_ret, v_ret (one row per sequence and KV head) and cache->len_retain, although the
+ * struct declares them const.  A sequence whose retained block is already full (len_retain[b] equal
+ * to its capacity) still attends over its new token, but the token is not stored and the length
+ * stays: give the blocks room for the tokens to come.  VECTOR_ERR_ARG if cap_retain < 1. */
+VECTOR_API int vector_decode_step(const vector_cache* cache, const void* q, const void* k_new, const void* v_new,
+                       float scale, void* out, int32_t flags, void* ws, size_t ws_bytes, void* stream);
+
 /* ---- measurement ---------------------------------------------------------- */
 
 /* Optional per-kernel timing for benchmarks.  While enabled, every kernel launch
@@ -301,6 +314,11 @@ VECTOR_API int vector_score_residual_rope(const vector_shape* shape, const void*
  * logits from the cached keys.  bf16 caches only (VECTOR_ERR_DTYPE otherwise). */
 VECTOR_API int vector_decode_attn_rope(const vector_cache* cache, const vector_rope* rope, const void* q, float scale,
                             void* out, int32_t flags, void* ws, size_t ws_bytes, void* stream);
+/* vector_decode_step on a post-RoPE cache: k_new is the new token's key as cached (after its rotary
+ * embedding); retained rows are never un-rotated, so the append itself is the same. */
+VECTOR_API int vector_decode_step_rope(const vector_cache* cache, const vector_rope* rope, const void* q, const void* k_new,
+                            const void* v_new, float scale, void* out, int32_t flags, void* ws, size_t ws_bytes,
+                            void* stream);
 
 /* ---- calibration of the value map ---------------------------------------- */
 

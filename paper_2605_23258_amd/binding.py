@@ -28,6 +28,7 @@ EXPORTS = (
     "vector_timing_enable", "vector_timing_kernels", "vector_timing_name", "vector_timing_read",
     "vector_probe_residual_mfma", "vector_probe_mfma_loop",
     "vector_residual_rope", "vector_score_residual_rope", "vector_decode_attn_rope",
+    "vector_decode_step", "vector_decode_step_rope",
     "vector_calibrate_workspace_bytes", "vector_calibrate",
     "vector_distortion_workspace_bytes", "vector_distortion",
     "vector_r2_workspace_bytes", "vector_r2",
@@ -120,6 +121,8 @@ def lib() -> C.CDLL:
         L.vector_route_static_scratch_bytes.restype = sz
         L.vector_compact.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, i32, i32, vp, vp, vp, i32, vp]
         L.vector_decode_attn.argtypes = [C.POINTER(Cache), vp, C.c_float, vp, i32, vp, sz, vp]
+        L.vector_decode_step.argtypes = [C.POINTER(Cache), vp, vp, vp, C.c_float, vp, i32, vp, sz, vp]
+        L.vector_decode_step_rope.argtypes = [C.POINTER(Cache), C.POINTER(Rope), vp, vp, vp, C.c_float, vp, i32, vp, sz, vp]
         L.vector_timing_enable.argtypes = [C.c_int]
         L.vector_timing_name.argtypes = [C.c_int]
         L.vector_timing_name.restype = C.c_char_p
@@ -237,6 +240,18 @@ def vector_compact(shape: Shape, k, v, idx_retain, idx_approx, n_retain: int, n_
 def vector_decode_attn(cache: Cache, q, scale: float, out, ws, flags: int = 0, stream=None) -> None:
     _check(lib().vector_decode_attn(C.byref(cache), _ptr(q), float(scale), _ptr(out), flags, _ptr(ws), _nbytes(ws),
                                     _stream(stream)), "vector_decode_attn")
+
+
+def vector_decode_step(cache: Cache, q, k_new, v_new, scale: float, out, ws, flags: int = 0, stream=None) -> None:
+    """Decode attention with the step's own token appended to the retained segments (cache rows and
+    len_retain are written)."""
+    _check(lib().vector_decode_step(C.byref(cache), _ptr(q), _ptr(k_new), _ptr(v_new), float(scale), _ptr(out), flags,
+                                    _ptr(ws), _nbytes(ws), _stream(stream)), "vector_decode_step")
+
+
+def vector_decode_step_rope(cache: Cache, rope: Rope, q, k_new, v_new, scale: float, out, ws, flags: int = 0, stream=None) -> None:
+    _check(lib().vector_decode_step_rope(C.byref(cache), C.byref(rope), _ptr(q), _ptr(k_new), _ptr(v_new), float(scale),
+                                         _ptr(out), flags, _ptr(ws), _nbytes(ws), _stream(stream)), "vector_decode_step_rope")
 
 
 def vector_timing_enable(on: bool) -> None:

@@ -35,6 +35,9 @@ struct DecodeParams {
   // per-sequence capacities and first rows of the sequences' blocks (all null: uniform blocks)
   const int32_t* cap_retain_seq; const int32_t* n_approx_seq;
   const int64_t* ret_row_start; const int64_t* apx_row_start;
+  // the step's own token (null: none): exact key and value [B, Hkv, D]; it is attended as row
+  // len_retain[b] of the retained segment and stored there when the block has room
+  const void* k_new; const void* v_new;
   void* out;
   float* part;            // [B, Hkv, S, 2*G + G*D] floats: m[G], l[G], acc[G][D]
   int B, Hq, Hkv, cap_retain, n_approx;
@@ -47,7 +50,7 @@ struct DecodeParams {
 
 // Where the rows of one (sequence, KV head) lie: row offsets into k_ret / v_ret and into k_apx,
 // the live length of the retained segment and the length of the approximated one.
-struct SegmentRows { size_t ret_row0, apx_row0; int len_retain, n_approx; };
+struct SegmentRows { size_t ret_row0, apx_row0; int len_retain, n_approx, new_row, cap; };
 __device__ __forceinline__ SegmentRows segment_rows(const DecodeParams& p, int b, int h) {
   SegmentRows s;
   int cap = p.cap_retain;
@@ -63,7 +66,28 @@ __device__ __forceinline__ SegmentRows segment_rows(const DecodeParams& p, int b
     s.apx_row0 = bh * s.n_approx;
   }
   s.len_retain = min(max(p.len_retain[b], 0), cap);
+  s.cap = cap;
+  s.new_row = -1;
+  if (p.k_new) { s.new_row = s.len_retain; s.len_retain += 1; }      // the new token is the last live row
   return s;
+}
+
+// The workgroup whose rows include the step's own token stores it in the cache (when the block has
+// room) for the steps to come; this step reads it from the caller's buffers, so nothing waits for
+// the store.
+template <typename T, int D>
+__device__ __forceinline__ void append_new_row(const DecodeParams& p, const SegmentRows& seg, bool is_apx, int row_begin, int row_end,
+                                               const T* k_new, const T* v_new) {
+  constexpr int kPieces = D * (int)sizeof(T) / 16;
+  if (is_apx || seg.new_row < row_begin || seg.new_row >= row_end || seg.new_row >= seg.cap) return;
+  if ((int)threadIdx.x < 2 * kPieces) {
+    const int piece = (int)threadIdx.x % kPieces;
+    const bool is_v = (int)threadIdx.x >= kPieces;
+    unsigned char* dst = reinterpret_cast<unsigned char*>(const_cast<void*>(is_v ? p.v_ret : p.k_ret)) +
+                         (seg.ret_row0 + (size_t)seg.new_row) * D * sizeof(T) + piece * 16;
+    const unsigned char* src = reinterpret_cast<const unsigned char*>(is_v ? v_new : k_new) + piece * 16;
+    *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+  }
 }
 
 constexpr int DT_ = 256;          // threads per workgroup
@@ -123,6 +147,9 @@ __global__ __launch_bounds__(DT_) void decode_split_kernel(DecodeParams p) {
   const T* kseg = is_apx ? reinterpret_cast<const T*>(p.k_apx) + seg.apx_row0 * D
                          : reinterpret_cast<const T*>(p.k_ret) + seg.ret_row0 * D;
   const T* vseg = reinterpret_cast<const T*>(p.v_ret) + seg.ret_row0 * D;
+  const T* k_new = p.k_new ? reinterpret_cast<const T*>(p.k_new) + bh * D : kseg;
+  const T* v_new = p.k_new ? reinterpret_cast<const T*>(p.v_new) + bh * D : vseg;
+  append_new_row<T, D>(p, seg, is_apx, row_begin, row_end, k_new, v_new);
 
   // this lane's slice of the G query rows, pre-scaled into the log2 domain
   float qf[G][E];
@@ -149,8 +176,9 @@ __global__ __launch_bounds__(DT_) void decode_split_kernel(DecodeParams p) {
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
       const int r = min(r0 + u, seg_len - 1);      // clamped: never reads past the live rows
-      kraw[u] = load_chunk(kseg + (size_t)r * D + piece * E);
-      if (!is_apx) vraw[u] = load_chunk(vseg + (size_t)r * D + piece * E);
+      const bool fresh = !is_apx && r == seg.new_row;        // the step's own token comes from the caller's buffers
+      kraw[u] = load_chunk(fresh ? k_new + piece * E : kseg + (size_t)r * D + piece * E);
+      if (!is_apx) vraw[u] = load_chunk(fresh ? v_new + piece * E : vseg + (size_t)r * D + piece * E);
     }
   };
   auto consume = [&](const uint4* kraw, const uint4* vraw, int base) {
@@ -333,6 +361,9 @@ __global__ __launch_bounds__(DT_, 2) void decode_split_mfma_kernel(DecodeParams 
   const T* kseg = is_apx ? reinterpret_cast<const T*>(p.k_apx) + seg.apx_row0 * D
                          : reinterpret_cast<const T*>(p.k_ret) + seg.ret_row0 * D;
   const T* vseg = reinterpret_cast<const T*>(p.v_ret) + seg.ret_row0 * D;
+  const T* k_new = p.k_new ? reinterpret_cast<const T*>(p.k_new) + bh * D : kseg;
+  const T* v_new = p.k_new ? reinterpret_cast<const T*>(p.v_new) + bh * D : vseg;
+  append_new_row<T, D>(p, seg, is_apx, row_begin, row_end, k_new, v_new);
 
   unsigned char* k_tile = dec_lds + wave * 2 * TL::kTileBytes;
   unsigned char* v_tile = k_tile + TL::kTileBytes;
@@ -376,8 +407,9 @@ __global__ __launch_bounds__(DT_, 2) void decode_split_mfma_kernel(DecodeParams 
 #pragma unroll
       for (int i = 0; i < TL::kLoads; ++i) {
         const int r = min(base + i * TL::kRowsPerLoad + ld_row, seg_len - 1);   // clamped: never past the live rows
-        kraw[i] = load_chunk(kseg + (size_t)r * D + ld_piece * 8);
-        if (!is_apx) vraw[i] = load_chunk(vseg + (size_t)r * D + ld_piece * 8);
+        const bool fresh = !is_apx && r == seg.new_row;      // the step's own token comes from the caller's buffers
+        kraw[i] = load_chunk(fresh ? k_new + ld_piece * 8 : kseg + (size_t)r * D + ld_piece * 8);
+        if (!is_apx) vraw[i] = load_chunk(fresh ? v_new + ld_piece * 8 : vseg + (size_t)r * D + ld_piece * 8);
       }
     } else {
 #pragma unroll
@@ -649,6 +681,13 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(DecodeParams p) {
   const T* Wh = reinterpret_cast<const T*>(p.W) + (int64_t)h * p.w_sh;
   uint4 wraw[RP];
   const bool use_w = p.n_approx > 0 && !p.literal;      // literal partials are values already
+  // the step's own token is now a row of the cache (the split launch has finished): one thread per
+  // sequence makes it live, unless the block was full
+  if (p.k_new && h == 0 && threadIdx.x == 0) {
+    const int cap = p.cap_retain_seq ? max(p.cap_retain_seq[b], 0) : p.cap_retain;
+    int* len = const_cast<int*>(p.len_retain) + b;
+    *len = min(min(max(*len, 0), cap) + 1, cap);
+  }
   if (use_w) {
 #pragma unroll
     for (int r = 0; r < RP; ++r) wraw[r] = load_chunk(Wh + (size_t)(rg * RP + r) * D + cg * E);
@@ -808,12 +847,13 @@ size_t decode_workspace_bytes(int batch, int n_q_heads, int n_kv_heads, int head
 }
 
 int launch_decode_attn(const vector_cache& c, const void* q, float scale, void* out, int flags, void* ws,
-                       hipStream_t stream, const RopeParams* rope) {
+                       hipStream_t stream, const RopeParams* rope, const void* k_new, const void* v_new) {
   DecodeParams p;
   p.literal = (flags & VECTOR_DECODE_LITERAL) ? 1 : 0;
   p.out_f32 = (flags & VECTOR_DECODE_OUT_F32) ? 1 : 0;
   if (p.literal && (rope || c.dtype != VECTOR_BF16)) return VECTOR_ERR_DTYPE;
   p.q = q; p.k_ret = c.k_ret; p.v_ret = c.v_ret; p.k_apx = c.k_apx; p.W = c.W; p.len_retain = c.len_retain;
+  p.k_new = k_new; p.v_new = v_new;
   p.cap_retain_seq = c.cap_retain_seq; p.n_approx_seq = c.n_approx_seq;
   p.ret_row_start = c.ret_row_start; p.apx_row_start = c.apx_row_start;
   p.out = out; p.part = reinterpret_cast<float*>(ws);

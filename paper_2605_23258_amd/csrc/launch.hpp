@@ -76,6 +76,7 @@ int launch_compact(const vector_shape& s, const void* k, const void* v, const in
 
 size_t decode_workspace_bytes(int batch, int n_q_heads, int n_kv_heads, int head_dim, int cap_retain, int n_approx);
 int launch_decode_attn(const vector_cache& c, const void* q, float scale, void* out, int flags, void* ws,
-                       hipStream_t stream, const RopeParams* rope = nullptr);
+                       hipStream_t stream, const RopeParams* rope = nullptr, const void* k_new = nullptr,
+                       const void* v_new = nullptr);
 
 }  // namespace vec

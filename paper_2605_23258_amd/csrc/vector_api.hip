@@ -358,8 +358,10 @@ int vector_compact(const vector_shape* s, const void* k, const void* v, const in
 }
 
 static int decode_checked(const vector_cache* c, const void* q, float scale, void* out, int32_t flags, void* ws,
-                          size_t ws_bytes, void* stream, const vec::RopeParams* rope) {
+                          size_t ws_bytes, void* stream, const vec::RopeParams* rope, const void* k_new = nullptr,
+                          const void* v_new = nullptr, bool step = false) {
   if (!c || !q || !out) return VECTOR_ERR_ARG;
+  if (step && (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new) || c->cap_retain < 1)) return VECTOR_ERR_ARG;
   if (c->dtype != VECTOR_F32 && c->dtype != VECTOR_BF16) return VECTOR_ERR_DTYPE;
   if (rope && c->dtype != VECTOR_BF16) return VECTOR_ERR_DTYPE;
   if (c->head_dim != 64 && c->head_dim != 128) return VECTOR_ERR_SHAPE;
@@ -380,7 +382,21 @@ static int decode_checked(const vector_cache* c, const void* q, float scale, voi
   int rc = check_ws(ws, ws_bytes,
                     vec::decode_workspace_bytes(c->batch, c->n_q_heads, c->n_kv_heads, c->head_dim, c->cap_retain, c->n_approx));
   if (rc) return rc;
-  return vec::launch_decode_attn(*c, q, scale, out, flags, ws, (hipStream_t)stream, rope);
+  return vec::launch_decode_attn(*c, q, scale, out, flags, ws, (hipStream_t)stream, rope, k_new, v_new);
+}
+
+int vector_decode_step(const vector_cache* c, const void* q, const void* k_new, const void* v_new, float scale, void* out,
+                       int32_t flags, void* ws, size_t ws_bytes, void* stream) {
+  return decode_checked(c, q, scale, out, flags, ws, ws_bytes, stream, nullptr, k_new, v_new, true);
+}
+
+int vector_decode_step_rope(const vector_cache* c, const vector_rope* rope, const void* q, const void* k_new, const void* v_new,
+                            float scale, void* out, int32_t flags, void* ws, size_t ws_bytes, void* stream) {
+  if (!c) return VECTOR_ERR_ARG;
+  vec::RopeParams rp;
+  int rc = make_rope(rope, c->head_dim, rp);
+  if (rc) return rc;
+  return decode_checked(c, q, scale, out, flags, ws, ws_bytes, stream, &rp, k_new, v_new, true);
 }
 
 int vector_decode_attn(const vector_cache* c, const void* q, float scale, void* out, int32_t flags, void* ws,

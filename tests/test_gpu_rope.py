@@ -108,6 +108,42 @@ def test_decode_on_rotated_cache(d, B, Hq, Hkv, n_r, n_a, interleaved):
     assert np.abs(dg.widen(pl.to_host(out2)) - ref).max() > 10 * ATOL
 
 
+def test_decode_step_on_rotated_cache():
+    """vector_decode_step_rope: the new token's key is appended as cached (rotated), attends with
+    the others, and only approximated rows are turned back."""
+    d, B, Hq, Hkv, cap, n_a = 128, 2, 8, 2, 120, 90
+    rng = np.random.default_rng(321)
+    inv_freq = dg.rotary_inv_freq(d, THETA)
+    bf = lambda x: dg.f32_to_bf16_bits(np.asarray(x, np.float32))
+    k_ret, v_ret = bf(rng.standard_normal((B, Hkv, cap, d))), bf(rng.standard_normal((B, Hkv, cap, d)))
+    pos = np.sort(rng.choice(32768, size=(B, Hkv, n_a)), axis=-1).astype(np.int32)
+    k_apx = bf(dg.apply_rotary(rng.standard_normal((B, Hkv, n_a, d)), pos, inv_freq, False))
+    W = bf(rng.standard_normal((Hkv, d, d)) / np.sqrt(d))
+    q, k_new, v_new = bf(rng.standard_normal((B, Hq, d))), bf(rng.standard_normal((B, Hkv, d))), bf(rng.standard_normal((B, Hkv, d)))
+    lens = np.array([cap - 1, 40], dtype=np.int32)
+    kk, vv = k_ret.copy(), v_ret.copy()
+    for b in range(B):
+        kk[b, :, lens[b]] = k_new[b]
+        vv[b, :, lens[b]] = v_new[b]
+    scale = 1.0 / np.sqrt(d)
+    ref = vo.decode_attn(dg.widen(q), dg.widen(kk), dg.widen(vv), lens + 1, dg.widen(k_apx), dg.widen(W), scale,
+                         pos_apx=pos, inv_freq=inv_freq, interleaved=False)
+    t = [pl.to_device(x) for x in (k_ret, v_ret, k_apx, W, q, pos, k_new, v_new)]
+    length = pl.to_device(lens)
+    cache = vb.Cache(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, dtype=vb.VECTOR_BF16, cap_retain=cap, n_approx=n_a)
+    cache.len_retain, cache.k_ret, cache.v_ret, cache.k_apx, cache.W = (length.data_ptr(), t[0].data_ptr(), t[1].data_ptr(),
+                                                                      t[2].data_ptr(), t[3].data_ptr())
+    shape = vb.Shape(n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, seq_len=cap + n_a, window=1, pool_kernel=1, dtype=1)
+    ws = pl.alloc_workspace(vb.vector_workspace_bytes(shape, cap + n_a, n_a, B))
+    rope, keep = vb.make_rope(inv_freq, t[5], False, 0)
+    out = torch.empty((B, Hq, d), dtype=torch.float32, device="cuda:0")
+    vb.vector_decode_step_rope(cache, rope, t[4], t[6], t[7], scale, out, ws, flags=vb.VECTOR_DECODE_OUT_F32)
+    torch.cuda.synchronize()
+    close(out.cpu().numpy(), ref, "decode step (rotary cache)")
+    assert length.cpu().numpy().tolist() == (lens + 1).tolist()
+    assert np.array_equal(pl.to_host(t[0]), kk) and np.array_equal(pl.to_host(t[1]), vv)
+
+
 def test_full_size_layer_and_decode_step():
     """The 32k-token layer and the batch-16 decode shape of the benchmark, read as post-RoPE caches."""
     cfg = dg.CONFIGS["cfg3"]
