@@ -477,6 +477,38 @@ def run_extras(vb, dg, pl, torch, np, dev, cfg, shape, layer, out, ws, n_p, n_a)
     wsd = pl.alloc_workspace(vb.vector_distortion_workspace_bytes(shape), dev)
     wts = torch.softmax(torch.randn(H, n, generator=g, device=dev), dim=-1)
     res["distortion_us_per_layer"] = per_call_us(lambda: vb.vector_distortion(shape, wts, out.tier, out.eps, layer["v"], dout, wsd))
+    # a batch of equal prompts (8 x 8192 tokens, cfg-2 shape): one call with the heads of the run stacked
+    # against one vector_compress call per sequence
+    c2 = dg.CONFIGS["cfg2"]
+    Bq, n2 = 8, c2.seq_len
+    npool2, napx2 = vb.vector_budget_counts_frac(n2, c2.f_retain, c2.f_approx)
+    nr2 = npool2 - napx2
+    shape2 = pl.shape_of(c2)
+    kb, vbt = rnd(H, Bq * n2, d), rnd(H, Bq * n2, d)                    # ragged layout: [Hkv, T, d]
+    qb = rnd(Bq, c2.n_q_heads, c2.window, d)
+    batch, keep_b = vb.make_batch([n2] * Bq, [npool2] * Bq, [napx2] * Bq, [nr2] * Bq)
+    wsb = pl.alloc_workspace(vb.vector_compress_batch_workspace_bytes(shape2, batch), dev)
+    ob = dict(score=torch.empty(Bq * H * n2, device=dev), eps=torch.empty(Bq * H * n2, device=dev),
+              tier=torch.empty(Bq * H * n2, dtype=torch.uint8, device=dev),
+              ir=torch.empty(Bq * H * nr2, dtype=torch.int32, device=dev), ia=torch.empty(Bq * H * napx2, dtype=torch.int32, device=dev),
+              kr=torch.empty(Bq * H * nr2, d, dtype=torch.bfloat16, device=dev), vr=torch.empty(Bq * H * nr2, d, dtype=torch.bfloat16, device=dev),
+              ka=torch.empty(Bq * H * napx2, d, dtype=torch.bfloat16, device=dev))
+    res["compress_batch_8x8192_us"] = per_call_us(
+        lambda: vb.vector_compress_batch(shape2, batch, qb, kb, vbt, layer["w_cal"], ob["score"], ob["eps"], ob["tier"], ob["ir"], ob["ia"],
+                                         ob["kr"], ob["vr"], ob["ka"], wsb), 10)
+    one_b, keep_1 = vb.make_batch([n2], [npool2], [napx2], [nr2])
+    # the same sequences one call each: sequence b alone is a batch of one with its own strides
+    shape2s = pl.shape_of(c2)
+    shape2s.k_stride_head = shape2s.v_stride_head = Bq * n2 * d
+    shape2s.k_stride_tok = shape2s.v_stride_tok = d
+
+    def per_sequence():
+        for b in range(Bq):
+            vb.vector_compress(shape2s, qb[b], kb[:, b * n2:], vbt[:, b * n2:], layer["w_cal"], npool2, napx2,
+                               ob["score"][b * H * n2:], ob["eps"][b * H * n2:], ob["tier"][b * H * n2:], ob["ir"][b * H * nr2:],
+                               ob["ia"][b * H * napx2:], ob["kr"][b * H * nr2:], ob["vr"][b * H * nr2:], ob["ka"][b * H * napx2:], nr2, wsb)
+    res["compress_8x8192_one_call_each_us"] = per_call_us(per_sequence, 10)
+    del kb, vbt, ob, keep_1, one_b
     # Section 5's approximation-ratio sweep re-expressed on the distortion measure of Section 4: at a
     # fixed compression ratio (fixed footprint of 2 (1 - p_c) n rows) budget moves from retained
     # values to pool keys; p_a = 0 is binary eviction with the same memory.  Weights: the layer's

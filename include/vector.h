@@ -194,8 +194,11 @@ VECTOR_API int vector_compress(const vector_shape* shape, const void* q_win, con
  * what vector_compress gives for it alone.  Every sequence must satisfy vector_compress's
  * conditions (window <= seq_len[b], n_approx[b] <= n_pool[b] <= seq_len[b],
  * cap_retain[b] >= n_pool[b] - n_approx[b]); everything is validated before the first launch.
- * The sequences are processed one after the other on `stream` and share ws:
- * vector_compress_batch_workspace_bytes(shape, batch) bytes. */
+ * Consecutive sequences with the same length, counts and capacity share their launches (their heads
+ * are stacked into one problem, with the chunking one sequence alone would get, so the results do not
+ * change); runs follow each other on `stream` and share ws:
+ * vector_compress_batch_workspace_bytes(shape, batch) bytes.  Sort or bucket a batch by length to
+ * make the runs long. */
 typedef struct {
   int32_t batch;
   const int32_t* seq_len;      /* host [batch] */

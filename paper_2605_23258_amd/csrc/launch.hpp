@@ -40,9 +40,17 @@ void timing_end(int id, hipStream_t stream);
 // kernel-file entry points used by the C ABI layer
 size_t score_workspace_bytes(const vector_shape& s);
 struct RopeParams;
+// Several sequences of one shape handled as one problem with batch * Hkv heads (the shape passed
+// along says so: n_kv_heads and n_q_heads are the stacked counts).  Head hv of the launch is KV
+// head hv % heads_per_seq of sequence hv / heads_per_seq: its keys and values lie
+// k_stride_seq / v_stride_seq elements (rows: k_stride_seq etc. of launch_compact are in elements
+// too) after the previous sequence's, its W is that KV head's.  Every other array is indexed by
+// hv as it is.
+struct SeqStack { int heads_per_seq; int64_t k_stride_seq, v_stride_seq; };
+
 int launch_score_residual(const vector_shape& s, const void* q, const void* k, const void* v, const void* W,
                           float* score, float* eps, void* ws, hipStream_t stream, const RopeParams* rope = nullptr,
-                          void* route_ws = nullptr);
+                          void* route_ws = nullptr, const SeqStack* stack = nullptr);
 
 int launch_residual_probe(const vector_shape& s, const void* k, const void* v, const void* W, float* eps, int repeat,
                           hipStream_t stream);
@@ -72,7 +80,7 @@ int launch_route(int n_kv_heads, int seq_len, const float* score, const float* e
 
 int launch_compact(const vector_shape& s, const void* k, const void* v, const int32_t* idx_retain,
                    const int32_t* idx_approx, int n_retain, int n_approx, void* k_ret, void* v_ret, void* k_apx,
-                   int cap_retain, hipStream_t stream);
+                   int cap_retain, hipStream_t stream, const SeqStack* stack = nullptr);
 
 size_t decode_workspace_bytes(int batch, int n_q_heads, int n_kv_heads, int head_dim, int cap_retain, int n_approx);
 int launch_decode_attn(const vector_cache& c, const void* q, float scale, void* out, int flags, void* ws,

@@ -809,6 +809,8 @@ __global__ __launch_bounds__(256) void route_evict_all_kernel(uint8_t* __restric
 struct GatherParams {
   const unsigned char* k; const unsigned char* v;
   int64_t k_sh, k_st, v_sh, v_st;          // byte strides
+  int hps;                                 // stacked sequences: KV heads per sequence (0: one sequence)
+  int64_t k_sb, v_sb;                      // byte strides between sequences
   const int32_t* idx_retain; const int32_t* idx_approx;
   int n_retain, n_approx, cap_retain, row_bytes, n;
   unsigned char* k_ret; unsigned char* v_ret; unsigned char* k_apx;
@@ -824,7 +826,9 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(GatherParams p) {
   const int32_t* idx = (seg == 2) ? p.idx_approx + (size_t)h * p.n_approx : p.idx_retain + (size_t)h * p.n_retain;
   int tok = idx[row];
   tok = min(max(tok, 0), p.n - 1);                  // an index list is trusted, but never walk out of the tensor
-  const unsigned char* src = (seg == 1) ? p.v + h * p.v_sh + (int64_t)tok * p.v_st : p.k + h * p.k_sh + (int64_t)tok * p.k_st;
+  const int64_t hs = p.hps ? h / p.hps : 0, hh = p.hps ? h % p.hps : h;      // sequence and KV head of the launch head
+  const unsigned char* src = (seg == 1) ? p.v + hs * p.v_sb + hh * p.v_sh + (int64_t)tok * p.v_st
+                                        : p.k + hs * p.k_sb + hh * p.k_sh + (int64_t)tok * p.k_st;
   unsigned char* dst = (seg == 0) ? p.k_ret + ((size_t)h * p.cap_retain + row) * p.row_bytes
                      : (seg == 1) ? p.v_ret + ((size_t)h * p.cap_retain + row) * p.row_bytes
                                   : p.k_apx + ((size_t)h * p.n_approx + row) * p.row_bytes;
@@ -932,7 +936,7 @@ int launch_route(int n_kv_heads, int seq_len, const float* score, const float* e
 
 int launch_compact(const vector_shape& s, const void* k, const void* v, const int32_t* idx_retain,
                    const int32_t* idx_approx, int n_retain, int n_approx, void* k_ret, void* v_ret, void* k_apx,
-                   int cap_retain, hipStream_t stream) {
+                   int cap_retain, hipStream_t stream, const SeqStack* stack) {
   const int esz = (s.dtype == VECTOR_BF16) ? 2 : 4;
   GatherParams p;
   p.k = reinterpret_cast<const unsigned char*>(k);
@@ -943,6 +947,9 @@ int launch_compact(const vector_shape& s, const void* k, const void* v, const in
   p.v_st = v_st * esz;
   p.k_sh = (s.k_stride_head ? s.k_stride_head : (int64_t)s.seq_len * k_st) * esz;
   p.v_sh = (s.v_stride_head ? s.v_stride_head : (int64_t)s.seq_len * v_st) * esz;
+  p.hps = stack ? stack->heads_per_seq : 0;
+  p.k_sb = stack ? stack->k_stride_seq * esz : 0;
+  p.v_sb = stack ? stack->v_stride_seq * esz : 0;
   p.idx_retain = idx_retain; p.idx_approx = idx_approx;
   p.n_retain = n_retain; p.n_approx = n_approx; p.cap_retain = cap_retain;
   p.row_bytes = s.head_dim * esz; p.n = s.seq_len;

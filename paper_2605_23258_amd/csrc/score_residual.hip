@@ -42,6 +42,8 @@ struct PassParams {
   const void* v;
   const void* W;
   int64_t k_sh, k_st, v_sh, v_st, w_sh;   // element strides
+  int hps;              // stacked sequences: KV heads per sequence (0: one sequence); head hv of the launch is
+  int64_t k_sb, v_sb;   // KV head hv % hps of sequence hv / hps, sequences k_sb / v_sb elements apart
   int n, w, R, R_pad, n_prefix;
   int tokens_per_chunk;  // pass 2: tokens per workgroup
   int tpc1, n_chunks;    // pass 1: tokens per workgroup, and the number of such chunks (= partials per row)
@@ -53,6 +55,12 @@ struct PassParams {
   float* eps;           // [Hkv, n]
   int repeat;           // probe kernels only: times each tile's arithmetic is run on the same registers
 };
+
+// element offset of a launch head's keys (or values), and the KV head whose W it uses
+__device__ __forceinline__ int64_t head_offset(const PassParams& p, int h, int64_t seq_stride, int64_t head_stride) {
+  return p.hps ? (int64_t)(h / p.hps) * seq_stride + (int64_t)(h % p.hps) * head_stride : (int64_t)h * head_stride;
+}
+__device__ __forceinline__ int w_head(const PassParams& p, int h) { return p.hps ? h % p.hps : h; }
 
 template <typename T, int D> struct Tile {
   static constexpr int E = Elem<T>::kPerChunk;
@@ -141,7 +149,7 @@ __global__ __launch_bounds__(NT) void score_stats_kernel(PassParams p) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l31 = lane & 31;
   const int nrb = p.R_pad / 32;
 
-  const T* k_head = reinterpret_cast<const T*>(p.k) + (int64_t)h * p.k_sh;
+  const T* k_head = reinterpret_cast<const T*>(p.k) + head_offset(p, h, p.k_sb, p.k_sh);
   const int c_begin = chunk * p.tpc1;
   const int c_end = min(p.n, c_begin + p.tpc1);
   constexpr int kStep = NW * TW;
@@ -319,7 +327,7 @@ __global__ __launch_bounds__(kV2Threads) void score_stats_tiles_kernel(PassParam
   const int h = blockIdx.y, chunk = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l31 = lane & 31;
   const int rb = wave % NRB, tg = wave / NRB;
-  const T* k_head = reinterpret_cast<const T*>(p.k) + (int64_t)h * p.k_sh;
+  const T* k_head = reinterpret_cast<const T*>(p.k) + head_offset(p, h, p.k_sb, p.k_sh);
   const int c_begin = chunk * p.tpc1;
   const int c_end = min(p.n, c_begin + p.tpc1);
   const int n_steps = (c_end - c_begin + kStepTokens - 1) / kStepTokens;
@@ -595,8 +603,8 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l31 = lane & 31;
   const int nrb = p.R_pad / 32;
 
-  const T* k_head = reinterpret_cast<const T*>(p.k) + (int64_t)h * p.k_sh;
-  const T* v_head = DO_RES ? reinterpret_cast<const T*>(p.v) + (int64_t)h * p.v_sh : nullptr;
+  const T* k_head = reinterpret_cast<const T*>(p.k) + head_offset(p, h, p.k_sb, p.k_sh);
+  const T* v_head = DO_RES ? reinterpret_cast<const T*>(p.v) + head_offset(p, h, p.v_sb, p.v_sh) : nullptr;
   const int c_begin = chunk * p.tokens_per_chunk;
   const int c_end = min(p.n, c_begin + p.tokens_per_chunk);
   // the mass of window columns is never used: stop the score part at the prefix
@@ -616,7 +624,7 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
   union WPiece { uint4 raw; T el[E]; };
   WPiece wpiece[WU];
   if (DO_RES) {
-    const T* Wh = reinterpret_cast<const T*>(p.W) + (int64_t)h * p.w_sh;
+    const T* Wh = reinterpret_cast<const T*>(p.W) + (int64_t)w_head(p, h) * p.w_sh;
 #pragma unroll
     for (int u = 0; u < WU; ++u) {
       const int i = min(threadIdx.x + u * NT, D * D / E - 1);      // clamped: the store below is guarded
@@ -942,15 +950,19 @@ int pick_tokens_per_chunk(int n, int n_kv_heads) {
 }
 
 template <typename T, int D>
-int make_plan(const vector_shape& s, bool do_mass, bool do_res, Plan& plan) {
+// plan_heads: the head count the chunk sizes are chosen for.  A stack of sequences plans for one
+// sequence's heads, so that every sequence gets the chunking (and with it the order of the
+// floating-point sums) it would get alone.
+int make_plan(const vector_shape& s, bool do_mass, bool do_res, Plan& plan, int plan_heads = 0) {
+  if (plan_heads <= 0) plan_heads = s.n_kv_heads;
   using TL = Tile<T, D>;
   PassParams& p = plan.pp;
   const int G = s.n_q_heads / s.n_kv_heads;
   p.n = s.seq_len; p.w = s.window; p.R = G * s.window; p.R_pad = (p.R + 31) / 32 * 32;
   p.n_prefix = s.seq_len - s.window;
-  p.tokens_per_chunk = pick_tokens_per_chunk(s.seq_len, s.n_kv_heads);
+  p.tokens_per_chunk = pick_tokens_per_chunk(s.seq_len, plan_heads);
   plan.tiles = stats_by_tiles(p.R_pad / 32, (size_t)Tile<T, D>::kLdsStride);
-  p.tpc1 = plan.tiles ? pick_tokens_per_chunk_tiles(s.seq_len, s.n_kv_heads) : p.tokens_per_chunk;
+  p.tpc1 = plan.tiles ? pick_tokens_per_chunk_tiles(s.seq_len, plan_heads) : p.tokens_per_chunk;
   p.n_chunks = (s.seq_len + p.tpc1 - 1) / p.tpc1;
   int tpr = 1;
   while (tpr * 2 <= 64 && tpr * 2 * p.R_pad <= kThreads && tpr * 2 <= p.n_chunks) tpr *= 2;
@@ -962,6 +974,7 @@ int make_plan(const vector_shape& s, bool do_mass, bool do_res, Plan& plan) {
   p.v_st = s.v_stride_tok ? s.v_stride_tok : D;
   p.v_sh = s.v_stride_head ? s.v_stride_head : (int64_t)s.seq_len * p.v_st;
   p.w_sh = s.w_shared ? 0 : (s.w_stride_head ? s.w_stride_head : (int64_t)D * D);
+  p.hps = 0; p.k_sb = 0; p.v_sb = 0;
   constexpr int NW = kThreads1 / kWave;
   plan.lds_stats = (size_t)p.R_pad * TL::kLdsStride + (size_t)NW * (p.R_pad / 32) * 64 * sizeof(float2);
   plan.lds_pass2 = (do_mass ? (size_t)p.R_pad * (TL::kLdsStride + sizeof(float)) : 0) + (do_res ? (size_t)D * TL::kLdsStride : 0);
@@ -983,15 +996,18 @@ size_t score_workspace_bytes(const vector_shape& s) {
 }
 
 template <typename T, int D>
-static int run_score_residual(const vector_shape& s, const void* q, const void* k, const void* v, const void* W,
+static int run_score_residual(const SeqStack* stack, const vector_shape& s, const void* q, const void* k, const void* v, const void* W,
                               float* score, float* eps, void* ws, hipStream_t stream, const RopeParams* rope,
                               void* route_ws) {
   const bool do_mass = score != nullptr, do_res = eps != nullptr;
   Plan plan;
-  int rc = make_plan<T, D>(s, do_mass, do_res, plan);
+  int rc = make_plan<T, D>(s, do_mass, do_res, plan, stack ? stack->heads_per_seq : 0);
   if (rc != VECTOR_OK) return rc;
   PassParams& p = plan.pp;
   p.q = q; p.k = k; p.v = v; p.W = W; p.eps = eps; p.repeat = 1;
+  if (stack) {                      // the strides inside a sequence are the shape's, as for one sequence
+    p.hps = stack->heads_per_seq; p.k_sb = stack->k_stride_seq; p.v_sb = stack->v_stride_seq;
+  }
   unsigned char* w8 = reinterpret_cast<unsigned char*>(ws);
   p.part = reinterpret_cast<float2*>(w8);
   w8 += align_up((size_t)s.n_kv_heads * ((s.seq_len + 255) / 256) * p.R_pad * sizeof(float2), 256);
@@ -1054,13 +1070,13 @@ int launch_residual_probe(const vector_shape& s, const void* k, const void* v, c
 
 int launch_score_residual(const vector_shape& s, const void* q, const void* k, const void* v, const void* W,
                           float* score, float* eps, void* ws, hipStream_t stream, const RopeParams* rope,
-                          void* route_ws) {
+                          void* route_ws, const SeqStack* stack) {
   if (s.dtype == VECTOR_BF16) {
-    if (s.head_dim == 128) return run_score_residual<bf16_t, 128>(s, q, k, v, W, score, eps, ws, stream, rope, route_ws);
-    if (s.head_dim == 64) return run_score_residual<bf16_t, 64>(s, q, k, v, W, score, eps, ws, stream, rope, route_ws);
+    if (s.head_dim == 128) return run_score_residual<bf16_t, 128>(stack, s, q, k, v, W, score, eps, ws, stream, rope, route_ws);
+    if (s.head_dim == 64) return run_score_residual<bf16_t, 64>(stack, s, q, k, v, W, score, eps, ws, stream, rope, route_ws);
   } else if (s.dtype == VECTOR_F32) {
-    if (s.head_dim == 128) return run_score_residual<float, 128>(s, q, k, v, W, score, eps, ws, stream, rope, route_ws);
-    if (s.head_dim == 64) return run_score_residual<float, 64>(s, q, k, v, W, score, eps, ws, stream, rope, route_ws);
+    if (s.head_dim == 128) return run_score_residual<float, 128>(stack, s, q, k, v, W, score, eps, ws, stream, rope, route_ws);
+    if (s.head_dim == 64) return run_score_residual<float, 64>(stack, s, q, k, v, W, score, eps, ws, stream, rope, route_ws);
   } else {
     return VECTOR_ERR_DTYPE;
   }

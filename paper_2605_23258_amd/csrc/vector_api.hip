@@ -144,9 +144,11 @@ size_t vector_compress_workspace_bytes(const vector_shape* s, int32_t n_pool, in
   return vec::score_workspace_bytes(*s) + vec::route_workspace_bytes(s->n_kv_heads, s->seq_len, n_pool) + 256;
 }
 
-int vector_compress(const vector_shape* s, const void* q_win, const void* k, const void* v, const void* W, int32_t n_pool,
-                    int32_t n_approx, float* score, float* eps, uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx,
-                    void* k_ret, void* v_ret, void* k_apx, int32_t cap_retain, void* ws, size_t ws_bytes, void* stream) {
+// vector_compress; with `stack`, several sequences of one shape as one problem (s holds the stacked head counts)
+static int compress_impl(const vector_shape* s, const void* q_win, const void* k, const void* v, const void* W, int32_t n_pool,
+                         int32_t n_approx, float* score, float* eps, uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx,
+                         void* k_ret, void* v_ret, void* k_apx, int32_t cap_retain, void* ws, size_t ws_bytes, void* stream,
+                         const vec::SeqStack* stack) {
   int rc = check_shape(s, true);
   if (rc) return rc;
   const int n_retain = n_pool - n_approx;
@@ -161,11 +163,18 @@ int vector_compress(const vector_shape* s, const void* q_win, const void* k, con
   void* route_ws = reinterpret_cast<unsigned char*>(ws) + (score_ws + 255) / 256 * 256;
   // the scorer's pooling launch also builds the routing's buckets of score keys
   void* buckets = n_pool > 0 ? route_ws : nullptr;
-  if ((rc = vec::launch_score_residual(*s, q_win, k, v, W, score, eps, ws, st, nullptr, buckets))) return rc;
+  if ((rc = vec::launch_score_residual(*s, q_win, k, v, W, score, eps, ws, st, nullptr, buckets, stack))) return rc;
   if ((rc = vec::launch_route(s->n_kv_heads, s->seq_len, score, eps, n_pool, n_approx, tier, idx_retain, idx_approx, route_ws,
                               buckets != nullptr, st)))
     return rc;
-  return vec::launch_compact(*s, k, v, idx_retain, idx_approx, n_retain, n_approx, k_ret, v_ret, k_apx, cap_retain, st);
+  return vec::launch_compact(*s, k, v, idx_retain, idx_approx, n_retain, n_approx, k_ret, v_ret, k_apx, cap_retain, st, stack);
+}
+
+int vector_compress(const vector_shape* s, const void* q_win, const void* k, const void* v, const void* W, int32_t n_pool,
+                    int32_t n_approx, float* score, float* eps, uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx,
+                    void* k_ret, void* v_ret, void* k_apx, int32_t cap_retain, void* ws, size_t ws_bytes, void* stream) {
+  return compress_impl(s, q_win, k, v, W, n_pool, n_approx, score, eps, tier, idx_retain, idx_approx, k_ret, v_ret, k_apx, cap_retain,
+                       ws, ws_bytes, stream, nullptr);
 }
 
 namespace {
@@ -194,6 +203,17 @@ int check_batch(const vector_shape* s, const vector_batch* bt) {
   return VECTOR_OK;
 }
 
+// Sequences b0, b0 + 1, ... with the same length, counts and capacity are handled as one problem
+// with their heads stacked: the launches then fill the chip instead of running once per sequence.
+int run_length(const vector_shape* s, const vector_batch* bt, int b0) {
+  const int max_run = 65535 / s->n_q_heads;              // stacked head counts stay within the grid limits
+  int r = 1;
+  while (b0 + r < bt->batch && r < max_run && bt->seq_len[b0 + r] == bt->seq_len[b0] && bt->n_pool[b0 + r] == bt->n_pool[b0] &&
+         bt->n_approx[b0 + r] == bt->n_approx[b0] && bt->cap_retain[b0 + r] == bt->cap_retain[b0])
+    ++r;
+  return r;
+}
+
 BatchItem batch_item(const vector_shape* s, const vector_batch* bt, int b, int64_t total_tokens, const BatchItem* prev) {
   BatchItem it;
   it.shape = *s;
@@ -214,11 +234,15 @@ BatchItem batch_item(const vector_shape* s, const vector_batch* bt, int b, int64
 size_t vector_compress_batch_workspace_bytes(const vector_shape* s, const vector_batch* bt) {
   if (check_batch(s, bt) != VECTOR_OK) return 0;
   size_t need = 0;
-  for (int b = 0; b < bt->batch; ++b) {
+  for (int b = 0; b < bt->batch;) {
+    const int run = run_length(s, bt, b);
     vector_shape t = *s;
     t.seq_len = bt->seq_len[b];
+    t.n_kv_heads *= run;
+    t.n_q_heads *= run;
     const size_t one = vector_compress_workspace_bytes(&t, bt->n_pool[b], bt->n_approx[b]);
     if (one > need) need = one;
+    b += run;
   }
   return need;
 }
@@ -239,25 +263,35 @@ int vector_compress_batch(const vector_shape* s, const vector_batch* bt, const v
   if (total_ret > 0 && (!idx_retain || !k_ret || !v_ret || !aligned16(k_ret) || !aligned16(v_ret))) return VECTOR_ERR_ARG;
   if (total_apx > 0 && (!idx_approx || !k_apx || !aligned16(k_apx))) return VECTOR_ERR_ARG;
   if ((rc = check_ws(ws, ws_bytes, vector_compress_batch_workspace_bytes(s, bt)))) return rc;
-  // One sequence after the other on the stream, through the one-sequence pass: the launches of
-  // consecutive sequences follow each other without a host wait, and the workspace is reused in
-  // stream order.
+  // One run of equal sequences after the other on the stream, through the one-sequence pass with
+  // the run's heads stacked: the launches follow each other without a host wait, and the workspace
+  // is reused in stream order.
   const size_t esz = s->dtype == VECTOR_BF16 ? 2 : 4;
   const int64_t H = s->n_kv_heads, d = s->head_dim;
   BatchItem it{}, prev{};
+  int run_left = 0;
   for (int b = 0; b < bt->batch; ++b) {
     it = batch_item(s, bt, b, total, b ? &prev : nullptr);
     prev = it;
+    if (run_left > 0) { --run_left; continue; }          // part of the run launched at its first sequence
+    const int run = run_length(s, bt, b);
+    run_left = run - 1;
+    vec::SeqStack stack;
+    stack.heads_per_seq = s->n_kv_heads;
+    stack.k_stride_seq = (int64_t)bt->seq_len[b] * it.shape.k_stride_tok;     // ragged token axis: the next sequence follows
+    stack.v_stride_seq = (int64_t)bt->seq_len[b] * it.shape.v_stride_tok;
+    it.shape.n_kv_heads *= run;
+    it.shape.n_q_heads *= run;
     const unsigned char* kb = reinterpret_cast<const unsigned char*>(k) + (size_t)(it.tok0 * it.shape.k_stride_tok) * esz;
     const unsigned char* vb = reinterpret_cast<const unsigned char*>(v) + (size_t)(it.tok0 * it.shape.v_stride_tok) * esz;
     const unsigned char* qb = reinterpret_cast<const unsigned char*>(q_win) + (size_t)b * s->n_q_heads * s->window * d * esz;
     const int n_pool = bt->n_pool[b], n_approx = bt->n_approx[b];
-    rc = vector_compress(&it.shape, qb, kb, vb, W, n_pool, n_approx, score + H * it.tok0, eps + H * it.tok0, tier + H * it.tok0,
+    rc = compress_impl(&it.shape, qb, kb, vb, W, n_pool, n_approx, score + H * it.tok0, eps + H * it.tok0, tier + H * it.tok0,
                          idx_retain ? idx_retain + H * it.ret0 : nullptr, idx_approx ? idx_approx + H * it.apx0 : nullptr,
                          k_ret ? reinterpret_cast<unsigned char*>(k_ret) + (size_t)(H * it.cap0 * d) * esz : nullptr,
                          v_ret ? reinterpret_cast<unsigned char*>(v_ret) + (size_t)(H * it.cap0 * d) * esz : nullptr,
                          k_apx ? reinterpret_cast<unsigned char*>(k_apx) + (size_t)(H * it.apx0 * d) * esz : nullptr,
-                         bt->cap_retain[b], ws, ws_bytes, stream);
+                         bt->cap_retain[b], ws, ws_bytes, stream, run > 1 ? &stack : nullptr);
     if (rc) return rc;
   }
   return VECTOR_OK;

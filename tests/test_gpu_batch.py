@@ -25,6 +25,9 @@ BATCHES = {
     "f32_three_lengths": ("cfg1", dict(n_kv_heads=2, n_q_heads=4, window=20), (1000, 333, 1024), (0, 3, 1)),
     "bf16_one_sequence": ("cfg2", dict(n_kv_heads=1, n_q_heads=4, window=24, pool_kernel=5), (1777,), (4,)),
     "bf16_max_pool": ("cfg2", dict(n_kv_heads=2, n_q_heads=4, window=16, pool_mode="max"), (640, 900), (0, 0)),
+    # runs of equal sequences are launched with their heads stacked; a change of capacity alone ends a run
+    "bf16_equal_runs": ("cfg2", dict(n_kv_heads=2, n_q_heads=8, window=32), (1024, 1024, 1024, 700, 700, 2048, 2048), (3, 3, 3, 0, 0, 1, 2)),
+    "f32_equal_pair": ("cfg1", dict(n_kv_heads=2, n_q_heads=4, window=20), (1000, 1000), (2, 2)),
 }
 
 
@@ -122,9 +125,11 @@ def test_compress_batch_against_the_oracle_sequence_by_sequence(name):
         assert flips <= max(2, 0.004 * tier.size), what
 
 
-def test_compress_batch_equals_one_call_per_sequence():
-    """Bit for bit what vector_compress gives for each sequence alone (token-major strided K/V here)."""
-    rb = RaggedBatch("bf16_four_lengths")
+@pytest.mark.parametrize("name", ["bf16_four_lengths", "bf16_equal_runs"])
+def test_compress_batch_equals_one_call_per_sequence(name):
+    """Bit for bit what vector_compress gives for each sequence alone, also where equal sequences
+    share their launches."""
+    rb = RaggedBatch(name)
     cfg = rb.cfg
     H, d = cfg.n_kv_heads, cfg.head_dim
     shape, dev, out = _run_batch(rb)
