@@ -27,15 +27,17 @@ def _close(got, ref, what):
     assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} outside tolerance, max err {err.max():.3e}"
 
 
-def _compress_and_check(cfg, layer):
+def _compress_and_check(cfg, layer, one_call=True):
+    """one_call: the whole pass through vector_compress, as the benchmark launches it; otherwise the
+    three entry points one after the other."""
     li = wl.make_layer(cfg, layer)
     shape = pl.shape_of(cfg)
     n_r, n_a, n_p = cfg.counts()
     n, w = cfg.seq_len, cfg.window
     dev = {k: pl.to_device(getattr(li, k)) for k in ("q_win", "k", "v", "w_cal")}
-    ws = pl.alloc_workspace(vb.vector_workspace_bytes(shape, n_p, n_a, 1))
+    ws = pl.alloc_workspace(max(vb.vector_workspace_bytes(shape, n_p, n_a, 1), vb.vector_compress_workspace_bytes(shape, n_p, n_a)))
     out = pl.alloc_outputs(shape, n_p, n_a, n_r, torch.bfloat16)
-    pl.compress_layer(shape, dev["q_win"], dev["k"], dev["v"], dev["w_cal"], n_p, n_a, out, ws)
+    pl.compress_layer(shape, dev["q_win"], dev["k"], dev["v"], dev["w_cal"], n_p, n_a, out, ws, one_call=one_call)
     torch.cuda.synchronize()
     wide = {k: dg.widen(getattr(li, k)) for k in ("q_win", "k", "v", "w_cal")}
     o_score = vo.score(wide["q_win"], wide["k"], w, cfg.pool_kernel)
@@ -73,8 +75,9 @@ def _compress_and_check(cfg, layer):
         assert (tier[li.heavy] != vo.EVICT).mean() > 2 * (tier != vo.EVICT).mean()
 
 
-def test_llama_layer_8k():
-    _compress_and_check(dg.CONFIGS["cfg2"], 0)
+@pytest.mark.parametrize("one_call", [True, False])
+def test_llama_layer_8k(one_call):
+    _compress_and_check(dg.CONFIGS["cfg2"], 0, one_call)
 
 
 @pytest.mark.parametrize("layer", [0, 31])
@@ -82,10 +85,13 @@ def test_prefill_32k_layer(layer):
     _compress_and_check(dg.CONFIGS["cfg3"], layer)
 
 
-def test_prefill_32k_layers_on_three_streams():
-    """The benchmark's launch configuration: consecutive layers enqueued on three streams, each
-    with its own workspace, before anything is waited for.  Every layer is then checked as above
-    (floats against the oracle, routing and compaction bit for bit on the GPU's floats)."""
+@pytest.mark.parametrize("n_streams", [1, 3])
+def test_prefill_32k_layers_back_to_back(n_streams):
+    """The benchmark's launch configurations: consecutive layers through vector_compress, layer by
+    layer on one stream sharing one workspace (the headline), or spread over three streams with a
+    workspace each (its overlapped figure), everything enqueued before anything is waited for.
+    Every layer is then checked as above (floats against the oracle, routing and compaction bit for
+    bit on the GPU's floats)."""
     cfg = dg.CONFIGS["cfg3"]
     layers = [4, 5, 6, 7, 8, 9]
     shape = pl.shape_of(cfg)
@@ -95,13 +101,14 @@ def test_prefill_32k_layers_on_three_streams():
     with threadpool_limits(limits=1), ThreadPoolExecutor(6) as ex:
         lis = list(ex.map(lambda l: wl.make_layer(cfg, l), layers))
     devs = [{k: pl.to_device(getattr(li, k)) for k in ("q_win", "k", "v", "w_cal")} for li in lis]
-    streams = [torch.cuda.Stream() for _ in range(3)]
-    wss = [pl.alloc_workspace(vb.vector_workspace_bytes(shape, n_p, n_a, 1)) for _ in range(3)]
+    streams = [torch.cuda.Stream() for _ in range(n_streams)]
+    wss = [pl.alloc_workspace(vb.vector_compress_workspace_bytes(shape, n_p, n_a)) for _ in range(n_streams)]
     outs = [pl.alloc_outputs(shape, n_p, n_a, n_r, torch.bfloat16) for _ in layers]
     torch.cuda.synchronize()
     for rep in range(2):                               # the second round reuses the workspaces while the first drains
         for i, (dev, out) in enumerate(zip(devs, outs)):
-            pl.compress_layer(shape, dev["q_win"], dev["k"], dev["v"], dev["w_cal"], n_p, n_a, out, wss[i % 3], stream=streams[i % 3])
+            pl.compress_layer(shape, dev["q_win"], dev["k"], dev["v"], dev["w_cal"], n_p, n_a, out, wss[i % n_streams],
+                              stream=streams[i % n_streams], one_call=True)
     torch.cuda.synchronize()
     for li, out in list(zip(lis, outs))[::2]:          # the oracle takes a few seconds per layer: every other one
         wide = {k: dg.widen(getattr(li, k)) for k in ("q_win", "k", "v", "w_cal")}
