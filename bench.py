@@ -457,6 +457,16 @@ def run_extras(vb, dg, pl, torch, np, dev, cfg, shape, layer, out, ws, n_p, n_a)
     res["decode_attn_us_per_step"] = per_call_us(lambda: vb.vector_decode_attn(cache, q, scale, o5, ws5), 50)
     res["decode_attn_literal_us_per_step"] = per_call_us(
         lambda: vb.vector_decode_attn(cache, q, scale, o5, ws5, flags=vb.VECTOR_DECODE_LITERAL), 50)
+    # the same retained rows read through a block table (blocks of 64 rows in shuffled order)
+    blk = 64
+    bps = (n_r5 + blk - 1) // blk
+    table = torch.randperm(B * H * bps, generator=torch.Generator().manual_seed(3)).to(torch.int32).to(dev)
+    k_pool, v_pool = rnd(B * H * bps, blk, d), rnd(B * H * bps, blk, d)
+    paged = vb.Cache(batch=B, n_q_heads=c5.n_q_heads, n_kv_heads=H, head_dim=d, dtype=vb.VECTOR_BF16, cap_retain=n_r5, n_approx=n_a5)
+    paged.len_retain, paged.k_ret, paged.v_ret = length.data_ptr(), k_pool.data_ptr(), v_pool.data_ptr()
+    paged.k_apx, paged.W = k_apx.data_ptr(), layer["w_cal"].data_ptr()
+    paged.ret_block_table, paged.ret_block_rows, paged.ret_blocks_per_seq = table.data_ptr(), blk, bps
+    res["decode_attn_paged_us_per_step"] = per_call_us(lambda: vb.vector_decode_attn(paged, q, scale, o5, ws5), 50)
     # calibration on 262144 tokens per head (random keys, values linear in them plus noise)
     m = 262144
     kc = rnd(H, m, d)

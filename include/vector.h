@@ -235,6 +235,17 @@ typedef struct {
   const int32_t* n_approx_seq;
   const int64_t* ret_row_start;
   const int64_t* apx_row_start;
+  /* Paged retained segments (the segment that grows during generation): ret_block_table null, or a
+   * device array [batch, Hkv, ret_blocks_per_seq] of block ids.  Then k_ret / v_ret are pools of
+   * blocks of ret_block_rows rows each ([n_blocks, ret_block_rows, d]; ret_block_rows a power of two,
+   * at least 16), row r of sequence b and KV head h is row r % ret_block_rows of block
+   * ret_block_table[b][h][r / ret_block_rows], and cap_retain <= ret_blocks_per_seq * ret_block_rows is
+   * the capacity of every sequence (table entries up to that capacity must name blocks that exist).
+   * The per-sequence arrays above must be null with a block table; the approximated segment stays
+   * contiguous ([batch, Hkv, n_approx, d]). */
+  const int32_t* ret_block_table;
+  int32_t ret_block_rows;
+  int32_t ret_blocks_per_seq;
 } vector_cache;
 
 /* One query token per sequence (Section 3.2 Step 3: discarded values are

@@ -76,6 +76,7 @@ class Cache(C.Structure):
         ("W", C.c_void_p),
         ("cap_retain_seq", C.c_void_p), ("n_approx_seq", C.c_void_p), ("ret_row_start", C.c_void_p),
         ("apx_row_start", C.c_void_p),
+        ("ret_block_table", C.c_void_p), ("ret_block_rows", C.c_int32), ("ret_blocks_per_seq", C.c_int32),
     ]
 
 

@@ -38,6 +38,10 @@ struct DecodeParams {
   // the step's own token (null: none): exact key and value [B, Hkv, D]; it is attended as row
   // len_retain[b] of the retained segment and stored there when the block has room
   const void* k_new; const void* v_new;
+  // paged retained segments (null: contiguous): block ids [B, Hkv, blocks_per_seq]; a block is
+  // 1 << block_shift rows of the k_ret / v_ret pools
+  const int32_t* block_table;
+  int block_shift, blocks_per_seq;
   void* out;
   float* part;            // [B, Hkv, S, 2*G + G*D] floats: m[G], l[G], acc[G][D]
   int B, Hq, Hkv, cap_retain, n_approx;
@@ -50,7 +54,19 @@ struct DecodeParams {
 
 // Where the rows of one (sequence, KV head) lie: row offsets into k_ret / v_ret and into k_apx,
 // the live length of the retained segment and the length of the approximated one.
-struct SegmentRows { size_t ret_row0, apx_row0; int len_retain, n_approx, new_row, cap; };
+struct SegmentRows {
+  size_t ret_row0, apx_row0;
+  int len_retain, n_approx, new_row, cap;
+  const int32_t* blocks;      // paged: this (sequence, head)'s block ids; ret_row0 is then 0
+  int block_shift;
+};
+// row r of the retained segment as a row of the k_ret / v_ret arrays.  PAGED is a template
+// argument of the kernels: the lookups cost registers that the contiguous layout should not pay.
+template <bool PAGED>
+__device__ __forceinline__ size_t retained_row(const SegmentRows& s, int r) {
+  if (PAGED) return ((size_t)s.blocks[r >> s.block_shift] << s.block_shift) + (size_t)(r & ((1 << s.block_shift) - 1));
+  return s.ret_row0 + (size_t)r;
+}
 __device__ __forceinline__ SegmentRows segment_rows(const DecodeParams& p, int b, int h) {
   SegmentRows s;
   int cap = p.cap_retain;
@@ -65,6 +81,13 @@ __device__ __forceinline__ SegmentRows segment_rows(const DecodeParams& p, int b
     s.ret_row0 = bh * cap;
     s.apx_row0 = bh * s.n_approx;
   }
+  s.blocks = nullptr;
+  s.block_shift = 0;
+  if (p.block_table) {
+    s.blocks = p.block_table + ((size_t)b * p.Hkv + h) * p.blocks_per_seq;
+    s.block_shift = p.block_shift;
+    s.ret_row0 = 0;
+  }
   s.len_retain = min(max(p.len_retain[b], 0), cap);
   s.cap = cap;
   s.new_row = -1;
@@ -75,7 +98,7 @@ __device__ __forceinline__ SegmentRows segment_rows(const DecodeParams& p, int b
 // The workgroup whose rows include the step's own token stores it in the cache (when the block has
 // room) for the steps to come; this step reads it from the caller's buffers, so nothing waits for
 // the store.
-template <typename T, int D>
+template <typename T, int D, bool PAGED>
 __device__ __forceinline__ void append_new_row(const DecodeParams& p, const SegmentRows& seg, bool is_apx, int row_begin, int row_end,
                                                const T* k_new, const T* v_new) {
   constexpr int kPieces = D * (int)sizeof(T) / 16;
@@ -84,7 +107,7 @@ __device__ __forceinline__ void append_new_row(const DecodeParams& p, const Segm
     const int piece = (int)threadIdx.x % kPieces;
     const bool is_v = (int)threadIdx.x >= kPieces;
     unsigned char* dst = reinterpret_cast<unsigned char*>(const_cast<void*>(is_v ? p.v_ret : p.k_ret)) +
-                         (seg.ret_row0 + (size_t)seg.new_row) * D * sizeof(T) + piece * 16;
+                         retained_row<PAGED>(seg, seg.new_row) * D * sizeof(T) + piece * 16;
     const unsigned char* src = reinterpret_cast<const unsigned char*>(is_v ? v_new : k_new) + piece * 16;
     *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
   }
@@ -119,7 +142,7 @@ template <int LPR> __device__ __forceinline__ float group_sum(float x) {
   }
 }
 
-template <typename T, int D, int G>
+template <typename T, int D, int G, bool PAGED = false>
 __global__ __launch_bounds__(DT_) void decode_split_kernel(DecodeParams p) {
   constexpr int E = Elem<T>::kPerChunk;          // elements per 16-byte piece
   constexpr int LPR = D / E;                     // lanes per row
@@ -144,12 +167,13 @@ __global__ __launch_bounds__(DT_) void decode_split_kernel(DecodeParams p) {
   const int row_end = min(seg_len, (int)((int64_t)steps * (sp + 1) / n_sp) * kStepRows);
 
   const size_t bh = (size_t)b * p.Hkv + h;
-  const T* kseg = is_apx ? reinterpret_cast<const T*>(p.k_apx) + seg.apx_row0 * D
-                         : reinterpret_cast<const T*>(p.k_ret) + seg.ret_row0 * D;
-  const T* vseg = reinterpret_cast<const T*>(p.v_ret) + seg.ret_row0 * D;
+  // a segment's rows: the approximated block, the retained block, or (paged) the retained pool
+  const T* kseg = is_apx ? reinterpret_cast<const T*>(p.k_apx) + seg.apx_row0 * D : reinterpret_cast<const T*>(p.k_ret);
+  const T* vseg = reinterpret_cast<const T*>(p.v_ret);
+  auto seg_row = [&](int r) { return is_apx ? (size_t)r : retained_row<PAGED>(seg, r); };
   const T* k_new = p.k_new ? reinterpret_cast<const T*>(p.k_new) + bh * D : kseg;
   const T* v_new = p.k_new ? reinterpret_cast<const T*>(p.v_new) + bh * D : vseg;
-  append_new_row<T, D>(p, seg, is_apx, row_begin, row_end, k_new, v_new);
+  append_new_row<T, D, PAGED>(p, seg, is_apx, row_begin, row_end, k_new, v_new);
 
   // this lane's slice of the G query rows, pre-scaled into the log2 domain
   float qf[G][E];
@@ -177,8 +201,9 @@ __global__ __launch_bounds__(DT_) void decode_split_kernel(DecodeParams p) {
     for (int u = 0; u < kUnroll; ++u) {
       const int r = min(r0 + u, seg_len - 1);      // clamped: never reads past the live rows
       const bool fresh = !is_apx && r == seg.new_row;        // the step's own token comes from the caller's buffers
-      kraw[u] = load_chunk(fresh ? k_new + piece * E : kseg + (size_t)r * D + piece * E);
-      if (!is_apx) vraw[u] = load_chunk(fresh ? v_new + piece * E : vseg + (size_t)r * D + piece * E);
+      const size_t at = seg_row(fresh ? 0 : r) * D + piece * E;
+      kraw[u] = load_chunk(fresh ? k_new + piece * E : kseg + at);
+      if (!is_apx) vraw[u] = load_chunk(fresh ? v_new + piece * E : vseg + at);
     }
   };
   auto consume = [&](const uint4* kraw, const uint4* vraw, int base) {
@@ -332,7 +357,7 @@ template <int D> struct MfmaDecodeTile {
 // rows that stand in for values of approximated tokens are the keys turned back by their
 // original positions (rp.positions, one per row of k_apx), written to the second tile as bf16.
 // LITERAL: approximated rows are rebuilt one by one, v_hat = k W, before they are weighted.
-template <int D, int G, bool ROPE, bool LITERAL = false>
+template <int D, int G, bool ROPE, bool LITERAL = false, bool PAGED = false>
 __global__ __launch_bounds__(DT_, 2) void decode_split_mfma_kernel(DecodeParams p, RopeParams rp) {
   using T = bf16_t;
   using TL = MfmaDecodeTile<D>;
@@ -358,12 +383,13 @@ __global__ __launch_bounds__(DT_, 2) void decode_split_mfma_kernel(DecodeParams 
   const int row_end = min(seg_len, (int)((int64_t)steps * (sp + 1) / n_sp) * kStepRows);
 
   const size_t bh = (size_t)b * p.Hkv + h;
-  const T* kseg = is_apx ? reinterpret_cast<const T*>(p.k_apx) + seg.apx_row0 * D
-                         : reinterpret_cast<const T*>(p.k_ret) + seg.ret_row0 * D;
-  const T* vseg = reinterpret_cast<const T*>(p.v_ret) + seg.ret_row0 * D;
+  // a segment's rows: the approximated block, the retained block, or (paged) the retained pool
+  const T* kseg = is_apx ? reinterpret_cast<const T*>(p.k_apx) + seg.apx_row0 * D : reinterpret_cast<const T*>(p.k_ret);
+  const T* vseg = reinterpret_cast<const T*>(p.v_ret);
+  auto seg_row = [&](int r) { return is_apx ? (size_t)r : retained_row<PAGED>(seg, r); };
   const T* k_new = p.k_new ? reinterpret_cast<const T*>(p.k_new) + bh * D : kseg;
   const T* v_new = p.k_new ? reinterpret_cast<const T*>(p.v_new) + bh * D : vseg;
-  append_new_row<T, D>(p, seg, is_apx, row_begin, row_end, k_new, v_new);
+  append_new_row<T, D, PAGED>(p, seg, is_apx, row_begin, row_end, k_new, v_new);
 
   unsigned char* k_tile = dec_lds + wave * 2 * TL::kTileBytes;
   unsigned char* v_tile = k_tile + TL::kTileBytes;
@@ -402,14 +428,31 @@ __global__ __launch_bounds__(DT_, 2) void decode_split_mfma_kernel(DecodeParams 
   // (in .x) instead of a value row.
   // (the segment is the same for the whole workgroup: one straight-line loop per case, so that
   // all loads of a tile go out together)
+  // Paged with blocks of at least a tile's 32 rows: tiles start at multiples of 32 rows, so a tile
+  // lies in one block.  The block ids of the workgroup's row range sit in one register across the
+  // wave (lane j: block (row_begin / block rows) + j), read once before the loop; a tile's id then
+  // comes out of that register instead of memory.
+  const bool tile_in_block = PAGED && !is_apx && seg.block_shift >= 5 &&
+                             ((row_end - 1) >> seg.block_shift) - (row_begin >> seg.block_shift) < kWave;
+  int my_block = 0;
+  if (tile_in_block && row_begin < row_end) {
+    const int j = min((row_begin >> seg.block_shift) + lane, (row_end - 1) >> seg.block_shift);
+    my_block = seg.blocks[j];
+  }
   auto fetch = [&](uint4* kraw, uint4* vraw, int base) {
     if (!ROPE || !is_apx) {
+      size_t tile_shift = 0;                     // paged, one block per tile: array row = tile_shift + segment row
+      if (tile_in_block) {
+        const int blk = __builtin_amdgcn_readlane(my_block, (base >> seg.block_shift) - (row_begin >> seg.block_shift));
+        tile_shift = ((size_t)blk << seg.block_shift) - (size_t)((base >> seg.block_shift) << seg.block_shift);
+      }
 #pragma unroll
       for (int i = 0; i < TL::kLoads; ++i) {
         const int r = min(base + i * TL::kRowsPerLoad + ld_row, seg_len - 1);   // clamped: never past the live rows
         const bool fresh = !is_apx && r == seg.new_row;      // the step's own token comes from the caller's buffers
-        kraw[i] = load_chunk(fresh ? k_new + ld_piece * 8 : kseg + (size_t)r * D + ld_piece * 8);
-        if (!is_apx) vraw[i] = load_chunk(fresh ? v_new + ld_piece * 8 : vseg + (size_t)r * D + ld_piece * 8);
+        const size_t at = (tile_in_block ? tile_shift + (size_t)r : seg_row(fresh ? 0 : r)) * D + ld_piece * 8;
+        kraw[i] = load_chunk(fresh ? k_new + ld_piece * 8 : kseg + at);
+        if (!is_apx) vraw[i] = load_chunk(fresh ? v_new + ld_piece * 8 : vseg + at);
       }
     } else {
 #pragma unroll
@@ -798,28 +841,33 @@ void pick_splits(int target, int batch, int n_kv_heads, int cap_retain, int n_ap
   if (s_ret + s_apx == 0) s_ret = 1;             // nothing cached: one workgroup writes the empty partial
 }
 
-template <typename T, int D, int G>
-int run_decode(const vector_cache& c, DecodeParams& p, hipStream_t stream, const RopeParams* rope) {
+template <typename T, int D, int G, bool PAGED>
+int run_decode_layout(const vector_cache& c, DecodeParams& p, hipStream_t stream, const RopeParams* rope) {
   const dim3 grid(p.splits_ret + p.splits_apx, c.n_kv_heads, c.batch);
   if constexpr (Elem<T>::kDtype == VECTOR_BF16) {
     constexpr int lds = MfmaDecodeTile<D>::kLdsBytes;
     if (rope) {
-      VEC_HIP(set_max_lds(reinterpret_cast<const void*>(decode_split_mfma_kernel<D, G, true>), lds));
-      VEC_LAUNCH(K_DECODE_SPLIT, (decode_split_mfma_kernel<D, G, true>), grid, dim3(DT_), lds, stream, p, *rope);
+      VEC_HIP(set_max_lds(reinterpret_cast<const void*>(decode_split_mfma_kernel<D, G, true, false, PAGED>), lds));
+      VEC_LAUNCH(K_DECODE_SPLIT, (decode_split_mfma_kernel<D, G, true, false, PAGED>), grid, dim3(DT_), lds, stream, p, *rope);
     } else if (p.literal) {
-      VEC_HIP(set_max_lds(reinterpret_cast<const void*>(decode_split_mfma_kernel<D, G, false, true>), lds));
-      VEC_LAUNCH(K_DECODE_SPLIT, (decode_split_mfma_kernel<D, G, false, true>), grid, dim3(DT_), lds, stream, p, RopeParams{});
+      VEC_HIP(set_max_lds(reinterpret_cast<const void*>(decode_split_mfma_kernel<D, G, false, true, PAGED>), lds));
+      VEC_LAUNCH(K_DECODE_SPLIT, (decode_split_mfma_kernel<D, G, false, true, PAGED>), grid, dim3(DT_), lds, stream, p, RopeParams{});
     } else {
-      VEC_HIP(set_max_lds(reinterpret_cast<const void*>(decode_split_mfma_kernel<D, G, false>), lds));
-      VEC_LAUNCH(K_DECODE_SPLIT, (decode_split_mfma_kernel<D, G, false>), grid, dim3(DT_), lds, stream, p, RopeParams{});
+      VEC_HIP(set_max_lds(reinterpret_cast<const void*>(decode_split_mfma_kernel<D, G, false, false, PAGED>), lds));
+      VEC_LAUNCH(K_DECODE_SPLIT, (decode_split_mfma_kernel<D, G, false, false, PAGED>), grid, dim3(DT_), lds, stream, p, RopeParams{});
     }
   } else {
     if (rope) return VECTOR_ERR_DTYPE;             // rotary caches: bf16 only
-    VEC_LAUNCH(K_DECODE_SPLIT, (decode_split_kernel<T, D, G>), grid, dim3(DT_), 0, stream, p);
+    VEC_LAUNCH(K_DECODE_SPLIT, (decode_split_kernel<T, D, G, PAGED>), grid, dim3(DT_), 0, stream, p);
   }
   VEC_LAUNCH(K_DECODE_COMBINE, (decode_combine_kernel<T, D, G>), dim3(c.n_kv_heads, c.batch), dim3(256), 0, stream, p);
   VEC_HIP(hipGetLastError());
   return VECTOR_OK;
+}
+
+template <typename T, int D, int G>
+int run_decode(const vector_cache& c, DecodeParams& p, hipStream_t stream, const RopeParams* rope) {
+  return p.block_table ? run_decode_layout<T, D, G, true>(c, p, stream, rope) : run_decode_layout<T, D, G, false>(c, p, stream, rope);
 }
 
 template <typename T, int D>
@@ -854,6 +902,8 @@ int launch_decode_attn(const vector_cache& c, const void* q, float scale, void* 
   if (p.literal && (rope || c.dtype != VECTOR_BF16)) return VECTOR_ERR_DTYPE;
   p.q = q; p.k_ret = c.k_ret; p.v_ret = c.v_ret; p.k_apx = c.k_apx; p.W = c.W; p.len_retain = c.len_retain;
   p.k_new = k_new; p.v_new = v_new;
+  p.block_table = c.ret_block_table; p.block_shift = 0; p.blocks_per_seq = c.ret_blocks_per_seq;
+  while (c.ret_block_table && (1 << p.block_shift) < c.ret_block_rows) ++p.block_shift;
   p.cap_retain_seq = c.cap_retain_seq; p.n_approx_seq = c.n_approx_seq;
   p.ret_row_start = c.ret_row_start; p.apx_row_start = c.apx_row_start;
   p.out = out; p.part = reinterpret_cast<float*>(ws);

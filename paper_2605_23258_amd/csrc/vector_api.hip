@@ -410,6 +410,11 @@ static int decode_checked(const vector_cache* c, const void* q, float scale, voi
   const int n_seq_arrays = (c->cap_retain_seq != nullptr) + (c->n_approx_seq != nullptr) + (c->ret_row_start != nullptr) +
                            (c->apx_row_start != nullptr);
   if (n_seq_arrays != 0 && n_seq_arrays != 4) return VECTOR_ERR_ARG;
+  if (c->ret_block_table) {
+    const int rows = c->ret_block_rows;
+    if (n_seq_arrays != 0 || rows < 16 || (rows & (rows - 1)) || c->ret_blocks_per_seq < 1) return VECTOR_ERR_ARG;
+    if ((int64_t)c->cap_retain > (int64_t)c->ret_blocks_per_seq * rows) return VECTOR_ERR_ARG;
+  }
   if (c->cap_retain > 0 && (!c->k_ret || !c->v_ret || !aligned16(c->k_ret) || !aligned16(c->v_ret))) return VECTOR_ERR_ARG;
   if (c->n_approx > 0 && (!c->k_apx || !c->W || !aligned16(c->k_apx) || !aligned16(c->W))) return VECTOR_ERR_ARG;
   if (!aligned16(q) || !aligned16(out)) return VECTOR_ERR_ARG;

@@ -183,3 +183,79 @@ def test_step_over_per_sequence_blocks_and_bad_arguments():
     with pytest.raises(vb.VectorError) as ei:
         vb.vector_decode_step(cache, dq, dk, dv, scale, out, ws, flags=vb.VECTOR_DECODE_OUT_F32)
     assert ei.value.code == vb.VECTOR_ERR_ARG
+
+
+@pytest.mark.parametrize("dtype,d,block_rows", [("bf16", 128, 64), ("bf16", 64, 16), ("f32", 64, 32)])
+def test_paged_retained_segments(dtype, d, block_rows):
+    """Retained segments scattered over a pool of blocks: attention and two steps with appends give
+    what the oracle gives on the same rows laid out contiguously; new rows land in the right blocks."""
+    Hq, H, B, n_a = 8, 2, 3, 50
+    blocks_per_seq = 5
+    cap = blocks_per_seq * block_rows
+    lens = np.array([block_rows * 2 - 1, 0, cap - 2], dtype=np.int32)       # a block boundary, an empty and a nearly full sequence
+    is_bf = dtype == "bf16"
+    store = _store(dtype)
+    rng = np.random.default_rng(zlib.crc32(f"paged {dtype} {d} {block_rows}".encode()))
+    k_lin, v_lin = store(rng.standard_normal((B, H, cap, d))), store(rng.standard_normal((B, H, cap, d)))
+    k_apx, W = store(rng.standard_normal((B, H, n_a, d))), store(rng.standard_normal((H, d, d)) / np.sqrt(d))
+    # a shuffled block table over a pool with some blocks nobody owns
+    n_blocks = B * H * blocks_per_seq + 7
+    table = rng.permutation(n_blocks)[: B * H * blocks_per_seq].astype(np.int32).reshape(B, H, blocks_per_seq)
+    k_pool = store(np.full((n_blocks, block_rows, d), 3e30))
+    v_pool = store(np.full((n_blocks, block_rows, d), -3e30))
+    for b in range(B):
+        for h in range(H):
+            for j in range(blocks_per_seq):
+                k_pool[table[b, h, j]] = k_lin[b, h, j * block_rows: (j + 1) * block_rows]
+                v_pool[table[b, h, j]] = v_lin[b, h, j * block_rows: (j + 1) * block_rows]
+    t = dict(len=pl.to_device(lens), k=pl.to_device(k_pool), v=pl.to_device(v_pool), k_apx=pl.to_device(k_apx), W=pl.to_device(W),
+             table=pl.to_device(table))
+    cache = vb.Cache(batch=B, n_q_heads=Hq, n_kv_heads=H, head_dim=d, dtype=vb.VECTOR_BF16 if is_bf else vb.VECTOR_F32,
+                     cap_retain=cap, n_approx=n_a)
+    cache.len_retain, cache.k_ret, cache.v_ret = t["len"].data_ptr(), t["k"].data_ptr(), t["v"].data_ptr()
+    cache.k_apx, cache.W = t["k_apx"].data_ptr(), t["W"].data_ptr()
+    cache.ret_block_table, cache.ret_block_rows, cache.ret_blocks_per_seq = t["table"].data_ptr(), block_rows, blocks_per_seq
+    shape = vb.Shape(n_q_heads=Hq, n_kv_heads=H, head_dim=d, seq_len=max(cap, 64), window=1, pool_kernel=1, dtype=cache.dtype)
+    ws = pl.alloc_workspace(vb.vector_workspace_bytes(shape, cap, 0, B) + (1 << 20))
+    scale = 1.0 / np.sqrt(d)
+    host_k, host_v, host_len = k_lin.copy(), v_lin.copy(), lens.copy()
+    q = store(rng.standard_normal((B, Hq, d)))
+    ref = vo.decode_attn(dg.widen(q), dg.widen(host_k), dg.widen(host_v), host_len, dg.widen(k_apx), dg.widen(W), scale)
+    out = torch.full((B, Hq, d), 7.0, dtype=torch.float32, device="cuda:0")
+    vb.vector_decode_attn(cache, pl.to_device(q), scale, out, ws, flags=vb.VECTOR_DECODE_OUT_F32)
+    torch.cuda.synchronize()
+    close(out.cpu().numpy(), ref, "paged attention")
+    for step in range(2):
+        q = store(rng.standard_normal((B, Hq, d)))
+        k_new, v_new = store(rng.standard_normal((B, H, d))), store(rng.standard_normal((B, H, d)))
+        ref = _oracle_step(q, host_k, host_v, host_len, k_new, v_new, k_apx, W, scale)
+        vb.vector_decode_step(cache, pl.to_device(q), pl.to_device(k_new), pl.to_device(v_new), scale, out, ws,
+                              flags=vb.VECTOR_DECODE_OUT_F32)
+        torch.cuda.synchronize()
+        close(out.cpu().numpy(), ref, f"paged step {step}")
+        got_k, got_v = pl.to_host(t["k"]), pl.to_host(t["v"])
+        for b in range(B):
+            r = int(host_len[b])
+            assert r < cap
+            for h in range(H):
+                blk, off = table[b, h, r // block_rows], r % block_rows
+                assert np.array_equal(got_k[blk, off], k_new[b, h]) and np.array_equal(got_v[blk, off], v_new[b, h])
+            host_k[b, :, r], host_v[b, :, r] = k_new[b], v_new[b]
+            host_len[b] += 1
+        assert np.array_equal(t["len"].cpu().numpy(), host_len)
+    # blocks nobody owns are untouched
+    owned = set(table.reshape(-1).tolist())
+    got_k = pl.to_host(t["k"])
+    for blk in range(n_blocks):
+        if blk not in owned:
+            assert np.array_equal(got_k[blk], k_pool[blk])
+    # a block table excludes per-sequence arrays, and needs a power-of-two block
+    cache.ret_block_rows = 48
+    with pytest.raises(vb.VectorError) as ei:
+        vb.vector_decode_attn(cache, pl.to_device(q), scale, out, ws, flags=vb.VECTOR_DECODE_OUT_F32)
+    assert ei.value.code == vb.VECTOR_ERR_ARG
+    cache.ret_block_rows = block_rows
+    cache.cap_retain = cap + 1
+    with pytest.raises(vb.VectorError) as ei:
+        vb.vector_decode_attn(cache, pl.to_device(q), scale, out, ws, flags=vb.VECTOR_DECODE_OUT_F32)
+    assert ei.value.code == vb.VECTOR_ERR_ARG

@@ -27,7 +27,7 @@ def test_header_symbols_are_exported():
 def test_struct_sizes_match_header_layout():
     import ctypes
     assert ctypes.sizeof(vb.Shape) == 8 * 4 + 5 * 8 + 2 * 4
-    assert ctypes.sizeof(vb.Cache) == 8 * 4 + 5 * 8 + 4 * 8
+    assert ctypes.sizeof(vb.Cache) == 8 * 4 + 5 * 8 + 4 * 8 + 8 + 2 * 4
     assert ctypes.sizeof(vb.Batch) == 8 + 4 * 8
 
 
