@@ -43,9 +43,9 @@ struct RopeParams;
 // Several sequences of one shape handled as one problem with batch * Hkv heads (the shape passed
 // along says so: n_kv_heads and n_q_heads are the stacked counts).  Head hv of the launch is KV
 // head hv % heads_per_seq of sequence hv / heads_per_seq: its keys and values lie
-// k_stride_seq / v_stride_seq elements (rows: k_stride_seq etc. of launch_compact are in elements
-// too) after the previous sequence's, its W is that KV head's.  Every other array is indexed by
-// hv as it is.
+// k_stride_seq / v_stride_seq elements after the previous sequence's (the strides inside a
+// sequence stay the shape's), and its W is that KV head's.  Every other array is indexed by hv
+// as it is.
 struct SeqStack { int heads_per_seq; int64_t k_stride_seq, v_stride_seq; };
 
 int launch_score_residual(const vector_shape& s, const void* q, const void* k, const void* v, const void* W,
