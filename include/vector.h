@@ -325,7 +325,7 @@ VECTOR_API int vector_score_residual_rope(const vector_shape* shape, const void*
                                const void* W, const vector_rope* rope, float* score, float* eps, void* ws,
                                size_t ws_bytes, void* stream);
 /* vector_decode_attn on a post-RoPE cache: out = sum_ret p_t v_t + sum_apx p_t ((R^-1 k_t) . W[h]),
- * logits from the cached keys.  bf16 caches only (VECTOR_ERR_DTYPE otherwise). */
+ * logits from the cached keys.  VECTOR_DECODE_LITERAL is not available here (VECTOR_ERR_DTYPE). */
 VECTOR_API int vector_decode_attn_rope(const vector_cache* cache, const vector_rope* rope, const void* q, float scale,
                             void* out, int32_t flags, void* ws, size_t ws_bytes, void* stream);
 /* vector_decode_step on a post-RoPE cache: k_new is the new token's key as cached (after its rotary

@@ -142,8 +142,11 @@ template <int LPR> __device__ __forceinline__ float group_sum(float x) {
   }
 }
 
-template <typename T, int D, int G, bool PAGED = false>
-__global__ __launch_bounds__(DT_) void decode_split_kernel(DecodeParams p) {
+// ROPE: the cache holds keys after their rotary embedding; logits use them as cached, and the rows
+// that stand in for values of approximated tokens are the keys turned back by their original
+// positions (rp.positions, one per row of k_apx).
+template <typename T, int D, int G, bool PAGED = false, bool ROPE = false>
+__global__ __launch_bounds__(DT_) void decode_split_kernel(DecodeParams p, RopeParams rp) {
   constexpr int E = Elem<T>::kPerChunk;          // elements per 16-byte piece
   constexpr int LPR = D / E;                     // lanes per row
   constexpr int RPI = kWave / LPR;               // rows per wave-wide load instruction
@@ -193,6 +196,41 @@ __global__ __launch_bounds__(DT_) void decode_split_kernel(DecodeParams p) {
     for (int e = 0; e < E; ++e) acc[g][e] = 0.f;
   }
 
+  // ROPE: the rotary pair of each of the lane's E elements, and its frequency.  Pairs (x[2i], x[2i+1])
+  // lie inside the lane's piece; pairs (x[i], x[i + D/2]) are split between this lane and the lane
+  // LPR/2 further along the row, which holds the same e of the other half.
+  const int32_t* pos_seg = (ROPE && is_apx && rp.positions) ? rp.positions + seg.apx_row0 : nullptr;
+  const bool lower_half = piece < LPR / 2;
+  float t_hi[E], t_lo[E];
+  if (ROPE && is_apx) {
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      const int i = rp.interleaved ? (piece * E + e) / 2 : (piece % (LPR / 2)) * E + e;
+      t_hi[e] = rp.turns_hi[i];
+      t_lo[e] = rp.turns_lo[i];
+    }
+  }
+  auto unrotate_row = [&](const float* kf, int pos, float* out) {
+    const float pf = (float)pos;
+    if (rp.interleaved) {
+#pragma unroll
+      for (int e = 0; e < E; e += 2) {
+        float cs, sn;
+        rotary_cos_sin(pf, t_hi[e], t_lo[e], cs, sn);
+        rotary_back(kf[e], kf[e + 1], cs, sn, out[e], out[e + 1]);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        const float other = __shfl_xor(kf[e], LPR / 2, kWave);
+        float cs, sn, a_pre, b_pre;
+        rotary_cos_sin(pf, t_hi[e], t_lo[e], cs, sn);
+        rotary_back(lower_half ? kf[e] : other, lower_half ? other : kf[e], cs, sn, a_pre, b_pre);
+        out[e] = lower_half ? a_pre : b_pre;
+      }
+    }
+  };
+
   // The loop bound is the same for every lane of a wave; rows past the range are masked.
   // The rows of the next step are requested before the current ones are consumed.
   auto fetch = [&](uint4* kraw, uint4* vraw, int base) {
@@ -204,6 +242,7 @@ __global__ __launch_bounds__(DT_) void decode_split_kernel(DecodeParams p) {
       const size_t at = seg_row(fresh ? 0 : r) * D + piece * E;
       kraw[u] = load_chunk(fresh ? k_new + piece * E : kseg + at);
       if (!is_apx) vraw[u] = load_chunk(fresh ? v_new + piece * E : vseg + at);
+      else if (ROPE) vraw[u].x = (uint32_t)((pos_seg ? pos_seg[r] : r) + rp.pos_offset);    // the row's position rides along
     }
   };
   auto consume = [&](const uint4* kraw, const uint4* vraw, int base) {
@@ -240,8 +279,12 @@ __global__ __launch_bounds__(DT_) void decode_split_kernel(DecodeParams p) {
       }
       float rowf[E];
       if (is_apx) {
+        if (ROPE) {
+          unrotate_row(kf, (int)vraw[u].x, rowf);
+        } else {
 #pragma unroll
-        for (int e = 0; e < E; ++e) rowf[e] = kf[e];
+          for (int e = 0; e < E; ++e) rowf[e] = kf[e];
+        }
       } else {
         Unpack16<T>::run(vraw[u], rowf);
       }
@@ -857,8 +900,11 @@ int run_decode_layout(const vector_cache& c, DecodeParams& p, hipStream_t stream
       VEC_LAUNCH(K_DECODE_SPLIT, (decode_split_mfma_kernel<D, G, false, false, PAGED>), grid, dim3(DT_), lds, stream, p, RopeParams{});
     }
   } else {
-    if (rope) return VECTOR_ERR_DTYPE;             // rotary caches: bf16 only
-    VEC_LAUNCH(K_DECODE_SPLIT, (decode_split_kernel<T, D, G, PAGED>), grid, dim3(DT_), 0, stream, p);
+    if (rope) {
+      VEC_LAUNCH(K_DECODE_SPLIT, (decode_split_kernel<T, D, G, PAGED, true>), grid, dim3(DT_), 0, stream, p, *rope);
+    } else {
+      VEC_LAUNCH(K_DECODE_SPLIT, (decode_split_kernel<T, D, G, PAGED, false>), grid, dim3(DT_), 0, stream, p, RopeParams{});
+    }
   }
   VEC_LAUNCH(K_DECODE_COMBINE, (decode_combine_kernel<T, D, G>), dim3(c.n_kv_heads, c.batch), dim3(256), 0, stream, p);
   VEC_HIP(hipGetLastError());

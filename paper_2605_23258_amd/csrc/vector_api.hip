@@ -397,7 +397,6 @@ static int decode_checked(const vector_cache* c, const void* q, float scale, voi
   if (!c || !q || !out) return VECTOR_ERR_ARG;
   if (step && (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new) || c->cap_retain < 1)) return VECTOR_ERR_ARG;
   if (c->dtype != VECTOR_F32 && c->dtype != VECTOR_BF16) return VECTOR_ERR_DTYPE;
-  if (rope && c->dtype != VECTOR_BF16) return VECTOR_ERR_DTYPE;
   if (c->head_dim != 64 && c->head_dim != 128) return VECTOR_ERR_SHAPE;
   if (c->batch < 1 || c->batch > 65535 || c->n_kv_heads < 1 || c->n_kv_heads > 65535) return VECTOR_ERR_SHAPE;
   if (c->n_q_heads < c->n_kv_heads || c->n_q_heads % c->n_kv_heads) return VECTOR_ERR_SHAPE;

@@ -108,6 +108,52 @@ def test_decode_on_rotated_cache(d, B, Hq, Hkv, n_r, n_a, interleaved):
     assert np.abs(dg.widen(pl.to_host(out2)) - ref).max() > 10 * ATOL
 
 
+@pytest.mark.parametrize("d,B,Hq,Hkv,n_r,n_a,interleaved", [
+    (64, 2, 4, 2, 100, 77, False),
+    (64, 1, 6, 1, 33, 140, True),
+    (128, 2, 4, 2, 50, 65, False),
+    (128, 1, 2, 2, 0, 40, True),
+])
+def test_decode_on_rotated_fp32_cache(d, B, Hq, Hkv, n_r, n_a, interleaved):
+    """The fp32 (vector-ALU) decode kernel un-rotates approximated rows as well; a step with its
+    append goes through the same kernel."""
+    rng = np.random.default_rng(1000 + d + n_a)
+    inv_freq = dg.rotary_inv_freq(d, THETA)
+    f32 = lambda x: np.asarray(x, np.float32)
+    cap = max(n_r, 1) + 2
+    k_ret, v_ret = f32(rng.standard_normal((B, Hkv, cap, d))), f32(rng.standard_normal((B, Hkv, cap, d)))
+    pos = np.sort(rng.choice(32768, size=(B, Hkv, n_a)), axis=-1).astype(np.int32)
+    k_apx = f32(dg.apply_rotary(rng.standard_normal((B, Hkv, n_a, d)), pos, inv_freq, interleaved))
+    W = f32(rng.standard_normal((Hkv, d, d)) / np.sqrt(d))
+    q, k_new, v_new = f32(rng.standard_normal((B, Hq, d))), f32(rng.standard_normal((B, Hkv, d))), f32(rng.standard_normal((B, Hkv, d)))
+    t = [pl.to_device(x) for x in (k_ret, v_ret, k_apx, W, q, pos, k_new, v_new)]
+    length = torch.full((B,), n_r, dtype=torch.int32, device="cuda:0")
+    cache = vb.Cache(batch=B, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, dtype=vb.VECTOR_F32, cap_retain=cap, n_approx=n_a)
+    cache.len_retain, cache.k_ret, cache.v_ret, cache.k_apx, cache.W = (length.data_ptr(), t[0].data_ptr(), t[1].data_ptr(),
+                                                                      t[2].data_ptr(), t[3].data_ptr())
+    shape = vb.Shape(n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, seq_len=max(cap + n_a, 64), window=1, pool_kernel=1, dtype=0)
+    ws = pl.alloc_workspace(vb.vector_workspace_bytes(shape, cap + n_a, n_a, B))
+    scale = 1.0 / np.sqrt(d)
+    rope, keep = vb.make_rope(inv_freq, t[5], interleaved, 0)
+    ref = vo.decode_attn(q, k_ret, v_ret, np.full(B, n_r), k_apx, W, scale, pos_apx=pos, inv_freq=inv_freq, interleaved=interleaved)
+    out = torch.empty((B, Hq, d), dtype=torch.float32, device="cuda:0")
+    vb.vector_decode_attn_rope(cache, rope, t[4], scale, out, ws)
+    torch.cuda.synchronize()
+    close(out.cpu().numpy(), ref, "decode (rotary fp32 cache)")
+    # the literal variant stays bf16-only and rotation-free
+    with pytest.raises(vb.VectorError) as ei:
+        vb.vector_decode_attn_rope(cache, rope, t[4], scale, out, ws, flags=vb.VECTOR_DECODE_LITERAL)
+    assert ei.value.code == vb.VECTOR_ERR_DTYPE
+    # one step with its append
+    kk, vv = k_ret.copy(), v_ret.copy()
+    kk[:, :, n_r], vv[:, :, n_r] = k_new, v_new
+    ref = vo.decode_attn(q, kk, vv, np.full(B, n_r + 1), k_apx, W, scale, pos_apx=pos, inv_freq=inv_freq, interleaved=interleaved)
+    vb.vector_decode_step_rope(cache, rope, t[4], t[6], t[7], scale, out, ws)
+    torch.cuda.synchronize()
+    close(out.cpu().numpy(), ref, "decode step (rotary fp32 cache)")
+    assert length.cpu().numpy().tolist() == [n_r + 1] * B
+
+
 def test_decode_step_on_rotated_cache():
     """vector_decode_step_rope: the new token's key is appended as cached (rotated), attends with
     the others, and only approximated rows are turned back."""
