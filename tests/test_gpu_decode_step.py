@@ -259,3 +259,94 @@ def test_paged_retained_segments(dtype, d, block_rows):
     with pytest.raises(vb.VectorError) as ei:
         vb.vector_decode_attn(cache, pl.to_device(q), scale, out, ws, flags=vb.VECTOR_DECODE_OUT_F32)
     assert ei.value.code == vb.VECTOR_ERR_ARG
+
+
+def _random_step_cases():
+    rng = np.random.default_rng(4242)
+    out = []
+    for i in range(18):
+        dtype = "bf16" if rng.random() < 0.65 else "f32"
+        d = int(rng.choice([64, 128]))
+        hkv = int(rng.integers(1, 4))
+        g = int(rng.integers(1, 9))
+        B = int(rng.integers(1, 5))
+        layout = ["uniform", "per_sequence", "paged"][i % 3]
+        out.append((i, dtype, d, hkv, g, B, layout))
+    return out
+
+
+@pytest.mark.parametrize("case", _random_step_cases(), ids=lambda c: f"{c[0]}-{c[1]}-d{c[2]}-h{c[3]}g{c[4]}-B{c[5]}-{c[6]}")
+def test_random_decode_steps(case):
+    """Seeded sweep: three steps with appends over caches of random sizes in each of the three
+    layouts of the retained segment (one capacity, per-sequence blocks, paged), every group size."""
+    i, dtype, d, H, g, B, layout = case
+    Hq = H * g
+    is_bf = dtype == "bf16"
+    store = _store(dtype)
+    rng = np.random.default_rng(9000 + i)
+    block_rows = int(rng.choice([16, 32, 64]))
+    if layout == "per_sequence":
+        caps = [int(rng.integers(4, 400)) for _ in range(B)]
+        n_as = [int(rng.integers(0, 300)) for _ in range(B)]
+    elif layout == "paged":
+        bps = int(rng.integers(1, 7))
+        caps = [bps * block_rows] * B
+        n_as = [int(rng.integers(0, 300))] * B
+    else:
+        caps = [int(rng.integers(4, 400))] * B
+        n_as = [int(rng.integers(0, 300))] * B
+    lens = np.array([int(rng.integers(0, c - 2)) if c > 3 else 0 for c in caps], dtype=np.int32)
+    # the oracle's picture: one (k, v, k_apx) set per sequence, contiguous
+    ks = [store(rng.standard_normal((H, c, d))) for c in caps]
+    vs = [store(rng.standard_normal((H, c, d))) for c in caps]
+    kas = [store(rng.standard_normal((H, max(a, 1), d)))[:, :a] for a in n_as]
+    W = store(rng.standard_normal((H, d, d)) / np.sqrt(d))
+    scale = 1.0 / np.sqrt(d)
+    cache = vb.Cache(batch=B, n_q_heads=Hq, n_kv_heads=H, head_dim=d, dtype=vb.VECTOR_BF16 if is_bf else vb.VECTOR_F32,
+                     cap_retain=max(caps), n_approx=max(n_as))
+    keep = {}
+    if layout == "paged":
+        n_blocks = B * H * bps + 3
+        table = rng.permutation(n_blocks)[: B * H * bps].astype(np.int32).reshape(B, H, bps)
+        k_pool, v_pool = store(np.zeros((n_blocks, block_rows, d))), store(np.zeros((n_blocks, block_rows, d)))
+        for b in range(B):
+            for h in range(H):
+                for j in range(bps):
+                    k_pool[table[b, h, j]] = ks[b][h, j * block_rows: (j + 1) * block_rows]
+                    v_pool[table[b, h, j]] = vs[b][h, j * block_rows: (j + 1) * block_rows]
+        keep.update(k=pl.to_device(k_pool), v=pl.to_device(v_pool), table=pl.to_device(table),
+                    ka=pl.to_device(np.ascontiguousarray(np.stack(kas))) if n_as[0] else None)
+        cache.ret_block_table, cache.ret_block_rows, cache.ret_blocks_per_seq = keep["table"].data_ptr(), block_rows, bps
+    else:
+        keep.update(k=pl.to_device(np.concatenate([x.reshape(-1, d) for x in ks])), v=pl.to_device(np.concatenate([x.reshape(-1, d) for x in vs])),
+                    ka=pl.to_device(np.concatenate([x.reshape(-1, d) for x in kas])) if sum(n_as) else None)
+        if layout == "per_sequence":
+            i32 = lambda x: torch.tensor(list(x), dtype=torch.int32, device="cuda:0")
+            i64 = lambda x: torch.tensor(list(x), dtype=torch.int64, device="cuda:0")
+            keep.update(cap=i32(caps), na=i32(n_as), r0=i64(np.concatenate([[0], np.cumsum([H * c for c in caps])])[:-1]),
+                        a0=i64(np.concatenate([[0], np.cumsum([H * a for a in n_as])])[:-1]))
+            cache.cap_retain_seq, cache.n_approx_seq = keep["cap"].data_ptr(), keep["na"].data_ptr()
+            cache.ret_row_start, cache.apx_row_start = keep["r0"].data_ptr(), keep["a0"].data_ptr()
+    keep["len"], keep["W"] = pl.to_device(lens), pl.to_device(W)
+    cache.len_retain, cache.k_ret, cache.v_ret = keep["len"].data_ptr(), keep["k"].data_ptr(), keep["v"].data_ptr()
+    cache.k_apx = keep["ka"].data_ptr() if keep["ka"] is not None else None
+    cache.W = keep["W"].data_ptr()
+    shape = vb.Shape(n_q_heads=Hq, n_kv_heads=H, head_dim=d, seq_len=max(max(caps), 64), window=1, pool_kernel=1, dtype=cache.dtype)
+    ws = pl.alloc_workspace(vb.vector_workspace_bytes(shape, max(caps), 0, B) + (1 << 20))
+    host_len = lens.copy()
+    out = torch.empty((B, Hq, d), dtype=torch.float32, device="cuda:0")
+    for step in range(3):
+        q = store(rng.standard_normal((B, Hq, d)))
+        k_new, v_new = store(rng.standard_normal((B, H, d))), store(rng.standard_normal((B, H, d)))
+        ref = np.zeros((B, Hq, d))
+        for b in range(B):
+            ref[b] = _oracle_step(q[b: b + 1], ks[b][None], vs[b][None], np.array([host_len[b]]), k_new[b: b + 1], v_new[b: b + 1],
+                                  kas[b][None], W, scale)[0]
+        vb.vector_decode_step(cache, pl.to_device(q), pl.to_device(k_new), pl.to_device(v_new), scale, out, ws, flags=vb.VECTOR_DECODE_OUT_F32)
+        torch.cuda.synchronize()
+        close(out.cpu().numpy(), ref, f"case {i} step {step}")
+        for b in range(B):
+            if host_len[b] < caps[b]:
+                ks[b][:, host_len[b]], vs[b][:, host_len[b]] = k_new[b], v_new[b]
+                host_len[b] += 1
+        assert np.array_equal(keep["len"].cpu().numpy(), host_len)
