@@ -99,8 +99,11 @@ VECTOR_API const char* vector_strerror(int code);
  * tokens t >= n-w get +inf.
  * q_win: device [Hq, w, d] packed.  k: device, strides from shape.
  * score: device fp32 [Hkv, n] packed (output).
- * The G*w query rows of a KV head are held in LDS: VECTOR_ERR_SHAPE beyond 288 rows (bf16) or
- * 160 rows (fp32) at d = 128, 384 or 288 rows at d = 64. */
+ * The query rows of a KV head are staged in LDS, up to 288 rows (bf16) or 160 rows (fp32) at
+ * d = 128, 384 or 288 rows at d = 64.  With more than that (G*w = 512 for 8 query heads per KV
+ * head and a 64-token window) the query heads go through the two passes in groups of as many
+ * heads as fit, each group adding its share to the column mass: one more read of K per group.
+ * VECTOR_ERR_SHAPE only when a single head's w rows exceed the limit. */
 VECTOR_API int vector_score(const vector_shape* shape, const void* q_win, const void* k,
                  float* score, void* ws, size_t ws_bytes, void* stream);
 

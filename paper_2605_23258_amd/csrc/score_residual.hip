@@ -45,6 +45,10 @@ struct PassParams {
   int hps;              // stacked sequences: KV heads per sequence (0: one sequence); head hv of the launch is
   int64_t k_sb, v_sb;   // KV head hv % hps of sequence hv / hps, sequences k_sb / v_sb elements apart
   int n, w, R, R_pad, n_prefix;
+  // Query heads of a KV head taken a group at a time (when all G * w rows do not fit at once): this
+  // launch sees R rows starting at row q_row0 of the head's q_head_rows = G * w rows, and its
+  // column mass is added to what the earlier groups left.
+  int q_head_rows, q_row0, accumulate;
   int tokens_per_chunk;  // pass 2: tokens per workgroup
   int tpc1, n_chunks;    // pass 1: tokens per workgroup, and the number of such chunks (= partials per row)
   int threads_per_row;  // pass-2 prologue: lanes that share the merge of one row's partials
@@ -161,7 +165,7 @@ __global__ __launch_bounds__(NT) void score_stats_kernel(PassParams p) {
   };
   int t0 = c_begin + wave * TW;
   if (t0 < c_end) load_keys(t0);          // first tile's keys fly while Q is staged
-  fill_rows_lds<T, D, NT>(q_lds, reinterpret_cast<const T*>(p.q) + (size_t)h * p.R * D, p.R, p.R_pad, chunk * 8);
+  fill_rows_lds<T, D, NT>(q_lds, reinterpret_cast<const T*>(p.q) + ((size_t)h * p.q_head_rows + p.q_row0) * D, p.R, p.R_pad, chunk * 8);
   for (int i = threadIdx.x; i < NW * nrb * 64; i += NT) st_lds[i] = make_float2(-INFINITY, 0.f);
   __syncthreads();
 
@@ -336,7 +340,7 @@ __global__ __launch_bounds__(kV2Threads) void score_stats_tiles_kernel(PassParam
   chunk_t qf[NC];
   {
     const int qrow = rb * 32 + l31;
-    const T* qrow_p = reinterpret_cast<const T*>(p.q) + ((size_t)h * p.R + min(qrow, p.R - 1)) * D;
+    const T* qrow_p = reinterpret_cast<const T*>(p.q) + ((size_t)h * p.q_head_rows + p.q_row0 + min(qrow, p.R - 1)) * D;
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
       qf[c] = load_chunk(qrow_p + chunk_elem_offset<T>(c, half));
@@ -644,7 +648,7 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
 #pragma unroll
       for (int u = 0; u < kPre; ++u) pre[u] = part[min(sub + u * tpr, p.n_chunks - 1)];   // blanked when folded
     }
-    fill_rows_lds<T, D, NT>(q_lds, reinterpret_cast<const T*>(p.q) + (size_t)h * p.R * D, p.R, p.R_pad, chunk * 8);
+    fill_rows_lds<T, D, NT>(q_lds, reinterpret_cast<const T*>(p.q) + ((size_t)h * p.q_head_rows + p.q_row0) * D, p.R, p.R_pad, chunk * 8);
   }
   if (DO_RES) {
     // W^T into LDS as the M-side operand.  MFMA row m of block jb stands for value dim
@@ -833,7 +837,11 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
       col0 += __shfl_xor(col0, 32, kWave);
       col1 += __shfl_xor(col1, 32, kWave);
       const int t = t0 + lane;             // lanes 0..31 -> subtile 0, 32..63 -> subtile 1
-      if (t < mass_end) p.mass[(size_t)h * p.n + t] = (half ? col1 : col0) * p.inv_R;
+      if (t < mass_end) {
+        float* dst = p.mass + (size_t)h * p.n + t;
+        const float m = (half ? col1 : col0) * p.inv_R;
+        *dst = p.accumulate ? *dst + m : m;
+      }
     } else if (DO_MASS && !DO_RES) {
       load_next(tn);
     }
@@ -969,6 +977,7 @@ int make_plan(const vector_shape& s, bool do_mass, bool do_res, Plan& plan, int 
   p.threads_per_row = tpr;
   p.c2 = kLog2e / sqrtf((float)D);
   p.inv_R = 1.0f / (float)p.R;
+  p.q_head_rows = p.R; p.q_row0 = 0; p.accumulate = 0;
   p.k_st = s.k_stride_tok ? s.k_stride_tok : D;
   p.k_sh = s.k_stride_head ? s.k_stride_head : (int64_t)s.seq_len * p.k_st;
   p.v_st = s.v_stride_tok ? s.v_stride_tok : D;
@@ -995,23 +1004,33 @@ size_t score_workspace_bytes(const vector_shape& s) {
   return b;
 }
 
+// One pair of passes over the keys for the query rows [q_row0, q_row0 + rows of `g`) of every KV
+// head (g: the shape with the group's query-head count).  accumulate: the column mass is added to
+// what earlier groups left.  The residual rides along when eps is given.
 template <typename T, int D>
-static int run_score_residual(const SeqStack* stack, const vector_shape& s, const void* q, const void* k, const void* v, const void* W,
-                              float* score, float* eps, void* ws, hipStream_t stream, const RopeParams* rope,
-                              void* route_ws) {
-  const bool do_mass = score != nullptr, do_res = eps != nullptr;
+static int run_passes(const SeqStack* stack, const vector_shape& s, const vector_shape& g, int q_row0, bool accumulate, const void* q,
+                      const void* k, const void* v, const void* W, bool do_mass, float* eps, void* ws, hipStream_t stream,
+                      const RopeParams* rope, float** mass_out, int* n_prefix_out) {
+  const bool do_res = eps != nullptr;
   Plan plan;
-  int rc = make_plan<T, D>(s, do_mass, do_res, plan, stack ? stack->heads_per_seq : 0);
+  int rc = make_plan<T, D>(g, do_mass, do_res, plan, stack ? stack->heads_per_seq : 0);
   if (rc != VECTOR_OK) return rc;
   PassParams& p = plan.pp;
   p.q = q; p.k = k; p.v = v; p.W = W; p.eps = eps; p.repeat = 1;
+  const int rows_all = (s.n_q_heads / s.n_kv_heads) * s.window;
+  p.q_head_rows = rows_all; p.q_row0 = q_row0; p.accumulate = accumulate ? 1 : 0;
+  p.inv_R = 1.0f / (float)rows_all;
   if (stack) {                      // the strides inside a sequence are the shape's, as for one sequence
     p.hps = stack->heads_per_seq; p.k_sb = stack->k_stride_seq; p.v_sb = stack->v_stride_seq;
   }
+  // workspace: partials (sized for all rows of a head, so any group fits), then the mass
+  const int rows_all_pad = (rows_all + 31) / 32 * 32;
   unsigned char* w8 = reinterpret_cast<unsigned char*>(ws);
   p.part = reinterpret_cast<float2*>(w8);
-  w8 += align_up((size_t)s.n_kv_heads * ((s.seq_len + 255) / 256) * p.R_pad * sizeof(float2), 256);
+  w8 += align_up((size_t)s.n_kv_heads * ((s.seq_len + 255) / 256) * rows_all_pad * sizeof(float2), 256);
   p.mass = reinterpret_cast<float*>(w8);
+  if (mass_out) *mass_out = p.mass;
+  if (n_prefix_out) *n_prefix_out = p.n_prefix;
   RopeParams rp = {};
   const bool use_rope = rope != nullptr && do_res;         // the scores use the keys as cached
   if (use_rope) rp = *rope;
@@ -1040,8 +1059,44 @@ static int run_score_residual(const SeqStack* stack, const vector_shape& s, cons
   VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k2), lds2));
   VEC_LAUNCH(K_MASS_RESIDUAL, k2, grid, dim3(kThreads), lds2, stream, p, rp);
   VEC_HIP(hipGetLastError());
-  if (do_mass) return launch_pool_scores(p.mass, score, s.n_kv_heads, s.seq_len, p.n_prefix, s.pool_kernel, s.pool_mode, route_ws, stream);
   return VECTOR_OK;
+}
+
+// Query heads per pair of passes: all G of a KV head when their G * w rows fit the kernels' LDS
+// layouts, else the largest count that does (0: not even one head's window fits).
+template <typename T, int D>
+static int heads_per_group(const vector_shape& s, bool do_res) {
+  const int G = s.n_q_heads / s.n_kv_heads;
+  for (int gh = G; gh >= 1; --gh) {
+    vector_shape g = s;
+    g.n_q_heads = s.n_kv_heads * gh;
+    Plan plan;
+    if (make_plan<T, D>(g, true, do_res, plan) == VECTOR_OK) return gh;
+  }
+  return 0;
+}
+
+template <typename T, int D>
+static int run_score_residual(const SeqStack* stack, const vector_shape& s, const void* q, const void* k, const void* v, const void* W,
+                              float* score, float* eps, void* ws, hipStream_t stream, const RopeParams* rope,
+                              void* route_ws) {
+  const bool do_mass = score != nullptr;
+  if (!do_mass) return run_passes<T, D>(stack, s, s, 0, false, q, k, v, W, false, eps, ws, stream, rope, nullptr, nullptr);
+  // The query heads of a KV head go through the two passes a group at a time; usually one group.
+  // The first group's second pass carries the residual.
+  const int G = s.n_q_heads / s.n_kv_heads;
+  const int gh = heads_per_group<T, D>(s, eps != nullptr);
+  if (gh == 0) return VECTOR_ERR_SHAPE;
+  float* mass = nullptr;
+  int n_prefix = 0;
+  for (int g0 = 0; g0 < G; g0 += gh) {
+    vector_shape g = s;
+    g.n_q_heads = s.n_kv_heads * (g0 + gh <= G ? gh : G - g0);
+    const int rc = run_passes<T, D>(stack, s, g, g0 * s.window, g0 > 0, q, k, v, W, true, g0 == 0 ? eps : nullptr, ws, stream, rope,
+                                    &mass, &n_prefix);
+    if (rc != VECTOR_OK) return rc;
+  }
+  return launch_pool_scores(mass, score, s.n_kv_heads, s.seq_len, n_prefix, s.pool_kernel, s.pool_mode, route_ws, stream);
 }
 
 template <typename T, int D>

@@ -185,24 +185,29 @@ def test_one_call_pass_equals_the_three_calls(base, over):
 
 
 def test_query_row_limit():
-    """G*w rows per KV head live in LDS: the largest supported count works, the next one is refused."""
-    ok = dg.scaled(dg.CONFIGS["cfg2"], seq_len=600, n_kv_heads=1, n_q_heads=4, window=72)       # 288 rows
-    li = wl.make_layer(ok, 0)
-    shape = pl.shape_of(ok)
-    n_r, n_a, n_p = ok.counts()
-    dev = {x: pl.to_device(getattr(li, x)) for x in ("q_win", "k", "v", "w_cal")}
-    ws = pl.alloc_workspace(vb.vector_workspace_bytes(shape, n_p, n_a, 1))
-    score = torch.empty((1, 600), device="cuda:0")
-    eps = torch.empty((1, 600), device="cuda:0")
-    vb.vector_score_residual(shape, dev["q_win"], dev["k"], dev["v"], dev["w_cal"], score, eps, ws)
-    torch.cuda.synchronize()
-    wide = {x: dg.widen(getattr(li, x)) for x in ("q_win", "k", "v", "w_cal")}
-    ref = vo.score(wide["q_win"], wide["k"], 72, ok.pool_kernel)
-    close(score.cpu().numpy()[:, :528].astype(np.float64) * 600, ref[:, :528].astype(np.float64) * 600, "n*score (288 rows)")
-    too_many = dg.scaled(ok, window=80)                                                          # 320 rows
-    q_big = torch.zeros((4, 80, 128), dtype=torch.bfloat16, device="cuda:0")
+    """The query rows of a KV head are staged in LDS.  288 rows go in one group; 320 rows go as
+    groups of query heads; a single head's window that does not fit is refused."""
+    def run(cfg):
+        li = wl.make_layer(cfg, 0)
+        shape = pl.shape_of(cfg)
+        n_r, n_a, n_p = cfg.counts()
+        dev = {x: pl.to_device(getattr(li, x)) for x in ("q_win", "k", "v", "w_cal")}
+        ws = pl.alloc_workspace(vb.vector_workspace_bytes(shape, n_p, n_a, 1))
+        score = torch.empty((1, cfg.seq_len), device="cuda:0")
+        eps = torch.empty((1, cfg.seq_len), device="cuda:0")
+        vb.vector_score_residual(shape, dev["q_win"], dev["k"], dev["v"], dev["w_cal"], score, eps, ws)
+        torch.cuda.synchronize()
+        return li, score.cpu().numpy(), eps.cpu().numpy()
+    for window in (72, 80):                                                                      # 288 and 320 rows
+        cfg = dg.scaled(dg.CONFIGS["cfg2"], seq_len=600, n_kv_heads=1, n_q_heads=4, window=window)
+        li, score, eps = run(cfg)
+        ref = vo.score(dg.widen(li.q_win), dg.widen(li.k), window, cfg.pool_kernel)
+        m = 600 - window
+        close(score[:, :m].astype(np.float64) * 600, ref[:, :m].astype(np.float64) * 600, f"n*score ({4 * window} rows)")
+        close(eps, vo.residual(dg.widen(li.k), dg.widen(li.v), dg.widen(li.w_cal)), f"eps ({4 * window} rows)")
+    too_wide = dg.scaled(dg.CONFIGS["cfg2"], seq_len=600, n_kv_heads=1, n_q_heads=1, window=300)  # one head, 300 rows
     with pytest.raises(vb.VectorError) as ei:
-        vb.vector_score_residual(pl.shape_of(too_many), q_big, dev["k"], dev["v"], dev["w_cal"], score, eps, ws)
+        run(too_wide)
     assert ei.value.code == vb.VECTOR_ERR_SHAPE
 
 

@@ -48,6 +48,12 @@ CASES = {
     # maximum pooling: the vector path (kernel <= 9), the general loop (kernel 13), an unaligned length
     "bf16_maxpool7": ("cfg2", dict(seq_len=2048, n_kv_heads=2, n_q_heads=8, pool_mode="max")),
     "bf16_maxpool5_ragged": ("cfg2", dict(seq_len=1777, n_kv_heads=2, n_q_heads=8, window=24, pool_kernel=5, pool_mode="max")),
+    # more query rows per KV head than the kernels hold at once: the query heads go in groups
+    # (two groups of 4 heads; 4 + 2 heads; 3 + 1 heads of fp32 rows; 6 + 1 heads at d = 64)
+    "bf16_G8_w64_groups": ("cfg3", dict(seq_len=1536, n_kv_heads=2, n_q_heads=16, layers=1)),
+    "bf16_G6_w64_groups": ("cfg3", dict(seq_len=1300, n_kv_heads=1, n_q_heads=6, layers=1)),
+    "f32_d128_G4_w48_groups": ("cfg1", dict(seq_len=700, head_dim=128, n_kv_heads=1, n_q_heads=4, window=48, pool_kernel=3)),
+    "bf16_d64_G7_w60_groups": ("cfg2", dict(seq_len=900, head_dim=64, n_kv_heads=2, n_q_heads=14, window=60, pool_mode="max")),
     "f32_maxpool13": ("cfg1", dict(seq_len=1000, window=20, n_q_heads=6, n_kv_heads=2, pool_kernel=13, pool_mode="max")),
 }
 
@@ -247,7 +253,7 @@ def test_decode_attn(dtype, d, B, Hq, Hkv, n_r, n_a, cap):
         assert ei.value.code == vb.VECTOR_ERR_DTYPE
 
 
-@pytest.mark.parametrize("name", ["f32_d64_n1024", "bf16_d128_n2048", "bf16_d128_ragged"])
+@pytest.mark.parametrize("name", ["f32_d64_n1024", "bf16_d128_n2048", "bf16_d128_ragged", "bf16_G8_w64_groups"])
 def test_end_to_end_compress(name):
     cfg, li, dev, wide = _inputs(name)
     shape = pl.shape_of(cfg)
