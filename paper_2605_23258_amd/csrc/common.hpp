@@ -137,6 +137,40 @@ __device__ __forceinline__ int wave_incl_scan_i(int x, int lane) {
   return x;
 }
 
+// Smallest / largest of a value over the wave on the DPP network (no LDS traffic); every lane
+// gets the result.  Lanes that a step does not feed take the identity (`idle`).
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ float dpp_take_f(float idle, float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(idle), __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
+}
+__device__ __forceinline__ float wave_min_dpp(float v) {
+  v = fminf(v, dpp_take_f<0x111, 0xf>(INFINITY, v));   // row_shr:1 .. 8: lane 15 of each row of 16 holds the row's
+  v = fminf(v, dpp_take_f<0x112, 0xf>(INFINITY, v));
+  v = fminf(v, dpp_take_f<0x114, 0xf>(INFINITY, v));
+  v = fminf(v, dpp_take_f<0x118, 0xf>(INFINITY, v));
+  v = fminf(v, dpp_take_f<0x142, 0xa>(INFINITY, v));   // row_bcast:15 into rows 1 and 3
+  v = fminf(v, dpp_take_f<0x143, 0xc>(INFINITY, v));   // row_bcast:31 into rows 2 and 3: lane 63 holds the wave's
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+__device__ __forceinline__ float wave_max_dpp(float v) {
+  v = fmaxf(v, dpp_take_f<0x111, 0xf>(-INFINITY, v));
+  v = fmaxf(v, dpp_take_f<0x112, 0xf>(-INFINITY, v));
+  v = fmaxf(v, dpp_take_f<0x114, 0xf>(-INFINITY, v));
+  v = fmaxf(v, dpp_take_f<0x118, 0xf>(-INFINITY, v));
+  v = fmaxf(v, dpp_take_f<0x142, 0xa>(-INFINITY, v));
+  v = fmaxf(v, dpp_take_f<0x143, 0xc>(-INFINITY, v));
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
+__device__ __forceinline__ float wave_sum_dpp(float v) {    // one fixed order of additions: the same bits every time
+  v += dpp_take_f<0x111, 0xf>(0.f, v);
+  v += dpp_take_f<0x112, 0xf>(0.f, v);
+  v += dpp_take_f<0x114, 0xf>(0.f, v);
+  v += dpp_take_f<0x118, 0xf>(0.f, v);
+  v += dpp_take_f<0x142, 0xa>(0.f, v);
+  v += dpp_take_f<0x143, 0xc>(0.f, v);
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // ---------------------------------------------------------------------------

@@ -70,11 +70,17 @@ int launch_key_diversity(const vector_shape& s, const void* k, float* score, voi
 
 constexpr int kRouteMaxSeqLen = 1 << 20;      // per-chunk digit tables carry 16-bit counts: at most 32 chunks of 32768 tokens
 size_t route_workspace_bytes(int n_kv_heads, int seq_len, int n_pool);
+// Where, inside a routing workspace, the scorer's second pass leaves statistics of the attention
+// mass: per head n_range float4 (count, sum, sum of squares of log2 mass), one per workgroup of that
+// launch (n_range <= route_mass_range_slots(seq_len)).
+void* route_mass_range(void* route_ws, int n_kv_heads);
+int route_mass_range_slots(int seq_len);
 // average pooling of the attention mass into the score; with a routing workspace (route_ws, sized by
 // route_workspace_bytes) also the routing's buckets of score keys (then launch_route is told so and
 // skips its own bucket launch)
+// n_range: records per head the scorer left at route_mass_range (0: none, the buckets go by the keys' top bits)
 int launch_pool_scores(const float* mass, float* score, int n_kv_heads, int seq_len, int n_prefix, int pool_kernel, int pool_mode,
-                       void* route_ws, hipStream_t stream);
+                       void* route_ws, int n_range, hipStream_t stream);
 int launch_route(int n_kv_heads, int seq_len, const float* score, const float* eps, int n_pool, int n_approx,
                  uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx, void* ws, bool have_buckets, hipStream_t stream);
 

@@ -49,6 +49,7 @@ constexpr int kTableStride = kBins + 8;   // 16-bit entries of a D table: D[0 ..
 constexpr int EPT = 4;                    // consecutive elements per thread and tile (one 16-byte load)
 constexpr int BT = 512;                   // threads of the bucket kernel
 constexpr int kBucketTile = BT * EPT;
+constexpr int kStageTokens = 4096;        // a chunk's bucket list is put together in LDS up to this length
 constexpr int ST = 256;                   // threads of a selecting workgroup: one wave per SIMD
 constexpr int SW = ST / kWave;
 constexpr int kTile = ST * EPT;           // elements per tile of a selecting workgroup
@@ -62,6 +63,53 @@ constexpr int kMaxChunks = 32;
 __device__ __forceinline__ uint32_t float_key(float x) {
   uint32_t b = __float_as_uint(x + 0.0f);
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+// Leading digit of a key: which of the 2048 buckets of the first radix level it falls in.  Plain:
+// the key's top 11 bits, a quarter of an octave of scores per bucket.  When the scorer has told
+// where the bulk of a head's scores lies, 2046 buckets of 2^shift keys each are laid over that
+// range instead, so that scores which agree in their leading bits (a flat attention row: every
+// score within a few per cent of 1/n) still spread over the buckets; bucket 0 takes every key below
+// the range and bucket 2047 every key above it (attention sinks, the +inf of the window columns).
+// Keys of one bucket between 1 and 2046 agree in all bits from `shift` up; the two end buckets
+// (and they alone) may hold keys that differ anywhere.  Wherever a score falls the select stays
+// exact: the range only decides how evenly the buckets fill.
+struct DigitMap {
+  uint32_t lowq;
+  int shift;
+  __device__ __forceinline__ bool plain() const { return shift == 21 && lowq == 0u; }
+  __device__ __forceinline__ uint32_t digit(uint32_t key) const {
+    // a saturating difference: written with max (a compare-and-select around `q - lowq` is folded away by
+    // this compiler at -O3, which then lets the difference wrap)
+    const uint32_t q = key >> shift;
+    return min(max(q, lowq) - lowq, 2047u);
+  }
+  __device__ __forceinline__ bool shares_high_bits(int d) const { return plain() || (d > 0 && d < 2047); }
+};
+// cnt, sum_l, sum_ll: over the head's prefix columns of positive attention mass m, their number and
+// the sums of l = log2(m) - log_ref and of l * l.  The buckets cover the mean of log2(m) give or
+// take four standard deviations (and a 64th of an octave, so that equal masses still get a
+// range): at most a sixteenth of the columns lie outside, whatever their distribution, and a few
+// columns far from the rest (attention sinks, the zero-padded edges of the pooling) move the range
+// very little.
+__device__ __forceinline__ DigitMap digit_map_for_stats(float cnt, float sum_l, float sum_ll, float log_ref) {
+  DigitMap plain = {0u, 21};
+  if (!(cnt >= 1.f)) return plain;
+  // hardware reciprocal, square root and exponential: a rough range is all that is needed, and
+  // every wave of the head gets the same bits from the same inputs
+  const float inv = __builtin_amdgcn_rcpf(cnt);
+  const float mu = sum_l * inv;
+  const float sd = __builtin_amdgcn_sqrtf(fmaxf(sum_ll * inv - mu * mu, 0.f));
+  const float mid = log_ref + mu, half = 4.f * sd + 0.015625f;
+  if (!(mid - half > -120.f) || !(mid + half < 120.f)) return plain;        // also NaN
+  const uint32_t klo = float_key(__builtin_amdgcn_exp2f(mid - half)), khi = float_key(__builtin_amdgcn_exp2f(mid + half));
+  // (khi >> s) - (klo >> s) <= ((khi - klo) >> s) + 1: start where the difference has 11 bits left
+  const uint32_t diff = khi - klo;
+  int s = diff ? max(0, 21 - (int)__clz(diff)) : 0;
+  if ((khi >> s) - (klo >> s) > 2045u) ++s;
+  if (s >= 21) return plain;
+  DigitMap m = {(klo >> s) - 1u, s};
+  return m;
 }
 
 // hist[digit] += cnt (cnt in 0..7) for every lane.  Keys of neighbouring tokens often share their
@@ -87,10 +135,11 @@ __device__ __forceinline__ void hist_add_weighted(int* hist, uint32_t digit, int
 
 // Leading digits of a thread's EPT consecutive keys into an LDS histogram: the keys that agree
 // with the thread's first valid one go in together, the others one by one.
-__device__ __forceinline__ void hist_add_thread_keys(int* hist, const uint32_t (&key)[EPT], const bool (&ok)[EPT], int lane) {
+__device__ __forceinline__ void hist_add_thread_keys(int* hist, const uint32_t (&key)[EPT], const bool (&ok)[EPT], int lane,
+                                                     const DigitMap& map) {
   uint32_t dg[EPT];
 #pragma unroll
-  for (int j = 0; j < EPT; ++j) dg[j] = key[j] >> 21;
+  for (int j = 0; j < EPT; ++j) dg[j] = map.digit(key[j]);
   int first = -1;
 #pragma unroll
   for (int j = EPT - 1; j >= 0; --j)
@@ -178,22 +227,59 @@ struct BucketParams {
   int32_t* bpos;          // [H, n]: the token each key belongs to
   int n, n_prefix, kernel, chunk_tokens, n_chunks;
   int take_max;           // POOL: the window's largest mass instead of its sum over the kernel size
+  uint32_t* map;          // [H, 2] with the buckets: the digit map (lowq, shift) this launch chooses, for the selecting launch
+  const float4* range;    // [H, n_range] (count, sum l, sum l * l) of the mass left by the scorer's workgroups, when n_range > 0
+  int n_range;
+  float log_ref;          // what the scorer subtracted from log2(mass)
 };
 
 template <bool POOL>
 __global__ __launch_bounds__(BT) void route_bucket_kernel(BucketParams p) {
   __shared__ int hist[kBins];
   __shared__ int row[BT / kWave];
+  __shared__ __align__(16) uint32_t stage_key[kStageTokens];
+  __shared__ __align__(16) int32_t stage_pos[kStageTokens];
   const int h = blockIdx.y, chunk = blockIdx.x;
   const int lane = threadIdx.x & 63;
   const bool do_buckets = p.table != nullptr;
-  if (do_buckets) {
-    for (int i = threadIdx.x; i < kBins; i += BT) hist[i] = 0;
-    __syncthreads();
+  DigitMap map = {0u, 21};
+  // every wave adds up the head's statistics itself (in one fixed order), so all workgroups of
+  // the head cut the same buckets
+  constexpr int kRangeRegs = 2;
+  float4 range_x[kRangeRegs];
+  if (do_buckets && p.n_range > 0) {
+    const float4* r = p.range + (size_t)h * p.n_range;
+#pragma unroll
+    for (int u = 0; u < kRangeRegs; ++u) {
+      const int i = u * kWave + lane;
+      range_x[u] = i < p.n_range ? r[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
   }
   const float* src = p.src + (size_t)h * p.n;
   const float* scores = POOL ? p.score + (size_t)h * p.n : src;
   const int begin = chunk * p.chunk_tokens, end = min(p.n, begin + p.chunk_tokens);
+  // the thread's first four inputs are requested now and only touched (not used) after the map is
+  // there: they travel while the statistics are turned into the map, and the first tile's loads
+  // below find them in the cache
+  float warm = 0.f;
+  if (do_buckets && p.n_range > 0) warm = src[min(begin + (int)threadIdx.x * EPT, p.n - 1)];
+  if (do_buckets) {
+    for (int i = threadIdx.x; i < kBins; i += BT) hist[i] = 0;
+    if (p.n_range > 0) {
+      float cnt = 0.f, sl = 0.f, sll = 0.f;
+#pragma unroll
+      for (int u = 0; u < kRangeRegs; ++u) { cnt += range_x[u].x; sl += range_x[u].y; sll += range_x[u].z; }
+      const float4* r = p.range + (size_t)h * p.n_range;
+      for (int i = kRangeRegs * kWave + lane; i < p.n_range; i += kWave) {       // long sequences only
+        const float4 x = r[i];
+        cnt += x.x; sl += x.y; sll += x.z;
+      }
+      map = digit_map_for_stats(wave_sum_dpp(cnt), wave_sum_dpp(sl), wave_sum_dpp(sll), p.log_ref);
+      asm volatile("" ::"v"(warm));
+    }
+    if (chunk == 0 && threadIdx.x == 0) { p.map[2 * h] = map.lowq; p.map[2 * h + 1] = (uint32_t)map.shift; }
+    __syncthreads();
+  }
   const bool vec4 = (p.n & 3) == 0 && ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(scores)) & 15u) == 0;
   auto load_scores = [&](int t0, float (&s)[EPT]) {
     if (vec4 && t0 + EPT <= end) {
@@ -261,7 +347,7 @@ __global__ __launch_bounds__(BT) void route_bucket_kernel(BucketParams p) {
       uint32_t key[EPT];
 #pragma unroll
       for (int j = 0; j < EPT; ++j) key[j] = float_key(s[j]);
-      hist_add_thread_keys(hist, key, ok, lane);
+      hist_add_thread_keys(hist, key, ok, lane, map);
       if (tile == begin) {
 #pragma unroll
         for (int j = 0; j < EPT; ++j) key0[j] = key[j];
@@ -272,8 +358,12 @@ __global__ __launch_bounds__(BT) void route_bucket_kernel(BucketParams p) {
   __syncthreads();
   counts_to_table<BT>(hist, p.table + ((size_t)h * p.n_chunks + chunk) * kTableStride, row);
   // scatter: hist[b] is now the next free slot of bin b in the chunk's list
+  // The slots of neighbouring tokens are far apart in the list (the finer the buckets, the farther),
+  // so the list of a chunk that fits is put together in LDS and written out in order; longer
+  // chunks scatter their entries straight to memory.
   uint32_t* bkey = p.bkey + (size_t)h * p.n + begin;
   int32_t* bpos = p.bpos + (size_t)h * p.n + begin;
+  const bool staged = p.chunk_tokens <= kStageTokens;
   for (int tile = begin; tile < end; tile += kBucketTile) {
     const int t0 = tile + (int)threadIdx.x * EPT;
     uint32_t key[EPT];
@@ -289,9 +379,28 @@ __global__ __launch_bounds__(BT) void route_bucket_kernel(BucketParams p) {
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
       if (t0 + j < end) {
-        const int slot = atomicAdd(&hist[key[j] >> 21], 1);
-        if (slot < end - begin) { bkey[slot] = key[j]; bpos[slot] = t0 + j; }    // always true: counted above
+        const int slot = atomicAdd(&hist[map.digit(key[j])], 1);
+        if (slot < end - begin) {                                                // always true: counted above
+          if (staged) { stage_key[slot] = key[j]; stage_pos[slot] = t0 + j; }
+          else { bkey[slot] = key[j]; bpos[slot] = t0 + j; }
+        }
       }
+    }
+  }
+  if (staged) {                                  // the list leaves LDS in order: whole cache lines per wave
+    __syncthreads();
+    const int cnt = end - begin;
+    if ((((size_t)h * p.n) & 3) == 0) {
+      for (int i = (int)threadIdx.x * 4; i < cnt; i += BT * 4) {
+        if (i + 4 <= cnt) {
+          *reinterpret_cast<uint4*>(bkey + i) = *reinterpret_cast<const uint4*>(stage_key + i);
+          *reinterpret_cast<int4*>(bpos + i) = *reinterpret_cast<const int4*>(stage_pos + i);
+        } else {
+          for (int j = i; j < cnt; ++j) { bkey[j] = stage_key[j]; bpos[j] = stage_pos[j]; }
+        }
+      }
+    } else {
+      for (int i = threadIdx.x; i < cnt; i += BT) { bkey[i] = stage_key[i]; bpos[i] = stage_pos[i]; }
     }
   }
 }
@@ -422,13 +531,22 @@ struct CandidateList {
   }
 };
 
-// Second and third digit of the threshold on the candidates, and how many candidates at positions
-// below `before` are above / equal to the threshold.  each_global(f) visits every candidate from
-// memory (used when a wave's list overflowed).  Called by all threads after the candidates are
-// in (lists written, sh.hist[0] filled); starts with the barrier that publishes them.
+// The bits of the threshold below its leading digit, found on the candidates, and how many
+// candidates at positions below `before` are above / equal to the threshold.  The candidates agree
+// in every bit from `low_bits` up (`prefix` holds those bits; low_bits = 32, prefix = 0 for a bucket
+// whose keys may differ anywhere); the bits below are taken at most 11 at a time from the top, one
+// LDS histogram per step.  The first step's histogram, of first_digit(key, low_bits), is sh.hist[0],
+// filled by the caller while it collected the candidates.  each_global(f) visits every candidate
+// from memory (used when a wave's list overflowed).  Called by all threads after the candidates
+// are in; starts with the barrier that publishes them.
+__device__ __forceinline__ uint32_t first_digit(uint32_t key, int low_bits) {
+  const int w = min(11, low_bits);
+  return (key >> (low_bits - w)) & ((1u << w) - 1u);
+}
 template <typename GlobalEach>
-__device__ __forceinline__ void finish_select(const CandidateList& list, GlobalEach each_global, int d0, int remaining, int before,
-                                              int gt, SelectShared& sh, uint32_t& thr, int& quota, int& base_gt, int& base_eq) {
+__device__ __forceinline__ void finish_select(const CandidateList& list, GlobalEach each_global, uint32_t prefix, int low_bits,
+                                              int remaining, int before, int gt, SelectShared& sh, uint32_t& thr, int& quota,
+                                              int& base_gt, int& base_eq) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (!list.shared && list.n > kWaveCand && lane == 0) sh.overflow = 1;
   __syncthreads();
@@ -441,18 +559,27 @@ __device__ __forceinline__ void finish_select(const CandidateList& list, GlobalE
       each_global(f);
     }
   };
-  int d1, above1;
-  pick_digit(sh.hist[0], remaining, sh, 1, d1, above1);
-  remaining -= above1;
-  const uint32_t prefix22 = (((uint32_t)d0) << 21) | (((uint32_t)d1) << 10);
-  for_each_candidate([&](uint32_t key, int) {
-    if ((key >> 10) == (prefix22 >> 10)) atomicAdd(&sh.hist[1][key & 1023u], 1);
-  });
-  __syncthreads();
-  int d2, above2;
-  pick_digit(sh.hist[1], remaining, sh, 2, d2, above2);
-  remaining -= above2;
-  thr = prefix22 | (uint32_t)d2;
+  for (int step = 0;; ++step) {
+    int* hist = sh.hist[step & 1];
+    int d, above;
+    pick_digit(hist, remaining, sh, 1 + (step & 1), d, above);
+    remaining -= above;
+    const int w = min(11, low_bits);
+    low_bits -= w;
+    prefix |= (uint32_t)d << low_bits;
+    if (low_bits == 0) break;
+    if (low_bits > 11) {                         // a third step follows the next one, in this histogram again
+      for (int i = threadIdx.x; i < kBins; i += ST) hist[i] = 0;
+    }
+    int* next = sh.hist[(step + 1) & 1];
+    const uint32_t known = prefix >> low_bits;   // low_bits <= 21 here
+    const int lb = low_bits;
+    for_each_candidate([&](uint32_t key, int) {
+      if ((key >> lb) == known) atomicAdd(&next[first_digit(key, lb)], 1);
+    });
+    __syncthreads();
+  }
+  thr = prefix;
   quota = remaining;
   int eq = 0;
   const uint32_t t_key = thr;
@@ -520,6 +647,7 @@ struct RouteParams {
   uint16_t* table1;                // [H, C, kTableStride] leading digits of the residual keys of pool members
   uint8_t* tier; int32_t* idx_retain; int32_t* idx_approx;
   int32_t* pool_idx; uint32_t* pool_key;
+  const uint32_t* map;             // [H, 2]: the digit map (lowq, shift) of the head's score buckets
 };
 
 // Step 1: the pool is the n_pool tokens of highest score
@@ -533,6 +661,8 @@ __global__ __launch_bounds__(ST) void route_pool_kernel(RouteParams p) {
   const int n = p.n;
   VEC_TRACE(0);
   select_shared_init(sh);
+  // how the bucket launch cut the keys into leading digits
+  DigitMap map = {p.map[2 * h], min((int)p.map[2 * h + 1], 21)};
   const bool vec4 = (n & 3) == 0 && ((reinterpret_cast<uintptr_t>(sc) | reinterpret_cast<uintptr_t>(ep)) & 15u) == 0;
   auto load_f4 = [&](const float* a, int i0, float (&x)[EPT]) {
     if (vec4 && i0 + EPT <= n) {
@@ -585,6 +715,10 @@ __global__ __launch_bounds__(ST) void route_pool_kernel(RouteParams p) {
   const int tpc = ST / groups;                   // threads per chunk (at least 8)
   const int my_c = (int)threadIdx.x / tpc, my_sub = (int)threadIdx.x % tpc;
   const bool fits = m0 <= kCandCap;
+  // what the candidates already agree on: everything above the digit's 2^shift keys, or nothing
+  const bool high_shared = map.shares_high_bits(d0);
+  const int low_bits = high_shared ? map.shift : 32;
+  const uint32_t prefix = high_shared ? ((uint32_t)d0 + map.lowq) << map.shift : 0u;
   {
     const bool live = my_c < p.n_chunks;
     const int cnt = live ? sh.seg_count[my_c] : 0;
@@ -604,7 +738,7 @@ __global__ __launch_bounds__(ST) void route_pool_kernel(RouteParams p) {
         const int i = i0 + u * tpc + my_sub;
         if (i < cnt) {
           if (fits) { cand_key[dst0 + i] = ck[u]; cand_pos[dst0 + i] = cp[u]; }
-          atomicAdd(&sh.hist[0][(ck[u] >> 10) & 2047u], 1);
+          atomicAdd(&sh.hist[0][first_digit(ck[u], low_bits)], 1);
         }
       }
     }
@@ -625,7 +759,7 @@ __global__ __launch_bounds__(ST) void route_pool_kernel(RouteParams p) {
         const int src0 = my_c < p.n_chunks ? my_c * p.chunk_tokens + sh.seg_first[my_c] : 0;
         for (int i = my_sub; i < cnt; i += tpc) f(bkey[src0 + i], bpos[src0 + i]);
       },
-      d0, p.n_pool - above0, begin, gt, sh, thr, quota, base_gt, base_eq);
+      prefix, low_bits, p.n_pool - above0, begin, gt, sh, thr, quota, base_gt, base_eq);
   VEC_TRACE(4);
 
   // ordered pass over the chunk: tiers, pool list, leading digits of the residual keys
@@ -766,7 +900,7 @@ __global__ __launch_bounds__(ST) void route_split_kernel(RouteParams p) {
             if (i0 + j < m && (int)(key[j] >> 21) == d0) f(key[j], i0 + j);
         }
       },
-      d0, p.n_approx - above0, begin, gt, sh, thr, quota, base_gt, base_eq);
+      (uint32_t)d0 << 21, 21, p.n_approx - above0, begin, gt, sh, thr, quota, base_gt, base_eq);
   VEC_TRACE(19);
   uint32_t tok[EPT];
   ordered_emit(
@@ -849,7 +983,7 @@ static int route_chunk_tokens(int seq_len) {
 namespace {
 struct RouteLayout {
   int chunk_tokens, n_chunks, pool_stride;
-  size_t off_table0, off_table1, off_bkey, off_bpos, off_idx, off_key, total;
+  size_t off_map, off_range, off_table0, off_table1, off_bkey, off_bpos, off_idx, off_key, total;
 };
 RouteLayout route_layout(int n_kv_heads, int seq_len, int n_pool) {
   RouteLayout L;
@@ -860,6 +994,8 @@ RouteLayout route_layout(int n_kv_heads, int seq_len, int n_pool) {
   const size_t per_token = align_up((size_t)n_kv_heads * seq_len * sizeof(uint32_t), 256);
   const size_t per_pool = align_up((size_t)n_kv_heads * L.pool_stride * sizeof(uint32_t), 256);
   size_t off = 0;
+  L.off_map = off;    off += align_up((size_t)n_kv_heads * 2 * sizeof(uint32_t), 256);
+  L.off_range = off;  off += align_up((size_t)n_kv_heads * route_mass_range_slots(seq_len) * sizeof(float4), 256);
   L.off_table0 = off; off += tables;
   L.off_table1 = off; off += tables;
   L.off_bkey = off;   off += per_token;
@@ -875,6 +1011,10 @@ void fill_bucket_params(BucketParams& bp, const RouteLayout& L, void* route_ws) 
   bp.table = w8 ? reinterpret_cast<uint16_t*>(w8 + L.off_table0) : nullptr;
   bp.bkey = w8 ? reinterpret_cast<uint32_t*>(w8 + L.off_bkey) : nullptr;
   bp.bpos = w8 ? reinterpret_cast<int32_t*>(w8 + L.off_bpos) : nullptr;
+  bp.map = w8 ? reinterpret_cast<uint32_t*>(w8 + L.off_map) : nullptr;
+  bp.range = w8 ? reinterpret_cast<const float4*>(w8 + L.off_range) : nullptr;
+  bp.n_range = 0;
+  bp.log_ref = 0.f;
   bp.chunk_tokens = L.chunk_tokens;
   bp.n_chunks = L.n_chunks;
 }
@@ -882,12 +1022,21 @@ void fill_bucket_params(BucketParams& bp, const RouteLayout& L, void* route_ws) 
 
 size_t route_workspace_bytes(int n_kv_heads, int seq_len, int n_pool) { return route_layout(n_kv_heads, seq_len, n_pool).total; }
 
+// the scorer's second pass runs at least 512 tokens per workgroup
+int route_mass_range_slots(int seq_len) { return (seq_len + 511) / 512; }
+void* route_mass_range(void* route_ws, int n_kv_heads) {
+  return reinterpret_cast<unsigned char*>(route_ws) + route_layout(n_kv_heads, 1, 0).off_range;
+}
+
 int launch_pool_scores(const float* mass, float* score, int n_kv_heads, int seq_len, int n_prefix, int pool_kernel, int pool_mode,
-                       void* route_ws, hipStream_t stream) {
+                       void* route_ws, int n_range, hipStream_t stream) {
+  if (n_range < 0 || n_range > route_mass_range_slots(seq_len)) return VECTOR_ERR_ARG;
   const RouteLayout L = route_layout(n_kv_heads, seq_len, 0);      // the bucket areas do not depend on the pool size
   BucketParams bp;
   bp.src = mass; bp.score = score; bp.n = seq_len; bp.n_prefix = n_prefix; bp.kernel = pool_kernel; bp.take_max = pool_mode == VECTOR_POOL_MAX;
   fill_bucket_params(bp, L, route_ws);
+  bp.n_range = route_ws ? n_range : 0;
+  bp.log_ref = -log2f((float)(n_prefix > 0 ? n_prefix : 1));     // as in the scorer's second pass
   VEC_LAUNCH(K_POOL, route_bucket_kernel<true>, dim3(L.n_chunks, n_kv_heads), dim3(BT), 0, stream, bp);
   VEC_HIP(hipGetLastError());
   return VECTOR_OK;
@@ -909,6 +1058,7 @@ int launch_route(int n_kv_heads, int seq_len, const float* score, const float* e
   p.slice = kTile;
   while ((n_pool + p.slice - 1) / p.slice > kMaxChunks) p.slice *= 2;
   p.n_slices = (n_pool + p.slice - 1) / p.slice;
+  p.map = reinterpret_cast<const uint32_t*>(w8 + L.off_map);
   p.table0 = reinterpret_cast<uint16_t*>(w8 + L.off_table0);
   p.table1 = reinterpret_cast<uint16_t*>(w8 + L.off_table1);
   p.bkey = reinterpret_cast<uint32_t*>(w8 + L.off_bkey);

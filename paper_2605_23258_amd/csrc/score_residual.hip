@@ -57,6 +57,11 @@ struct PassParams {
   float2* part;         // [Hkv, R_pad, n_chunks]  (max, sum-exp), log2 domain
   float* mass;          // [Hkv, n]
   float* eps;           // [Hkv, n]
+  float4* range;        // [Hkv, gridDim.x] or null: every workgroup of pass 2 leaves, over the prefix columns
+                        // it stored with a positive mass m, their count and the sums of l and l * l, where
+                        // l = log2(m) - log_ref; the routing's bucket launch turns them into the head's
+                        // typical score range
+  float log_ref;        // log2 of the mean mass of a prefix column, -log2(n_prefix): keeps l small
   int repeat;           // probe kernels only: times each tile's arithmetic is run on the same registers
 };
 
@@ -811,6 +816,7 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
     }
   };
 
+  float st_n = 0.f, st_l = 0.f, st_ll = 0.f;   // over the columns this lane stores
   while (t0 < c_end) {
     const int tn = t0 + kStep;
     if (DO_RES && !ROPE && (!PROBE || rep == 0)) {   // values arrive while the score part computes
@@ -839,8 +845,15 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
       const int t = t0 + lane;             // lanes 0..31 -> subtile 0, 32..63 -> subtile 1
       if (t < mass_end) {
         float* dst = p.mass + (size_t)h * p.n + t;
-        const float m = (half ? col1 : col0) * p.inv_R;
-        *dst = p.accumulate ? *dst + m : m;
+        float m = (half ? col1 : col0) * p.inv_R;
+        if (p.accumulate) m += *dst;
+        *dst = m;
+        if (m > 0.f) {
+          const float l = __log2f(m) - p.log_ref;
+          st_n += 1.f;
+          st_l += l;
+          st_ll = fmaf(l, l, st_ll);
+        }
       }
     } else if (DO_MASS && !DO_RES) {
       load_next(tn);
@@ -915,6 +928,21 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
     rep = 0;
     t0 = tn;
   }
+  if (DO_MASS && p.range) {                   // uniform: the workgroup's sums, waves added in one fixed order
+    st_n = wave_sum_dpp(st_n);
+    st_l = wave_sum_dpp(st_l);
+    st_ll = wave_sum_dpp(st_ll);
+    __syncthreads();                          // every wave is done with the staged query rows
+    float* part = reinterpret_cast<float*>(q_lds);
+    if (lane == 0) { part[3 * wave] = st_n; part[3 * wave + 1] = st_l; part[3 * wave + 2] = st_ll; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      float a = 0.f, b = 0.f, c = 0.f;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) { a += part[3 * w]; b += part[3 * w + 1]; c += part[3 * w + 2]; }
+      p.range[(size_t)h * gridDim.x + blockIdx.x] = make_float4(a, b, c, 0.f);
+    }
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -977,7 +1005,7 @@ int make_plan(const vector_shape& s, bool do_mass, bool do_res, Plan& plan, int 
   p.threads_per_row = tpr;
   p.c2 = kLog2e / sqrtf((float)D);
   p.inv_R = 1.0f / (float)p.R;
-  p.q_head_rows = p.R; p.q_row0 = 0; p.accumulate = 0;
+  p.q_head_rows = p.R; p.q_row0 = 0; p.accumulate = 0; p.range = nullptr; p.log_ref = 0.f;
   p.k_st = s.k_stride_tok ? s.k_stride_tok : D;
   p.k_sh = s.k_stride_head ? s.k_stride_head : (int64_t)s.seq_len * p.k_st;
   p.v_st = s.v_stride_tok ? s.v_stride_tok : D;
@@ -1010,7 +1038,7 @@ size_t score_workspace_bytes(const vector_shape& s) {
 template <typename T, int D>
 static int run_passes(const SeqStack* stack, const vector_shape& s, const vector_shape& g, int q_row0, bool accumulate, const void* q,
                       const void* k, const void* v, const void* W, bool do_mass, float* eps, void* ws, hipStream_t stream,
-                      const RopeParams* rope, float** mass_out, int* n_prefix_out) {
+                      const RopeParams* rope, float4* range, int* n_range_out, float** mass_out, int* n_prefix_out) {
   const bool do_res = eps != nullptr;
   Plan plan;
   int rc = make_plan<T, D>(g, do_mass, do_res, plan, stack ? stack->heads_per_seq : 0);
@@ -1019,6 +1047,8 @@ static int run_passes(const SeqStack* stack, const vector_shape& s, const vector
   p.q = q; p.k = k; p.v = v; p.W = W; p.eps = eps; p.repeat = 1;
   const int rows_all = (s.n_q_heads / s.n_kv_heads) * s.window;
   p.q_head_rows = rows_all; p.q_row0 = q_row0; p.accumulate = accumulate ? 1 : 0;
+  p.range = do_mass ? range : nullptr;
+  p.log_ref = -log2f((float)(p.n_prefix > 0 ? p.n_prefix : 1));
   p.inv_R = 1.0f / (float)rows_all;
   if (stack) {                      // the strides inside a sequence are the shape's, as for one sequence
     p.hps = stack->heads_per_seq; p.k_sb = stack->k_stride_seq; p.v_sb = stack->v_stride_seq;
@@ -1039,6 +1069,7 @@ static int run_passes(const SeqStack* stack, const vector_shape& s, const vector
 
   const dim3 grid1(p.n_chunks, s.n_kv_heads);
   const dim3 grid((s.seq_len + p.tokens_per_chunk - 1) / p.tokens_per_chunk, s.n_kv_heads);
+  if (n_range_out) *n_range_out = (int)grid.x;
   if (do_mass) {
     const int nrb = p.R_pad / 32;
     if (plan.tiles) {
@@ -1081,22 +1112,24 @@ static int run_score_residual(const SeqStack* stack, const vector_shape& s, cons
                               float* score, float* eps, void* ws, hipStream_t stream, const RopeParams* rope,
                               void* route_ws) {
   const bool do_mass = score != nullptr;
-  if (!do_mass) return run_passes<T, D>(stack, s, s, 0, false, q, k, v, W, false, eps, ws, stream, rope, nullptr, nullptr);
+  if (!do_mass) return run_passes<T, D>(stack, s, s, 0, false, q, k, v, W, false, eps, ws, stream, rope, nullptr, nullptr, nullptr, nullptr);
   // The query heads of a KV head go through the two passes a group at a time; usually one group.
   // The first group's second pass carries the residual.
   const int G = s.n_q_heads / s.n_kv_heads;
   const int gh = heads_per_group<T, D>(s, eps != nullptr);
   if (gh == 0) return VECTOR_ERR_SHAPE;
   float* mass = nullptr;
-  int n_prefix = 0;
+  int n_prefix = 0, n_range = 0;
   for (int g0 = 0; g0 < G; g0 += gh) {
     vector_shape g = s;
     g.n_q_heads = s.n_kv_heads * (g0 + gh <= G ? gh : G - g0);
+    // the last group's second pass sees the finished mass: it leaves its statistics for the routing's buckets
+    float4* range = (route_ws && g0 + gh >= G) ? reinterpret_cast<float4*>(route_mass_range(route_ws, s.n_kv_heads)) : nullptr;
     const int rc = run_passes<T, D>(stack, s, g, g0 * s.window, g0 > 0, q, k, v, W, true, g0 == 0 ? eps : nullptr, ws, stream, rope,
-                                    &mass, &n_prefix);
+                                    range, &n_range, &mass, &n_prefix);
     if (rc != VECTOR_OK) return rc;
   }
-  return launch_pool_scores(mass, score, s.n_kv_heads, s.seq_len, n_prefix, s.pool_kernel, s.pool_mode, route_ws, stream);
+  return launch_pool_scores(mass, score, s.n_kv_heads, s.seq_len, n_prefix, s.pool_kernel, s.pool_mode, route_ws, n_range, stream);
 }
 
 template <typename T, int D>
