@@ -86,6 +86,18 @@ struct DigitMap {
   }
   __device__ __forceinline__ bool shares_high_bits(int d) const { return plain() || (d > 0 && d < 2047); }
 };
+// 2046 buckets of 2^shift keys each over [klo, khi], shift as small as that allows
+__device__ __forceinline__ DigitMap digit_map_for_keys(uint32_t klo, uint32_t khi) {
+  DigitMap plain = {0u, 21};
+  if (khi < klo) return plain;
+  // (khi >> s) - (klo >> s) <= ((khi - klo) >> s) + 1: start where the difference has 11 bits left
+  const uint32_t diff = khi - klo;
+  int s = diff ? max(0, 21 - (int)__clz(diff)) : 0;
+  if ((khi >> s) - (klo >> s) > 2045u) ++s;
+  if (s >= 21) return plain;
+  DigitMap m = {max(klo >> s, 1u) - 1u, s};
+  return m;
+}
 // cnt, sum_l, sum_ll: over the head's prefix columns of positive attention mass m, their number and
 // the sums of l = log2(m) - log_ref and of l * l.  The buckets cover the mean of log2(m) give or
 // take four standard deviations (and a 64th of an octave, so that equal masses still get a
@@ -102,14 +114,21 @@ __device__ __forceinline__ DigitMap digit_map_for_stats(float cnt, float sum_l, 
   const float sd = __builtin_amdgcn_sqrtf(fmaxf(sum_ll * inv - mu * mu, 0.f));
   const float mid = log_ref + mu, half = 4.f * sd + 0.015625f;
   if (!(mid - half > -120.f) || !(mid + half < 120.f)) return plain;        // also NaN
-  const uint32_t klo = float_key(__builtin_amdgcn_exp2f(mid - half)), khi = float_key(__builtin_amdgcn_exp2f(mid + half));
-  // (khi >> s) - (klo >> s) <= ((khi - klo) >> s) + 1: start where the difference has 11 bits left
-  const uint32_t diff = khi - klo;
-  int s = diff ? max(0, 21 - (int)__clz(diff)) : 0;
-  if ((khi >> s) - (klo >> s) > 2045u) ++s;
-  if (s >= 21) return plain;
-  DigitMap m = {(klo >> s) - 1u, s};
-  return m;
+  return digit_map_for_keys(float_key(__builtin_amdgcn_exp2f(mid - half)), float_key(__builtin_amdgcn_exp2f(mid + half)));
+}
+// The same from a sample of the keys themselves, for scores of any sign that arrive without
+// statistics (vector_route on its own): cnt keys k = key >> 12 with sum s1 and sum of squares s2.
+// For positive floats the key is linear in the score inside an octave and counts octaves across
+// them, so its mean and deviation bound the bulk the same way.
+__device__ __forceinline__ DigitMap digit_map_for_sample(unsigned long long cnt, unsigned long long s1, unsigned long long s2) {
+  DigitMap plain = {0u, 21};
+  if (cnt < 32) return plain;
+  const double inv = 1.0 / (double)cnt, mu = (double)s1 * inv;
+  const double var = (double)s2 * inv - mu * mu;
+  const double half = 4.0 * sqrt(var > 0.0 ? var : 0.0) + 32.0;             // 32 * 4096 keys: a 64th of an octave
+  const double lo = (mu - half) * 4096.0, hi = (mu + half) * 4096.0;
+  const uint32_t klo = lo > 0.0 ? (uint32_t)lo : 0u, khi = hi < 4294967295.0 ? (uint32_t)hi : 0xffffffffu;
+  return digit_map_for_keys(klo, khi);
 }
 
 // hist[digit] += cnt (cnt in 0..7) for every lane.  Keys of neighbouring tokens often share their
@@ -237,6 +256,7 @@ template <bool POOL>
 __global__ __launch_bounds__(BT) void route_bucket_kernel(BucketParams p) {
   __shared__ int hist[kBins];
   __shared__ int row[BT / kWave];
+  __shared__ uint32_t sample[BT / kWave][4];
   __shared__ __align__(16) uint32_t stage_key[kStageTokens];
   __shared__ __align__(16) int32_t stage_pos[kStageTokens];
   const int h = blockIdx.y, chunk = blockIdx.x;
@@ -276,6 +296,45 @@ __global__ __launch_bounds__(BT) void route_bucket_kernel(BucketParams p) {
       }
       map = digit_map_for_stats(wave_sum_dpp(cnt), wave_sum_dpp(sl), wave_sum_dpp(sll), p.log_ref);
       asm volatile("" ::"v"(warm));
+    }
+    if (!POOL) {
+      // no statistics came with the scores: four keys out of every 256, the same sample in every
+      // workgroup of the head (integer sums: any order gives the same map)
+      uint32_t c = 0, s1 = 0, s2lo = 0, s2hi = 0;
+      const bool al = (((size_t)h * p.n) & 3) == 0 && (reinterpret_cast<uintptr_t>(p.src) & 15u) == 0;
+      for (int i = (int)threadIdx.x * 256; i < p.n; i += BT * 256) {
+        float x[4] = {INFINITY, INFINITY, INFINITY, INFINITY};
+        if (al && i + 4 <= p.n) {
+          const float4 v = *reinterpret_cast<const float4*>(src + i);
+          x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            if (i + j < p.n) x[j] = src[i + j];
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const uint32_t key = float_key(x[j]);
+          if (key > 0x007fffffu && key < 0xff800000u) {                     // finite
+            const unsigned long long k = key >> 12, kk = k * k;
+            c += 1; s1 += (uint32_t)k; s2lo += (uint32_t)(kk & 0xfffffu); s2hi += (uint32_t)(kk >> 20);
+          }
+        }
+      }
+      const int wave = threadIdx.x >> 6;
+      c = (uint32_t)wave_total_of_scan(wave_incl_scan_dpp((int)c));
+      s1 = (uint32_t)wave_total_of_scan(wave_incl_scan_dpp((int)s1));
+      s2lo = (uint32_t)wave_total_of_scan(wave_incl_scan_dpp((int)s2lo));
+      s2hi = (uint32_t)wave_total_of_scan(wave_incl_scan_dpp((int)s2hi));
+      if (lane == 0) { sample[wave][0] = c; sample[wave][1] = s1; sample[wave][2] = s2lo; sample[wave][3] = s2hi; }
+      __syncthreads();
+      unsigned long long tc = 0, t1 = 0, t2 = 0;
+#pragma unroll
+      for (int w = 0; w < BT / kWave; ++w) {
+        tc += sample[w][0]; t1 += sample[w][1];
+        t2 += (unsigned long long)sample[w][2] + ((unsigned long long)sample[w][3] << 20);
+      }
+      map = digit_map_for_sample(tc, t1, t2);
     }
     if (chunk == 0 && threadIdx.x == 0) { p.map[2 * h] = map.lowq; p.map[2 * h + 1] = (uint32_t)map.shift; }
     __syncthreads();
