@@ -519,6 +519,24 @@ def run_extras(vb, dg, pl, torch, np, dev, cfg, shape, layer, out, ws, n_p, n_a)
                                ob["ia"][b * H * napx2:], ob["kr"][b * H * nr2:], ob["vr"][b * H * nr2:], ob["ka"][b * H * napx2:], nr2, wsb)
     res["compress_8x8192_one_call_each_us"] = per_call_us(per_sequence, 10)
     del kb, vbt, ob, keep_1, one_b
+    # The same layer shape with attention rows that are nearly uniform (queries scaled to 0.02, every
+    # score within a few per cent of 1/n) plus eight sink and eight anti-sink keys: the selection's
+    # radix buckets then have to follow the bulk of the scores, not the keys' leading bits.
+    gq = torch.Generator(device=dev).manual_seed(11)
+    q_flat = torch.randn(cfg.n_q_heads, cfg.window, d, generator=gq, device=dev) * 0.02
+    q_flat[:, :, 0] += 1.0
+    k_flat = torch.randn(H, n, d, generator=gq, device=dev)
+    at = torch.randperm(n - cfg.window, generator=gq, device=dev)[:16]
+    k_flat[:, at] = 0
+    k_flat[:, at[:8], 0] = 8.0 * d ** 0.5
+    k_flat[:, at[8:], 0] = -8.0 * d ** 0.5
+    q_flat, k_flat = q_flat.bfloat16(), k_flat.bfloat16()
+    wsc = pl.alloc_workspace(vb.vector_compress_workspace_bytes(shape, n_p, n_a), dev)
+    res["compress_flat_heads_us_per_layer"] = per_call_us(
+        lambda: pl.compress_layer(shape, q_flat, k_flat, layer["v"], layer["w_cal"], n_p, n_a, out, wsc, one_call=True))
+    res["compress_us_per_layer"] = per_call_us(
+        lambda: pl.compress_layer(shape, layer["q_win"], layer["k"], layer["v"], layer["w_cal"], n_p, n_a, out, wsc, one_call=True))
+    del q_flat, k_flat, wsc
     # Section 5's approximation-ratio sweep re-expressed on the distortion measure of Section 4: at a
     # fixed compression ratio (fixed footprint of 2 (1 - p_c) n rows) budget moves from retained
     # values to pool keys; p_a = 0 is binary eviction with the same memory.  Weights: the layer's
