@@ -534,9 +534,22 @@ def run_extras(vb, dg, pl, torch, np, dev, cfg, shape, layer, out, ws, n_p, n_a)
     wsc = pl.alloc_workspace(vb.vector_compress_workspace_bytes(shape, n_p, n_a), dev)
     res["compress_flat_heads_us_per_layer"] = per_call_us(
         lambda: pl.compress_layer(shape, q_flat, k_flat, layer["v"], layer["w_cal"], n_p, n_a, out, wsc, one_call=True))
+    # the same pass when the prefill's attention kernel hands over the window rows' log-sum-exp
+    # (an input here: formed with torch in fp32), so that the first pass over the keys is not run
+    G = cfg.n_q_heads // H
+    w = cfg.window
+    logits = torch.einsum("hgrd,hnd->hgrn", layer["q_win"].float().view(H, G, w, d), layer["k"].float()) / float(np.sqrt(d))
+    cols = torch.arange(n, device=dev).view(1, 1, 1, n)
+    rows = (n - w + torch.arange(w, device=dev)).view(1, 1, w, 1)
+    lse = torch.logsumexp(logits.masked_fill(cols > rows, float("-inf")), dim=-1).reshape(cfg.n_q_heads, w).contiguous()
+    del logits
+    res["compress_with_lse_us_per_layer"] = per_call_us(
+        lambda: vb.vector_compress_lse(shape, layer["q_win"], layer["k"], layer["v"], layer["w_cal"], lse, 0, n_p, n_a, out.score,
+                                       out.eps, out.tier, out.idx_retain, out.idx_approx, out.k_ret, out.v_ret, out.k_apx,
+                                       out.k_ret.shape[1], wsc))
     res["compress_us_per_layer"] = per_call_us(
         lambda: pl.compress_layer(shape, layer["q_win"], layer["k"], layer["v"], layer["w_cal"], n_p, n_a, out, wsc, one_call=True))
-    del q_flat, k_flat, wsc
+    del q_flat, k_flat, wsc, lse
     # Section 5's approximation-ratio sweep re-expressed on the distortion measure of Section 4: at a
     # fixed compression ratio (fixed footprint of 2 (1 - p_c) n rows) budget moves from retained
     # values to pool keys; p_a = 0 is binary eviction with the same memory.  Weights: the layer's

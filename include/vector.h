@@ -180,6 +180,24 @@ VECTOR_API int vector_compress(const vector_shape* shape, const void* q_win, con
                     int32_t* idx_retain, int32_t* idx_approx, void* k_ret, void* v_ret, void* k_apx,
                     int32_t cap_retain, void* ws, size_t ws_bytes, void* stream);
 
+/* vector_score_residual and vector_compress for callers that already hold the log-sum-exp of the
+ * window queries' attention rows (Section 3.2 Step 1's scorer attends from the last w positions; the
+ * attention kernel of the prefill has computed exactly these rows and returns their log-sum-exp).
+ * Then the first of the two passes over k is not needed.
+ *   lse   device fp32: lse[hq * lse_stride_head + r] = log sum_{t <= n - w + r} exp(q[hq,r] . k[hq / G, t] / sqrt(d))
+ *         (natural logarithm, causal, r = 0 .. w-1 the last w positions); lse_stride_head in elements,
+ *         0 meaning w (a slice of a [Hq, n] array has stride n).
+ * Same outputs as the calls without it, to the tolerance of the fp32 log-sum-exp given; a wrong
+ * lse gives wrong scores, nothing checks it.  Other arguments, layouts and errors as there. */
+VECTOR_API int vector_score_residual_lse(const vector_shape* shape, const void* q_win, const void* k, const void* v,
+                              const void* W, const float* lse, int64_t lse_stride_head, float* score, float* eps,
+                              void* ws, size_t ws_bytes, void* stream);
+VECTOR_API int vector_compress_lse(const vector_shape* shape, const void* q_win, const void* k, const void* v, const void* W,
+                        const float* lse, int64_t lse_stride_head,
+                        int32_t n_pool, int32_t n_approx, float* score, float* eps, uint8_t* tier,
+                        int32_t* idx_retain, int32_t* idx_approx, void* k_ret, void* v_ret, void* k_apx,
+                        int32_t cap_retain, void* ws, size_t ws_bytes, void* stream);
+
 /* The compression pass of one layer for a batch of sequences of unequal length (Section 3.2 applies
  * per sequence: every sequence is scored, routed and packed on its own, with its own counts).
  * Sizes are host arrays of `batch` entries; shape->seq_len is ignored.  With

@@ -25,6 +25,7 @@ EXPORTS = (
     "vector_strerror", "vector_score", "vector_residual", "vector_score_residual", "vector_route",
     "vector_route_static", "vector_route_static_scratch_bytes", "vector_compact", "vector_decode_attn", "vector_compress_workspace_bytes", "vector_compress",
     "vector_compress_batch_workspace_bytes", "vector_compress_batch",
+    "vector_score_residual_lse", "vector_compress_lse",
     "vector_timing_enable", "vector_timing_kernels", "vector_timing_name", "vector_timing_read",
     "vector_probe_residual_mfma", "vector_probe_mfma_loop",
     "vector_residual_rope", "vector_score_residual_rope", "vector_decode_attn_rope",
@@ -117,6 +118,9 @@ def lib() -> C.CDLL:
         L.vector_residual.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, sz, vp]
         L.vector_score_residual.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.vector_route.argtypes = [i32, i32, vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
+        L.vector_score_residual_lse.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, C.c_int64, vp, vp, vp, sz, vp]
+        L.vector_compress_lse.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, C.c_int64, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp,
+                                          i32, vp, sz, vp]
         L.vector_route_static.argtypes = [i32, i32, vp, vp, i32, i32, vp, vp, vp, vp]
         L.vector_route_static_scratch_bytes.argtypes = []
         L.vector_route_static_scratch_bytes.restype = sz
@@ -215,6 +219,20 @@ def vector_residual(shape: Shape, k, v, W, eps, ws=None, stream=None) -> None:
 def vector_score_residual(shape: Shape, q_win, k, v, W, score, eps, ws, stream=None) -> None:
     _check(lib().vector_score_residual(C.byref(shape), _ptr(q_win), _ptr(k), _ptr(v), _ptr(W), _ptr(score),
                                        _ptr(eps), _ptr(ws), _nbytes(ws), _stream(stream)), "vector_score_residual")
+
+
+def vector_score_residual_lse(shape: Shape, q_win, k, v, W, lse, lse_stride_head: int, score, eps, ws, stream=None) -> None:
+    _check(lib().vector_score_residual_lse(C.byref(shape), _ptr(q_win), _ptr(k), _ptr(v), _ptr(W), _ptr(lse), lse_stride_head,
+                                           _ptr(score), _ptr(eps), _ptr(ws), _nbytes(ws), _stream(stream)),
+           "vector_score_residual_lse")
+
+
+def vector_compress_lse(shape: Shape, q_win, k, v, W, lse, lse_stride_head: int, n_pool: int, n_approx: int, score, eps, tier,
+                        idx_retain, idx_approx, k_ret, v_ret, k_apx, cap_retain: int, ws, stream=None) -> None:
+    _check(lib().vector_compress_lse(C.byref(shape), _ptr(q_win), _ptr(k), _ptr(v), _ptr(W), _ptr(lse), lse_stride_head,
+                                     n_pool, n_approx, _ptr(score), _ptr(eps), _ptr(tier), _ptr(idx_retain), _ptr(idx_approx),
+                                     _ptr(k_ret), _ptr(v_ret), _ptr(k_apx), cap_retain, _ptr(ws), _nbytes(ws), _stream(stream)),
+           "vector_compress_lse")
 
 
 def vector_route(n_kv_heads: int, seq_len: int, score, eps, n_pool: int, n_approx: int, tier, idx_retain,

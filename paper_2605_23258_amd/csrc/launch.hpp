@@ -48,9 +48,14 @@ struct RopeParams;
 // as it is.
 struct SeqStack { int heads_per_seq; int64_t k_stride_seq, v_stride_seq; };
 
+// The log-sum-exp of the window queries' attention rows, when the caller already has it (the
+// attention kernel of the prefill returns it): natural log, logits scaled by 1 / sqrt(d), causal.
+// Row r of query head hq at lse[hq * stride_head + r] (stride_head 0: w).
+struct QueryLse { const float* lse; int64_t stride_head; };
+
 int launch_score_residual(const vector_shape& s, const void* q, const void* k, const void* v, const void* W,
                           float* score, float* eps, void* ws, hipStream_t stream, const RopeParams* rope = nullptr,
-                          void* route_ws = nullptr, const SeqStack* stack = nullptr);
+                          void* route_ws = nullptr, const SeqStack* stack = nullptr, const QueryLse* lse = nullptr);
 
 int launch_residual_probe(const vector_shape& s, const void* k, const void* v, const void* W, float* eps, int repeat,
                           hipStream_t stream);

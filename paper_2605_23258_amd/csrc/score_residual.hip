@@ -61,6 +61,8 @@ struct PassParams {
                         // it stored with a positive mass m, their count and the sums of l and l * l, where
                         // l = log2(m) - log_ref; the routing's bucket launch turns them into the head's
                         // typical score range
+  const float* lse;     // null, or the log-sum-exp (natural log, logits scaled by 1/sqrt(d)) of every query row,
+  int64_t lse_sh;       // row r of query head hq at lse[hq * lse_sh + r]: then pass 2 needs no pass 1
   float log_ref;        // log2 of the mean mass of a prefix column, -log2(n_prefix): keeps l small
   int repeat;           // probe kernels only: times each tile's arithmetic is run on the same registers
 };
@@ -647,7 +649,7 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
   const int rows_per_sweep = NT / tpr;
   float2 pre[kPre];
   if (DO_MASS) {
-    {
+    if (!p.lse) {
       const int row = min((int)threadIdx.x / tpr, p.R_pad - 1);      // threads beyond R_pad rows load a duplicate
       const float2* part = p.part + ((size_t)h * p.R_pad + row) * p.n_chunks;
 #pragma unroll
@@ -683,7 +685,13 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
       l = l * fast_exp2(m - ms) + l2 * fast_exp2(m2 - ms);
       m = mn;
     };
-    for (int row0 = 0; row0 < p.R_pad; row0 += rows_per_sweep) {
+    if (p.lse) {                              // the caller's log-sum-exp, turned into the log2 domain of the logits
+      for (int row = threadIdx.x; row < p.R_pad; row += NT) {
+        const int qr = p.q_row0 + row, g = qr / p.w, r = qr - g * p.w;
+        bias_lds[row] = (row < p.R) ? p.lse[((int64_t)h * (p.q_head_rows / p.w) + g) * p.lse_sh + r] * kLog2e : INFINITY;
+      }
+    }
+    for (int row0 = 0; !p.lse && row0 < p.R_pad; row0 += rows_per_sweep) {
       const int row = row0 + threadIdx.x / tpr;
       float m = -INFINITY, l = 0.f;
       if (row < p.R_pad) {
@@ -1005,7 +1013,7 @@ int make_plan(const vector_shape& s, bool do_mass, bool do_res, Plan& plan, int 
   p.threads_per_row = tpr;
   p.c2 = kLog2e / sqrtf((float)D);
   p.inv_R = 1.0f / (float)p.R;
-  p.q_head_rows = p.R; p.q_row0 = 0; p.accumulate = 0; p.range = nullptr; p.log_ref = 0.f;
+  p.q_head_rows = p.R; p.q_row0 = 0; p.accumulate = 0; p.range = nullptr; p.log_ref = 0.f; p.lse = nullptr; p.lse_sh = 0;
   p.k_st = s.k_stride_tok ? s.k_stride_tok : D;
   p.k_sh = s.k_stride_head ? s.k_stride_head : (int64_t)s.seq_len * p.k_st;
   p.v_st = s.v_stride_tok ? s.v_stride_tok : D;
@@ -1038,7 +1046,7 @@ size_t score_workspace_bytes(const vector_shape& s) {
 template <typename T, int D>
 static int run_passes(const SeqStack* stack, const vector_shape& s, const vector_shape& g, int q_row0, bool accumulate, const void* q,
                       const void* k, const void* v, const void* W, bool do_mass, float* eps, void* ws, hipStream_t stream,
-                      const RopeParams* rope, float4* range, int* n_range_out, float** mass_out, int* n_prefix_out) {
+                      const RopeParams* rope, const QueryLse* lse, float4* range, int* n_range_out, float** mass_out, int* n_prefix_out) {
   const bool do_res = eps != nullptr;
   Plan plan;
   int rc = make_plan<T, D>(g, do_mass, do_res, plan, stack ? stack->heads_per_seq : 0);
@@ -1048,6 +1056,7 @@ static int run_passes(const SeqStack* stack, const vector_shape& s, const vector
   const int rows_all = (s.n_q_heads / s.n_kv_heads) * s.window;
   p.q_head_rows = rows_all; p.q_row0 = q_row0; p.accumulate = accumulate ? 1 : 0;
   p.range = do_mass ? range : nullptr;
+  if (lse && do_mass) { p.lse = lse->lse; p.lse_sh = lse->stride_head ? lse->stride_head : s.window; }
   p.log_ref = -log2f((float)(p.n_prefix > 0 ? p.n_prefix : 1));
   p.inv_R = 1.0f / (float)rows_all;
   if (stack) {                      // the strides inside a sequence are the shape's, as for one sequence
@@ -1070,7 +1079,7 @@ static int run_passes(const SeqStack* stack, const vector_shape& s, const vector
   const dim3 grid1(p.n_chunks, s.n_kv_heads);
   const dim3 grid((s.seq_len + p.tokens_per_chunk - 1) / p.tokens_per_chunk, s.n_kv_heads);
   if (n_range_out) *n_range_out = (int)grid.x;
-  if (do_mass) {
+  if (do_mass && !p.lse) {                    // pass 1: the rows' (max, sum-exp); not needed when the caller brings them
     const int nrb = p.R_pad / 32;
     if (plan.tiles) {
       const size_t lds_tiles = stats_tiles_lds(nrb, Tile<T, D>::kLdsStride);
@@ -1110,9 +1119,9 @@ static int heads_per_group(const vector_shape& s, bool do_res) {
 template <typename T, int D>
 static int run_score_residual(const SeqStack* stack, const vector_shape& s, const void* q, const void* k, const void* v, const void* W,
                               float* score, float* eps, void* ws, hipStream_t stream, const RopeParams* rope,
-                              void* route_ws) {
+                              void* route_ws, const QueryLse* lse) {
   const bool do_mass = score != nullptr;
-  if (!do_mass) return run_passes<T, D>(stack, s, s, 0, false, q, k, v, W, false, eps, ws, stream, rope, nullptr, nullptr, nullptr, nullptr);
+  if (!do_mass) return run_passes<T, D>(stack, s, s, 0, false, q, k, v, W, false, eps, ws, stream, rope, nullptr, nullptr, nullptr, nullptr, nullptr);
   // The query heads of a KV head go through the two passes a group at a time; usually one group.
   // The first group's second pass carries the residual.
   const int G = s.n_q_heads / s.n_kv_heads;
@@ -1126,7 +1135,7 @@ static int run_score_residual(const SeqStack* stack, const vector_shape& s, cons
     // the last group's second pass sees the finished mass: it leaves its statistics for the routing's buckets
     float4* range = (route_ws && g0 + gh >= G) ? reinterpret_cast<float4*>(route_mass_range(route_ws, s.n_kv_heads)) : nullptr;
     const int rc = run_passes<T, D>(stack, s, g, g0 * s.window, g0 > 0, q, k, v, W, true, g0 == 0 ? eps : nullptr, ws, stream, rope,
-                                    range, &n_range, &mass, &n_prefix);
+                                    lse, range, &n_range, &mass, &n_prefix);
     if (rc != VECTOR_OK) return rc;
   }
   return launch_pool_scores(mass, score, s.n_kv_heads, s.seq_len, n_prefix, s.pool_kernel, s.pool_mode, route_ws, n_range, stream);
@@ -1158,13 +1167,13 @@ int launch_residual_probe(const vector_shape& s, const void* k, const void* v, c
 
 int launch_score_residual(const vector_shape& s, const void* q, const void* k, const void* v, const void* W,
                           float* score, float* eps, void* ws, hipStream_t stream, const RopeParams* rope,
-                          void* route_ws, const SeqStack* stack) {
+                          void* route_ws, const SeqStack* stack, const QueryLse* lse) {
   if (s.dtype == VECTOR_BF16) {
-    if (s.head_dim == 128) return run_score_residual<bf16_t, 128>(stack, s, q, k, v, W, score, eps, ws, stream, rope, route_ws);
-    if (s.head_dim == 64) return run_score_residual<bf16_t, 64>(stack, s, q, k, v, W, score, eps, ws, stream, rope, route_ws);
+    if (s.head_dim == 128) return run_score_residual<bf16_t, 128>(stack, s, q, k, v, W, score, eps, ws, stream, rope, route_ws, lse);
+    if (s.head_dim == 64) return run_score_residual<bf16_t, 64>(stack, s, q, k, v, W, score, eps, ws, stream, rope, route_ws, lse);
   } else if (s.dtype == VECTOR_F32) {
-    if (s.head_dim == 128) return run_score_residual<float, 128>(stack, s, q, k, v, W, score, eps, ws, stream, rope, route_ws);
-    if (s.head_dim == 64) return run_score_residual<float, 64>(stack, s, q, k, v, W, score, eps, ws, stream, rope, route_ws);
+    if (s.head_dim == 128) return run_score_residual<float, 128>(stack, s, q, k, v, W, score, eps, ws, stream, rope, route_ws, lse);
+    if (s.head_dim == 64) return run_score_residual<float, 64>(stack, s, q, k, v, W, score, eps, ws, stream, rope, route_ws, lse);
   } else {
     return VECTOR_ERR_DTYPE;
   }

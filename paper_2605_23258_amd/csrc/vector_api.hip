@@ -144,13 +144,20 @@ size_t vector_compress_workspace_bytes(const vector_shape* s, int32_t n_pool, in
   return vec::score_workspace_bytes(*s) + vec::route_workspace_bytes(s->n_kv_heads, s->seq_len, n_pool) + 256;
 }
 
+static int check_lse(const vector_shape* s, const vec::QueryLse* lse) {
+  if (!lse->lse || (reinterpret_cast<uintptr_t>(lse->lse) & 3u)) return VECTOR_ERR_ARG;
+  if (lse->stride_head != 0 && lse->stride_head < s->window) return VECTOR_ERR_ARG;
+  return VECTOR_OK;
+}
+
 // vector_compress; with `stack`, several sequences of one shape as one problem (s holds the stacked head counts)
 static int compress_impl(const vector_shape* s, const void* q_win, const void* k, const void* v, const void* W, int32_t n_pool,
                          int32_t n_approx, float* score, float* eps, uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx,
                          void* k_ret, void* v_ret, void* k_apx, int32_t cap_retain, void* ws, size_t ws_bytes, void* stream,
-                         const vec::SeqStack* stack) {
+                         const vec::SeqStack* stack, const vec::QueryLse* lse = nullptr) {
   int rc = check_shape(s, true);
   if (rc) return rc;
+  if (lse && (rc = check_lse(s, lse))) return rc;
   const int n_retain = n_pool - n_approx;
   if (n_approx < 0 || n_pool < n_approx || n_pool > s->seq_len || cap_retain < n_retain) return VECTOR_ERR_ARG;
   if (!q_win || !k || !v || !W || !score || !eps || !tier) return VECTOR_ERR_ARG;
@@ -163,7 +170,7 @@ static int compress_impl(const vector_shape* s, const void* q_win, const void* k
   void* route_ws = reinterpret_cast<unsigned char*>(ws) + (score_ws + 255) / 256 * 256;
   // the scorer's pooling launch also builds the routing's buckets of score keys
   void* buckets = n_pool > 0 ? route_ws : nullptr;
-  if ((rc = vec::launch_score_residual(*s, q_win, k, v, W, score, eps, ws, st, nullptr, buckets, stack))) return rc;
+  if ((rc = vec::launch_score_residual(*s, q_win, k, v, W, score, eps, ws, st, nullptr, buckets, stack, lse))) return rc;
   if ((rc = vec::launch_route(s->n_kv_heads, s->seq_len, score, eps, n_pool, n_approx, tier, idx_retain, idx_approx, route_ws,
                               buckets != nullptr, st)))
     return rc;
@@ -175,6 +182,15 @@ int vector_compress(const vector_shape* s, const void* q_win, const void* k, con
                     void* k_ret, void* v_ret, void* k_apx, int32_t cap_retain, void* ws, size_t ws_bytes, void* stream) {
   return compress_impl(s, q_win, k, v, W, n_pool, n_approx, score, eps, tier, idx_retain, idx_approx, k_ret, v_ret, k_apx, cap_retain,
                        ws, ws_bytes, stream, nullptr);
+}
+
+int vector_compress_lse(const vector_shape* s, const void* q_win, const void* k, const void* v, const void* W, const float* lse,
+                        int64_t lse_stride_head, int32_t n_pool, int32_t n_approx, float* score, float* eps, uint8_t* tier,
+                        int32_t* idx_retain, int32_t* idx_approx, void* k_ret, void* v_ret, void* k_apx, int32_t cap_retain,
+                        void* ws, size_t ws_bytes, void* stream) {
+  const vec::QueryLse ql = {lse, lse_stride_head};
+  return compress_impl(s, q_win, k, v, W, n_pool, n_approx, score, eps, tier, idx_retain, idx_approx, k_ret, v_ret, k_apx, cap_retain,
+                       ws, ws_bytes, stream, nullptr, &ql);
 }
 
 namespace {
@@ -363,6 +379,19 @@ int vector_score_residual(const vector_shape* s, const void* q_win, const void* 
   if (!aligned16(q_win) || !aligned16(k) || !aligned16(v) || !aligned16(W)) return VECTOR_ERR_ARG;
   if ((rc = check_ws(ws, ws_bytes, vec::score_workspace_bytes(*s)))) return rc;
   return vec::launch_score_residual(*s, q_win, k, v, W, score, eps, ws, (hipStream_t)stream);
+}
+
+int vector_score_residual_lse(const vector_shape* s, const void* q_win, const void* k, const void* v, const void* W,
+                              const float* lse, int64_t lse_stride_head, float* score, float* eps, void* ws, size_t ws_bytes,
+                              void* stream) {
+  int rc = check_shape(s, true);
+  if (rc) return rc;
+  const vec::QueryLse ql = {lse, lse_stride_head};
+  if ((rc = check_lse(s, &ql))) return rc;
+  if (!q_win || !k || !v || !W || !score || !eps) return VECTOR_ERR_ARG;
+  if (!aligned16(q_win) || !aligned16(k) || !aligned16(v) || !aligned16(W)) return VECTOR_ERR_ARG;
+  if ((rc = check_ws(ws, ws_bytes, vec::score_workspace_bytes(*s)))) return rc;
+  return vec::launch_score_residual(*s, q_win, k, v, W, score, eps, ws, (hipStream_t)stream, nullptr, nullptr, nullptr, &ql);
 }
 
 int vector_route(int32_t n_kv_heads, int32_t seq_len, const float* score, const float* eps, int32_t n_pool,
