@@ -345,6 +345,13 @@ VECTOR_API int vector_residual_rope(const vector_shape* shape, const void* k, co
 VECTOR_API int vector_score_residual_rope(const vector_shape* shape, const void* q_win, const void* k, const void* v,
                                const void* W, const vector_rope* rope, float* score, float* eps, void* ws,
                                size_t ws_bytes, void* stream);
+/* vector_compress on post-RoPE keys: vector_score_residual_rope, vector_route and vector_compact in
+ * one call, the same outputs bit for bit (the packed cache holds the keys as cached, rotated: the
+ * decode-time entry points turn approximated rows back).  ws: vector_compress_workspace_bytes. */
+VECTOR_API int vector_compress_rope(const vector_shape* shape, const vector_rope* rope, const void* q_win, const void* k,
+                         const void* v, const void* W, int32_t n_pool, int32_t n_approx, float* score, float* eps,
+                         uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx, void* k_ret, void* v_ret, void* k_apx,
+                         int32_t cap_retain, void* ws, size_t ws_bytes, void* stream);
 /* vector_decode_attn on a post-RoPE cache: out = sum_ret p_t v_t + sum_apx p_t ((R^-1 k_t) . W[h]),
  * logits from the cached keys.  VECTOR_DECODE_LITERAL is not available here (VECTOR_ERR_DTYPE). */
 VECTOR_API int vector_decode_attn_rope(const vector_cache* cache, const vector_rope* rope, const void* q, float scale,

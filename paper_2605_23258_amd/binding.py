@@ -25,7 +25,7 @@ EXPORTS = (
     "vector_strerror", "vector_score", "vector_residual", "vector_score_residual", "vector_route",
     "vector_route_static", "vector_route_static_scratch_bytes", "vector_compact", "vector_decode_attn", "vector_compress_workspace_bytes", "vector_compress",
     "vector_compress_batch_workspace_bytes", "vector_compress_batch",
-    "vector_score_residual_lse", "vector_compress_lse",
+    "vector_score_residual_lse", "vector_compress_lse", "vector_compress_rope",
     "vector_timing_enable", "vector_timing_kernels", "vector_timing_name", "vector_timing_read",
     "vector_probe_residual_mfma", "vector_probe_mfma_loop",
     "vector_residual_rope", "vector_score_residual_rope", "vector_decode_attn_rope",
@@ -118,6 +118,8 @@ def lib() -> C.CDLL:
         L.vector_residual.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, sz, vp]
         L.vector_score_residual.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.vector_route.argtypes = [i32, i32, vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
+        L.vector_compress_rope.argtypes = [C.POINTER(Shape), C.POINTER(Rope), vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp,
+                                           i32, vp, sz, vp]
         L.vector_score_residual_lse.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, C.c_int64, vp, vp, vp, sz, vp]
         L.vector_compress_lse.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, C.c_int64, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp,
                                           i32, vp, sz, vp]
@@ -358,6 +360,14 @@ def vector_compress(shape: Shape, q_win, k, v, W, n_pool: int, n_approx: int, sc
     _check(lib().vector_compress(C.byref(shape), _ptr(q_win), _ptr(k), _ptr(v), _ptr(W), n_pool, n_approx, _ptr(score),
                                  _ptr(eps), _ptr(tier), _ptr(idx_retain), _ptr(idx_approx), _ptr(k_ret), _ptr(v_ret),
                                  _ptr(k_apx), cap_retain, _ptr(ws), _nbytes(ws), _stream(stream)), "vector_compress")
+
+
+def vector_compress_rope(shape: Shape, rope: Rope, q_win, k, v, W, n_pool: int, n_approx: int, score, eps, tier, idx_retain,
+                         idx_approx, k_ret, v_ret, k_apx, cap_retain: int, ws, stream=None) -> None:
+    _check(lib().vector_compress_rope(C.byref(shape), C.byref(rope), _ptr(q_win), _ptr(k), _ptr(v), _ptr(W), n_pool, n_approx,
+                                      _ptr(score), _ptr(eps), _ptr(tier), _ptr(idx_retain), _ptr(idx_approx), _ptr(k_ret),
+                                      _ptr(v_ret), _ptr(k_apx), cap_retain, _ptr(ws), _nbytes(ws), _stream(stream)),
+           "vector_compress_rope")
 
 
 def vector_compress_batch_workspace_bytes(shape: Shape, batch: Batch) -> int:

@@ -154,7 +154,7 @@ static int check_lse(const vector_shape* s, const vec::QueryLse* lse) {
 static int compress_impl(const vector_shape* s, const void* q_win, const void* k, const void* v, const void* W, int32_t n_pool,
                          int32_t n_approx, float* score, float* eps, uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx,
                          void* k_ret, void* v_ret, void* k_apx, int32_t cap_retain, void* ws, size_t ws_bytes, void* stream,
-                         const vec::SeqStack* stack, const vec::QueryLse* lse = nullptr) {
+                         const vec::SeqStack* stack, const vec::QueryLse* lse = nullptr, const vec::RopeParams* rope = nullptr) {
   int rc = check_shape(s, true);
   if (rc) return rc;
   if (lse && (rc = check_lse(s, lse))) return rc;
@@ -170,7 +170,7 @@ static int compress_impl(const vector_shape* s, const void* q_win, const void* k
   void* route_ws = reinterpret_cast<unsigned char*>(ws) + (score_ws + 255) / 256 * 256;
   // the scorer's pooling launch also builds the routing's buckets of score keys
   void* buckets = n_pool > 0 ? route_ws : nullptr;
-  if ((rc = vec::launch_score_residual(*s, q_win, k, v, W, score, eps, ws, st, nullptr, buckets, stack, lse))) return rc;
+  if ((rc = vec::launch_score_residual(*s, q_win, k, v, W, score, eps, ws, st, rope, buckets, stack, lse))) return rc;
   if ((rc = vec::launch_route(s->n_kv_heads, s->seq_len, score, eps, n_pool, n_approx, tier, idx_retain, idx_approx, route_ws,
                               buckets != nullptr, st)))
     return rc;
@@ -504,6 +504,18 @@ int vector_score_residual_rope(const vector_shape* s, const void* q_win, const v
   if ((rc = make_rope(rope, s->head_dim, rp))) return rc;
   if ((rc = check_ws(ws, ws_bytes, vec::score_workspace_bytes(*s)))) return rc;
   return vec::launch_score_residual(*s, q_win, k, v, W, score, eps, ws, (hipStream_t)stream, &rp);
+}
+
+int vector_compress_rope(const vector_shape* s, const vector_rope* rope, const void* q_win, const void* k, const void* v,
+                         const void* W, int32_t n_pool, int32_t n_approx, float* score, float* eps, uint8_t* tier,
+                         int32_t* idx_retain, int32_t* idx_approx, void* k_ret, void* v_ret, void* k_apx, int32_t cap_retain,
+                         void* ws, size_t ws_bytes, void* stream) {
+  if (!s) return VECTOR_ERR_ARG;
+  vec::RopeParams rp;
+  const int rc = make_rope(rope, s->head_dim, rp);
+  if (rc) return rc;
+  return compress_impl(s, q_win, k, v, W, n_pool, n_approx, score, eps, tier, idx_retain, idx_approx, k_ret, v_ret, k_apx, cap_retain,
+                       ws, ws_bytes, stream, nullptr, nullptr, &rp);
 }
 
 }  // extern "C"

@@ -72,6 +72,45 @@ def test_residual_and_score_on_rotated_keys(name):
     close(got[:, : n - w].astype(np.float64) * n, ref_score[:, : n - w].astype(np.float64) * n, "n*score (rope call)")
 
 
+@pytest.mark.parametrize("name", ["bf16_d128_ragged_offset", "bf16_d128_interleaved", "f32_d64"])
+def test_one_call_compress_on_rotated_keys(name):
+    """vector_compress_rope = vector_score_residual_rope + vector_route + vector_compact, bit for bit;
+    the routing of its own floats is the oracle's and the packed rows are the cached (rotated) rows."""
+    base, over, interleaved, offset = CASES[name]
+    cfg = dg.scaled(dg.CONFIGS[base], **over)
+    li = wl.make_layer(cfg, 0, rope_theta=THETA, rope_interleaved=interleaved, pos_offset=offset)
+    H, n, w = cfg.n_kv_heads, cfg.seq_len, cfg.window
+    n_r, n_a, n_p = cfg.counts()
+    shape = pl.shape_of(cfg)
+    dev = {x: pl.to_device(getattr(li, x)) for x in ("q_win", "k", "v", "w_cal")}
+    rope, keep = vb.make_rope(li.extra["inv_freq"], None, interleaved, offset)
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    one = pl.alloc_outputs(shape, n_p, n_a, n_r + 2, tdt)
+    ws1 = pl.alloc_workspace(vb.vector_compress_workspace_bytes(shape, n_p, n_a))
+    vb.vector_compress_rope(shape, rope, dev["q_win"], dev["k"], dev["v"], dev["w_cal"], n_p, n_a, one.score, one.eps, one.tier,
+                            one.idx_retain, one.idx_approx, one.k_ret, one.v_ret, one.k_apx, n_r + 2, ws1)
+    three = pl.alloc_outputs(shape, n_p, n_a, n_r + 2, tdt)
+    ws3 = pl.alloc_workspace(vb.vector_workspace_bytes(shape, n_p, n_a, 1))
+    vb.vector_score_residual_rope(shape, dev["q_win"], dev["k"], dev["v"], dev["w_cal"], rope, three.score, three.eps, ws3)
+    vb.vector_route(H, n, three.score, three.eps, n_p, n_a, three.tier, three.idx_retain, three.idx_approx, ws3)
+    vb.vector_compact(shape, dev["k"], dev["v"], three.idx_retain, three.idx_approx, n_r, n_a, three.k_ret, three.v_ret, three.k_apx, n_r + 2)
+    torch.cuda.synchronize()
+    for f in ("score", "eps", "tier", "idx_retain", "idx_approx", "k_ret", "v_ret", "k_apx"):
+        a, b = getattr(one, f), getattr(three, f)
+        if a.dtype == torch.bfloat16:
+            a, b = a.view(torch.int16), b.view(torch.int16)
+        assert torch.equal(a, b), f
+    wide = {x: dg.widen(getattr(li, x)) for x in ("k", "v", "w_cal")}
+    close(one.eps.cpu().numpy(), vo.residual(wide["k"], wide["v"], wide["w_cal"], pos=li.extra["pos"], inv_freq=li.extra["inv_freq"],
+                                             interleaved=interleaved), "eps (one call)")
+    tier, idx_r, idx_a = vo.route(one.score.cpu().numpy(), one.eps.cpu().numpy(), n_p, n_a)
+    assert np.array_equal(one.tier.cpu().numpy(), tier)
+    assert np.array_equal(one.idx_retain.cpu().numpy(), idx_r) and np.array_equal(one.idx_approx.cpu().numpy(), idx_a)
+    rk, rv, ra = vo.compact(li.k, li.v, idx_r, idx_a)
+    assert np.array_equal(pl.to_host(one.k_ret)[:, :n_r], rk) and np.array_equal(pl.to_host(one.v_ret)[:, :n_r], rv)
+    assert np.array_equal(pl.to_host(one.k_apx)[:, :n_a], ra)
+
+
 @pytest.mark.parametrize("d,B,Hq,Hkv,n_r,n_a,interleaved", [
     (128, 2, 8, 2, 300, 200, False),
     (128, 1, 4, 4, 0, 65, True),
