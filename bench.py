@@ -518,7 +518,34 @@ def run_extras(vb, dg, pl, torch, np, dev, cfg, shape, layer, out, ws, n_p, n_a)
                                ob["score"][b * H * n2:], ob["eps"][b * H * n2:], ob["tier"][b * H * n2:], ob["ir"][b * H * nr2:],
                                ob["ia"][b * H * napx2:], ob["kr"][b * H * nr2:], ob["vr"][b * H * nr2:], ob["ka"][b * H * napx2:], nr2, wsb)
     res["compress_8x8192_one_call_each_us"] = per_call_us(per_sequence, 10)
-    del kb, vbt, ob, keep_1, one_b
+    # eight prompts of different lengths in the same buffers (one set of launches over their
+    # parameter tables), against one vector_compress call per prompt
+    lens = [8192, 3000, 6100, 4096, 7000, 2048, 5000, 7500]
+    cnt = [vb.vector_budget_counts_frac(m, c2.f_retain, c2.f_approx) for m in lens]
+    np_u, na_u = [c[0] for c in cnt], [c[1] for c in cnt]
+    nr_u = [p_ - a_ for p_, a_ in zip(np_u, na_u)]
+    ubatch, keep_u = vb.make_batch(lens, np_u, na_u, nr_u)
+    wsu = pl.alloc_workspace(vb.vector_compress_batch_workspace_bytes(shape2, ubatch), dev)
+    res["compress_batch_8_unequal_us"] = per_call_us(
+        lambda: vb.vector_compress_batch(shape2, ubatch, qb, kb, vbt, layer["w_cal"], ob["score"], ob["eps"], ob["tier"], ob["ir"], ob["ia"],
+                                         ob["kr"], ob["vr"], ob["ka"], wsu), 10)
+    t0s = np.concatenate([[0], np.cumsum(lens)])
+    r0s = np.concatenate([[0], np.cumsum(nr_u)])
+    a0s = np.concatenate([[0], np.cumsum(na_u)])
+    shape_u = pl.shape_of(c2)
+    shape_u.k_stride_head = shape_u.v_stride_head = Bq * n2 * d
+    shape_u.k_stride_tok = shape_u.v_stride_tok = d
+
+    def per_unequal_sequence():
+        for b in range(len(lens)):
+            shape_u.seq_len = lens[b]
+            t0, r0, a0 = int(t0s[b]), int(r0s[b]), int(a0s[b])
+            vb.vector_compress(shape_u, qb[b], kb[:, t0:], vbt[:, t0:], layer["w_cal"], np_u[b], na_u[b],
+                               ob["score"][H * t0:], ob["eps"][H * t0:], ob["tier"][H * t0:], ob["ir"][H * r0:],
+                               ob["ia"][H * a0:], ob["kr"][H * r0:], ob["vr"][H * r0:], ob["ka"][H * a0:], nr_u[b], wsb)
+    res["compress_8_unequal_one_call_each_us"] = per_call_us(per_unequal_sequence, 10)
+    res["compress_8_unequal_tokens"] = int(sum(lens))
+    del kb, vbt, ob, keep_1, one_b, keep_u, ubatch, wsu
     # The same layer shape with attention rows that are nearly uniform (queries scaled to 0.02, every
     # score within a few per cent of 1/n) plus eight sink and eight anti-sink keys: the selection's
     # radix buckets then have to follow the bulk of the scores, not the keys' leading bits.

@@ -215,11 +215,15 @@ VECTOR_API int vector_compress_lse(const vector_shape* shape, const void* q_win,
  * what vector_compress gives for it alone.  Every sequence must satisfy vector_compress's
  * conditions (window <= seq_len[b], n_approx[b] <= n_pool[b] <= seq_len[b],
  * cap_retain[b] >= n_pool[b] - n_approx[b]); everything is validated before the first launch.
- * Consecutive sequences with the same length, counts and capacity share their launches (their heads
- * are stacked into one problem, with the chunking one sequence alone would get, so the results do not
- * change); runs follow each other on `stream` and share ws:
- * vector_compress_batch_workspace_bytes(shape, batch) bytes.  Sort or bucket a batch by length to
- * make the runs long. */
+ * Sequences share their launches, whatever their lengths: consecutive sequences with the same length,
+ * counts and capacity have their heads stacked into one problem; up to 64 consecutive sequences that
+ * differ go through one set of launches in which every workgroup looks up its own sequence's
+ * parameters (which are those vector_compress would compute for it, so the results do not change;
+ * the parameter tables live at the start of ws and are written by small copy launches, nothing is
+ * read from host memory after the call returns).  Parts follow each other on `stream` and share ws:
+ * vector_compress_batch_workspace_bytes(shape, batch) bytes (the sequences of a part each have their
+ * own piece of it).  A sequence with n_pool = 0, or a shape whose G * w query rows need more than one
+ * pair of passes, is taken on its own. */
 typedef struct {
   int32_t batch;
   const int32_t* seq_len;      /* host [batch] */

@@ -57,6 +57,37 @@ int launch_score_residual(const vector_shape& s, const void* q, const void* k, c
                           float* score, float* eps, void* ws, hipStream_t stream, const RopeParams* rope = nullptr,
                           void* route_ws = nullptr, const SeqStack* stack = nullptr, const QueryLse* lse = nullptr);
 
+// A batch of sequences of different lengths through one set of launches.  Every sequence is
+// the one-sequence problem it would be alone (its own shape with explicit strides, pointers to
+// its own blocks, its own workspace), and gets exactly the parameters that call would compute;
+// the parameter blocks go to `tables` (device, ragged_table_bytes(count) bytes) and every
+// workgroup picks its sequence's block (launch head hv: sequence hv / Hkv, head hv % Hkv).
+constexpr int kMaxRaggedSeqs = 64;
+struct RaggedSeq {
+  vector_shape shape;
+  const void *q, *k, *v;
+  float *score, *eps;
+  uint8_t* tier;
+  int32_t *idx_retain, *idx_approx;
+  void *k_ret, *v_ret, *k_apx;
+  int n_pool, n_approx, cap_retain;
+  void *score_ws, *route_ws;
+};
+struct PoolSeq { const float* mass; float* score; int seq_len, n_prefix; void* route_ws; int n_range; };
+size_t ragged_table_bytes(int count);
+// whether the G * w query rows of a KV head go through the two passes at once (a ragged launch needs that)
+bool score_heads_in_one_group(const vector_shape& s);
+size_t route_ragged_table_bytes(int count);
+int launch_score_residual_ragged(const vector_shape& s, const RaggedSeq* seqs, int count, const void* W, void* tables,
+                                 hipStream_t stream);
+int launch_pool_scores_ragged(const PoolSeq* seqs, int count, int n_kv_heads, int pool_kernel, int pool_mode, void* tables,
+                              hipStream_t stream);
+// tables: the part of the table area after the scorer's (ragged_table_bytes - route_ragged_table_bytes from its start)
+int launch_route_compact_ragged(const vector_shape& s, const RaggedSeq* seqs, int count, void* tables, hipStream_t stream);
+// host bytes -> device memory in stream order, as kernel arguments of small copy launches (no
+// host buffer has to outlive the call, and the copies can be captured into a graph)
+int upload_table(const void* host, size_t bytes, void* dev, hipStream_t stream);
+
 int launch_residual_probe(const vector_shape& s, const void* k, const void* v, const void* W, float* eps, int repeat,
                           hipStream_t stream);
 

@@ -27,6 +27,8 @@
 // No workgroup waits for another inside a kernel.
 //
 // gather_rows_kernel: row gather k_ret / v_ret / k_apx by the index lists.
+#include <cstring>
+
 #include "common.hpp"
 #include "launch.hpp"
 
@@ -238,6 +240,7 @@ __device__ __forceinline__ void counts_to_table(int* hist, uint16_t* table, int*
 // ---------------------------------------------------------------------------
 // buckets of the score keys by leading digit (and, POOL, the pooled score itself)
 // ---------------------------------------------------------------------------
+struct BucketParams;
 struct BucketParams {
   const float* src;       // POOL: attention mass [H, n]; otherwise the scores [H, n]
   float* score;           // POOL: output [H, n]
@@ -250,16 +253,32 @@ struct BucketParams {
   const float4* range;    // [H, n_range] (count, sum l, sum l * l) of the mass left by the scorer's workgroups, when n_range > 0
   int n_range;
   float log_ref;          // what the scorer subtracted from log2(mass)
+  const BucketParams* seq_table;   // RAGGED launches: the sequences' parameter blocks, seq_hps heads each
+  int seq_hps;
 };
 
-template <bool POOL>
+// RAGGED launches (several sequences of different lengths at once): launch head hv is head
+// hv % seq_hps of sequence hv / seq_hps, whose parameter block replaces the launch's own
+template <bool RAGGED, typename P>
+__device__ __forceinline__ void take_sequence(P& p, int& h) {
+  if constexpr (RAGGED) {
+    const int seq = h / p.seq_hps;
+    h -= seq * p.seq_hps;
+    p = p.seq_table[seq];
+  }
+}
+
+template <bool POOL, bool RAGGED = false>
 __global__ __launch_bounds__(BT) void route_bucket_kernel(BucketParams p) {
+  int h = blockIdx.y;
+  take_sequence<RAGGED>(p, h);
+  if (RAGGED && (int)blockIdx.x >= p.n_chunks) return;
   __shared__ int hist[kBins];
   __shared__ int row[BT / kWave];
   __shared__ uint32_t sample[BT / kWave][4];
   __shared__ __align__(16) uint32_t stage_key[kStageTokens];
   __shared__ __align__(16) int32_t stage_pos[kStageTokens];
-  const int h = blockIdx.y, chunk = blockIdx.x;
+  const int chunk = blockIdx.x;
   const int lane = threadIdx.x & 63;
   const bool do_buckets = p.table != nullptr;
   DigitMap map = {0u, 21};
@@ -694,6 +713,7 @@ __device__ __forceinline__ void ordered_emit(ClsFn load_cls, EmitFn emit, int be
   }
 }
 
+struct RouteParams;
 struct RouteParams {
   const float* score; const float* eps;
   int n, n_pool, n_approx, n_heads;
@@ -707,13 +727,19 @@ struct RouteParams {
   uint8_t* tier; int32_t* idx_retain; int32_t* idx_approx;
   int32_t* pool_idx; uint32_t* pool_key;
   const uint32_t* map;             // [H, 2]: the digit map (lowq, shift) of the head's score buckets
+  const RouteParams* seq_table;        // RAGGED launches: the sequences' parameter blocks, seq_hps heads each
+  int seq_hps;
 };
 
 // Step 1: the pool is the n_pool tokens of highest score
+template <bool RAGGED>
 __global__ __launch_bounds__(ST) void route_pool_kernel(RouteParams p) {
+  int h = blockIdx.y;
+  take_sequence<RAGGED>(p, h);
+  if (RAGGED && (int)blockIdx.x >= p.n_chunks) return;
   __shared__ SelectShared sh;
   extern __shared__ __align__(16) unsigned char dyn_lds[];
-  const int h = blockIdx.y, chunk = blockIdx.x;
+  const int chunk = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const float* sc = p.score + (size_t)h * p.n;
   const float* ep = p.eps + (size_t)h * p.n;
@@ -861,10 +887,14 @@ __global__ __launch_bounds__(ST) void route_pool_kernel(RouteParams p) {
 }
 
 // Step 3: inside the pool, the n_approx tokens of lowest residual lose their value
+template <bool RAGGED>
 __global__ __launch_bounds__(ST) void route_split_kernel(RouteParams p) {
+  int h = blockIdx.y;
+  take_sequence<RAGGED>(p, h);
+  if (RAGGED && (int)blockIdx.x >= p.n_slices) return;
   __shared__ SelectShared sh;
   extern __shared__ __align__(16) unsigned char dyn_lds[];
-  const int h = blockIdx.y, slice = blockIdx.x;
+  const int slice = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int m = p.n_pool;
   const int32_t* pidx = p.pool_idx + (size_t)h * p.pool_stride;
@@ -999,6 +1029,7 @@ __global__ __launch_bounds__(256) void route_evict_all_kernel(uint8_t* __restric
 // ---------------------------------------------------------------------------
 // compaction: one 16-byte piece per thread, P pieces per row
 // ---------------------------------------------------------------------------
+struct GatherParams;
 struct GatherParams {
   const unsigned char* k; const unsigned char* v;
   int64_t k_sh, k_st, v_sh, v_st;          // byte strides
@@ -1007,10 +1038,15 @@ struct GatherParams {
   const int32_t* idx_retain; const int32_t* idx_approx;
   int n_retain, n_approx, cap_retain, row_bytes, n;
   unsigned char* k_ret; unsigned char* v_ret; unsigned char* k_apx;
+  const GatherParams* seq_table;               // RAGGED launches: the sequences' parameter blocks, seq_hps heads each
+  int seq_hps;
 };
 
+template <bool RAGGED>
 __global__ __launch_bounds__(256) void gather_rows_kernel(GatherParams p) {
-  const int h = blockIdx.y, seg = blockIdx.z;       // seg 0: k_ret, 1: v_ret, 2: k_apx
+  int h = blockIdx.y;
+  take_sequence<RAGGED>(p, h);
+  const int seg = blockIdx.z;                       // seg 0: k_ret, 1: v_ret, 2: k_apx
   const int pieces = p.row_bytes / 16;
   const int rows = (seg == 2) ? p.n_approx : p.n_retain;
   const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -1074,6 +1110,8 @@ void fill_bucket_params(BucketParams& bp, const RouteLayout& L, void* route_ws) 
   bp.range = w8 ? reinterpret_cast<const float4*>(w8 + L.off_range) : nullptr;
   bp.n_range = 0;
   bp.log_ref = 0.f;
+  bp.seq_table = nullptr;
+  bp.seq_hps = 0;
   bp.chunk_tokens = L.chunk_tokens;
   bp.n_chunks = L.n_chunks;
 }
@@ -1087,29 +1125,21 @@ void* route_mass_range(void* route_ws, int n_kv_heads) {
   return reinterpret_cast<unsigned char*>(route_ws) + route_layout(n_kv_heads, 1, 0).off_range;
 }
 
-int launch_pool_scores(const float* mass, float* score, int n_kv_heads, int seq_len, int n_prefix, int pool_kernel, int pool_mode,
-                       void* route_ws, int n_range, hipStream_t stream) {
-  if (n_range < 0 || n_range > route_mass_range_slots(seq_len)) return VECTOR_ERR_ARG;
-  const RouteLayout L = route_layout(n_kv_heads, seq_len, 0);      // the bucket areas do not depend on the pool size
+namespace {
+BucketParams pool_bucket_params(const float* mass, float* score, int n_kv_heads, int seq_len, int n_prefix, int pool_kernel,
+                                int pool_mode, void* route_ws, int n_range, RouteLayout& L) {
+  L = route_layout(n_kv_heads, seq_len, 0);      // the bucket areas do not depend on the pool size
   BucketParams bp;
   bp.src = mass; bp.score = score; bp.n = seq_len; bp.n_prefix = n_prefix; bp.kernel = pool_kernel; bp.take_max = pool_mode == VECTOR_POOL_MAX;
   fill_bucket_params(bp, L, route_ws);
   bp.n_range = route_ws ? n_range : 0;
   bp.log_ref = -log2f((float)(n_prefix > 0 ? n_prefix : 1));     // as in the scorer's second pass
-  VEC_LAUNCH(K_POOL, route_bucket_kernel<true>, dim3(L.n_chunks, n_kv_heads), dim3(BT), 0, stream, bp);
-  VEC_HIP(hipGetLastError());
-  return VECTOR_OK;
+  return bp;
 }
 
-int launch_route(int n_kv_heads, int seq_len, const float* score, const float* eps, int n_pool, int n_approx,
-                 uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx, void* ws, bool have_buckets, hipStream_t stream) {
-  if (n_pool == 0) {
-    const size_t total = (size_t)n_kv_heads * seq_len;
-    VEC_LAUNCH(K_ROUTE, route_evict_all_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, tier, total);
-    VEC_HIP(hipGetLastError());
-    return VECTOR_OK;
-  }
-  const RouteLayout L = route_layout(n_kv_heads, seq_len, n_pool);
+RouteParams route_params(int n_kv_heads, int seq_len, const float* score, const float* eps, int n_pool, int n_approx, uint8_t* tier,
+                         int32_t* idx_retain, int32_t* idx_approx, void* ws, RouteLayout& L) {
+  L = route_layout(n_kv_heads, seq_len, n_pool);
   unsigned char* w8 = reinterpret_cast<unsigned char*>(ws);
   RouteParams p;
   p.score = score; p.eps = eps; p.n = seq_len; p.n_pool = n_pool; p.n_approx = n_approx; p.n_heads = n_kv_heads;
@@ -1125,27 +1155,12 @@ int launch_route(int n_kv_heads, int seq_len, const float* score, const float* e
   p.pool_idx = reinterpret_cast<int32_t*>(w8 + L.off_idx);
   p.pool_key = reinterpret_cast<uint32_t*>(w8 + L.off_key);
   p.tier = tier; p.idx_retain = idx_retain; p.idx_approx = idx_approx;
-  const size_t lds = (size_t)kCandCap * 8;
-  VEC_HIP(set_max_lds(reinterpret_cast<const void*>(route_pool_kernel), lds));
-  VEC_HIP(set_max_lds(reinterpret_cast<const void*>(route_split_kernel), lds));
-  const bool t_ = timing_enabled();
-  if (t_) timing_begin(K_ROUTE, stream);             // the launches count as one routing step
-  if (!have_buckets) {
-    BucketParams bp;
-    bp.src = score; bp.score = nullptr; bp.n = seq_len; bp.n_prefix = seq_len; bp.kernel = 1;
-    fill_bucket_params(bp, L, ws);
-    hipLaunchKernelGGL(route_bucket_kernel<false>, dim3(L.n_chunks, n_kv_heads), dim3(BT), 0, stream, bp);
-  }
-  hipLaunchKernelGGL(route_pool_kernel, dim3(L.n_chunks, n_kv_heads), dim3(ST), lds, stream, p);
-  hipLaunchKernelGGL(route_split_kernel, dim3(p.n_slices, n_kv_heads), dim3(ST), lds, stream, p);
-  if (t_) timing_end(K_ROUTE, stream);
-  VEC_HIP(hipGetLastError());
-  return VECTOR_OK;
+  p.seq_table = nullptr; p.seq_hps = 0;
+  return p;
 }
 
-int launch_compact(const vector_shape& s, const void* k, const void* v, const int32_t* idx_retain,
-                   const int32_t* idx_approx, int n_retain, int n_approx, void* k_ret, void* v_ret, void* k_apx,
-                   int cap_retain, hipStream_t stream, const SeqStack* stack) {
+GatherParams gather_params(const vector_shape& s, const void* k, const void* v, const int32_t* idx_retain, const int32_t* idx_approx,
+                           int n_retain, int n_approx, void* k_ret, void* v_ret, void* k_apx, int cap_retain, const SeqStack* stack) {
   const int esz = (s.dtype == VECTOR_BF16) ? 2 : 4;
   GatherParams p;
   p.k = reinterpret_cast<const unsigned char*>(k);
@@ -1165,12 +1180,165 @@ int launch_compact(const vector_shape& s, const void* k, const void* v, const in
   p.k_ret = reinterpret_cast<unsigned char*>(k_ret);
   p.v_ret = reinterpret_cast<unsigned char*>(v_ret);
   p.k_apx = reinterpret_cast<unsigned char*>(k_apx);
+  p.seq_table = nullptr; p.seq_hps = 0;
+  return p;
+}
+
+unsigned gather_grid_x(const GatherParams& p) {
   const int pieces = p.row_bytes / 16;
-  const int max_rows = n_retain > n_approx ? n_retain : n_approx;
-  if (max_rows == 0) return VECTOR_OK;
-  const int64_t threads = (int64_t)max_rows * pieces;
-  dim3 grid((unsigned)((threads + 255) / 256), s.n_kv_heads, 3);
-  VEC_LAUNCH(K_GATHER, gather_rows_kernel, grid, dim3(256), 0, stream, p);
+  const int max_rows = p.n_retain > p.n_approx ? p.n_retain : p.n_approx;
+  return (unsigned)(((int64_t)max_rows * pieces + 255) / 256);
+}
+constexpr size_t kSelectLds = (size_t)kCandCap * 8;
+}  // namespace
+
+int launch_pool_scores(const float* mass, float* score, int n_kv_heads, int seq_len, int n_prefix, int pool_kernel, int pool_mode,
+                       void* route_ws, int n_range, hipStream_t stream) {
+  if (n_range < 0 || n_range > route_mass_range_slots(seq_len)) return VECTOR_ERR_ARG;
+  RouteLayout L;
+  const BucketParams bp = pool_bucket_params(mass, score, n_kv_heads, seq_len, n_prefix, pool_kernel, pool_mode, route_ws, n_range, L);
+  VEC_LAUNCH(K_POOL, route_bucket_kernel<true>, dim3(L.n_chunks, n_kv_heads), dim3(BT), 0, stream, bp);
+  VEC_HIP(hipGetLastError());
+  return VECTOR_OK;
+}
+
+int launch_route(int n_kv_heads, int seq_len, const float* score, const float* eps, int n_pool, int n_approx,
+                 uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx, void* ws, bool have_buckets, hipStream_t stream) {
+  if (n_pool == 0) {
+    const size_t total = (size_t)n_kv_heads * seq_len;
+    VEC_LAUNCH(K_ROUTE, route_evict_all_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, tier, total);
+    VEC_HIP(hipGetLastError());
+    return VECTOR_OK;
+  }
+  RouteLayout L;
+  const RouteParams p = route_params(n_kv_heads, seq_len, score, eps, n_pool, n_approx, tier, idx_retain, idx_approx, ws, L);
+  VEC_HIP(set_max_lds(reinterpret_cast<const void*>(route_pool_kernel<false>), kSelectLds));
+  VEC_HIP(set_max_lds(reinterpret_cast<const void*>(route_split_kernel<false>), kSelectLds));
+  const bool t_ = timing_enabled();
+  if (t_) timing_begin(K_ROUTE, stream);             // the launches count as one routing step
+  if (!have_buckets) {
+    BucketParams bp;
+    bp.src = score; bp.score = nullptr; bp.n = seq_len; bp.n_prefix = seq_len; bp.kernel = 1; bp.take_max = 0;
+    fill_bucket_params(bp, L, ws);
+    hipLaunchKernelGGL(route_bucket_kernel<false>, dim3(L.n_chunks, n_kv_heads), dim3(BT), 0, stream, bp);
+  }
+  hipLaunchKernelGGL(route_pool_kernel<false>, dim3(L.n_chunks, n_kv_heads), dim3(ST), kSelectLds, stream, p);
+  hipLaunchKernelGGL(route_split_kernel<false>, dim3(p.n_slices, n_kv_heads), dim3(ST), kSelectLds, stream, p);
+  if (t_) timing_end(K_ROUTE, stream);
+  VEC_HIP(hipGetLastError());
+  return VECTOR_OK;
+}
+
+int launch_compact(const vector_shape& s, const void* k, const void* v, const int32_t* idx_retain,
+                   const int32_t* idx_approx, int n_retain, int n_approx, void* k_ret, void* v_ret, void* k_apx,
+                   int cap_retain, hipStream_t stream, const SeqStack* stack) {
+  const GatherParams p = gather_params(s, k, v, idx_retain, idx_approx, n_retain, n_approx, k_ret, v_ret, k_apx, cap_retain, stack);
+  const unsigned gx = gather_grid_x(p);
+  if (gx == 0) return VECTOR_OK;
+  VEC_LAUNCH(K_GATHER, gather_rows_kernel<false>, dim3(gx, s.n_kv_heads, 3), dim3(256), 0, stream, p);
+  VEC_HIP(hipGetLastError());
+  return VECTOR_OK;
+}
+
+// ---------------------------------------------------------------------------
+// several sequences of different lengths in one set of launches
+// ---------------------------------------------------------------------------
+size_t route_ragged_table_bytes(int count) {
+  return align_up(sizeof(BucketParams) * count, 256) + align_up(sizeof(RouteParams) * count, 256) +
+         align_up(sizeof(GatherParams) * count, 256);
+}
+
+int launch_pool_scores_ragged(const PoolSeq* seqs, int count, int n_kv_heads, int pool_kernel, int pool_mode, void* tables,
+                              hipStream_t stream) {
+  if (count < 1 || count > kMaxRaggedSeqs) return VECTOR_ERR_ARG;
+  BucketParams host[kMaxRaggedSeqs];
+  unsigned gx = 0;
+  for (int b = 0; b < count; ++b) {
+    if (!seqs[b].route_ws || seqs[b].n_range < 0 || seqs[b].n_range > route_mass_range_slots(seqs[b].seq_len)) return VECTOR_ERR_ARG;
+    RouteLayout L;
+    host[b] = pool_bucket_params(seqs[b].mass, seqs[b].score, n_kv_heads, seqs[b].seq_len, seqs[b].n_prefix, pool_kernel, pool_mode,
+                                 seqs[b].route_ws, seqs[b].n_range, L);
+    if ((unsigned)L.n_chunks > gx) gx = (unsigned)L.n_chunks;
+  }
+  const int rc = upload_table(host, sizeof(BucketParams) * count, tables, stream);
+  if (rc != VECTOR_OK) return rc;
+  BucketParams lp = host[0];
+  lp.seq_table = reinterpret_cast<const BucketParams*>(tables);
+  lp.seq_hps = n_kv_heads;
+  auto kernel = route_bucket_kernel<true, true>;
+  VEC_LAUNCH(K_POOL, kernel, dim3(gx, (unsigned)count * n_kv_heads), dim3(BT), 0, stream, lp);
+  VEC_HIP(hipGetLastError());
+  return VECTOR_OK;
+}
+
+int launch_route_compact_ragged(const vector_shape& s, const RaggedSeq* seqs, int count, void* tables, hipStream_t stream) {
+  if (count < 1 || count > kMaxRaggedSeqs) return VECTOR_ERR_ARG;
+  RouteParams rhost[kMaxRaggedSeqs];
+  GatherParams ghost[kMaxRaggedSeqs];
+  unsigned g_pool = 0, g_split = 0, g_gather = 0;
+  for (int b = 0; b < count; ++b) {
+    const RaggedSeq& q = seqs[b];
+    if (q.n_pool < 1) return VECTOR_ERR_ARG;               // nothing kept: that sequence goes through launch_route on its own
+    RouteLayout L;
+    rhost[b] = route_params(s.n_kv_heads, q.shape.seq_len, q.score, q.eps, q.n_pool, q.n_approx, q.tier, q.idx_retain, q.idx_approx,
+                            q.route_ws, L);
+    ghost[b] = gather_params(q.shape, q.k, q.v, q.idx_retain, q.idx_approx, q.n_pool - q.n_approx, q.n_approx, q.k_ret, q.v_ret, q.k_apx,
+                             q.cap_retain, nullptr);
+    if ((unsigned)rhost[b].n_chunks > g_pool) g_pool = (unsigned)rhost[b].n_chunks;
+    if ((unsigned)rhost[b].n_slices > g_split) g_split = (unsigned)rhost[b].n_slices;
+    const unsigned gg = gather_grid_x(ghost[b]);
+    if (gg > g_gather) g_gather = gg;
+  }
+  unsigned char* t8 = reinterpret_cast<unsigned char*>(tables) + align_up(sizeof(BucketParams) * count, 256);
+  unsigned char* rt = t8;
+  unsigned char* gt = t8 + align_up(sizeof(RouteParams) * count, 256);
+  int rc = upload_table(rhost, sizeof(RouteParams) * count, rt, stream);
+  if (rc == VECTOR_OK) rc = upload_table(ghost, sizeof(GatherParams) * count, gt, stream);
+  if (rc != VECTOR_OK) return rc;
+  RouteParams rp = rhost[0];
+  rp.seq_table = reinterpret_cast<const RouteParams*>(rt);
+  rp.seq_hps = s.n_kv_heads;
+  GatherParams gp = ghost[0];
+  gp.seq_table = reinterpret_cast<const GatherParams*>(gt);
+  gp.seq_hps = s.n_kv_heads;
+  const unsigned heads = (unsigned)count * s.n_kv_heads;
+  VEC_HIP(set_max_lds(reinterpret_cast<const void*>(route_pool_kernel<true>), kSelectLds));
+  VEC_HIP(set_max_lds(reinterpret_cast<const void*>(route_split_kernel<true>), kSelectLds));
+  const bool t_ = timing_enabled();
+  if (t_) timing_begin(K_ROUTE, stream);
+  hipLaunchKernelGGL(route_pool_kernel<true>, dim3(g_pool, heads), dim3(ST), kSelectLds, stream, rp);
+  hipLaunchKernelGGL(route_split_kernel<true>, dim3(g_split, heads), dim3(ST), kSelectLds, stream, rp);
+  if (t_) timing_end(K_ROUTE, stream);
+  VEC_HIP(hipGetLastError());
+  if (g_gather > 0) {
+    VEC_LAUNCH(K_GATHER, gather_rows_kernel<true>, dim3(g_gather, heads, 3), dim3(256), 0, stream, gp);
+    VEC_HIP(hipGetLastError());
+  }
+  return VECTOR_OK;
+}
+
+// ---------------------------------------------------------------------------
+// parameter tables: host bytes to device memory as the arguments of small copy launches
+// ---------------------------------------------------------------------------
+namespace {
+constexpr int kBlobBytes = 3584;
+struct Blob { uint4 w[kBlobBytes / 16]; };
+__global__ __launch_bounds__(256) void table_copy_kernel(Blob blob, uint4* dst, int words) {
+  for (int i = threadIdx.x; i < words; i += 256) dst[i] = blob.w[i];
+}
+}  // namespace
+
+int upload_table(const void* host, size_t bytes, void* dev, hipStream_t stream) {
+  if (!host || !dev || (reinterpret_cast<uintptr_t>(dev) & 15u)) return VECTOR_ERR_ARG;
+  const unsigned char* src = reinterpret_cast<const unsigned char*>(host);
+  unsigned char* dst = reinterpret_cast<unsigned char*>(dev);
+  for (size_t off = 0; off < bytes; off += kBlobBytes) {
+    const size_t part = bytes - off < (size_t)kBlobBytes ? bytes - off : (size_t)kBlobBytes;
+    Blob blob;
+    memset(&blob, 0, sizeof(blob));
+    memcpy(&blob, src + off, part);
+    hipLaunchKernelGGL(table_copy_kernel, dim3(1), dim3(256), 0, stream, blob, reinterpret_cast<uint4*>(dst + off), (int)((part + 15) / 16));
+  }
   VEC_HIP(hipGetLastError());
   return VECTOR_OK;
 }

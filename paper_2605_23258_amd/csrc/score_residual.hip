@@ -57,15 +57,32 @@ struct PassParams {
   float2* part;         // [Hkv, R_pad, n_chunks]  (max, sum-exp), log2 domain
   float* mass;          // [Hkv, n]
   float* eps;           // [Hkv, n]
-  float4* range;        // [Hkv, gridDim.x] or null: every workgroup of pass 2 leaves, over the prefix columns
+  float4* range;        // [Hkv, range_stride] or null: every workgroup of pass 2 leaves, over the prefix columns
                         // it stored with a positive mass m, their count and the sums of l and l * l, where
                         // l = log2(m) - log_ref; the routing's bucket launch turns them into the head's
                         // typical score range
+  int range_stride;     // entries of `range` per head (the second pass's workgroups per head)
+  // Several sequences of different lengths in one launch (template flag RAGGED): the launch's
+  // own parameters only say where the sequences' parameter blocks lie; launch head hv belongs
+  // to sequence hv / seq_hps and is its head hv % seq_hps, and a workgroup whose chunk
+  // index lies beyond its sequence's chunks leaves at once.
+  const PassParams* seq_table;
+  int seq_hps;
   const float* lse;     // null, or the log-sum-exp (natural log, logits scaled by 1/sqrt(d)) of every query row,
   int64_t lse_sh;       // row r of query head hq at lse[hq * lse_sh + r]: then pass 2 needs no pass 1
   float log_ref;        // log2 of the mean mass of a prefix column, -log2(n_prefix): keeps l small
   int repeat;           // probe kernels only: times each tile's arithmetic is run on the same registers
 };
+
+// RAGGED launches: swap in the parameters of the sequence this workgroup belongs to
+template <bool RAGGED>
+__device__ __forceinline__ void take_sequence(PassParams& p, int& h) {
+  if constexpr (RAGGED) {
+    const int seq = h / p.seq_hps;
+    h -= seq * p.seq_hps;
+    p = p.seq_table[seq];
+  }
+}
 
 // element offset of a launch head's keys (or values), and the KV head whose W it uses
 __device__ __forceinline__ int64_t head_offset(const PassParams& p, int h, int64_t seq_stride, int64_t head_stride) {
@@ -147,8 +164,11 @@ __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(
 // ---------------------------------------------------------------------------
 // pass 1: per-row softmax statistics over a chunk of tokens
 // ---------------------------------------------------------------------------
-template <typename T, int D, int NT, int NS>     // NS subtiles of 32 tokens per wave tile
+template <typename T, int D, int NT, int NS, bool RAGGED = false>     // NS subtiles of 32 tokens per wave tile
 __global__ __launch_bounds__(NT) void score_stats_kernel(PassParams p) {
+  int h = blockIdx.y;
+  take_sequence<RAGGED>(p, h);
+  if (RAGGED && (int)blockIdx.x >= p.n_chunks) return;
   using TL = Tile<T, D>;
   constexpr int NW = NT / kWave;
   constexpr int TW = 32 * NS;                    // tokens per wave tile
@@ -156,7 +176,7 @@ __global__ __launch_bounds__(NT) void score_stats_kernel(PassParams p) {
   unsigned char* q_lds = smem;
   float2* st_lds = reinterpret_cast<float2*>(smem + (size_t)p.R_pad * TL::kLdsStride);   // [NW][NRB][64]
 
-  const int h = blockIdx.y, chunk = blockIdx.x;
+  const int chunk = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l31 = lane & 31;
   const int nrb = p.R_pad / 32;
 
@@ -321,8 +341,11 @@ __global__ __launch_bounds__(NT) void score_stats_kernel(PassParams p) {
 constexpr int kV2Threads = 512;
 constexpr int kV2TileTokens = 64;
 
-template <typename T, int D, int NRB>
+template <typename T, int D, int NRB, bool RAGGED = false>
 __global__ __launch_bounds__(kV2Threads) void score_stats_tiles_kernel(PassParams p) {
+  int h = blockIdx.y;
+  take_sequence<RAGGED>(p, h);
+  if (RAGGED && (int)blockIdx.x >= p.n_chunks) return;
   using TL = Tile<T, D>;
   constexpr int NT = kV2Threads;
   constexpr int NW = NT / kWave;
@@ -335,7 +358,7 @@ __global__ __launch_bounds__(kV2Threads) void score_stats_tiles_kernel(PassParam
   constexpr int kBufBytes = kStepTokens * TL::kLdsStride;
   extern __shared__ __align__(16) unsigned char smem[];
 
-  const int h = blockIdx.y, chunk = blockIdx.x;
+  const int chunk = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l31 = lane & 31;
   const int rb = wave % NRB, tg = wave / NRB;
   const T* k_head = reinterpret_cast<const T*>(p.k) + head_offset(p, h, p.k_sb, p.k_sh);
@@ -595,8 +618,11 @@ __device__ __forceinline__ void load_v_subtile(chunk_t* vf, const T* v_head, int
 // holds (no further loads), to time the contraction code with memory out of the picture.
 // ROPE: the keys are cached after rotary position embedding; the residual un-rotates them
 // (the scores use them as cached).
-template <typename T, int D, int NT, bool DO_MASS, bool DO_RES, bool PROBE = false, bool ROPE = false>
+template <typename T, int D, int NT, bool DO_MASS, bool DO_RES, bool PROBE = false, bool ROPE = false, bool RAGGED = false>
 __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopeParams rp) {
+  int h = blockIdx.y;
+  take_sequence<RAGGED>(p, h);
+  if (RAGGED && (int)blockIdx.x * p.tokens_per_chunk >= p.n) return;
   using TL = Tile<T, D>;
   constexpr int NW = NT / kWave;
   constexpr int JB = TL::JB;
@@ -610,7 +636,7 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
   off += DO_RES ? (size_t)D * TL::kLdsStride : 0;
   float2* turns_lds = reinterpret_cast<float2*>(smem + off);                 // ROPE: [D/2] rotary frequencies (hi, lo)
 
-  const int h = blockIdx.y, chunk = blockIdx.x;
+  const int chunk = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l31 = lane & 31;
   const int nrb = p.R_pad / 32;
 
@@ -948,7 +974,7 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
       float a = 0.f, b = 0.f, c = 0.f;
 #pragma unroll
       for (int w = 0; w < NW; ++w) { a += part[3 * w]; b += part[3 * w + 1]; c += part[3 * w + 2]; }
-      p.range[(size_t)h * gridDim.x + blockIdx.x] = make_float4(a, b, c, 0.f);
+      p.range[(size_t)h * p.range_stride + chunk] = make_float4(a, b, c, 0.f);
     }
   }
 }
@@ -1013,7 +1039,7 @@ int make_plan(const vector_shape& s, bool do_mass, bool do_res, Plan& plan, int 
   p.threads_per_row = tpr;
   p.c2 = kLog2e / sqrtf((float)D);
   p.inv_R = 1.0f / (float)p.R;
-  p.q_head_rows = p.R; p.q_row0 = 0; p.accumulate = 0; p.range = nullptr; p.log_ref = 0.f; p.lse = nullptr; p.lse_sh = 0;
+  p.q_head_rows = p.R; p.q_row0 = 0; p.accumulate = 0; p.range = nullptr; p.range_stride = 0; p.log_ref = 0.f; p.lse = nullptr; p.lse_sh = 0; p.seq_table = nullptr; p.seq_hps = 0;
   p.k_st = s.k_stride_tok ? s.k_stride_tok : D;
   p.k_sh = s.k_stride_head ? s.k_stride_head : (int64_t)s.seq_len * p.k_st;
   p.v_st = s.v_stride_tok ? s.v_stride_tok : D;
@@ -1042,16 +1068,26 @@ size_t score_workspace_bytes(const vector_shape& s) {
 
 // One pair of passes over the keys for the query rows [q_row0, q_row0 + rows of `g`) of every KV
 // head (g: the shape with the group's query-head count).  accumulate: the column mass is added to
-// what earlier groups left.  The residual rides along when eps is given.
-template <typename T, int D>
-static int run_passes(const SeqStack* stack, const vector_shape& s, const vector_shape& g, int q_row0, bool accumulate, const void* q,
-                      const void* k, const void* v, const void* W, bool do_mass, float* eps, void* ws, hipStream_t stream,
-                      const RopeParams* rope, const QueryLse* lse, float4* range, int* n_range_out, float** mass_out, int* n_prefix_out) {
-  const bool do_res = eps != nullptr;
+// what earlier groups left.  The residual rides along when eps is given.  prepare_passes fills in
+// the parameters, launch_passes enqueues the kernels (RAGGED: one launch for several sequences'
+// parameter blocks, see PassParams::seq_table).
+struct PassLaunch {
   Plan plan;
-  int rc = make_plan<T, D>(g, do_mass, do_res, plan, stack ? stack->heads_per_seq : 0);
+  dim3 grid1, grid2;
+  size_t lds2;
+  bool do_mass, do_res, use_rope;
+  RopeParams rp;
+};
+
+template <typename T, int D>
+static int prepare_passes(const SeqStack* stack, const vector_shape& s, const vector_shape& g, int q_row0, bool accumulate, const void* q,
+                          const void* k, const void* v, const void* W, bool do_mass, float* eps, void* ws, const RopeParams* rope,
+                          const QueryLse* lse, float4* range, PassLaunch& L) {
+  L.do_mass = do_mass;
+  L.do_res = eps != nullptr;
+  int rc = make_plan<T, D>(g, do_mass, L.do_res, L.plan, stack ? stack->heads_per_seq : 0);
   if (rc != VECTOR_OK) return rc;
-  PassParams& p = plan.pp;
+  PassParams& p = L.plan.pp;
   p.q = q; p.k = k; p.v = v; p.W = W; p.eps = eps; p.repeat = 1;
   const int rows_all = (s.n_q_heads / s.n_kv_heads) * s.window;
   p.q_head_rows = rows_all; p.q_row0 = q_row0; p.accumulate = accumulate ? 1 : 0;
@@ -1068,38 +1104,56 @@ static int run_passes(const SeqStack* stack, const vector_shape& s, const vector
   p.part = reinterpret_cast<float2*>(w8);
   w8 += align_up((size_t)s.n_kv_heads * ((s.seq_len + 255) / 256) * rows_all_pad * sizeof(float2), 256);
   p.mass = reinterpret_cast<float*>(w8);
-  if (mass_out) *mass_out = p.mass;
-  if (n_prefix_out) *n_prefix_out = p.n_prefix;
-  RopeParams rp = {};
-  const bool use_rope = rope != nullptr && do_res;         // the scores use the keys as cached
-  if (use_rope) rp = *rope;
-  const size_t lds2 = plan.lds_pass2 + (use_rope ? (D / 2) * sizeof(float2) : 0);
-  if (lds2 > kMaxLdsBytes) return VECTOR_ERR_SHAPE;
+  L.rp = RopeParams{};
+  L.use_rope = rope != nullptr && L.do_res;                // the scores use the keys as cached
+  if (L.use_rope) L.rp = *rope;
+  L.lds2 = L.plan.lds_pass2 + (L.use_rope ? (D / 2) * sizeof(float2) : 0);
+  if (L.lds2 > kMaxLdsBytes) return VECTOR_ERR_SHAPE;
+  L.grid1 = dim3(p.n_chunks, s.n_kv_heads);
+  L.grid2 = dim3((s.seq_len + p.tokens_per_chunk - 1) / p.tokens_per_chunk, s.n_kv_heads);
+  p.range_stride = (int)L.grid2.x;
+  return VECTOR_OK;
+}
 
-  const dim3 grid1(p.n_chunks, s.n_kv_heads);
-  const dim3 grid((s.seq_len + p.tokens_per_chunk - 1) / p.tokens_per_chunk, s.n_kv_heads);
-  if (n_range_out) *n_range_out = (int)grid.x;
-  if (do_mass && !p.lse) {                    // pass 1: the rows' (max, sum-exp); not needed when the caller brings them
-    const int nrb = p.R_pad / 32;
-    if (plan.tiles) {
+// p: the launch's parameters (RAGGED: only seq_table / seq_hps are looked at); L: what decides the
+// kernels and their LDS, the same for every sequence of a ragged launch
+template <typename T, int D, bool RAGGED>
+static int launch_passes(const PassParams& p, const PassLaunch& L, dim3 grid1, dim3 grid2, hipStream_t stream) {
+  if (L.do_mass && !L.plan.pp.lse) {          // pass 1: the rows' (max, sum-exp); not needed when the caller brings them
+    const int nrb = L.plan.pp.R_pad / 32;
+    if (L.plan.tiles) {
       const size_t lds_tiles = stats_tiles_lds(nrb, Tile<T, D>::kLdsStride);
-      void (*k1)(PassParams) = nrb == 8 ? score_stats_tiles_kernel<T, D, 8> : score_stats_tiles_kernel<T, D, 4>;
+      void (*k1)(PassParams) = nrb == 8 ? score_stats_tiles_kernel<T, D, 8, RAGGED> : score_stats_tiles_kernel<T, D, 4, RAGGED>;
       VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k1), lds_tiles));
       VEC_LAUNCH(K_SCORE_STATS, k1, grid1, dim3(kV2Threads), lds_tiles, stream, p);
     } else {
-      auto k1 = score_stats_kernel<T, D, kThreads1, kSub1>;
-      VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k1), plan.lds_stats));
-      VEC_LAUNCH(K_SCORE_STATS, k1, grid1, dim3(kThreads1), plan.lds_stats, stream, p);
+      auto k1 = score_stats_kernel<T, D, kThreads1, kSub1, RAGGED>;
+      VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k1), L.plan.lds_stats));
+      VEC_LAUNCH(K_SCORE_STATS, k1, grid1, dim3(kThreads1), L.plan.lds_stats, stream, p);
     }
   }
   void (*k2)(PassParams, RopeParams);
-  if (do_mass && do_res) k2 = use_rope ? mass_residual_kernel<T, D, kThreads, true, true, false, true> : mass_residual_kernel<T, D, kThreads, true, true>;
-  else if (do_mass) k2 = mass_residual_kernel<T, D, kThreads, true, false>;
-  else k2 = use_rope ? mass_residual_kernel<T, D, kThreads, false, true, false, true> : mass_residual_kernel<T, D, kThreads, false, true>;
-  VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k2), lds2));
-  VEC_LAUNCH(K_MASS_RESIDUAL, k2, grid, dim3(kThreads), lds2, stream, p, rp);
+  if (RAGGED) k2 = mass_residual_kernel<T, D, kThreads, true, true, false, false, RAGGED>;
+  else if (L.do_mass && L.do_res) k2 = L.use_rope ? mass_residual_kernel<T, D, kThreads, true, true, false, true> : mass_residual_kernel<T, D, kThreads, true, true>;
+  else if (L.do_mass) k2 = mass_residual_kernel<T, D, kThreads, true, false>;
+  else k2 = L.use_rope ? mass_residual_kernel<T, D, kThreads, false, true, false, true> : mass_residual_kernel<T, D, kThreads, false, true>;
+  VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k2), L.lds2));
+  VEC_LAUNCH(K_MASS_RESIDUAL, k2, grid2, dim3(kThreads), L.lds2, stream, p, L.rp);
   VEC_HIP(hipGetLastError());
   return VECTOR_OK;
+}
+
+template <typename T, int D>
+static int run_passes(const SeqStack* stack, const vector_shape& s, const vector_shape& g, int q_row0, bool accumulate, const void* q,
+                      const void* k, const void* v, const void* W, bool do_mass, float* eps, void* ws, hipStream_t stream,
+                      const RopeParams* rope, const QueryLse* lse, float4* range, int* n_range_out, float** mass_out, int* n_prefix_out) {
+  PassLaunch L;
+  const int rc = prepare_passes<T, D>(stack, s, g, q_row0, accumulate, q, k, v, W, do_mass, eps, ws, rope, lse, range, L);
+  if (rc != VECTOR_OK) return rc;
+  if (mass_out) *mass_out = L.plan.pp.mass;
+  if (n_prefix_out) *n_prefix_out = L.plan.pp.n_prefix;
+  if (n_range_out) *n_range_out = (int)L.grid2.x;
+  return launch_passes<T, D, false>(L.plan.pp, L, L.grid1, L.grid2, stream);
 }
 
 // Query heads per pair of passes: all G of a KV head when their G * w rows fit the kernels' LDS
@@ -1114,6 +1168,45 @@ static int heads_per_group(const vector_shape& s, bool do_res) {
     if (make_plan<T, D>(g, true, do_res, plan) == VECTOR_OK) return gh;
   }
   return 0;
+}
+
+// Several sequences of different lengths, each with all its query heads in one group and its own
+// score workspace: one pair of passes for all of them, then one pooling launch.
+template <typename T, int D>
+static int run_score_residual_ragged(const vector_shape& s, const RaggedSeq* seqs, int count, const void* W, void* tables,
+                                     hipStream_t stream) {
+  if (count < 1 || count > kMaxRaggedSeqs) return VECTOR_ERR_ARG;
+  PassParams host[kMaxRaggedSeqs];
+  PassLaunch first;
+  unsigned g1 = 0, g2 = 0;
+  for (int b = 0; b < count; ++b) {
+    vector_shape t = seqs[b].shape;
+    if (heads_per_group<T, D>(t, true) != t.n_q_heads / t.n_kv_heads) return VECTOR_ERR_SHAPE;
+    PassLaunch L;
+    float4* range = reinterpret_cast<float4*>(route_mass_range(seqs[b].route_ws, t.n_kv_heads));
+    const int rc = prepare_passes<T, D>(nullptr, t, t, 0, false, seqs[b].q, seqs[b].k, seqs[b].v, W, true, seqs[b].eps, seqs[b].score_ws,
+                                        nullptr, nullptr, range, L);
+    if (rc != VECTOR_OK) return rc;
+    host[b] = L.plan.pp;
+    if (b == 0) first = L;
+    if (L.grid1.x > g1) g1 = L.grid1.x;
+    if (L.grid2.x > g2) g2 = L.grid2.x;
+  }
+  unsigned char* t8 = reinterpret_cast<unsigned char*>(tables);
+  int rc = upload_table(host, sizeof(PassParams) * count, t8, stream);
+  if (rc != VECTOR_OK) return rc;
+  PassParams lp = host[0];
+  lp.seq_table = reinterpret_cast<const PassParams*>(t8);
+  lp.seq_hps = s.n_kv_heads;
+  const unsigned heads = (unsigned)count * s.n_kv_heads;
+  if ((rc = launch_passes<T, D, true>(lp, first, dim3(g1, heads), dim3(g2, heads), stream)) != VECTOR_OK) return rc;
+  // pooling + score-key buckets of every sequence
+  PoolSeq pool[kMaxRaggedSeqs];
+  for (int b = 0; b < count; ++b) {
+    pool[b].mass = host[b].mass; pool[b].score = seqs[b].score; pool[b].seq_len = seqs[b].shape.seq_len;
+    pool[b].n_prefix = host[b].n_prefix; pool[b].route_ws = seqs[b].route_ws; pool[b].n_range = host[b].range_stride;
+  }
+  return launch_pool_scores_ragged(pool, count, s.n_kv_heads, s.pool_kernel, s.pool_mode, t8 + align_up(sizeof(PassParams) * count, 256), stream);
 }
 
 template <typename T, int D>
@@ -1174,6 +1267,30 @@ int launch_score_residual(const vector_shape& s, const void* q, const void* k, c
   } else if (s.dtype == VECTOR_F32) {
     if (s.head_dim == 128) return run_score_residual<float, 128>(stack, s, q, k, v, W, score, eps, ws, stream, rope, route_ws, lse);
     if (s.head_dim == 64) return run_score_residual<float, 64>(stack, s, q, k, v, W, score, eps, ws, stream, rope, route_ws, lse);
+  } else {
+    return VECTOR_ERR_DTYPE;
+  }
+  return VECTOR_ERR_SHAPE;
+}
+
+bool score_heads_in_one_group(const vector_shape& s) {
+  const int G = s.n_q_heads / s.n_kv_heads;
+  if (s.dtype == VECTOR_BF16) return s.head_dim == 128 ? heads_per_group<bf16_t, 128>(s, true) == G : heads_per_group<bf16_t, 64>(s, true) == G;
+  return s.head_dim == 128 ? heads_per_group<float, 128>(s, true) == G : heads_per_group<float, 64>(s, true) == G;
+}
+
+size_t ragged_table_bytes(int count) {
+  return align_up(sizeof(PassParams) * count, 256) + route_ragged_table_bytes(count);
+}
+
+int launch_score_residual_ragged(const vector_shape& s, const RaggedSeq* seqs, int count, const void* W, void* tables,
+                                 hipStream_t stream) {
+  if (s.dtype == VECTOR_BF16) {
+    if (s.head_dim == 128) return run_score_residual_ragged<bf16_t, 128>(s, seqs, count, W, tables, stream);
+    if (s.head_dim == 64) return run_score_residual_ragged<bf16_t, 64>(s, seqs, count, W, tables, stream);
+  } else if (s.dtype == VECTOR_F32) {
+    if (s.head_dim == 128) return run_score_residual_ragged<float, 128>(s, seqs, count, W, tables, stream);
+    if (s.head_dim == 64) return run_score_residual_ragged<float, 64>(s, seqs, count, W, tables, stream);
   } else {
     return VECTOR_ERR_DTYPE;
   }

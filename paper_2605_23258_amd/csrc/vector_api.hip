@@ -4,6 +4,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <algorithm>
+
 #include "../../include/vector.h"
 #include "common.hpp"
 #include "launch.hpp"
@@ -247,18 +249,49 @@ BatchItem batch_item(const vector_shape* s, const vector_batch* bt, int b, int64
 
 }  // namespace
 
+namespace {
+// How the sequences from b0 on are taken together: a run of equal sequences (stacked heads), or a
+// group of sequences of different lengths (one set of launches over their parameter tables), or
+// one sequence on its own.
+enum { PART_SINGLE = 0, PART_STACK, PART_RAGGED };
+struct BatchPart { int kind, count; };
+
+BatchPart next_part(const vector_shape* s, const vector_batch* bt, int b0, bool ragged_ok) {
+  const int run = run_length(s, bt, b0);
+  if (run > 1) return {PART_STACK, run};
+  if (!ragged_ok || bt->n_pool[b0] < 1) return {PART_SINGLE, 1};
+  const int max_count = std::min(vec::kMaxRaggedSeqs, 65535 / s->n_q_heads);
+  int c = 1;
+  while (b0 + c < bt->batch && c < max_count && bt->n_pool[b0 + c] >= 1 && run_length(s, bt, b0 + c) == 1) ++c;
+  return {c > 1 ? PART_RAGGED : PART_SINGLE, c};
+}
+
+size_t seq_workspace_bytes(const vector_shape* s, const vector_batch* bt, int b) {
+  vector_shape t = *s;
+  t.seq_len = bt->seq_len[b];
+  return (vector_compress_workspace_bytes(&t, bt->n_pool[b], bt->n_approx[b]) + 255) / 256 * 256;
+}
+}  // namespace
+
 size_t vector_compress_batch_workspace_bytes(const vector_shape* s, const vector_batch* bt) {
   if (check_batch(s, bt) != VECTOR_OK) return 0;
+  const bool ragged_ok = vec::score_heads_in_one_group(*s);
   size_t need = 0;
   for (int b = 0; b < bt->batch;) {
-    const int run = run_length(s, bt, b);
-    vector_shape t = *s;
-    t.seq_len = bt->seq_len[b];
-    t.n_kv_heads *= run;
-    t.n_q_heads *= run;
-    const size_t one = vector_compress_workspace_bytes(&t, bt->n_pool[b], bt->n_approx[b]);
+    const BatchPart part = next_part(s, bt, b, ragged_ok);
+    size_t one = 0;
+    if (part.kind == PART_RAGGED) {
+      one = (vec::ragged_table_bytes(part.count) + 255) / 256 * 256;
+      for (int i = 0; i < part.count; ++i) one += seq_workspace_bytes(s, bt, b + i);
+    } else {
+      vector_shape t = *s;
+      t.seq_len = bt->seq_len[b];
+      t.n_kv_heads *= part.count;
+      t.n_q_heads *= part.count;
+      one = vector_compress_workspace_bytes(&t, bt->n_pool[b], bt->n_approx[b]);
+    }
     if (one > need) need = one;
-    b += run;
+    b += part.count;
   }
   return need;
 }
@@ -279,25 +312,57 @@ int vector_compress_batch(const vector_shape* s, const vector_batch* bt, const v
   if (total_ret > 0 && (!idx_retain || !k_ret || !v_ret || !aligned16(k_ret) || !aligned16(v_ret))) return VECTOR_ERR_ARG;
   if (total_apx > 0 && (!idx_approx || !k_apx || !aligned16(k_apx))) return VECTOR_ERR_ARG;
   if ((rc = check_ws(ws, ws_bytes, vector_compress_batch_workspace_bytes(s, bt)))) return rc;
-  // One run of equal sequences after the other on the stream, through the one-sequence pass with
-  // the run's heads stacked: the launches follow each other without a host wait, and the workspace
-  // is reused in stream order.
+  // One part after the other on the stream (a run of equal sequences with its heads stacked, a group
+  // of unequal ones over parameter tables, or a single sequence): the launches follow each other
+  // without a host wait, and the workspace is reused in stream order.
   const size_t esz = s->dtype == VECTOR_BF16 ? 2 : 4;
   const int64_t H = s->n_kv_heads, d = s->head_dim;
+  const bool ragged_ok = vec::score_heads_in_one_group(*s);
+  hipStream_t st = (hipStream_t)stream;
   BatchItem it{}, prev{};
-  int run_left = 0;
-  for (int b = 0; b < bt->batch; ++b) {
+  for (int b = 0; b < bt->batch;) {
+    const BatchPart part = next_part(s, bt, b, ragged_ok);
+    if (part.kind == PART_RAGGED) {
+      vec::RaggedSeq seqs[vec::kMaxRaggedSeqs];
+      unsigned char* w8 = reinterpret_cast<unsigned char*>(ws);
+      void* tables = w8;
+      w8 += (vec::ragged_table_bytes(part.count) + 255) / 256 * 256;
+      for (int i = 0; i < part.count; ++i) {
+        const int bi = b + i;
+        it = batch_item(s, bt, bi, total, bi ? &prev : nullptr);
+        prev = it;
+        vec::RaggedSeq& q = seqs[i];
+        q.shape = it.shape;
+        q.q = reinterpret_cast<const unsigned char*>(q_win) + (size_t)bi * s->n_q_heads * s->window * d * esz;
+        q.k = reinterpret_cast<const unsigned char*>(k) + (size_t)(it.tok0 * it.shape.k_stride_tok) * esz;
+        q.v = reinterpret_cast<const unsigned char*>(v) + (size_t)(it.tok0 * it.shape.v_stride_tok) * esz;
+        q.score = score + H * it.tok0; q.eps = eps + H * it.tok0; q.tier = tier + H * it.tok0;
+        q.idx_retain = idx_retain ? idx_retain + H * it.ret0 : nullptr;
+        q.idx_approx = idx_approx ? idx_approx + H * it.apx0 : nullptr;
+        q.k_ret = k_ret ? reinterpret_cast<unsigned char*>(k_ret) + (size_t)(H * it.cap0 * d) * esz : nullptr;
+        q.v_ret = v_ret ? reinterpret_cast<unsigned char*>(v_ret) + (size_t)(H * it.cap0 * d) * esz : nullptr;
+        q.k_apx = k_apx ? reinterpret_cast<unsigned char*>(k_apx) + (size_t)(H * it.apx0 * d) * esz : nullptr;
+        q.n_pool = bt->n_pool[bi]; q.n_approx = bt->n_approx[bi]; q.cap_retain = bt->cap_retain[bi];
+        q.score_ws = w8;
+        q.route_ws = w8 + (vec::score_workspace_bytes(it.shape) + 255) / 256 * 256;
+        w8 += seq_workspace_bytes(s, bt, bi);
+      }
+      if ((rc = vec::launch_score_residual_ragged(*s, seqs, part.count, W, tables, st))) return rc;
+      unsigned char* route_tables = reinterpret_cast<unsigned char*>(tables) + vec::ragged_table_bytes(part.count) -
+                                    vec::route_ragged_table_bytes(part.count);
+      if ((rc = vec::launch_route_compact_ragged(*s, seqs, part.count, route_tables, st))) return rc;
+      b += part.count;
+      continue;
+    }
     it = batch_item(s, bt, b, total, b ? &prev : nullptr);
     prev = it;
-    if (run_left > 0) { --run_left; continue; }          // part of the run launched at its first sequence
-    const int run = run_length(s, bt, b);
-    run_left = run - 1;
+    for (int i = 1; i < part.count; ++i) prev = batch_item(s, bt, b + i, total, &prev);     // the running sums skip over the run
     vec::SeqStack stack;
     stack.heads_per_seq = s->n_kv_heads;
     stack.k_stride_seq = (int64_t)bt->seq_len[b] * it.shape.k_stride_tok;     // ragged token axis: the next sequence follows
     stack.v_stride_seq = (int64_t)bt->seq_len[b] * it.shape.v_stride_tok;
-    it.shape.n_kv_heads *= run;
-    it.shape.n_q_heads *= run;
+    it.shape.n_kv_heads *= part.count;
+    it.shape.n_q_heads *= part.count;
     const unsigned char* kb = reinterpret_cast<const unsigned char*>(k) + (size_t)(it.tok0 * it.shape.k_stride_tok) * esz;
     const unsigned char* vb = reinterpret_cast<const unsigned char*>(v) + (size_t)(it.tok0 * it.shape.v_stride_tok) * esz;
     const unsigned char* qb = reinterpret_cast<const unsigned char*>(q_win) + (size_t)b * s->n_q_heads * s->window * d * esz;
@@ -307,8 +372,9 @@ int vector_compress_batch(const vector_shape* s, const vector_batch* bt, const v
                          k_ret ? reinterpret_cast<unsigned char*>(k_ret) + (size_t)(H * it.cap0 * d) * esz : nullptr,
                          v_ret ? reinterpret_cast<unsigned char*>(v_ret) + (size_t)(H * it.cap0 * d) * esz : nullptr,
                          k_apx ? reinterpret_cast<unsigned char*>(k_apx) + (size_t)(H * it.apx0 * d) * esz : nullptr,
-                         bt->cap_retain[b], ws, ws_bytes, stream, run > 1 ? &stack : nullptr);
+                         bt->cap_retain[b], ws, ws_bytes, stream, part.count > 1 ? &stack : nullptr);
     if (rc) return rc;
+    b += part.count;
   }
   return VECTOR_OK;
 }

@@ -28,6 +28,15 @@ BATCHES = {
     # runs of equal sequences are launched with their heads stacked; a change of capacity alone ends a run
     "bf16_equal_runs": ("cfg2", dict(n_kv_heads=2, n_q_heads=8, window=32), (1024, 1024, 1024, 700, 700, 2048, 2048), (3, 3, 3, 0, 0, 1, 2)),
     "f32_equal_pair": ("cfg1", dict(n_kv_heads=2, n_q_heads=4, window=20), (1000, 1000), (2, 2)),
+    # sequences of different lengths go through one set of launches, each with its own parameter block:
+    # twenty lengths from one tile to several chunks; equal runs between unequal neighbours; more
+    # sequences than one such group takes
+    "bf16_twenty_lengths": ("cfg2", dict(n_kv_heads=2, n_q_heads=8, window=32),
+                            (40, 5000, 333, 2048, 6100, 64, 1500, 4097, 900, 32, 2500, 777, 4096, 128, 3000, 1025, 450, 5500, 70, 2000),
+                            (1, 0, 2, 0, 3, 0, 1, 0, 2, 0, 1, 0, 2, 0, 1, 0, 2, 0, 1, 0)),
+    "bf16_runs_between_unequal": ("cfg2", dict(n_kv_heads=2, n_q_heads=8, window=32), (500, 900, 900, 700, 1200, 1200, 1200, 300, 333),
+                                  (0, 1, 1, 0, 2, 2, 2, 0, 5)),
+    "f32_seventy_short": ("cfg1", dict(n_kv_heads=1, n_q_heads=4, window=20), tuple(64 + 5 * i for i in range(70)), tuple(i % 3 for i in range(70))),
 }
 
 
@@ -125,10 +134,10 @@ def test_compress_batch_against_the_oracle_sequence_by_sequence(name):
         assert flips <= max(2, 0.004 * tier.size), what
 
 
-@pytest.mark.parametrize("name", ["bf16_four_lengths", "bf16_equal_runs"])
+@pytest.mark.parametrize("name", ["bf16_four_lengths", "bf16_equal_runs", "bf16_twenty_lengths", "bf16_runs_between_unequal"])
 def test_compress_batch_equals_one_call_per_sequence(name):
-    """Bit for bit what vector_compress gives for each sequence alone, also where equal sequences
-    share their launches."""
+    """Bit for bit what vector_compress gives for each sequence alone, also where sequences share
+    their launches (equal ones with their heads stacked, unequal ones over parameter tables)."""
     rb = RaggedBatch(name)
     cfg = rb.cfg
     H, d = cfg.n_kv_heads, cfg.head_dim
