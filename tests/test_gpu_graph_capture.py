@@ -101,3 +101,71 @@ def test_decode_step_replays_and_advances_its_length():
         torch.cuda.synchronize()
         assert torch.equal(o, eager[s]), f"replayed step {s}"
     assert torch.equal(lg, le) and torch.equal(kg, ke) and torch.equal(vg, ve)
+
+
+def test_batch_of_unequal_sequences_replays_bit_for_bit():
+    """The batch call ships its per-sequence parameter tables as arguments of copy launches, so a
+    captured call keeps them: replays with other inputs in the same buffers give what the eager
+    call gives."""
+    cfg = dg.scaled(dg.CONFIGS["cfg2"], n_kv_heads=2, n_q_heads=8, window=32)
+    lens = [900, 2500, 333, 1200]
+    H, d = cfg.n_kv_heads, cfg.head_dim
+    counts = [vb.vector_budget_counts_frac(n, cfg.f_retain, cfg.f_approx) for n in lens]
+    n_pool, n_approx = [c[0] for c in counts], [c[1] for c in counts]
+    n_ret = [p - a for p, a in zip(n_pool, n_approx)]
+    shape = pl.shape_of(cfg, seq_len=1)
+    batch, keep = vb.make_batch(lens, n_pool, n_approx, n_ret)
+    ws = pl.alloc_workspace(vb.vector_compress_batch_workspace_bytes(shape, batch))
+    T, R, A = sum(lens), sum(n_ret), sum(n_approx)
+
+    def draw(seed):
+        layers = [wl.make_layer(dg.scaled(cfg, seq_len=n), layer=seed * 10 + b) for b, n in enumerate(lens)]
+        return dict(q=pl.to_device(np.stack([li.q_win for li in layers])), k=pl.to_device(np.concatenate([li.k for li in layers], axis=1)),
+                    v=pl.to_device(np.concatenate([li.v for li in layers], axis=1)), W=pl.to_device(layers[0].w_cal))
+
+    def outputs():
+        return dict(score=torch.full((H * T,), -1.0, device="cuda:0"), eps=torch.full((H * T,), -1.0, device="cuda:0"),
+                    tier=torch.full((H * T,), 9, dtype=torch.uint8, device="cuda:0"),
+                    ir=torch.full((H * R,), -1, dtype=torch.int32, device="cuda:0"), ia=torch.full((H * A,), -1, dtype=torch.int32, device="cuda:0"),
+                    kr=torch.zeros((H * R, d), dtype=torch.bfloat16, device="cuda:0"), vr=torch.zeros((H * R, d), dtype=torch.bfloat16, device="cuda:0"),
+                    ka=torch.zeros((H * A, d), dtype=torch.bfloat16, device="cuda:0"))
+
+    def call(buf, o, stream=None):
+        vb.vector_compress_batch(shape, batch, buf["q"], buf["k"], buf["v"], buf["W"], o["score"], o["eps"], o["tier"], o["ir"], o["ia"],
+                                 o["kr"], o["vr"], o["ka"], ws, stream)
+
+    inputs = [draw(0), draw(1)]
+    buf = {x: t.clone() for x, t in inputs[0].items()}
+    eager = []
+    for inp in inputs:
+        for x in buf:
+            buf[x].copy_(inp[x])
+        ref = outputs()
+        call(buf, ref)
+        torch.cuda.synchronize()
+        eager.append(ref)
+    out = outputs()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call(buf, out, side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call(buf, out, torch.cuda.current_stream())
+    for rep in range(4):
+        inp, ref = inputs[rep % 2], eager[rep % 2]
+        for x in buf:
+            buf[x].copy_(inp[x])
+        out["tier"].fill_(7)
+        ws.zero_()                                      # the tables are rewritten by the replay itself
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name in out:
+            a, b = out[name], ref[name]
+            if a.dtype == torch.bfloat16:
+                a, b = a.view(torch.int16), b.view(torch.int16)
+            assert torch.equal(a, b), f"replay {rep}: {name}"
+    del keep
