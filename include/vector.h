@@ -279,7 +279,7 @@ typedef struct {
  * approximated rows together, logits q . k_t * scale, and
  *   out = sum_ret p_t v_t + sum_apx p_t (k_t . W[h]).
  * q: device [batch, Hq, d]; out: device [batch, Hq, d], same dtype as the cache.
- * Hq / Hkv may be 1 .. 8 (VECTOR_ERR_SHAPE otherwise).
+ * Hq / Hkv may be 1 .. 8, 10, 12 or 16 (VECTOR_ERR_SHAPE otherwise).
  * flags: 0, or VECTOR_DECODE_LITERAL to rebuild v_hat = k . W for every approximated row on
  * the matrix cores before weighting it (bf16 caches only); by default the weighted keys are
  * summed first and W is applied once, (sum p_t k_t) . W, which is the same sum in another

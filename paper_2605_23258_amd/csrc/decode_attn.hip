@@ -927,6 +927,9 @@ int run_decode_g(const vector_cache& c, DecodeParams& p, hipStream_t stream, con
     case 6: return run_decode<T, D, 6>(c, p, stream, rope);
     case 7: return run_decode<T, D, 7>(c, p, stream, rope);
     case 8: return run_decode<T, D, 8>(c, p, stream, rope);
+    case 10: return run_decode<T, D, 10>(c, p, stream, rope);
+    case 12: return run_decode<T, D, 12>(c, p, stream, rope);
+    case 16: return run_decode<T, D, 16>(c, p, stream, rope);
     default: return VECTOR_ERR_SHAPE;
   }
 }

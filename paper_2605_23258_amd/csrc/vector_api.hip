@@ -496,7 +496,7 @@ static int decode_checked(const vector_cache* c, const void* q, float scale, voi
   if (c->batch < 1 || c->batch > 65535 || c->n_kv_heads < 1 || c->n_kv_heads > 65535) return VECTOR_ERR_SHAPE;
   if (c->n_q_heads < c->n_kv_heads || c->n_q_heads % c->n_kv_heads) return VECTOR_ERR_SHAPE;
   const int G = c->n_q_heads / c->n_kv_heads;
-  if (G > 8) return VECTOR_ERR_SHAPE;
+  if (G > 8 && G != 10 && G != 12 && G != 16) return VECTOR_ERR_SHAPE;      // the group sizes the kernels are built for
   if (c->cap_retain < 0 || c->n_approx < 0 || (flags & ~(VECTOR_DECODE_LITERAL | VECTOR_DECODE_OUT_F32)) || !(scale == scale))
     return VECTOR_ERR_ARG;
   if ((flags & VECTOR_DECODE_LITERAL) && (rope || c->dtype != VECTOR_BF16)) return VECTOR_ERR_DTYPE;

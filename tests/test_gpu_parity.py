@@ -206,6 +206,11 @@ DECODE_CASES = [
     ("bf16", 64, 1, 4, 2, 1, 1, 1),
     ("f32", 128, 1, 2, 2, 50, 31, 50),
     ("bf16", 128, 1, 32, 8, 1500, 1400, 1600),
+    # sixteen, twelve and ten query heads per KV head
+    ("bf16", 128, 2, 32, 2, 700, 300, 710),
+    ("bf16", 64, 1, 24, 2, 90, 333, 100),
+    ("f32", 64, 2, 10, 1, 120, 77, 128),
+    ("f32", 128, 1, 16, 1, 65, 40, 70),
 ]
 
 
