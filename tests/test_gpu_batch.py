@@ -36,6 +36,10 @@ BATCHES = {
                             (1, 0, 2, 0, 3, 0, 1, 0, 2, 0, 1, 0, 2, 0, 1, 0, 2, 0, 1, 0)),
     "bf16_runs_between_unequal": ("cfg2", dict(n_kv_heads=2, n_q_heads=8, window=32), (500, 900, 900, 700, 1200, 1200, 1200, 300, 333),
                                   (0, 1, 1, 0, 2, 2, 2, 0, 5)),
+    # counts at their limits inside one ragged part: the whole sequence kept, a pool with no retained
+    # token, nothing kept at all (that sequence is routed on its own), no approximated token
+    "bf16_counts_at_the_limits": ("cfg2", dict(n_kv_heads=2, n_q_heads=8, window=32), (600, 900, 700, 1200, 450), (0, 2, 1, 0, 3),
+                                  ((600, 200), (100, 100), (0, 0), (300, 0), (32, 7))),
     "f32_seventy_short": ("cfg1", dict(n_kv_heads=1, n_q_heads=4, window=20), tuple(64 + 5 * i for i in range(70)), tuple(i % 3 for i in range(70))),
 }
 
@@ -44,12 +48,13 @@ class RaggedBatch:
     """Seeded sequences of one layer, concatenated along the token axis, and their per-sequence sizes."""
 
     def __init__(self, name):
-        base, over, lens, spare = BATCHES[name]
+        base, over, lens, spare = BATCHES[name][:4]
+        given = BATCHES[name][4] if len(BATCHES[name]) > 4 else None
         self.cfg = dg.scaled(dg.CONFIGS[base], **over)
         self.lens = list(lens)
         self.layers = [wl.make_layer(dg.scaled(self.cfg, seq_len=n), layer=b) for b, n in enumerate(lens)]
         self.W = self.layers[0].w_cal                     # one calibrated map for all sequences
-        counts = [vo.budget_counts_frac(n, self.cfg.f_retain, self.cfg.f_approx) for n in lens]
+        counts = given or [vo.budget_counts_frac(n, self.cfg.f_retain, self.cfg.f_approx) for n in lens]
         self.n_pool = [c[0] for c in counts]
         self.n_approx = [c[1] for c in counts]
         self.n_retain = [p - a for p, a in zip(self.n_pool, self.n_approx)]
@@ -134,7 +139,7 @@ def test_compress_batch_against_the_oracle_sequence_by_sequence(name):
         assert flips <= max(2, 0.004 * tier.size), what
 
 
-@pytest.mark.parametrize("name", ["bf16_four_lengths", "bf16_equal_runs", "bf16_twenty_lengths", "bf16_runs_between_unequal"])
+@pytest.mark.parametrize("name", ["bf16_four_lengths", "bf16_equal_runs", "bf16_twenty_lengths", "bf16_runs_between_unequal", "bf16_counts_at_the_limits"])
 def test_compress_batch_equals_one_call_per_sequence(name):
     """Bit for bit what vector_compress gives for each sequence alone, also where sequences share
     their launches (equal ones with their heads stacked, unequal ones over parameter tables)."""
