@@ -804,7 +804,36 @@ __global__ __launch_bounds__(ST) void route_pool_kernel(RouteParams p) {
   const bool high_shared = map.shares_high_bits(d0);
   const int low_bits = high_shared ? map.shift : 32;
   const uint32_t prefix = high_shared ? ((uint32_t)d0 + map.lowq) << map.shift : 0u;
-  {
+  // More candidates than LDS holds usually means a plateau: scores that are all the same number (the
+  // zeros of attention rows that underflow, a constant fill).  One look at the keys tells; then the
+  // threshold is that number, and which of the equal tokens get in follows from the counts alone.
+  bool plateau = false;
+  uint32_t plateau_key = 0u;
+  if (!fits) {
+    uint32_t kmin = 0xffffffffu, kmax = 0u;
+    const int cnt = my_c < p.n_chunks ? sh.seg_count[my_c] : 0;
+    const int src0 = my_c < p.n_chunks ? my_c * p.chunk_tokens + sh.seg_first[my_c] : 0;
+    for (int i0 = 0; i0 < cnt; i0 += tpc * kBatch) {
+      uint32_t ck[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) ck[u] = bkey[src0 + min(i0 + u * tpc + my_sub, cnt - 1)];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) { kmin = min(kmin, ck[u]); kmax = max(kmax, ck[u]); }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o, kWave));
+      kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o, kWave));
+    }
+    if (lane == 0) { sh.row[ROW_GT][wave] = (int)kmin; sh.row[ROW_EQ][wave] = (int)kmax; }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < SW; ++q) { kmin = min(kmin, (uint32_t)sh.row[ROW_GT][q]); kmax = max(kmax, (uint32_t)sh.row[ROW_EQ][q]); }
+    plateau = kmin == kmax;
+    plateau_key = kmin;
+    __syncthreads();                               // the rows are used again below
+  }
+  if (!plateau) {
     const bool live = my_c < p.n_chunks;
     const int cnt = live ? sh.seg_count[my_c] : 0;
     const int src0 = live ? my_c * p.chunk_tokens + sh.seg_first[my_c] : 0;
@@ -837,14 +866,22 @@ __global__ __launch_bounds__(ST) void route_pool_kernel(RouteParams p) {
   VEC_TRACE(3);
   uint32_t thr;
   int quota, base_gt, base_eq;
-  finish_select(
-      list,
-      [&](auto f) {
-        const int cnt = my_c < p.n_chunks ? sh.seg_count[my_c] : 0;
-        const int src0 = my_c < p.n_chunks ? my_c * p.chunk_tokens + sh.seg_first[my_c] : 0;
-        for (int i = my_sub; i < cnt; i += tpc) f(bkey[src0 + i], bpos[src0 + i]);
-      },
-      prefix, low_bits, p.n_pool - above0, begin, gt, sh, thr, quota, base_gt, base_eq);
+  if (plateau) {                                   // uniform
+    thr = plateau_key;
+    quota = p.n_pool - above0;                     // equal keys still to take, lowest token index first
+    base_gt = 0;
+    for (int c = 0; c < chunk; ++c) base_gt += sh.seg_first[c];
+    base_eq = sh.seg_start[chunk];                 // the equal keys of earlier chunks come first
+  } else {
+    finish_select(
+        list,
+        [&](auto f) {
+          const int cnt = my_c < p.n_chunks ? sh.seg_count[my_c] : 0;
+          const int src0 = my_c < p.n_chunks ? my_c * p.chunk_tokens + sh.seg_first[my_c] : 0;
+          for (int i = my_sub; i < cnt; i += tpc) f(bkey[src0 + i], bpos[src0 + i]);
+        },
+        prefix, low_bits, p.n_pool - above0, begin, gt, sh, thr, quota, base_gt, base_eq);
+  }
   VEC_TRACE(4);
 
   // ordered pass over the chunk: tiers, pool list, leading digits of the residual keys

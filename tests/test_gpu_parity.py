@@ -164,6 +164,21 @@ def test_route_long_sequence_with_heavy_ties():
         _assert_route_equal(score, eps, n_pool, n_approx)
 
 
+def test_route_many_candidates_one_ulp_apart():
+    """More keys share the threshold's bucket than the kernel keeps in LDS, and they are not all
+    equal (two neighbouring floats, for the scores and for the residuals): the select has to go
+    back to memory for every level.  With one value only, the plateau shortcut takes over."""
+    rng = np.random.default_rng(21)
+    n = 60000
+    one, nxt = np.float32(1.0), np.nextafter(np.float32(1.0), np.float32(2.0))
+    score = np.where(rng.random((3, n)) < 0.5, one, nxt).astype(np.float32)
+    eps = np.where(rng.random((3, n)) < 0.3, one, nxt).astype(np.float32)
+    score[2] = one                                        # a plateau
+    score[:, ::9973] = 50.0                               # a few tokens far above
+    for n_pool, n_approx in ((20000, 9000), (45000, 44000), (7, 3)):
+        _assert_route_equal(score, eps, n_pool, n_approx)
+
+
 def test_route_is_deterministic():
     rng = np.random.default_rng(6)
     score = rng.integers(0, 50, size=(8, 20000)).astype(np.float32)
