@@ -237,6 +237,7 @@ VECTOR_API int vector_compress_batch(const vector_shape* shape, const vector_bat
                           int32_t* idx_retain, int32_t* idx_approx, void* k_ret, void* v_ret, void* k_apx,
                           void* ws, size_t ws_bytes, void* stream);
 
+
 /* ---- decode attention over packed caches -------------------------------- */
 
 typedef struct {
@@ -356,6 +357,13 @@ VECTOR_API int vector_compress_rope(const vector_shape* shape, const vector_rope
                          const void* v, const void* W, int32_t n_pool, int32_t n_approx, float* score, float* eps,
                          uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx, void* k_ret, void* v_ret, void* k_apx,
                          int32_t cap_retain, void* ws, size_t ws_bytes, void* stream);
+/* vector_compress_batch on post-RoPE keys (vector_compress_rope per sequence).  rope->positions is
+ * NULL (every sequence's positions are its row indices, plus pos_offset) or a device array ragged
+ * along the token axis like k: [T], sequence b owning entries T_b .. T_b + seq_len[b] - 1. */
+VECTOR_API int vector_compress_batch_rope(const vector_shape* shape, const vector_batch* batch, const vector_rope* rope,
+                               const void* q_win, const void* k, const void* v, const void* W, float* score, float* eps,
+                               uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx, void* k_ret, void* v_ret,
+                               void* k_apx, void* ws, size_t ws_bytes, void* stream);
 /* vector_decode_attn on a post-RoPE cache: out = sum_ret p_t v_t + sum_apx p_t ((R^-1 k_t) . W[h]),
  * logits from the cached keys.  VECTOR_DECODE_LITERAL is not available here (VECTOR_ERR_DTYPE). */
 VECTOR_API int vector_decode_attn_rope(const vector_cache* cache, const vector_rope* rope, const void* q, float scale,

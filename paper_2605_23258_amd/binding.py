@@ -25,7 +25,7 @@ EXPORTS = (
     "vector_strerror", "vector_score", "vector_residual", "vector_score_residual", "vector_route",
     "vector_route_static", "vector_route_static_scratch_bytes", "vector_compact", "vector_decode_attn", "vector_compress_workspace_bytes", "vector_compress",
     "vector_compress_batch_workspace_bytes", "vector_compress_batch",
-    "vector_score_residual_lse", "vector_compress_lse", "vector_compress_rope",
+    "vector_score_residual_lse", "vector_compress_lse", "vector_compress_rope", "vector_compress_batch_rope",
     "vector_timing_enable", "vector_timing_kernels", "vector_timing_name", "vector_timing_read",
     "vector_probe_residual_mfma", "vector_probe_mfma_loop",
     "vector_residual_rope", "vector_score_residual_rope", "vector_decode_attn_rope",
@@ -118,6 +118,8 @@ def lib() -> C.CDLL:
         L.vector_residual.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, sz, vp]
         L.vector_score_residual.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.vector_route.argtypes = [i32, i32, vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
+        L.vector_compress_batch_rope.argtypes = [C.POINTER(Shape), C.POINTER(Batch), C.POINTER(Rope), vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                                 vp, vp, vp, vp, sz, vp]
         L.vector_compress_rope.argtypes = [C.POINTER(Shape), C.POINTER(Rope), vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp,
                                            i32, vp, sz, vp]
         L.vector_score_residual_lse.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, C.c_int64, vp, vp, vp, sz, vp]
@@ -379,6 +381,14 @@ def vector_compress_batch(shape: Shape, batch: Batch, q_win, k, v, W, score, eps
     _check(lib().vector_compress_batch(C.byref(shape), C.byref(batch), _ptr(q_win), _ptr(k), _ptr(v), _ptr(W), _ptr(score),
                                        _ptr(eps), _ptr(tier), _ptr(idx_retain), _ptr(idx_approx), _ptr(k_ret), _ptr(v_ret),
                                        _ptr(k_apx), _ptr(ws), _nbytes(ws), _stream(stream)), "vector_compress_batch")
+
+
+def vector_compress_batch_rope(shape: Shape, batch: Batch, rope: Rope, q_win, k, v, W, score, eps, tier, idx_retain, idx_approx,
+                               k_ret, v_ret, k_apx, ws, stream=None) -> None:
+    _check(lib().vector_compress_batch_rope(C.byref(shape), C.byref(batch), C.byref(rope), _ptr(q_win), _ptr(k), _ptr(v), _ptr(W),
+                                            _ptr(score), _ptr(eps), _ptr(tier), _ptr(idx_retain), _ptr(idx_approx), _ptr(k_ret),
+                                            _ptr(v_ret), _ptr(k_apx), _ptr(ws), _nbytes(ws), _stream(stream)),
+           "vector_compress_batch_rope")
 
 
 def vector_score_key_diversity_workspace_bytes(shape: Shape) -> int:

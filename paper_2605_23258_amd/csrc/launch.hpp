@@ -72,6 +72,7 @@ struct RaggedSeq {
   void *k_ret, *v_ret, *k_apx;
   int n_pool, n_approx, cap_retain;
   void *score_ws, *route_ws;
+  int64_t pos_base;          // post-RoPE keys with a position array: where the sequence's positions start in it
 };
 struct PoolSeq { const float* mass; float* score; int seq_len, n_prefix; void* route_ws; int n_range; };
 size_t ragged_table_bytes(int count);
@@ -79,7 +80,7 @@ size_t ragged_table_bytes(int count);
 bool score_heads_in_one_group(const vector_shape& s);
 size_t route_ragged_table_bytes(int count);
 int launch_score_residual_ragged(const vector_shape& s, const RaggedSeq* seqs, int count, const void* W, void* tables,
-                                 hipStream_t stream);
+                                 hipStream_t stream, const RopeParams* rope = nullptr);
 int launch_pool_scores_ragged(const PoolSeq* seqs, int count, int n_kv_heads, int pool_kernel, int pool_mode, void* tables,
                               hipStream_t stream);
 // tables: the part of the table area after the scorer's (ragged_table_bytes - route_ragged_table_bytes from its start)

@@ -66,6 +66,8 @@ struct PassParams {
   // own parameters only say where the sequences' parameter blocks lie; launch head hv belongs
   // to sequence hv / seq_hps and is its head hv % seq_hps, and a workgroup whose chunk
   // index lies beyond its sequence's chunks leaves at once.
+  int64_t pos_base;     // post-RoPE keys with a position array: token t of this head is at positions[pos_base + t]
+                        // (+ the sequence's share when sequences are stacked)
   const PassParams* seq_table;
   int seq_hps;
   const float* lse;     // null, or the log-sum-exp (natural log, logits scaled by 1/sqrt(d)) of every query row,
@@ -899,7 +901,8 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub) {
         const int tok = min(t0 + 32 * sub + l31, p.n - 1);
-        const float pos = (float)((rp.positions ? rp.positions[tok] : tok) + rp.pos_offset);
+        const int64_t at = p.pos_base + (p.hps ? (int64_t)(h / p.hps) * p.n : 0) + tok;
+        const float pos = (float)((rp.positions ? rp.positions[at] : tok) + rp.pos_offset);
         chunk_t kh[TL::NC], kl[TL::NC];
         const float2* turns = turns_lds;            // re-read per subtile: hoisting the table out of the
         asm volatile("" : "+v"(turns));             // tile loop would pin 64 registers for the whole kernel
@@ -1039,7 +1042,7 @@ int make_plan(const vector_shape& s, bool do_mass, bool do_res, Plan& plan, int 
   p.threads_per_row = tpr;
   p.c2 = kLog2e / sqrtf((float)D);
   p.inv_R = 1.0f / (float)p.R;
-  p.q_head_rows = p.R; p.q_row0 = 0; p.accumulate = 0; p.range = nullptr; p.range_stride = 0; p.log_ref = 0.f; p.lse = nullptr; p.lse_sh = 0; p.seq_table = nullptr; p.seq_hps = 0;
+  p.q_head_rows = p.R; p.q_row0 = 0; p.accumulate = 0; p.range = nullptr; p.range_stride = 0; p.log_ref = 0.f; p.lse = nullptr; p.lse_sh = 0; p.seq_table = nullptr; p.seq_hps = 0; p.pos_base = 0;
   p.k_st = s.k_stride_tok ? s.k_stride_tok : D;
   p.k_sh = s.k_stride_head ? s.k_stride_head : (int64_t)s.seq_len * p.k_st;
   p.v_st = s.v_stride_tok ? s.v_stride_tok : D;
@@ -1133,7 +1136,7 @@ static int launch_passes(const PassParams& p, const PassLaunch& L, dim3 grid1, d
     }
   }
   void (*k2)(PassParams, RopeParams);
-  if (RAGGED) k2 = mass_residual_kernel<T, D, kThreads, true, true, false, false, RAGGED>;
+  if (RAGGED) k2 = L.use_rope ? mass_residual_kernel<T, D, kThreads, true, true, false, true, RAGGED> : mass_residual_kernel<T, D, kThreads, true, true, false, false, RAGGED>;
   else if (L.do_mass && L.do_res) k2 = L.use_rope ? mass_residual_kernel<T, D, kThreads, true, true, false, true> : mass_residual_kernel<T, D, kThreads, true, true>;
   else if (L.do_mass) k2 = mass_residual_kernel<T, D, kThreads, true, false>;
   else k2 = L.use_rope ? mass_residual_kernel<T, D, kThreads, false, true, false, true> : mass_residual_kernel<T, D, kThreads, false, true>;
@@ -1174,7 +1177,7 @@ static int heads_per_group(const vector_shape& s, bool do_res) {
 // score workspace: one pair of passes for all of them, then one pooling launch.
 template <typename T, int D>
 static int run_score_residual_ragged(const vector_shape& s, const RaggedSeq* seqs, int count, const void* W, void* tables,
-                                     hipStream_t stream) {
+                                     hipStream_t stream, const RopeParams* rope) {
   if (count < 1 || count > kMaxRaggedSeqs) return VECTOR_ERR_ARG;
   PassParams host[kMaxRaggedSeqs];
   PassLaunch first;
@@ -1185,8 +1188,9 @@ static int run_score_residual_ragged(const vector_shape& s, const RaggedSeq* seq
     PassLaunch L;
     float4* range = reinterpret_cast<float4*>(route_mass_range(seqs[b].route_ws, t.n_kv_heads));
     const int rc = prepare_passes<T, D>(nullptr, t, t, 0, false, seqs[b].q, seqs[b].k, seqs[b].v, W, true, seqs[b].eps, seqs[b].score_ws,
-                                        nullptr, nullptr, range, L);
+                                        rope, nullptr, range, L);
     if (rc != VECTOR_OK) return rc;
+    L.plan.pp.pos_base = seqs[b].pos_base;
     host[b] = L.plan.pp;
     if (b == 0) first = L;
     if (L.grid1.x > g1) g1 = L.grid1.x;
@@ -1284,13 +1288,13 @@ size_t ragged_table_bytes(int count) {
 }
 
 int launch_score_residual_ragged(const vector_shape& s, const RaggedSeq* seqs, int count, const void* W, void* tables,
-                                 hipStream_t stream) {
+                                 hipStream_t stream, const RopeParams* rope) {
   if (s.dtype == VECTOR_BF16) {
-    if (s.head_dim == 128) return run_score_residual_ragged<bf16_t, 128>(s, seqs, count, W, tables, stream);
-    if (s.head_dim == 64) return run_score_residual_ragged<bf16_t, 64>(s, seqs, count, W, tables, stream);
+    if (s.head_dim == 128) return run_score_residual_ragged<bf16_t, 128>(s, seqs, count, W, tables, stream, rope);
+    if (s.head_dim == 64) return run_score_residual_ragged<bf16_t, 64>(s, seqs, count, W, tables, stream, rope);
   } else if (s.dtype == VECTOR_F32) {
-    if (s.head_dim == 128) return run_score_residual_ragged<float, 128>(s, seqs, count, W, tables, stream);
-    if (s.head_dim == 64) return run_score_residual_ragged<float, 64>(s, seqs, count, W, tables, stream);
+    if (s.head_dim == 128) return run_score_residual_ragged<float, 128>(s, seqs, count, W, tables, stream, rope);
+    if (s.head_dim == 64) return run_score_residual_ragged<float, 64>(s, seqs, count, W, tables, stream, rope);
   } else {
     return VECTOR_ERR_DTYPE;
   }

@@ -296,9 +296,12 @@ size_t vector_compress_batch_workspace_bytes(const vector_shape* s, const vector
   return need;
 }
 
-int vector_compress_batch(const vector_shape* s, const vector_batch* bt, const void* q_win, const void* k, const void* v,
-                          const void* W, float* score, float* eps, uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx,
-                          void* k_ret, void* v_ret, void* k_apx, void* ws, size_t ws_bytes, void* stream) {
+// rope: null, or the rotary parameters with `positions` still the batch's array (ragged along the
+// token axis like k), of which every part gets its piece
+static int compress_batch_impl(const vector_shape* s, const vector_batch* bt, const void* q_win, const void* k, const void* v,
+                               const void* W, float* score, float* eps, uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx,
+                               void* k_ret, void* v_ret, void* k_apx, void* ws, size_t ws_bytes, void* stream,
+                               const vec::RopeParams* rope) {
   int rc = check_batch(s, bt);
   if (rc) return rc;
   if (!q_win || !k || !v || !W || !score || !eps || !tier) return VECTOR_ERR_ARG;
@@ -327,10 +330,12 @@ int vector_compress_batch(const vector_shape* s, const vector_batch* bt, const v
       unsigned char* w8 = reinterpret_cast<unsigned char*>(ws);
       void* tables = w8;
       w8 += (vec::ragged_table_bytes(part.count) + 255) / 256 * 256;
+      int64_t seqs_tok0 = 0;
       for (int i = 0; i < part.count; ++i) {
         const int bi = b + i;
         it = batch_item(s, bt, bi, total, bi ? &prev : nullptr);
         prev = it;
+        if (i == 0) seqs_tok0 = it.tok0;
         vec::RaggedSeq& q = seqs[i];
         q.shape = it.shape;
         q.q = reinterpret_cast<const unsigned char*>(q_win) + (size_t)bi * s->n_q_heads * s->window * d * esz;
@@ -343,11 +348,17 @@ int vector_compress_batch(const vector_shape* s, const vector_batch* bt, const v
         q.v_ret = v_ret ? reinterpret_cast<unsigned char*>(v_ret) + (size_t)(H * it.cap0 * d) * esz : nullptr;
         q.k_apx = k_apx ? reinterpret_cast<unsigned char*>(k_apx) + (size_t)(H * it.apx0 * d) * esz : nullptr;
         q.n_pool = bt->n_pool[bi]; q.n_approx = bt->n_approx[bi]; q.cap_retain = bt->cap_retain[bi];
+        q.pos_base = it.tok0 - seqs_tok0;
         q.score_ws = w8;
         q.route_ws = w8 + (vec::score_workspace_bytes(it.shape) + 255) / 256 * 256;
         w8 += seq_workspace_bytes(s, bt, bi);
       }
-      if ((rc = vec::launch_score_residual_ragged(*s, seqs, part.count, W, tables, st))) return rc;
+      vec::RopeParams rp_part;
+      if (rope) {
+        rp_part = *rope;
+        if (rope->positions) rp_part.positions = rope->positions + seqs_tok0;
+      }
+      if ((rc = vec::launch_score_residual_ragged(*s, seqs, part.count, W, tables, st, rope ? &rp_part : nullptr))) return rc;
       unsigned char* route_tables = reinterpret_cast<unsigned char*>(tables) + vec::ragged_table_bytes(part.count) -
                                     vec::route_ragged_table_bytes(part.count);
       if ((rc = vec::launch_route_compact_ragged(*s, seqs, part.count, route_tables, st))) return rc;
@@ -367,16 +378,38 @@ int vector_compress_batch(const vector_shape* s, const vector_batch* bt, const v
     const unsigned char* vb = reinterpret_cast<const unsigned char*>(v) + (size_t)(it.tok0 * it.shape.v_stride_tok) * esz;
     const unsigned char* qb = reinterpret_cast<const unsigned char*>(q_win) + (size_t)b * s->n_q_heads * s->window * d * esz;
     const int n_pool = bt->n_pool[b], n_approx = bt->n_approx[b];
+    vec::RopeParams rp_one;
+    if (rope) {
+      rp_one = *rope;
+      if (rope->positions) rp_one.positions = rope->positions + it.tok0;
+    }
     rc = compress_impl(&it.shape, qb, kb, vb, W, n_pool, n_approx, score + H * it.tok0, eps + H * it.tok0, tier + H * it.tok0,
                          idx_retain ? idx_retain + H * it.ret0 : nullptr, idx_approx ? idx_approx + H * it.apx0 : nullptr,
                          k_ret ? reinterpret_cast<unsigned char*>(k_ret) + (size_t)(H * it.cap0 * d) * esz : nullptr,
                          v_ret ? reinterpret_cast<unsigned char*>(v_ret) + (size_t)(H * it.cap0 * d) * esz : nullptr,
                          k_apx ? reinterpret_cast<unsigned char*>(k_apx) + (size_t)(H * it.apx0 * d) * esz : nullptr,
-                         bt->cap_retain[b], ws, ws_bytes, stream, part.count > 1 ? &stack : nullptr);
+                         bt->cap_retain[b], ws, ws_bytes, stream, part.count > 1 ? &stack : nullptr, nullptr, rope ? &rp_one : nullptr);
     if (rc) return rc;
     b += part.count;
   }
   return VECTOR_OK;
+}
+
+int vector_compress_batch(const vector_shape* s, const vector_batch* bt, const void* q_win, const void* k, const void* v,
+                          const void* W, float* score, float* eps, uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx,
+                          void* k_ret, void* v_ret, void* k_apx, void* ws, size_t ws_bytes, void* stream) {
+  return compress_batch_impl(s, bt, q_win, k, v, W, score, eps, tier, idx_retain, idx_approx, k_ret, v_ret, k_apx, ws, ws_bytes, stream,
+                             nullptr);
+}
+
+int vector_compress_batch_rope(const vector_shape* s, const vector_batch* bt, const vector_rope* rope, const void* q_win, const void* k,
+                               const void* v, const void* W, float* score, float* eps, uint8_t* tier, int32_t* idx_retain,
+                               int32_t* idx_approx, void* k_ret, void* v_ret, void* k_apx, void* ws, size_t ws_bytes, void* stream) {
+  if (!s) return VECTOR_ERR_ARG;
+  vec::RopeParams rp;
+  const int rc = make_rope(rope, s->head_dim, rp);
+  if (rc) return rc;
+  return compress_batch_impl(s, bt, q_win, k, v, W, score, eps, tier, idx_retain, idx_approx, k_ret, v_ret, k_apx, ws, ws_bytes, stream, &rp);
 }
 
 size_t vector_calibrate_workspace_bytes(const vector_shape* s) {

@@ -253,3 +253,65 @@ def test_decode_over_per_sequence_blocks(name, flags):
         vb.vector_decode_attn(cache, t["q"], scale, torch.empty((B, Hq, d), dtype=torch.float32, device="cuda:0"), ws,
                               flags=vb.VECTOR_DECODE_OUT_F32)
     assert ei.value.code == vb.VECTOR_ERR_ARG
+
+
+@pytest.mark.parametrize("explicit", [False, True], ids=["row_index_positions", "position_array"])
+def test_compress_batch_on_rotated_keys(explicit):
+    """The batch call on post-RoPE keys: unequal sequences around a run of equal ones, positions
+    either implied (row index plus one offset for all) or given as an array ragged like the keys
+    (every sequence with an offset of its own).  Bit for bit vector_compress_rope per sequence,
+    and the residual is the oracle's with the keys turned back."""
+    theta = 500000.0
+    cfg = dg.scaled(dg.CONFIGS["cfg2"], n_kv_heads=2, n_q_heads=8, window=32)
+    lens = [700, 1200, 1200, 333, 2100]
+    offsets = [11 + 1000 * b for b in range(len(lens))] if explicit else [40] * len(lens)
+    H, d = cfg.n_kv_heads, cfg.head_dim
+    layers = [wl.make_layer(dg.scaled(cfg, seq_len=n), layer=b, rope_theta=theta, rope_interleaved=False, pos_offset=offsets[b])
+              for b, n in enumerate(lens)]
+    inv_freq = layers[0].extra["inv_freq"]
+    W = layers[0].w_cal
+    counts = [vo.budget_counts_frac(n, cfg.f_retain, cfg.f_approx) for n in lens]
+    n_pool, n_approx = [c[0] for c in counts], [c[1] for c in counts]
+    n_ret = [p - a for p, a in zip(n_pool, n_approx)]
+    tok0 = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    ret0 = np.concatenate([[0], np.cumsum(n_ret)]).astype(np.int64)
+    apx0 = np.concatenate([[0], np.cumsum(n_approx)]).astype(np.int64)
+    T, R, A = int(tok0[-1]), int(ret0[-1]), int(apx0[-1])
+    dev = dict(q=pl.to_device(np.stack([li.q_win for li in layers])), k=pl.to_device(np.concatenate([li.k for li in layers], axis=1)),
+               v=pl.to_device(np.concatenate([li.v for li in layers], axis=1)), W=pl.to_device(W))
+    pos_all = pl.to_device(np.concatenate([li.extra["pos"] for li in layers]).astype(np.int32)) if explicit else None
+    rope, keep_r = vb.make_rope(inv_freq, pos_all, False, 0 if explicit else offsets[0])
+    shape = pl.shape_of(cfg, seq_len=1)
+    batch, keep = vb.make_batch(lens, n_pool, n_approx, n_ret)
+    ws = pl.alloc_workspace(vb.vector_compress_batch_workspace_bytes(shape, batch))
+    out = dict(score=torch.full((H * T,), -1.0, device="cuda:0"), eps=torch.full((H * T,), -1.0, device="cuda:0"),
+               tier=torch.full((H * T,), 9, dtype=torch.uint8, device="cuda:0"),
+               ir=torch.full((H * R,), -1, dtype=torch.int32, device="cuda:0"), ia=torch.full((H * A,), -1, dtype=torch.int32, device="cuda:0"),
+               kr=torch.zeros((H * R, d), dtype=torch.bfloat16, device="cuda:0"), vr=torch.zeros((H * R, d), dtype=torch.bfloat16, device="cuda:0"),
+               ka=torch.zeros((H * A, d), dtype=torch.bfloat16, device="cuda:0"))
+    vb.vector_compress_batch_rope(shape, batch, rope, dev["q"], dev["k"], dev["v"], dev["W"], out["score"], out["eps"], out["tier"],
+                                  out["ir"], out["ia"], out["kr"], out["vr"], out["ka"], ws)
+    torch.cuda.synchronize()
+    w_wide = dg.widen(W)
+    for b, li in enumerate(layers):
+        n, n_p, n_a, n_r = lens[b], n_pool[b], n_approx[b], n_ret[b]
+        t0, r0, a0 = int(tok0[b]), int(ret0[b]), int(apx0[b])
+        s1 = pl.shape_of(cfg, seq_len=n)
+        one = pl.alloc_outputs(s1, n_p, n_a, n_r, torch.bfloat16)
+        ws1 = pl.alloc_workspace(vb.vector_compress_workspace_bytes(s1, n_p, n_a))
+        pos_b = pl.to_device(li.extra["pos"].astype(np.int32)) if explicit else None
+        rope1, keep1 = vb.make_rope(inv_freq, pos_b, False, 0 if explicit else offsets[b])
+        vb.vector_compress_rope(s1, rope1, pl.to_device(li.q_win), pl.to_device(li.k), pl.to_device(li.v), dev["W"], n_p, n_a, one.score,
+                                one.eps, one.tier, one.idx_retain, one.idx_approx, one.k_ret, one.v_ret, one.k_apx, n_r, ws1)
+        torch.cuda.synchronize()
+        what = f"sequence {b}"
+        assert torch.equal(out["score"][H * t0: H * (t0 + n)].view(H, n), one.score), what
+        assert torch.equal(out["eps"][H * t0: H * (t0 + n)].view(H, n), one.eps), what
+        assert torch.equal(out["tier"][H * t0: H * (t0 + n)].view(H, n), one.tier), what
+        assert torch.equal(out["ir"][H * r0: H * (r0 + n_r)].view(H, n_r), one.idx_retain), what
+        assert torch.equal(out["ia"][H * a0: H * (a0 + n_a)].view(H, n_a), one.idx_approx), what
+        assert torch.equal(out["kr"][H * r0: H * (r0 + n_r)].view(torch.int16), one.k_ret.view(torch.int16).reshape(H * n_r, d)), what
+        assert torch.equal(out["ka"][H * a0: H * (a0 + n_a)].view(torch.int16), one.k_apx.view(torch.int16).reshape(H * n_a, d)), what
+        ref_eps = vo.residual(dg.widen(li.k), dg.widen(li.v), w_wide, pos=li.extra["pos"], inv_freq=inv_freq, interleaved=False)
+        close(one.eps.cpu().numpy(), ref_eps, what + " eps")
+    del keep, keep_r
