@@ -364,6 +364,26 @@ VECTOR_API int vector_compress_batch_rope(const vector_shape* shape, const vecto
                                const void* q_win, const void* k, const void* v, const void* W, float* score, float* eps,
                                uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx, void* k_ret, void* v_ret,
                                void* k_apx, void* ws, size_t ws_bytes, void* stream);
+
+/* The compression pass with any combination of the two variants above: keys cached after RoPE
+ * (rope) and the window rows' log-sum-exp handed in (lse), as a production prefill has them.
+ * options NULL, or with both members NULL, is vector_compress / vector_compress_batch.
+ *   rope             as in vector_compress_rope / vector_compress_batch_rope, or NULL
+ *   lse              as in vector_compress_lse, or NULL; for a batch: device [batch, Hq, lse_stride_head]
+ *   lse_stride_head  floats between two query heads' rows (0: w); must be 0 when lse is NULL */
+typedef struct {
+  const vector_rope* rope;
+  const float* lse;
+  int64_t lse_stride_head;
+} vector_compress_options;
+VECTOR_API int vector_compress_ex(const vector_shape* shape, const vector_compress_options* options, const void* q_win,
+                       const void* k, const void* v, const void* W, int32_t n_pool, int32_t n_approx, float* score,
+                       float* eps, uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx, void* k_ret, void* v_ret,
+                       void* k_apx, int32_t cap_retain, void* ws, size_t ws_bytes, void* stream);
+VECTOR_API int vector_compress_batch_ex(const vector_shape* shape, const vector_batch* batch, const vector_compress_options* options,
+                             const void* q_win, const void* k, const void* v, const void* W, float* score, float* eps,
+                             uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx, void* k_ret, void* v_ret,
+                             void* k_apx, void* ws, size_t ws_bytes, void* stream);
 /* vector_decode_attn on a post-RoPE cache: out = sum_ret p_t v_t + sum_apx p_t ((R^-1 k_t) . W[h]),
  * logits from the cached keys.  VECTOR_DECODE_LITERAL is not available here (VECTOR_ERR_DTYPE). */
 VECTOR_API int vector_decode_attn_rope(const vector_cache* cache, const vector_rope* rope, const void* q, float scale,

@@ -26,6 +26,7 @@ EXPORTS = (
     "vector_route_static", "vector_route_static_scratch_bytes", "vector_compact", "vector_decode_attn", "vector_compress_workspace_bytes", "vector_compress",
     "vector_compress_batch_workspace_bytes", "vector_compress_batch",
     "vector_score_residual_lse", "vector_compress_lse", "vector_compress_rope", "vector_compress_batch_rope",
+    "vector_compress_ex", "vector_compress_batch_ex",
     "vector_timing_enable", "vector_timing_kernels", "vector_timing_name", "vector_timing_read",
     "vector_probe_residual_mfma", "vector_probe_mfma_loop",
     "vector_residual_rope", "vector_score_residual_rope", "vector_decode_attn_rope",
@@ -57,6 +58,12 @@ class Rope(C.Structure):
     """vector_rope: inv_freq is HOST memory (keep the array it points into alive during the call)."""
     _fields_ = [("inv_freq", C.POINTER(C.c_double)), ("interleaved", C.c_int32), ("pos_offset", C.c_int32),
                 ("positions", C.c_void_p)]
+
+
+class CompressOptions(C.Structure):
+    """vector_compress_options: any of a rotary description and the window rows' log-sum-exp."""
+    _fields_ = [("rope", C.POINTER(Rope)), ("lse", C.c_void_p), ("lse_stride_head", C.c_int64)]
+
 
 
 def make_rope(inv_freq, positions=None, interleaved: bool = False, pos_offset: int = 0):
@@ -118,6 +125,10 @@ def lib() -> C.CDLL:
         L.vector_residual.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, sz, vp]
         L.vector_score_residual.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.vector_route.argtypes = [i32, i32, vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
+        L.vector_compress_ex.argtypes = [C.POINTER(Shape), C.POINTER(CompressOptions), vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp,
+                                         vp, vp, i32, vp, sz, vp]
+        L.vector_compress_batch_ex.argtypes = [C.POINTER(Shape), C.POINTER(Batch), C.POINTER(CompressOptions), vp, vp, vp, vp, vp, vp,
+                                               vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.vector_compress_batch_rope.argtypes = [C.POINTER(Shape), C.POINTER(Batch), C.POINTER(Rope), vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                                  vp, vp, vp, vp, sz, vp]
         L.vector_compress_rope.argtypes = [C.POINTER(Shape), C.POINTER(Rope), vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp,
@@ -381,6 +392,30 @@ def vector_compress_batch(shape: Shape, batch: Batch, q_win, k, v, W, score, eps
     _check(lib().vector_compress_batch(C.byref(shape), C.byref(batch), _ptr(q_win), _ptr(k), _ptr(v), _ptr(W), _ptr(score),
                                        _ptr(eps), _ptr(tier), _ptr(idx_retain), _ptr(idx_approx), _ptr(k_ret), _ptr(v_ret),
                                        _ptr(k_apx), _ptr(ws), _nbytes(ws), _stream(stream)), "vector_compress_batch")
+
+
+def make_options(rope: Optional[Rope] = None, lse=None, lse_stride_head: int = 0) -> CompressOptions:
+    o = CompressOptions()
+    o.rope = C.pointer(rope) if rope is not None else None
+    o.lse = _ptr(lse)
+    o.lse_stride_head = lse_stride_head
+    return o
+
+
+def vector_compress_ex(shape: Shape, options: Optional[CompressOptions], q_win, k, v, W, n_pool: int, n_approx: int, score, eps, tier,
+                       idx_retain, idx_approx, k_ret, v_ret, k_apx, cap_retain: int, ws, stream=None) -> None:
+    _check(lib().vector_compress_ex(C.byref(shape), C.byref(options) if options is not None else None, _ptr(q_win), _ptr(k), _ptr(v),
+                                    _ptr(W), n_pool, n_approx, _ptr(score), _ptr(eps), _ptr(tier), _ptr(idx_retain), _ptr(idx_approx),
+                                    _ptr(k_ret), _ptr(v_ret), _ptr(k_apx), cap_retain, _ptr(ws), _nbytes(ws), _stream(stream)),
+           "vector_compress_ex")
+
+
+def vector_compress_batch_ex(shape: Shape, batch: Batch, options: Optional[CompressOptions], q_win, k, v, W, score, eps, tier, idx_retain,
+                             idx_approx, k_ret, v_ret, k_apx, ws, stream=None) -> None:
+    _check(lib().vector_compress_batch_ex(C.byref(shape), C.byref(batch), C.byref(options) if options is not None else None, _ptr(q_win),
+                                          _ptr(k), _ptr(v), _ptr(W), _ptr(score), _ptr(eps), _ptr(tier), _ptr(idx_retain),
+                                          _ptr(idx_approx), _ptr(k_ret), _ptr(v_ret), _ptr(k_apx), _ptr(ws), _nbytes(ws),
+                                          _stream(stream)), "vector_compress_batch_ex")
 
 
 def vector_compress_batch_rope(shape: Shape, batch: Batch, rope: Rope, q_win, k, v, W, score, eps, tier, idx_retain, idx_approx,

@@ -73,6 +73,8 @@ struct RaggedSeq {
   int n_pool, n_approx, cap_retain;
   void *score_ws, *route_ws;
   int64_t pos_base;          // post-RoPE keys with a position array: where the sequence's positions start in it
+  const float* lse;          // the sequence's window rows' log-sum-exp, or null
+  int64_t lse_stride_head;
 };
 struct PoolSeq { const float* mass; float* score; int seq_len, n_prefix; void* route_ws; int n_range; };
 size_t ragged_table_bytes(int count);

@@ -1187,8 +1187,9 @@ static int run_score_residual_ragged(const vector_shape& s, const RaggedSeq* seq
     if (heads_per_group<T, D>(t, true) != t.n_q_heads / t.n_kv_heads) return VECTOR_ERR_SHAPE;
     PassLaunch L;
     float4* range = reinterpret_cast<float4*>(route_mass_range(seqs[b].route_ws, t.n_kv_heads));
+    const QueryLse ql = {seqs[b].lse, seqs[b].lse_stride_head};
     const int rc = prepare_passes<T, D>(nullptr, t, t, 0, false, seqs[b].q, seqs[b].k, seqs[b].v, W, true, seqs[b].eps, seqs[b].score_ws,
-                                        rope, nullptr, range, L);
+                                        rope, seqs[b].lse ? &ql : nullptr, range, L);
     if (rc != VECTOR_OK) return rc;
     L.plan.pp.pos_base = seqs[b].pos_base;
     host[b] = L.plan.pp;

@@ -301,9 +301,13 @@ size_t vector_compress_batch_workspace_bytes(const vector_shape* s, const vector
 static int compress_batch_impl(const vector_shape* s, const vector_batch* bt, const void* q_win, const void* k, const void* v,
                                const void* W, float* score, float* eps, uint8_t* tier, int32_t* idx_retain, int32_t* idx_approx,
                                void* k_ret, void* v_ret, void* k_apx, void* ws, size_t ws_bytes, void* stream,
-                               const vec::RopeParams* rope) {
+                               const vec::RopeParams* rope, const vec::QueryLse* lse = nullptr) {
   int rc = check_batch(s, bt);
   if (rc) return rc;
+  if (lse && (rc = check_lse(s, lse))) return rc;
+  // lse: [batch, Hq, stride_head] floats, sequence after sequence
+  const int64_t lse_sh = lse ? (lse->stride_head ? lse->stride_head : s->window) : 0;
+  const int64_t lse_seq = lse_sh * s->n_q_heads;
   if (!q_win || !k || !v || !W || !score || !eps || !tier) return VECTOR_ERR_ARG;
   if (!aligned16(q_win) || !aligned16(k) || !aligned16(v) || !aligned16(W)) return VECTOR_ERR_ARG;
   int64_t total = 0, total_ret = 0, total_apx = 0;
@@ -349,6 +353,8 @@ static int compress_batch_impl(const vector_shape* s, const vector_batch* bt, co
         q.k_apx = k_apx ? reinterpret_cast<unsigned char*>(k_apx) + (size_t)(H * it.apx0 * d) * esz : nullptr;
         q.n_pool = bt->n_pool[bi]; q.n_approx = bt->n_approx[bi]; q.cap_retain = bt->cap_retain[bi];
         q.pos_base = it.tok0 - seqs_tok0;
+        q.lse = lse ? lse->lse + bi * lse_seq : nullptr;
+        q.lse_stride_head = lse_sh;
         q.score_ws = w8;
         q.route_ws = w8 + (vec::score_workspace_bytes(it.shape) + 255) / 256 * 256;
         w8 += seq_workspace_bytes(s, bt, bi);
@@ -378,6 +384,7 @@ static int compress_batch_impl(const vector_shape* s, const vector_batch* bt, co
     const unsigned char* vb = reinterpret_cast<const unsigned char*>(v) + (size_t)(it.tok0 * it.shape.v_stride_tok) * esz;
     const unsigned char* qb = reinterpret_cast<const unsigned char*>(q_win) + (size_t)b * s->n_q_heads * s->window * d * esz;
     const int n_pool = bt->n_pool[b], n_approx = bt->n_approx[b];
+    const vec::QueryLse lse_one = {lse ? lse->lse + b * lse_seq : nullptr, lse_sh};     // a run's sequences follow each other
     vec::RopeParams rp_one;
     if (rope) {
       rp_one = *rope;
@@ -388,7 +395,8 @@ static int compress_batch_impl(const vector_shape* s, const vector_batch* bt, co
                          k_ret ? reinterpret_cast<unsigned char*>(k_ret) + (size_t)(H * it.cap0 * d) * esz : nullptr,
                          v_ret ? reinterpret_cast<unsigned char*>(v_ret) + (size_t)(H * it.cap0 * d) * esz : nullptr,
                          k_apx ? reinterpret_cast<unsigned char*>(k_apx) + (size_t)(H * it.apx0 * d) * esz : nullptr,
-                         bt->cap_retain[b], ws, ws_bytes, stream, part.count > 1 ? &stack : nullptr, nullptr, rope ? &rp_one : nullptr);
+                         bt->cap_retain[b], ws, ws_bytes, stream, part.count > 1 ? &stack : nullptr, lse ? &lse_one : nullptr,
+                         rope ? &rp_one : nullptr);
     if (rc) return rc;
     b += part.count;
   }
@@ -615,6 +623,56 @@ int vector_compress_rope(const vector_shape* s, const vector_rope* rope, const v
   if (rc) return rc;
   return compress_impl(s, q_win, k, v, W, n_pool, n_approx, score, eps, tier, idx_retain, idx_approx, k_ret, v_ret, k_apx, cap_retain,
                        ws, ws_bytes, stream, nullptr, nullptr, &rp);
+}
+
+// options -> the internal forms; rope parameters are built into `rp`
+static int take_options(const vector_shape* s, const vector_compress_options* opt, vec::RopeParams& rp, const vec::RopeParams** rope,
+                        vec::QueryLse& ql, const vec::QueryLse** lse) {
+  *rope = nullptr;
+  *lse = nullptr;
+  if (!s) return VECTOR_ERR_ARG;
+  if (!opt) return VECTOR_OK;
+  if (opt->rope) {
+    const int rc = make_rope(opt->rope, s->head_dim, rp);
+    if (rc) return rc;
+    *rope = &rp;
+  }
+  if (opt->lse) {
+    ql.lse = opt->lse;
+    ql.stride_head = opt->lse_stride_head;
+    *lse = &ql;
+  } else if (opt->lse_stride_head != 0) {
+    return VECTOR_ERR_ARG;
+  }
+  return VECTOR_OK;
+}
+
+int vector_compress_ex(const vector_shape* s, const vector_compress_options* opt, const void* q_win, const void* k, const void* v,
+                       const void* W, int32_t n_pool, int32_t n_approx, float* score, float* eps, uint8_t* tier,
+                       int32_t* idx_retain, int32_t* idx_approx, void* k_ret, void* v_ret, void* k_apx, int32_t cap_retain,
+                       void* ws, size_t ws_bytes, void* stream) {
+  vec::RopeParams rp;
+  vec::QueryLse ql;
+  const vec::RopeParams* rope;
+  const vec::QueryLse* lse;
+  const int rc = take_options(s, opt, rp, &rope, ql, &lse);
+  if (rc) return rc;
+  return compress_impl(s, q_win, k, v, W, n_pool, n_approx, score, eps, tier, idx_retain, idx_approx, k_ret, v_ret, k_apx, cap_retain,
+                       ws, ws_bytes, stream, nullptr, lse, rope);
+}
+
+int vector_compress_batch_ex(const vector_shape* s, const vector_batch* bt, const vector_compress_options* opt, const void* q_win,
+                             const void* k, const void* v, const void* W, float* score, float* eps, uint8_t* tier,
+                             int32_t* idx_retain, int32_t* idx_approx, void* k_ret, void* v_ret, void* k_apx, void* ws,
+                             size_t ws_bytes, void* stream) {
+  vec::RopeParams rp;
+  vec::QueryLse ql;
+  const vec::RopeParams* rope;
+  const vec::QueryLse* lse;
+  const int rc = take_options(s, opt, rp, &rope, ql, &lse);
+  if (rc) return rc;
+  return compress_batch_impl(s, bt, q_win, k, v, W, score, eps, tier, idx_retain, idx_approx, k_ret, v_ret, k_apx, ws, ws_bytes, stream,
+                             rope, lse);
 }
 
 }  // extern "C"

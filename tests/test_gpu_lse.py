@@ -103,3 +103,79 @@ def test_lse_arguments_are_checked():
         assert ei.value.code == vb.VECTOR_ERR_ARG
     torch.cuda.synchronize()
     assert (score == -1.0).all() and (eps == -1.0).all(), "an error must not launch anything"
+
+
+def test_rotated_keys_and_lse_together_single_and_batch():
+    """What a production prefill has: keys cached after RoPE and the window rows' log-sum-exp from its
+    attention kernel.  vector_compress_ex with both: scores and residuals against the oracle, the
+    routing of its own floats exact; vector_compress_batch_ex (unequal sequences around an equal
+    run) bit for bit the single calls."""
+    theta = 500000.0
+    cfg = dg.scaled(dg.CONFIGS["cfg2"], n_kv_heads=2, n_q_heads=8, window=32)
+    lens = [900, 640, 640, 1500, 333]
+    offset = 17
+    H, Hq, d, w = cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim, cfg.window
+    layers = [wl.make_layer(dg.scaled(cfg, seq_len=n), layer=b, rope_theta=theta, rope_interleaved=False, pos_offset=offset)
+              for b, n in enumerate(lens)]
+    inv_freq, W = layers[0].extra["inv_freq"], layers[0].w_cal
+    counts = [vo.budget_counts_frac(n, cfg.f_retain, cfg.f_approx) for n in lens]
+    n_pool, n_approx = [c[0] for c in counts], [c[1] for c in counts]
+    n_ret = [p - a for p, a in zip(n_pool, n_approx)]
+    rope, keep_r = vb.make_rope(inv_freq, None, False, offset)
+    lse_all = pl.to_device(np.stack([window_lse(li.q_win, li.k) for li in layers]))            # [batch, Hq, w]
+    W_dev = pl.to_device(W)
+    singles = []
+    for b, li in enumerate(layers):
+        n, n_p, n_a, n_r = lens[b], n_pool[b], n_approx[b], n_ret[b]
+        s1 = pl.shape_of(cfg, seq_len=n)
+        one = pl.alloc_outputs(s1, n_p, n_a, n_r, torch.bfloat16)
+        ws1 = pl.alloc_workspace(vb.vector_compress_workspace_bytes(s1, n_p, n_a))
+        opt = vb.make_options(rope, lse_all[b], 0)
+        vb.vector_compress_ex(s1, opt, pl.to_device(li.q_win), pl.to_device(li.k), pl.to_device(li.v), W_dev, n_p, n_a, one.score, one.eps,
+                              one.tier, one.idx_retain, one.idx_approx, one.k_ret, one.v_ret, one.k_apx, n_r, ws1)
+        torch.cuda.synchronize()
+        g_score, g_eps = one.score.cpu().numpy(), one.eps.cpu().numpy()
+        ref_score = vo.score(dg.widen(li.q_win), dg.widen(li.k), w, cfg.pool_kernel)
+        ref_eps = vo.residual(dg.widen(li.k), dg.widen(li.v), dg.widen(W), pos=li.extra["pos"], inv_freq=inv_freq, interleaved=False)
+        close(g_score[:, : n - w].astype(np.float64) * n, ref_score[:, : n - w].astype(np.float64) * n, f"sequence {b} n*score")
+        close(g_eps, ref_eps, f"sequence {b} eps")
+        tier, idx_r, idx_a = vo.route(g_score, g_eps, n_p, n_a)
+        assert np.array_equal(one.tier.cpu().numpy(), tier)
+        assert np.array_equal(one.idx_retain.cpu().numpy(), idx_r) and np.array_equal(one.idx_approx.cpu().numpy(), idx_a)
+        singles.append(one)
+    tok0 = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    ret0 = np.concatenate([[0], np.cumsum(n_ret)]).astype(np.int64)
+    apx0 = np.concatenate([[0], np.cumsum(n_approx)]).astype(np.int64)
+    T, R, A = int(tok0[-1]), int(ret0[-1]), int(apx0[-1])
+    shape = pl.shape_of(cfg, seq_len=1)
+    batch, keep = vb.make_batch(lens, n_pool, n_approx, n_ret)
+    ws = pl.alloc_workspace(vb.vector_compress_batch_workspace_bytes(shape, batch))
+    out = dict(score=torch.full((H * T,), -1.0, device="cuda:0"), eps=torch.full((H * T,), -1.0, device="cuda:0"),
+               tier=torch.full((H * T,), 9, dtype=torch.uint8, device="cuda:0"),
+               ir=torch.full((H * R,), -1, dtype=torch.int32, device="cuda:0"), ia=torch.full((H * A,), -1, dtype=torch.int32, device="cuda:0"),
+               kr=torch.zeros((H * R, d), dtype=torch.bfloat16, device="cuda:0"), vr=torch.zeros((H * R, d), dtype=torch.bfloat16, device="cuda:0"),
+               ka=torch.zeros((H * A, d), dtype=torch.bfloat16, device="cuda:0"))
+    opt = vb.make_options(rope, lse_all, 0)
+    vb.vector_compress_batch_ex(shape, batch, opt, pl.to_device(np.stack([li.q_win for li in layers])),
+                                pl.to_device(np.concatenate([li.k for li in layers], axis=1)),
+                                pl.to_device(np.concatenate([li.v for li in layers], axis=1)), W_dev, out["score"], out["eps"], out["tier"],
+                                out["ir"], out["ia"], out["kr"], out["vr"], out["ka"], ws)
+    torch.cuda.synchronize()
+    for b, one in enumerate(singles):
+        n, n_a, n_r = lens[b], n_approx[b], n_ret[b]
+        t0, r0, a0 = int(tok0[b]), int(ret0[b]), int(apx0[b])
+        what = f"sequence {b}"
+        assert torch.equal(out["score"][H * t0: H * (t0 + n)].view(H, n), one.score), what
+        assert torch.equal(out["eps"][H * t0: H * (t0 + n)].view(H, n), one.eps), what
+        assert torch.equal(out["tier"][H * t0: H * (t0 + n)].view(H, n), one.tier), what
+        assert torch.equal(out["ir"][H * r0: H * (r0 + n_r)].view(H, n_r), one.idx_retain), what
+        assert torch.equal(out["ia"][H * a0: H * (a0 + n_a)].view(H, n_a), one.idx_approx), what
+        assert torch.equal(out["kr"][H * r0: H * (r0 + n_r)].view(torch.int16), one.k_ret.view(torch.int16).reshape(H * n_r, d)), what
+        assert torch.equal(out["vr"][H * r0: H * (r0 + n_r)].view(torch.int16), one.v_ret.view(torch.int16).reshape(H * n_r, d)), what
+    # no options at all is the plain call
+    vb.vector_compress_batch_ex(shape, batch, None, pl.to_device(np.stack([li.q_win for li in layers])),
+                                pl.to_device(np.concatenate([li.k for li in layers], axis=1)),
+                                pl.to_device(np.concatenate([li.v for li in layers], axis=1)), W_dev, out["score"], out["eps"], out["tier"],
+                                out["ir"], out["ia"], out["kr"], out["vr"], out["ka"], ws)
+    torch.cuda.synchronize()
+    del keep, keep_r

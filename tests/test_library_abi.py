@@ -29,6 +29,7 @@ def test_struct_sizes_match_header_layout():
     assert ctypes.sizeof(vb.Shape) == 8 * 4 + 5 * 8 + 2 * 4
     assert ctypes.sizeof(vb.Cache) == 8 * 4 + 5 * 8 + 4 * 8 + 8 + 2 * 4
     assert ctypes.sizeof(vb.Batch) == 8 + 4 * 8
+    assert ctypes.sizeof(vb.CompressOptions) == 3 * 8
 
 
 def test_budget_helpers_match_oracle():
