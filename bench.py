@@ -576,6 +576,13 @@ def run_extras(vb, dg, pl, torch, np, dev, cfg, shape, layer, out, ws, n_p, n_a)
                                        out.k_ret.shape[1], wsc))
     res["compress_us_per_layer"] = per_call_us(
         lambda: pl.compress_layer(shape, layer["q_win"], layer["k"], layer["v"], layer["w_cal"], n_p, n_a, out, wsc, one_call=True))
+    # the layer read as a post-RoPE cache, without and with that log-sum-exp: what a production prefill calls
+    for key, opt in (("compress_rope_us_per_layer", vb.make_options(rope, None, 0)),
+                     ("compress_rope_with_lse_us_per_layer", vb.make_options(rope, lse, 0))):
+        res[key] = per_call_us(
+            lambda: vb.vector_compress_ex(shape, opt, layer["q_win"], layer["k"], layer["v"], layer["w_cal"], n_p, n_a, out.score, out.eps,
+                                          out.tier, out.idx_retain, out.idx_approx, out.k_ret, out.v_ret, out.k_apx, out.k_ret.shape[1],
+                                          wsc))
     del q_flat, k_flat, wsc, lse
     # Section 5's approximation-ratio sweep re-expressed on the distortion measure of Section 4: at a
     # fixed compression ratio (fixed footprint of 2 (1 - p_c) n rows) budget moves from retained
