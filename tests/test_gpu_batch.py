@@ -40,6 +40,8 @@ BATCHES = {
     # token, nothing kept at all (that sequence is routed on its own), no approximated token
     "bf16_counts_at_the_limits": ("cfg2", dict(n_kv_heads=2, n_q_heads=8, window=32), (600, 900, 700, 1200, 450), (0, 2, 1, 0, 3),
                                   ((600, 200), (100, 100), (0, 0), (300, 0), (32, 7))),
+    "f32_d128_unequal": ("cfg1", dict(head_dim=128, n_kv_heads=1, n_q_heads=2, window=8, pool_kernel=3), (500, 777, 300), (0, 1, 0)),
+    "bf16_d64_unequal": ("cfg2", dict(head_dim=64, n_kv_heads=2, n_q_heads=4, window=16), (900, 450, 1300, 2200), (0, 0, 2, 1)),
     "f32_seventy_short": ("cfg1", dict(n_kv_heads=1, n_q_heads=4, window=20), tuple(64 + 5 * i for i in range(70)), tuple(i % 3 for i in range(70))),
 }
 
