@@ -42,6 +42,8 @@ BATCHES = {
                                   ((600, 200), (100, 100), (0, 0), (300, 0), (32, 7))),
     "f32_d128_unequal": ("cfg1", dict(head_dim=128, n_kv_heads=1, n_q_heads=2, window=8, pool_kernel=3), (500, 777, 300), (0, 1, 0)),
     "bf16_d64_unequal": ("cfg2", dict(head_dim=64, n_kv_heads=2, n_q_heads=4, window=16), (900, 450, 1300, 2200), (0, 0, 2, 1)),
+    "f32_tiny_lengths": ("cfg1", dict(n_kv_heads=1, n_q_heads=2, window=1, pool_kernel=3), (1, 2, 5, 1, 9, 3), (0, 1, 0, 2, 0, 0),
+                         ((1, 0), (2, 1), (3, 1), (1, 1), (4, 2), (2, 0))),
     "f32_seventy_short": ("cfg1", dict(n_kv_heads=1, n_q_heads=4, window=20), tuple(64 + 5 * i for i in range(70)), tuple(i % 3 for i in range(70))),
 }
 
