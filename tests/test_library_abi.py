@@ -71,6 +71,53 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert vb.strerror(-3).startswith("workspace")
 
 
+def test_batch_workspace_follows_how_the_sequences_share_launches():
+    """Host-side planning of a batch: a run of equal sequences needs what one call on the stacked
+    heads needs; unequal neighbours run together, each in its own piece of the workspace after
+    their parameter tables; the batch needs the largest part."""
+    s = vb.Shape(n_q_heads=8, n_kv_heads=2, head_dim=128, seq_len=1, window=32, pool_kernel=7, dtype=vb.VECTOR_BF16)
+
+    def one(n, heads_times=1):
+        t = vb.Shape(n_q_heads=8 * heads_times, n_kv_heads=2 * heads_times, head_dim=128, seq_len=n, window=32, pool_kernel=7,
+                     dtype=vb.VECTOR_BF16)
+        n_p, n_a = vb.vector_budget_counts_frac(n, 0.15, 0.15)
+        return vb.vector_compress_workspace_bytes(t, n_p, n_a)
+
+    def batch_bytes(lens):
+        counts = [vb.vector_budget_counts_frac(n, 0.15, 0.15) for n in lens]
+        b, keep = vb.make_batch(lens, [c[0] for c in counts], [c[1] for c in counts], [c[0] - c[1] for c in counts])
+        return vb.vector_compress_batch_workspace_bytes(s, b)
+
+    assert batch_bytes([4096]) == one(4096)
+    assert batch_bytes([4096, 4096, 4096]) == one(4096, 3)
+    ragged = batch_bytes([4096, 1000, 2500])
+    pieces = sum((one(n) + 255) // 256 * 256 for n in (4096, 1000, 2500))
+    assert pieces < ragged <= pieces + 65536                   # the tables are a few hundred bytes per sequence and kernel
+    assert batch_bytes([700, 4096, 4096, 4096, 900]) == one(4096, 3)      # singles around a run: the run is the largest part
+    assert batch_bytes([4096, 1000, 2500, 8192, 8192]) == max(ragged, one(8192, 2))
+
+
+def test_batch_and_option_arguments_are_rejected_on_the_host():
+    import ctypes as C
+    L = vb.lib()
+    s = vb.Shape(n_q_heads=8, n_kv_heads=2, head_dim=128, seq_len=1, window=32, pool_kernel=7, dtype=vb.VECTOR_BF16)
+    good, keep = vb.make_batch([100, 200], [30, 60], [10, 20], [20, 40])
+    assert vb.vector_compress_batch_workspace_bytes(s, good) > 0
+    for lens, pool, apx, cap in (([100, 20], [30, 6], [10, 2], [20, 4]),          # shorter than the window
+                                 ([100, 200], [30, 260], [10, 20], [20, 240]),     # pool larger than the sequence
+                                 ([100, 200], [30, 60], [40, 20], [20, 40]),       # more approximated than pooled
+                                 ([100, 200], [30, 60], [10, 20], [19, 40])):      # capacity below the retained count
+        bad, keep_b = vb.make_batch(lens, pool, apx, cap)
+        assert vb.vector_compress_batch_workspace_bytes(s, bad) == 0
+        assert L.vector_compress_batch(C.byref(s), C.byref(bad), *([None] * 13), 0, None) < 0
+    # null tensors with a valid batch; a null shape; a stride for a log-sum-exp that is not there
+    assert L.vector_compress_batch(C.byref(s), C.byref(good), *([None] * 13), 0, None) == -1
+    assert L.vector_compress_ex(None, None, *([None] * 4), 1, 0, *([None] * 8), 0, None, 0, None) == -1
+    opt = vb.CompressOptions()
+    opt.rope, opt.lse, opt.lse_stride_head = None, None, 64
+    assert L.vector_compress_batch_ex(C.byref(s), C.byref(good), C.byref(opt), *([None] * 13), 0, None) == -1
+
+
 def test_bench_refuses_more_than_one_gpu():
     """The benchmark measures one GPU; asking for more ends with a message and a non-zero status
     before anything touches a device."""
