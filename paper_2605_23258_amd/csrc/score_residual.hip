@@ -332,16 +332,24 @@ __global__ __launch_bounds__(NT) void score_stats_kernel(PassParams p) {
 // ---------------------------------------------------------------------------
 // pass 1, key tiles through LDS: for R_pad = 128 or 256 (4 or 8 row blocks)
 // ---------------------------------------------------------------------------
-// Eight waves; a wave owns one 32-row block of Q_h for the whole launch and keeps it in
-// registers as the B operand, so its lanes carry the running (max, sum-exp) of their own
+// Eight waves; a wave owns one or two 32-row blocks of Q_h for the whole launch and keeps them
+// in registers as B operands, so its lanes carry the running (max, sum-exp) of their own
 // query rows in registers too.  The keys of the chunk stream through LDS in 64-token
-// tiles per token group (NW / NRB groups work on different tiles): all 512 threads load
-// a tile with 16-byte loads, 16 adjacent lanes per row, one tile ahead of the one being
-// consumed (double buffered, one barrier per step), and every wave of a token group reads
-// the tile back in operand order.  Compared with score_stats_kernel the key loads are
-// fully coalesced, overlap with the arithmetic, and no statistics pass through LDS.
-constexpr int kV2Threads = 512;
+// tiles per token group (the waves that own the same rows form the groups, which work on
+// different tiles): all 512 threads load a step's tiles with 16-byte loads, 16 adjacent lanes
+// per row, one step ahead of the one being consumed (double buffered, one barrier per step),
+// and every wave of a token group reads its tile back in operand order.  With two row blocks
+// per wave (256 bf16 rows) an operand chunk read from LDS feeds two MFMAs of independent
+// chains: half the LDS traffic per MFMA, and no MFMA waits for the one before it.
+// Compared with score_stats_kernel the key loads are fully coalesced, overlap with the
+// arithmetic, and no statistics pass through LDS.
 constexpr int kV2TileTokens = 64;
+constexpr int kV2Threads = 512;
+// row blocks per wave, and the token groups that follow from it
+constexpr int tiles_blocks_per_wave(int nrb, int elem_bytes) { return (nrb == 8 && elem_bytes == 2) ? 2 : 1; }
+constexpr int tiles_token_groups(int nrb, int elem_bytes) {
+  return (kV2Threads / kWave) / (nrb / tiles_blocks_per_wave(nrb, elem_bytes));
+}
 
 template <typename T, int D, int NRB, bool RAGGED = false>
 __global__ __launch_bounds__(kV2Threads) void score_stats_tiles_kernel(PassParams p) {
@@ -351,34 +359,25 @@ __global__ __launch_bounds__(kV2Threads) void score_stats_tiles_kernel(PassParam
   using TL = Tile<T, D>;
   constexpr int NT = kV2Threads;
   constexpr int NW = NT / kWave;
-  constexpr int TG = NW / NRB;                       // token groups
+  constexpr int RBW = tiles_blocks_per_wave(NRB, (int)sizeof(T));   // row blocks per wave
+  constexpr int NRW = NRB / RBW;                     // waves that cover all rows
+  constexpr int TG = NW / NRW;                       // token groups
   constexpr int NC = TL::NC;
   constexpr int kStepTokens = TG * kV2TileTokens;
   constexpr int kPieces = TL::kRowBytes / 16;        // 16-byte pieces per key row
   constexpr int kLoads = kStepTokens * kPieces / NT; // pieces per thread and step
-  static_assert(NW % NRB == 0 && (kStepTokens * kPieces) % NT == 0, "tile shape");
+  static_assert(NW % NRW == 0 && (kStepTokens * kPieces) % NT == 0, "tile shape");
   constexpr int kBufBytes = kStepTokens * TL::kLdsStride;
   extern __shared__ __align__(16) unsigned char smem[];
 
   const int chunk = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l31 = lane & 31;
-  const int rb = wave % NRB, tg = wave / NRB;
+  const int rw = wave % NRW, tg = wave / NRW;
   const T* k_head = reinterpret_cast<const T*>(p.k) + head_offset(p, h, p.k_sb, p.k_sh);
   const int c_begin = chunk * p.tpc1;
   const int c_end = min(p.n, c_begin + p.tpc1);
   const int n_steps = (c_end - c_begin + kStepTokens - 1) / kStepTokens;
 
-  // this wave's query rows: B operand, zero beyond R
-  chunk_t qf[NC];
-  {
-    const int qrow = rb * 32 + l31;
-    const T* qrow_p = reinterpret_cast<const T*>(p.q) + ((size_t)h * p.q_head_rows + p.q_row0 + min(qrow, p.R - 1)) * D;
-#pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      qf[c] = load_chunk(qrow_p + chunk_elem_offset<T>(c, half));
-      if (qrow >= p.R) qf[c] = make_uint4(0, 0, 0, 0);
-    }
-  }
   // piece i of a step: token i / kPieces of the step, 16 bytes at piece i % kPieces
   auto fetch = [&](uint4* raw, int step) {
 #pragma unroll
@@ -396,24 +395,41 @@ __global__ __launch_bounds__(kV2Threads) void score_stats_tiles_kernel(PassParam
     }
   };
 
-  float m_run = -INFINITY, l_run = 0.f;              // of query row rb*32 + l31, over this lane half's tokens
-  // rows = tokens, columns = query rows
-  auto mma_sub = [&](f32x16& x, const unsigned char* tile, int sub) {
+  // Key tiles are requested kAhead steps before they are consumed (a step's arithmetic is
+  // shorter than a trip to HBM); they wait in registers and enter LDS one step ahead.  The first
+  // tile is asked for before anything else: the launch's first MFMA waits for it longest.
+  constexpr int kAhead = (kLoads > 2) ? 2 : 3;
+  uint4 raw[kAhead][kLoads];
+  fetch(raw[0], 0);
+  // this wave's query rows: B operands, zero beyond R
+  chunk_t qf[RBW][NC];
+  int qrow[RBW];
+#pragma unroll
+  for (int j = 0; j < RBW; ++j) {
+    qrow[j] = (rw * RBW + j) * 32 + l31;
+    const T* qrow_p = reinterpret_cast<const T*>(p.q) + ((size_t)h * p.q_head_rows + p.q_row0 + min(qrow[j], p.R - 1)) * D;
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-      const chunk_t kf = lds_chunk<T, D>(tile, sub * 32 + l31, c, half);
-      if (c == 0) mma_chunk_first<T>(x, kf, qf[c]);
-      else mma_chunk<T>(x, kf, qf[c]);
+      qf[j][c] = load_chunk(qrow_p + chunk_elem_offset<T>(c, half));
+      if (qrow[j] >= p.R) qf[j][c] = make_uint4(0, 0, 0, 0);
     }
-  };
+  }
+#pragma unroll
+  for (int a = 1; a < kAhead; ++a)
+    if (a < n_steps) fetch(raw[a], a);
+  // of query rows qrow[j], over this lane half's tokens
+  float m_run[RBW], l_run[RBW];
+#pragma unroll
+  for (int j = 0; j < RBW; ++j) { m_run[j] = -INFINITY; l_run[j] = 0.f; }
+  // rows = tokens, columns = query rows
   auto tile_max1 = [&](const f32x16& x) {
     float m0 = max3(x[0], x[1], x[2]), m1 = max3(x[8], x[9], x[10]);
     m0 = max3(m0, x[3], x[4]); m1 = max3(m1, x[11], x[12]);
     m0 = max3(m0, x[5], x[6]); m1 = max3(m1, x[13], x[14]);
     return fmaxf(fmaxf(m0, x[7]), fmaxf(m1, x[15])) * p.c2;
   };
-  auto fold = [&](const f32x16& x) {
-    const float m_new = fmaxf(m_run, tile_max1(x));
+  auto fold = [&](const f32x16& x, int j) {
+    const float m_new = fmaxf(m_run[j], tile_max1(x));
     const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
     float s0 = 0.f, s1 = 0.f;
 #pragma unroll
@@ -421,66 +437,89 @@ __global__ __launch_bounds__(kV2Threads) void score_stats_tiles_kernel(PassParam
       s0 += fast_exp2(fmaf(x[v], p.c2, -m_safe));
       s1 += fast_exp2(fmaf(x[v + 1], p.c2, -m_safe));
     }
-    l_run = l_run * fast_exp2(m_run - m_safe) + (s0 + s1);
-    m_run = m_new;
+    l_run[j] = l_run[j] * fast_exp2(m_run[j] - m_safe) + (s0 + s1);
+    m_run[j] = m_new;
   };
-  // second subtile's MFMAs one at a time, each followed by exponentials of the first subtile
-  auto mma_fold = [&](f32x16& nx, const unsigned char* tile, const f32x16& cu) {
-    const float m_new = fmaxf(m_run, tile_max1(cu));
-    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-    float s0 = 0.f, s1 = 0.f;
-    chunk_t kf = lds_chunk<T, D>(tile, 32 + l31, 0, half);
+  // MFMAs of one subtile (for every row block of the wave), one operand chunk at a time, each
+  // followed by its share of the exponentials of a subtile that is already complete: the matrix
+  // pipe works through the new products while the vector ALU folds the finished ones into the
+  // running statistics
+  auto mma_fold = [&](auto refill_tag, f32x16* nx, chunk_t* kf, f32x16* cu, const unsigned char* refill) {
+    constexpr bool kRefill = decltype(refill_tag)::value;
+    float m_new[RBW], m_safe[RBW], s0[RBW], s1[RBW];
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-      const chunk_t k_now = kf;
-      if (c + 1 < NC) kf = lds_chunk<T, D>(tile, 32 + l31, c + 1, half);
-      if (c == 0) mma_chunk_first<T>(nx, k_now, qf[c]);
-      else mma_chunk<T>(nx, k_now, qf[c]);
 #pragma unroll
-      for (int v = c * 16 / NC; v < (c + 1) * 16 / NC; ++v) {
-        const float e = fast_exp2(fmaf(cu[v], p.c2, -m_safe));
-        if (v & 1) s1 += e; else s0 += e;
+      for (int j = 0; j < RBW; ++j) {
+        if (c == 0) mma_chunk_first<T>(nx[j], kf[c], qf[j][c]);
+        else mma_chunk<T>(nx[j], kf[c], qf[j][c]);
+        // the next subtile's chunk, into the registers just read for the last time
+        if (kRefill && j == RBW - 1) kf[c] = lds_chunk<T, D>(refill, 32 + l31, c, half);
+        if (c == 0) {
+          // the finished subtile's row maxima wait for its last MFMA: taken once the new subtile's
+          // first MFMA is in the pipe, not before
+          VEC_PIN(nx[j], cu[j]);
+          m_new[j] = fmaxf(m_run[j], tile_max1(cu[j]));
+          m_safe[j] = (m_new[j] == -INFINITY) ? 0.f : m_new[j];
+          s0[j] = 0.f; s1[j] = 0.f;
+        }
+#pragma unroll
+        for (int v = c * 16 / NC; v < (c + 1) * 16 / NC; ++v) {
+          const float e = fast_exp2(fmaf(cu[j][v], p.c2, -m_safe[j]));
+          if (v & 1) s1[j] += e; else s0[j] += e;
+        }
+        VEC_PIN3(nx[j], s0[j], s1[j]);
       }
-      VEC_PIN3(nx, s0, s1);
     }
-    l_run = l_run * fast_exp2(m_run - m_safe) + (s0 + s1);
-    m_run = m_new;
+#pragma unroll
+    for (int j = 0; j < RBW; ++j) {
+      l_run[j] = l_run[j] * fast_exp2(m_run[j] - m_safe[j]) + (s0[j] + s1[j]);
+      m_run[j] = m_new[j];
+    }
   };
 
-  // Key tiles are requested kAhead steps before they are consumed (a step's arithmetic is
-  // shorter than a trip to HBM); they wait in registers and enter LDS one step ahead.
-  constexpr int kAhead = 3;
-  uint4 raw[kAhead][kLoads];
-  const int qrow = rb * 32 + l31;
+  // The second subtile of a step is folded during the first subtile's MFMAs of the next step,
+  // so `pend` carries products across steps; all -inf folds to nothing.
+  f32x16 pend[RBW];
+#pragma unroll
+  for (int j = 0; j < RBW; ++j)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) pend[j][v] = -INFINITY;
   auto compute = [&](int step) {
     const unsigned char* tile = smem + (step & 1) * kBufBytes + tg * kV2TileTokens * TL::kLdsStride;
     const int t0 = c_begin + step * kStepTokens + tg * kV2TileTokens;
     if (t0 < c_end) {
-      f32x16 A, B;
+      // the first subtile in operand order, requested before the first MFMA; the second subtile's
+      // chunks follow into the same registers as the first one's are consumed
+      chunk_t kf[NC];
+#pragma unroll
+      for (int c = 0; c < NC; ++c) kf[c] = lds_chunk<T, D>(tile, l31, c, half);
+      f32x16 A[RBW];
       // a tile needs masking if it reaches past the first window position or past the chunk
       const bool tail = (t0 + kV2TileTokens > p.n_prefix + 1) || (t0 + kV2TileTokens > c_end);
       if (!tail) {
-        mma_sub(A, tile, 0);
-        mma_fold(B, tile, A);
-        fold(B);
+        mma_fold(std::true_type{}, A, kf, pend, tile);
+        mma_fold(std::false_type{}, pend, kf, A, tile);
       } else {
         // query row (g, r) sits at position n - w + r and sees tokens <= that
-        const int last = (qrow < p.R) ? min(p.n_prefix + (qrow % p.w), c_end - 1) : c_end - 1;
-        mma_sub(A, tile, 0);
-        mma_sub(B, tile, 1);
+        int last[RBW];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          if (t0 + acc_row(v, half) > last) A[v] = -INFINITY;
-          if (t0 + 32 + acc_row(v, half) > last) B[v] = -INFINITY;
-        }
-        fold(A);
-        fold(B);
+        for (int j = 0; j < RBW; ++j) last[j] = (qrow[j] < p.R) ? min(p.n_prefix + (qrow[j] % p.w), c_end - 1) : c_end - 1;
+        mma_fold(std::true_type{}, A, kf, pend, tile);
+#pragma unroll
+        for (int j = 0; j < RBW; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            if (t0 + acc_row(v, half) > last[j]) A[j][v] = -INFINITY;
+        mma_fold(std::false_type{}, pend, kf, A, tile);
+#pragma unroll
+        for (int j = 0; j < RBW; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            if (t0 + 32 + acc_row(v, half) > last[j]) pend[j][v] = -INFINITY;
       }
     }
   };
-#pragma unroll
-  for (int a = 0; a < kAhead; ++a)
-    if (a < n_steps) fetch(raw[a], a);
   stash(raw[0], 0);
   for (int step0 = 0; step0 < n_steps; step0 += kAhead) {
 #pragma unroll
@@ -494,17 +533,21 @@ __global__ __launch_bounds__(kV2Threads) void score_stats_tiles_kernel(PassParam
       }
     }
   }
-  // merge the two lane halves, then the token groups; one (max, sum) per (row, chunk)
-  {
-    const float m2 = __shfl_xor(m_run, 32, kWave), l2 = __shfl_xor(l_run, 32, kWave);
-    const float mn = fmaxf(m_run, m2);
+  // the last pending subtile; then merge the two lane halves, then the token groups: one (max, sum) per (row, chunk)
+#pragma unroll
+  for (int j = 0; j < RBW; ++j) {
+    fold(pend[j], j);
+    const float m2 = __shfl_xor(m_run[j], 32, kWave), l2 = __shfl_xor(l_run[j], 32, kWave);
+    const float mn = fmaxf(m_run[j], m2);
     const float ms = (mn == -INFINITY) ? 0.f : mn;
-    l_run = l_run * fast_exp2(m_run - ms) + l2 * fast_exp2(m2 - ms);
-    m_run = mn;
+    l_run[j] = l_run[j] * fast_exp2(m_run[j] - ms) + l2 * fast_exp2(m2 - ms);
+    m_run[j] = mn;
   }
   __syncthreads();                         // tiles are dead: reuse LDS for the group merge
   float2* grp = reinterpret_cast<float2*>(smem);     // [TG][NRB * 32]
-  if (half == 0) grp[tg * (NRB * 32) + qrow] = make_float2(m_run, l_run);
+#pragma unroll
+  for (int j = 0; j < RBW; ++j)
+    if (half == 0) grp[tg * (NRB * 32) + qrow[j]] = make_float2(m_run[j], l_run[j]);
   __syncthreads();
   float2* out = p.part + (size_t)h * p.R_pad * p.n_chunks + chunk;
   for (int row = threadIdx.x; row < NRB * 32; row += NT) {
@@ -1007,11 +1050,11 @@ int pick_tokens_per_chunk_tiles(int n, int n_kv_heads) {
   return tpc;
 }
 
-size_t stats_tiles_lds(int nrb, size_t lds_stride) {
-  return (size_t)2 * (kV2Threads / kWave / (nrb ? nrb : 1)) * kV2TileTokens * lds_stride;
+size_t stats_tiles_lds(int nrb, int elem_bytes, size_t lds_stride) {
+  return (size_t)2 * tiles_token_groups(nrb, elem_bytes) * kV2TileTokens * lds_stride;
 }
-bool stats_by_tiles(int nrb, size_t lds_stride) {
-  return (nrb == 8 || nrb == 4) && stats_tiles_lds(nrb, lds_stride) <= kMaxLdsBytes;
+bool stats_by_tiles(int nrb, int elem_bytes, size_t lds_stride) {
+  return (nrb == 8 || nrb == 4) && stats_tiles_lds(nrb, elem_bytes, lds_stride) <= kMaxLdsBytes;
 }
 
 int pick_tokens_per_chunk(int n, int n_kv_heads) {
@@ -1034,7 +1077,7 @@ int make_plan(const vector_shape& s, bool do_mass, bool do_res, Plan& plan, int 
   p.n = s.seq_len; p.w = s.window; p.R = G * s.window; p.R_pad = (p.R + 31) / 32 * 32;
   p.n_prefix = s.seq_len - s.window;
   p.tokens_per_chunk = pick_tokens_per_chunk(s.seq_len, plan_heads);
-  plan.tiles = stats_by_tiles(p.R_pad / 32, (size_t)Tile<T, D>::kLdsStride);
+  plan.tiles = stats_by_tiles(p.R_pad / 32, (int)sizeof(T), (size_t)Tile<T, D>::kLdsStride);
   p.tpc1 = plan.tiles ? pick_tokens_per_chunk_tiles(s.seq_len, plan_heads) : p.tokens_per_chunk;
   p.n_chunks = (s.seq_len + p.tpc1 - 1) / p.tpc1;
   int tpr = 1;
@@ -1125,7 +1168,7 @@ static int launch_passes(const PassParams& p, const PassLaunch& L, dim3 grid1, d
   if (L.do_mass && !L.plan.pp.lse) {          // pass 1: the rows' (max, sum-exp); not needed when the caller brings them
     const int nrb = L.plan.pp.R_pad / 32;
     if (L.plan.tiles) {
-      const size_t lds_tiles = stats_tiles_lds(nrb, Tile<T, D>::kLdsStride);
+      const size_t lds_tiles = stats_tiles_lds(nrb, (int)sizeof(T), Tile<T, D>::kLdsStride);
       void (*k1)(PassParams) = nrb == 8 ? score_stats_tiles_kernel<T, D, 8, RAGGED> : score_stats_tiles_kernel<T, D, 4, RAGGED>;
       VEC_HIP(set_max_lds(reinterpret_cast<const void*>(k1), lds_tiles));
       VEC_LAUNCH(K_SCORE_STATS, k1, grid1, dim3(kV2Threads), lds_tiles, stream, p);
