@@ -329,6 +329,27 @@ __global__ __launch_bounds__(NT) void score_stats_kernel(PassParams p) {
   }
 }
 
+// Workgroups go to the eight XCDs in turn by their linear index (x fastest), and every XCD has an
+// L2 of its own.  This permutation of the grid puts all chunks of a head on one XCD (the heads
+// are dealt out over the XCDs, or the XCDs over a head's chunks when there are fewer heads than
+// XCDs): the head's query rows, its W and the first pass's partials are then fetched into one L2
+// instead of eight, and the second pass finds the partials where the first one wrote them.  Any
+// grid it does not divide evenly keeps the plain order.
+constexpr int kXcds = 8;
+__device__ __forceinline__ void xcd_chunk_head(int& chunk, int& h) {
+  const int gx = gridDim.x, gy = gridDim.y;
+  chunk = blockIdx.x; h = blockIdx.y;
+  const int id = chunk + gx * h, x = id % kXcds, k = id / kXcds;
+  if (gy % kXcds == 0) {
+    h = x + kXcds * (k / gx);
+    chunk = k % gx;
+  } else if (kXcds % gy == 0 && gx % (kXcds / gy) == 0) {
+    const int s = kXcds / gy;                  // XCDs per head
+    h = x % gy;
+    chunk = (x / gy) * (gx / s) + k;
+  }
+}
+
 // ---------------------------------------------------------------------------
 // pass 1, key tiles through LDS: for R_pad = 128 or 256 (4 or 8 row blocks)
 // ---------------------------------------------------------------------------
@@ -353,9 +374,11 @@ constexpr int tiles_token_groups(int nrb, int elem_bytes) {
 
 template <typename T, int D, int NRB, bool RAGGED = false>
 __global__ __launch_bounds__(kV2Threads) void score_stats_tiles_kernel(PassParams p) {
-  int h = blockIdx.y;
+  int chunk, h;
+  if (RAGGED) { chunk = blockIdx.x; h = blockIdx.y; }
+  else xcd_chunk_head(chunk, h);
   take_sequence<RAGGED>(p, h);
-  if (RAGGED && (int)blockIdx.x >= p.n_chunks) return;
+  if (RAGGED && chunk >= p.n_chunks) return;
   using TL = Tile<T, D>;
   constexpr int NT = kV2Threads;
   constexpr int NW = NT / kWave;
@@ -370,7 +393,6 @@ __global__ __launch_bounds__(kV2Threads) void score_stats_tiles_kernel(PassParam
   constexpr int kBufBytes = kStepTokens * TL::kLdsStride;
   extern __shared__ __align__(16) unsigned char smem[];
 
-  const int chunk = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l31 = lane & 31;
   const int rw = wave % NRW, tg = wave / NRW;
   const T* k_head = reinterpret_cast<const T*>(p.k) + head_offset(p, h, p.k_sb, p.k_sh);
@@ -665,9 +687,11 @@ __device__ __forceinline__ void load_v_subtile(chunk_t* vf, const T* v_head, int
 // (the scores use them as cached).
 template <typename T, int D, int NT, bool DO_MASS, bool DO_RES, bool PROBE = false, bool ROPE = false, bool RAGGED = false>
 __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopeParams rp) {
-  int h = blockIdx.y;
+  int chunk, h;
+  if (RAGGED) { chunk = blockIdx.x; h = blockIdx.y; }
+  else xcd_chunk_head(chunk, h);
   take_sequence<RAGGED>(p, h);
-  if (RAGGED && (int)blockIdx.x * p.tokens_per_chunk >= p.n) return;
+  if (RAGGED && chunk * p.tokens_per_chunk >= p.n) return;
   using TL = Tile<T, D>;
   constexpr int NW = NT / kWave;
   constexpr int JB = TL::JB;
@@ -681,7 +705,6 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
   off += DO_RES ? (size_t)D * TL::kLdsStride : 0;
   float2* turns_lds = reinterpret_cast<float2*>(smem + off);                 // ROPE: [D/2] rotary frequencies (hi, lo)
 
-  const int chunk = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, l31 = lane & 31;
   const int nrb = p.R_pad / 32;
 
@@ -693,9 +716,12 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
   const int mass_end = min(c_end, p.n_prefix);
   constexpr int kStep = NW * 64;
 
+  // A wave takes its tiles from the chunk's end towards its start: the first pass read the chunk
+  // forwards on the same XCD, so what is left of the keys in that L2 is the chunk's end.
   chunk_t kf0[TL::NC], kf1[TL::NC];
-  int t0 = c_begin + wave * 64;
-  if (t0 < c_end) {                       // first tile's keys fly during the prologue
+  const int t_first = c_begin + wave * 64;
+  int t0 = t_first < c_end ? t_first + (c_end - t_first - 1) / kStep * kStep : t_first - kStep;
+  if (t0 >= t_first) {                    // first tile's keys fly during the prologue
     load_k_subtile<T, D>(kf0, k_head, p.k_st, t0, p.n, lane);
     load_k_subtile<T, D>(kf1, k_head, p.k_st, t0 + 32, p.n, lane);
   }
@@ -889,15 +915,15 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
   int rep = 0;
   auto load_next = [&](int tn) {
     if (PROBE && rep + 1 < p.repeat) return;
-    if (tn < c_end) {                    // every MFMA of the tile is issued: fetch the next keys
+    if (tn >= t_first) {                 // every MFMA of the tile is issued: fetch the next keys
       load_k_subtile<T, D>(kf0, k_head, p.k_st, tn, p.n, lane);
       load_k_subtile<T, D>(kf1, k_head, p.k_st, tn + 32, p.n, lane);
     }
   };
 
   float st_n = 0.f, st_l = 0.f, st_ll = 0.f;   // over the columns this lane stores
-  while (t0 < c_end) {
-    const int tn = t0 + kStep;
+  while (t0 >= t_first) {
+    const int tn = t0 - kStep;
     if (DO_RES && !ROPE && (!PROBE || rep == 0)) {   // values arrive while the score part computes
       load_v_subtile<T, D>(vf0, v_head, p.v_st, t0, p.n, lane);
       load_v_subtile<T, D>(vf1, v_head, p.v_st, t0 + 32, p.n, lane);
