@@ -61,6 +61,28 @@ template <typename T> __device__ __forceinline__ int chunk_elem_offset(int c, in
   return (c * 2 + half) * Elem<T>::kPerChunk;
 }
 
+// Workgroups go to the eight XCDs in turn by their linear index (x fastest), and every XCD has an
+// L2 of its own.  This permutation of a (chunks, heads) grid puts all chunks of a head on one XCD
+// (the heads are dealt out over the XCDs, or the XCDs over a head's chunks when there are fewer
+// heads than XCDs): what the head's workgroups share (query rows, W, partial results) is then
+// fetched into one L2 instead of eight, and a launch finds what the launch before it wrote
+// for the same head in the L2 it was written through.  Any grid it does not divide evenly keeps
+// the plain order.
+constexpr int kXcds = 8;
+__device__ __forceinline__ void xcd_chunk_head(int& chunk, int& h) {
+  const int gx = gridDim.x, gy = gridDim.y;
+  chunk = blockIdx.x; h = blockIdx.y;
+  const int id = chunk + gx * h, x = id % kXcds, k = id / kXcds;
+  if (gy % kXcds == 0) {
+    h = x + kXcds * (k / gx);
+    chunk = k % gx;
+  } else if (kXcds % gy == 0 && gx % (kXcds / gy) == 0) {
+    const int s = kXcds / gy;                  // XCDs per head
+    h = x % gy;
+    chunk = (x / gy) * (gx / s) + k;
+  }
+}
+
 __device__ __forceinline__ chunk_t load_chunk(const void* p) { return *reinterpret_cast<const chunk_t*>(p); }
 
 // acc += A(32 x chunk) * B(chunk x 32): a holds rows of the M side, b rows of the N side.

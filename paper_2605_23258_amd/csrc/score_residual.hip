@@ -329,27 +329,6 @@ __global__ __launch_bounds__(NT) void score_stats_kernel(PassParams p) {
   }
 }
 
-// Workgroups go to the eight XCDs in turn by their linear index (x fastest), and every XCD has an
-// L2 of its own.  This permutation of the grid puts all chunks of a head on one XCD (the heads
-// are dealt out over the XCDs, or the XCDs over a head's chunks when there are fewer heads than
-// XCDs): the head's query rows, its W and the first pass's partials are then fetched into one L2
-// instead of eight, and the second pass finds the partials where the first one wrote them.  Any
-// grid it does not divide evenly keeps the plain order.
-constexpr int kXcds = 8;
-__device__ __forceinline__ void xcd_chunk_head(int& chunk, int& h) {
-  const int gx = gridDim.x, gy = gridDim.y;
-  chunk = blockIdx.x; h = blockIdx.y;
-  const int id = chunk + gx * h, x = id % kXcds, k = id / kXcds;
-  if (gy % kXcds == 0) {
-    h = x + kXcds * (k / gx);
-    chunk = k % gx;
-  } else if (kXcds % gy == 0 && gx % (kXcds / gy) == 0) {
-    const int s = kXcds / gy;                  // XCDs per head
-    h = x % gy;
-    chunk = (x / gy) * (gx / s) + k;
-  }
-}
-
 // ---------------------------------------------------------------------------
 // pass 1, key tiles through LDS: for R_pad = 128 or 256 (4 or 8 row blocks)
 // ---------------------------------------------------------------------------
