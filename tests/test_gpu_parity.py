@@ -42,6 +42,13 @@ CASES = {
     "bf16_d128_ragged": ("cfg2", dict(seq_len=1777, n_kv_heads=2, n_q_heads=8, window=24, pool_kernel=5)),
     "bf16_d128_w64": ("cfg3", dict(seq_len=1536, n_kv_heads=1, n_q_heads=4, layers=1)),
     "bf16_d64": ("cfg2", dict(seq_len=900, head_dim=64, n_kv_heads=2, n_q_heads=4, window=16)),
+    # 256 query rows per KV head (two row blocks per wave in the first pass): an odd length whose last
+    # chunk and last 128-token step are partial, rows padded from 240 to 256, d = 64, and eight and two
+    # KV heads (the grid of both passes is dealt out over the XCDs by head)
+    "bf16_d128_w64_ragged": ("cfg3", dict(seq_len=1733, n_kv_heads=2, n_q_heads=8, layers=1)),
+    "bf16_d128_w60_padded_rows": ("cfg3", dict(seq_len=1100, n_kv_heads=1, n_q_heads=4, window=60, layers=1)),
+    "bf16_d64_w64": ("cfg3", dict(seq_len=1400, head_dim=64, n_kv_heads=1, n_q_heads=4, layers=1)),
+    "bf16_d128_w64_eight_heads": ("cfg3", dict(seq_len=700, n_kv_heads=8, n_q_heads=32, layers=1)),
     "f32_d128": ("cfg1", dict(seq_len=700, head_dim=128, n_kv_heads=1, n_q_heads=2, window=8, pool_kernel=3)),
     "tiny_n_equals_w": ("cfg1", dict(seq_len=32, window=32)),
     "short": ("cfg2", dict(seq_len=70, n_kv_heads=1, n_q_heads=4, window=5, pool_kernel=1)),
@@ -273,7 +280,8 @@ def test_decode_attn(dtype, d, B, Hq, Hkv, n_r, n_a, cap):
         assert ei.value.code == vb.VECTOR_ERR_DTYPE
 
 
-@pytest.mark.parametrize("name", ["f32_d64_n1024", "bf16_d128_n2048", "bf16_d128_ragged", "bf16_G8_w64_groups"])
+@pytest.mark.parametrize("name", ["f32_d64_n1024", "bf16_d128_n2048", "bf16_d128_ragged", "bf16_G8_w64_groups", "bf16_d128_w64_ragged",
+                                  "bf16_d128_w64_eight_heads"])
 def test_end_to_end_compress(name):
     cfg, li, dev, wide = _inputs(name)
     shape = pl.shape_of(cfg)
