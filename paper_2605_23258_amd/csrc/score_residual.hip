@@ -1050,7 +1050,7 @@ struct Plan {
 // pass 1 through LDS tiles: one workgroup per CU where the sequence allows it (more, shorter chunks
 // gain a microsecond in pass 1 and lose two in the partial merge of pass 2)
 int pick_tokens_per_chunk_tiles(int n, int n_kv_heads) {
-  int tpc = 2048;
+  int tpc = 8192;
   while (tpc > 256 && (int64_t)((n + tpc - 1) / tpc) * n_kv_heads < VEC_TILES_MIN_WGS) tpc >>= 1;
   return tpc;
 }
@@ -1065,7 +1065,7 @@ bool stats_by_tiles(int nrb, int elem_bytes, size_t lds_stride) {
 int pick_tokens_per_chunk(int n, int n_kv_heads) {
   // at least one workgroup per CU where the sequence allows it, and then as many
   // 64-token tiles per wave as possible so that the key prefetch has something to hide
-  int tpc = 2048;
+  int tpc = 8192;
   while (tpc > 512 && (int64_t)((n + tpc - 1) / tpc) * n_kv_heads < 256) tpc >>= 1;
   return tpc;
 }
