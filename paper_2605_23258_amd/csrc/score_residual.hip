@@ -10,9 +10,9 @@
 //                           p = exp2(S*c - bias_r), column mean -> mass; fused on the
 //                           same K registers: v_hat^T = W^T K^T (MFMA),
 //                           eps = sum_j (v - v_hat)^2
-//   pool                  : average pooling of mass over prefix columns, +inf on the window
-//                           columns (route_hist_kernel in route_compact.hip, which can hand the
-//                           routing its first histogram in the same launch)
+//   pool                  : average or maximum pooling of mass over prefix columns, +inf on the
+//                           window columns (route_bucket_kernel in route_compact.hip, which hands
+//                           the routing its first histogram and bucket lists in the same launch)
 //
 // Pass 1 has two kernels: score_stats_tiles_kernel (R_pad = 128 or 256: key tiles through LDS,
 // a wave keeps its block of Q_h and the rows' running statistics in registers) and
@@ -20,8 +20,10 @@
 // In pass 2 K rows go straight from HBM into MFMA operand registers (16 bytes per lane); the
 // next tile's rows are requested as soon as the last MFMA of the current tile has been issued;
 // Q_h, W_h^T and the row biases live in LDS for the life of a workgroup.  MFMAs of row block
-// i+1 are written between the exponentials of row block i; on this chip vector-ALU work does not
-// overlap the MFMAs of its own wave and only partly those of the SIMD's other wave.
+// i+1 are written between the exponentials of row block i: the vector port is the narrow
+// resource of both passes, and a wave's MFMAs only hide under its own vector work when the two
+// alternate in the instruction stream.  Both passes put all chunks of a KV head on one XCD, and
+// pass 2 walks a chunk backwards, towards what pass 1 left in that XCD's L2.
 // Template flags of pass 2: PROBE (repeat a tile's arithmetic on resident operands, for
 // measuring the contraction alone), ROPE (keys are un-rotated by position for the residual).
 #include "common.hpp"
