@@ -270,6 +270,10 @@ def main() -> None:
             roofline["frac_of_measured_copy"] = round(dom_gbs / cp, 4)
             roofline["score_residual_pair"]["frac_of_measured_copy"] = round(roofline["score_residual_pair"]["achieved"] / cp, 4)
             roofline["pass_frac_of_measured_copy"] = round(pass_bytes * cfg.layers / (ms_per_step * 1e-3) / 1e9 / cp, 4)
+        rd = sweep.get("measured_peaks", {}).get("device_read_GBs")
+        if rd:
+            roofline["frac_of_measured_read"] = round(dom_gbs / rd, 4)
+            roofline["pass_frac_of_measured_read"] = round(pass_bytes * cfg.layers / (ms_per_step * 1e-3) / 1e9 / rd, 4)
 
     # ---- decode attention over compressed caches ----
     decode = None
@@ -384,14 +388,22 @@ def run_sweep(args, vb, dg, pl, torch, np, dev, workers):
     dt = timed(lambda: dst.copy_(src), torch, 20)
     copy_gbs = 2 * src.numel() * 2 / dt / 1e9
     del src, dst
+    # a buffer that is only read, four times the Infinity Cache
+    big = torch.empty(512 * 1024 * 1024, dtype=torch.bfloat16, device=dev).normal_()
+    rsink = torch.zeros(1024, dtype=torch.float32, device=dev)
+    nread = vb.vector_probe_read_stream(big, rsink)
+    dt = timed(lambda: vb.vector_probe_read_stream(big, rsink), torch, 10)
+    read_gbs = nread / dt / 1e9
+    del big, rsink
     sink = torch.empty(262144, dtype=torch.float32, device=dev)
     iters = 20000
     flops = vb.vector_probe_mfma_loop(sink, iters)
     dt = timed(lambda: vb.vector_probe_mfma_loop(sink, iters), torch, 5)
     res["measured_peaks"] = {"device_copy_GBs": round(copy_gbs, 1), "device_copy_frac_of_hbm_peak": round(copy_gbs / HBM_PEAK_GBS, 4),
+                             "device_read_GBs": round(read_gbs, 1), "device_read_frac_of_hbm_peak": round(read_gbs / HBM_PEAK_GBS, 4),
                              "mfma_loop_TFLOPs": round(flops / dt / 1e12, 1),
                              "mfma_loop_frac_of_bf16_peak": round(flops / dt / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-                             "what": "256 MiB device-to-device copy (bytes read + written); 32x32x16 bf16 MFMA loop on register operands, 16 waves per CU"}
+                             "what": "256 MiB device-to-device copy (bytes read + written); 1 GiB read-only stream (vector_probe_read_stream); 32x32x16 bf16 MFMA loop on register operands, 16 waves per CU"}
     log(f"measured peaks: {res['measured_peaks']}")
     return res
 

@@ -458,6 +458,14 @@ VECTOR_API int vector_probe_residual_mfma(const vector_shape* shape, const void*
  * keeps the loop alive; its contents mean nothing).  Time the launch on `stream` to get FLOP/s. */
 VECTOR_API int vector_probe_mfma_loop(float* out, int32_t iters, int64_t* flops, void* stream);
 
+/* Diagnostic: the rate at which this chip streams a buffer that is only read (what the compression
+ * pass and the decode step mostly do), next to the device copy that reads and writes.  1024
+ * workgroups each read a contiguous slice of src (device, 16-byte aligned, `bytes` long) with 16-byte
+ * loads, eight in flight per thread; *bytes_read (host) receives what the launch reads (`bytes`
+ * rounded down to whole rounds of loads of 64 KiB per workgroup; VECTOR_ERR_ARG for a NULL or
+ * misaligned pointer and for less than 64 MiB).  out: device fp32 [1024], a sink.  Time the launch on `stream`. */
+VECTOR_API int vector_probe_read_stream(const void* src, size_t bytes, float* out, int64_t* bytes_read, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -28,7 +28,7 @@ EXPORTS = (
     "vector_score_residual_lse", "vector_compress_lse", "vector_compress_rope", "vector_compress_batch_rope",
     "vector_compress_ex", "vector_compress_batch_ex",
     "vector_timing_enable", "vector_timing_kernels", "vector_timing_name", "vector_timing_read",
-    "vector_probe_residual_mfma", "vector_probe_mfma_loop",
+    "vector_probe_residual_mfma", "vector_probe_mfma_loop", "vector_probe_read_stream",
     "vector_residual_rope", "vector_score_residual_rope", "vector_decode_attn_rope",
     "vector_decode_step", "vector_decode_step_rope",
     "vector_calibrate_workspace_bytes", "vector_calibrate",
@@ -149,6 +149,7 @@ def lib() -> C.CDLL:
         L.vector_timing_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         L.vector_probe_residual_mfma.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, i32, vp]
         L.vector_probe_mfma_loop.argtypes = [vp, i32, C.POINTER(C.c_int64), vp]
+        L.vector_probe_read_stream.argtypes = [vp, sz, vp, C.POINTER(C.c_int64), vp]
         L.vector_calibrate_workspace_bytes.argtypes = [C.POINTER(Shape)]
         L.vector_calibrate_workspace_bytes.restype = sz
         L.vector_calibrate.argtypes = [C.POINTER(Shape), vp, vp, vp, vp, sz, vp]
@@ -313,6 +314,13 @@ def vector_probe_mfma_loop(out, iters: int, stream=None) -> int:
     flops = C.c_int64()
     _check(lib().vector_probe_mfma_loop(_ptr(out), iters, C.byref(flops), _stream(stream)), "vector_probe_mfma_loop")
     return flops.value
+
+
+def vector_probe_read_stream(src, out, stream=None) -> int:
+    """Launch the read-only streaming kernel over `src`; returns the bytes the launch reads."""
+    n = C.c_int64()
+    _check(lib().vector_probe_read_stream(_ptr(src), _nbytes(src), _ptr(out), C.byref(n), _stream(stream)), "vector_probe_read_stream")
+    return n.value
 
 
 def vector_residual_rope(shape: Shape, k, v, W, rope: Rope, eps, ws=None, stream=None) -> None:

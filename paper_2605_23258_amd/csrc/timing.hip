@@ -103,10 +103,38 @@ __global__ __launch_bounds__(kMfmaProbeThreads) void mfma_loop_kernel(float* out
   for (int i = 0; i < 16; ++i) s += a0[i] + a1[i] + a2[i] + a3[i];
   out[(size_t)blockIdx.x * kMfmaProbeThreads + threadIdx.x] = s;
 }
+
+// Read-only stream: every workgroup takes a contiguous slice with 16-byte loads, eight in flight per
+// thread; the xor of what was read reaches memory only for one impossible value.
+constexpr int kReadProbeThreads = 512, kReadProbeLoads = 8;
+__global__ __launch_bounds__(kReadProbeThreads) void read_stream_kernel(const uint4* __restrict__ src, size_t per_wg, float* out) {
+  const uint4* p = src + (size_t)blockIdx.x * per_wg;
+  unsigned acc = 0;
+  for (size_t i = threadIdx.x; i + (kReadProbeLoads - 1) * kReadProbeThreads < per_wg; i += (size_t)kReadProbeLoads * kReadProbeThreads) {
+    uint4 v[kReadProbeLoads];
+#pragma unroll
+    for (int u = 0; u < kReadProbeLoads; ++u) v[u] = p[i + (size_t)u * kReadProbeThreads];
+#pragma unroll
+    for (int u = 0; u < kReadProbeLoads; ++u) acc += v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+  }
+  if (acc == 0x9e3779b9u && out) out[blockIdx.x] = 1.f;
+}
 }  // namespace
 }  // namespace vec
 
 extern "C" {
+
+int vector_probe_read_stream(const void* src, size_t bytes, float* out, int64_t* bytes_read, void* stream) {
+  constexpr size_t kGrid = 1024, kSlice = (size_t)vec::kReadProbeThreads * vec::kReadProbeLoads * 16;
+  if (!src || !out || !bytes_read || (reinterpret_cast<uintptr_t>(src) & 15u)) return VECTOR_ERR_ARG;
+  const size_t per_wg_bytes = bytes / kGrid / kSlice * kSlice;      // whole rounds of loads only: nothing beyond `bytes` is read
+  if (per_wg_bytes == 0) return VECTOR_ERR_ARG;
+  hipLaunchKernelGGL(vec::read_stream_kernel, dim3((unsigned)kGrid), dim3(vec::kReadProbeThreads), 0, (hipStream_t)stream,
+                     static_cast<const uint4*>(src), per_wg_bytes / 16, out);
+  if (hipGetLastError() != hipSuccess) return VECTOR_ERR_HIP;
+  *bytes_read = (int64_t)(per_wg_bytes * kGrid);
+  return VECTOR_OK;
+}
 
 int vector_probe_mfma_loop(float* out, int32_t iters, int64_t* flops, void* stream) {
   if (!out || iters < 1 || !flops) return VECTOR_ERR_ARG;

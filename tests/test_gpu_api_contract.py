@@ -238,3 +238,21 @@ def test_layers_stacked_along_the_head_axis():
         if got.dtype == torch.bfloat16:
             got, want = got.view(torch.int16), want.view(torch.int16)
         assert torch.equal(got, want), name
+
+
+def test_read_stream_probe_reads_what_it_reports():
+    """The read-only streaming probe reads whole rounds of 64 KiB per workgroup and nothing beyond
+    the buffer, leaves its sink alone, and refuses buffers it cannot cut that way."""
+    import ctypes as C
+    src = torch.ones(96 * 1024 * 1024 + 4096, dtype=torch.uint8, device="cuda:0")     # one and a half rounds
+    sink = torch.zeros(1024, dtype=torch.float32, device="cuda:0")
+    assert vb.vector_probe_read_stream(src, sink) == 64 * 1024 * 1024
+    assert vb.vector_probe_read_stream(src[: 64 * 1024 * 1024], sink) == 64 * 1024 * 1024
+    torch.cuda.synchronize()
+    assert float(sink.abs().sum()) == 0.0
+    n = C.c_int64()
+    L = vb.lib()
+    too_small = src[: 32 * 1024 * 1024]
+    assert L.vector_probe_read_stream(too_small.data_ptr(), too_small.numel(), sink.data_ptr(), C.byref(n), None) == -1
+    assert L.vector_probe_read_stream(src.data_ptr() + 4, src.numel() - 4, sink.data_ptr(), C.byref(n), None) == -1
+    assert L.vector_probe_read_stream(None, src.numel(), sink.data_ptr(), C.byref(n), None) == -1
