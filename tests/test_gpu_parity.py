@@ -49,6 +49,9 @@ CASES = {
     "bf16_d128_w60_padded_rows": ("cfg3", dict(seq_len=1100, n_kv_heads=1, n_q_heads=4, window=60, layers=1)),
     "bf16_d64_w64": ("cfg3", dict(seq_len=1400, head_dim=64, n_kv_heads=1, n_q_heads=4, layers=1)),
     "bf16_d128_w64_eight_heads": ("cfg3", dict(seq_len=700, n_kv_heads=8, n_q_heads=32, layers=1)),
+    # four KV heads (two XCDs per head, the chunks of a head split between them) and sixteen (two heads per XCD)
+    "bf16_d128_four_heads": ("cfg2", dict(seq_len=2040, n_kv_heads=4, n_q_heads=16)),    # 8 and 4 chunks: even, as the split needs
+    "bf16_d128_sixteen_heads": ("cfg2", dict(seq_len=1300, n_kv_heads=16, n_q_heads=32, window=48)),
     "f32_d128": ("cfg1", dict(seq_len=700, head_dim=128, n_kv_heads=1, n_q_heads=2, window=8, pool_kernel=3)),
     "tiny_n_equals_w": ("cfg1", dict(seq_len=32, window=32)),
     "short": ("cfg2", dict(seq_len=70, n_kv_heads=1, n_q_heads=4, window=5, pool_kernel=1)),
@@ -281,7 +284,7 @@ def test_decode_attn(dtype, d, B, Hq, Hkv, n_r, n_a, cap):
 
 
 @pytest.mark.parametrize("name", ["f32_d64_n1024", "bf16_d128_n2048", "bf16_d128_ragged", "bf16_G8_w64_groups", "bf16_d128_w64_ragged",
-                                  "bf16_d128_w64_eight_heads"])
+                                  "bf16_d128_w64_eight_heads", "bf16_d128_four_heads", "bf16_d128_sixteen_heads"])
 def test_end_to_end_compress(name):
     cfg, li, dev, wide = _inputs(name)
     shape = pl.shape_of(cfg)
