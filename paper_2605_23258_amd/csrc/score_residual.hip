@@ -381,13 +381,29 @@ __global__ __launch_bounds__(kV2Threads) void score_stats_tiles_kernel(PassParam
   const int c_end = min(p.n, c_begin + p.tpc1);
   const int n_steps = (c_end - c_begin + kStepTokens - 1) / kStepTokens;
 
-  // piece i of a step: token i / kPieces of the step, 16 bytes at piece i % kPieces
-  auto fetch = [&](uint4* raw, int step) {
+  // piece i of a step: token i / kPieces of the step, 16 bytes at piece i % kPieces.  A thread's
+  // pieces sit at fixed byte offsets from the step's first row, worked out once; a step moves
+  // them by a whole number of rows (one scalar product per step, no 64-bit vector multiplies in
+  // the loop).  Only a step that reaches past the sequence's end clamps its rows one by one.
+  int64_t piece_off[kLoads];
 #pragma unroll
-    for (int u = 0; u < kLoads; ++u) {
-      const int i = threadIdx.x + u * NT;
-      const int t = min(c_begin + step * kStepTokens + i / kPieces, p.n - 1);    // clamped: masked below
-      raw[u] = load_chunk(reinterpret_cast<const unsigned char*>(k_head + (int64_t)t * p.k_st) + (i % kPieces) * 16);
+  for (int u = 0; u < kLoads; ++u) {
+    const int i = threadIdx.x + u * NT;
+    piece_off[u] = ((int64_t)(i / kPieces) * p.k_st) * (int64_t)sizeof(T) + (i % kPieces) * 16;
+  }
+  auto fetch = [&](uint4* raw, int step) {
+    const int row0 = c_begin + step * kStepTokens;
+    if (row0 + kStepTokens <= p.n) {                 // uniform
+      const unsigned char* base = reinterpret_cast<const unsigned char*>(k_head + (int64_t)row0 * p.k_st);
+#pragma unroll
+      for (int u = 0; u < kLoads; ++u) raw[u] = load_chunk(base + piece_off[u]);
+    } else {
+#pragma unroll
+      for (int u = 0; u < kLoads; ++u) {
+        const int i = threadIdx.x + u * NT;
+        const int t = min(row0 + i / kPieces, p.n - 1);                          // clamped: masked below
+        raw[u] = load_chunk(reinterpret_cast<const unsigned char*>(k_head + (int64_t)t * p.k_st) + (i % kPieces) * 16);
+      }
     }
   };
   auto stash = [&](const uint4* raw, int buf) {
