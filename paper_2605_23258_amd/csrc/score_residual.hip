@@ -56,7 +56,7 @@ struct PassParams {
   int threads_per_row;  // pass-2 prologue: lanes that share the merge of one row's partials
   float c2;             // log2(e) / sqrt(d)
   float inv_R;
-  float2* part;         // [Hkv, R_pad, n_chunks]  (max, sum-exp), log2 domain
+  float2* part;         // [Hkv, n_chunks, R_pad]  (max, sum-exp), log2 domain
   float* mass;          // [Hkv, n]
   float* eps;           // [Hkv, n]
   float4* range;        // [Hkv, range_stride] or null: every workgroup of pass 2 leaves, over the prefix columns
@@ -138,6 +138,56 @@ __device__ __forceinline__ void fill_rows_lds(unsigned char* lds, const T* src, 
       if (i >= total) i -= total;
       const int row = i / P, piece = i - row * P;
       if (base + u * NT < total) *reinterpret_cast<uint4*>(lds + row * Tile<T, D>::kLdsStride + piece * 16) = x[u];
+    }
+  }
+}
+
+// fill_rows_lds in two halves, for a caller that has other work between the request and the use:
+// the first batch of eight loads per thread goes out in fill_rows_request, fill_rows_finish
+// stores it and runs the remaining batches (if the block has more than NT * 8 pieces).
+template <typename T, int D, int NT>
+__device__ __forceinline__ void fill_rows_request(uint4 (&x)[8], const T* src, int rows, int rows_pad, int rot) {
+  constexpr int P = Tile<T, D>::kRowBytes / 16;
+  const int total = rows_pad * P;
+  const int shift = (rot % rows_pad) * P;
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    int i = (int)threadIdx.x + u * NT + shift;
+    if (i >= total) i -= total;
+    i = min(i, total - 1);                       // threads beyond the block load a duplicate
+    const int row = i / P, piece = i - row * P;
+    x[u] = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(src) + (size_t)min(row, rows - 1) * Tile<T, D>::kRowBytes + piece * 16);
+  }
+}
+template <typename T, int D, int NT>
+__device__ __forceinline__ void fill_rows_finish(uint4 (&x)[8], unsigned char* lds, const T* src, int rows, int rows_pad, int rot) {
+  constexpr int P = Tile<T, D>::kRowBytes / 16;
+  constexpr int U = 8;
+  const int total = rows_pad * P;
+  const int shift = (rot % rows_pad) * P;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    int i = (int)threadIdx.x + u * NT + shift;
+    if (i >= total) i -= total;
+    const int row = i / P, piece = i - row * P;
+    if ((int)threadIdx.x + u * NT < total)
+      *reinterpret_cast<uint4*>(lds + row * Tile<T, D>::kLdsStride + piece * 16) = row < rows ? x[u] : make_uint4(0, 0, 0, 0);
+  }
+  for (int base = (int)threadIdx.x + NT * U; base < total; base += NT * U) {
+    uint4 y[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int i = base + u * NT + shift;
+      if (i >= total) i -= total;
+      const int row = i / P, piece = i - row * P;
+      y[u] = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(src) + (size_t)min(row, rows - 1) * Tile<T, D>::kRowBytes + piece * 16);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int i = base + u * NT + shift;
+      if (i >= total) i -= total;
+      const int row = i / P, piece = i - row * P;
+      if (base + u * NT < total) *reinterpret_cast<uint4*>(lds + row * Tile<T, D>::kLdsStride + piece * 16) = row < rows ? y[u] : make_uint4(0, 0, 0, 0);
     }
   }
 }
@@ -314,7 +364,7 @@ __global__ __launch_bounds__(NT) void score_stats_kernel(PassParams p) {
   }
   __syncthreads();
   // merge the NW waves x 2 lane halves that saw different tokens of the same query row
-  float2* out = p.part + (size_t)h * p.R_pad * p.n_chunks + chunk;
+  float2* out = p.part + ((size_t)h * p.n_chunks + chunk) * p.R_pad;     // [head][chunk][row]: rows of a chunk side by side
   for (int row = threadIdx.x; row < p.R_pad; row += NT) {
     const int rb = row >> 5, c = row & 31;
     float m = -INFINITY;
@@ -327,7 +377,7 @@ __global__ __launch_bounds__(NT) void score_stats_kernel(PassParams p) {
         float2 s = st_lds[((size_t)wv * nrb + rb) * 64 + hf * 32 + c];
         l += s.y * fast_exp2(s.x - m_safe);
       }
-    out[(size_t)row * p.n_chunks] = make_float2(m, l);
+    out[row] = make_float2(m, l);
   }
 }
 
@@ -568,7 +618,7 @@ __global__ __launch_bounds__(kV2Threads) void score_stats_tiles_kernel(PassParam
   for (int j = 0; j < RBW; ++j)
     if (half == 0) grp[tg * (NRB * 32) + qrow[j]] = make_float2(m_run[j], l_run[j]);
   __syncthreads();
-  float2* out = p.part + (size_t)h * p.R_pad * p.n_chunks + chunk;
+  float2* out = p.part + ((size_t)h * p.n_chunks + chunk) * p.R_pad;     // [head][chunk][row]: rows of a chunk side by side
   for (int row = threadIdx.x; row < NRB * 32; row += NT) {
     float m = -INFINITY;
 #pragma unroll
@@ -580,7 +630,7 @@ __global__ __launch_bounds__(kV2Threads) void score_stats_tiles_kernel(PassParam
       const float2 sv = grp[g * (NRB * 32) + row];
       l += sv.y * fast_exp2(sv.x - ms);
     }
-    out[(size_t)row * p.n_chunks] = make_float2(m, l);
+    out[row] = make_float2(m, l);
   }
 }
 
@@ -718,10 +768,6 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
   chunk_t kf0[TL::NC], kf1[TL::NC];
   const int t_first = c_begin + wave * 64;
   int t0 = t_first < c_end ? t_first + (c_end - t_first - 1) / kStep * kStep : t_first - kStep;
-  if (t0 >= t_first) {                    // first tile's keys fly during the prologue
-    load_k_subtile<T, D>(kf0, k_head, p.k_st, t0, p.n, lane);
-    load_k_subtile<T, D>(kf1, k_head, p.k_st, t0 + 32, p.n, lane);
-  }
 
   // Prologue: every global load of the staging below is issued before the first result is
   // used, so the workgroup pays one memory round trip, not one per stage.
@@ -742,14 +788,23 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
   const int tpr = p.threads_per_row, sub = threadIdx.x % tpr;
   const int rows_per_sweep = NT / tpr;
   float2 pre[kPre];
+  uint4 q_first[8];
+  const T* q_rows = reinterpret_cast<const T*>(p.q) + ((size_t)h * p.q_head_rows + p.q_row0) * D;
   if (DO_MASS) {
     if (!p.lse) {
       const int row = min((int)threadIdx.x / tpr, p.R_pad - 1);      // threads beyond R_pad rows load a duplicate
-      const float2* part = p.part + ((size_t)h * p.R_pad + row) * p.n_chunks;
+      const float2* part = p.part + (size_t)h * p.n_chunks * p.R_pad + row;
 #pragma unroll
-      for (int u = 0; u < kPre; ++u) pre[u] = part[min(sub + u * tpr, p.n_chunks - 1)];   // blanked when folded
+      for (int u = 0; u < kPre; ++u) pre[u] = part[(size_t)min(sub + u * tpr, p.n_chunks - 1) * p.R_pad];   // blanked when folded
     }
-    fill_rows_lds<T, D, NT>(q_lds, reinterpret_cast<const T*>(p.q) + ((size_t)h * p.q_head_rows + p.q_row0) * D, p.R, p.R_pad, chunk * 8);
+    fill_rows_request<T, D, NT>(q_first, q_rows, p.R, p.R_pad, chunk * 8);
+  }
+  // The first tile's keys are asked for after the staged operands (loads return in the order
+  // they were issued: ahead of the staging loads, the keys' trip to HBM would hold up everything
+  // below); they fly while W^T is laid out, the partials are merged and the query rows stored.
+  if (t0 >= t_first) {
+    load_k_subtile<T, D>(kf0, k_head, p.k_st, t0, p.n, lane);
+    load_k_subtile<T, D>(kf1, k_head, p.k_st, t0 + 32, p.n, lane);
   }
   if (DO_RES) {
     // W^T into LDS as the M-side operand.  MFMA row m of block jb stands for value dim
@@ -785,29 +840,35 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
         bias_lds[row] = (row < p.R) ? p.lse[((int64_t)h * (p.q_head_rows / p.w) + g) * p.lse_sh + r] * kLog2e : INFINITY;
       }
     }
+    // a batch of partials at once: their maximum first, then the sum against it (independent
+    // exponentials, no chain from one partial to the next), then one fold into the running pair
+    auto fold_batch = [&](float& m, float& l, const float2* sv, int count_in, int stride_in, int first_in, int nb) {
+      float bm = -INFINITY;
+#pragma unroll
+      for (int u = 0; u < 16; ++u)
+        if (u < nb && first_in + u * stride_in < count_in) bm = fmaxf(bm, sv[u].x);
+      const float bs = (bm == -INFINITY) ? 0.f : bm;
+      float bl = 0.f;
+#pragma unroll
+      for (int u = 0; u < 16; ++u)
+        if (u < nb && first_in + u * stride_in < count_in) bl += sv[u].y * fast_exp2(sv[u].x - bs);
+      fold(m, l, bm, bl);
+    };
     for (int row0 = 0; !p.lse && row0 < p.R_pad; row0 += rows_per_sweep) {
       const int row = row0 + threadIdx.x / tpr;
       float m = -INFINITY, l = 0.f;
       if (row < p.R_pad) {
-        const float2* part = p.part + ((size_t)h * p.R_pad + row) * p.n_chunks;
+        const float2* part = p.part + (size_t)h * p.n_chunks * p.R_pad + row;
         int c_from = sub;
         if (row0 == 0) {                       // the preloaded ones
-#pragma unroll
-          for (int u = 0; u < kPre; ++u) {
-            const bool in = sub + u * tpr < p.n_chunks;
-            fold(m, l, in ? pre[u].x : -INFINITY, in ? pre[u].y : 0.f);
-          }
+          fold_batch(m, l, pre, p.n_chunks, tpr, sub, kPre);
           c_from = sub + kPre * tpr;
         }
         for (int c0 = c_from; c0 < p.n_chunks; c0 += 8 * tpr) {       // the rest, eight loads in flight at a time
-          float2 sv[8];
+          float2 sv[16];
 #pragma unroll
-          for (int u = 0; u < 8; ++u) sv[u] = part[min(c0 + u * tpr, p.n_chunks - 1)];
-#pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            const bool in = c0 + u * tpr < p.n_chunks;
-            fold(m, l, in ? sv[u].x : -INFINITY, in ? sv[u].y : 0.f);
-          }
+          for (int u = 0; u < 8; ++u) sv[u] = part[(size_t)min(c0 + u * tpr, p.n_chunks - 1) * p.R_pad];
+          fold_batch(m, l, sv, p.n_chunks, tpr, c0, 8);
         }
       }
       for (int o = 1; o < tpr; o <<= 1) {
@@ -816,8 +877,19 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
       }
       if (sub == 0 && row < p.R_pad) bias_lds[row] = (row < p.R) ? m + __builtin_amdgcn_logf(l) : INFINITY;
     }
+    fill_rows_finish<T, D, NT>(q_first, q_lds, q_rows, p.R, p.R_pad, chunk * 8);
   }
   if (ROPE && threadIdx.x < D / 2) turns_lds[threadIdx.x] = make_float2(rp.turns_hi[threadIdx.x], rp.turns_lo[threadIdx.x]);
+  // The first tile's values are asked for before the barrier: memory keeps working while the
+  // workgroup waits for its slowest wave, and no wave starts its first tile stuck behind sixteen
+  // loads in a queue that the keys of all eight waves still fill.
+  chunk_t vf0[TL::VP], vf1[TL::VP];
+  bool values_requested = false;
+  if (DO_RES && !ROPE && t0 >= t_first) {
+    load_v_subtile<T, D>(vf0, v_head, p.v_st, t0, p.n, lane);
+    load_v_subtile<T, D>(vf1, v_head, p.v_st, t0 + 32, p.n, lane);
+    values_requested = true;
+  }
   __syncthreads();
 
   // ---- score part: rows = query rows, columns = tokens ----
@@ -876,7 +948,6 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
   };
 
   // ---- residual part: rows = value dims, columns = tokens; block bi = subtile * JB + jb ----
-  chunk_t vf0[TL::VP], vf1[TL::VP];
   auto res_mma = [&](f32x16& a, int bi) {
     const chunk_t* kf = (bi / JB) ? kf1 : kf0;
 #pragma unroll
@@ -921,10 +992,11 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
   float st_n = 0.f, st_l = 0.f, st_ll = 0.f;   // over the columns this lane stores
   while (t0 >= t_first) {
     const int tn = t0 - kStep;
-    if (DO_RES && !ROPE && (!PROBE || rep == 0)) {   // values arrive while the score part computes
+    if (DO_RES && !ROPE && (!PROBE || rep == 0) && !values_requested) {   // values arrive while the score part computes
       load_v_subtile<T, D>(vf0, v_head, p.v_st, t0, p.n, lane);
       load_v_subtile<T, D>(vf1, v_head, p.v_st, t0 + 32, p.n, lane);
     }
+    values_requested = false;
     if (DO_MASS && t0 < mass_end) {
       float col0 = 0.f, col1 = 0.f;
       f32x16 A0, A1, B0, B1;
