@@ -988,6 +988,11 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
       load_k_subtile<T, D>(kf1, k_head, p.k_st, tn + 32, p.n, lane);
     }
   };
+  // one subtile's share of it, as soon as the last MFMA that reads that subtile's keys is issued
+  auto load_next_subtile = [&](int tn, int sub) {
+    if (PROBE && rep + 1 < p.repeat) return;
+    if (tn >= t_first) load_k_subtile<T, D>(sub ? kf1 : kf0, k_head, p.k_st, tn + 32 * sub, p.n, lane);
+  };
 
   float st_n = 0.f, st_l = 0.f, st_ll = 0.f;   // over the columns this lane stores
   while (t0 >= t_first) {
@@ -1090,8 +1095,9 @@ __global__ __launch_bounds__(NT) void mass_residual_kernel(PassParams p, RopePar
         float& e = (bi / JB) ? e1 : e0;
         if (bi & 1) res_step(RA, bi + 1, RB, bi, e);
         else res_step(RB, bi + 1, RA, bi, e);
+        if (bi + 1 == JB - 1) load_next_subtile(tn, 0);     // block JB - 1 was the last one on the first subtile's keys
       }
-      load_next(tn);
+      load_next_subtile(tn, 1);
 #pragma unroll
       for (int v = 0; v < 16; ++v) res_diff(((2 * JB - 1) & 1) ? RB : RA, 2 * JB - 1, v, e1);
       e0 += __shfl_xor(e0, 32, kWave);       // the two halves of the value row
