@@ -491,7 +491,8 @@ enum { ROW_PICK1 = 0, ROW_PICK2, ROW_GT, ROW_EQ, ROW_EMIT0, ROW_EMIT1, ROW_TABLE
 struct SelectShared {
   __align__(16) int hist[3][kBins];      // digits of levels 1 and 2 of a select, and one for the caller; zeroed at the start
   int row[ROW_COUNT][SW];                // per-wave terms of the workgroup-wide sums, one row per use
-  int pick[3][4];                        // per level: digit, #(digit above it), count of its bin
+  int pick[3][4];                        // per level: digit, #(digit above it), count of its bin (and the first level's group of eight bins)
+  int coarse[ST + 1];                    // first step of the leading digit: sums at every eighth bin
   int seg_first[kMaxChunks], seg_count[kMaxChunks], seg_start[kMaxChunks];   // per chunk: where the keys with the chosen
                                          // leading digit sit, how many, and how many in earlier chunks
   int overflow;                          // a wave found more candidates than it can keep
@@ -505,45 +506,61 @@ __device__ __forceinline__ void select_shared_init(SelectShared& sh) {
 
 // Leading digit of the k-th largest key from the D tables of a head's chunks: summed over the
 // chunks, S[b] = #(digit >= b) falls from the key count at b = 0 to 0 at b = 2048, and the digit is
-// the one bin with S[b+1] < k <= S[b].  Thread t looks at bins 2040-8t .. 2047-8t (one 16-byte
-// load per chunk plus the entry above).  Every thread gets the digit, #(digit above it) and the
-// count of its bin.  prefetch() is called once the table loads are out, so that the caller's own
-// first loads travel with them.
+// the one bin with S[b+1] < k <= S[b].  Two steps, because what this costs is load instructions:
+// thread t first sums only the entry at the low end of its eight bins (b = 2040 - 8t) over the
+// chunks; the entry above its bins is its neighbour's sum, and one thread finds k between the two.
+// Then one wave reads that thread's eight entries of every chunk (one 16-byte load per chunk and
+// lane) and sums them across lanes.  Every thread gets the digit, #(digit above it) and the count
+// of its bin.  prefetch() is called once the first loads are out, so that the caller's own first
+// loads travel with them.
 template <typename Prefetch>
 __device__ __forceinline__ void pick_leading_digit(const uint16_t* tables, int n_parts, int k, SelectShared& sh, Prefetch prefetch,
                                                    int& digit, int& above, int& count) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lo = kBins - 8 - 8 * (int)threadIdx.x;
-  int S[9];
-#pragma unroll
-  for (int j = 0; j < 9; ++j) S[j] = 0;
+  int s_lo = 0;
   bool first = true;
-  constexpr int kInFlight = 16;                 // tables requested together: one trip to memory for up to 16 chunks
+  constexpr int kInFlight = 16;                 // chunks requested together: one trip to memory for up to 16 of them
   for (int c = 0; c < n_parts; c += kInFlight) {
-    uint4 v[kInFlight];
     uint16_t e[kInFlight];
 #pragma unroll
-    for (int u = 0; u < kInFlight; ++u) {
-      const uint16_t* t = tables + (size_t)min(c + u, n_parts - 1) * kTableStride + lo;
-      v[u] = *reinterpret_cast<const uint4*>(t);
-      e[u] = t[8];
-    }
+    for (int u = 0; u < kInFlight; ++u) e[u] = tables[(size_t)min(c + u, n_parts - 1) * kTableStride + lo];
     if (first) { prefetch(); first = false; }
 #pragma unroll
-    for (int u = 0; u < kInFlight; ++u) {
-      if (c + u < n_parts) {
-        const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
-#pragma unroll
-        for (int q = 0; q < 4; ++q) { S[2 * q] += (int)(w[q] & 0xffffu); S[2 * q + 1] += (int)(w[q] >> 16); }
-        S[8] += (int)e[u];
-      }
-    }
+    for (int u = 0; u < kInFlight; ++u)
+      if (c + u < n_parts) s_lo += (int)e[u];
   }
+  sh.coarse[threadIdx.x + 1] = s_lo;            // coarse[t + 1] = S[2040 - 8t]; coarse[0] = S[2048] = 0
+  if (threadIdx.x == 0) { sh.coarse[0] = 0; sh.pick[0][3] = 0; }    // no bracket (k outside the counts): the second step still reads inside the tables
+  __syncthreads();
+  const int s_hi = sh.coarse[threadIdx.x];      // S at the bin above this thread's eight
+  if (s_hi < k && k <= s_lo) { sh.pick[0][3] = lo; sh.pick[0][1] = s_hi; }
+  __syncthreads();
+  if (wave == 0) {
+    const int at = sh.pick[0][3];
+    int S[9];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    if (S[j + 1] < k && k <= S[j]) {
-      sh.pick[0][0] = lo + j;
-      sh.pick[0][1] = S[j + 1];
-      sh.pick[0][2] = S[j] - S[j + 1];
+    for (int j = 0; j < 8; ++j) S[j] = 0;
+    for (int c = lane; c < n_parts; c += kWave) {
+      const uint4 v = *reinterpret_cast<const uint4*>(tables + (size_t)c * kTableStride + at);
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) { S[2 * q] += (int)(w[q] & 0xffffu); S[2 * q + 1] += (int)(w[q] >> 16); }
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) S[j] += __shfl_xor(S[j], o, kWave);
+    S[8] = sh.pick[0][1];
+    if (lane == 0) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        if (S[j + 1] < k && k <= S[j]) {
+          sh.pick[0][0] = at + j;
+          sh.pick[0][1] = S[j + 1];
+          sh.pick[0][2] = S[j] - S[j + 1];
+        }
+      }
     }
   }
   __syncthreads();
